@@ -1,0 +1,193 @@
+/*
+ * gcada.h -- C-ABI of the G-CADA hot path for AMD MI355X (gfx950).
+ *
+ * G-CADA (grouping-based communication-adaptive distributed Adam) runs a parameter-server
+ * loop over G groups of M_G workers; every worker of a group holds the same data shard
+ * (paper Sec. IV).  This library simulates all groups of that loop on ONE GPU.  One call of
+ * gcada_step is one iteration k of Algorithm 1 for all groups at once:
+ *
+ *   a1  each group g evaluates the minibatch gradient (gradient of the SUM of the per-sample
+ *       losses over its minibatch xi_g^k, Sec. II-A) twice on the same samples: at the current
+ *       iterate theta^k and at theta_stale_g = theta^{k - tau_g}, the iterate of its last upload;
+ *   a2  stat_g = || grad(theta^k; xi_g^k) - grad(theta_stale_g; xi_g^k) ||^2 -- the quantity
+ *       that the left side of the selection rule Eq. (9) estimates (Sec. III) -- is compared
+ *       with rhs = (c/D) * sum_{d=1..D} || theta^{k+1-d} - theta^{k-d} ||^2 (right side of
+ *       Eq. (9) with c_d = c/D).  Group g is selected when stat_g > rhs, or tau_g >= D
+ *       (Algorithm 1), or rhs == 0;
+ *   a3  the lazily aggregated gradient (Sec. IV; Eq. (3)) is updated with the innovations of the
+ *       selected groups: agg += grad_g - last_g, last_g <- grad_g, tau_g <- 1; the other groups
+ *       keep their stored gradient and tau_g <- tau_g + 1 (Algorithm 1);
+ *   a4  server update, Eq. (8a)-(8c): h <- b1 h + (1-b1) agg;  v <- b2 vhat + (1-b2) agg^2;
+ *       vhat <- max(vhat, v);  theta^{k+1} = theta^k - alpha h / sqrt(eps + vhat);  and
+ *       || theta^{k+1} - theta^k ||^2 enters the history of Eq. (9).
+ *
+ * Every step above runs in hand-written HIP kernels; there is no CPU fallback.  All entry
+ * points return a status code (0 = GCADA_OK) and never throw or abort; on error, output
+ * arguments are left untouched and gcada_last_error gives a message.
+ *
+ * Pointers are marked [host] or [device].  "Borrowed" memory stays owned by the caller and
+ * must stay valid while the context uses it.  Unless said otherwise a call is asynchronous on
+ * the given HIP stream and does not synchronise with the host.  A context is not thread-safe;
+ * all calls on one context must use one stream (or be ordered by the caller).
+ *
+ * Parameter vector layout theta[p]:
+ *   logistic regression: theta[d], no intercept; labels y in {-1,+1};
+ *                        loss = log(1 + exp(-y x.theta)) + (l2/2)||theta||^2 per sample.
+ *   MLP: for each layer l = 1..L:  W_l (n_l x n_{l-1}, row-major) then b_l (n_l);
+ *        a_l = ReLU(W_l a_{l-1} + b_l), logits = W_L a_{L-1} + b_L, softmax cross-entropy,
+ *        ReLU'(0) = 0.
+ */
+#ifndef GCADA_H
+#define GCADA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gcada_ctx gcada_ctx;   /* opaque, owned by the library */
+
+enum {
+    GCADA_OK = 0,
+    GCADA_EINVAL = 1,   /* bad argument (message says which)            */
+    GCADA_ENOMEM = 2,   /* device or host allocation failed             */
+    GCADA_EDEVICE = 3,  /* a HIP call failed                            */
+    GCADA_ESTATE = 4    /* call order: shards / theta not set yet, ...  */
+};
+
+enum { GCADA_LOGREG = 0, GCADA_MLP = 1 };
+enum { GCADA_F32 = 0, GCADA_BF16 = 1 };
+
+#define GCADA_MAX_WIDTHS 8
+
+/* Model and batch geometry (Algorithm 1's problem statement). */
+typedef struct gcada_dims {
+    int32_t model;      /* GCADA_LOGREG | GCADA_MLP                                          */
+    int32_t dtype;      /* storage type of X and of the weights the gradients are evaluated
+                           at: GCADA_F32, or GCADA_BF16 (MLP only: bf16 X, bf16 copy of theta,
+                           fp32 accumulation, fp32 master theta and moments)                 */
+    int32_t n_widths;   /* LOGREG: 1; MLP: number of layer widths including input, 2..8      */
+    int32_t widths[GCADA_MAX_WIDTHS]; /* LOGREG: {d}; MLP: {n_0, ..., n_L}                   */
+    int32_t batch;      /* mu: minibatch size per group (fixed, Sec. II-A)                   */
+    float   l2;         /* lambda >= 0; must be 0 for GCADA_BF16                             */
+} gcada_dims;
+
+/*
+ * Create a context for G groups of M_G workers (Sec. IV), history depth / maximum age D >= 1
+ * and rule constant c >= 0 (Eq. (9)), stepsize alpha > 0, momentum weights beta1, beta2 in
+ * [0,1) and eps > 0 (Eq. (8a)-(8c)).  M_G only enters gcada_cost_model; the numerics do not
+ * depend on it (one gradient per selected group is uploaded, Sec. IV).
+ * Allocates all state on the current HIP device.  Synchronous.
+ * Errors: GCADA_EINVAL (dims / ranges), GCADA_ENOMEM, GCADA_EDEVICE.
+ */
+int gcada_create(const gcada_dims* dims /*[host]*/, int32_t G, int32_t M_G, int32_t D, double c,
+                 double alpha, double beta1, double beta2, double eps,
+                 gcada_ctx** out /*[host]*/);
+
+/* Frees the context and all device state.  NULL is allowed.  Synchronous. */
+void gcada_destroy(gcada_ctx* ctx);
+
+/*
+ * Give group g its data shard D_g (Sec. IV: all workers of a group hold the same shard, so one
+ * copy per group).  X: rows x widths[0], row-major with leading dimension ld (elements), fp32 or
+ * bf16 per dims.dtype.  y: rows entries; fp32 in {-1,+1} for LOGREG, int32 class id in
+ * [0, n_L) for MLP.  Both [device], BORROWED until destroy or the next set_shard for g.
+ * Errors: GCADA_EINVAL (g, rows < 1, ld < widths[0], NULL).
+ */
+int gcada_set_shard(gcada_ctx* ctx, int32_t g, const void* X /*[device]*/,
+                    const void* y /*[device]*/, int64_t rows, int64_t ld);
+
+/*
+ * Start a run (Algorithm 1's initialisation): theta^0 <- theta0 (copied), h = vhat = agg = 0,
+ * stored gradients 0, every stale iterate = theta^0, every age tau_g = D (so step 0 selects all
+ * groups), empty history, k = 0.  theta0: p floats, [host] or [device].  Synchronous.
+ */
+int gcada_set_theta(gcada_ctx* ctx, const float* theta0);
+
+/*
+ * One iteration k for all groups (steps a1-a4 above).
+ *   idx:      [device] G*mu int32 row ids, idx[g*mu + i] in [0, rows_g): group g's minibatch
+ *             xi_g^k; or NULL for the cyclic window rows (k*mu + i) mod rows_g.  Borrowed until
+ *             the step has run.  Ids are not range-checked on the device.
+ *   mask_out: [device] or pinned-host, G bytes: 1 if group g was selected; may be NULL.
+ *   loss_out: [device] or pinned-host, 1 float: mean over all G*mu samples of the per-sample
+ *             loss at theta^k (including (l2/2)||theta^k||^2); may be NULL.
+ *   stream:   a hipStream_t (NULL = default stream).
+ * Asynchronous; outputs are written in stream order.  Calls no allocator.
+ * Errors: GCADA_ESTATE (a shard or theta missing), GCADA_EDEVICE (launch failure).
+ */
+int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* loss_out,
+               void* stream);
+
+/* Views of the device state, valid until the next gcada_step / set_* / destroy. */
+typedef struct gcada_state_view {
+    int64_t p;               /* number of parameters                                          */
+    int32_t G, D, M_G;
+    int64_t k;               /* iterations done (host mirror of the device counter)           */
+    int64_t slot_stride;     /* floats between consecutive slots of theta_ring                */
+    int32_t cur_slot;        /* theta^k is slot k mod (D+1); theta^{k-t} is slot (k-t) mod (D+1) */
+    float*   theta_ring;     /* [device] (D+1) slots of p floats: the last D+1 iterates       */
+    float*   h;              /* [device] p                                                    */
+    float*   vhat;           /* [device] p                                                    */
+    float*   agg;            /* [device] p: lazily aggregated gradient                        */
+    float*   grad;           /* [device] G x p: fresh gradients of the last step              */
+    float*   last;           /* [device] G x p: gradient each group uploaded last             */
+    int32_t* tau;            /* [device] G ages                                               */
+    double*  dtheta_sq;      /* [device] D: ||theta^{j+1}-theta^j||^2 stored at index j mod D */
+    double*  stat;           /* [device] G: stat_g of the last step                           */
+    double*  rhs;            /* [device] 1: threshold of the last step                        */
+    uint8_t* mask;           /* [device] G: selection of the last step                        */
+    double*  loss;           /* [device] 1: loss of the last step                             */
+} gcada_state_view;
+
+int gcada_state(gcada_ctx* ctx, gcada_state_view* out /*[host]*/);
+
+/* Whole state in caller-owned HOST buffers, for checkpoints and step-by-step comparison. */
+typedef struct gcada_state_host {
+    float*   theta;        /* p                                   */
+    float*   h;            /* p                                   */
+    float*   vhat;         /* p                                   */
+    float*   agg;          /* p                                   */
+    float*   theta_stale;  /* G x p: theta^{k - tau_g} per group  */
+    float*   last;         /* G x p                               */
+    int32_t* tau;          /* G, each in [1, D]                   */
+    double*  dtheta_sq;    /* D, index j mod D as above           */
+    int64_t  k;
+} gcada_state_host;
+
+/* Copy the state out (fills the buffers and k).  Synchronises the device. */
+int gcada_get_state(gcada_ctx* ctx, gcada_state_host* out /*[host]*/);
+
+/*
+ * Overwrite the state.  Groups with equal tau must carry equal theta_stale rows (they are one
+ * iterate of the history); the row of the lowest such g is used.  Errors: GCADA_EINVAL when a
+ * tau is outside [1, D] or k < 0.  Synchronises the device.
+ */
+int gcada_set_state(gcada_ctx* ctx, const gcada_state_host* in /*[host]*/);
+
+/*
+ * Host-only cost model of Sec. II-B / Sec. V for one iteration of G groups of M_G workers with
+ * minibatch size mu, from the selection mask and seeded per-worker compute times T
+ * (G x M_G doubles, [host], e.g. iid Exp(eta)):
+ *   time  = max over selected groups of the min over the group's workers (the server waits
+ *           for the fastest worker of each selected group; 0 if nothing is selected),
+ *   comm  = |selected| * (M_G + 1)   (downloads + uploads, Eq. (5), (19)),
+ *   comp  = |selected| * M_G * mu    (Eq. (6), (22)).
+ * Any of the three outputs may be NULL (T may be NULL when time is).  Touches no device.
+ * Errors: GCADA_EINVAL (G, M_G, mu < 1, NULL mask, time without T).
+ */
+int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[host] G*/,
+                     const double* T /*[host] G*M_G*/, double* time, int64_t* comm,
+                     int64_t* comp);
+
+/* Message of the last error on this context ("" if none); NULL ctx: last gcada_create error. */
+const char* gcada_last_error(const gcada_ctx* ctx);
+
+/* Library version string. */
+const char* gcada_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GCADA_H */

@@ -1,0 +1,153 @@
+"""ctypes binding of libgcada.so -- argument marshalling only.
+
+Function names and arguments mirror ``include/gcada.h``; every step of the iteration runs in the
+library's HIP kernels.  There is no fallback: if the library is missing, importing fails.
+PyTorch appears only as the owner of device buffers and streams (``tensor.data_ptr()``,
+``torch.cuda.current_stream().cuda_stream``).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgcada.so")
+
+GCADA_OK, GCADA_EINVAL, GCADA_ENOMEM, GCADA_EDEVICE, GCADA_ESTATE = range(5)
+GCADA_LOGREG, GCADA_MLP = 0, 1
+GCADA_F32, GCADA_BF16 = 0, 1
+GCADA_MAX_WIDTHS = 8
+
+EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
+           "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
+           "gcada_last_error", "gcada_version"]
+
+
+class gcada_dims(C.Structure):
+    _fields_ = [("model", C.c_int32), ("dtype", C.c_int32), ("n_widths", C.c_int32),
+                ("widths", C.c_int32 * GCADA_MAX_WIDTHS), ("batch", C.c_int32), ("l2", C.c_float)]
+
+
+class gcada_state_view(C.Structure):
+    _fields_ = [("p", C.c_int64), ("G", C.c_int32), ("D", C.c_int32), ("M_G", C.c_int32),
+                ("k", C.c_int64), ("slot_stride", C.c_int64), ("cur_slot", C.c_int32),
+                ("theta_ring", C.c_void_p), ("h", C.c_void_p), ("vhat", C.c_void_p),
+                ("agg", C.c_void_p), ("grad", C.c_void_p), ("last", C.c_void_p),
+                ("tau", C.c_void_p), ("dtheta_sq", C.c_void_p), ("stat", C.c_void_p),
+                ("rhs", C.c_void_p), ("mask", C.c_void_p), ("loss", C.c_void_p)]
+
+
+class gcada_state_host(C.Structure):
+    _fields_ = [("theta", C.c_void_p), ("h", C.c_void_p), ("vhat", C.c_void_p),
+                ("agg", C.c_void_p), ("theta_stale", C.c_void_p), ("last", C.c_void_p),
+                ("tau", C.c_void_p), ("dtheta_sq", C.c_void_p), ("k", C.c_int64)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -m paper_2201_04301_amd.build` "
+            "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    L.gcada_create.restype = C.c_int
+    L.gcada_create.argtypes = [C.POINTER(gcada_dims), C.c_int32, C.c_int32, C.c_int32, C.c_double,
+                               C.c_double, C.c_double, C.c_double, C.c_double,
+                               C.POINTER(C.c_void_p)]
+    L.gcada_destroy.restype = None
+    L.gcada_destroy.argtypes = [C.c_void_p]
+    L.gcada_set_shard.restype = C.c_int
+    L.gcada_set_shard.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64,
+                                  C.c_int64]
+    L.gcada_set_theta.restype = C.c_int
+    L.gcada_set_theta.argtypes = [C.c_void_p, C.c_void_p]
+    L.gcada_step.restype = C.c_int
+    L.gcada_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.gcada_state.restype = C.c_int
+    L.gcada_state.argtypes = [C.c_void_p, C.POINTER(gcada_state_view)]
+    L.gcada_get_state.restype = C.c_int
+    L.gcada_get_state.argtypes = [C.c_void_p, C.POINTER(gcada_state_host)]
+    L.gcada_set_state.restype = C.c_int
+    L.gcada_set_state.argtypes = [C.c_void_p, C.POINTER(gcada_state_host)]
+    L.gcada_cost_model.restype = C.c_int
+    L.gcada_cost_model.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                   C.POINTER(C.c_double),
+                                   C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    L.gcada_last_error.restype = C.c_char_p
+    L.gcada_last_error.argtypes = [C.c_void_p]
+    L.gcada_version.restype = C.c_char_p
+    L.gcada_version.argtypes = []
+    return L
+
+
+lib = _load()
+
+
+class GcadaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"gcada error {code}: {msg}")
+        self.code = code
+
+
+def _check(rc: int, ctx=None):
+    if rc != GCADA_OK:
+        raise GcadaError(rc, (lib.gcada_last_error(ctx) or b"").decode())
+
+
+def make_dims(model: int, dtype: int, widths, batch: int, l2: float = 0.0) -> gcada_dims:
+    d = gcada_dims()
+    d.model, d.dtype, d.n_widths, d.batch, d.l2 = model, dtype, len(widths), batch, l2
+    for i, w in enumerate(widths):
+        d.widths[i] = int(w)
+    return d
+
+
+def gcada_create(dims: gcada_dims, G, M_G, D, c, alpha, beta1, beta2, eps) -> C.c_void_p:
+    out = C.c_void_p()
+    _check(lib.gcada_create(C.byref(dims), G, M_G, D, c, alpha, beta1, beta2, eps, C.byref(out)))
+    return out
+
+
+def gcada_destroy(ctx):
+    lib.gcada_destroy(ctx)
+
+
+def gcada_set_shard(ctx, g: int, X_ptr: int, y_ptr: int, rows: int, ld: int):
+    _check(lib.gcada_set_shard(ctx, g, X_ptr, y_ptr, rows, ld), ctx)
+
+
+def gcada_set_theta(ctx, theta0_ptr: int):
+    _check(lib.gcada_set_theta(ctx, theta0_ptr), ctx)
+
+
+def gcada_step(ctx, idx_ptr, mask_out_ptr, loss_out_ptr, stream_ptr=None):
+    _check(lib.gcada_step(ctx, idx_ptr, mask_out_ptr, loss_out_ptr, stream_ptr), ctx)
+
+
+def gcada_state(ctx) -> gcada_state_view:
+    v = gcada_state_view()
+    _check(lib.gcada_state(ctx, C.byref(v)), ctx)
+    return v
+
+
+def gcada_get_state(ctx, st: gcada_state_host):
+    _check(lib.gcada_get_state(ctx, C.byref(st)), ctx)
+
+
+def gcada_set_state(ctx, st: gcada_state_host):
+    _check(lib.gcada_set_state(ctx, C.byref(st)), ctx)
+
+
+def gcada_cost_model(G: int, M_G: int, mu: int, mask_ptr, T_ptr):
+    t, cm, cp = C.c_double(), C.c_int64(), C.c_int64()
+    rc = lib.gcada_cost_model(G, M_G, mu, mask_ptr, T_ptr, C.byref(t), C.byref(cm), C.byref(cp))
+    if rc != GCADA_OK:
+        raise GcadaError(rc, "gcada_cost_model: bad argument")
+    return t.value, cm.value, cp.value
+
+
+def gcada_version() -> str:
+    return lib.gcada_version().decode()
+
+
+def gcada_last_error(ctx=None) -> str:
+    return (lib.gcada_last_error(ctx) or b"").decode()

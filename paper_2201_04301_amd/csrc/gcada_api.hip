@@ -1,0 +1,360 @@
+// C-ABI of libgcada: context management, argument checks, state transfer, and the order of the
+// kernels that make one iteration (Algorithm 1 of the paper, all groups at once).
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "gcada_internal.h"
+
+using gcada::Ctl;
+using gcada::ShardDesc;
+
+namespace {
+
+thread_local std::string g_create_err;
+
+int fail(gcada_ctx* c, int code, const std::string& msg)
+{
+    if (c) c->err = msg; else g_create_err = msg;
+    return code;
+}
+
+int fail_hip(gcada_ctx* c, hipError_t e, const char* what)
+{
+    std::string m = std::string(what) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();   // clear the sticky launch error
+    return fail(c, e == hipErrorOutOfMemory ? GCADA_ENOMEM : GCADA_EDEVICE, m);
+}
+
+#define HIP_TRY(ctx, call)                                             \
+    do {                                                               \
+        hipError_t e__ = (call);                                       \
+        if (e__ != hipSuccess) return fail_hip(ctx, e__, #call);       \
+    } while (0)
+
+template <typename T>
+hipError_t dalloc(T** p, size_t n)
+{
+    hipError_t e = hipMalloc((void**)p, std::max<size_t>(n, 1) * sizeof(T));
+    if (e == hipSuccess) e = hipMemset(*p, 0, std::max<size_t>(n, 1) * sizeof(T));
+    return e;
+}
+
+int64_t param_count(const gcada_dims& d)
+{
+    if (d.model == GCADA_LOGREG) return d.widths[0];
+    int64_t p = 0;
+    for (int l = 1; l < d.n_widths; ++l)
+        p += (int64_t)d.widths[l] * d.widths[l - 1] + d.widths[l];
+    return p;
+}
+
+void free_all(gcada_ctx* c)
+{
+    if (!c) return;
+    gcada::mlp_free(c);
+    void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->grad, c->last, c->tau,
+                    c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat,
+                    c->part_sq};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* gcada_version(void) { return "gcada-gfx950 0.1"; }
+
+const char* gcada_last_error(const gcada_ctx* ctx)
+{
+    return ctx ? ctx->err.c_str() : g_create_err.c_str();
+}
+
+int gcada_create(const gcada_dims* dims, int32_t G, int32_t M_G, int32_t D, double c,
+                 double alpha, double beta1, double beta2, double eps, gcada_ctx** out)
+try {
+    if (!dims || !out) return fail(nullptr, GCADA_EINVAL, "dims and out must not be NULL");
+    if (dims->model != GCADA_LOGREG && dims->model != GCADA_MLP)
+        return fail(nullptr, GCADA_EINVAL, "dims.model must be GCADA_LOGREG or GCADA_MLP");
+    if (dims->dtype != GCADA_F32 && dims->dtype != GCADA_BF16)
+        return fail(nullptr, GCADA_EINVAL, "dims.dtype must be GCADA_F32 or GCADA_BF16");
+    if (dims->model == GCADA_LOGREG && (dims->n_widths != 1 || dims->dtype != GCADA_F32))
+        return fail(nullptr, GCADA_EINVAL, "logistic regression takes one width and fp32 data");
+    if (dims->model == GCADA_MLP && (dims->n_widths < 2 || dims->n_widths > GCADA_MAX_WIDTHS))
+        return fail(nullptr, GCADA_EINVAL, "MLP takes 2..8 layer widths");
+    for (int l = 0; l < dims->n_widths; ++l)
+        if (dims->widths[l] < 1)
+            return fail(nullptr, GCADA_EINVAL, "every width must be >= 1");
+    if (dims->batch < 1 || dims->batch > 4096)
+        return fail(nullptr, GCADA_EINVAL, "dims.batch (mu) must be in [1, 4096]");
+    if (!(dims->l2 >= 0.0f) || (dims->dtype == GCADA_BF16 && dims->l2 != 0.0f))
+        return fail(nullptr, GCADA_EINVAL, "dims.l2 must be >= 0 (and 0 for bf16)");
+    if (G < 1 || G > 4096) return fail(nullptr, GCADA_EINVAL, "G must be in [1, 4096]");
+    if (M_G < 1) return fail(nullptr, GCADA_EINVAL, "M_G must be >= 1");
+    if (D < 1 || D > 1024) return fail(nullptr, GCADA_EINVAL, "D must be in [1, 1024]");
+    if (!(c >= 0.0)) return fail(nullptr, GCADA_EINVAL, "c must be >= 0");
+    if (!(alpha > 0.0)) return fail(nullptr, GCADA_EINVAL, "alpha must be > 0");
+    if (!(beta1 >= 0.0 && beta1 < 1.0 && beta2 >= 0.0 && beta2 < 1.0))
+        return fail(nullptr, GCADA_EINVAL, "beta1, beta2 must be in [0, 1)");
+    if (!(eps > 0.0)) return fail(nullptr, GCADA_EINVAL, "eps must be > 0");
+
+    gcada_ctx* x = new (std::nothrow) gcada_ctx();
+    if (!x) return fail(nullptr, GCADA_ENOMEM, "host allocation failed");
+    x->dims = *dims;
+    x->M_G = M_G;
+    gcada::Hyper& hy = x->hy;
+    hy.G = G; hy.D = D; hy.mu = dims->batch;
+    hy.p = param_count(*dims);
+    hy.pstride = (hy.p + 63) / 64 * 64;
+    hy.l2 = dims->l2;
+    hy.c = c; hy.alpha = alpha; hy.beta1 = beta1; hy.beta2 = beta2; hy.eps = eps;
+    x->shards.assign(G, ShardDesc{nullptr, nullptr, 0, 0});
+    x->shard_set.assign(G, 0);
+
+    auto bail = [&](hipError_t e, const char* what) {
+        int rc = fail_hip(nullptr, e, what);
+        free_all(x);
+        delete x;
+        return rc;
+    };
+    hipError_t e;
+    if ((e = hipGetDevice(&x->device)) != hipSuccess) return bail(e, "hipGetDevice");
+    const size_t p = (size_t)hy.p, Gp = (size_t)G * p;
+    if ((e = dalloc(&x->d_shards, (size_t)G)) != hipSuccess) return bail(e, "alloc shards");
+    if ((e = dalloc(&x->ring, (size_t)(D + 1) * hy.pstride)) != hipSuccess) return bail(e, "alloc iterates");
+    if ((e = dalloc(&x->h, p)) != hipSuccess) return bail(e, "alloc h");
+    if ((e = dalloc(&x->vhat, p)) != hipSuccess) return bail(e, "alloc vhat");
+    if ((e = dalloc(&x->agg, p)) != hipSuccess) return bail(e, "alloc aggregate");
+    if ((e = dalloc(&x->grad, Gp)) != hipSuccess) return bail(e, "alloc gradients");
+    if ((e = dalloc(&x->last, Gp)) != hipSuccess) return bail(e, "alloc stored gradients");
+    if ((e = dalloc(&x->tau, (size_t)G)) != hipSuccess) return bail(e, "alloc ages");
+    if ((e = dalloc(&x->nring, (size_t)D)) != hipSuccess) return bail(e, "alloc history");
+    if ((e = dalloc(&x->stat, (size_t)G)) != hipSuccess) return bail(e, "alloc stat");
+    if ((e = dalloc(&x->mask, (size_t)G)) != hipSuccess) return bail(e, "alloc mask");
+    if ((e = dalloc(&x->ctl, 1)) != hipSuccess) return bail(e, "alloc control block");
+
+    e = dims->model == GCADA_LOGREG ? gcada::lr_plan(x) : gcada::mlp_plan(x);
+    if (e != hipSuccess) return bail(e, "model plan");
+    if ((e = gcada::select_plan(x)) != hipSuccess) return bail(e, "server plan");
+    if ((e = dalloc(&x->part_loss, (size_t)G * x->n_loss_part)) != hipSuccess) return bail(e, "alloc scratch");
+    if ((e = dalloc(&x->part_stat, (size_t)G * x->n_stat_part)) != hipSuccess) return bail(e, "alloc scratch");
+    if ((e = dalloc(&x->part_sq, (size_t)2 * x->n_epi_blocks)) != hipSuccess) return bail(e, "alloc scratch");
+    if ((e = hipDeviceSynchronize()) != hipSuccess) return bail(e, "hipDeviceSynchronize");
+    *out = x;
+    return GCADA_OK;
+} catch (...) {
+    return fail(nullptr, GCADA_ENOMEM, "unexpected exception in gcada_create");
+}
+
+void gcada_destroy(gcada_ctx* ctx)
+{
+    if (!ctx) return;
+    (void)hipDeviceSynchronize();
+    free_all(ctx);
+    delete ctx;
+}
+
+int gcada_set_shard(gcada_ctx* ctx, int32_t g, const void* X, const void* y, int64_t rows,
+                    int64_t ld)
+try {
+    if (!ctx) return GCADA_EINVAL;
+    if (g < 0 || g >= ctx->hy.G) return fail(ctx, GCADA_EINVAL, "set_shard: g out of range");
+    if (!X || !y) return fail(ctx, GCADA_EINVAL, "set_shard: X and y must not be NULL");
+    if (rows < 1) return fail(ctx, GCADA_EINVAL, "set_shard: rows must be >= 1");
+    if (ld < ctx->dims.widths[0]) return fail(ctx, GCADA_EINVAL, "set_shard: ld < widths[0]");
+    const int esz = ctx->dims.dtype == GCADA_BF16 ? 2 : 4;
+    if ((uintptr_t)X % esz || (uintptr_t)y % 4)
+        return fail(ctx, GCADA_EINVAL, "set_shard: misaligned pointer");
+    ShardDesc s{X, y, rows, ld};
+    HIP_TRY(ctx, hipMemcpy(ctx->d_shards + g, &s, sizeof(s), hipMemcpyHostToDevice));
+    ctx->shards[g] = s;
+    ctx->shard_set[g] = 1;
+    return GCADA_OK;
+} catch (...) {
+    return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_set_shard");
+}
+
+// Fill every ring slot with theta0, zero the rest, ages = D.
+static int reset_run(gcada_ctx* ctx, const float* theta0_any)
+{
+    const gcada::Hyper& hy = ctx->hy;
+    const size_t p = (size_t)hy.p, Gp = (size_t)hy.G * p;
+    for (int s = 0; s <= hy.D; ++s)
+        HIP_TRY(ctx, hipMemcpy(ctx->ring + (size_t)s * hy.pstride, theta0_any, p * sizeof(float),
+                               hipMemcpyDefault));
+    HIP_TRY(ctx, hipMemset(ctx->h, 0, p * 4));
+    HIP_TRY(ctx, hipMemset(ctx->vhat, 0, p * 4));
+    HIP_TRY(ctx, hipMemset(ctx->agg, 0, p * 4));
+    HIP_TRY(ctx, hipMemset(ctx->grad, 0, Gp * 4));
+    HIP_TRY(ctx, hipMemset(ctx->last, 0, Gp * 4));
+    HIP_TRY(ctx, hipMemset(ctx->nring, 0, (size_t)hy.D * 8));
+    HIP_TRY(ctx, hipMemset(ctx->stat, 0, (size_t)hy.G * 8));
+    HIP_TRY(ctx, hipMemset(ctx->mask, 0, (size_t)hy.G));
+    std::vector<int32_t> tau(hy.G, hy.D);
+    HIP_TRY(ctx, hipMemcpy(ctx->tau, tau.data(), (size_t)hy.G * 4, hipMemcpyHostToDevice));
+    Ctl z{};
+    HIP_TRY(ctx, hipMemcpy(ctx->ctl, &z, sizeof(z), hipMemcpyHostToDevice));
+    ctx->k = 0;
+    return GCADA_OK;
+}
+
+static int after_state_change(gcada_ctx* ctx)
+{
+    HIP_TRY(ctx, gcada::refresh_theta_sq(ctx, nullptr));
+    if (ctx->dims.model == GCADA_MLP) HIP_TRY(ctx, gcada::mlp_refresh_weights(ctx, nullptr));
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    return GCADA_OK;
+}
+
+int gcada_set_theta(gcada_ctx* ctx, const float* theta0)
+try {
+    if (!ctx) return GCADA_EINVAL;
+    if (!theta0) return fail(ctx, GCADA_EINVAL, "set_theta: theta0 must not be NULL");
+    int rc = reset_run(ctx, theta0);
+    if (rc != GCADA_OK) return rc;
+    rc = after_state_change(ctx);
+    if (rc != GCADA_OK) return rc;
+    ctx->theta_set = true;
+    return GCADA_OK;
+} catch (...) {
+    return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_set_theta");
+}
+
+int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* loss_out,
+               void* stream)
+{
+    if (!ctx) return GCADA_EINVAL;
+    if (!ctx->theta_set) return fail(ctx, GCADA_ESTATE, "step: gcada_set_theta has not been called");
+    for (int g = 0; g < ctx->hy.G; ++g)
+        if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "step: a group has no shard");
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, idx, s)
+                                                   : gcada::mlp_gradients(ctx, idx, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
+    if ((e = gcada::select_groups(ctx, mask_out, loss_out, s)) != hipSuccess)
+        return fail_hip(ctx, e, "selection kernel");
+    if ((e = gcada::server_update(ctx, s)) != hipSuccess)
+        return fail_hip(ctx, e, "server update kernel");
+    ctx->k += 1;
+    return GCADA_OK;
+}
+
+int gcada_state(gcada_ctx* ctx, gcada_state_view* out)
+{
+    if (!ctx) return GCADA_EINVAL;
+    if (!out) return fail(ctx, GCADA_EINVAL, "state: out must not be NULL");
+    gcada_state_view v{};
+    v.p = ctx->hy.p; v.G = ctx->hy.G; v.D = ctx->hy.D; v.M_G = ctx->M_G;
+    v.k = ctx->k;
+    v.slot_stride = ctx->hy.pstride;
+    v.cur_slot = (int32_t)(ctx->k % (ctx->hy.D + 1));
+    v.theta_ring = ctx->ring; v.h = ctx->h; v.vhat = ctx->vhat; v.agg = ctx->agg;
+    v.grad = ctx->grad; v.last = ctx->last; v.tau = ctx->tau; v.dtheta_sq = ctx->nring;
+    v.stat = ctx->stat; v.rhs = &ctx->ctl->rhs; v.mask = ctx->mask; v.loss = &ctx->ctl->loss;
+    *out = v;
+    return GCADA_OK;
+}
+
+int gcada_get_state(gcada_ctx* ctx, gcada_state_host* out)
+try {
+    if (!ctx) return GCADA_EINVAL;
+    if (!out) return fail(ctx, GCADA_EINVAL, "get_state: out must not be NULL");
+    const gcada::Hyper& hy = ctx->hy;
+    const size_t p = (size_t)hy.p;
+    const int nslot = hy.D + 1;
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    std::vector<int32_t> tau(hy.G);
+    HIP_TRY(ctx, hipMemcpy(tau.data(), ctx->tau, (size_t)hy.G * 4, hipMemcpyDeviceToHost));
+    const int cur = (int)(ctx->k % nslot);
+    if (out->theta)
+        HIP_TRY(ctx, hipMemcpy(out->theta, ctx->ring + (size_t)cur * hy.pstride, p * 4, hipMemcpyDeviceToHost));
+    if (out->h) HIP_TRY(ctx, hipMemcpy(out->h, ctx->h, p * 4, hipMemcpyDeviceToHost));
+    if (out->vhat) HIP_TRY(ctx, hipMemcpy(out->vhat, ctx->vhat, p * 4, hipMemcpyDeviceToHost));
+    if (out->agg) HIP_TRY(ctx, hipMemcpy(out->agg, ctx->agg, p * 4, hipMemcpyDeviceToHost));
+    if (out->theta_stale)
+        for (int g = 0; g < hy.G; ++g) {
+            const int slot = (int)(((ctx->k - tau[g]) % nslot + nslot) % nslot);
+            HIP_TRY(ctx, hipMemcpy(out->theta_stale + (size_t)g * p, ctx->ring + (size_t)slot * hy.pstride,
+                                   p * 4, hipMemcpyDeviceToHost));
+        }
+    if (out->last)
+        HIP_TRY(ctx, hipMemcpy(out->last, ctx->last, (size_t)hy.G * p * 4, hipMemcpyDeviceToHost));
+    if (out->tau) std::memcpy(out->tau, tau.data(), (size_t)hy.G * 4);
+    if (out->dtheta_sq)
+        HIP_TRY(ctx, hipMemcpy(out->dtheta_sq, ctx->nring, (size_t)hy.D * 8, hipMemcpyDeviceToHost));
+    out->k = ctx->k;
+    return GCADA_OK;
+} catch (...) {
+    return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_get_state");
+}
+
+int gcada_set_state(gcada_ctx* ctx, const gcada_state_host* in)
+try {
+    if (!ctx) return GCADA_EINVAL;
+    if (!in || !in->theta || !in->h || !in->vhat || !in->agg || !in->theta_stale || !in->last ||
+        !in->tau || !in->dtheta_sq)
+        return fail(ctx, GCADA_EINVAL, "set_state: every buffer must be given");
+    const gcada::Hyper& hy = ctx->hy;
+    if (in->k < 0) return fail(ctx, GCADA_EINVAL, "set_state: k must be >= 0");
+    for (int g = 0; g < hy.G; ++g)
+        if (in->tau[g] < 1 || in->tau[g] > hy.D)
+            return fail(ctx, GCADA_EINVAL, "set_state: tau out of [1, D]");
+    const size_t p = (size_t)hy.p;
+    const int nslot = hy.D + 1;
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    const int cur = (int)(in->k % nslot);
+    // unreferenced slots get the current iterate (they are never read before being rewritten)
+    for (int s = 0; s < nslot; ++s)
+        HIP_TRY(ctx, hipMemcpy(ctx->ring + (size_t)s * hy.pstride, in->theta, p * 4, hipMemcpyHostToDevice));
+    std::vector<uint8_t> filled(nslot, 0);
+    for (int g = 0; g < hy.G; ++g) {
+        const int slot = (int)(((in->k - in->tau[g]) % nslot + nslot) % nslot);
+        if (filled[slot] || slot == cur) continue;
+        HIP_TRY(ctx, hipMemcpy(ctx->ring + (size_t)slot * hy.pstride, in->theta_stale + (size_t)g * p,
+                               p * 4, hipMemcpyHostToDevice));
+        filled[slot] = 1;
+    }
+    HIP_TRY(ctx, hipMemcpy(ctx->h, in->h, p * 4, hipMemcpyHostToDevice));
+    HIP_TRY(ctx, hipMemcpy(ctx->vhat, in->vhat, p * 4, hipMemcpyHostToDevice));
+    HIP_TRY(ctx, hipMemcpy(ctx->agg, in->agg, p * 4, hipMemcpyHostToDevice));
+    HIP_TRY(ctx, hipMemcpy(ctx->last, in->last, (size_t)hy.G * p * 4, hipMemcpyHostToDevice));
+    HIP_TRY(ctx, hipMemcpy(ctx->tau, in->tau, (size_t)hy.G * 4, hipMemcpyHostToDevice));
+    HIP_TRY(ctx, hipMemcpy(ctx->nring, in->dtheta_sq, (size_t)hy.D * 8, hipMemcpyHostToDevice));
+    Ctl z{};
+    z.k = in->k;
+    HIP_TRY(ctx, hipMemcpy(ctx->ctl, &z, sizeof(z), hipMemcpyHostToDevice));
+    ctx->k = in->k;
+    int rc = after_state_change(ctx);
+    if (rc != GCADA_OK) return rc;
+    ctx->theta_set = true;
+    return GCADA_OK;
+} catch (...) {
+    return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_set_state");
+}
+
+int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask, const double* T,
+                     double* time, int64_t* comm, int64_t* comp)
+{
+    if (G < 1 || M_G < 1 || mu < 1 || !mask) return GCADA_EINVAL;
+    if (time && !T) return GCADA_EINVAL;
+    int64_t nsel = 0;
+    double tmax = 0.0;
+    for (int g = 0; g < G; ++g) {
+        if (!mask[g]) continue;
+        ++nsel;
+        if (time) {
+            double tmin = T[(size_t)g * M_G];
+            for (int m = 1; m < M_G; ++m) tmin = std::min(tmin, T[(size_t)g * M_G + m]);
+            tmax = std::max(tmax, tmin);
+        }
+    }
+    if (time) *time = tmax;
+    if (comm) *comm = nsel * (int64_t)(M_G + 1);
+    if (comp) *comp = nsel * (int64_t)M_G * (int64_t)mu;
+    return GCADA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,104 @@
+// Internal declarations shared by the translation units of libgcada (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "gcada.h"
+
+namespace gcada {
+
+// One group's data shard as the kernels see it.
+struct ShardDesc {
+    const void* X;   // rows x ld, fp32 or bf16
+    const void* y;   // rows: fp32 +-1 (logistic) or int32 class (MLP)
+    int64_t rows;
+    int64_t ld;
+};
+
+// Device-resident control block: everything a step decides stays on the device.
+struct Ctl {
+    long long k;            // iterations done
+    double rhs;             // threshold of the last step
+    double loss;            // loss of the last step
+    double theta_sq;        // ||theta^k||^2 (for the l2 term of the loss)
+    unsigned int cnt_a;     // "last block done" counters, reset by the block that finishes
+    unsigned int cnt_b;
+    unsigned int cnt_c;
+    unsigned int error;     // sticky device-side error flag (0 = none)
+};
+
+// Scalars every kernel needs, passed by value.
+struct Hyper {
+    int32_t G, D, mu;
+    int64_t p, pstride;     // parameters; floats between ring slots
+    float l2;
+    double c, alpha, beta1, beta2, eps;
+};
+
+struct MlpWork;   // MLP activations and compute copies (mlp_kernels.hip)
+
+}  // namespace gcada
+
+struct gcada_ctx {
+    gcada_dims dims{};
+    gcada::Hyper hy{};
+    int32_t M_G = 1;
+    int device = 0;
+    int64_t k = 0;                 // host mirror of Ctl::k
+    bool theta_set = false;
+    std::vector<gcada::ShardDesc> shards;   // host copy
+    std::vector<uint8_t> shard_set;
+
+    // device state
+    gcada::ShardDesc* d_shards = nullptr;
+    float* ring = nullptr;         // (D+1) x pstride : last D+1 iterates
+    float* h = nullptr;
+    float* vhat = nullptr;
+    float* agg = nullptr;
+    float* grad = nullptr;         // G x p
+    float* last = nullptr;         // G x p
+    int32_t* tau = nullptr;        // G
+    double* nring = nullptr;       // D
+    double* stat = nullptr;        // G
+    uint8_t* mask = nullptr;       // G
+    gcada::Ctl* ctl = nullptr;
+
+    // scratch
+    float* res = nullptr;          // logistic: G x mu x 2 (residual at theta^k, residual difference)
+    double* part_loss = nullptr;   // per-block partial loss sums
+    double* part_stat = nullptr;   // G x n_stat_part partial squared norms
+    double* part_sq = nullptr;     // epilogue partials: 2 per block (||step||^2, ||theta_new||^2)
+    int32_t n_loss_part = 0;   // partial loss sums per group
+    int32_t n_stat_part = 0;   // allocated partial squared norms per group
+    int32_t n_stat_used = 0;   // partials per group the last gradient launch wrote
+    int32_t n_epi_blocks = 0;
+
+    gcada::MlpWork* mlp = nullptr;
+
+    std::string err;
+};
+
+namespace gcada {
+
+// Each returns hipSuccess or the launch error.  All work is enqueued on `s`.
+hipError_t lr_plan(gcada_ctx* c);                      // sizes scratch (create time)
+hipError_t lr_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
+
+hipError_t mlp_plan(gcada_ctx* c);
+void mlp_free(gcada_ctx* c);
+hipError_t mlp_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
+hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s);   // bf16 copies of all ring slots
+
+hipError_t select_plan(gcada_ctx* c);
+// stat/loss partials -> stat, rhs, mask, tau; writes mask_out / loss_out
+hipError_t select_groups(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s);
+// masked innovation sum + server update + history; advances Ctl::k
+hipError_t server_update(gcada_ctx* c, hipStream_t s);
+// ||theta^k||^2 of the current slot -> Ctl::theta_sq (after set_theta / set_state)
+hipError_t refresh_theta_sq(gcada_ctx* c, hipStream_t s);
+
+}  // namespace gcada

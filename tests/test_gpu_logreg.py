@@ -1,0 +1,89 @@
+"""GPU parity of the logistic-regression path with the fp64 oracle (through the C-ABI)."""
+import numpy as np
+import pytest
+import torch
+
+from gcada_inputs import CONFIGS, make_indices, make_shards, scaled
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def par():
+    import parity
+    return parity
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def test_lr_small_full_run_teacher_forced(par):
+    # configuration 1: d=64, G=3, mu=32, 512 rows per shard, 200 iterations from theta = 0
+    w = CONFIGS["lr_small"]
+    _say("case lr_small", w)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, w.iters)
+    worst = par.teacher_forced(w, w.iters, Xs, ys, idx)
+    _say(worst)
+    # the rule must both fire and hold back during the run
+    assert w.G * 20 < worst["selected"] < w.G * w.iters
+
+
+def test_lr_small_cyclic_window(par):
+    w = CONFIGS["lr_small"]
+    Xs, ys = make_shards(w, "cuda")
+    worst = par.teacher_forced(w, 40, Xs, ys, idx=None)
+    _say(worst)
+
+
+@pytest.mark.parametrize("d,mu,G,rows,l2,c", [
+    (67, 33, 3, 100, 0.0, 1.0),      # ragged d (scalar path), ragged mu
+    (260, 17, 5, 64, 1e-3, 0.5),     # one column slab plus a 4-column tail, l2 on
+    (1028, 130, 2, 300, 1e-4, 2.0),  # several slabs, mu not a multiple of the row tiles
+    (4, 1, 1, 3, 0.0, 1.0),          # degenerate: one sample, one group
+])
+def test_lr_ragged_shapes(par, d, mu, G, rows, l2, c):
+    w = scaled(CONFIGS["lr_small"], name="ragged", widths=(d,), mu=mu, G=G, rows=rows, l2=l2, c=c,
+               D=4)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, 25)
+    worst = par.teacher_forced(w, 25, Xs, ys, idx)
+    _say(worst)
+
+
+@pytest.mark.parametrize("c", [0.0, 0.5, 2.0])
+def test_lr_4k_reduced_rows_c_sweep(par, c):
+    # configuration 2's geometry (d=4096, G=16, mu=256, l2=1e-4) on shorter shards
+    w = scaled(CONFIGS["lr_4k"], rows=2048, c=c)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, 30)
+    worst = par.teacher_forced(w, 30, Xs, ys, idx)
+    _say(worst)
+    if c == 0.0:
+        assert worst["selected"] == w.G * 30
+
+
+def test_lr_free_run_tracks_oracle(par):
+    w = CONFIGS["lr_small"]
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, w.iters)
+    r = par.free_running(w, w.iters, Xs, ys, idx)
+    agree = (r["masks_gpu"] == r["masks_oracle"]).mean()
+    _say("mask agreement", agree, "final loss", r["loss_gpu"][-1], r["loss_oracle"][-1])
+    assert agree >= 0.98
+    np.testing.assert_allclose(r["loss_gpu"], r["loss_oracle"], rtol=2e-3)
+    assert r["loss_gpu"][-1] < 0.9 * r["loss_gpu"][0]
+
+
+def test_lr_deterministic(par):
+    # same inputs twice => bit-identical iterate (all reductions have a fixed order)
+    w = scaled(CONFIGS["lr_4k"], rows=1024)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, 12)
+    a = par.free_running(w, 12, Xs, ys, idx)
+    b = par.free_running(w, 12, Xs, ys, idx)
+    np.testing.assert_array_equal(a["theta_gpu"], b["theta_gpu"])
+    np.testing.assert_array_equal(a["masks_gpu"], b["masks_gpu"])

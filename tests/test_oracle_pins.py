@@ -390,3 +390,18 @@ def test_bf16_mode_evaluates_at_rounded_iterate():
         np.testing.assert_allclose(orc.grad[1], O.loss_grad_sum(one, thr, Xs[1][rows], ys[1][rows])[1],
                                    rtol=1e-13, atol=0)
     assert not np.array_equal(orc.theta, torch.tensor(orc.theta).to(torch.bfloat16).to(torch.float64).numpy())
+
+
+def test_zero_threshold_selects_even_when_nothing_moves():
+    # degenerate case: all-zero features give a zero gradient, the iterate never moves, so both
+    # sides of the rule are 0; the reading taken is "threshold 0 => upload", which keeps
+    # "c = 0 <=> distributed AMSGrad" exact.
+    cfg = O.Config(O.LOGISTIC, [5], batch=3, G=2, D=4, c=0.0)
+    orc = O.Oracle(cfg, np.ones(5))
+    X = np.zeros((2, 3, 5), dtype=np.float32)
+    y = np.ones((2, 3), dtype=np.float32)
+    for k in range(6):
+        mask, loss = orc.step(X, y)
+        assert mask.all() and orc.rhs == 0.0 and (orc.stat == 0).all()
+        assert loss == pytest.approx(math.log(2.0))
+        np.testing.assert_array_equal(orc.theta, np.ones(5))

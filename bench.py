@@ -1,0 +1,140 @@
+#!/usr/bin/env python3
+"""Throughput of the G-CADA hot path on one MI355X.
+
+A step is one whole iteration (dual-iterate gradients of all groups, selection, masked innovation
+sum, server update) on one minibatch per group of the synthetic workload.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="lr_4k")
+    ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1 = auto)")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from gcada_inputs import CONFIGS, gather_rows, make_delays, make_indices, make_shards, make_theta0
+    from paper_2201_04301_amd import Gcada, binding as B
+
+    torch.cuda.set_device(0)
+    w = CONFIGS[args.workload]
+    K, W = args.steps, args.warmup
+    t0 = time.time()
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, K + W)
+    idx_dev = torch.as_tensor(idx, device="cuda")
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    gpu = Gcada.from_workload(w)
+    gpu.set_shards(Xs, ys)
+    gpu.set_theta(make_theta0(w))
+    masks = torch.zeros(K + W, w.G, dtype=torch.uint8, device="cuda")
+    losses = torch.zeros(K + W, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    base_idx, base_m, base_l = idx_dev.data_ptr(), masks.data_ptr(), losses.data_ptr()
+    stride_idx = w.G * w.mu * 4
+
+    def run_fast(k0, k1):
+        ctx, step = gpu.ctx, B.lib.gcada_step
+        for k in range(k0, k1):
+            rc = step(ctx, base_idx + k * stride_idx, base_m + k * w.G, base_l + 4 * k, stream)
+            if rc != 0:
+                raise RuntimeError(B.gcada_last_error(ctx))
+
+    run_fast(0, W)
+    torch.cuda.synchronize()
+    B.gcada_timing_begin(gpu.ctx, K)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_fast(W, W + K)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_timed, grad_ms = B.gcada_timing_end(gpu.ctx)
+
+    ms_per_step = dt / K * 1e3
+    iters_s = K / dt
+    # algorithmic bytes of the gradient stage per step: one read of the touched minibatch rows
+    esz = 2 if w.dtype == "bf16" else 4
+    alg_bytes = w.G * w.mu * w.widths[0] * esz
+    grad_ms_avg = grad_ms / max(n_timed, 1)
+    achieved = alg_bytes / (grad_ms_avg * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "gradient stage (lr_forward + lr_backward)",
+                "avg_ms": round(grad_ms_avg, 5), "algorithmic_bytes": alg_bytes}
+
+    m_host = masks[W:].cpu().numpy()
+    l_host = losses[W:].cpu().numpy()
+    # modelled wall-clock / communication / computation of the paper's cost model (reported only)
+    T = make_delays(w, K)
+    tm = cm = pm = 0.0
+    for k in range(K):
+        t, c_, p_ = gpu.cost_model(m_host[k], T[k])
+        tm += t; cm += c_; pm += p_
+    model = {"eta_s": 1e-4, "modelled_time_s": tm, "comm_load": cm, "comp_load": pm,
+             "mean_selected": float(m_host.sum(1).mean())}
+
+    cpu = None
+    if not args.no_cpu:
+        import oracle as O
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from parity import oracle_config
+        orc = O.Oracle(oracle_config(w), make_theta0(w))
+        n_cpu = args.cpu_steps
+        budget_s = 15.0
+        done, spent = 0, 0.0
+        kk = 0
+        while True:
+            Xmb, ymb = gather_rows(Xs, ys, idx[kk])
+            t1 = time.perf_counter()
+            orc.step(Xmb, ymb)
+            spent += time.perf_counter() - t1
+            done += 1
+            kk += 1
+            if (n_cpu > 0 and done >= n_cpu) or (n_cpu <= 0 and (spent > budget_s or kk >= K + W)):
+                break
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = {"value": round(done / spent, 3), "unit": "iters/s", "cores": cores, "kind": "oracle",
+               "sample": f"first {done} iterations of the same workload, same shards and row ids "
+                         f"(oracle time only; row gather excluded)"}
+
+    out = {"metric": "G-CADA iterations/s", "value": round(iters_s, 2), "unit": "iters/s",
+           "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 5),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if w.dtype == "f32" else "bf16",
+           "data": "synthetic",
+           "config": {"workload": w.name, "model": None, "G": w.G, "M_G": w.M_G, "mu": w.mu,
+                      "widths": list(w.widths), "rows_per_shard": w.rows, "D": w.D, "c": w.c,
+                      "l2": w.l2, "parallelism": "1 GPU, all groups simulated"},
+           "grad_evals_per_s": round(2 * w.G * iters_s, 1),
+           "sample_grad_evals_per_s": round(2 * w.G * w.mu * iters_s, 1),
+           "final_loss": float(l_host[-1]), "roofline": roofline, "cpu_baseline": cpu,
+           "cost_model": model, "setup_s": round(gen_s, 2)}
+    out["config"].pop("model")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

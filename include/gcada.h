@@ -181,6 +181,17 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
                      const double* T /*[host] G*M_G*/, double* time, int64_t* comm,
                      int64_t* comp);
 
+/*
+ * Diagnostics for benchmarks: time the gradient stage (step a1, the kernels that read the
+ * minibatch) of the next `max_steps` calls of gcada_step with HIP events recorded on the step's
+ * stream.  gcada_timing_begin creates the events (synchronous, allocates; call it outside the
+ * measured loop); gcada_timing_end synchronises the device, returns the number of timed steps
+ * and the sum of their gradient-stage durations in milliseconds, and releases the events.
+ * Errors: GCADA_EINVAL (max_steps < 1), GCADA_EDEVICE.
+ */
+int gcada_timing_begin(gcada_ctx* ctx, int32_t max_steps);
+int gcada_timing_end(gcada_ctx* ctx, int32_t* steps /*[host]*/, double* grad_ms /*[host]*/);
+
 /* Message of the last error on this context ("" if none); NULL ctx: last gcada_create error. */
 const char* gcada_last_error(const gcada_ctx* ctx);
 

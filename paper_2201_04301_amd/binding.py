@@ -20,7 +20,7 @@ GCADA_MAX_WIDTHS = 8
 
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
-           "gcada_last_error", "gcada_version"]
+           "gcada_last_error", "gcada_version", "gcada_timing_begin", "gcada_timing_end"]
 
 
 class gcada_dims(C.Structure):
@@ -72,6 +72,10 @@ def _load():
     L.gcada_cost_model.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.POINTER(C.c_double),
                                    C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    L.gcada_timing_begin.restype = C.c_int
+    L.gcada_timing_begin.argtypes = [C.c_void_p, C.c_int32]
+    L.gcada_timing_end.restype = C.c_int
+    L.gcada_timing_end.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
     L.gcada_last_error.restype = C.c_char_p
     L.gcada_last_error.argtypes = [C.c_void_p]
     L.gcada_version.restype = C.c_char_p
@@ -151,3 +155,13 @@ def gcada_version() -> str:
 
 def gcada_last_error(ctx=None) -> str:
     return (lib.gcada_last_error(ctx) or b"").decode()
+
+
+def gcada_timing_begin(ctx, max_steps: int):
+    _check(lib.gcada_timing_begin(ctx, max_steps), ctx)
+
+
+def gcada_timing_end(ctx):
+    n, ms = C.c_int32(), C.c_double()
+    _check(lib.gcada_timing_end(ctx, C.byref(n), C.byref(ms)), ctx)
+    return n.value, ms.value

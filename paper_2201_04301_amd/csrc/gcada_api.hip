@@ -55,6 +55,8 @@ void free_all(gcada_ctx* c)
 {
     if (!c) return;
     gcada::mlp_free(c);
+    for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+    c->ev.clear();
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->grad, c->last, c->tau,
                     c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat,
                     c->part_sq};
@@ -231,9 +233,15 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     for (int g = 0; g < ctx->hy.G; ++g)
         if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "step: a group has no shard");
     hipStream_t s = (hipStream_t)stream;
+    const bool timed = (size_t)ctx->ev_used + 2 <= ctx->ev.size();
+    if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], s);
     hipError_t e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, idx, s)
                                                    : gcada::mlp_gradients(ctx, idx, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
+    if (timed) {
+        (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], s);
+        ctx->ev_used += 2;
+    }
     if ((e = gcada::select_groups(ctx, mask_out, loss_out, s)) != hipSuccess)
         return fail_hip(ctx, e, "selection kernel");
     if ((e = gcada::server_update(ctx, s)) != hipSuccess)
@@ -333,6 +341,42 @@ try {
     return GCADA_OK;
 } catch (...) {
     return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_set_state");
+}
+
+int gcada_timing_begin(gcada_ctx* ctx, int32_t max_steps)
+try {
+    if (!ctx) return GCADA_EINVAL;
+    if (max_steps < 1) return fail(ctx, GCADA_EINVAL, "timing_begin: max_steps must be >= 1");
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+    ctx->ev.clear();
+    ctx->ev_used = 0;
+    ctx->ev.reserve((size_t)2 * max_steps);
+    for (int i = 0; i < 2 * max_steps; ++i) {
+        hipEvent_t e;
+        HIP_TRY(ctx, hipEventCreate(&e));
+        ctx->ev.push_back(e);
+    }
+    return GCADA_OK;
+} catch (...) {
+    return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_timing_begin");
+}
+
+int gcada_timing_end(gcada_ctx* ctx, int32_t* steps, double* grad_ms)
+{
+    if (!ctx) return GCADA_EINVAL;
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    double total = 0;
+    for (int i = 0; i + 1 < ctx->ev_used; i += 2) {
+        float ms = 0;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]));
+        total += ms;
+    }
+    if (steps) *steps = ctx->ev_used / 2;
+    if (grad_ms) *grad_ms = total;
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+    ctx->ev.clear();
+    ctx->ev_used = 0;
+    return GCADA_OK;
 }
 
 int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask, const double* T,

@@ -79,6 +79,10 @@ struct gcada_ctx {
 
     gcada::MlpWork* mlp = nullptr;
 
+    // optional event timing of the gradient stage
+    std::vector<hipEvent_t> ev;    // 2 per step: before / after
+    int32_t ev_used = 0;
+
     std::string err;
 };
 

@@ -182,6 +182,16 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
                      int64_t* comp);
 
 /*
+ * Tuning switches (defaults in brackets).  GCADA_OPT_SINGLE_PASS_LOGREG [1]: compute the logistic
+ * gradients with the kernel that reads the minibatch from HBM once (whole-row register tiles)
+ * when the shape allows it (d in {256, 512, 1024, 2048, 4096}, mu a multiple of the tile's rows,
+ * 16-byte aligned shards); 0 forces the general two-pass kernels.  Both compute the same step
+ * a1.  Errors: GCADA_EINVAL (unknown option).
+ */
+enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1 };
+int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
+
+/*
  * Diagnostics for benchmarks: time the gradient stage (step a1, the kernels that read the
  * minibatch) of the next `max_steps` calls of gcada_step with HIP events recorded on the step's
  * stream.  gcada_timing_begin creates the events (synchronous, allocates; call it outside the

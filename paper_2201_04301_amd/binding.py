@@ -17,10 +17,12 @@ GCADA_OK, GCADA_EINVAL, GCADA_ENOMEM, GCADA_EDEVICE, GCADA_ESTATE = range(5)
 GCADA_LOGREG, GCADA_MLP = 0, 1
 GCADA_F32, GCADA_BF16 = 0, 1
 GCADA_MAX_WIDTHS = 8
+GCADA_OPT_SINGLE_PASS_LOGREG = 1
 
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
-           "gcada_last_error", "gcada_version", "gcada_timing_begin", "gcada_timing_end"]
+           "gcada_last_error", "gcada_version", "gcada_timing_begin", "gcada_timing_end",
+           "gcada_set_option"]
 
 
 class gcada_dims(C.Structure):
@@ -72,6 +74,8 @@ def _load():
     L.gcada_cost_model.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.POINTER(C.c_double),
                                    C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    L.gcada_set_option.restype = C.c_int
+    L.gcada_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.gcada_timing_begin.restype = C.c_int
     L.gcada_timing_begin.argtypes = [C.c_void_p, C.c_int32]
     L.gcada_timing_end.restype = C.c_int
@@ -165,3 +169,7 @@ def gcada_timing_end(ctx):
     n, ms = C.c_int32(), C.c_double()
     _check(lib.gcada_timing_end(ctx, C.byref(n), C.byref(ms)), ctx)
     return n.value, ms.value
+
+
+def gcada_set_option(ctx, option: int, value: int):
+    _check(lib.gcada_set_option(ctx, option, value), ctx)

@@ -42,6 +42,16 @@ hipError_t dalloc(T** p, size_t n)
     return e;
 }
 
+// A bounded wait inside a kernel gave up: the results of that step are not valid.
+int check_device_flag(gcada_ctx* c)
+{
+    Ctl z{};
+    hipError_t e = hipMemcpy(&z, c->ctl, sizeof(z), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(c, e, "read control block");
+    if (z.error != 0) return fail(c, GCADA_EDEVICE, "a barrier wait inside a kernel timed out");
+    return GCADA_OK;
+}
+
 int64_t param_count(const gcada_dims& d)
 {
     if (d.model == GCADA_LOGREG) return d.widths[0];
@@ -55,6 +65,7 @@ void free_all(gcada_ctx* c)
 {
     if (!c) return;
     gcada::mlp_free(c);
+    gcada::lr_tile_free(c);
     for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
     c->ev.clear();
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->grad, c->last, c->tau,
@@ -141,6 +152,8 @@ try {
     e = dims->model == GCADA_LOGREG ? gcada::lr_plan(x) : gcada::mlp_plan(x);
     if (e != hipSuccess) return bail(e, "model plan");
     if ((e = gcada::select_plan(x)) != hipSuccess) return bail(e, "server plan");
+    if (dims->model == GCADA_LOGREG && (e = gcada::lr_tile_plan(x)) != hipSuccess)
+        return bail(e, "single-pass logistic plan");
     if ((e = dalloc(&x->part_loss, (size_t)G * x->n_loss_part)) != hipSuccess) return bail(e, "alloc scratch");
     if ((e = dalloc(&x->part_stat, (size_t)G * x->n_stat_part)) != hipSuccess) return bail(e, "alloc scratch");
     if ((e = dalloc(&x->part_sq, (size_t)2 * x->n_epi_blocks)) != hipSuccess) return bail(e, "alloc scratch");
@@ -205,6 +218,7 @@ static int reset_run(gcada_ctx* ctx, const float* theta0_any)
 
 static int after_state_change(gcada_ctx* ctx)
 {
+    ctx->hy.k = ctx->k;
     HIP_TRY(ctx, gcada::refresh_theta_sq(ctx, nullptr));
     if (ctx->dims.model == GCADA_MLP) HIP_TRY(ctx, gcada::mlp_refresh_weights(ctx, nullptr));
     HIP_TRY(ctx, hipDeviceSynchronize());
@@ -233,6 +247,7 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     for (int g = 0; g < ctx->hy.G; ++g)
         if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "step: a group has no shard");
     hipStream_t s = (hipStream_t)stream;
+    ctx->hy.k = ctx->k;
     const bool timed = (size_t)ctx->ev_used + 2 <= ctx->ev.size();
     if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], s);
     hipError_t e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, idx, s)
@@ -242,10 +257,8 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
         (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], s);
         ctx->ev_used += 2;
     }
-    if ((e = gcada::select_groups(ctx, mask_out, loss_out, s)) != hipSuccess)
-        return fail_hip(ctx, e, "selection kernel");
-    if ((e = gcada::server_update(ctx, s)) != hipSuccess)
-        return fail_hip(ctx, e, "server update kernel");
+    if ((e = gcada::server_step(ctx, mask_out, loss_out, s)) != hipSuccess)
+        return fail_hip(ctx, e, "server kernels");
     ctx->k += 1;
     return GCADA_OK;
 }
@@ -274,6 +287,7 @@ try {
     const size_t p = (size_t)hy.p;
     const int nslot = hy.D + 1;
     HIP_TRY(ctx, hipDeviceSynchronize());
+    if (int rc = check_device_flag(ctx)) return rc;
     std::vector<int32_t> tau(hy.G);
     HIP_TRY(ctx, hipMemcpy(tau.data(), ctx->tau, (size_t)hy.G * 4, hipMemcpyDeviceToHost));
     const int cur = (int)(ctx->k % nslot);
@@ -332,7 +346,6 @@ try {
     HIP_TRY(ctx, hipMemcpy(ctx->tau, in->tau, (size_t)hy.G * 4, hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->nring, in->dtheta_sq, (size_t)hy.D * 8, hipMemcpyHostToDevice));
     Ctl z{};
-    z.k = in->k;
     HIP_TRY(ctx, hipMemcpy(ctx->ctl, &z, sizeof(z), hipMemcpyHostToDevice));
     ctx->k = in->k;
     int rc = after_state_change(ctx);
@@ -341,6 +354,16 @@ try {
     return GCADA_OK;
 } catch (...) {
     return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_set_state");
+}
+
+int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
+{
+    if (!ctx) return GCADA_EINVAL;
+    if (option == GCADA_OPT_SINGLE_PASS_LOGREG) {
+        ctx->allow_single_pass = value != 0;
+        return GCADA_OK;
+    }
+    return fail(ctx, GCADA_EINVAL, "set_option: unknown option");
 }
 
 int gcada_timing_begin(gcada_ctx* ctx, int32_t max_steps)
@@ -353,7 +376,7 @@ try {
     ctx->ev.reserve((size_t)2 * max_steps);
     for (int i = 0; i < 2 * max_steps; ++i) {
         hipEvent_t e;
-        HIP_TRY(ctx, hipEventCreate(&e));
+        HIP_TRY(ctx, hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
         ctx->ev.push_back(e);
     }
     return GCADA_OK;
@@ -365,6 +388,7 @@ int gcada_timing_end(gcada_ctx* ctx, int32_t* steps, double* grad_ms)
 {
     if (!ctx) return GCADA_EINVAL;
     HIP_TRY(ctx, hipDeviceSynchronize());
+    if (int rc = check_device_flag(ctx)) return rc;
     double total = 0;
     for (int i = 0; i + 1 < ctx->ev_used; i += 2) {
         float ms = 0;

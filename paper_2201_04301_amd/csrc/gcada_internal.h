@@ -21,7 +21,6 @@ struct ShardDesc {
 
 // Device-resident control block: everything a step decides stays on the device.
 struct Ctl {
-    long long k;            // iterations done
     double rhs;             // threshold of the last step
     double loss;            // loss of the last step
     double theta_sq;        // ||theta^k||^2 (for the l2 term of the loss)
@@ -33,13 +32,15 @@ struct Ctl {
 
 // Scalars every kernel needs, passed by value.
 struct Hyper {
+    long long k;            // iteration index of this launch (the host counts the iterations)
     int32_t G, D, mu;
     int64_t p, pstride;     // parameters; floats between ring slots
     float l2;
     double c, alpha, beta1, beta2, eps;
 };
 
-struct MlpWork;   // MLP activations and compute copies (mlp_kernels.hip)
+struct MlpWork;       // MLP activations and compute copies (mlp_kernels.hip)
+struct LrTilePlan;    // single-pass logistic path (lr_tiles.hip)
 
 }  // namespace gcada
 
@@ -48,7 +49,7 @@ struct gcada_ctx {
     gcada::Hyper hy{};
     int32_t M_G = 1;
     int device = 0;
-    int64_t k = 0;                 // host mirror of Ctl::k
+    int64_t k = 0;                 // iterations done; copied into Hyper::k before every launch
     bool theta_set = false;
     std::vector<gcada::ShardDesc> shards;   // host copy
     std::vector<uint8_t> shard_set;
@@ -72,12 +73,16 @@ struct gcada_ctx {
     double* part_loss = nullptr;   // per-block partial loss sums
     double* part_stat = nullptr;   // G x n_stat_part partial squared norms
     double* part_sq = nullptr;     // epilogue partials: 2 per block (||step||^2, ||theta_new||^2)
-    int32_t n_loss_part = 0;   // partial loss sums per group
+    int32_t n_loss_part = 0;   // allocated partial loss sums per group
+    int32_t n_loss_part_lr = 0;   // blocks per group of the general logistic forward kernel
     int32_t n_stat_part = 0;   // allocated partial squared norms per group
     int32_t n_stat_used = 0;   // partials per group the last gradient launch wrote
+    int32_t n_loss_used = 0;   // partial loss sums (all groups) the last gradient launch wrote
     int32_t n_epi_blocks = 0;
 
     gcada::MlpWork* mlp = nullptr;
+    gcada::LrTilePlan* lr_tiles = nullptr;
+    bool allow_single_pass = true;
 
     // optional event timing of the gradient stage
     std::vector<hipEvent_t> ev;    // 2 per step: before / after
@@ -92,16 +97,21 @@ namespace gcada {
 hipError_t lr_plan(gcada_ctx* c);                      // sizes scratch (create time)
 hipError_t lr_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
 
+// single-pass logistic gradients with whole-row register tiles (lr_tiles.hip)
+hipError_t lr_tile_plan(gcada_ctx* c);
+void lr_tile_free(gcada_ctx* c);
+bool lr_tile_applies(const gcada_ctx* c);
+hipError_t lr_tile_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
+
 hipError_t mlp_plan(gcada_ctx* c);
 void mlp_free(gcada_ctx* c);
 hipError_t mlp_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
 hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s);   // bf16 copies of all ring slots
 
 hipError_t select_plan(gcada_ctx* c);
-// stat/loss partials -> stat, rhs, mask, tau; writes mask_out / loss_out
-hipError_t select_groups(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s);
-// masked innovation sum + server update + history; advances Ctl::k
-hipError_t server_update(gcada_ctx* c, hipStream_t s);
+// selection (a2) + masked innovation sum (a3) + server update and history (a4); advances
+// Ctl::k and the ages; writes mask_out / loss_out
+hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s);
 // ||theta^k||^2 of the current slot -> Ctl::theta_sq (after set_theta / set_state)
 hipError_t refresh_theta_sq(gcada_ctx* c, hipStream_t s);
 

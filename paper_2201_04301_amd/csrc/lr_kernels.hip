@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kFwdWaves* kWave) void lr_forward(
     const int g = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int d = (int)hy.p, mu = hy.mu;
-    const long long k = ctl->k;
+    const long long k = hy.k;
     const int nslot = hy.D + 1;
     const int cur = (int)(k % nslot);
     const int old = (int)(((k - tau[g]) % nslot + nslot) % nslot);
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kBwdWaves* kWave) void lr_backward(
     const int g = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int d = (int)hy.p, mu = hy.mu;
-    const long long k = ctl->k;
+    const long long k = hy.k;
     const ShardDesc sh = shards[g];
     const float* __restrict__ X = (const float*)sh.X;
 
@@ -253,7 +253,8 @@ hipError_t lr_plan(gcada_ctx* c)
 {
     const int mu = c->hy.mu;
     const int d = (int)c->hy.p;
-    c->n_loss_part = (mu + kFwdWaves * kFwdRows - 1) / (kFwdWaves * kFwdRows);   // per group
+    c->n_loss_part_lr = (mu + kFwdWaves * kFwdRows - 1) / (kFwdWaves * kFwdRows);   // per group
+    c->n_loss_part = c->n_loss_part_lr;
     c->n_stat_part = (d + kWave - 1) / kWave;        // per group, worst case (scalar path)
     hipError_t e;
     if ((e = hipMalloc(&c->res, sizeof(float) * 2 * (size_t)c->hy.G * mu)) != hipSuccess) return e;
@@ -270,10 +271,12 @@ static bool lr_vec_ok(const gcada_ctx* c)
 
 hipError_t lr_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
 {
+    if (lr_tile_applies(c)) return lr_tile_gradients(c, idx, s);
+    c->n_loss_used = c->n_loss_part_lr * c->hy.G;
     const Hyper& hy = c->hy;
     const bool vec = lr_vec_ok(c);
     const int d = (int)hy.p;
-    dim3 gf(c->n_loss_part, hy.G), bf(kFwdWaves * kWave);
+    dim3 gf(c->n_loss_part_lr, hy.G), bf(kFwdWaves * kWave);
     if (vec) {
         lr_forward<true><<<gf, bf, 0, s>>>(c->d_shards, idx, c->ring, c->tau, c->ctl, hy, c->res,
                                             c->part_loss);

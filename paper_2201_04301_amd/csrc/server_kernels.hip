@@ -36,22 +36,54 @@ __device__ double block_sum_strided(const double* __restrict__ v, int n, double*
 
 constexpr int kSelBlock = 256;
 
-// One block.  stat_g <- sum of its partials; rhs <- (c/D) * sum of the history ring;
-// mask_g <- stat_g > rhs  or  tau_g >= D  or  rhs == 0;  ages updated;  loss assembled.
+// Selection (step a2) by one wave per group: stat_g <- sum of its partials (fixed order);
+// mask_g <- stat_g > rhs  or  tau_g >= D  or  rhs == 0.
+__device__ __forceinline__ void select_groups_block(const Hyper& hy, const double* __restrict__ part_stat,
+                                                    int n_stat, const int32_t* __restrict__ tau,
+                                                    double rhs, uint8_t* s_mask, double* stat_out,
+                                                    uint8_t* mask_a, uint8_t* mask_b, int nwaves)
+{
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    for (int g = wave; g < hy.G; g += nwaves) {
+        double a = 0;
+        const double* v = part_stat + (int64_t)g * n_stat;
+        for (int i = lane; i < n_stat; i += kWave) a += v[i];
+        a = wave_sum(a);
+        if (lane == 0) {
+            const bool sel = (a > rhs) || (tau[g] >= hy.D) || (rhs == 0.0);
+            s_mask[g] = sel ? 1 : 0;
+            if (stat_out) stat_out[g] = a;
+            if (mask_a) mask_a[g] = sel ? 1 : 0;
+            if (mask_b) mask_b[g] = sel ? 1 : 0;
+        }
+    }
+}
+
+// Right side of Eq. (9) with c_d = c/D.  Called by one whole wave: the D history entries are
+// loaded in parallel and added in the butterfly's fixed order.
+__device__ __forceinline__ double history_threshold(const Hyper& hy, const double* __restrict__ nring)
+{
+    const int lane = threadIdx.x % kWave;
+    double v = 0;
+    for (int j = lane; j < hy.D; j += kWave) v += nring[j];
+    v = wave_sum(v);
+    return hy.c / (double)hy.D * v;
+}
+
+// One block, used when the partial statistics are too many for every update block to re-add.
+// Writes stat, mask, rhs, loss and the caller's outputs; the ages are advanced by the update.
 __global__ __launch_bounds__(kSelBlock) void select_kernel(
     Hyper hy, const double* __restrict__ part_stat, int n_stat, const double* __restrict__ part_loss,
-    int n_loss_total, const double* __restrict__ nring, int32_t* __restrict__ tau,
+    int n_loss_total, const double* __restrict__ nring, const int32_t* __restrict__ tau,
     double* __restrict__ stat, uint8_t* __restrict__ mask, Ctl* __restrict__ ctl,
     uint8_t* __restrict__ mask_out, float* __restrict__ loss_out)
 {
     __shared__ double s_tmp[kSelBlock / kWave];
     __shared__ double s_rhs;
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-
-    if (threadIdx.x == 0) {
-        double hsum = 0;
-        for (int j = 0; j < hy.D; ++j) hsum += nring[j];
-        s_rhs = hy.c / (double)hy.D * hsum;
+    extern __shared__ uint8_t s_mask[];
+    if (threadIdx.x < kWave) {
+        const double r = history_threshold(hy, nring);
+        if (threadIdx.x == 0) s_rhs = r;
     }
     const double lsum = block_sum_strided<kSelBlock>(part_loss, n_loss_total, s_tmp);
     __syncthreads();
@@ -63,21 +95,8 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
         ctl->loss = loss;
         if (loss_out) *loss_out = (float)loss;
     }
-    // one wave per group, groups dealt round-robin to the waves
-    for (int g = wave; g < hy.G; g += kSelBlock / kWave) {
-        double a = 0;
-        const double* v = part_stat + (int64_t)g * n_stat;
-        for (int i = lane; i < n_stat; i += kWave) a += v[i];
-        a = wave_sum(a);
-        if (lane == 0) {
-            const int t = tau[g];
-            const bool sel = (a > rhs) || (t >= hy.D) || (rhs == 0.0);
-            stat[g] = a;
-            mask[g] = sel ? 1 : 0;
-            if (mask_out) mask_out[g] = sel ? 1 : 0;
-            tau[g] = sel ? 1 : t + 1;
-        }
-    }
+    select_groups_block(hy, part_stat, n_stat, tau, rhs, s_mask, stat, mask, mask_out,
+                        kSelBlock / kWave);
 }
 
 constexpr int kUpdBlock = 256;
@@ -103,83 +122,203 @@ __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&v
     }
 }
 
-// grid: ceil(p / (256*VW)) blocks.  Thread owns VW consecutive parameters.
-//   agg  += sum over selected g (ascending) of grad_g - last_g;  last_g <- grad_g
-//   h, vhat, theta^{k+1} by Eq. (8a)-(8c);  theta^{k+1} goes to ring slot (k+1) mod (D+1)
+struct ServerArgs {
+    Hyper hy;
+    const double* part_stat;   // SELECT: [G][n_stat]
+    int n_stat;
+    const double* part_loss;   // SELECT: n_loss_total entries
+    int n_loss_total;
+    double* stat;
+    uint8_t* mask;             // written (SELECT) or read (!SELECT)
+    uint8_t* mask_out;
+    float* loss_out;
+    const float* grad;
+    float* last;
+    float* agg;
+    float* h;
+    float* vhat;
+    float* ring;
+    double* nring;
+    int32_t* tau;
+    double* part_sq;
+    Ctl* ctl;
+};
+
+// grid: ceil(p / (B*VW)) blocks of B threads.  Thread owns VW consecutive parameters.
+//   SELECT: every block first derives the selection mask from the partial statistics (same
+//           fixed order everywhere, so all blocks agree); block 0 publishes it with the loss.
+//   a3: agg += sum over selected g (ascending) of grad_g - last_g;  last_g <- grad_g
+//   a4: h, vhat, theta^{k+1} by Eq. (8a)-(8c);  theta^{k+1} goes to ring slot (k+1) mod (D+1)
 //   per-block partials of ||alpha h / sqrt(eps+vhat)||^2 and ||theta^{k+1}||^2;
-//   the block that finishes last adds them up in a fixed order, stores the history entry at
-//   index k mod D and advances k.
-template <int VW>
-__global__ __launch_bounds__(kUpdBlock) void server_update_kernel(
-    Hyper hy, const uint8_t* __restrict__ mask, const float* __restrict__ grad,
-    float* __restrict__ last, float* __restrict__ agg, float* __restrict__ h,
-    float* __restrict__ vhat, float* __restrict__ ring, double* __restrict__ nring,
-    double* part_sq, Ctl* ctl)
+//   the block that finishes last (the only block, when the grid has one) adds them up in a
+//   fixed order, stores the history entry at index k mod D and advances the ages (Algorithm 1).
+// The kernel is a chain of dependent memory round trips, so every load that does not depend on
+// the mask is issued at the top, and the loads of the selected groups go out four groups at a
+// time.  dynamic LDS: G bytes (mask) + G ints (selected list) + G doubles (statistics).
+template <int B, int VW, bool SELECT>
+__global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
 {
-    __shared__ double s_a[kUpdBlock / kWave], s_b[kUpdBlock / kWave];
+    __shared__ double s_a[B / kWave], s_b[B / kWave];
+    __shared__ double s_rhs;
+    __shared__ int s_nsel;
     __shared__ bool s_last;
+    extern __shared__ double s_dyn[];
+    const Hyper& hy = a.hy;
+    double* s_stat = s_dyn;                                   // G
+    int* s_sel = (int*)(s_dyn + hy.G);                        // G
+    uint8_t* s_mask = (uint8_t*)(s_sel + hy.G);               // G
+    Ctl* ctl = a.ctl;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const long long k = ctl->k;
+    constexpr int NW = B / kWave;
+    const long long k = hy.k;
     const int nslot = hy.D + 1;
-    const float* __restrict__ th = ring + (int64_t)(k % nslot) * hy.pstride;
-    float* __restrict__ tn = ring + (int64_t)((k + 1) % nslot) * hy.pstride;
+    const float* __restrict__ th = a.ring + (int64_t)(k % nslot) * hy.pstride;
+    float* __restrict__ tn = a.ring + (int64_t)((k + 1) % nslot) * hy.pstride;
+
+    const int64_t j0 = ((int64_t)blockIdx.x * B + threadIdx.x) * VW;
+    const bool active = j0 < hy.p;
+    float ac[VW] = {}, hv[VW] = {}, vv[VW] = {}, tv[VW] = {}, nv[VW];
+    if (active) {
+        load_vec<VW>(a.agg + j0, ac);
+        load_vec<VW>(a.h + j0, hv);
+        load_vec<VW>(a.vhat + j0, vv);
+        load_vec<VW>(th + j0, tv);
+    }
+    const bool pub = SELECT && blockIdx.x == 0;
+    int my_tau = 0;
+    if ((int)threadIdx.x < hy.G) my_tau = a.tau[threadIdx.x];      // groups beyond B are read below
+    if constexpr (SELECT) {
+        // statistics: one wave per group, partials added in lane-strided order then butterfly
+        for (int g = wave; g < hy.G; g += NW) {
+            double t = 0;
+            const double* v = a.part_stat + (int64_t)g * a.n_stat;
+            for (int i = lane; i < a.n_stat; i += kWave) t += v[i];
+            t = wave_sum(t);
+            if (lane == 0) s_stat[g] = t;
+        }
+        double lpart = 0;
+        if (pub)
+            for (int i = threadIdx.x; i < a.n_loss_total; i += B) lpart += a.part_loss[i];
+        if (wave == 0) {
+            const double r = history_threshold(hy, a.nring);
+            if (lane == 0) s_rhs = r;
+        }
+        if (pub) {
+            lpart = wave_sum(lpart);
+            if (lane == 0) s_a[wave] = lpart;
+        }
+        __syncthreads();
+        const double rhs = s_rhs;
+        for (int g = threadIdx.x; g < hy.G; g += B) {
+            const int t = g < B ? my_tau : a.tau[g];
+            const double st = s_stat[g];
+            const bool sel = (st > rhs) || (t >= hy.D) || (rhs == 0.0);
+            s_mask[g] = sel ? 1 : 0;
+            if (pub) {
+                a.stat[g] = st;
+                a.mask[g] = sel ? 1 : 0;
+                if (a.mask_out) a.mask_out[g] = sel ? 1 : 0;
+            }
+        }
+        if (pub && threadIdx.x == 0) {
+            double lsum = 0;
+            for (int w = 0; w < NW; ++w) lsum += s_a[w];
+            const double loss =
+                lsum / ((double)hy.G * (double)hy.mu) + 0.5 * (double)hy.l2 * ctl->theta_sq;
+            ctl->rhs = rhs;
+            ctl->loss = loss;
+            if (a.loss_out) *a.loss_out = (float)loss;
+        }
+    } else {
+        for (int g = threadIdx.x; g < hy.G; g += B) s_mask[g] = a.mask[g];
+    }
+    __syncthreads();
+    // ascending list of the selected groups (wave 0, 64 groups per ballot)
+    if (wave == 0) {
+        int n = 0;
+        for (int g0 = 0; g0 < hy.G; g0 += kWave) {
+            const int g = g0 + lane;
+            const bool sel = g < hy.G && s_mask[g];
+            const unsigned long long bal = __ballot(sel);
+            if (sel) s_sel[n + __popcll(bal & ((1ull << lane) - 1ull))] = g;
+            n += __popcll(bal);
+        }
+        if (lane == 0) s_nsel = n;
+    }
+    __syncthreads();
+    const int nsel = s_nsel;
+
     const float b1 = (float)hy.beta1, b2 = (float)hy.beta2, al = (float)hy.alpha,
                 ep = (float)hy.eps;
     const float ob1 = (float)(1.0 - hy.beta1), ob2 = (float)(1.0 - hy.beta2);
-
-    const int64_t j0 = ((int64_t)blockIdx.x * kUpdBlock + threadIdx.x) * VW;
     double sq = 0, tsq = 0;
-    if (j0 < hy.p) {
-        float a[VW], hv[VW], vv[VW], tv[VW], nv[VW];
-        load_vec<VW>(agg + j0, a);
-        for (int g = 0; g < hy.G; ++g) {
-            if (!mask[g]) continue;
-            const int64_t o = (int64_t)g * hy.p + j0;
-            float gg[VW], ll[VW];
-            load_vec<VW>(grad + o, gg);
-            load_vec<VW>(last + o, ll);
+    if (active) {
+        int i = 0;
+        for (; i + 4 <= nsel; i += 4) {              // four groups' loads in flight, added in order
+            float gg[4][VW], ll[4][VW];
 #pragma unroll
-            for (int q = 0; q < VW; ++q) a[q] += gg[q] - ll[q];
-            store_vec<VW>(last + o, gg);
+            for (int e = 0; e < 4; ++e) {
+                const int64_t o = (int64_t)s_sel[i + e] * hy.p + j0;
+                load_vec<VW>(a.grad + o, gg[e]);
+                load_vec<VW>(a.last + o, ll[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                for (int q = 0; q < VW; ++q) ac[q] += gg[e][q] - ll[e][q];
+                store_vec<VW>(a.last + (int64_t)s_sel[i + e] * hy.p + j0, gg[e]);
+            }
         }
-        load_vec<VW>(h + j0, hv);
-        load_vec<VW>(vhat + j0, vv);
-        load_vec<VW>(th + j0, tv);
+        for (; i < nsel; ++i) {
+            const int64_t o = (int64_t)s_sel[i] * hy.p + j0;
+            float gg[VW], ll[VW];
+            load_vec<VW>(a.grad + o, gg);
+            load_vec<VW>(a.last + o, ll);
+#pragma unroll
+            for (int q = 0; q < VW; ++q) ac[q] += gg[q] - ll[q];
+            store_vec<VW>(a.last + o, gg);
+        }
 #pragma unroll
         for (int q = 0; q < VW; ++q) {
-            hv[q] = b1 * hv[q] + ob1 * a[q];
-            const float v = b2 * vv[q] + ob2 * a[q] * a[q];
+            hv[q] = b1 * hv[q] + ob1 * ac[q];
+            const float v = b2 * vv[q] + ob2 * ac[q] * ac[q];
             vv[q] = fmaxf(vv[q], v);
             const float step = al * hv[q] / sqrtf(ep + vv[q]);
             nv[q] = tv[q] - step;
             sq += (double)step * (double)step;
             tsq += (double)nv[q] * (double)nv[q];
         }
-        store_vec<VW>(agg + j0, a);
-        store_vec<VW>(h + j0, hv);
-        store_vec<VW>(vhat + j0, vv);
+        store_vec<VW>(a.agg + j0, ac);
+        store_vec<VW>(a.h + j0, hv);
+        store_vec<VW>(a.vhat + j0, vv);
         store_vec<VW>(tn + j0, nv);
     }
     sq = wave_sum(sq);
     tsq = wave_sum(tsq);
+    __syncthreads();
     if (lane == 0) { s_a[wave] = sq; s_b[wave] = tsq; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        double x = 0, y = 0;
-        for (int w = 0; w < kUpdBlock / kWave; ++w) { x += s_a[w]; y += s_b[w]; }
-        part_sq[2 * (int64_t)blockIdx.x] = x;
-        part_sq[2 * (int64_t)blockIdx.x + 1] = y;
-        __threadfence();                                    // publish the partials device-wide
-        const unsigned int done = atomicAdd(&ctl->cnt_b, 1u);
-        s_last = (done == gridDim.x - 1);
-    }
-    __syncthreads();
-    if (s_last) {
+    double xs = 0, ys = 0;
+    if (gridDim.x == 1) {
+        if (threadIdx.x == 0)
+            for (int w = 0; w < NW; ++w) { xs += s_a[w]; ys += s_b[w]; }
+    } else {
+        if (threadIdx.x == 0) {
+            double x = 0, y = 0;
+            for (int w = 0; w < NW; ++w) { x += s_a[w]; y += s_b[w]; }
+            a.part_sq[2 * (int64_t)blockIdx.x] = x;
+            a.part_sq[2 * (int64_t)blockIdx.x + 1] = y;
+            __threadfence();                                // publish the partials device-wide
+            const unsigned int done = atomicAdd(&ctl->cnt_b, 1u);
+            s_last = (done == gridDim.x - 1);
+        }
+        __syncthreads();
+        if (!s_last) return;
         __threadfence();                                    // see every block's partials
         double x = 0, y = 0;
-        for (int i = threadIdx.x; i < (int)gridDim.x; i += kUpdBlock) {
-            x += part_sq[2 * (int64_t)i];
-            y += part_sq[2 * (int64_t)i + 1];
+        for (int i = threadIdx.x; i < (int)gridDim.x; i += B) {
+            x += a.part_sq[2 * (int64_t)i];
+            y += a.part_sq[2 * (int64_t)i + 1];
         }
         x = wave_sum(x);
         y = wave_sum(y);
@@ -187,13 +326,18 @@ __global__ __launch_bounds__(kUpdBlock) void server_update_kernel(
         if (lane == 0) { s_a[wave] = x; s_b[wave] = y; }
         __syncthreads();
         if (threadIdx.x == 0) {
-            double xs = 0, ys = 0;
-            for (int w = 0; w < kUpdBlock / kWave; ++w) { xs += s_a[w]; ys += s_b[w]; }
-            nring[k % hy.D] = xs;
-            ctl->theta_sq = ys;
-            ctl->k = k + 1;
+            for (int w = 0; w < NW; ++w) { xs += s_a[w]; ys += s_b[w]; }
             ctl->cnt_b = 0;
         }
+    }
+    if (threadIdx.x == 0) {
+        a.nring[k % hy.D] = xs;
+        ctl->theta_sq = ys;
+    }
+    // every block has used the old ages by now
+    for (int g = threadIdx.x; g < hy.G; g += B) {
+        const int t = g < B ? my_tau : a.tau[g];
+        a.tau[g] = s_mask[g] ? 1 : t + 1;
     }
 }
 
@@ -202,7 +346,7 @@ __global__ __launch_bounds__(256) void theta_sq_kernel(Hyper hy, const float* __
                                                         Ctl* __restrict__ ctl)
 {
     __shared__ double s_tmp[256 / kWave];
-    const float* th = ring + (int64_t)(ctl->k % (hy.D + 1)) * hy.pstride;
+    const float* th = ring + (int64_t)(hy.k % (hy.D + 1)) * hy.pstride;
     double a = 0;
     for (int64_t i = threadIdx.x; i < hy.p; i += 256) a += (double)th[i] * (double)th[i];
     a = wave_sum(a);
@@ -217,33 +361,49 @@ __global__ __launch_bounds__(256) void theta_sq_kernel(Hyper hy, const float* __
 
 }  // namespace
 
+constexpr int kBigBlock = 1024;
+
 hipError_t select_plan(gcada_ctx* c)
 {
-    const int64_t per_block = kUpdBlock * 4;
+    const int vw = c->hy.p % 4 == 0 ? 4 : 1;
+    const int64_t per_block = (int64_t)kUpdBlock * vw;
     c->n_epi_blocks = (int32_t)((c->hy.p + per_block - 1) / per_block);
-    // the scalar update path (p % 4 != 0) needs 4x the blocks
-    if (c->hy.p % 4) c->n_epi_blocks = (int32_t)((c->hy.p + kUpdBlock - 1) / kUpdBlock);
     return hipSuccess;
 }
 
-hipError_t select_groups(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s)
+template <int B, int VW>
+static void launch_server(bool self_select, int blocks, size_t lds, hipStream_t s, const ServerArgs& a)
 {
-    select_kernel<<<1, kSelBlock, 0, s>>>(c->hy, c->part_stat, c->n_stat_used, c->part_loss,
-                                          c->n_loss_part * c->hy.G, c->nring, c->tau, c->stat,
-                                          c->mask, c->ctl, mask_out, loss_out);
-    return hipGetLastError();
+    if (self_select) server_step_kernel<B, VW, true><<<blocks, B, lds, s>>>(a);
+    else server_step_kernel<B, VW, false><<<blocks, B, lds, s>>>(a);
 }
 
-hipError_t server_update(gcada_ctx* c, hipStream_t s)
+// Selection + masked innovation sum + server update + history for one iteration.
+hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s)
 {
-    if (c->hy.p % 4 == 0)
-        server_update_kernel<4><<<c->n_epi_blocks, kUpdBlock, 0, s>>>(
-            c->hy, c->mask, c->grad, c->last, c->agg, c->h, c->vhat, c->ring, c->nring,
-            c->part_sq, c->ctl);
-    else
-        server_update_kernel<1><<<c->n_epi_blocks, kUpdBlock, 0, s>>>(
-            c->hy, c->mask, c->grad, c->last, c->agg, c->h, c->vhat, c->ring, c->nring,
-            c->part_sq, c->ctl);
+    const size_t lds = ((size_t)c->hy.G * 13 + 15) / 16 * 16;   // doubles, ints, bytes per group
+    ServerArgs a{};
+    a.hy = c->hy; a.part_stat = c->part_stat; a.n_stat = c->n_stat_used;
+    a.part_loss = c->part_loss; a.n_loss_total = c->n_loss_used;
+    a.stat = c->stat; a.mask = c->mask; a.mask_out = mask_out; a.loss_out = loss_out;
+    a.grad = c->grad; a.last = c->last; a.agg = c->agg; a.h = c->h; a.vhat = c->vhat;
+    a.ring = c->ring; a.nring = c->nring; a.tau = c->tau; a.part_sq = c->part_sq; a.ctl = c->ctl;
+    const bool vec = c->hy.p % 4 == 0;
+    // every update block re-adds the partial statistics when that is cheap
+    const bool self_select = (int64_t)c->hy.G * c->n_stat_used + c->n_loss_used <= 4096;
+    if (!self_select)
+        select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(c->hy, c->part_stat, c->n_stat_used, c->part_loss,
+                                                c->n_loss_used, c->nring, c->tau, c->stat, c->mask,
+                                                c->ctl, mask_out, loss_out);
+    const int vw = vec ? 4 : 1;
+    if (c->hy.p <= (int64_t)kBigBlock * vw) {
+        // the whole parameter vector fits one block: no cross-block hand-over at the end
+        if (vec) launch_server<kBigBlock, 4>(self_select, 1, lds, s, a);
+        else launch_server<kBigBlock, 1>(self_select, 1, lds, s, a);
+    } else {
+        if (vec) launch_server<kUpdBlock, 4>(self_select, c->n_epi_blocks, lds, s, a);
+        else launch_server<kUpdBlock, 1>(self_select, c->n_epi_blocks, lds, s, a);
+    }
     return hipGetLastError();
 }
 

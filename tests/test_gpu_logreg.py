@@ -87,3 +87,52 @@ def test_lr_deterministic(par):
     b = par.free_running(w, 12, Xs, ys, idx)
     np.testing.assert_array_equal(a["theta_gpu"], b["theta_gpu"])
     np.testing.assert_array_equal(a["masks_gpu"], b["masks_gpu"])
+
+
+# ---- single-pass kernel (whole-row register tiles): every wave arrangement, one and several
+# tiles per group; the last two shapes are too wide for it and take the general kernels
+
+@pytest.mark.parametrize("d,mu,G,rows,l2,use_idx", [
+    (4096, 256, 16, 1024, 1e-4, True),    # 16 x 4096 tiles, 16 tiles per group
+    (4096, 48, 40, 600, 0.0, True),       # three tiles per group
+    (2048, 128, 7, 300, 1e-3, True),      # 32 x 2048 tiles
+    (1024, 64, 5, 100, 0.0, True),        # 64 x 1024 tiles, one tile per group
+    (512, 256, 3, 300, 1e-4, True),       # 128 x 512 tiles
+    (256, 512, 2, 600, 0.0, True),        # 256 x 256 tiles
+    (4096, 256, 16, 700, 1e-4, False),    # cyclic window
+    (8192, 48, 5, 100, 0.0, True),        # general kernels
+    (65536, 32, 4, 64, 0.0, True),        # general kernels, d of the largest configuration
+])
+def test_lr_tile_shapes(par, d, mu, G, rows, l2, use_idx):
+    w = scaled(CONFIGS["lr_small"], name="tiles", widths=(d,), mu=mu, G=G, rows=rows, l2=l2, c=1.0,
+               D=5, flip=0.05)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 14
+    idx = make_indices(w, steps) if use_idx else None
+    worst = par.teacher_forced(w, steps, Xs, ys, idx)
+    _say(worst)
+
+
+def test_lr_single_pass_matches_general_kernels(par):
+    # the single-pass kernel and the general two-pass kernels compute the same iteration
+    from paper_2201_04301_amd import Gcada, binding as B
+    from gcada_inputs import make_theta0
+    w = scaled(CONFIGS["lr_4k"], rows=1024, c=0.5)
+    Xs, ys = make_shards(w, "cuda")
+    idx = torch.as_tensor(make_indices(w, 25), device="cuda")
+    res = []
+    for fused in (1, 0):
+        gpu = Gcada.from_workload(w)
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_SINGLE_PASS_LOGREG, fused)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        masks = torch.zeros(25, w.G, dtype=torch.uint8, device="cuda")
+        for k in range(25):
+            gpu.step(idx[k].contiguous(), mask_out=masks[k])
+        st = gpu.get_state()
+        res.append((masks.cpu().numpy(), st["theta"], gpu.outputs()["stat"]))
+        gpu.close()
+    np.testing.assert_array_equal(res[0][0], res[1][0])
+    np.testing.assert_allclose(res[0][1], res[1][1], rtol=0, atol=2e-4 * np.abs(res[1][1]).max())
+    np.testing.assert_allclose(res[0][2], res[1][2], rtol=2e-5)

@@ -23,7 +23,7 @@ _LIB = os.path.join(_HERE, "libgcada_oracle.so")
 LOGISTIC, MLP, QUADRATIC = 0, 1, 2
 
 (F_THETA, F_H, F_VHAT, F_AGG, F_THETA_STALE, F_LAST, F_GRAD, F_GRAD_STALE, F_STAT, F_RING,
- F_LOSS_G) = range(11)
+ F_LOSS_G, F_KINK) = range(12)
 
 
 def build(force: bool = False) -> str:
@@ -196,6 +196,7 @@ class Oracle:
     stat = property(lambda s: s._view(F_STAT, (s.cfg.G,)))
     ring = property(lambda s: s._view(F_RING, (s.cfg.D,)))
     loss_g = property(lambda s: s._view(F_LOSS_G, (s.cfg.G,)))
+    kink = property(lambda s: s._view(F_KINK, (s.cfg.G,)))
 
     @property
     def tau(self):

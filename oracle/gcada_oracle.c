@@ -68,6 +68,8 @@ typedef struct orc_ctx {
     double *stat;                        /* G                                   */
     double *ring;                        /* D squared iterate differences       */
     double *loss_g;                      /* G: minibatch loss sums at theta^k   */
+    double *kink;                        /* G: smallest relative distance of a hidden pre-activation
+                                            to the ReLU kink in this step (diagnostic; 1 if none) */
     double rhs, loss;
     int32_t *tau;                        /* G                                   */
     uint8_t *mask;                       /* G                                   */
@@ -142,7 +144,7 @@ static double quadratic_sample(const double *theta, const float *x, double y, in
    loss = log sum exp(logits) - logits[y].  ReLU'(0) = 0.
    work: 2 * sum(widths) doubles (activations, then deltas). */
 static double mlp_sample(const orc_config *cfg, const double *theta, const float *x, int32_t y,
-                         double *grad, double *work)
+                         double *grad, double *work, double *kink)
 {
     const int L = cfg->n_widths - 1;
     const int32_t *n = cfg->widths;
@@ -156,9 +158,16 @@ static double mlp_sample(const orc_config *cfg, const double *theta, const float
     for (int l = 1; l <= L; ++l) {
         const double *b = W + (int64_t)n[l] * n[l - 1];
         for (int o = 0; o < n[l]; ++o) {
-            double z = b[o];
+            double z = b[o], az = fabs(b[o]);
             const double *row = W + (int64_t)o * n[l - 1];
-            for (int i = 0; i < n[l - 1]; ++i) z += row[i] * act[l - 1][i];
+            for (int i = 0; i < n[l - 1]; ++i) {
+                z += row[i] * act[l - 1][i];
+                az += fabs(row[i] * act[l - 1][i]);
+            }
+            /* diagnostic only: how close this hidden pre-activation is to the ReLU kink, relative
+               to the sum of the magnitudes of its terms (a comparison in lower precision may
+               land on the other side of the kink when this is tiny) */
+            if (kink && l < L && az > 0 && fabs(z) / az < *kink) *kink = fabs(z) / az;
             act[l][o] = (l < L && z < 0) ? 0.0 : z;      /* z == 0 stays 0 either way */
         }
         W = b + n[l];
@@ -202,8 +211,8 @@ static double mlp_sample(const orc_config *cfg, const double *theta, const float
 /* Sum over n samples of [ loss(theta; z) + (l2/2)||theta||^2 ]; if grad != NULL it is
    OVERWRITTEN with the gradient of that sum.  X is n x widths[0] row-major fp32 (promoted
    exactly); y is float[n] (logistic: +-1, quadratic: target) or int32[n] (MLP class id). */
-double orc_loss_grad_sum(const orc_config *cfg, const double *theta, const float *X, const void *y,
-                         int64_t n, double *grad)
+static double loss_grad_sum_k(const orc_config *cfg, const double *theta, const float *X,
+                              const void *y, int64_t n, double *grad, double *kink)
 {
     const int64_t p = orc_param_count(cfg);
     const int64_t d = cfg->widths[0];
@@ -222,7 +231,7 @@ double orc_loss_grad_sum(const orc_config *cfg, const double *theta, const float
         else if (cfg->model == ORC_QUADRATIC)
             loss += quadratic_sample(theta, x, (double)((const float *)y)[i], d, grad);
         else
-            loss += mlp_sample(cfg, theta, x, ((const int32_t *)y)[i], grad, work);
+            loss += mlp_sample(cfg, theta, x, ((const int32_t *)y)[i], grad, work, kink);
     }
     free(work);
     if (cfg->l2 != 0) {
@@ -233,6 +242,12 @@ double orc_loss_grad_sum(const orc_config *cfg, const double *theta, const float
             for (int64_t j = 0; j < p; ++j) grad[j] += (double)n * cfg->l2 * theta[j];
     }
     return loss;
+}
+
+double orc_loss_grad_sum(const orc_config *cfg, const double *theta, const float *X, const void *y,
+                         int64_t n, double *grad)
+{
+    return loss_grad_sum_k(cfg, theta, X, y, n, grad, NULL);
 }
 
 /* Server update, Eq. (8a)-(8c):
@@ -264,7 +279,7 @@ void orc_destroy(orc_ctx *c)
     if (!c) return;
     free(c->theta); free(c->h); free(c->vhat); free(c->agg);
     free(c->theta_stale); free(c->last); free(c->grad); free(c->grad_stale);
-    free(c->stat); free(c->ring); free(c->loss_g); free(c->tau); free(c->mask);
+    free(c->stat); free(c->ring); free(c->loss_g); free(c->kink); free(c->tau); free(c->mask);
     free(c);
 }
 
@@ -280,7 +295,7 @@ orc_ctx *orc_create(const orc_config *cfg)
     c->theta = calloc(p, 8); c->h = calloc(p, 8); c->vhat = calloc(p, 8); c->agg = calloc(p, 8);
     c->theta_stale = calloc(G * p, 8); c->last = calloc(G * p, 8);
     c->grad = calloc(G * p, 8); c->grad_stale = calloc(G * p, 8);
-    c->stat = calloc(G, 8); c->ring = calloc(cfg->D, 8); c->loss_g = calloc(G, 8);
+    c->stat = calloc(G, 8); c->ring = calloc(cfg->D, 8); c->loss_g = calloc(G, 8); c->kink = calloc(G, 8);
     c->tau = calloc(G, 4); c->mask = calloc(G, 1);
     for (int g = 0; g < G; ++g) c->tau[g] = cfg->D;
     return c;
@@ -323,8 +338,9 @@ void orc_step(orc_ctx *c, const float *X, const void *y, uint8_t *mask_out, doub
             for (int64_t j = 0; j < p; ++j) { ev[j] = bf16_round(pt[j]); evs[j] = bf16_round(ps[j]); }
             pt = ev; ps = evs;
         }
-        c->loss_g[g] = orc_loss_grad_sum(cfg, pt, Xg, yg, mu, c->grad + g * p);
-        orc_loss_grad_sum(cfg, ps, Xg, yg, mu, c->grad_stale + g * p);
+        c->kink[g] = 1.0;
+        c->loss_g[g] = loss_grad_sum_k(cfg, pt, Xg, yg, mu, c->grad + g * p, c->kink + g);
+        loss_grad_sum_k(cfg, ps, Xg, yg, mu, c->grad_stale + g * p, c->kink + g);
         double s = 0;
         for (int64_t j = 0; j < p; ++j) {
             double df = c->grad[g * p + j] - c->grad_stale[g * p + j];
@@ -371,7 +387,7 @@ void orc_step(orc_ctx *c, const float *X, const void *y, uint8_t *mask_out, doub
 /* ---------- state access for the tests --------------------------------- */
 
 enum { ORC_F_THETA = 0, ORC_F_H, ORC_F_VHAT, ORC_F_AGG, ORC_F_THETA_STALE, ORC_F_LAST,
-       ORC_F_GRAD, ORC_F_GRAD_STALE, ORC_F_STAT, ORC_F_RING, ORC_F_LOSS_G };
+       ORC_F_GRAD, ORC_F_GRAD_STALE, ORC_F_STAT, ORC_F_RING, ORC_F_LOSS_G, ORC_F_KINK };
 
 double *orc_field(orc_ctx *c, int32_t id, int64_t *count)
 {
@@ -388,6 +404,7 @@ double *orc_field(orc_ctx *c, int32_t id, int64_t *count)
     case ORC_F_STAT: *count = G; return c->stat;
     case ORC_F_RING: *count = c->cfg.D; return c->ring;
     case ORC_F_LOSS_G: *count = G; return c->loss_g;
+    case ORC_F_KINK: *count = G; return c->kink;
     default: *count = 0; return NULL;
     }
 }

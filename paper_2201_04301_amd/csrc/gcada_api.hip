@@ -101,6 +101,11 @@ try {
     for (int l = 0; l < dims->n_widths; ++l)
         if (dims->widths[l] < 1)
             return fail(nullptr, GCADA_EINVAL, "every width must be >= 1");
+    if (dims->model == GCADA_MLP && dims->widths[dims->n_widths - 1] > 32)
+        return fail(nullptr, GCADA_EINVAL, "MLP output width (classes) must be <= 32");
+    if (dims->model == GCADA_MLP &&
+        (size_t)2 * dims->batch * dims->widths[dims->n_widths - 1] * sizeof(float) > 64 * 1024)
+        return fail(nullptr, GCADA_EINVAL, "MLP: batch * classes must be <= 8192");
     if (dims->batch < 1 || dims->batch > 4096)
         return fail(nullptr, GCADA_EINVAL, "dims.batch (mu) must be in [1, 4096]");
     if (!(dims->l2 >= 0.0f) || (dims->dtype == GCADA_BF16 && dims->l2 != 0.0f))
@@ -192,6 +197,16 @@ try {
     return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_set_shard");
 }
 
+// Copy the host's iteration count and the ring indices derived from it into the kernel arguments.
+static void set_iteration(gcada_ctx* ctx)
+{
+    gcada::Hyper& hy = ctx->hy;
+    hy.k = ctx->k;
+    hy.cur = (int32_t)(ctx->k % (hy.D + 1));
+    hy.nxt = (int32_t)((ctx->k + 1) % (hy.D + 1));
+    hy.kmodD = (int32_t)(ctx->k % hy.D);
+}
+
 // Fill every ring slot with theta0, zero the rest, ages = D.
 static int reset_run(gcada_ctx* ctx, const float* theta0_any)
 {
@@ -218,7 +233,7 @@ static int reset_run(gcada_ctx* ctx, const float* theta0_any)
 
 static int after_state_change(gcada_ctx* ctx)
 {
-    ctx->hy.k = ctx->k;
+    set_iteration(ctx);
     HIP_TRY(ctx, gcada::refresh_theta_sq(ctx, nullptr));
     if (ctx->dims.model == GCADA_MLP) HIP_TRY(ctx, gcada::mlp_refresh_weights(ctx, nullptr));
     HIP_TRY(ctx, hipDeviceSynchronize());
@@ -247,7 +262,7 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     for (int g = 0; g < ctx->hy.G; ++g)
         if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "step: a group has no shard");
     hipStream_t s = (hipStream_t)stream;
-    ctx->hy.k = ctx->k;
+    set_iteration(ctx);
     const bool timed = (size_t)ctx->ev_used + 2 <= ctx->ev.size();
     if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], s);
     hipError_t e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, idx, s)
@@ -259,6 +274,11 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     }
     if ((e = gcada::server_step(ctx, mask_out, loss_out, s)) != hipSuccess)
         return fail_hip(ctx, e, "server kernels");
+    if (ctx->dims.model == GCADA_MLP) {
+        // compute copies (padded, transposed, bf16) of the new iterate's hidden-layer weights
+        e = gcada::mlp_refresh_slot(ctx, (int)((ctx->k + 1) % (ctx->hy.D + 1)), s);
+        if (e != hipSuccess) return fail_hip(ctx, e, "weight copy kernel");
+    }
     ctx->k += 1;
     return GCADA_OK;
 }

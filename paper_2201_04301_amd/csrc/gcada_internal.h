@@ -33,11 +33,21 @@ struct Ctl {
 // Scalars every kernel needs, passed by value.
 struct Hyper {
     long long k;            // iteration index of this launch (the host counts the iterations)
+    int32_t cur;            // ring slot of theta^k      = k mod (D+1)
+    int32_t nxt;            // ring slot of theta^{k+1}  = (k+1) mod (D+1)
+    int32_t kmodD;          // history index of this iteration = k mod D
     int32_t G, D, mu;
     int64_t p, pstride;     // parameters; floats between ring slots
     float l2;
     double c, alpha, beta1, beta2, eps;
 };
+
+// Ring slot of group g's stale iterate theta^{k - tau_g}; 1 <= tau_g <= D < number of slots.
+__host__ __device__ inline int stale_slot_of(const Hyper& hy, int tau_g)
+{
+    const int s = hy.cur - tau_g;
+    return s < 0 ? s + hy.D + 1 : s;
+}
 
 struct MlpWork;       // MLP activations and compute copies (mlp_kernels.hip)
 struct LrTilePlan;    // single-pass logistic path (lr_tiles.hip)
@@ -106,7 +116,8 @@ hipError_t lr_tile_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
 hipError_t mlp_plan(gcada_ctx* c);
 void mlp_free(gcada_ctx* c);
 hipError_t mlp_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
-hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s);   // bf16 copies of all ring slots
+hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s);   // compute copies of all ring slots
+hipError_t mlp_refresh_slot(gcada_ctx* c, int slot, hipStream_t s);   // ... of one slot
 
 hipError_t select_plan(gcada_ctx* c);
 // selection (a2) + masked innovation sum (a3) + server update and history (a4); advances

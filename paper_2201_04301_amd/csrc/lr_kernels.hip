@@ -82,9 +82,8 @@ __global__ __launch_bounds__(kFwdWaves* kWave) void lr_forward(
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int d = (int)hy.p, mu = hy.mu;
     const long long k = hy.k;
-    const int nslot = hy.D + 1;
-    const int cur = (int)(k % nslot);
-    const int old = (int)(((k - tau[g]) % nslot + nslot) % nslot);
+    const int cur = hy.cur;
+    const int old = stale_slot_of(hy, tau[g]);
     const float* __restrict__ th = ring + (int64_t)cur * hy.pstride;
     const float* __restrict__ ts = ring + (int64_t)old * hy.pstride;
     const ShardDesc sh = shards[g];
@@ -222,9 +221,8 @@ __global__ __launch_bounds__(kBwdWaves* kWave) void lr_backward(
                 tg.x += a.x; tg.y += a.y; tg.z += a.z; tg.w += a.w;
                 tsn.x += b.x; tsn.y += b.y; tsn.z += b.z; tsn.w += b.w;
             }
-            const int nslot = hy.D + 1;
-            const int cur = (int)(k % nslot);
-            const int old = (int)(((k - tau[g]) % nslot + nslot) % nslot);
+            const int cur = hy.cur;
+            const int old = stale_slot_of(hy, tau[g]);
             const float* th = ring + (int64_t)cur * hy.pstride;
             const float* ts = ring + (int64_t)old * hy.pstride;
             const float ml = (float)mu * hy.l2;

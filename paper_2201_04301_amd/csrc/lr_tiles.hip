@@ -110,7 +110,6 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     const int g = blockIdx.x / a.RB, rb = blockIdx.x % a.RB;
     const int mu = hy.mu;
     const long long k = hy.k;
-    const int nslot = hy.D + 1;
     const ShardDesc sh = a.shards[g];
     const float* __restrict__ X = (const float*)sh.X;
 
@@ -142,8 +141,8 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     // while the tile streams in: labels, the two iterates
     float my_y = 1.0f;
     if (tid < R) my_y = ((const float*)sh.y)[my_row];
-    const float* __restrict__ th = a.ring + (int64_t)(k % nslot) * hy.pstride;
-    const int old = (int)(((k - a.tau[g]) % nslot + nslot) % nslot);
+    const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
+    const int old = stale_slot_of(hy, a.tau[g]);
     const float* __restrict__ ts = a.ring + (int64_t)old * hy.pstride;
     const float4 th4 = *(const float4*)(th + col);
     const float4 u4 = *(const float4*)(ts + col);
@@ -229,9 +228,8 @@ __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
         const float* ps = part_s + (int64_t)g * RB * hy.p + j;
         float4 t = make_float4(0, 0, 0, 0), u = t;
         if (hy.l2 != 0.0f) {
-            const int nslot = hy.D + 1;
-            t = *(const float4*)(ring + (int64_t)(hy.k % nslot) * hy.pstride + j);
-            const int old = (int)(((hy.k - tau[g]) % nslot + nslot) % nslot);
+            t = *(const float4*)(ring + (int64_t)hy.cur * hy.pstride + j);
+            const int old = stale_slot_of(hy, tau[g]);
             u = *(const float4*)(ring + (int64_t)old * hy.pstride + j);
         }
         float4 ag = make_float4(0, 0, 0, 0), as = ag;

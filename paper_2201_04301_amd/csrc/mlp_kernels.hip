@@ -1,9 +1,879 @@
-// MLP gradients at two iterates (placeholder until the MFMA kernels land).
+// MLP gradients at two iterates on the same minibatch (step a1; gradient of the sum of the
+// per-sample softmax cross-entropy losses, paper Sec. II-A), with MFMA GEMMs.
+//
+// Model: a_0 = x; a_l = ReLU(W_l a_{l-1} + b_l) for l < L; logits = W_L a_{L-1} + b_L.
+// For every group g the forward and backward passes run twice: at theta^k (shared by all
+// groups) and at theta_stale_g = ring slot (k - tau_g).  The weight gradients of the two
+// iterates are formed in the same workgroup, so that their difference (for stat_g) is taken
+// in fp32 registers and only the fresh gradient is written.
+//
+// Every GEMM is brought to the form C[M][N] = sum_k P[M][k] Q[N][k] with both operands
+// contiguous along k: activations and back-propagated signals are stored row-major AND
+// transposed by the kernel that produces them, and the weights have a padded compute copy and a
+// transposed copy per ring slot.  T is float (v_mfma_f32_32x32x2_f32) or bf16
+// (v_mfma_f32_32x32x16_bf16); accumulation is fp32 in both cases.
+#include <hip/hip_bf16.h>
+
 #include "gcada_internal.h"
 
 namespace gcada {
-hipError_t mlp_plan(gcada_ctx*) { return hipErrorNotSupported; }
-void mlp_free(gcada_ctx*) {}
-hipError_t mlp_gradients(gcada_ctx*, const int32_t*, hipStream_t) { return hipErrorNotSupported; }
-hipError_t mlp_refresh_weights(gcada_ctx*, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+constexpr int kWave = 64;
+using bf16_t = __bf16;
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// float -> T -> float with round to nearest even (identity for float)
+template <typename T> __device__ __forceinline__ float round_to(float v);
+template <> __device__ __forceinline__ float round_to<float>(float v) { return v; }
+template <> __device__ __forceinline__ float round_to<bf16_t>(float v)
+{
+    unsigned u = __float_as_uint(v);
+    if ((u & 0x7f800000u) != 0x7f800000u) {
+        u += 0x7fffu + ((u >> 16) & 1u);
+        u &= 0xffff0000u;
+    }
+    return __uint_as_float(u);
+}
+template <typename T> __device__ __forceinline__ T to_T(float v);
+template <> __device__ __forceinline__ float to_T<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t to_T<bf16_t>(float v)
+{
+    const unsigned u = __float_as_uint(round_to<bf16_t>(v)) >> 16;
+    unsigned short s = (unsigned short)u;
+    bf16_t r;
+    __builtin_memcpy(&r, &s, 2);
+    return r;
+}
+template <typename T> __device__ __forceinline__ float to_f(T v);
+template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v)
+{
+    unsigned short s;
+    __builtin_memcpy(&s, &v, 2);
+    return __uint_as_float((unsigned)s << 16);
+}
+
+__host__ __device__ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// ---------------------------------------------------------------------------------------
+// Layout of one context's MLP work space (all leading dimensions are multiples of 64 elements
+// and every pad element stays zero, so GEMM k-loops may run over the padding).
+struct Layout {
+    int L;                       // layers (widths - 1)
+    int n[GCADA_MAX_WIDTHS];     // widths n_0..n_L
+    int ld[GCADA_MAX_WIDTHS];    // round_up(n_l, 64)
+    int ldmu;                    // round_up(mu, 64)
+    int64_t woff[GCADA_MAX_WIDTHS];   // offset of W_l in theta (l = 1..L)
+    int64_t boff[GCADA_MAX_WIDTHS];   // offset of b_l in theta
+};
+
+// ---------------------------------------------------------------------------------------
+// GEMM  C[M][N] = sum_k P[M][k] Q[N][k],  128 x 128 tile, 256 threads = 2 x 2 waves of 64 x 64.
+// A row of a tile in LDS is 128 bytes of k (64 bf16 or 32 floats) plus 16 bytes of padding.
+constexpr int kBM = 128, kBN = 128;
+constexpr int kRowBytes = 128, kRowPitch = 144;
+constexpr int kTileBytes = kBM * kRowPitch;               // 18432
+constexpr int kGemmThreads = 256;
+constexpr int kGemmLds = 4 * kTileBytes;                  // P,Q x two stages = 73728
+
+enum { EPI_FWD = 0, EPI_DA = 1, EPI_DW = 2 };
+
+struct GemmArgs {
+    Hyper hy;
+    const int32_t* tau;
+    int M, N, K;                 // K in elements (the loop runs over round_up(K, k per tile))
+    // P operand: base + it*p_it + g*p_g, rows of ldp elements
+    const void* P; int64_t p_it, p_g; int ldp;
+    // Q operand: either per (it,g) like P, or a weight copy indexed by ring slot
+    const void* Q; int64_t q_it, q_g, q_slot; int ldq; int q_is_weight;
+    // FWD: bias from the fp32 ring (offset boff), outputs A [M][ldo] and AT [N][ldt]
+    // DA : relu mask read from `mask` (same layout as the output), outputs dZ and dZT
+    const float* ring; int64_t boff;
+    const void* maskp; int64_t m_it, m_g; int ldm;
+    void* O; int64_t o_it, o_g; int ldo;
+    void* OT; int64_t t_it, t_g; int ldt;
+    // DW : fresh gradient block -> grad[g*p + goff + m*N + n]; partial ||fresh-stale||^2
+    float* grad; int64_t goff;
+    double* part_stat; int n_stat; int stat_off;
+    int G;
+};
+
+template <typename T>
+__device__ __forceinline__ void mfma_step(const uint4& a, const uint4& b, f32x16& acc);
+
+template <>
+__device__ __forceinline__ void mfma_step<bf16_t>(const uint4& a, const uint4& b, f32x16& acc)
+{
+    bf16x8 av, bv;
+    __builtin_memcpy(&av, &a, 16);
+    __builtin_memcpy(&bv, &b, 16);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+}
+
+template <>
+__device__ __forceinline__ void mfma_step<float>(const uint4& a, const uint4& b, f32x16& acc)
+{
+    // four k-pairs; the k index a lane half contributes is the same for both operands
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+
+// global -> registers: 4 chunks of 16 bytes per operand per thread (one 128 x 128-byte k-tile)
+__device__ __forceinline__ void tile_gload(const char* __restrict__ Pg, const char* __restrict__ Qg,
+                                           int64_t ldp_b, int64_t ldq_b, int kt, uint4 (&rp)[4],
+                                           uint4 (&rq)[4])
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid + kGemmThreads * i, row = c >> 3, kc = c & 7;
+        rp[i] = *(const uint4*)(Pg + (int64_t)row * ldp_b + (int64_t)kt * kRowBytes + kc * 16);
+        rq[i] = *(const uint4*)(Qg + (int64_t)row * ldq_b + (int64_t)kt * kRowBytes + kc * 16);
+    }
+}
+
+__device__ __forceinline__ void tile_lstore(char* lp, char* lq, const uint4 (&rp)[4], const uint4 (&rq)[4])
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid + kGemmThreads * i, row = c >> 3, kc = c & 7;
+        *(uint4*)(lp + row * kRowPitch + kc * 16) = rp[i];
+        *(uint4*)(lq + row * kRowPitch + kc * 16) = rq[i];
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void tile_mma(const char* lp, const char* lq, f32x16 (&acc)[2][2])
+{
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int wm = wave / 2, wn = wave % 2;
+    const int half = lane >> 5, r = lane & 31;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        uint4 a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            a[i] = *(const uint4*)(lp + (wm * 64 + i * 32 + r) * kRowPitch + ks * 32 + half * 16);
+            b[i] = *(const uint4*)(lq + (wn * 64 + i * 32 + r) * kRowPitch + ks * 32 + half * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) mfma_step<T>(a[i], b[j], acc[i][j]);
+    }
+}
+
+// One pass of the k-loop for a 128x128 tile: acc[2][2] (per wave 64x64) += P_tile Q_tile^T.
+// Two LDS stages; the next k-tile travels global -> registers while the current one is multiplied.
+template <typename T>
+__device__ __forceinline__ void gemm_mainloop(const char* __restrict__ Pg, const char* __restrict__ Qg,
+                                              int64_t ldp_b, int64_t ldq_b, int K, char* lds,
+                                              f32x16 (&acc)[2][2])
+{
+    constexpr int kElemsPerTileK = kRowBytes / (int)sizeof(T);
+    const int nk = (K + kElemsPerTileK - 1) / kElemsPerTileK;
+    uint4 rp[4], rq[4];
+    tile_gload(Pg, Qg, ldp_b, ldq_b, 0, rp, rq);
+    tile_lstore(lds, lds + kTileBytes, rp, rq);
+    __syncthreads();
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        char* cur = lds + (kt & 1) * 2 * kTileBytes;
+        char* nxt = lds + ((kt + 1) & 1) * 2 * kTileBytes;
+        tile_gload(Pg, Qg, ldp_b, ldq_b, kt + 1, rp, rq);
+        tile_mma<T>(cur, cur + kTileBytes, acc);
+        tile_lstore(nxt, nxt + kTileBytes, rp, rq);
+        __syncthreads();
+    }
+    {
+        const char* cur = lds + ((nk - 1) & 1) * 2 * kTileBytes;
+        tile_mma<T>(cur, cur + kTileBytes, acc);
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ int stale_slot(const Hyper& hy, const int32_t* tau, int g)
+{
+    return stale_slot_of(hy, tau[g]);
+}
+
+// grid: (ceil(N/128), ceil(M/128), batch);  batch = 2G (it*G + g) for FWD / DA, G for DW.
+template <typename T, int EPI>
+__global__ __launch_bounds__(kGemmThreads) void mlp_gemm(GemmArgs a)
+{
+    extern __shared__ __align__(16) char lds[];
+    const Hyper& hy = a.hy;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int wm = wave / 2, wn = wave % 2;
+    const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
+    constexpr int esz = (int)sizeof(T);
+
+    f32x16 acc[2][2];
+    f32x16 acc_s[2][2];     // DW: stale-iterate accumulators
+    const int n_it = EPI == EPI_DW ? 2 : 1;
+    int g, it0;
+    if (EPI == EPI_DW) { g = blockIdx.z; it0 = 1; } else { g = blockIdx.z % a.G; it0 = blockIdx.z / a.G; }
+
+    for (int pass = 0; pass < n_it; ++pass) {
+        const int it = EPI == EPI_DW ? 1 - pass : it0;      // DW: stale first, then fresh
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+        const char* Pg = (const char*)a.P + ((int64_t)it * a.p_it + (int64_t)g * a.p_g + (int64_t)m0 * a.ldp) * esz;
+        const char* Qg;
+        if (a.q_is_weight) {
+            const int slot = it == 0 ? hy.cur : stale_slot(hy, a.tau, g);
+            Qg = (const char*)a.Q + ((int64_t)slot * a.q_slot + (int64_t)n0 * a.ldq) * esz;
+        } else {
+            Qg = (const char*)a.Q + ((int64_t)it * a.q_it + (int64_t)g * a.q_g + (int64_t)n0 * a.ldq) * esz;
+        }
+        gemm_mainloop<T>(Pg, Qg, (int64_t)a.ldp * esz, (int64_t)a.ldq * esz, a.K, lds, acc);
+        if (EPI == EPI_DW && pass == 0) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc_s[i][j] = acc[i][j];
+        }
+    }
+
+    // accumulator element e of lane: column n = lane % 32, row m = (e/4)*8 + (lane/32)*4 + e%4
+    const int cl = lane & 31, rh = (lane >> 5) * 4;
+    if constexpr (EPI == EPI_DW) {
+        double sq = 0;
+        float* gb = a.grad + (int64_t)g * hy.p + a.goff;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + rh + (e & 3);
+                    const int n = n0 + wn * 64 + j * 32 + cl;
+                    if (m < a.M && n < a.N) {
+                        const float f = acc[i][j][e];
+                        const float df = f - acc_s[i][j][e];
+                        sq += (double)df * (double)df;
+                        gb[(int64_t)m * a.N + n] = f;
+                    }
+                }
+        sq = wave_sum(sq);
+        double* red = (double*)lds;
+        __syncthreads();
+        if (lane == 0) red[wave] = sq;
+        __syncthreads();
+        if (tid == 0)
+            a.part_stat[(int64_t)g * a.n_stat + a.stat_off + blockIdx.y * gridDim.x + blockIdx.x] =
+                red[0] + red[1] + red[2] + red[3];
+    } else {
+        // stage the tile in LDS as T [128][128 + 8], then write it row-major and transposed
+        constexpr int pitch = kBN + 8;
+        T* st = (T*)lds;
+        const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
+        const float* bias = EPI == EPI_FWD ? a.ring + (int64_t)slot * hy.pstride + a.boff : nullptr;
+        const T* mk = EPI == EPI_DA
+            ? (const T*)a.maskp + (int64_t)it0 * a.m_it + (int64_t)g * a.m_g : nullptr;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int nl = wn * 64 + j * 32 + cl, n = n0 + nl;
+                float bv = 0.0f;
+                if (EPI == EPI_FWD && n < a.N) bv = round_to<T>(bias[n]);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int ml = wm * 64 + i * 32 + (e >> 2) * 8 + rh + (e & 3), m = m0 + ml;
+                    float v = acc[i][j][e];
+                    if (EPI == EPI_FWD) v = fmaxf(v + bv, 0.0f);
+                    if (EPI == EPI_DA) {
+                        const bool on = (m < a.M && n < a.N) && to_f<T>(mk[(int64_t)m * a.ldm + n]) > 0.0f;
+                        v = on ? v : 0.0f;
+                    }
+                    st[ml * pitch + nl] = to_T<T>(v);
+                }
+            }
+        __syncthreads();
+        T* O = (T*)a.O + (int64_t)it0 * a.o_it + (int64_t)g * a.o_g;
+        T* OT = (T*)a.OT + (int64_t)it0 * a.t_it + (int64_t)g * a.t_g;
+        constexpr int V = 16 / esz;                 // elements per 16-byte vector
+        // row-major: 128 rows x (128 / V) vectors
+        for (int c = tid; c < kBM * (kBN / V); c += kGemmThreads) {
+            const int ml = c / (kBN / V), nv = (c % (kBN / V)) * V;
+            const int m = m0 + ml, n = n0 + nv;
+            if (m < a.M && n < a.N) {
+                // ldo is a multiple of 64 and pads stay zero: mask the lanes beyond N
+                alignas(16) T tmp[V];
+#pragma unroll
+                for (int q = 0; q < V; ++q) tmp[q] = (n + q < a.N) ? st[ml * pitch + nv + q] : to_T<T>(0.0f);
+                *(uint4*)(O + (int64_t)m * a.ldo + n) = *(const uint4*)tmp;
+            }
+        }
+        // transposed: 128 columns x (128 / V) vectors along m
+        for (int c = tid; c < kBN * (kBM / V); c += kGemmThreads) {
+            const int nl = c / (kBM / V), mv = (c % (kBM / V)) * V;
+            const int n = n0 + nl, m = m0 + mv;
+            if (n < a.N && m < a.M) {
+                alignas(16) T tmp[V];
+#pragma unroll
+                for (int q = 0; q < V; ++q) tmp[q] = (m + q < a.M) ? st[(mv + q) * pitch + nl] : to_T<T>(0.0f);
+                *(uint4*)(OT + (int64_t)n * a.ldt + m) = *(const uint4*)tmp;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Gather the minibatch rows of every group: Xg [G][mu][ld0] and its transpose XgT [G][n0][ldmu].
+// grid: (ceil(n0/64), ceil(mu/64), G), block 256.
+template <typename T>
+__global__ __launch_bounds__(256) void mlp_gather(Hyper hy, const ShardDesc* __restrict__ shards,
+                                                  const int32_t* __restrict__ idx, int n0, int ld0,
+                                                  int ldmu, T* __restrict__ Xg, T* __restrict__ XgT)
+{
+    __shared__ T tile[64][64 + 2];
+    const int g = blockIdx.z, c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+    const ShardDesc sh = shards[g];
+    const T* X = (const T*)sh.X;
+    const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+    for (int r = ty; r < 64; r += 4) {
+        const int i = r0 + r;
+        T v = to_T<T>(0.0f);
+        if (i < hy.mu && c0 + tx < n0) {
+            int64_t row;
+            if (idx) row = idx[(int64_t)g * hy.mu + i];
+            else row = (int64_t)(((unsigned long long)hy.k * (unsigned long long)hy.mu +
+                                  (unsigned long long)i) % (unsigned long long)sh.rows);
+            v = X[row * sh.ld + c0 + tx];
+            Xg[((int64_t)g * hy.mu + i) * ld0 + c0 + tx] = v;
+        }
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    for (int c = ty; c < 64; c += 4) {
+        const int n = c0 + c, i = r0 + tx;
+        if (n < n0 && i < hy.mu) XgT[((int64_t)g * n0 + n) * ldmu + i] = tile[tx][c];
+    }
+}
+
+// Compute copies of the hidden-layer weights of one ring slot: Wc [n_l][ld_{l-1}] and the
+// transpose WcT [n_{l-1}][ld_l], both in T.  grid: (ceil(n_in/64), ceil(n_out/64)), block 256.
+template <typename T>
+__global__ __launch_bounds__(256) void mlp_weight_copy(const float* __restrict__ W, int n_out, int n_in,
+                                                       int ld_in, int ld_out, T* __restrict__ Wc,
+                                                       T* __restrict__ WcT)
+{
+    __shared__ T tile[64][64 + 2];
+    const int i0 = blockIdx.x * 64, o0 = blockIdx.y * 64;
+    const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
+    for (int r = ty; r < 64; r += 4) {
+        const int o = o0 + r, i = i0 + tx;
+        T v = to_T<T>(0.0f);
+        if (o < n_out && i < n_in) {
+            v = to_T<T>(W[(int64_t)o * n_in + i]);
+            Wc[(int64_t)o * ld_in + i] = v;
+        }
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    for (int c = ty; c < 64; c += 4) {
+        const int i = i0 + c, o = o0 + tx;
+        if (i < n_in && o < n_out) WcT[(int64_t)i * ld_out + o] = tile[tx][c];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Output layer.  One block handles 32 samples of one (iterate, group):
+//   logits = W_L a_{L-1} + b_L,  softmax cross-entropy, dZ_L = softmax - onehot   (fp32)
+//   dZ_{L-1} = (W_L^T dZ_L) * [a_{L-1} > 0]  -> stored row-major and transposed in T
+// The last layer's weights come from the fp32 ring, rounded to T, staged in LDS when they fit.
+constexpr int kHeadRows = 32;
+constexpr int kMaxClasses = 32;
+constexpr int kHeadWLds = 48 * 1024;     // bytes of LDS the staged W_L may take
+
+struct HeadArgs {
+    Hyper hy;
+    const int32_t* tau;
+    const ShardDesc* shards;
+    const int32_t* idx;
+    const float* ring;
+    int64_t woff, boff;
+    int nc, nh, ldh, ldmu, G, has_hidden, w_in_lds;
+    const void* Aprev; int64_t a_it, a_g;
+    float* dZL;                 // [2][G][mu][nc]
+    void* dZ; void* dZT; int64_t z_it, z_g, zt_it, zt_g;
+    double* part_loss;
+};
+
+// grid: (ceil(mu/32), 2G), block 256; NC = class count rounded up to a power of two
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void mlp_head(HeadArgs a)
+{
+    __shared__ float s_logit[kHeadRows][NC];
+    __shared__ float s_dz[kHeadRows][NC];
+    __shared__ double s_loss[4];
+    extern __shared__ float s_w[];              // [nc][nh] when w_in_lds
+    const Hyper& hy = a.hy;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int g = blockIdx.y % a.G, it = blockIdx.y / a.G;
+    const int r0 = blockIdx.x * kHeadRows;
+    const int nc = a.nc, nh = a.nh, ldh = a.ldh;
+    const int slot = it == 0 ? hy.cur : stale_slot(hy, a.tau, g);
+    const float* __restrict__ Wg = a.ring + (int64_t)slot * hy.pstride + a.woff;     // [nc][nh]
+    const float* __restrict__ b = a.ring + (int64_t)slot * hy.pstride + a.boff;
+    const T* __restrict__ A = (const T*)a.Aprev + (int64_t)it * a.a_it + (int64_t)g * a.a_g;
+    const ShardDesc sh = a.shards[g];
+
+    if (a.w_in_lds) {
+        for (int e = tid; e < nc * nh; e += 256) s_w[e] = round_to<T>(Wg[e]);
+        __syncthreads();
+    }
+    // logits: wave w takes rows w, w+4, ...; lanes stride over the hidden units
+    for (int r = wave; r < kHeadRows; r += 4) {
+        const int i = r0 + r;
+        float accv[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) accv[c] = 0.0f;
+        if (i < hy.mu) {
+            for (int n = lane; n < nh; n += kWave) {
+                const float av = to_f<T>(A[(int64_t)i * ldh + n]);
+#pragma unroll
+                for (int c = 0; c < NC; ++c)
+                    if (c < nc)
+                        accv[c] += av * (a.w_in_lds ? s_w[c * nh + n] : round_to<T>(Wg[(int64_t)c * nh + n]));
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if (c < nc) {
+                const float t = wave_sum(accv[c]);
+                if (lane == 0) s_logit[r][c] = t + round_to<T>(b[c]);
+            }
+        }
+    }
+    __syncthreads();
+    // softmax / loss / dZ_L: one thread per row
+    double lsum = 0;
+    if (tid < kHeadRows) {
+        const int i = r0 + tid;
+        if (i < hy.mu) {
+            int64_t row;
+            if (a.idx) row = a.idx[(int64_t)g * hy.mu + i];
+            else row = (int64_t)(((unsigned long long)hy.k * (unsigned long long)hy.mu +
+                                  (unsigned long long)i) % (unsigned long long)sh.rows);
+            const int y = ((const int32_t*)sh.y)[row];
+            // Everything relative to the true class, so that a confidently right sample
+            // (p_y -> 1) loses no digits: t_c = z_c - z_y, m = max_c t_c >= 0,
+            // S = sum_c exp(t_c - m); loss = m + log S; p_c = exp(t_c - m) / S;
+            // dZ_c = p_c (c != y), dZ_y = -sum_{c != y} p_c.
+            const float zy = s_logit[tid][y];
+            float m = 0.0f;
+            for (int c = 0; c < nc; ++c) m = fmaxf(m, s_logit[tid][c] - zy);
+            float so = 0.0f;                                  // the classes other than y
+            for (int c = 0; c < nc; ++c)
+                if (c != y) so += expf(s_logit[tid][c] - zy - m);
+            const float ey = expf(-m);
+            const float inv = 1.0f / (ey + so);
+            float* dzl = a.dZL + (((int64_t)it * a.G + g) * hy.mu + i) * nc;
+            float others = 0.0f;
+            for (int c = 0; c < nc; ++c) {
+                if (c == y) continue;
+                const float dv = expf(s_logit[tid][c] - zy - m) * inv;
+                others += dv;
+                s_dz[tid][c] = dv;
+                dzl[c] = dv;
+            }
+            s_dz[tid][y] = -others;
+            dzl[y] = -others;
+            lsum = m == 0.0f ? (double)log1pf(so) : (double)(m + logf(ey + so));
+            for (int c = nc; c < NC; ++c) s_dz[tid][c] = 0.0f;     // padding classes contribute nothing
+        } else {
+            for (int c = 0; c < NC; ++c) s_dz[tid][c] = 0.0f;
+        }
+    }
+    if (wave == 0) {
+        lsum = wave_sum(lsum);
+        if (lane == 0) s_loss[0] = lsum;
+    }
+    __syncthreads();
+    if (it == 0 && tid == 0) a.part_loss[(int64_t)g * gridDim.x + blockIdx.x] = s_loss[0];
+    if (!a.has_hidden) return;
+    // back-propagated signal of the last hidden layer for these 32 rows
+    T* __restrict__ Z = (T*)a.dZ + (int64_t)it * a.z_it + (int64_t)g * a.z_g;        // [mu][ldh]
+    T* __restrict__ ZT = (T*)a.dZT + (int64_t)it * a.zt_it + (int64_t)g * a.zt_g;    // [nh][ldmu]
+    for (int n = tid; n < nh; n += 256) {
+        float w[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            w[c] = c < nc ? (a.w_in_lds ? s_w[c * nh + n] : round_to<T>(Wg[(int64_t)c * nh + n])) : 0.0f;
+        // V consecutive samples of column n at a time: one 16-byte store into the transposed copy
+        // (r0 is a multiple of 32; ldmu a multiple of 64)
+        constexpr int V = 16 / (int)sizeof(T);
+#pragma unroll 1
+        for (int q = 0; q < kHeadRows / V; ++q) {
+            alignas(16) T col[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const int r = q * V + e, i = r0 + r;
+                float v = 0.0f;
+                if (i < hy.mu) {
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) v += s_dz[r][c] * w[c];
+                    if (!(to_f<T>(A[(int64_t)i * ldh + n]) > 0.0f)) v = 0.0f;
+                    Z[(int64_t)i * ldh + n] = to_T<T>(v);
+                }
+                col[e] = to_T<T>(v);
+            }
+            *(uint4*)(ZT + (int64_t)n * a.ldmu + r0 + q * V) = *(const uint4*)col;
+        }
+    }
+}
+
+// Gradient of the output layer: dW_L[c][n] = sum_i dZ_L[i][c] a_{L-1}[i][n], db_L[c] = sum_i dZ_L[i][c],
+// for both iterates; fresh values -> grad, squared differences -> one partial per block.
+// grid: (ceil(nh/256), G), block 256: thread = hidden unit n.
+template <typename T>
+__global__ __launch_bounds__(256) void mlp_head_grad(Hyper hy, int nc, int nh, int ldh,
+                                                     const T* __restrict__ Aprev, int64_t a_it, int64_t a_g,
+                                                     const float* __restrict__ dZL, float* __restrict__ grad,
+                                                     int64_t woff, int64_t boff, double* __restrict__ part_stat,
+                                                     int n_stat, int stat_off, int G)
+{
+    extern __shared__ float s_dzl[];            // [2][mu][nc]
+    __shared__ double s_red[4];
+    const int g = blockIdx.y, tid = threadIdx.x, n = blockIdx.x * 256 + tid;
+    const int mu = hy.mu;
+    for (int it = 0; it < 2; ++it)
+        for (int e = tid; e < mu * nc; e += 256)
+            s_dzl[(it * mu) * nc + e] = dZL[(((int64_t)it * G + g) * mu) * nc + e];
+    __syncthreads();
+    double sq = 0;
+    if (n < nh) {
+        float acc[2][kMaxClasses];
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c) acc[0][c] = acc[1][c] = 0.0f;
+        for (int it = 0; it < 2; ++it) {
+            const T* A = Aprev + (int64_t)it * a_it + (int64_t)g * a_g;
+            for (int i = 0; i < mu; ++i) {
+                const float av = to_f<T>(A[(int64_t)i * ldh + n]);
+#pragma unroll
+                for (int c = 0; c < kMaxClasses; ++c)
+                    if (c < nc) acc[it][c] += s_dzl[(it * mu + i) * nc + c] * av;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < kMaxClasses; ++c)
+            if (c < nc) {
+                grad[(int64_t)g * hy.p + woff + (int64_t)c * nh + n] = acc[0][c];
+                const float df = acc[0][c] - acc[1][c];
+                sq += (double)df * (double)df;
+            }
+    }
+    // bias gradient: block 0, one thread per class
+    if (blockIdx.x == 0 && tid < nc) {
+        float s0 = 0, s1 = 0;
+        for (int i = 0; i < mu; ++i) {
+            s0 += s_dzl[i * nc + tid];
+            s1 += s_dzl[(mu + i) * nc + tid];
+        }
+        grad[(int64_t)g * hy.p + boff + tid] = s0;
+        const float df = s0 - s1;
+        sq += (double)df * (double)df;
+    }
+    sq = wave_sum(sq);
+    if (tid % kWave == 0) s_red[tid / kWave] = sq;
+    __syncthreads();
+    if (tid == 0)
+        part_stat[(int64_t)g * n_stat + stat_off + blockIdx.x] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+}
+
+// Bias gradient of a hidden layer from the transposed signal dZT [n][ldmu]: db[n] = sum_i dZ[i][n].
+// grid: (ceil(n/4), G), block 256: one wave per hidden unit, both iterates.
+template <typename T>
+__global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu, const T* __restrict__ dZT,
+                                                     int64_t zt_it, int64_t zt_g, float* __restrict__ grad,
+                                                     int64_t boff, double* __restrict__ part_stat, int n_stat,
+                                                     int stat_off)
+{
+    __shared__ double s_red[4];
+    const int g = blockIdx.y, wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int n = blockIdx.x * 4 + wave;
+    double sq = 0;
+    if (n < nl) {
+        float s[2] = {0.0f, 0.0f};
+        for (int it = 0; it < 2; ++it) {
+            const T* z = dZT + (int64_t)it * zt_it + (int64_t)g * zt_g + (int64_t)n * ldmu;
+            for (int i = lane; i < hy.mu; i += kWave) s[it] += to_f<T>(z[i]);
+            s[it] = wave_sum(s[it]);
+        }
+        if (lane == 0) {
+            grad[(int64_t)g * hy.p + boff + n] = s[0];
+            const float df = s[0] - s[1];
+            sq = (double)df * (double)df;
+        }
+    }
+    if (lane == 0) s_red[wave] = sq;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        part_stat[(int64_t)g * n_stat + stat_off + blockIdx.x] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------
+struct MlpWork {
+    Layout lay{};
+    bool bf16 = false;
+    int esz = 4;
+    // per layer l (index l): activations A_l, AT_l (l = 1..L-1), signals dZ_l, dZT_l (l = 1..L-1)
+    void* Xg = nullptr; void* XgT = nullptr;
+    void* A[GCADA_MAX_WIDTHS] = {};  void* AT[GCADA_MAX_WIDTHS] = {};
+    void* dZ[GCADA_MAX_WIDTHS] = {}; void* dZT[GCADA_MAX_WIDTHS] = {};
+    float* dZL = nullptr;
+    // weight copies per ring slot: Wc_l [slot][n_l][ld_{l-1}], WcT_l [slot][n_{l-1}][ld_l]
+    void* Wc[GCADA_MAX_WIDTHS] = {}; void* WcT[GCADA_MAX_WIDTHS] = {};
+    int64_t wc_slot[GCADA_MAX_WIDTHS] = {}, wct_slot[GCADA_MAX_WIDTHS] = {};
+    // partial-statistic slots
+    int stat_off_w[GCADA_MAX_WIDTHS] = {}, stat_off_b[GCADA_MAX_WIDTHS] = {};
+    int n_stat = 0, n_loss = 0;
+    size_t slack = 0;
+    std::vector<void*> allocs;
+};
+
+static hipError_t walloc(MlpWork* w, void** p, size_t bytes)
+{
+    // slack: GEMM tiles read up to 127 rows past the end of the last batch entry
+    bytes += w->slack;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) return e;
+    w->allocs.push_back(*p);
+    return hipMemset(*p, 0, bytes);
+}
+
+hipError_t mlp_plan(gcada_ctx* c)
+{
+    auto* w = new MlpWork();
+    c->mlp = w;
+    const gcada_dims& d = c->dims;
+    Layout& lay = w->lay;
+    lay.L = d.n_widths - 1;
+    w->bf16 = d.dtype == GCADA_BF16;
+    w->esz = w->bf16 ? 2 : 4;
+    int64_t off = 0;
+    for (int l = 0; l <= lay.L; ++l) {
+        lay.n[l] = d.widths[l];
+        lay.ld[l] = round_up(d.widths[l], 64);
+        if (l >= 1) {
+            lay.woff[l] = off;
+            off += (int64_t)lay.n[l] * lay.n[l - 1];
+            lay.boff[l] = off;
+            off += lay.n[l];
+        }
+    }
+    if (lay.n[lay.L] > kMaxClasses) return hipErrorInvalidValue;
+    const int mu = c->hy.mu, G = c->hy.G, L = lay.L, nslot = c->hy.D + 1;
+    lay.ldmu = round_up(mu, 64);
+    int maxld = lay.ldmu;
+    for (int l = 0; l <= L; ++l) maxld = std::max(maxld, lay.ld[l]);
+    w->slack = (size_t)128 * maxld * 4 + 256;
+    if ((size_t)2 * mu * lay.n[L] * sizeof(float) > 64 * 1024) return hipErrorInvalidValue;
+    const size_t es = w->esz;
+    hipError_t e;
+    if ((e = walloc(w, &w->Xg, (size_t)G * mu * lay.ld[0] * es)) != hipSuccess) return e;
+    if ((e = walloc(w, &w->XgT, (size_t)G * lay.n[0] * lay.ldmu * es)) != hipSuccess) return e;
+    for (int l = 1; l < L; ++l) {
+        const size_t rm = (size_t)2 * G * mu * lay.ld[l] * es, tr = (size_t)2 * G * lay.n[l] * lay.ldmu * es;
+        if ((e = walloc(w, &w->A[l], rm)) != hipSuccess) return e;
+        if ((e = walloc(w, &w->AT[l], tr)) != hipSuccess) return e;
+        if ((e = walloc(w, &w->dZ[l], rm)) != hipSuccess) return e;
+        if ((e = walloc(w, &w->dZT[l], tr)) != hipSuccess) return e;
+        w->wc_slot[l] = (int64_t)lay.n[l] * lay.ld[l - 1];
+        w->wct_slot[l] = (int64_t)lay.n[l - 1] * lay.ld[l];
+        if ((e = walloc(w, &w->Wc[l], (size_t)nslot * w->wc_slot[l] * es)) != hipSuccess) return e;
+        if ((e = walloc(w, &w->WcT[l], (size_t)nslot * w->wct_slot[l] * es)) != hipSuccess) return e;
+    }
+    if ((e = walloc(w, (void**)&w->dZL, (size_t)2 * G * mu * lay.n[L] * 4)) != hipSuccess) return e;
+    // partial statistics: per layer the weight-gradient tiles (or head blocks) and bias blocks
+    int ns = 0;
+    for (int l = 1; l <= L; ++l) {
+        w->stat_off_w[l] = ns;
+        if (l < L) ns += ((lay.n[l] + kBM - 1) / kBM) * ((lay.n[l - 1] + kBN - 1) / kBN);
+        else ns += (lay.n[l - 1] + 255) / 256;
+        w->stat_off_b[l] = ns;
+        if (l < L) ns += (lay.n[l] + 3) / 4;
+    }
+    w->n_stat = ns;
+    w->n_loss = (mu + kHeadRows - 1) / kHeadRows;
+    c->n_stat_part = std::max(c->n_stat_part, ns);
+    c->n_loss_part = std::max(c->n_loss_part, w->n_loss);
+    return hipSuccess;
+}
+
+void mlp_free(gcada_ctx* c)
+{
+    if (!c->mlp) return;
+    for (void* p : c->mlp->allocs) (void)hipFree(p);
+    delete c->mlp;
+    c->mlp = nullptr;
+}
+
+template <typename T>
+static hipError_t refresh_slot_t(gcada_ctx* c, int slot, hipStream_t s)
+{
+    MlpWork* w = c->mlp;
+    const Layout& lay = w->lay;
+    const float* th = c->ring + (int64_t)slot * c->hy.pstride;
+    for (int l = 1; l < lay.L; ++l) {
+        dim3 grid((lay.n[l - 1] + 63) / 64, (lay.n[l] + 63) / 64);
+        mlp_weight_copy<T><<<grid, 256, 0, s>>>(th + lay.woff[l], lay.n[l], lay.n[l - 1], lay.ld[l - 1],
+                                                 lay.ld[l], (T*)w->Wc[l] + (int64_t)slot * w->wc_slot[l],
+                                                 (T*)w->WcT[l] + (int64_t)slot * w->wct_slot[l]);
+    }
+    return hipGetLastError();
+}
+
+hipError_t mlp_refresh_slot(gcada_ctx* c, int slot, hipStream_t s)
+{
+    return c->mlp->bf16 ? refresh_slot_t<bf16_t>(c, slot, s) : refresh_slot_t<float>(c, slot, s);
+}
+
+hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s)
+{
+    for (int slot = 0; slot <= c->hy.D; ++slot) {
+        hipError_t e = mlp_refresh_slot(c, slot, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+template <typename T>
+static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t s)
+{
+    MlpWork* w = c->mlp;
+    const Layout& lay = w->lay;
+    const Hyper& hy = c->hy;
+    const int G = hy.G, mu = hy.mu, L = lay.L;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_FWD>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_DA>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_DW>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        attr_set = true;
+    }
+    // 1. gather the minibatch rows (row-major and transposed)
+    {
+        dim3 grid((lay.n[0] + 63) / 64, (mu + 63) / 64, G);
+        mlp_gather<T><<<grid, 256, 0, s>>>(hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
+                                            (T*)w->Xg, (T*)w->XgT);
+    }
+    auto rm_it = [&](int l) { return (int64_t)G * mu * lay.ld[l]; };       // iterate stride, row-major
+    auto rm_g = [&](int l) { return (int64_t)mu * lay.ld[l]; };
+    auto tr_it = [&](int l) { return (int64_t)G * lay.n[l] * lay.ldmu; };  // transposed
+    auto tr_g = [&](int l) { return (int64_t)lay.n[l] * lay.ldmu; };
+    // 2. hidden layers, forward
+    for (int l = 1; l < L; ++l) {
+        GemmArgs a{};
+        a.hy = hy; a.tau = c->tau; a.G = G;
+        a.M = mu; a.N = lay.n[l]; a.K = lay.n[l - 1];
+        if (l == 1) { a.P = w->Xg; a.p_it = 0; a.p_g = rm_g(0); a.ldp = lay.ld[0]; }
+        else { a.P = w->A[l - 1]; a.p_it = rm_it(l - 1); a.p_g = rm_g(l - 1); a.ldp = lay.ld[l - 1]; }
+        a.Q = w->Wc[l]; a.q_is_weight = 1; a.q_slot = w->wc_slot[l]; a.ldq = lay.ld[l - 1];
+        a.ring = c->ring; a.boff = lay.boff[l];
+        a.O = w->A[l]; a.o_it = rm_it(l); a.o_g = rm_g(l); a.ldo = lay.ld[l];
+        a.OT = w->AT[l]; a.t_it = tr_it(l); a.t_g = tr_g(l); a.ldt = lay.ldmu;
+        dim3 grid((a.N + kBN - 1) / kBN, (a.M + kBM - 1) / kBM, 2 * G);
+        mlp_gemm<T, EPI_FWD><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+    }
+    // 3. output layer: loss, dZ_L, and the signal of the last hidden layer
+    {
+        const int nh = lay.n[L - 1], ldh = lay.ld[L - 1];
+        const T* Ap = L == 1 ? (const T*)w->Xg : (const T*)w->A[L - 1];
+        const int64_t a_it = L == 1 ? 0 : rm_it(L - 1), a_g = rm_g(L - 1);
+        HeadArgs h{};
+        h.hy = hy; h.tau = c->tau; h.shards = c->d_shards; h.idx = idx; h.ring = c->ring;
+        h.woff = lay.woff[L]; h.boff = lay.boff[L];
+        h.nc = lay.n[L]; h.nh = nh; h.ldh = ldh; h.ldmu = lay.ldmu; h.G = G; h.has_hidden = L > 1 ? 1 : 0;
+        h.Aprev = Ap; h.a_it = a_it; h.a_g = a_g; h.dZL = w->dZL;
+        h.dZ = w->dZ[L - 1]; h.dZT = w->dZT[L - 1];
+        if (L > 1) { h.z_it = rm_it(L - 1); h.z_g = rm_g(L - 1); h.zt_it = tr_it(L - 1); h.zt_g = tr_g(L - 1); }
+        h.part_loss = c->part_loss;
+        const size_t wbytes = (size_t)lay.n[L] * nh * sizeof(float);
+        h.w_in_lds = wbytes <= (size_t)kHeadWLds ? 1 : 0;
+        const size_t hl = h.w_in_lds ? wbytes : 0;
+        dim3 grid(w->n_loss, 2 * G);
+        const int ncl = lay.n[L];
+        if (ncl <= 2) mlp_head<T, 2><<<grid, 256, hl, s>>>(h);
+        else if (ncl <= 4) mlp_head<T, 4><<<grid, 256, hl, s>>>(h);
+        else if (ncl <= 8) mlp_head<T, 8><<<grid, 256, hl, s>>>(h);
+        else if (ncl <= 16) mlp_head<T, 16><<<grid, 256, hl, s>>>(h);
+        else mlp_head<T, 32><<<grid, 256, hl, s>>>(h);
+        dim3 gg((nh + 255) / 256, G);
+        const size_t lds = (size_t)2 * mu * lay.n[L] * sizeof(float);
+        mlp_head_grad<T><<<gg, 256, lds, s>>>(hy, lay.n[L], nh, ldh, Ap, a_it, a_g, w->dZL, c->grad,
+                                               lay.woff[L], lay.boff[L], c->part_stat, w->n_stat,
+                                               w->stat_off_w[L], G);
+    }
+    // 4. hidden layers, backward
+    for (int l = L - 1; l >= 1; --l) {
+        {   // weight gradient of layer l, both iterates in one workgroup
+            GemmArgs a{};
+            a.hy = hy; a.tau = c->tau; a.G = G;
+            a.M = lay.n[l]; a.N = lay.n[l - 1]; a.K = mu;
+            a.P = w->dZT[l]; a.p_it = tr_it(l); a.p_g = tr_g(l); a.ldp = lay.ldmu;
+            if (l == 1) { a.Q = w->XgT; a.q_it = 0; a.q_g = tr_g(0); }
+            else { a.Q = w->AT[l - 1]; a.q_it = tr_it(l - 1); a.q_g = tr_g(l - 1); }
+            a.ldq = lay.ldmu; a.q_is_weight = 0;
+            a.grad = c->grad; a.goff = lay.woff[l];
+            a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[l];
+            dim3 grid((a.N + kBN - 1) / kBN, (a.M + kBM - 1) / kBM, G);
+            mlp_gemm<T, EPI_DW><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+        }
+        {
+            dim3 grid((lay.n[l] + 3) / 4, G);
+            mlp_bias_grad<T><<<grid, 256, 0, s>>>(hy, lay.n[l], lay.ldmu, (const T*)w->dZT[l], tr_it(l),
+                                                   tr_g(l), c->grad, lay.boff[l], c->part_stat, w->n_stat,
+                                                   w->stat_off_b[l]);
+        }
+        if (l > 1) {   // signal of layer l-1: dZ_{l-1} = (dZ_l W_l) * [a_{l-1} > 0]
+            GemmArgs a{};
+            a.hy = hy; a.tau = c->tau; a.G = G;
+            a.M = mu; a.N = lay.n[l - 1]; a.K = lay.n[l];
+            a.P = w->dZ[l]; a.p_it = rm_it(l); a.p_g = rm_g(l); a.ldp = lay.ld[l];
+            a.Q = w->WcT[l]; a.q_is_weight = 1; a.q_slot = w->wct_slot[l]; a.ldq = lay.ld[l];
+            a.maskp = w->A[l - 1]; a.m_it = rm_it(l - 1); a.m_g = rm_g(l - 1); a.ldm = lay.ld[l - 1];
+            a.O = w->dZ[l - 1]; a.o_it = rm_it(l - 1); a.o_g = rm_g(l - 1); a.ldo = lay.ld[l - 1];
+            a.OT = w->dZT[l - 1]; a.t_it = tr_it(l - 1); a.t_g = tr_g(l - 1); a.ldt = lay.ldmu;
+            dim3 grid((a.N + kBN - 1) / kBN, (a.M + kBM - 1) / kBM, 2 * G);
+            mlp_gemm<T, EPI_DA><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+        }
+    }
+    c->n_stat_used = w->n_stat;
+    c->n_loss_used = G * w->n_loss;
+    return hipGetLastError();
+}
+
+hipError_t mlp_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
+{
+    return c->mlp->bf16 ? mlp_gradients_t<bf16_t>(c, idx, s) : mlp_gradients_t<float>(c, idx, s);
+}
+
 }  // namespace gcada

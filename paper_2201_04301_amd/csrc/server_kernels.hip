@@ -170,10 +170,8 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
     Ctl* ctl = a.ctl;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     constexpr int NW = B / kWave;
-    const long long k = hy.k;
-    const int nslot = hy.D + 1;
-    const float* __restrict__ th = a.ring + (int64_t)(k % nslot) * hy.pstride;
-    float* __restrict__ tn = a.ring + (int64_t)((k + 1) % nslot) * hy.pstride;
+    const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
+    float* __restrict__ tn = a.ring + (int64_t)hy.nxt * hy.pstride;
 
     const int64_t j0 = ((int64_t)blockIdx.x * B + threadIdx.x) * VW;
     const bool active = j0 < hy.p;
@@ -331,7 +329,7 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
         }
     }
     if (threadIdx.x == 0) {
-        a.nring[k % hy.D] = xs;
+        a.nring[hy.kmodD] = xs;
         ctl->theta_sq = ys;
     }
     // every block has used the old ages by now
@@ -346,7 +344,7 @@ __global__ __launch_bounds__(256) void theta_sq_kernel(Hyper hy, const float* __
                                                         Ctl* __restrict__ ctl)
 {
     __shared__ double s_tmp[256 / kWave];
-    const float* th = ring + (int64_t)(hy.k % (hy.D + 1)) * hy.pstride;
+    const float* th = ring + (int64_t)hy.cur * hy.pstride;
     double a = 0;
     for (int64_t i = threadIdx.x; i < hy.p; i += 256) a += (double)th[i] * (double)th[i];
     a = wave_sum(a);

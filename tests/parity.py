@@ -24,11 +24,19 @@ def oracle_config(w: Workload) -> O.Config:
                     round_bf16=(w.dtype == "bf16"))
 
 
+ATOL = 1e-12   # quantities below this are numerically zero for these workloads (e.g. the gradient
+               # of a network whose loss has underflowed to 0)
+
+
 def vec_err(a, b) -> float:
+    """max|a-b| / max|b|, with an absolute floor so that two vanishing vectors compare equal."""
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
-    den = np.abs(b).max()
-    return float(np.abs(a - b).max() / den) if den > 0 else float(np.abs(a).max())
+    return float(np.abs(a - b).max() / max(np.abs(b).max(), ATOL / 1e-5))
+
+
+def rel_err(a: float, b: float) -> float:
+    return abs(a - b) / max(abs(b), ATOL / 1e-5)
 
 
 def round_state_to_f32(orc: O.Oracle):
@@ -42,9 +50,18 @@ def push_state(orc: O.Oracle, gpu: Gcada):
                   orc.ring, orc.k)
 
 
-def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, check_steps=None,
-                   groups=None, verbose=False):
+def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, kink_tol=None,
+                   kink_grad_tol=5e-2, stat_vs_threshold=False, verbose=False):
     """Run `steps` iterations; idx: int32 (steps, G, mu) row ids or None for the cyclic window.
+    kink_tol (MLP): a group is "near a ReLU kink" in a step when some hidden pre-activation of the
+    oracle lies within kink_tol (relative to the sum of the magnitudes of its terms) of zero.
+    There both subgradients are valid results and a lower-precision evaluation may take the other
+    one, so for such a group only a loose gradient check (kink_grad_tol) is made and its
+    statistic / mask are not compared; the state checks of that step are skipped when such a
+    group takes part in the aggregate.
+    stat_vs_threshold (bf16): the statistic's error is measured against max(stat, rhs) -- the
+    statistic only matters through its comparison with the threshold, and once the gradients have
+    collapsed below the bf16 noise floor its relative error alone says nothing.
     Returns a dict of the worst errors seen.  Raises AssertionError on a violation."""
     orc = O.Oracle(oracle_config(w), make_theta0(w))
     gpu = Gcada.from_workload(w)
@@ -52,7 +69,7 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ch
     gpu.set_theta(make_theta0(w))
     idx_dev = torch.as_tensor(idx, device="cuda") if idx is not None else None
     worst = dict(grad=0.0, stat=0.0, rhs=0.0, loss=0.0, theta=0.0, h=0.0, vhat=0.0, agg=0.0,
-                 ring=0.0, edge_flips=0, selected=0)
+                 ring=0.0, edge_flips=0, selected=0, kink_groups=0, clean_groups=0, state_steps=0)
     rows_all = [X.shape[0] for X in Xs]
     for k in range(steps):
         round_state_to_f32(orc)
@@ -67,33 +84,46 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ch
         out = gpu.outputs()
         st = gpu.get_state()
         assert st["k"] == orc.k == k + 1
+        near = (orc.kink < kink_tol) if kink_tol is not None else np.zeros(w.G, bool)
+        worst["kink_groups"] += int(near.sum())
+        worst["clean_groups"] += int((~near).sum())
         # a1: fresh gradients, per group
         for g in range(w.G):
             e = vec_err(out["grad"][g], orc.grad[g])
+            if near[g]:
+                assert e <= kink_grad_tol, f"step {k} group {g} (near a kink): gradient error {e:.3e}"
+                continue
             worst["grad"] = max(worst["grad"], e)
             assert e <= tol, f"step {k} group {g}: gradient error {e:.3e}"
         # a2: statistic, threshold, mask
         s_o = orc.stat
         for g in range(w.G):
-            e = abs(out["stat"][g] - s_o[g]) / s_o[g] if s_o[g] > 0 else abs(out["stat"][g])
+            if near[g]:
+                continue
+            e = rel_err(out["stat"][g], s_o[g])
+            if stat_vs_threshold:
+                e = abs(out["stat"][g] - s_o[g]) / max(s_o[g], orc.rhs, ATOL)
             worst["stat"] = max(worst["stat"], e)
             assert e <= tol, f"step {k} group {g}: stat {out['stat'][g]} vs {s_o[g]} ({e:.3e})"
-        e = abs(out["rhs"] - orc.rhs) / orc.rhs if orc.rhs > 0 else abs(out["rhs"])
+        e = rel_err(out["rhs"], orc.rhs)
         worst["rhs"] = max(worst["rhs"], e)
         assert e <= tol, f"step {k}: rhs {out['rhs']} vs {orc.rhs}"
         flips = out["mask"] != mask_o
         for g in np.nonzero(flips)[0]:
+            if near[g]:
+                continue
             assert abs(s_o[g] - orc.rhs) < edge * orc.rhs, \
                 f"step {k} group {g}: mask {out['mask'][g]} vs {mask_o[g]}, stat {s_o[g]} rhs {orc.rhs}"
             worst["edge_flips"] += 1
         worst["selected"] += int(mask_o.sum())
         assert np.array_equal(gpu.mask_out.cpu().numpy(), out["mask"])
-        e = abs(out["loss"] - loss_o) / abs(loss_o)
+        e = rel_err(out["loss"], loss_o)
         worst["loss"] = max(worst["loss"], e)
         assert e <= tol, f"step {k}: loss {out['loss']} vs {loss_o}"
-        assert abs(float(gpu.loss_out.item()) - loss_o) <= 1e-6 * abs(loss_o) + tol * abs(loss_o)
-        if flips.any():
-            continue   # knife-edge: the states legitimately differ after this step
+        assert abs(float(gpu.loss_out.item()) - loss_o) <= (1e-6 + tol) * abs(loss_o) + ATOL
+        if flips.any() or (near & (mask_o != 0)).any():
+            continue   # knife-edge / kink: the states legitimately differ after this step
+        worst["state_steps"] += 1
         # a3 / a4
         for name in ("agg", "h", "vhat"):
             e = vec_err(st[name], getattr(orc, name))
@@ -155,3 +185,69 @@ def free_running(w: Workload, steps, Xs, ys, idx=None):
     return dict(masks_gpu=masks_g.cpu().numpy(), masks_oracle=masks_o,
                 loss_gpu=loss_g.cpu().numpy().astype(np.float64), loss_oracle=loss_o,
                 theta_gpu=theta_g, theta_oracle=orc.theta.copy())
+
+
+def synthetic_state(w: Workload, seed=7):
+    """A valid mid-run state made from seeded random numbers only (no run needed): ages in [1, D],
+    groups of equal age share their stale iterate, moments and stored gradients of plausible size."""
+    rng = np.random.default_rng(seed)
+    p, G, D = w.p, w.G, w.D
+    theta0 = make_theta0(w).astype(np.float64)
+    scale = max(np.abs(theta0).max(), 0.05)
+    # hist[t] = iterate t steps ago: further back, further away from the current iterate
+    hist = [theta0 + 0.02 * scale * (t + 1) * rng.standard_normal(p) for t in range(D + 1)]
+    tau = rng.integers(1, D + 1, size=G).astype(np.int32)
+    f32 = lambda a: np.asarray(a, np.float32).astype(np.float64)
+    st = dict(theta=f32(hist[0]), h=f32(0.1 * rng.standard_normal(p)), vhat=f32(rng.random(p) * 0.5),
+              agg=f32(rng.standard_normal(p)), theta_stale=f32(np.stack([hist[t] for t in tau])),
+              last=f32(rng.standard_normal((G, p))), tau=tau,
+              dtheta_sq=rng.random(D) * 1e-3 * p * scale ** 2, k=D + 3)
+    return st
+
+
+def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e-6, kink_tol=None,
+                        seed=7):
+    """One iteration of the full-size workload on the GPU from a synthetic state; the oracle
+    evaluates only the sampled `groups` (each group's gradients, statistic and mask depend on its
+    own shard and state only) and those outputs are compared."""
+    st = synthetic_state(w, seed)
+    gpu = Gcada.from_workload(w)
+    gpu.set_shards(Xs, ys)
+    gpu.set_theta(make_theta0(w))
+    gpu.set_state(**st)
+    ws = replace_groups(w, len(groups))
+    orc = O.Oracle(oracle_config(ws), make_theta0(w))
+    for name in ("theta", "h", "vhat", "agg"):
+        getattr(orc, name)[...] = st[name]
+    orc.theta_stale[...] = st["theta_stale"][groups]
+    orc.last[...] = st["last"][groups]
+    orc.tau[...] = st["tau"][groups]
+    orc.ring[...] = st["dtheta_sq"]
+    orc.k = st["k"]
+    Xmb, ymb = gather_rows([Xs[g] for g in groups], [ys[g] for g in groups], idx_step[groups])
+    mask_o, _ = orc.step(Xmb, ymb)
+    gpu.step(torch.as_tensor(idx_step, device="cuda").contiguous())
+    out = gpu.outputs()
+    worst = dict(grad=0.0, stat=0.0, rhs=rel_err(out["rhs"], orc.rhs), kink_groups=0)
+    assert worst["rhs"] <= 1e-9
+    for j, g in enumerate(groups):
+        near = kink_tol is not None and orc.kink[j] < kink_tol
+        e = vec_err(out["grad"][g], orc.grad[j])
+        if near:
+            worst["kink_groups"] += 1
+            assert e <= 5e-2, f"group {g} (near a kink): gradient error {e:.3e}"
+            continue
+        worst["grad"] = max(worst["grad"], e)
+        assert e <= tol, f"group {g}: gradient error {e:.3e}"
+        e = rel_err(out["stat"][g], orc.stat[j])
+        worst["stat"] = max(worst["stat"], e)
+        assert e <= tol, f"group {g}: stat {out['stat'][g]} vs {orc.stat[j]}"
+        if out["mask"][g] != mask_o[j]:
+            assert abs(orc.stat[j] - orc.rhs) < edge * orc.rhs, f"group {g}: mask differs"
+    gpu.close()
+    return worst
+
+
+def replace_groups(w: Workload, G: int) -> Workload:
+    from dataclasses import replace
+    return replace(w, G=G)

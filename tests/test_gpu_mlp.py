@@ -1,0 +1,100 @@
+"""GPU parity of the MLP path (MFMA GEMMs, fp32 and bf16) with the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from gcada_inputs import CONFIGS, make_indices, make_shards, scaled
+
+pytestmark = pytest.mark.gpu
+
+KINK = 5e-8   # fp32: a hidden pre-activation this close to 0 (relative) may flip its ReLU
+
+
+@pytest.fixture(scope="module")
+def par():
+    import parity
+    return parity
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+@pytest.mark.parametrize("widths,mu,G,rows,steps", [
+    ((20, 12, 5), 16, 3, 50, 15),             # everything ragged, one hidden layer
+    ((30, 6), 24, 2, 60, 12),                 # no hidden layer: softmax regression
+    ((100, 70, 50, 7), 40, 3, 90, 12),        # two hidden layers
+    ((784, 200, 10), 64, 4, 300, 12),         # layer widths of the fp32 configuration, small batch
+    ((130, 260, 129, 3), 130, 2, 200, 8),     # several GEMM tiles with ragged edges
+])
+def test_mlp_f32_shapes(par, widths, mu, G, rows, steps):
+    w = scaled(CONFIGS["mlp_784"], name="mlp_f32", widths=widths, mu=mu, G=G, rows=rows, D=4)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, steps)
+    worst = par.teacher_forced(w, steps, Xs, ys, idx, kink_tol=KINK)
+    _say(worst)
+    assert worst["clean_groups"] > 0.6 * G * steps
+    assert worst["state_steps"] > 0.4 * steps
+
+
+def test_mlp_f32_cyclic_window(par):
+    w = scaled(CONFIGS["mlp_784"], name="mlp_f32", widths=(50, 33, 4), mu=20, G=3, rows=70, D=3)
+    Xs, ys = make_shards(w, "cuda")
+    worst = par.teacher_forced(w, 10, Xs, ys, None, kink_tol=KINK)
+    _say(worst)
+
+
+def test_mlp_784_full_size(par):
+    # configuration 3: 784-200-10, G=10, mu=512, 6000 rows per shard, fp32
+    w = CONFIGS["mlp_784"]
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 6
+    idx = make_indices(w, steps)
+    worst = par.teacher_forced(w, steps, Xs, ys, idx, kink_tol=KINK)
+    _say(worst)
+    assert worst["clean_groups"] > 0.3 * w.G * steps
+
+
+# bf16: X, the weights the gradients are evaluated at, the activations and the back-propagated
+# signals are bf16 on the GPU; the oracle rounds only X and theta.  A hidden unit whose
+# pre-activation is within bf16 rounding of zero may take the other ReLU branch; with few samples
+# and units one such unit is a visible share of a gradient row, hence the wider tolerance on the
+# two small shapes.
+@pytest.mark.parametrize("widths,mu,G,rows,steps,tol", [
+    ((128, 96, 64, 10), 48, 4, 100, 7, 6e-2),
+    ((200, 150, 10), 256, 3, 300, 6, 2e-2),
+    ((3072, 1024, 1024, 10), 64, 2, 150, 3, 2e-2),   # layer widths of the bf16 configuration
+])
+def test_mlp_bf16_shapes(par, widths, mu, G, rows, steps, tol):
+    w = scaled(CONFIGS["mlp_3072_bf16"], name="mlp_bf16", widths=widths, mu=mu, G=G, rows=rows, D=4)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, steps)
+    worst = par.teacher_forced(w, steps, Xs, ys, idx, tol=tol, edge=tol, stat_vs_threshold=True)
+    _say(worst)
+
+
+def test_mlp_3072_bf16_full_size_sampled_groups(par):
+    # configuration 5 at full size (G=64, mu=256, 781 rows per shard): one iteration from a seeded
+    # synthetic state, three sampled groups checked against the oracle
+    w = CONFIGS["mlp_3072_bf16"]
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, 1)
+    worst = par.sampled_groups_step(w, Xs, ys, idx[0], groups=[0, 17, 63], tol=2e-2, edge=2e-2)
+    _say(worst)
+
+
+def test_mlp_free_run_loss_decreases_and_tracks_oracle(par):
+    w = scaled(CONFIGS["mlp_784"], name="mlp_f32", widths=(64, 48, 10), mu=64, G=4, rows=400, D=5)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 60
+    idx = make_indices(w, steps)
+    r = par.free_running(w, steps, Xs, ys, idx)
+    agree = (r["masks_gpu"] == r["masks_oracle"]).mean()
+    _say("mask agreement", agree, "loss", r["loss_gpu"][0], "->", r["loss_gpu"][-1], r["loss_oracle"][-1])
+    assert agree >= 0.9
+    assert r["loss_gpu"][-1] < 0.7 * r["loss_gpu"][0]
+    np.testing.assert_allclose(r["loss_gpu"], r["loss_oracle"], rtol=5e-2)

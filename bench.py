@@ -84,15 +84,28 @@ def main():
 
     ms_per_step = dt / K * 1e3
     iters_s = K / dt
-    # algorithmic bytes of the gradient stage per step: one read of the touched minibatch rows
-    esz = 2 if w.dtype == "bf16" else 4
-    alg_bytes = w.G * w.mu * w.widths[0] * esz
     grad_ms_avg = grad_ms / max(n_timed, 1)
-    achieved = alg_bytes / (grad_ms_avg * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": "gradient stage (lr_tile_kernel + lr_tile_reduce)",
-                "avg_ms": round(grad_ms_avg, 5), "algorithmic_bytes": alg_bytes}
+    if w.model == "logreg":
+        # algorithmic bytes of the gradient stage per step: one read of the touched minibatch rows
+        alg_bytes = w.G * w.mu * w.widths[0] * 4
+        achieved = alg_bytes / (grad_ms_avg * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "kernel": "gradient stage (lr_tile_kernel + lr_tile_reduce)",
+                    "avg_ms": round(grad_ms_avg, 5), "algorithmic_bytes": alg_bytes}
+    else:
+        # algorithmic flops of the gradient stage per step: forward + weight-gradient GEMMs of
+        # every layer and the back-propagation GEMMs of layers 2..L, for two iterates and G groups
+        n = w.widths
+        per = sum(2 * w.mu * n[l] * n[l - 1] for l in range(1, len(n))) * 2 \
+            + sum(2 * w.mu * n[l] * n[l - 1] for l in range(2, len(n)))
+        flops = per * 2 * w.G
+        peak = 2500.0 if w.dtype == "bf16" else 157.3
+        achieved = flops / (grad_ms_avg * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                    "frac": round(achieved / peak, 4), "traffic": None,
+                    "kernel": "gradient stage (mlp_gemm forward/backward/weight-gradient + output layer)",
+                    "avg_ms": round(grad_ms_avg, 5), "algorithmic_flops": flops}
 
     # modelled wall-clock / communication / computation of the paper's cost model (reported only)
     T = make_delays(w, K)

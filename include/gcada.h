@@ -126,13 +126,14 @@ typedef struct gcada_state_view {
     int32_t G, D, M_G;
     int64_t k;               /* iterations done (host mirror of the device counter)           */
     int64_t slot_stride;     /* floats between consecutive slots of theta_ring                */
+    int64_t grad_stride;     /* floats between consecutive groups in grad and last (>= p)     */
     int32_t cur_slot;        /* theta^k is slot k mod (D+1); theta^{k-t} is slot (k-t) mod (D+1) */
     float*   theta_ring;     /* [device] (D+1) slots of p floats: the last D+1 iterates       */
     float*   h;              /* [device] p                                                    */
     float*   vhat;           /* [device] p                                                    */
     float*   agg;            /* [device] p: lazily aggregated gradient                        */
-    float*   grad;           /* [device] G x p: fresh gradients of the last step              */
-    float*   last;           /* [device] G x p: gradient each group uploaded last             */
+    float*   grad;           /* [device] G rows of grad_stride: fresh gradients of the last step */
+    float*   last;           /* [device] G rows of grad_stride: gradient each group uploaded last */
     int32_t* tau;            /* [device] G ages                                               */
     double*  dtheta_sq;      /* [device] D: ||theta^{j+1}-theta^j||^2 stored at index j mod D */
     double*  stat;           /* [device] G: stat_g of the last step                           */

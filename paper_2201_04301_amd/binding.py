@@ -32,7 +32,8 @@ class gcada_dims(C.Structure):
 
 class gcada_state_view(C.Structure):
     _fields_ = [("p", C.c_int64), ("G", C.c_int32), ("D", C.c_int32), ("M_G", C.c_int32),
-                ("k", C.c_int64), ("slot_stride", C.c_int64), ("cur_slot", C.c_int32),
+                ("k", C.c_int64), ("slot_stride", C.c_int64), ("grad_stride", C.c_int64),
+                ("cur_slot", C.c_int32),
                 ("theta_ring", C.c_void_p), ("h", C.c_void_p), ("vhat", C.c_void_p),
                 ("agg", C.c_void_p), ("grad", C.c_void_p), ("last", C.c_void_p),
                 ("tau", C.c_void_p), ("dtheta_sq", C.c_void_p), ("stat", C.c_void_p),

@@ -69,7 +69,7 @@ void free_all(gcada_ctx* c)
     for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
     c->ev.clear();
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->grad, c->last, c->tau,
-                    c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat,
+                    c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat, c->stat_sum,
                     c->part_sq};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -101,11 +101,8 @@ try {
     for (int l = 0; l < dims->n_widths; ++l)
         if (dims->widths[l] < 1)
             return fail(nullptr, GCADA_EINVAL, "every width must be >= 1");
-    if (dims->model == GCADA_MLP && dims->widths[dims->n_widths - 1] > 32)
-        return fail(nullptr, GCADA_EINVAL, "MLP output width (classes) must be <= 32");
-    if (dims->model == GCADA_MLP &&
-        (size_t)2 * dims->batch * dims->widths[dims->n_widths - 1] * sizeof(float) > 64 * 1024)
-        return fail(nullptr, GCADA_EINVAL, "MLP: batch * classes must be <= 8192");
+    if (dims->model == GCADA_MLP && dims->widths[dims->n_widths - 1] > 128)
+        return fail(nullptr, GCADA_EINVAL, "MLP output width (classes) must be <= 128");
     if (dims->batch < 1 || dims->batch > 4096)
         return fail(nullptr, GCADA_EINVAL, "dims.batch (mu) must be in [1, 4096]");
     if (!(dims->l2 >= 0.0f) || (dims->dtype == GCADA_BF16 && dims->l2 != 0.0f))
@@ -140,7 +137,7 @@ try {
     };
     hipError_t e;
     if ((e = hipGetDevice(&x->device)) != hipSuccess) return bail(e, "hipGetDevice");
-    const size_t p = (size_t)hy.p, Gp = (size_t)G * p;
+    const size_t p = (size_t)hy.pstride, Gp = (size_t)G * p;   // every vector padded to pstride
     if ((e = dalloc(&x->d_shards, (size_t)G)) != hipSuccess) return bail(e, "alloc shards");
     if ((e = dalloc(&x->ring, (size_t)(D + 1) * hy.pstride)) != hipSuccess) return bail(e, "alloc iterates");
     if ((e = dalloc(&x->h, p)) != hipSuccess) return bail(e, "alloc h");
@@ -152,6 +149,7 @@ try {
     if ((e = dalloc(&x->nring, (size_t)D)) != hipSuccess) return bail(e, "alloc history");
     if ((e = dalloc(&x->stat, (size_t)G)) != hipSuccess) return bail(e, "alloc stat");
     if ((e = dalloc(&x->mask, (size_t)G)) != hipSuccess) return bail(e, "alloc mask");
+    if ((e = dalloc(&x->stat_sum, (size_t)G)) != hipSuccess) return bail(e, "alloc stat sums");
     if ((e = dalloc(&x->ctl, 1)) != hipSuccess) return bail(e, "alloc control block");
 
     e = dims->model == GCADA_LOGREG ? gcada::lr_plan(x) : gcada::mlp_plan(x);
@@ -211,10 +209,10 @@ static void set_iteration(gcada_ctx* ctx)
 static int reset_run(gcada_ctx* ctx, const float* theta0_any)
 {
     const gcada::Hyper& hy = ctx->hy;
-    const size_t p = (size_t)hy.p, Gp = (size_t)hy.G * p;
+    const size_t p = (size_t)hy.pstride, Gp = (size_t)hy.G * p;
     for (int s = 0; s <= hy.D; ++s)
-        HIP_TRY(ctx, hipMemcpy(ctx->ring + (size_t)s * hy.pstride, theta0_any, p * sizeof(float),
-                               hipMemcpyDefault));
+        HIP_TRY(ctx, hipMemcpy(ctx->ring + (size_t)s * hy.pstride, theta0_any,
+                               (size_t)hy.p * sizeof(float), hipMemcpyDefault));
     HIP_TRY(ctx, hipMemset(ctx->h, 0, p * 4));
     HIP_TRY(ctx, hipMemset(ctx->vhat, 0, p * 4));
     HIP_TRY(ctx, hipMemset(ctx->agg, 0, p * 4));
@@ -291,6 +289,7 @@ int gcada_state(gcada_ctx* ctx, gcada_state_view* out)
     v.p = ctx->hy.p; v.G = ctx->hy.G; v.D = ctx->hy.D; v.M_G = ctx->M_G;
     v.k = ctx->k;
     v.slot_stride = ctx->hy.pstride;
+    v.grad_stride = ctx->hy.pstride;
     v.cur_slot = (int32_t)(ctx->k % (ctx->hy.D + 1));
     v.theta_ring = ctx->ring; v.h = ctx->h; v.vhat = ctx->vhat; v.agg = ctx->agg;
     v.grad = ctx->grad; v.last = ctx->last; v.tau = ctx->tau; v.dtheta_sq = ctx->nring;
@@ -323,7 +322,8 @@ try {
                                    p * 4, hipMemcpyDeviceToHost));
         }
     if (out->last)
-        HIP_TRY(ctx, hipMemcpy(out->last, ctx->last, (size_t)hy.G * p * 4, hipMemcpyDeviceToHost));
+        HIP_TRY(ctx, hipMemcpy2D(out->last, p * 4, ctx->last, (size_t)hy.pstride * 4, p * 4, hy.G,
+                                 hipMemcpyDeviceToHost));
     if (out->tau) std::memcpy(out->tau, tau.data(), (size_t)hy.G * 4);
     if (out->dtheta_sq)
         HIP_TRY(ctx, hipMemcpy(out->dtheta_sq, ctx->nring, (size_t)hy.D * 8, hipMemcpyDeviceToHost));
@@ -362,7 +362,8 @@ try {
     HIP_TRY(ctx, hipMemcpy(ctx->h, in->h, p * 4, hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->vhat, in->vhat, p * 4, hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->agg, in->agg, p * 4, hipMemcpyHostToDevice));
-    HIP_TRY(ctx, hipMemcpy(ctx->last, in->last, (size_t)hy.G * p * 4, hipMemcpyHostToDevice));
+    HIP_TRY(ctx, hipMemcpy2D(ctx->last, (size_t)hy.pstride * 4, in->last, p * 4, p * 4, hy.G,
+                             hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->tau, in->tau, (size_t)hy.G * 4, hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->nring, in->dtheta_sq, (size_t)hy.D * 8, hipMemcpyHostToDevice));
     Ctl z{};

@@ -82,6 +82,7 @@ struct gcada_ctx {
     float* res = nullptr;          // logistic: G x mu x 2 (residual at theta^k, residual difference)
     double* part_loss = nullptr;   // per-block partial loss sums
     double* part_stat = nullptr;   // G x n_stat_part partial squared norms
+    double* stat_sum = nullptr;    // G: the partials of a group added up (when they are many)
     double* part_sq = nullptr;     // epilogue partials: 2 per block (||step||^2, ||theta_new||^2)
     int32_t n_loss_part = 0;   // allocated partial loss sums per group
     int32_t n_loss_part_lr = 0;   // blocks per group of the general logistic forward kernel

@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kBwdWaves* kWave) void lr_backward(
                         gv[q] += ml * t;
                         sv[q] += ml * (t - ts[j + q]);
                     }
-                    grad[(int64_t)g * hy.p + j + q] = gv[q];
+                    grad[(int64_t)g * hy.pstride + j + q] = gv[q];
                     sq += (double)sv[q] * (double)sv[q];
                 }
             }

@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
             as.x += ml * (t.x - u.x); as.y += ml * (t.y - u.y);
             as.z += ml * (t.z - u.z); as.w += ml * (t.w - u.w);
         }
-        *(float4*)(grad + (int64_t)g * hy.p + j) = ag;
+        *(float4*)(grad + (int64_t)g * hy.pstride + j) = ag;
         sq = (double)as.x * as.x + (double)as.y * as.y + (double)as.z * as.z + (double)as.w * as.w;
     }
     sq = wave_sum(sq);

@@ -92,7 +92,7 @@ constexpr int kTileBytes = kBM * kRowPitch;               // 18432
 constexpr int kGemmThreads = 256;
 constexpr int kGemmLds = 4 * kTileBytes;                  // P,Q x two stages = 73728
 
-enum { EPI_FWD = 0, EPI_DA = 1, EPI_DW = 2 };
+enum { EPI_FWD = 0, EPI_DA = 1, EPI_DW = 2, EPI_HEAD = 3 };
 
 struct GemmArgs {
     Hyper hy;
@@ -102,8 +102,10 @@ struct GemmArgs {
     const void* P; int64_t p_it, p_g; int ldp;
     // Q operand: either per (it,g) like P, or a weight copy indexed by ring slot
     const void* Q; int64_t q_it, q_g, q_slot; int ldq; int q_is_weight;
-    // FWD: bias from the fp32 ring (offset boff), outputs A [M][ldo] and AT [N][ldt]
-    // DA : relu mask read from `mask` (same layout as the output), outputs dZ and dZT
+    // FWD : bias from the fp32 ring (offset boff), outputs A [M][ldo] and AT [N][ldt]
+    // DA  : relu mask read from `mask` (same layout as the output), outputs dZ and dZT
+    // HEAD: output layer (N = classes <= 128, one tile holds whole rows): bias, softmax
+    //       cross-entropy against the labels, outputs dZ_L and dZ_L^T, one loss partial per block
     const float* ring; int64_t boff;
     const void* maskp; int64_t m_it, m_g; int ldm;
     void* O; int64_t o_it, o_g; int ldo;
@@ -112,6 +114,8 @@ struct GemmArgs {
     float* grad; int64_t goff;
     double* part_stat; int n_stat; int stat_off;
     int G;
+    // HEAD
+    const ShardDesc* shards; const int32_t* idx; double* part_loss;
 };
 
 template <typename T>
@@ -261,7 +265,7 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm(GemmArgs a)
     const int cl = lane & 31, rh = (lane >> 5) * 4;
     if constexpr (EPI == EPI_DW) {
         double sq = 0;
-        float* gb = a.grad + (int64_t)g * hy.p + a.goff;
+        float* gb = a.grad + (int64_t)g * hy.pstride + a.goff;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -285,6 +289,81 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm(GemmArgs a)
         if (tid == 0)
             a.part_stat[(int64_t)g * a.n_stat + a.stat_off + blockIdx.y * gridDim.x + blockIdx.x] =
                 red[0] + red[1] + red[2] + red[3];
+    } else if constexpr (EPI == EPI_HEAD) {
+        // logits tile -> LDS (fp32), then one thread per sample: softmax cross-entropy and dZ_L
+        constexpr int pitch = kBN + 4;
+        float* lg = (float*)lds;
+        const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
+        const float* bias = a.ring + (int64_t)slot * hy.pstride + a.boff;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int nl = wn * 64 + j * 32 + cl;
+                const float bv = nl < a.N ? round_to<T>(bias[nl]) : 0.0f;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int ml = wm * 64 + i * 32 + (e >> 2) * 8 + rh + (e & 3);
+                    lg[ml * pitch + nl] = acc[i][j][e] + bv;
+                }
+            }
+        __syncthreads();
+        T* O = (T*)a.O + (int64_t)it0 * a.o_it + (int64_t)g * a.o_g;        // dZ_L   [mu][ldo]
+        T* OT = (T*)a.OT + (int64_t)it0 * a.t_it + (int64_t)g * a.t_g;      // dZ_L^T [N][ldt]
+        double lsum = 0;
+        const int nc = a.N;
+        if (tid < kBM && m0 + tid < a.M) {
+            const int i = m0 + tid;
+            const ShardDesc sh = a.shards[g];
+            int64_t row;
+            if (a.idx) row = a.idx[(int64_t)g * hy.mu + i];
+            else row = (int64_t)(((unsigned long long)hy.k * (unsigned long long)hy.mu +
+                                  (unsigned long long)i) % (unsigned long long)sh.rows);
+            const int y = ((const int32_t*)sh.y)[row];
+            float* z = lg + tid * pitch;
+            // Everything relative to the true class, so that a confidently right sample
+            // (p_y -> 1) loses no digits: t_c = z_c - z_y, m = max_c t_c >= 0,
+            // S = sum_c exp(t_c - m); loss = m + log S; p_c = exp(t_c - m) / S;
+            // dZ_c = p_c (c != y), dZ_y = -sum_{c != y} p_c.
+            const float zy = z[y];
+            float m = 0.0f;
+            for (int c = 0; c < nc; ++c) m = fmaxf(m, z[c] - zy);
+            float so = 0.0f;
+            for (int c = 0; c < nc; ++c)
+                if (c != y) so += expf(z[c] - zy - m);
+            const float ey = expf(-m);
+            const float inv = 1.0f / (ey + so);
+            float others = 0.0f;
+            for (int c = 0; c < nc; ++c) {
+                if (c == y) continue;
+                const float dv = expf(z[c] - zy - m) * inv;
+                others += dv;
+                z[c] = dv;
+            }
+            z[y] = -others;
+            lsum = m == 0.0f ? (double)log1pf(so) : (double)(m + logf(ey + so));
+            for (int c = 0; c < nc; ++c) O[(int64_t)i * a.ldo + c] = to_T<T>(z[c]);
+        } else if (tid < kBM) {
+            for (int c = 0; c < nc; ++c) lg[tid * pitch + c] = 0.0f;
+        }
+        lsum = wave_sum(lsum);
+        __syncthreads();
+        double* red = (double*)(lg + kBM * pitch);
+        if (lane == 0) red[wave] = lsum;
+        // transposed copy: class c, samples m0 .. m0+127 (zeros beyond M keep the padding clean)
+        constexpr int V = 16 / esz;
+        for (int c2 = tid; c2 < nc * (kBM / V); c2 += kGemmThreads) {
+            const int c = c2 / (kBM / V), mv = (c2 % (kBM / V)) * V;
+            if (m0 + mv < a.M) {
+                alignas(16) T tmp[V];
+#pragma unroll
+                for (int q = 0; q < V; ++q) tmp[q] = to_T<T>(lg[(mv + q) * pitch + c]);
+                *(uint4*)(OT + (int64_t)c * a.ldt + m0 + mv) = *(const uint4*)tmp;
+            }
+        }
+        __syncthreads();
+        if (it0 == 0 && tid == 0)
+            a.part_loss[(int64_t)g * gridDim.y + blockIdx.y] = red[0] + red[1] + red[2] + red[3];
     } else {
         // stage the tile in LDS as T [128][128 + 8], then write it row-major and transposed
         constexpr int pitch = kBN + 8;
@@ -401,212 +480,7 @@ __global__ __launch_bounds__(256) void mlp_weight_copy(const float* __restrict__
     }
 }
 
-// ---------------------------------------------------------------------------------------
-// Output layer.  One block handles 32 samples of one (iterate, group):
-//   logits = W_L a_{L-1} + b_L,  softmax cross-entropy, dZ_L = softmax - onehot   (fp32)
-//   dZ_{L-1} = (W_L^T dZ_L) * [a_{L-1} > 0]  -> stored row-major and transposed in T
-// The last layer's weights come from the fp32 ring, rounded to T, staged in LDS when they fit.
-constexpr int kHeadRows = 32;
-constexpr int kMaxClasses = 32;
-constexpr int kHeadWLds = 48 * 1024;     // bytes of LDS the staged W_L may take
-
-struct HeadArgs {
-    Hyper hy;
-    const int32_t* tau;
-    const ShardDesc* shards;
-    const int32_t* idx;
-    const float* ring;
-    int64_t woff, boff;
-    int nc, nh, ldh, ldmu, G, has_hidden, w_in_lds;
-    const void* Aprev; int64_t a_it, a_g;
-    float* dZL;                 // [2][G][mu][nc]
-    void* dZ; void* dZT; int64_t z_it, z_g, zt_it, zt_g;
-    double* part_loss;
-};
-
-// grid: (ceil(mu/32), 2G), block 256; NC = class count rounded up to a power of two
-template <typename T, int NC>
-__global__ __launch_bounds__(256) void mlp_head(HeadArgs a)
-{
-    __shared__ float s_logit[kHeadRows][NC];
-    __shared__ float s_dz[kHeadRows][NC];
-    __shared__ double s_loss[4];
-    extern __shared__ float s_w[];              // [nc][nh] when w_in_lds
-    const Hyper& hy = a.hy;
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int g = blockIdx.y % a.G, it = blockIdx.y / a.G;
-    const int r0 = blockIdx.x * kHeadRows;
-    const int nc = a.nc, nh = a.nh, ldh = a.ldh;
-    const int slot = it == 0 ? hy.cur : stale_slot(hy, a.tau, g);
-    const float* __restrict__ Wg = a.ring + (int64_t)slot * hy.pstride + a.woff;     // [nc][nh]
-    const float* __restrict__ b = a.ring + (int64_t)slot * hy.pstride + a.boff;
-    const T* __restrict__ A = (const T*)a.Aprev + (int64_t)it * a.a_it + (int64_t)g * a.a_g;
-    const ShardDesc sh = a.shards[g];
-
-    if (a.w_in_lds) {
-        for (int e = tid; e < nc * nh; e += 256) s_w[e] = round_to<T>(Wg[e]);
-        __syncthreads();
-    }
-    // logits: wave w takes rows w, w+4, ...; lanes stride over the hidden units
-    for (int r = wave; r < kHeadRows; r += 4) {
-        const int i = r0 + r;
-        float accv[NC];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) accv[c] = 0.0f;
-        if (i < hy.mu) {
-            for (int n = lane; n < nh; n += kWave) {
-                const float av = to_f<T>(A[(int64_t)i * ldh + n]);
-#pragma unroll
-                for (int c = 0; c < NC; ++c)
-                    if (c < nc)
-                        accv[c] += av * (a.w_in_lds ? s_w[c * nh + n] : round_to<T>(Wg[(int64_t)c * nh + n]));
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            if (c < nc) {
-                const float t = wave_sum(accv[c]);
-                if (lane == 0) s_logit[r][c] = t + round_to<T>(b[c]);
-            }
-        }
-    }
-    __syncthreads();
-    // softmax / loss / dZ_L: one thread per row
-    double lsum = 0;
-    if (tid < kHeadRows) {
-        const int i = r0 + tid;
-        if (i < hy.mu) {
-            int64_t row;
-            if (a.idx) row = a.idx[(int64_t)g * hy.mu + i];
-            else row = (int64_t)(((unsigned long long)hy.k * (unsigned long long)hy.mu +
-                                  (unsigned long long)i) % (unsigned long long)sh.rows);
-            const int y = ((const int32_t*)sh.y)[row];
-            // Everything relative to the true class, so that a confidently right sample
-            // (p_y -> 1) loses no digits: t_c = z_c - z_y, m = max_c t_c >= 0,
-            // S = sum_c exp(t_c - m); loss = m + log S; p_c = exp(t_c - m) / S;
-            // dZ_c = p_c (c != y), dZ_y = -sum_{c != y} p_c.
-            const float zy = s_logit[tid][y];
-            float m = 0.0f;
-            for (int c = 0; c < nc; ++c) m = fmaxf(m, s_logit[tid][c] - zy);
-            float so = 0.0f;                                  // the classes other than y
-            for (int c = 0; c < nc; ++c)
-                if (c != y) so += expf(s_logit[tid][c] - zy - m);
-            const float ey = expf(-m);
-            const float inv = 1.0f / (ey + so);
-            float* dzl = a.dZL + (((int64_t)it * a.G + g) * hy.mu + i) * nc;
-            float others = 0.0f;
-            for (int c = 0; c < nc; ++c) {
-                if (c == y) continue;
-                const float dv = expf(s_logit[tid][c] - zy - m) * inv;
-                others += dv;
-                s_dz[tid][c] = dv;
-                dzl[c] = dv;
-            }
-            s_dz[tid][y] = -others;
-            dzl[y] = -others;
-            lsum = m == 0.0f ? (double)log1pf(so) : (double)(m + logf(ey + so));
-            for (int c = nc; c < NC; ++c) s_dz[tid][c] = 0.0f;     // padding classes contribute nothing
-        } else {
-            for (int c = 0; c < NC; ++c) s_dz[tid][c] = 0.0f;
-        }
-    }
-    if (wave == 0) {
-        lsum = wave_sum(lsum);
-        if (lane == 0) s_loss[0] = lsum;
-    }
-    __syncthreads();
-    if (it == 0 && tid == 0) a.part_loss[(int64_t)g * gridDim.x + blockIdx.x] = s_loss[0];
-    if (!a.has_hidden) return;
-    // back-propagated signal of the last hidden layer for these 32 rows
-    T* __restrict__ Z = (T*)a.dZ + (int64_t)it * a.z_it + (int64_t)g * a.z_g;        // [mu][ldh]
-    T* __restrict__ ZT = (T*)a.dZT + (int64_t)it * a.zt_it + (int64_t)g * a.zt_g;    // [nh][ldmu]
-    for (int n = tid; n < nh; n += 256) {
-        float w[NC];
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-            w[c] = c < nc ? (a.w_in_lds ? s_w[c * nh + n] : round_to<T>(Wg[(int64_t)c * nh + n])) : 0.0f;
-        // V consecutive samples of column n at a time: one 16-byte store into the transposed copy
-        // (r0 is a multiple of 32; ldmu a multiple of 64)
-        constexpr int V = 16 / (int)sizeof(T);
-#pragma unroll 1
-        for (int q = 0; q < kHeadRows / V; ++q) {
-            alignas(16) T col[V];
-#pragma unroll
-            for (int e = 0; e < V; ++e) {
-                const int r = q * V + e, i = r0 + r;
-                float v = 0.0f;
-                if (i < hy.mu) {
-#pragma unroll
-                    for (int c = 0; c < NC; ++c) v += s_dz[r][c] * w[c];
-                    if (!(to_f<T>(A[(int64_t)i * ldh + n]) > 0.0f)) v = 0.0f;
-                    Z[(int64_t)i * ldh + n] = to_T<T>(v);
-                }
-                col[e] = to_T<T>(v);
-            }
-            *(uint4*)(ZT + (int64_t)n * a.ldmu + r0 + q * V) = *(const uint4*)col;
-        }
-    }
-}
-
-// Gradient of the output layer: dW_L[c][n] = sum_i dZ_L[i][c] a_{L-1}[i][n], db_L[c] = sum_i dZ_L[i][c],
-// for both iterates; fresh values -> grad, squared differences -> one partial per block.
-// grid: (ceil(nh/256), G), block 256: thread = hidden unit n.
-template <typename T>
-__global__ __launch_bounds__(256) void mlp_head_grad(Hyper hy, int nc, int nh, int ldh,
-                                                     const T* __restrict__ Aprev, int64_t a_it, int64_t a_g,
-                                                     const float* __restrict__ dZL, float* __restrict__ grad,
-                                                     int64_t woff, int64_t boff, double* __restrict__ part_stat,
-                                                     int n_stat, int stat_off, int G)
-{
-    extern __shared__ float s_dzl[];            // [2][mu][nc]
-    __shared__ double s_red[4];
-    const int g = blockIdx.y, tid = threadIdx.x, n = blockIdx.x * 256 + tid;
-    const int mu = hy.mu;
-    for (int it = 0; it < 2; ++it)
-        for (int e = tid; e < mu * nc; e += 256)
-            s_dzl[(it * mu) * nc + e] = dZL[(((int64_t)it * G + g) * mu) * nc + e];
-    __syncthreads();
-    double sq = 0;
-    if (n < nh) {
-        float acc[2][kMaxClasses];
-#pragma unroll
-        for (int c = 0; c < kMaxClasses; ++c) acc[0][c] = acc[1][c] = 0.0f;
-        for (int it = 0; it < 2; ++it) {
-            const T* A = Aprev + (int64_t)it * a_it + (int64_t)g * a_g;
-            for (int i = 0; i < mu; ++i) {
-                const float av = to_f<T>(A[(int64_t)i * ldh + n]);
-#pragma unroll
-                for (int c = 0; c < kMaxClasses; ++c)
-                    if (c < nc) acc[it][c] += s_dzl[(it * mu + i) * nc + c] * av;
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < kMaxClasses; ++c)
-            if (c < nc) {
-                grad[(int64_t)g * hy.p + woff + (int64_t)c * nh + n] = acc[0][c];
-                const float df = acc[0][c] - acc[1][c];
-                sq += (double)df * (double)df;
-            }
-    }
-    // bias gradient: block 0, one thread per class
-    if (blockIdx.x == 0 && tid < nc) {
-        float s0 = 0, s1 = 0;
-        for (int i = 0; i < mu; ++i) {
-            s0 += s_dzl[i * nc + tid];
-            s1 += s_dzl[(mu + i) * nc + tid];
-        }
-        grad[(int64_t)g * hy.p + boff + tid] = s0;
-        const float df = s0 - s1;
-        sq += (double)df * (double)df;
-    }
-    sq = wave_sum(sq);
-    if (tid % kWave == 0) s_red[tid / kWave] = sq;
-    __syncthreads();
-    if (tid == 0)
-        part_stat[(int64_t)g * n_stat + stat_off + blockIdx.x] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
-}
-
-// Bias gradient of a hidden layer from the transposed signal dZT [n][ldmu]: db[n] = sum_i dZ[i][n].
+// Bias gradient of a layer from the transposed signal dZT [n][ldmu]: db[n] = sum_i dZ[i][n].
 // grid: (ceil(n/4), G), block 256: one wave per hidden unit, both iterates.
 template <typename T>
 __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu, const T* __restrict__ dZT,
@@ -626,7 +500,7 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
             s[it] = wave_sum(s[it]);
         }
         if (lane == 0) {
-            grad[(int64_t)g * hy.p + boff + n] = s[0];
+            grad[(int64_t)g * hy.pstride + boff + n] = s[0];
             const float df = s[0] - s[1];
             sq = (double)df * (double)df;
         }
@@ -644,11 +518,10 @@ struct MlpWork {
     Layout lay{};
     bool bf16 = false;
     int esz = 4;
-    // per layer l (index l): activations A_l, AT_l (l = 1..L-1), signals dZ_l, dZT_l (l = 1..L-1)
+    // per layer l (index l): activations A_l, AT_l (l = 1..L-1), signals dZ_l, dZT_l (l = 1..L)
     void* Xg = nullptr; void* XgT = nullptr;
     void* A[GCADA_MAX_WIDTHS] = {};  void* AT[GCADA_MAX_WIDTHS] = {};
     void* dZ[GCADA_MAX_WIDTHS] = {}; void* dZT[GCADA_MAX_WIDTHS] = {};
-    float* dZL = nullptr;
     // weight copies per ring slot: Wc_l [slot][n_l][ld_{l-1}], WcT_l [slot][n_{l-1}][ld_l]
     void* Wc[GCADA_MAX_WIDTHS] = {}; void* WcT[GCADA_MAX_WIDTHS] = {};
     int64_t wc_slot[GCADA_MAX_WIDTHS] = {}, wct_slot[GCADA_MAX_WIDTHS] = {};
@@ -689,21 +562,22 @@ hipError_t mlp_plan(gcada_ctx* c)
             off += lay.n[l];
         }
     }
-    if (lay.n[lay.L] > kMaxClasses) return hipErrorInvalidValue;
+    if (lay.n[lay.L] > kBN) return hipErrorInvalidValue;
     const int mu = c->hy.mu, G = c->hy.G, L = lay.L, nslot = c->hy.D + 1;
     lay.ldmu = round_up(mu, 64);
     int maxld = lay.ldmu;
     for (int l = 0; l <= L; ++l) maxld = std::max(maxld, lay.ld[l]);
     w->slack = (size_t)128 * maxld * 4 + 256;
-    if ((size_t)2 * mu * lay.n[L] * sizeof(float) > 64 * 1024) return hipErrorInvalidValue;
     const size_t es = w->esz;
     hipError_t e;
     if ((e = walloc(w, &w->Xg, (size_t)G * mu * lay.ld[0] * es)) != hipSuccess) return e;
     if ((e = walloc(w, &w->XgT, (size_t)G * lay.n[0] * lay.ldmu * es)) != hipSuccess) return e;
-    for (int l = 1; l < L; ++l) {
+    for (int l = 1; l <= L; ++l) {
         const size_t rm = (size_t)2 * G * mu * lay.ld[l] * es, tr = (size_t)2 * G * lay.n[l] * lay.ldmu * es;
-        if ((e = walloc(w, &w->A[l], rm)) != hipSuccess) return e;
-        if ((e = walloc(w, &w->AT[l], tr)) != hipSuccess) return e;
+        if (l < L) {
+            if ((e = walloc(w, &w->A[l], rm)) != hipSuccess) return e;
+            if ((e = walloc(w, &w->AT[l], tr)) != hipSuccess) return e;
+        }
         if ((e = walloc(w, &w->dZ[l], rm)) != hipSuccess) return e;
         if ((e = walloc(w, &w->dZT[l], tr)) != hipSuccess) return e;
         w->wc_slot[l] = (int64_t)lay.n[l] * lay.ld[l - 1];
@@ -711,18 +585,16 @@ hipError_t mlp_plan(gcada_ctx* c)
         if ((e = walloc(w, &w->Wc[l], (size_t)nslot * w->wc_slot[l] * es)) != hipSuccess) return e;
         if ((e = walloc(w, &w->WcT[l], (size_t)nslot * w->wct_slot[l] * es)) != hipSuccess) return e;
     }
-    if ((e = walloc(w, (void**)&w->dZL, (size_t)2 * G * mu * lay.n[L] * 4)) != hipSuccess) return e;
-    // partial statistics: per layer the weight-gradient tiles (or head blocks) and bias blocks
+    // partial statistics: per layer the weight-gradient tiles and the bias blocks
     int ns = 0;
     for (int l = 1; l <= L; ++l) {
         w->stat_off_w[l] = ns;
-        if (l < L) ns += ((lay.n[l] + kBM - 1) / kBM) * ((lay.n[l - 1] + kBN - 1) / kBN);
-        else ns += (lay.n[l - 1] + 255) / 256;
+        ns += ((lay.n[l] + kBM - 1) / kBM) * ((lay.n[l - 1] + kBN - 1) / kBN);
         w->stat_off_b[l] = ns;
-        if (l < L) ns += (lay.n[l] + 3) / 4;
+        ns += (lay.n[l] + 3) / 4;
     }
     w->n_stat = ns;
-    w->n_loss = (mu + kHeadRows - 1) / kHeadRows;
+    w->n_loss = (mu + kBM - 1) / kBM;
     c->n_stat_part = std::max(c->n_stat_part, ns);
     c->n_loss_part = std::max(c->n_loss_part, w->n_loss);
     return hipSuccess;
@@ -742,7 +614,7 @@ static hipError_t refresh_slot_t(gcada_ctx* c, int slot, hipStream_t s)
     MlpWork* w = c->mlp;
     const Layout& lay = w->lay;
     const float* th = c->ring + (int64_t)slot * c->hy.pstride;
-    for (int l = 1; l < lay.L; ++l) {
+    for (int l = 1; l <= lay.L; ++l) {
         dim3 grid((lay.n[l - 1] + 63) / 64, (lay.n[l] + 63) / 64);
         mlp_weight_copy<T><<<grid, 256, 0, s>>>(th + lay.woff[l], lay.n[l], lay.n[l - 1], lay.ld[l - 1],
                                                  lay.ld[l], (T*)w->Wc[l] + (int64_t)slot * w->wc_slot[l],
@@ -777,6 +649,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
         (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_FWD>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
         (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_DA>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
         (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_DW>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_HEAD>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
         attr_set = true;
     }
     // 1. gather the minibatch rows (row-major and transposed)
@@ -789,8 +662,8 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     auto rm_g = [&](int l) { return (int64_t)mu * lay.ld[l]; };
     auto tr_it = [&](int l) { return (int64_t)G * lay.n[l] * lay.ldmu; };  // transposed
     auto tr_g = [&](int l) { return (int64_t)lay.n[l] * lay.ldmu; };
-    // 2. hidden layers, forward
-    for (int l = 1; l < L; ++l) {
+    // 2. forward: hidden layers (bias + ReLU), then the output layer with its loss
+    for (int l = 1; l <= L; ++l) {
         GemmArgs a{};
         a.hy = hy; a.tau = c->tau; a.G = G;
         a.M = mu; a.N = lay.n[l]; a.K = lay.n[l - 1];
@@ -798,42 +671,20 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
         else { a.P = w->A[l - 1]; a.p_it = rm_it(l - 1); a.p_g = rm_g(l - 1); a.ldp = lay.ld[l - 1]; }
         a.Q = w->Wc[l]; a.q_is_weight = 1; a.q_slot = w->wc_slot[l]; a.ldq = lay.ld[l - 1];
         a.ring = c->ring; a.boff = lay.boff[l];
-        a.O = w->A[l]; a.o_it = rm_it(l); a.o_g = rm_g(l); a.ldo = lay.ld[l];
-        a.OT = w->AT[l]; a.t_it = tr_it(l); a.t_g = tr_g(l); a.ldt = lay.ldmu;
         dim3 grid((a.N + kBN - 1) / kBN, (a.M + kBM - 1) / kBM, 2 * G);
-        mlp_gemm<T, EPI_FWD><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+        if (l < L) {
+            a.O = w->A[l]; a.o_it = rm_it(l); a.o_g = rm_g(l); a.ldo = lay.ld[l];
+            a.OT = w->AT[l]; a.t_it = tr_it(l); a.t_g = tr_g(l); a.ldt = lay.ldmu;
+            mlp_gemm<T, EPI_FWD><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+        } else {
+            a.O = w->dZ[L]; a.o_it = rm_it(L); a.o_g = rm_g(L); a.ldo = lay.ld[L];
+            a.OT = w->dZT[L]; a.t_it = tr_it(L); a.t_g = tr_g(L); a.ldt = lay.ldmu;
+            a.shards = c->d_shards; a.idx = idx; a.part_loss = c->part_loss;
+            mlp_gemm<T, EPI_HEAD><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+        }
     }
-    // 3. output layer: loss, dZ_L, and the signal of the last hidden layer
-    {
-        const int nh = lay.n[L - 1], ldh = lay.ld[L - 1];
-        const T* Ap = L == 1 ? (const T*)w->Xg : (const T*)w->A[L - 1];
-        const int64_t a_it = L == 1 ? 0 : rm_it(L - 1), a_g = rm_g(L - 1);
-        HeadArgs h{};
-        h.hy = hy; h.tau = c->tau; h.shards = c->d_shards; h.idx = idx; h.ring = c->ring;
-        h.woff = lay.woff[L]; h.boff = lay.boff[L];
-        h.nc = lay.n[L]; h.nh = nh; h.ldh = ldh; h.ldmu = lay.ldmu; h.G = G; h.has_hidden = L > 1 ? 1 : 0;
-        h.Aprev = Ap; h.a_it = a_it; h.a_g = a_g; h.dZL = w->dZL;
-        h.dZ = w->dZ[L - 1]; h.dZT = w->dZT[L - 1];
-        if (L > 1) { h.z_it = rm_it(L - 1); h.z_g = rm_g(L - 1); h.zt_it = tr_it(L - 1); h.zt_g = tr_g(L - 1); }
-        h.part_loss = c->part_loss;
-        const size_t wbytes = (size_t)lay.n[L] * nh * sizeof(float);
-        h.w_in_lds = wbytes <= (size_t)kHeadWLds ? 1 : 0;
-        const size_t hl = h.w_in_lds ? wbytes : 0;
-        dim3 grid(w->n_loss, 2 * G);
-        const int ncl = lay.n[L];
-        if (ncl <= 2) mlp_head<T, 2><<<grid, 256, hl, s>>>(h);
-        else if (ncl <= 4) mlp_head<T, 4><<<grid, 256, hl, s>>>(h);
-        else if (ncl <= 8) mlp_head<T, 8><<<grid, 256, hl, s>>>(h);
-        else if (ncl <= 16) mlp_head<T, 16><<<grid, 256, hl, s>>>(h);
-        else mlp_head<T, 32><<<grid, 256, hl, s>>>(h);
-        dim3 gg((nh + 255) / 256, G);
-        const size_t lds = (size_t)2 * mu * lay.n[L] * sizeof(float);
-        mlp_head_grad<T><<<gg, 256, lds, s>>>(hy, lay.n[L], nh, ldh, Ap, a_it, a_g, w->dZL, c->grad,
-                                               lay.woff[L], lay.boff[L], c->part_stat, w->n_stat,
-                                               w->stat_off_w[L], G);
-    }
-    // 4. hidden layers, backward
-    for (int l = L - 1; l >= 1; --l) {
+    // 3. backward, layer by layer
+    for (int l = L; l >= 1; --l) {
         {   // weight gradient of layer l, both iterates in one workgroup
             GemmArgs a{};
             a.hy = hy; a.tau = c->tau; a.G = G;

@@ -70,6 +70,16 @@ __device__ __forceinline__ double history_threshold(const Hyper& hy, const doubl
     return hy.c / (double)hy.D * v;
 }
 
+// grid: G blocks.  Adds one group's partial statistics in a fixed order (thread-strided, then a
+// tree) so that the server kernel finds a single number per group.
+__global__ __launch_bounds__(kSelBlock) void stat_reduce_kernel(const double* __restrict__ part_stat,
+                                                               int n_stat, double* __restrict__ out)
+{
+    __shared__ double s_tmp[kSelBlock / kWave];
+    const double t = block_sum_strided<kSelBlock>(part_stat + (int64_t)blockIdx.x * n_stat, n_stat, s_tmp);
+    if (threadIdx.x == 0) out[blockIdx.x] = t;
+}
+
 // One block, used when the partial statistics are too many for every update block to re-add.
 // Writes stat, mask, rhs, loss and the caller's outputs; the ages are advanced by the update.
 __global__ __launch_bounds__(kSelBlock) void select_kernel(
@@ -174,7 +184,7 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
     float* __restrict__ tn = a.ring + (int64_t)hy.nxt * hy.pstride;
 
     const int64_t j0 = ((int64_t)blockIdx.x * B + threadIdx.x) * VW;
-    const bool active = j0 < hy.p;
+    const bool active = j0 < hy.pstride;      // pads stay zero: their step is alpha*0/sqrt(eps)
     float ac[VW] = {}, hv[VW] = {}, vv[VW] = {}, tv[VW] = {}, nv[VW];
     if (active) {
         load_vec<VW>(a.agg + j0, ac);
@@ -256,7 +266,7 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
             float gg[4][VW], ll[4][VW];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int64_t o = (int64_t)s_sel[i + e] * hy.p + j0;
+                const int64_t o = (int64_t)s_sel[i + e] * hy.pstride + j0;
                 load_vec<VW>(a.grad + o, gg[e]);
                 load_vec<VW>(a.last + o, ll[e]);
             }
@@ -264,11 +274,11 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
             for (int e = 0; e < 4; ++e) {
 #pragma unroll
                 for (int q = 0; q < VW; ++q) ac[q] += gg[e][q] - ll[e][q];
-                store_vec<VW>(a.last + (int64_t)s_sel[i + e] * hy.p + j0, gg[e]);
+                store_vec<VW>(a.last + (int64_t)s_sel[i + e] * hy.pstride + j0, gg[e]);
             }
         }
         for (; i < nsel; ++i) {
-            const int64_t o = (int64_t)s_sel[i] * hy.p + j0;
+            const int64_t o = (int64_t)s_sel[i] * hy.pstride + j0;
             float gg[VW], ll[VW];
             load_vec<VW>(a.grad + o, gg);
             load_vec<VW>(a.last + o, ll);
@@ -363,9 +373,9 @@ constexpr int kBigBlock = 1024;
 
 hipError_t select_plan(gcada_ctx* c)
 {
-    const int vw = c->hy.p % 4 == 0 ? 4 : 1;
-    const int64_t per_block = (int64_t)kUpdBlock * vw;
-    c->n_epi_blocks = (int32_t)((c->hy.p + per_block - 1) / per_block);
+    // every per-parameter vector is padded to pstride (a multiple of 64): always four per thread
+    const int64_t per_block = (int64_t)kUpdBlock * 4;
+    c->n_epi_blocks = (int32_t)((c->hy.pstride + per_block - 1) / per_block);
     return hipSuccess;
 }
 
@@ -386,22 +396,23 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStre
     a.stat = c->stat; a.mask = c->mask; a.mask_out = mask_out; a.loss_out = loss_out;
     a.grad = c->grad; a.last = c->last; a.agg = c->agg; a.h = c->h; a.vhat = c->vhat;
     a.ring = c->ring; a.nring = c->nring; a.tau = c->tau; a.part_sq = c->part_sq; a.ctl = c->ctl;
-    const bool vec = c->hy.p % 4 == 0;
-    // every update block re-adds the partial statistics when that is cheap
-    const bool self_select = (int64_t)c->hy.G * c->n_stat_used + c->n_loss_used <= 4096;
-    if (!self_select)
-        select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(c->hy, c->part_stat, c->n_stat_used, c->part_loss,
-                                                c->n_loss_used, c->nring, c->tau, c->stat, c->mask,
-                                                c->ctl, mask_out, loss_out);
-    const int vw = vec ? 4 : 1;
-    if (c->hy.p <= (int64_t)kBigBlock * vw) {
-        // the whole parameter vector fits one block: no cross-block hand-over at the end
-        if (vec) launch_server<kBigBlock, 4>(self_select, 1, lds, s, a);
-        else launch_server<kBigBlock, 1>(self_select, 1, lds, s, a);
-    } else {
-        if (vec) launch_server<kUpdBlock, 4>(self_select, c->n_epi_blocks, lds, s, a);
-        else launch_server<kUpdBlock, 1>(self_select, c->n_epi_blocks, lds, s, a);
+    if (c->n_stat_used > 16) {
+        // many partials per group (MLP weight-gradient tiles): add them up with one block per group
+        stat_reduce_kernel<<<c->hy.G, kSelBlock, 0, s>>>(c->part_stat, c->n_stat_used, c->stat_sum);
+        a.part_stat = c->stat_sum;
+        a.n_stat = 1;
     }
+    // every update block re-adds the (remaining) partial statistics when that is cheap
+    const bool self_select = (int64_t)c->hy.G * a.n_stat + c->n_loss_used <= 4096;
+    if (!self_select)
+        select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(
+            c->hy, a.part_stat, a.n_stat, c->part_loss, c->n_loss_used, c->nring, c->tau,
+            c->stat, c->mask, c->ctl, mask_out, loss_out);
+    if (c->hy.pstride <= (int64_t)kBigBlock * 4)
+        // the whole parameter vector fits one block: no cross-block hand-over at the end
+        launch_server<kBigBlock, 4>(self_select, 1, lds, s, a);
+    else
+        launch_server<kUpdBlock, 4>(self_select, c->n_epi_blocks, lds, s, a);
     return hipGetLastError();
 }
 

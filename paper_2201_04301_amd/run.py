@@ -99,7 +99,8 @@ class Gcada:
         v = B.gcada_state(self.ctx)
         return dict(mask=_d2h(v.mask, self.G, np.uint8), loss=float(_d2h(v.loss, 1, np.float64)[0]),
                     stat=_d2h(v.stat, self.G, np.float64), rhs=float(_d2h(v.rhs, 1, np.float64)[0]),
-                    grad=_d2h(v.grad, self.G * self.p, np.float32).reshape(self.G, self.p))
+                    grad=_d2h(v.grad, self.G * v.grad_stride, np.float32)
+                    .reshape(self.G, v.grad_stride)[:, :self.p].copy())
 
     def get_state(self):
         p, G, D = self.p, self.G, self.D

@@ -86,12 +86,12 @@ def main():
     iters_s = K / dt
     grad_ms_avg = grad_ms / max(n_timed, 1)
     if w.model == "logreg":
-        # algorithmic bytes of the gradient stage per step: one read of the touched minibatch rows
+        # algorithmic bytes per launch of the timed kernel(s): one read of the touched minibatch rows
         alg_bytes = w.G * w.mu * w.widths[0] * 4
         achieved = alg_bytes / (grad_ms_avg * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                    "kernel": "gradient stage (lr_tile_kernel + lr_tile_reduce)",
+                    "kernel": B.gcada_timed_stage(gpu.ctx),
                     "avg_ms": round(grad_ms_avg, 5), "algorithmic_bytes": alg_bytes}
     else:
         # algorithmic flops of the gradient stage per step: forward + weight-gradient GEMMs of
@@ -104,7 +104,7 @@ def main():
         achieved = flops / (grad_ms_avg * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                     "frac": round(achieved / peak, 4), "traffic": None,
-                    "kernel": "gradient stage (mlp_gemm forward/backward/weight-gradient + output layer)",
+                    "kernel": B.gcada_timed_stage(gpu.ctx),
                     "avg_ms": round(grad_ms_avg, 5), "algorithmic_flops": flops}
 
     # modelled wall-clock / communication / computation of the paper's cost model (reported only)

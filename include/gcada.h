@@ -193,15 +193,22 @@ enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*
- * Diagnostics for benchmarks: time the gradient stage (step a1, the kernels that read the
- * minibatch) of the next `max_steps` calls of gcada_step with HIP events recorded on the step's
- * stream.  gcada_timing_begin creates the events (synchronous, allocates; call it outside the
+ * Diagnostics for benchmarks: time the dominant kernel(s) of step a1 -- the kernels that read
+ * the minibatch; see gcada_timed_stage for which -- in the next `max_steps` calls of gcada_step
+ * with HIP events recorded on the step's stream.  gcada_timing_begin creates the events (synchronous, allocates; call it outside the
  * measured loop); gcada_timing_end synchronises the device, returns the number of timed steps
  * and the sum of their gradient-stage durations in milliseconds, and releases the events.
  * Errors: GCADA_EINVAL (max_steps < 1), GCADA_EDEVICE.
  */
 int gcada_timing_begin(gcada_ctx* ctx, int32_t max_steps);
 int gcada_timing_end(gcada_ctx* ctx, int32_t* steps /*[host]*/, double* grad_ms /*[host]*/);
+
+/*
+ * Name of what gcada_timing_begin/end time for this context and its current shards, e.g.
+ * "lr_tile_kernel" (the single kernel that reads the minibatch), "lr_forward+lr_backward",
+ * "mlp gradient stage".  Returns a pointer valid until the next call on this context.
+ */
+const char* gcada_timed_stage(gcada_ctx* ctx);
 
 /* Message of the last error on this context ("" if none); NULL ctx: last gcada_create error. */
 const char* gcada_last_error(const gcada_ctx* ctx);

@@ -22,7 +22,7 @@ GCADA_OPT_SINGLE_PASS_LOGREG = 1
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
            "gcada_last_error", "gcada_version", "gcada_timing_begin", "gcada_timing_end",
-           "gcada_set_option"]
+           "gcada_set_option", "gcada_timed_stage"]
 
 
 class gcada_dims(C.Structure):
@@ -77,6 +77,8 @@ def _load():
                                    C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     L.gcada_set_option.restype = C.c_int
     L.gcada_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    L.gcada_timed_stage.restype = C.c_char_p
+    L.gcada_timed_stage.argtypes = [C.c_void_p]
     L.gcada_timing_begin.restype = C.c_int
     L.gcada_timing_begin.argtypes = [C.c_void_p, C.c_int32]
     L.gcada_timing_end.restype = C.c_int
@@ -174,3 +176,7 @@ def gcada_timing_end(ctx):
 
 def gcada_set_option(ctx, option: int, value: int):
     _check(lib.gcada_set_option(ctx, option, value), ctx)
+
+
+def gcada_timed_stage(ctx) -> str:
+    return (lib.gcada_timed_stage(ctx) or b"").decode()

@@ -262,12 +262,16 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     hipStream_t s = (hipStream_t)stream;
     set_iteration(ctx);
     const bool timed = (size_t)ctx->ev_used + 2 <= ctx->ev.size();
-    if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], s);
+    if (timed) {
+        (void)hipEventRecord(ctx->ev[ctx->ev_used], s);
+        ctx->ev_after = ctx->ev[ctx->ev_used + 1];
+    }
     hipError_t e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, idx, s)
                                                    : gcada::mlp_gradients(ctx, idx, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
     if (timed) {
-        (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], s);
+        if (ctx->ev_after) (void)hipEventRecord(ctx->ev_after, s);   // not recorded earlier
+        ctx->ev_after = nullptr;
         ctx->ev_used += 2;
     }
     if ((e = gcada::server_step(ctx, mask_out, loss_out, s)) != hipSuccess)
@@ -385,6 +389,15 @@ int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
         return GCADA_OK;
     }
     return fail(ctx, GCADA_EINVAL, "set_option: unknown option");
+}
+
+const char* gcada_timed_stage(gcada_ctx* ctx)
+{
+    if (!ctx) return "";
+    if (ctx->dims.model == GCADA_MLP) ctx->stage_name = "mlp gradient stage (gather, mlp_gemm forward/backward/weight-gradient, bias)";
+    else if (gcada::lr_tile_applies(ctx)) ctx->stage_name = "lr_tile_kernel";
+    else ctx->stage_name = "lr_forward+lr_backward";
+    return ctx->stage_name.c_str();
 }
 
 int gcada_timing_begin(gcada_ctx* ctx, int32_t max_steps)

@@ -98,6 +98,8 @@ struct gcada_ctx {
     // optional event timing of the gradient stage
     std::vector<hipEvent_t> ev;    // 2 per step: before / after
     int32_t ev_used = 0;
+    hipEvent_t ev_after = nullptr; // set by a gradient path that wants the 'after' event early
+    std::string stage_name;
 
     std::string err;
 };

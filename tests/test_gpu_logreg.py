@@ -136,3 +136,30 @@ def test_lr_single_pass_matches_general_kernels(par):
     np.testing.assert_array_equal(res[0][0], res[1][0])
     np.testing.assert_allclose(res[0][1], res[1][1], rtol=0, atol=2e-4 * np.abs(res[1][1]).max())
     np.testing.assert_allclose(res[0][2], res[1][2], rtol=2e-5)
+
+
+# ---- full-size configurations
+
+def test_lr_4k_full_size_teacher_forced(par):
+    # configuration 2 at full size: 16 shards of 65,536 x 4,096 fp32 (17.2 GB), the launch
+    # configuration bench.py times; teacher-forced against the oracle
+    w = CONFIGS["lr_4k"]
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 14
+    idx = make_indices(w, steps)
+    worst = par.teacher_forced(w, steps, Xs, ys, idx)
+    _say(worst)
+    assert worst["selected"] >= 2 * w.G
+
+
+def test_lr_64k_full_step_shape(par):
+    # configuration 4's step shape (G=32, mu=1024, d=65,536: 8.6 GB of rows touched per step) on
+    # shards of 2,048 rows; every group checked against the oracle, teacher-forced
+    w = scaled(CONFIGS["lr_64k"], rows=2048)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda", chunk_rows=1024)
+    steps = 3
+    idx = make_indices(w, steps)
+    worst = par.teacher_forced(w, steps, Xs, ys, idx)
+    _say(worst)

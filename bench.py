@@ -73,18 +73,14 @@ def main():
     dt = time.perf_counter() - t0
     m_host = masks[W:].cpu().numpy()
     l_host = losses[W:].cpu().numpy()
-    # pass 2: the same K steps of work again (the run simply continues), now with a HIP event
-    # before and after the gradient stage of every step, on the stream the kernels run on.  The
-    # event records themselves open a gap of several microseconds in the stream, which is why
-    # the throughput above is taken without them.
-    B.gcada_timing_begin(gpu.ctx, K)
-    torch.cuda.synchronize()
-    run_fast(W, W + K)
-    n_timed, grad_ms = B.gcada_timing_end(gpu.ctx)
+    # the dominant kernel(s) of the gradient stage alone, live: many launches back to back between
+    # two HIP events on the same stream (per-step event records would open gaps of a few
+    # microseconds in the stream, so the throughput above is taken without any)
+    reps = min(K, 400)           # a different minibatch per repetition (those of the timed steps)
+    grad_ms_avg = B.gcada_time_gradient_stage(gpu.ctx, base_idx + W * stride_idx, w.G * w.mu, reps, stream)
 
     ms_per_step = dt / K * 1e3
     iters_s = K / dt
-    grad_ms_avg = grad_ms / max(n_timed, 1)
     if w.model == "logreg":
         # algorithmic bytes per launch of the timed kernel(s): one read of the touched minibatch rows
         alg_bytes = w.G * w.mu * w.widths[0] * 4

@@ -193,18 +193,21 @@ enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*
- * Diagnostics for benchmarks: time the dominant kernel(s) of step a1 -- the kernels that read
- * the minibatch; see gcada_timed_stage for which -- in the next `max_steps` calls of gcada_step
- * with HIP events recorded on the step's stream.  gcada_timing_begin creates the events (synchronous, allocates; call it outside the
- * measured loop); gcada_timing_end synchronises the device, returns the number of timed steps
- * and the sum of their gradient-stage durations in milliseconds, and releases the events.
- * Errors: GCADA_EINVAL (max_steps < 1), GCADA_EDEVICE.
+ * Diagnostics for benchmarks: run only the dominant kernel(s) of step a1 -- the kernels that
+ * read the minibatch; gcada_timed_stage names them -- `reps` times back to back on `stream`
+ * between two HIP events; repetition r uses the minibatch idx + r*idx_stride (G*mu ids each, as in
+ * gcada_step; give distinct minibatches, or the rows are served from cache after the first
+ * repetition; idx may be NULL for the cyclic window).  These kernels write only
+ * scratch and the fresh-gradient rows, so the run's state (theta, moments, aggregate, stored
+ * gradients, ages, history, k) is unchanged.  Synchronises the stream; returns the mean
+ * duration per repetition in milliseconds.  Creates and destroys two events (not for use
+ * under graph capture).  Errors: GCADA_EINVAL (reps < 1), GCADA_ESTATE, GCADA_EDEVICE.
  */
-int gcada_timing_begin(gcada_ctx* ctx, int32_t max_steps);
-int gcada_timing_end(gcada_ctx* ctx, int32_t* steps /*[host]*/, double* grad_ms /*[host]*/);
+int gcada_time_gradient_stage(gcada_ctx* ctx, const int32_t* idx, int64_t idx_stride, int32_t reps,
+                              void* stream, double* ms_per_rep /*[host]*/);
 
 /*
- * Name of what gcada_timing_begin/end time for this context and its current shards, e.g.
+ * Name of what gcada_time_gradient_stage times for this context and its current shards, e.g.
  * "lr_tile_kernel" (the single kernel that reads the minibatch), "lr_forward+lr_backward",
  * "mlp gradient stage".  Returns a pointer valid until the next call on this context.
  */

@@ -21,8 +21,8 @@ GCADA_OPT_SINGLE_PASS_LOGREG = 1
 
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
-           "gcada_last_error", "gcada_version", "gcada_timing_begin", "gcada_timing_end",
-           "gcada_set_option", "gcada_timed_stage"]
+           "gcada_last_error", "gcada_version", "gcada_time_gradient_stage", "gcada_set_option",
+           "gcada_timed_stage"]
 
 
 class gcada_dims(C.Structure):
@@ -79,10 +79,9 @@ def _load():
     L.gcada_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.gcada_timed_stage.restype = C.c_char_p
     L.gcada_timed_stage.argtypes = [C.c_void_p]
-    L.gcada_timing_begin.restype = C.c_int
-    L.gcada_timing_begin.argtypes = [C.c_void_p, C.c_int32]
-    L.gcada_timing_end.restype = C.c_int
-    L.gcada_timing_end.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+    L.gcada_time_gradient_stage.restype = C.c_int
+    L.gcada_time_gradient_stage.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
+                                            C.POINTER(C.c_double)]
     L.gcada_last_error.restype = C.c_char_p
     L.gcada_last_error.argtypes = [C.c_void_p]
     L.gcada_version.restype = C.c_char_p
@@ -164,14 +163,10 @@ def gcada_last_error(ctx=None) -> str:
     return (lib.gcada_last_error(ctx) or b"").decode()
 
 
-def gcada_timing_begin(ctx, max_steps: int):
-    _check(lib.gcada_timing_begin(ctx, max_steps), ctx)
-
-
-def gcada_timing_end(ctx):
-    n, ms = C.c_int32(), C.c_double()
-    _check(lib.gcada_timing_end(ctx, C.byref(n), C.byref(ms)), ctx)
-    return n.value, ms.value
+def gcada_time_gradient_stage(ctx, idx_ptr, idx_stride: int, reps: int, stream_ptr=None) -> float:
+    ms = C.c_double()
+    _check(lib.gcada_time_gradient_stage(ctx, idx_ptr, idx_stride, reps, stream_ptr, C.byref(ms)), ctx)
+    return ms.value
 
 
 def gcada_set_option(ctx, option: int, value: int):

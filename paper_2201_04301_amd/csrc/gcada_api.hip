@@ -66,8 +66,6 @@ void free_all(gcada_ctx* c)
     if (!c) return;
     gcada::mlp_free(c);
     gcada::lr_tile_free(c);
-    for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
-    c->ev.clear();
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->grad, c->last, c->tau,
                     c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat, c->stat_sum,
                     c->part_sq};
@@ -261,19 +259,9 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
         if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "step: a group has no shard");
     hipStream_t s = (hipStream_t)stream;
     set_iteration(ctx);
-    const bool timed = (size_t)ctx->ev_used + 2 <= ctx->ev.size();
-    if (timed) {
-        (void)hipEventRecord(ctx->ev[ctx->ev_used], s);
-        ctx->ev_after = ctx->ev[ctx->ev_used + 1];
-    }
     hipError_t e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, idx, s)
                                                    : gcada::mlp_gradients(ctx, idx, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
-    if (timed) {
-        if (ctx->ev_after) (void)hipEventRecord(ctx->ev_after, s);   // not recorded earlier
-        ctx->ev_after = nullptr;
-        ctx->ev_used += 2;
-    }
     if ((e = gcada::server_step(ctx, mask_out, loss_out, s)) != hipSuccess)
         return fail_hip(ctx, e, "server kernels");
     if (ctx->dims.model == GCADA_MLP) {
@@ -400,41 +388,39 @@ const char* gcada_timed_stage(gcada_ctx* ctx)
     return ctx->stage_name.c_str();
 }
 
-int gcada_timing_begin(gcada_ctx* ctx, int32_t max_steps)
+int gcada_time_gradient_stage(gcada_ctx* ctx, const int32_t* idx, int64_t idx_stride, int32_t reps,
+                              void* stream, double* ms_per_rep)
 try {
     if (!ctx) return GCADA_EINVAL;
-    if (max_steps < 1) return fail(ctx, GCADA_EINVAL, "timing_begin: max_steps must be >= 1");
-    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
-    ctx->ev.clear();
-    ctx->ev_used = 0;
-    ctx->ev.reserve((size_t)2 * max_steps);
-    for (int i = 0; i < 2 * max_steps; ++i) {
-        hipEvent_t e;
-        HIP_TRY(ctx, hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
-        ctx->ev.push_back(e);
+    if (reps < 1 || !ms_per_rep) return fail(ctx, GCADA_EINVAL, "time_gradient_stage: reps >= 1 and an output are required");
+    if (!ctx->theta_set) return fail(ctx, GCADA_ESTATE, "time_gradient_stage: gcada_set_theta has not been called");
+    for (int g = 0; g < ctx->hy.G; ++g)
+        if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "time_gradient_stage: a group has no shard");
+    hipStream_t s = (hipStream_t)stream;
+    set_iteration(ctx);
+    hipEvent_t e0, e1;
+    HIP_TRY(ctx, hipEventCreate(&e0));
+    HIP_TRY(ctx, hipEventCreate(&e1));
+    ctx->dominant_only = true;
+    hipError_t e = hipEventRecord(e0, s);
+    for (int r = 0; r < reps && e == hipSuccess; ++r)
+    {
+        const int32_t* ir = idx ? idx + (int64_t)r * idx_stride : nullptr;
+        e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, ir, s)
+                                            : gcada::mlp_gradients(ctx, ir, s);
     }
+    ctx->dominant_only = false;
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail_hip(ctx, e, "time_gradient_stage");
+    *ms_per_rep = (double)ms / reps;
     return GCADA_OK;
 } catch (...) {
-    return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_timing_begin");
-}
-
-int gcada_timing_end(gcada_ctx* ctx, int32_t* steps, double* grad_ms)
-{
-    if (!ctx) return GCADA_EINVAL;
-    HIP_TRY(ctx, hipDeviceSynchronize());
-    if (int rc = check_device_flag(ctx)) return rc;
-    double total = 0;
-    for (int i = 0; i + 1 < ctx->ev_used; i += 2) {
-        float ms = 0;
-        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]));
-        total += ms;
-    }
-    if (steps) *steps = ctx->ev_used / 2;
-    if (grad_ms) *grad_ms = total;
-    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
-    ctx->ev.clear();
-    ctx->ev_used = 0;
-    return GCADA_OK;
+    return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_time_gradient_stage");
 }
 
 int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask, const double* T,

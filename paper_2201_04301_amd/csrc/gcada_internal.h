@@ -95,10 +95,7 @@ struct gcada_ctx {
     gcada::LrTilePlan* lr_tiles = nullptr;
     bool allow_single_pass = true;
 
-    // optional event timing of the gradient stage
-    std::vector<hipEvent_t> ev;    // 2 per step: before / after
-    int32_t ev_used = 0;
-    hipEvent_t ev_after = nullptr; // set by a gradient path that wants the 'after' event early
+    bool dominant_only = false;    // benchmark diagnostic: launch only the dominant gradient kernel(s)
     std::string stage_name;
 
     std::string err;

@@ -132,8 +132,12 @@ typedef struct gcada_state_view {
     float*   h;              /* [device] p                                                    */
     float*   vhat;           /* [device] p                                                    */
     float*   agg;            /* [device] p: lazily aggregated gradient                        */
-    float*   grad;           /* [device] G rows of grad_stride: fresh gradients of the last step */
-    float*   last;           /* [device] G rows of grad_stride: gradient each group uploaded last */
+    float*   gbuf;           /* [device] two halves of G rows of grad_stride floats.  Row
+                                (which[g]*G + g) holds the gradient group g uploaded last; a step
+                                writes group g's fresh gradient to the other half's row g and an
+                                upload flips which[g].  So after a step the fresh gradient of g is
+                                row which[g] if mask[g], else the other half's row              */
+    int32_t* which;          /* [device] G, each 0 or 1                                        */
     int32_t* tau;            /* [device] G ages                                               */
     double*  dtheta_sq;      /* [device] D: ||theta^{j+1}-theta^j||^2 stored at index j mod D */
     double*  stat;           /* [device] G: stat_g of the last step                           */

@@ -35,7 +35,7 @@ class gcada_state_view(C.Structure):
                 ("k", C.c_int64), ("slot_stride", C.c_int64), ("grad_stride", C.c_int64),
                 ("cur_slot", C.c_int32),
                 ("theta_ring", C.c_void_p), ("h", C.c_void_p), ("vhat", C.c_void_p),
-                ("agg", C.c_void_p), ("grad", C.c_void_p), ("last", C.c_void_p),
+                ("agg", C.c_void_p), ("gbuf", C.c_void_p), ("which", C.c_void_p),
                 ("tau", C.c_void_p), ("dtheta_sq", C.c_void_p), ("stat", C.c_void_p),
                 ("rhs", C.c_void_p), ("mask", C.c_void_p), ("loss", C.c_void_p)]
 

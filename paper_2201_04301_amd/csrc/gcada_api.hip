@@ -66,7 +66,7 @@ void free_all(gcada_ctx* c)
     if (!c) return;
     gcada::mlp_free(c);
     gcada::lr_tile_free(c);
-    void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->grad, c->last, c->tau,
+    void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->gbuf, c->which, c->tau,
                     c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat, c->stat_sum,
                     c->part_sq};
     for (void* p : ptrs)
@@ -141,8 +141,8 @@ try {
     if ((e = dalloc(&x->h, p)) != hipSuccess) return bail(e, "alloc h");
     if ((e = dalloc(&x->vhat, p)) != hipSuccess) return bail(e, "alloc vhat");
     if ((e = dalloc(&x->agg, p)) != hipSuccess) return bail(e, "alloc aggregate");
-    if ((e = dalloc(&x->grad, Gp)) != hipSuccess) return bail(e, "alloc gradients");
-    if ((e = dalloc(&x->last, Gp)) != hipSuccess) return bail(e, "alloc stored gradients");
+    if ((e = dalloc(&x->gbuf, 2 * Gp)) != hipSuccess) return bail(e, "alloc gradients");
+    if ((e = dalloc(&x->which, (size_t)G)) != hipSuccess) return bail(e, "alloc gradient index");
     if ((e = dalloc(&x->tau, (size_t)G)) != hipSuccess) return bail(e, "alloc ages");
     if ((e = dalloc(&x->nring, (size_t)D)) != hipSuccess) return bail(e, "alloc history");
     if ((e = dalloc(&x->stat, (size_t)G)) != hipSuccess) return bail(e, "alloc stat");
@@ -214,8 +214,8 @@ static int reset_run(gcada_ctx* ctx, const float* theta0_any)
     HIP_TRY(ctx, hipMemset(ctx->h, 0, p * 4));
     HIP_TRY(ctx, hipMemset(ctx->vhat, 0, p * 4));
     HIP_TRY(ctx, hipMemset(ctx->agg, 0, p * 4));
-    HIP_TRY(ctx, hipMemset(ctx->grad, 0, Gp * 4));
-    HIP_TRY(ctx, hipMemset(ctx->last, 0, Gp * 4));
+    HIP_TRY(ctx, hipMemset(ctx->gbuf, 0, 2 * Gp * 4));
+    HIP_TRY(ctx, hipMemset(ctx->which, 0, (size_t)hy.G * 4));
     HIP_TRY(ctx, hipMemset(ctx->nring, 0, (size_t)hy.D * 8));
     HIP_TRY(ctx, hipMemset(ctx->stat, 0, (size_t)hy.G * 8));
     HIP_TRY(ctx, hipMemset(ctx->mask, 0, (size_t)hy.G));
@@ -284,7 +284,7 @@ int gcada_state(gcada_ctx* ctx, gcada_state_view* out)
     v.grad_stride = ctx->hy.pstride;
     v.cur_slot = (int32_t)(ctx->k % (ctx->hy.D + 1));
     v.theta_ring = ctx->ring; v.h = ctx->h; v.vhat = ctx->vhat; v.agg = ctx->agg;
-    v.grad = ctx->grad; v.last = ctx->last; v.tau = ctx->tau; v.dtheta_sq = ctx->nring;
+    v.gbuf = ctx->gbuf; v.which = ctx->which; v.tau = ctx->tau; v.dtheta_sq = ctx->nring;
     v.stat = ctx->stat; v.rhs = &ctx->ctl->rhs; v.mask = ctx->mask; v.loss = &ctx->ctl->loss;
     *out = v;
     return GCADA_OK;
@@ -313,9 +313,14 @@ try {
             HIP_TRY(ctx, hipMemcpy(out->theta_stale + (size_t)g * p, ctx->ring + (size_t)slot * hy.pstride,
                                    p * 4, hipMemcpyDeviceToHost));
         }
-    if (out->last)
-        HIP_TRY(ctx, hipMemcpy2D(out->last, p * 4, ctx->last, (size_t)hy.pstride * 4, p * 4, hy.G,
-                                 hipMemcpyDeviceToHost));
+    if (out->last) {
+        std::vector<int32_t> wh(hy.G);
+        HIP_TRY(ctx, hipMemcpy(wh.data(), ctx->which, (size_t)hy.G * 4, hipMemcpyDeviceToHost));
+        for (int g = 0; g < hy.G; ++g)
+            HIP_TRY(ctx, hipMemcpy(out->last + (size_t)g * p,
+                                   ctx->gbuf + ((size_t)wh[g] * hy.G + g) * hy.pstride, p * 4,
+                                   hipMemcpyDeviceToHost));
+    }
     if (out->tau) std::memcpy(out->tau, tau.data(), (size_t)hy.G * 4);
     if (out->dtheta_sq)
         HIP_TRY(ctx, hipMemcpy(out->dtheta_sq, ctx->nring, (size_t)hy.D * 8, hipMemcpyDeviceToHost));
@@ -354,7 +359,9 @@ try {
     HIP_TRY(ctx, hipMemcpy(ctx->h, in->h, p * 4, hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->vhat, in->vhat, p * 4, hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->agg, in->agg, p * 4, hipMemcpyHostToDevice));
-    HIP_TRY(ctx, hipMemcpy2D(ctx->last, (size_t)hy.pstride * 4, in->last, p * 4, p * 4, hy.G,
+    // stored gradients go to half 0 of gbuf
+    HIP_TRY(ctx, hipMemset(ctx->which, 0, (size_t)hy.G * 4));
+    HIP_TRY(ctx, hipMemcpy2D(ctx->gbuf, (size_t)hy.pstride * 4, in->last, p * 4, p * 4, hy.G,
                              hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->tau, in->tau, (size_t)hy.G * 4, hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->nring, in->dtheta_sq, (size_t)hy.D * 8, hipMemcpyHostToDevice));

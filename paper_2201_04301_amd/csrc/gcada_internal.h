@@ -49,6 +49,13 @@ __host__ __device__ inline int stale_slot_of(const Hyper& hy, int tau_g)
     return s < 0 ? s + hy.D + 1 : s;
 }
 
+// Row of gbuf the fresh gradient of group g is written to in this step (the half that does not
+// hold the gradient the group uploaded last); an upload then only flips which[g].
+__device__ inline float* fresh_row(float* gbuf, const int32_t* which, const Hyper& hy, int g)
+{
+    return gbuf + ((int64_t)(1 - which[g]) * hy.G + g) * hy.pstride;
+}
+
 struct MlpWork;       // MLP activations and compute copies (mlp_kernels.hip)
 struct LrTilePlan;    // single-pass logistic path (lr_tiles.hip)
 
@@ -70,8 +77,9 @@ struct gcada_ctx {
     float* h = nullptr;
     float* vhat = nullptr;
     float* agg = nullptr;
-    float* grad = nullptr;         // G x p
-    float* last = nullptr;         // G x p
+    float* gbuf = nullptr;         // 2 halves x G rows x pstride: gradients (see which)
+    int32_t* which = nullptr;      // G: half of gbuf that holds group g's last uploaded gradient;
+                                   //    the fresh gradient of a step is written to the other half
     int32_t* tau = nullptr;        // G
     double* nring = nullptr;       // D
     double* stat = nullptr;        // G

@@ -157,7 +157,7 @@ template <bool VEC>
 __global__ __launch_bounds__(kBwdWaves* kWave) void lr_backward(
     const ShardDesc* __restrict__ shards, const int32_t* __restrict__ idx,
     const float* __restrict__ ring, const int32_t* __restrict__ tau, const Ctl* __restrict__ ctl,
-    Hyper hy, const float* __restrict__ res, float* __restrict__ grad,
+    Hyper hy, const float* __restrict__ res, float* __restrict__ gbuf, const int32_t* __restrict__ which,
     double* __restrict__ part_stat)
 {
     extern __shared__ float2 s_res[];                       // mu entries
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kBwdWaves* kWave) void lr_backward(
                         gv[q] += ml * t;
                         sv[q] += ml * (t - ts[j + q]);
                     }
-                    grad[(int64_t)g * hy.pstride + j + q] = gv[q];
+                    fresh_row(gbuf, which, hy, g)[j + q] = gv[q];
                     sq += (double)sv[q] * (double)sv[q];
                 }
             }
@@ -281,14 +281,14 @@ hipError_t lr_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
         c->n_stat_used = (d + kBwdCols - 1) / kBwdCols;
         dim3 gb(c->n_stat_used, hy.G), bb(kBwdWaves * kWave);
         lr_backward<true><<<gb, bb, sizeof(float2) * hy.mu, s>>>(
-            c->d_shards, idx, c->ring, c->tau, c->ctl, hy, c->res, c->grad, c->part_stat);
+            c->d_shards, idx, c->ring, c->tau, c->ctl, hy, c->res, c->gbuf, c->which, c->part_stat);
     } else {
         lr_forward<false><<<gf, bf, 0, s>>>(c->d_shards, idx, c->ring, c->tau, c->ctl, hy, c->res,
                                              c->part_loss);
         c->n_stat_used = (d + kWave - 1) / kWave;
         dim3 gb(c->n_stat_used, hy.G), bb(kBwdWaves * kWave);
         lr_backward<false><<<gb, bb, sizeof(float2) * hy.mu, s>>>(
-            c->d_shards, idx, c->ring, c->tau, c->ctl, hy, c->res, c->grad, c->part_stat);
+            c->d_shards, idx, c->ring, c->tau, c->ctl, hy, c->res, c->gbuf, c->which, c->part_stat);
     }
     return hipGetLastError();
 }

@@ -216,7 +216,8 @@ constexpr int kRedBlock = 256;
 // l2 terms, writes the group's gradient and one partial squared norm per block.
 __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
     Hyper hy, const float* __restrict__ part_g, const float* __restrict__ part_s, int RB,
-    const float* __restrict__ ring, const int32_t* __restrict__ tau, float* __restrict__ grad,
+    const float* __restrict__ ring, const int32_t* __restrict__ tau, float* __restrict__ gbuf,
+    const int32_t* __restrict__ which,
     double* __restrict__ part_stat)
 {
     __shared__ double s_red[kRedBlock / kWave];
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
             as.x += ml * (t.x - u.x); as.y += ml * (t.y - u.y);
             as.z += ml * (t.z - u.z); as.w += ml * (t.w - u.w);
         }
-        *(float4*)(grad + (int64_t)g * hy.pstride + j) = ag;
+        *(float4*)(fresh_row(gbuf, which, hy, g) + j) = ag;
         sq = (double)as.x * as.x + (double)as.y * as.y + (double)as.z * as.z + (double)as.w * as.w;
     }
     sq = wave_sum(sq);
@@ -344,7 +345,7 @@ hipError_t lr_tile_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
     if (c->dominant_only) return hipSuccess;      // benchmark diagnostic: the tile kernel alone
     dim3 gr(pl->n_stat, c->hy.G);
     lr_tile_reduce<<<gr, kRedBlock, 0, s>>>(c->hy, pl->part_g, pl->part_s, pl->RB, c->ring, c->tau,
-                                             c->grad, c->part_stat);
+                                             c->gbuf, c->which, c->part_stat);
     c->n_stat_used = pl->n_stat;
     c->n_loss_used = c->hy.G * pl->RB;
     return hipGetLastError();

@@ -111,7 +111,7 @@ struct GemmArgs {
     void* O; int64_t o_it, o_g; int ldo;
     void* OT; int64_t t_it, t_g; int ldt;
     // DW : fresh gradient block -> grad[g*p + goff + m*N + n]; partial ||fresh-stale||^2
-    float* grad; int64_t goff;
+    float* gbuf; const int32_t* which; int64_t goff;
     double* part_stat; int n_stat; int stat_off;
     int G;
     // HEAD
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm(GemmArgs a)
     const int cl = lane & 31, rh = (lane >> 5) * 4;
     if constexpr (EPI == EPI_DW) {
         double sq = 0;
-        float* gb = a.grad + (int64_t)g * hy.pstride + a.goff;
+        float* gb = fresh_row(a.gbuf, a.which, hy, g) + a.goff;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -484,7 +484,8 @@ __global__ __launch_bounds__(256) void mlp_weight_copy(const float* __restrict__
 // grid: (ceil(n/4), G), block 256: one wave per hidden unit, both iterates.
 template <typename T>
 __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu, const T* __restrict__ dZT,
-                                                     int64_t zt_it, int64_t zt_g, float* __restrict__ grad,
+                                                     int64_t zt_it, int64_t zt_g, float* __restrict__ gbuf,
+                                                     const int32_t* __restrict__ which,
                                                      int64_t boff, double* __restrict__ part_stat, int n_stat,
                                                      int stat_off)
 {
@@ -500,7 +501,7 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
             s[it] = wave_sum(s[it]);
         }
         if (lane == 0) {
-            grad[(int64_t)g * hy.pstride + boff + n] = s[0];
+            fresh_row(gbuf, which, hy, g)[boff + n] = s[0];
             const float df = s[0] - s[1];
             sq = (double)df * (double)df;
         }
@@ -693,7 +694,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             if (l == 1) { a.Q = w->XgT; a.q_it = 0; a.q_g = tr_g(0); }
             else { a.Q = w->AT[l - 1]; a.q_it = tr_it(l - 1); a.q_g = tr_g(l - 1); }
             a.ldq = lay.ldmu; a.q_is_weight = 0;
-            a.grad = c->grad; a.goff = lay.woff[l];
+            a.gbuf = c->gbuf; a.which = c->which; a.goff = lay.woff[l];
             a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[l];
             dim3 grid((a.N + kBN - 1) / kBN, (a.M + kBM - 1) / kBM, G);
             mlp_gemm<T, EPI_DW><<<grid, kGemmThreads, kGemmLds, s>>>(a);
@@ -701,7 +702,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
         {
             dim3 grid((lay.n[l] + 3) / 4, G);
             mlp_bias_grad<T><<<grid, 256, 0, s>>>(hy, lay.n[l], lay.ldmu, (const T*)w->dZT[l], tr_it(l),
-                                                   tr_g(l), c->grad, lay.boff[l], c->part_stat, w->n_stat,
+                                                   tr_g(l), c->gbuf, c->which, lay.boff[l], c->part_stat, w->n_stat,
                                                    w->stat_off_b[l]);
         }
         if (l > 1) {   // signal of layer l-1: dZ_{l-1} = (dZ_l W_l) * [a_{l-1} > 0]

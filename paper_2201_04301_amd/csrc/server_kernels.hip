@@ -142,8 +142,8 @@ struct ServerArgs {
     uint8_t* mask;             // written (SELECT) or read (!SELECT)
     uint8_t* mask_out;
     float* loss_out;
-    const float* grad;
-    float* last;
+    const float* gbuf;         // 2 halves x G rows x pstride
+    int32_t* which;            // G: half holding the last uploaded gradient (flipped on upload)
     float* agg;
     float* h;
     float* vhat;
@@ -176,7 +176,8 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
     const Hyper& hy = a.hy;
     double* s_stat = s_dyn;                                   // G
     int* s_sel = (int*)(s_dyn + hy.G);                        // G
-    uint8_t* s_mask = (uint8_t*)(s_sel + hy.G);               // G
+    int* s_which = s_sel + hy.G;                              // G
+    uint8_t* s_mask = (uint8_t*)(s_which + hy.G);             // G
     Ctl* ctl = a.ctl;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     constexpr int NW = B / kWave;
@@ -195,6 +196,7 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
     const bool pub = SELECT && blockIdx.x == 0;
     int my_tau = 0;
     if ((int)threadIdx.x < hy.G) my_tau = a.tau[threadIdx.x];      // groups beyond B are read below
+    for (int g = threadIdx.x; g < hy.G; g += B) s_which[g] = a.which[g];
     if constexpr (SELECT) {
         // statistics: one wave per group, partials added in lane-strided order then butterfly
         for (int g = wave; g < hy.G; g += NW) {
@@ -261,30 +263,29 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
     const float ob1 = (float)(1.0 - hy.beta1), ob2 = (float)(1.0 - hy.beta2);
     double sq = 0, tsq = 0;
     if (active) {
+        // innovation of a selected group: its fresh row minus the row it uploaded last; nothing
+        // is copied -- the finishing block flips which[g] instead
         int i = 0;
         for (; i + 4 <= nsel; i += 4) {              // four groups' loads in flight, added in order
             float gg[4][VW], ll[4][VW];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int64_t o = (int64_t)s_sel[i + e] * hy.pstride + j0;
-                load_vec<VW>(a.grad + o, gg[e]);
-                load_vec<VW>(a.last + o, ll[e]);
+                const int g = s_sel[i + e], wl = s_which[g];
+                load_vec<VW>(a.gbuf + ((int64_t)(1 - wl) * hy.G + g) * hy.pstride + j0, gg[e]);
+                load_vec<VW>(a.gbuf + ((int64_t)wl * hy.G + g) * hy.pstride + j0, ll[e]);
             }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
                 for (int q = 0; q < VW; ++q) ac[q] += gg[e][q] - ll[e][q];
-                store_vec<VW>(a.last + (int64_t)s_sel[i + e] * hy.pstride + j0, gg[e]);
-            }
         }
         for (; i < nsel; ++i) {
-            const int64_t o = (int64_t)s_sel[i] * hy.pstride + j0;
+            const int g = s_sel[i], wl = s_which[g];
             float gg[VW], ll[VW];
-            load_vec<VW>(a.grad + o, gg);
-            load_vec<VW>(a.last + o, ll);
+            load_vec<VW>(a.gbuf + ((int64_t)(1 - wl) * hy.G + g) * hy.pstride + j0, gg);
+            load_vec<VW>(a.gbuf + ((int64_t)wl * hy.G + g) * hy.pstride + j0, ll);
 #pragma unroll
             for (int q = 0; q < VW; ++q) ac[q] += gg[q] - ll[q];
-            store_vec<VW>(a.last + o, gg);
         }
 #pragma unroll
         for (int q = 0; q < VW; ++q) {
@@ -346,6 +347,7 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
     for (int g = threadIdx.x; g < hy.G; g += B) {
         const int t = g < B ? my_tau : a.tau[g];
         a.tau[g] = s_mask[g] ? 1 : t + 1;
+        if (s_mask[g]) a.which[g] = 1 - s_which[g];          // the fresh row becomes the stored one
     }
 }
 
@@ -389,12 +391,12 @@ static void launch_server(bool self_select, int blocks, size_t lds, hipStream_t 
 // Selection + masked innovation sum + server update + history for one iteration.
 hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s)
 {
-    const size_t lds = ((size_t)c->hy.G * 13 + 15) / 16 * 16;   // doubles, ints, bytes per group
+    const size_t lds = ((size_t)c->hy.G * 17 + 15) / 16 * 16;   // a double, two ints, a byte per group
     ServerArgs a{};
     a.hy = c->hy; a.part_stat = c->part_stat; a.n_stat = c->n_stat_used;
     a.part_loss = c->part_loss; a.n_loss_total = c->n_loss_used;
     a.stat = c->stat; a.mask = c->mask; a.mask_out = mask_out; a.loss_out = loss_out;
-    a.grad = c->grad; a.last = c->last; a.agg = c->agg; a.h = c->h; a.vhat = c->vhat;
+    a.gbuf = c->gbuf; a.which = c->which; a.agg = c->agg; a.h = c->h; a.vhat = c->vhat;
     a.ring = c->ring; a.nring = c->nring; a.tau = c->tau; a.part_sq = c->part_sq; a.ctl = c->ctl;
     if (c->n_stat_used > 16) {
         // many partials per group (MLP weight-gradient tiles): add them up with one block per group

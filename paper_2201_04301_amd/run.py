@@ -97,10 +97,16 @@ class Gcada:
         """Synchronise and copy the last step's mask, loss, stat, rhs and fresh gradients."""
         torch.cuda.synchronize()
         v = B.gcada_state(self.ctx)
-        return dict(mask=_d2h(v.mask, self.G, np.uint8), loss=float(_d2h(v.loss, 1, np.float64)[0]),
+        mask = _d2h(v.mask, self.G, np.uint8)
+        which = _d2h(v.which, self.G, np.int32)
+        # the fresh gradient of the last step: the stored row if the group uploaded, else the other
+        half = np.where(mask != 0, which, 1 - which)
+        grad = np.empty((self.G, self.p), np.float32)
+        for g in range(self.G):
+            grad[g] = _d2h(v.gbuf + 4 * (int(half[g]) * self.G + g) * v.grad_stride, self.p, np.float32)
+        return dict(mask=mask, loss=float(_d2h(v.loss, 1, np.float64)[0]),
                     stat=_d2h(v.stat, self.G, np.float64), rhs=float(_d2h(v.rhs, 1, np.float64)[0]),
-                    grad=_d2h(v.grad, self.G * v.grad_stride, np.float32)
-                    .reshape(self.G, v.grad_stride)[:, :self.p].copy())
+                    grad=grad)
 
     def get_state(self):
         p, G, D = self.p, self.G, self.D

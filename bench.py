@@ -17,6 +17,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
+# HBM bytes per launch of the timed kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
+# the copy calibration (profiles/lr_4k_hbm_traffic.md).  Valid for the kernel named; set to None
+# when that kernel changes.
+MEASURED_TRAFFIC = {"lr_4k": ("lr_tile_kernel", 68.1e6 + 8.4e6)}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -26,6 +31,9 @@ def main():
     ap.add_argument("--workload", default="lr_4k")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark: copy a buffer of this many MiB five times with a "
+                         "plain device copy kernel (to calibrate rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -38,6 +46,16 @@ def main():
     from paper_2201_04301_amd import Gcada, binding as B
 
     torch.cuda.set_device(0)
+    if args.copy_calibration > 0:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n * 4, "bytes_written": n * 4, "copies": 5}))
+        return
     w = CONFIGS[args.workload]
     K, W = args.steps, args.warmup
     t0 = time.time()
@@ -86,7 +104,10 @@ def main():
         alg_bytes = w.G * w.mu * w.widths[0] * 4
         achieved = alg_bytes / (grad_ms_avg * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": (MEASURED_TRAFFIC[w.name][1]
+                                if w.name in MEASURED_TRAFFIC and
+                                MEASURED_TRAFFIC[w.name][0] == B.gcada_timed_stage(gpu.ctx) else None),
                     "kernel": B.gcada_timed_stage(gpu.ctx),
                     "avg_ms": round(grad_ms_avg, 5), "algorithmic_bytes": alg_bytes}
     else:

@@ -189,8 +189,10 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
 /*
  * Tuning switches (defaults in brackets).  GCADA_OPT_SINGLE_PASS_LOGREG [1]: compute the logistic
  * gradients with the kernel that reads the minibatch from HBM once (whole-row register tiles)
- * when the shape allows it (d in {256, 512, 1024, 2048, 4096}, mu a multiple of the tile's rows,
- * 16-byte aligned shards); 0 forces the general two-pass kernels.  Both compute the same step
+ * when the shape allows it (d in {256, 512, 1024, 2048, 4096} with mu a multiple of the tile's
+ * rows: whole-row register tiles; or d a multiple of 4096 up to 86,016 with mu a multiple of 4:
+ * tiles shared by a team of workgroups; 16-byte aligned shards); 0 forces the general two-pass
+ * kernels.  Both compute the same step
  * a1.  Errors: GCADA_EINVAL (unknown option).
  */
 enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1 };

@@ -66,6 +66,7 @@ void free_all(gcada_ctx* c)
     if (!c) return;
     gcada::mlp_free(c);
     gcada::lr_tile_free(c);
+    gcada::lr_team_free(c);
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->gbuf, c->which, c->tau,
                     c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat, c->stat_sum,
                     c->part_sq};
@@ -155,6 +156,8 @@ try {
     if ((e = gcada::select_plan(x)) != hipSuccess) return bail(e, "server plan");
     if (dims->model == GCADA_LOGREG && (e = gcada::lr_tile_plan(x)) != hipSuccess)
         return bail(e, "single-pass logistic plan");
+    if (dims->model == GCADA_LOGREG && (e = gcada::lr_team_plan(x)) != hipSuccess)
+        return bail(e, "team logistic plan");
     if ((e = dalloc(&x->part_loss, (size_t)G * x->n_loss_part)) != hipSuccess) return bail(e, "alloc scratch");
     if ((e = dalloc(&x->part_stat, (size_t)G * x->n_stat_part)) != hipSuccess) return bail(e, "alloc scratch");
     if ((e = dalloc(&x->part_sq, (size_t)2 * x->n_epi_blocks)) != hipSuccess) return bail(e, "alloc scratch");
@@ -230,6 +233,7 @@ static int reset_run(gcada_ctx* ctx, const float* theta0_any)
 static int after_state_change(gcada_ctx* ctx)
 {
     set_iteration(ctx);
+    if (ctx->dims.model == GCADA_LOGREG) HIP_TRY(ctx, gcada::lr_team_reset(ctx));
     HIP_TRY(ctx, gcada::refresh_theta_sq(ctx, nullptr));
     if (ctx->dims.model == GCADA_MLP) HIP_TRY(ctx, gcada::mlp_refresh_weights(ctx, nullptr));
     HIP_TRY(ctx, hipDeviceSynchronize());
@@ -391,6 +395,7 @@ const char* gcada_timed_stage(gcada_ctx* ctx)
     if (!ctx) return "";
     if (ctx->dims.model == GCADA_MLP) ctx->stage_name = "mlp gradient stage (gather, mlp_gemm forward/backward/weight-gradient, bias)";
     else if (gcada::lr_tile_applies(ctx)) ctx->stage_name = "lr_tile_kernel";
+    else if (gcada::lr_team_applies(ctx)) ctx->stage_name = "lr_team_kernel";
     else ctx->stage_name = "lr_forward+lr_backward";
     return ctx->stage_name.c_str();
 }

@@ -56,8 +56,24 @@ __device__ inline float* fresh_row(float* gbuf, const int32_t* which, const Hype
     return gbuf + ((int64_t)(1 - which[g]) * hy.G + g) * hy.pstride;
 }
 
+// Loads through pointers that were themselves read from memory (the shard table): the compiler
+// cannot tell their address space and would fall back to flat accesses, whose completion is
+// counted together with LDS and scalar traffic.  These helpers state that the data is global.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 global_load4(const float* p)
+{
+    const f32x4 v = *(const __attribute__((address_space(1))) f32x4*)p;
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+template <typename T>
+__device__ __forceinline__ T global_load(const T* p)
+{
+    return *(const __attribute__((address_space(1))) T*)p;
+}
+
 struct MlpWork;       // MLP activations and compute copies (mlp_kernels.hip)
-struct LrTilePlan;    // single-pass logistic path (lr_tiles.hip)
+struct LrTilePlan;    // single-pass logistic path, rows that fit one workgroup (lr_tiles.hip)
+struct LrTeamPlan;    // single-pass logistic path, wide rows shared by a team (lr_team.hip)
 
 }  // namespace gcada
 
@@ -101,6 +117,8 @@ struct gcada_ctx {
 
     gcada::MlpWork* mlp = nullptr;
     gcada::LrTilePlan* lr_tiles = nullptr;
+    gcada::LrTeamPlan* lr_team = nullptr;
+    unsigned team_launches = 0;    // advances the exchange tags of the team kernel
     bool allow_single_pass = true;
 
     bool dominant_only = false;    // benchmark diagnostic: launch only the dominant gradient kernel(s)
@@ -120,6 +138,13 @@ hipError_t lr_tile_plan(gcada_ctx* c);
 void lr_tile_free(gcada_ctx* c);
 bool lr_tile_applies(const gcada_ctx* c);
 hipError_t lr_tile_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
+
+// single-pass logistic gradients for wide rows: teams of workgroups share a tile (lr_team.hip)
+hipError_t lr_team_plan(gcada_ctx* c);
+void lr_team_free(gcada_ctx* c);
+bool lr_team_applies(const gcada_ctx* c);
+hipError_t lr_team_reset(gcada_ctx* c);       // clear the exchange buffer
+hipError_t lr_team_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
 
 hipError_t mlp_plan(gcada_ctx* c);
 void mlp_free(gcada_ctx* c);

@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kFwdWaves* kWave) void lr_forward(
         ok[r] = i0 + r < mu;
         const int64_t row = ok[r] ? row_of(idx, g, i0 + r, mu, k, sh.rows) : 0;
         xr[r] = X + row * sh.ld;
-        yv[r] = ok[r] ? Y[row] : 1.0f;
+        yv[r] = ok[r] ? global_load(Y + row) : 1.0f;
     }
     float z[kFwdRows] = {}, dz[kFwdRows] = {};
     if (VEC) {
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kFwdWaves* kWave) void lr_forward(
 #pragma unroll
             for (int r = 0; r < kFwdRows; ++r) {
                 if (!ok[r]) continue;
-                const float4 x = *(const float4*)(xr[r] + j);
+                const float4 x = global_load4(xr[r] + j);
                 z[r] += x.x * t.x + x.y * t.y + x.z * t.z + x.w * t.w;
                 dz[r] += x.x * dl.x + x.y * dl.y + x.z * dl.z + x.w * dl.w;
             }
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kFwdWaves* kWave) void lr_forward(
 #pragma unroll
             for (int r = 0; r < kFwdRows; ++r) {
                 if (!ok[r]) continue;
-                const float x = xr[r][j];
+                const float x = global_load(xr[r] + j);
                 z[r] += x * t;
                 dz[r] += x * dl;
             }
@@ -187,8 +187,8 @@ __global__ __launch_bounds__(kBwdWaves* kWave) void lr_backward(
             for (int u = 0; u < 4; ++u) {
                 const int ii = i + u * kBwdWaves;
                 const int64_t row = row_of(idx, g, ii, mu, k, sh.rows);
-                if (VEC) x[u] = *(const float4*)(X + row * sh.ld + j);
-                else x[u] = make_float4(X[row * sh.ld + j], 0, 0, 0);
+                if (VEC) x[u] = global_load4(X + row * sh.ld + j);
+                else x[u] = make_float4(global_load(X + row * sh.ld + j), 0, 0, 0);
                 w[u] = s_res[ii];
             }
 #pragma unroll
@@ -202,8 +202,8 @@ __global__ __launch_bounds__(kBwdWaves* kWave) void lr_backward(
         for (; i < mu; i += kBwdWaves) {
             const int64_t row = row_of(idx, g, i, mu, k, sh.rows);
             float4 x;
-            if (VEC) x = *(const float4*)(X + row * sh.ld + j);
-            else x = make_float4(X[row * sh.ld + j], 0, 0, 0);
+            if (VEC) x = global_load4(X + row * sh.ld + j);
+            else x = make_float4(global_load(X + row * sh.ld + j), 0, 0, 0);
             const float2 w = s_res[i];
             ag.x += w.x * x.x; ag.y += w.x * x.y; ag.z += w.x * x.z; ag.w += w.x * x.w;
             as.x += w.y * x.x; as.y += w.y * x.y; as.z += w.y * x.z; as.w += w.y * x.w;
@@ -270,6 +270,7 @@ static bool lr_vec_ok(const gcada_ctx* c)
 hipError_t lr_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
 {
     if (lr_tile_applies(c)) return lr_tile_gradients(c, idx, s);
+    if (lr_team_applies(c)) return lr_team_gradients(c, idx, s);
     c->n_loss_used = c->n_loss_part_lr * c->hy.G;
     const Hyper& hy = c->hy;
     const bool vec = lr_vec_ok(c);

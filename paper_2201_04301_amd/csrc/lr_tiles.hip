@@ -136,11 +136,11 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     for (int u = 0; u < kTR; ++u) {
         // the row id is the same for the whole wave: keep it in a scalar register
         const int64_t row = __builtin_amdgcn_readfirstlane(s_row[wr * kTR + u]);
-        x[u] = *(const float4*)(X + row * sh.ld + col);
+        x[u] = global_load4(X + row * sh.ld + col);
     }
     // while the tile streams in: labels, the two iterates
     float my_y = 1.0f;
-    if (tid < R) my_y = ((const float*)sh.y)[my_row];
+    if (tid < R) my_y = global_load((const float*)sh.y + my_row);
     const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
     const int old = stale_slot_of(hy, a.tau[g]);
     const float* __restrict__ ts = a.ring + (int64_t)old * hy.pstride;

@@ -10,35 +10,11 @@
 //   s_g    = sum_i dr_i x_i + mu*l2*(theta^k - theta_stale_g)     stat_g = ||s_g||^2
 // The forward kernel streams the rows once for the two dot products, the backward kernel
 // streams them again (column slabs) for the two weighted row sums.
-#include "gcada_internal.h"
+#include "lr_device.h"
 
 namespace gcada {
 
 namespace {
-
-constexpr int kWave = 64;
-
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
-}
-
-__device__ __forceinline__ double wave_sum(double v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
-}
-
-__device__ __forceinline__ float sigmoidf_(float t)
-{
-    // 1/(1+e^-t) without overflow
-    float e = expf(-fabsf(t));
-    float s = 1.0f / (1.0f + e);
-    return t >= 0 ? s : e * s;
-}
 
 // Row id of sample i of group g at iteration k.
 __device__ __forceinline__ int64_t row_of(const int32_t* idx, int g, int i, int mu, long long k,
@@ -47,25 +23,6 @@ __device__ __forceinline__ int64_t row_of(const int32_t* idx, int g, int i, int 
     if (idx) return (int64_t)idx[(int64_t)g * mu + i];
     return (int64_t)(((unsigned long long)k * (unsigned long long)mu + (unsigned long long)i) %
                      (unsigned long long)rows);
-}
-
-// residuals of one sample from its two dot products
-__device__ __forceinline__ void residuals(float z, float dz, float y, float& r, float& dr,
-                                          float& loss)
-{
-    const float a = -y * z;              // sigma(a) is the weight of this sample
-    const float sa = sigmoidf_(a);
-    r = -y * sa;
-    // stale logit z~ = z - dz;  b = -y z~ = a + y dz
-    const float t = y * dz;              // b - a
-    const float b = a + t;
-    float dsig;                          // sigma(a) - sigma(b)
-    if (fabsf(t) < 0.5f)
-        dsig = -sa * sigmoidf_(-b) * expm1f(t);
-    else
-        dsig = sa - sigmoidf_(b);
-    dr = -y * dsig;
-    loss = fmaxf(a, 0.0f) + log1pf(expf(-fabsf(a)));   // log(1 + e^a)
 }
 
 constexpr int kFwdWaves = 4;   // waves per block

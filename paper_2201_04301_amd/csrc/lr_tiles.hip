@@ -8,76 +8,15 @@
 // HBM exactly once and no workgroup ever waits for another.  Tiles of one group leave partial
 // column sums; a second, small kernel adds them in a fixed order (deterministic), writes the
 // group's gradient and the partial squared norms of the gradient difference.
-#include "gcada_internal.h"
+#include "lr_device.h"
 
 namespace gcada {
 
 namespace {
 
-constexpr int kWave = 64;
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / kWave;     // 16
 constexpr int kTR = 16;                      // tile rows per thread
-
-__device__ __forceinline__ double wave_sum(double v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
-}
-
-// v[0..N) per lane -> every lane l ends with the sum over all 64 lanes of v[l >> (6 - log2 N)].
-// Each of the log2(N) halving steps exchanges half of the remaining values with lane ^ S.
-template <int N, int S>
-struct Butterfly {
-    static __device__ __forceinline__ void run(float (&v)[N], int lane)
-    {
-        if constexpr (S >= 1) {
-            if constexpr (N > 1) {
-                const bool up = (lane & S) != 0;
-                float w[N / 2];
-#pragma unroll
-                for (int i = 0; i < N / 2; ++i) {
-                    const float send = up ? v[i] : v[i + N / 2];
-                    const float keep = up ? v[i + N / 2] : v[i];
-                    w[i] = keep + __shfl_xor(send, S, kWave);
-                }
-                Butterfly<N / 2, S / 2>::run(w, lane);
-                v[0] = w[0];
-            } else {
-                v[0] += __shfl_xor(v[0], S, kWave);
-                Butterfly<1, S / 2>::run(v, lane);
-            }
-        }
-    }
-};
-
-__device__ __forceinline__ float sigmoidf_(float t)
-{
-    const float e = expf(-fabsf(t));
-    const float s = 1.0f / (1.0f + e);
-    return t >= 0 ? s : e * s;
-}
-
-// r = residual at theta^k, dr = r - (residual at theta_stale), from z = x.theta^k and
-// dz = x.(theta^k - theta_stale); the difference of the two sigmoids is formed without
-// cancellation.
-__device__ __forceinline__ void residuals(float z, float dz, float y, float& r, float& dr,
-                                          float& loss)
-{
-    const float a = -y * z;
-    const float sa = sigmoidf_(a);
-    r = -y * sa;
-    const float t = y * dz;              // (-y z~) - (-y z)
-    const float b = a + t;
-    float dsig;                          // sigma(a) - sigma(b)
-    if (fabsf(t) < 0.5f)
-        dsig = -sa * sigmoidf_(-b) * expm1f(t);
-    else
-        dsig = sa - sigmoidf_(b);
-    dr = -y * dsig;
-    loss = fmaxf(a, 0.0f) + log1pf(expf(-fabsf(a)));
-}
 
 struct TileArgs {
     Hyper hy;

@@ -1,47 +1,64 @@
 // Single-pass logistic-regression gradients for wide rows (d a multiple of 4096, d >= 8192):
 // step a1 for shapes whose rows do not fit one workgroup's registers (paper Sec. II-A).
 //
-// A TEAM of TS = d/4096 workgroups shares the rows of a tile: member m keeps columns
-// [4096 m, 4096 (m+1)) of R = 4 rows in registers (two float4 per row and thread).  Every member
-// forms its partial dot products and publishes them (64 bytes) in a small exchange buffer; TWO
-// TILES LATER it collects the partials of all members, forms the residuals and adds the tile's
-// contribution to its 4096 columns of the two weighted row sums straight from the registers.
-// Four register tiles are live per thread (loading / multiplied / waiting / added), so the
-// exchange latency hides behind two tiles of loads and the minibatch is read from HBM exactly
-// once.  A member owns its columns for all rows of a group: the column sums never leave
-// registers until the group is finished, and no partial sums are written.
+// A TEAM of TS = d/4096 workgroups shares the rows of a tile: member m owns columns
+// [4096 m, 4096 (m+1)) of R = 4 rows (two float4 per row and thread).  Every member forms its
+// partial dot products and publishes them (64 bytes) in a small exchange buffer; TWO TILES LATER
+// it collects the partials of all members, forms the residuals and adds the tile's contribution
+// to its 4096 columns of the two weighted row sums.  While a tile waits for its residuals it is
+// parked in LDS (each thread keeps its own 128 bytes per tile there -- LDS as private spill
+// space, no synchronisation needed), so the registers hold the tile being multiplied plus the
+// TWO tiles whose loads are in flight.  The minibatch is read from HBM exactly once.  A member
+// owns its columns for all rows of a group: the column sums never leave registers until the
+// group is finished, and no partial sums are written.
 //
 // Exchange protocol (no read-modify-write atomics, no fences): a partial is eight 8-byte pairs
 // {value, tag}; tag = sequence number of the tile, so a pair is valid exactly when its tag
-// matches.  Pairs are written and read with system-scope cache policy (sc0 sc1), i.e. past the
+// matches.  Pairs are written and read as relaxed 64-bit atomics at system scope, i.e. past the
 // non-coherent L2 of the 8 XCDs.  Four slots per team: a member that publishes tile t has seen
 // every member's tile t-2, and a member that has published tile t-2 has already consumed tile
 // t-4, whose slot tile t takes.  Every wait is bounded; when a bound is hit the kernel raises
 // Ctl::error and runs to its end without waiting again.
 //
-// One workgroup barrier per tile: wave 0 forms the residuals of tile t-2 before the barrier of
-// stage t and publishes the partials of tile t after it; the two small LDS arrays involved are
-// double-buffered by the parity of t.
+// Eight DATA waves stream the tiles; a ninth CONTROL wave does the exchange (it loads no tiles,
+// so its polls never queue behind tile loads, which return in order).  One workgroup barrier per
+// tile: the control wave forms the residuals of tile t-2 before the barrier of stage t and
+// publishes the partials of tile t after it; the small LDS arrays involved are double-buffered
+// by the parity of t.
 #include "lr_device.h"
 
 namespace gcada {
 
 namespace {
 
-constexpr int kThreads = 512;
-constexpr int kWaves = 8;
+constexpr int kDataWaves = 8;
+constexpr int kDataThreads = kDataWaves * 64;
+constexpr int kThreads = kDataThreads + 64;   // plus the control wave
 constexpr int kV = 2;                    // float4 per row and thread, 256 columns apart
 constexpr int kR = 4;                    // rows per tile
 constexpr int kSlab = 4096;              // columns per member
 constexpr int kSlots = 4;
-constexpr int kTiles = 4;                // register tiles per thread
+constexpr int kRegTiles = 3;             // register tiles per thread: multiplied + two loading
 constexpr int kPartial = 2 * kR;         // values a member publishes per tile
 constexpr int kSlotBytes = kPartial * 8; // per member and slot
+constexpr int kParkBytes = 2 * kR * kV * kDataThreads * 16;   // two parked tiles: 131072
+constexpr int kLabelRing = 8;            // labels of tiles t-2 .. t+2 are live
 constexpr unsigned kPollLimit = 1u << 16;
-constexpr int kCoherent = 17;            // buffer cache policy: sc0 | sc1
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+// A pair {value, tag} of the exchange buffer travels as one 64-bit word.  Relaxed atomic
+// accesses at system scope: the hardware goes past the non-coherent L2s (sc0 sc1), and the
+// compiler neither merges nor hoists them -- a plain load in a polling loop would be read once.
+__device__ __forceinline__ unsigned long long pair_load(const unsigned long long* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ void pair_store(unsigned long long* p, float value, unsigned tag)
+{
+    __hip_atomic_store(p, ((unsigned long long)tag << 32) | __float_as_uint(value), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ float pair_value(unsigned long long w) { return __uint_as_float((unsigned)w); }
+__device__ __forceinline__ unsigned pair_tag(unsigned long long w) { return (unsigned)(w >> 32); }
 
 struct TeamArgs {
     Hyper hy;
@@ -50,7 +67,7 @@ struct TeamArgs {
     const float* ring;
     const int32_t* tau;
     Ctl* ctl;
-    void* xch;               // [NT][kSlots][TS][kPartial] pairs {value, tag}
+    unsigned long long* xch; // [NT][kSlots][TS][kPartial] pairs {value, tag}
     float* gbuf;
     const int32_t* which;
     double* part_stat;       // [G][TS]
@@ -74,72 +91,243 @@ __device__ __forceinline__ void team_of(int wg, int TS, int nWG, int& team, int&
     }
 }
 
-// Per-thread state of one group's pass that the stages share.
+// Per-thread state of a data wave.
 struct TeamRegs {
-    float4 xb[kTiles][kR][kV];   // register tiles; tile t lives in xb[t % kTiles]
-    float yl[kTiles];            // labels of the tile's rows (wave 0, lanes < kR)
-    float4 th4[kV], dl4[kV];     // theta^k and theta^k - theta_stale at this thread's columns
-    float4 ag[kV], as[kV];       // column sums of r_i x_i and dr_i x_i
-    int rows_nxt[kR];            // row ids of the tile that is loaded next (wave-uniform)
-    double lacc;                 // loss (wave 0, lanes < kR)
+    float4 xb[kRegTiles][kR][kV];   // register tiles; tile n lives in xb[n % 3]
+    float4 th4[kV], dl4[kV];        // theta^k and theta^k - theta_stale at this thread's columns
+    float4 ag[kV], as[kV];          // column sums of r_i x_i and dr_i x_i
 };
 
-// One pipeline stage; J = t mod 4 is a compile-time constant so that every tile index is static.
-//   tile t+1 starts loading, tile t is multiplied and published, tile t-2 gets its residuals
-//   and is added.  seq0 = sequence number of the group's tile 0.
-template <int J>
-__device__ __forceinline__ void team_stage(const TeamArgs& a, TeamRegs& R, const ShardDesc& sh,
-                                           __amdgpu_buffer_rsrc_t xr, int t, int ntile, int g, int m,
-                                           int col, unsigned seq0, unsigned cyc_base, bool& gave_up,
-                                           float (&s_dot)[2][kWaves][kPartial], float2 (&s_res)[2][kR])
+// Wave-uniform bookkeeping.  The team's tiles form ONE sequence n = 0 .. ntot-1 over all groups
+// the team works on (group ordinal n / ntile), so the loads never pause between groups.
+struct TeamSeq {
+    int ntile, ntot;                // tiles per group, tiles of this team in this launch
+    // the tile that is requested next (n+2 in stage n)
+    int rows_nxt[kR];
+    const float* x_nxt;
+    const float* y_nxt;
+    int64_t ld_nxt;
+    // where the row-id fetch stands (tile n+3 in stage n)
+    int gF, tF;
+    // tile n (multiplied) and tile n-2 (added): group and tile within the group
+    int gC, tC, gA, tA;
+};
+
+struct TeamLds {
+    float s_dot[2][kDataWaves][kPartial];   // per-wave partial dots, by parity of the tile
+    float2 s_res[2][kR];                    // residuals (r, dr), by parity of the stage
+    float s_y[kLabelRing][kR];              // labels by tile mod 8 (control wave only)
+    double s_red[kDataWaves];
+};
+
+// Describe the tile after the one S.gF/S.tF point at -- row ids through scalar loads (constant
+// address space, uniform address): they are counted apart from the vector loads, so fetching
+// them never waits for a tile in flight.  Past the end of the sequence the last tile is
+// described again (it is requested, never used).
+__device__ __forceinline__ void team_fetch(const TeamArgs& a, TeamSeq& S, int nF, int NT)
 {
-    constexpr int JN = (J + 1) % kTiles, JC = J, JA = (J + 2) % kTiles;   // loading, current, added
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const bool have_load = t + 1 < ntile, have_cur = t < ntile, have_add = t >= 2;
-    const bool poller = wave == 0 && lane < a.TS * kR;
     typedef const int32_t __attribute__((address_space(4))) const_i32;
-
-    // the poll goes out before this stage's tile loads, so it also comes back before them; the
-    // partials it reads were published two stages ago
-    u32x4 pol = {0u, 0u, 0u, 0u};
-    const int poll_off = (int)((seq0 + (unsigned)t - 2u) % kSlots) * a.TS * kSlotBytes + lane * 16;
-    if (have_add && poller) pol = __builtin_amdgcn_raw_buffer_load_b128(xr, poll_off, 0, kCoherent);
-
-    if (have_load) {
-        if (wave == 0 && lane < kR) {
-            int myrow = R.rows_nxt[0];
-#pragma unroll
-            for (int u = 1; u < kR; ++u) myrow = lane == u ? R.rows_nxt[u] : myrow;
-            R.yl[JN] = global_load((const float*)sh.y + myrow);
-        }
-#pragma unroll
-        for (int u = 0; u < kR; ++u) {
-            const float* xrow = (const float*)sh.X + (int64_t)R.rows_nxt[u] * sh.ld + col;
-#pragma unroll
-            for (int q = 0; q < kV; ++q) R.xb[JN][u][q] = global_load4(xrow + 256 * q);
-        }
+    typedef const ShardDesc __attribute__((address_space(4))) const_shard;
+    if (nF < S.ntot && nF > 0) {
+        if (++S.tF == S.ntile) { S.tF = 0; S.gF += NT; }
     }
-    // row ids of tile t+2 through scalar loads (constant address space, uniform address): they
-    // are counted apart from the vector loads, so fetching them never waits for a tile in flight
+    const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
+    const unsigned rows = (unsigned)sh->rows;
+    // cyclic window: first row of this step's window, (k * mu) mod rows, in 32 bits
+    const unsigned cyc_base = (unsigned)((((unsigned long long)a.hy.k % rows) *
+                                          ((unsigned long long)a.hy.mu % rows)) % rows);
 #pragma unroll
     for (int u = 0; u < kR; ++u) {
-        int rr = 0;
-        if (t + 2 < ntile) {
-            if (a.idx) rr = ((const_i32*)(uintptr_t)a.idx)[(int64_t)g * a.hy.mu + (t + 2) * kR + u];
-            else rr = (int)((cyc_base + (unsigned)((t + 2) * kR + u)) % (unsigned)sh.rows);
+        int rr;
+        if (a.idx) rr = ((const_i32*)(uintptr_t)a.idx)[(int64_t)S.gF * a.hy.mu + S.tF * kR + u];
+        else rr = (int)((cyc_base + (unsigned)(S.tF * kR + u)) % rows);
+        S.rows_nxt[u] = __builtin_amdgcn_readfirstlane(rr);
+    }
+    S.x_nxt = (const float*)sh->X;
+    S.y_nxt = (const float*)sh->y;
+    S.ld_nxt = sh->ld;
+}
+
+// Request the tile described in S into register tile JL.
+template <int JL>
+__device__ __forceinline__ void team_load_tile(TeamRegs& R, const TeamSeq& S, int col)
+{
+#pragma unroll
+    for (int u = 0; u < kR; ++u) {
+        const float* xrow = S.x_nxt + (int64_t)S.rows_nxt[u] * S.ld_nxt + col;
+#pragma unroll
+        for (int q = 0; q < kV; ++q) R.xb[JL][u][q] = global_load4(xrow + 256 * q);
+    }
+}
+
+// Label of row `lane` (< kR) of the tile S.gF/S.tF point at; the lane looks its row id up itself.
+__device__ __forceinline__ float team_load_label(const TeamArgs& a, const TeamSeq& S, int lane)
+{
+    typedef const ShardDesc __attribute__((address_space(4))) const_shard;
+    const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
+    const unsigned rows = (unsigned)sh->rows;
+    const int i = S.tF * kR + lane;
+    int myrow;
+    if (a.idx) {
+        myrow = a.idx[(int64_t)S.gF * a.hy.mu + i];
+    } else {
+        const unsigned cyc_base = (unsigned)((((unsigned long long)a.hy.k % rows) *
+                                              ((unsigned long long)a.hy.mu % rows)) % rows);
+        myrow = (int)((cyc_base + (unsigned)i) % rows);
+    }
+    return global_load((const float*)sh->y + myrow);
+}
+
+// Move S.gF/S.tF on to tile nF (the control wave's share of team_fetch).
+__device__ __forceinline__ void team_advance(TeamSeq& S, int nF, int NT)
+{
+    if (nF < S.ntot && nF > 0) {
+        if (++S.tF == S.ntile) { S.tF = 0; S.gF += NT; }
+    }
+}
+
+// theta^k - theta_stale of group g at this thread's columns
+__device__ __forceinline__ void team_delta(const TeamArgs& a, const TeamRegs& R, int g, int col, float4 (&dl)[kV])
+{
+    const float* stale = a.ring + (int64_t)stale_slot_of(a.hy, a.tau[g]) * a.hy.pstride + col;
+#pragma unroll
+    for (int q = 0; q < kV; ++q) {
+        const float4 u4 = *(const float4*)(stale + 256 * q);
+        dl[q] = make_float4(R.th4[q].x - u4.x, R.th4[q].y - u4.y, R.th4[q].z - u4.z, R.th4[q].w - u4.w);
+    }
+}
+
+// One pipeline stage of a DATA wave; J = n mod 3 is a compile-time constant so that every
+// register tile index is static, and every stage requests a tile, so that the number of loads
+// in flight at every wait is known statically (otherwise the compiler has to wait for all of
+// them, including the tiles that were only just requested).  Tile n+2 starts loading, tile n is
+// multiplied and parked, tile n-2 is added from where it was parked.
+template <int J>
+__device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, TeamSeq& S, int n, int m,
+                                                int col, TeamLds& L, float4* park)
+{
+    constexpr int JL = (J + 2) % kRegTiles;      // the register tile that is loaded in this stage
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const bool have_cur = n < S.ntot, have_add = n >= 2 && n - 2 < S.ntot;
+
+    team_load_tile<JL>(R, S, col);
+    team_fetch(a, S, n + 3, a.NT);
+
+    if (have_cur) {
+        if (S.tC == 0) team_delta(a, R, S.gC, col, R.dl4);       // first tile of a group
+        float v[kPartial];
+#pragma unroll
+        for (int u = 0; u < kR; ++u) {
+            float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+            for (int q = 0; q < kV; ++q) {
+                const float4 x4 = R.xb[J][u][q];
+                s0 += x4.x * R.th4[q].x + x4.y * R.th4[q].y + x4.z * R.th4[q].z + x4.w * R.th4[q].w;
+                s1 += x4.x * R.dl4[q].x + x4.y * R.dl4[q].y + x4.z * R.dl4[q].z + x4.w * R.dl4[q].w;
+            }
+            v[2 * u] = s0;
+            v[2 * u + 1] = s1;
         }
-        R.rows_nxt[u] = __builtin_amdgcn_readfirstlane(rr);
+        Butterfly<kPartial, 32>::run(v, lane);       // lanes 8e hold value e
+        if ((lane & 7) == 0) L.s_dot[n & 1][wave][lane >> 3] = v[0];
+    }
+    __syncthreads();
+
+    // this thread's slots of the parking area for tiles of this parity
+    float4* mine = park + (n & 1) * (kR * kV * kDataThreads) + tid;
+    if (have_add) {
+#pragma unroll
+        for (int u = 0; u < kR; ++u) {
+            const float2 w2 = L.s_res[n & 1][u];
+#pragma unroll
+            for (int q = 0; q < kV; ++q) {
+                const float4 x4 = mine[(u * kV + q) * kDataThreads];
+                R.ag[q].x += w2.x * x4.x; R.ag[q].y += w2.x * x4.y; R.ag[q].z += w2.x * x4.z; R.ag[q].w += w2.x * x4.w;
+                R.as[q].x += w2.y * x4.x; R.as[q].y += w2.y * x4.y; R.as[q].z += w2.y * x4.z; R.as[q].w += w2.y * x4.w;
+            }
+        }
+    }
+    if (have_cur) {
+#pragma unroll
+        for (int u = 0; u < kR; ++u)
+#pragma unroll
+            for (int q = 0; q < kV; ++q) mine[(u * kV + q) * kDataThreads] = R.xb[J][u][q];
+        if (++S.tC == S.ntile) { S.tC = 0; S.gC += a.NT; }
     }
 
-    // wave 0: residuals of tile t-2 from all members' partials
-    if (have_add && wave == 0) {
-        const unsigned want = a.tag_base + seq0 + (unsigned)t - 2u;
+    if (have_add) {
+        if (S.tA == S.ntile - 1) {
+            // group S.gA is finished: this member's 4096 columns of the gradient and of s_g
+            const int g = S.gA;
+            double sq = 0;
+            float* out = fresh_row(a.gbuf, a.which, a.hy, g) + col;
+            float4 dlo[kV];
+            if (a.hy.l2 != 0.0f) team_delta(a, R, g, col, dlo);
+#pragma unroll
+            for (int q = 0; q < kV; ++q) {
+                if (a.hy.l2 != 0.0f) {
+                    const float ml = (float)a.hy.mu * a.hy.l2;
+                    R.ag[q].x += ml * R.th4[q].x; R.ag[q].y += ml * R.th4[q].y; R.ag[q].z += ml * R.th4[q].z; R.ag[q].w += ml * R.th4[q].w;
+                    R.as[q].x += ml * dlo[q].x; R.as[q].y += ml * dlo[q].y; R.as[q].z += ml * dlo[q].z; R.as[q].w += ml * dlo[q].w;
+                }
+                *(float4*)(out + 256 * q) = R.ag[q];
+                sq += (double)R.as[q].x * R.as[q].x + (double)R.as[q].y * R.as[q].y + (double)R.as[q].z * R.as[q].z +
+                      (double)R.as[q].w * R.as[q].w;
+                R.ag[q] = make_float4(0, 0, 0, 0);
+                R.as[q] = make_float4(0, 0, 0, 0);
+            }
+            sq = wave_sum(sq);
+            if (lane == 0) L.s_red[wave] = sq;
+            __syncthreads();                     // the control wave joins this barrier as well
+            if (tid == 0) {
+                double tsum = 0;
+                for (int wv = 0; wv < kDataWaves; ++wv) tsum += L.s_red[wv];
+                a.part_stat[(int64_t)g * a.TS + m] = tsum;
+            }
+            S.tA = 0;
+            S.gA += a.NT;
+        } else {
+            ++S.tA;
+        }
+    }
+}
+
+// One pipeline stage of the CONTROL wave: it loads no tiles, so its poll of the exchange
+// buffer and its label loads never queue behind tile loads.  Before the barrier of stage n it
+// forms the residuals of tile n-2 from all members' partials (published two stages ago); after
+// the barrier it adds the data waves' partial dots of tile n and publishes them.
+__device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S, unsigned long long* xt,
+                                                   int n, int m, bool& gave_up, float& y_new, double& lacc,
+                                                   TeamLds& L)
+{
+    const int lane = threadIdx.x % kWave;
+    const bool have_cur = n < S.ntot, have_add = n >= 2 && n - 2 < S.ntot;
+    const bool poller = lane < a.TS * kR;
+
+    // lane l polls member l/4's pairs (z, dz) of row l%4; lanes without a member poll nothing
+    const unsigned long long* mine = xt + (int)(((unsigned)n + 2u) % kSlots) * a.TS * kPartial + lane * 2;
+    unsigned long long pz = 0, pdz = 0;
+    if (poller) {
+        pz = pair_load(mine);
+        pdz = pair_load(mine + 1);
+    }
+    // file the label requested in the previous stage (tile n+1), then request that of tile n+2
+    if (lane < kR) {
+        L.s_y[(n + 1) % kLabelRing][lane] = y_new;
+        y_new = team_load_label(a, S, lane);
+    }
+    team_advance(S, n + 3, a.NT);
+
+    if (have_add) {
+        const unsigned want = a.tag_base + (unsigned)n - 2u;
+        bool ok = !poller || (pair_tag(pz) == want && pair_tag(pdz) == want);
         unsigned spins = 0;
-        bool ok = !poller || (pol.y == want && pol.w == want);
-        while (!gave_up && !__all(ok)) {
+        while (!gave_up && !__all(ok)) {         // rare: a member is more than a tile behind
             if (poller && !ok) {
-                pol = __builtin_amdgcn_raw_buffer_load_b128(xr, poll_off, 0, kCoherent);
-                ok = pol.y == want && pol.w == want;
+                pz = pair_load(mine);
+                pdz = pair_load(mine + 1);
+                ok = pair_tag(pz) == want && pair_tag(pdz) == want;
             }
             if (++spins > kPollLimit) {
                 if (lane == 0)
@@ -148,8 +336,8 @@ __device__ __forceinline__ void team_stage(const TeamArgs& a, TeamRegs& R, const
             }
         }
         // lane l holds member l/4's partial (z, dz) of row l%4: add the members in a fixed tree
-        float z = poller ? __uint_as_float(pol.x) : 0.0f;
-        float dz = poller ? __uint_as_float(pol.z) : 0.0f;
+        float z = poller ? pair_value(pz) : 0.0f;
+        float dz = poller ? pair_value(pdz) : 0.0f;
 #pragma unroll
         for (int o = kR; o < kWave; o <<= 1) {
             z += __shfl_xor(z, o, kWave);
@@ -157,169 +345,101 @@ __device__ __forceinline__ void team_stage(const TeamArgs& a, TeamRegs& R, const
         }
         if (lane < kR) {
             float r, dr, ls;
-            residuals(z, dz, R.yl[JA], r, dr, ls);
-            s_res[t & 1][lane] = make_float2(r, dr);
-            R.lacc += (double)ls;
+            residuals(z, dz, L.s_y[(n - 2) % kLabelRing][lane], r, dr, ls);
+            L.s_res[n & 1][lane] = make_float2(r, dr);
+            lacc += (double)ls;
         }
-    }
-
-    if (have_cur) {
-        float v[kPartial];
-#pragma unroll
-        for (int u = 0; u < kR; ++u) {
-            float s0 = 0.0f, s1 = 0.0f;
-#pragma unroll
-            for (int q = 0; q < kV; ++q) {
-                const float4 x4 = R.xb[JC][u][q];
-                s0 += x4.x * R.th4[q].x + x4.y * R.th4[q].y + x4.z * R.th4[q].z + x4.w * R.th4[q].w;
-                s1 += x4.x * R.dl4[q].x + x4.y * R.dl4[q].y + x4.z * R.dl4[q].z + x4.w * R.dl4[q].w;
-            }
-            v[2 * u] = s0;
-            v[2 * u + 1] = s1;
-        }
-        Butterfly<kPartial, 32>::run(v, lane);       // lanes 8e hold value e
-        if ((lane & 7) == 0) s_dot[t & 1][wave][lane >> 3] = v[0];
     }
     __syncthreads();
 
-    if (have_cur && wave == 0) {
-        // member partial: lane l adds value l%8 over the waves in a fixed tree, lanes < 8 publish
-        float w = s_dot[t & 1][lane >> 3][lane & 7];
+    if (have_cur) {
+        // member partial: lane l adds value l%8 over the data waves in a fixed tree
+        float w = L.s_dot[n & 1][lane >> 3][lane & 7];
 #pragma unroll
         for (int o = 8; o < kWave; o <<= 1) w += __shfl_xor(w, o, kWave);
-        if (lane < kPartial) {
-            const unsigned seq = seq0 + (unsigned)t;
-            const u32x2 pr = {__float_as_uint(w), a.tag_base + seq};
-            __builtin_amdgcn_raw_buffer_store_b64(pr, xr, ((int)(seq % kSlots) * a.TS + m) * kSlotBytes + lane * 8,
-                                                  0, kCoherent);
-        }
+        if (lane < kPartial)
+            pair_store(xt + ((n % kSlots) * a.TS + m) * kPartial + lane, w, a.tag_base + (unsigned)n);
     }
     if (have_add) {
-#pragma unroll
-        for (int u = 0; u < kR; ++u) {
-            const float2 w2 = s_res[t & 1][u];
-#pragma unroll
-            for (int q = 0; q < kV; ++q) {
-                const float4 x4 = R.xb[JA][u][q];
-                R.ag[q].x += w2.x * x4.x; R.ag[q].y += w2.x * x4.y; R.ag[q].z += w2.x * x4.z; R.ag[q].w += w2.x * x4.w;
-                R.as[q].x += w2.y * x4.x; R.as[q].y += w2.y * x4.y; R.as[q].z += w2.y * x4.z; R.as[q].w += w2.y * x4.w;
-            }
+        if (S.tA == S.ntile - 1) {
+            __syncthreads();                     // the data waves' barrier at the end of a group
+            double l = lane < kR ? lacc : 0.0;
+            l = wave_sum(l);
+            if (m == 0 && lane == 0) a.part_loss[S.gA] = l;
+            lacc = 0;
+            S.tA = 0;
+            S.gA += a.NT;
+        } else {
+            ++S.tA;
         }
     }
 }
 
-// grid: NT * TS workgroups of 512 threads, all resident at once (checked on the host).
+// grid: NT * TS workgroups of 576 threads (eight data waves and a control wave), all resident
+// at once (checked on the host); dynamic LDS: kParkBytes.
 __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
 {
-    __shared__ float s_dot[2][kWaves][kPartial];  // per-wave partial dots, by parity of the tile
-    __shared__ float2 s_res[2][kR];               // residuals (r, dr), by parity of the stage
-    __shared__ double s_red[kWaves];
+    extern __shared__ float4 park[];
+    __shared__ TeamLds L;
 
     const Hyper& hy = a.hy;
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: the role branch is scalar
     int team, m;
     team_of(blockIdx.x, a.TS, a.NT * a.TS, team, m);
-    const int mu = hy.mu;
-    const int col = m * kSlab + wave * (256 * kV) + lane * 4;    // and col + 256
-    const int ntile = mu / kR;
-    __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
-        (char*)a.xch + (int64_t)team * kSlots * a.TS * kSlotBytes, 0, kSlots * a.TS * kSlotBytes, 0x00020000);
-    unsigned seq0 = 0;                           // sequence number of the group's first tile
-    bool gave_up = false;                        // wave 0: a bounded wait was exhausted
-    typedef const int32_t __attribute__((address_space(4))) const_i32;
+    if (team >= hy.G) return;                    // the whole team leaves: nobody waits for it
 
-    TeamRegs R;
-#pragma unroll
-    for (int q = 0; q < kV; ++q)
-        R.th4[q] = *(const float4*)(a.ring + (int64_t)hy.cur * hy.pstride + col + 256 * q);
-#pragma unroll
-    for (int j = 0; j < kTiles; ++j) R.yl[j] = 1.0f;
+    // stages 0 .. ntot+1 (the last two only drain), three at a time; stages past the end do
+    // nothing but request the last tile again
+    const int ntile = hy.mu / kR;
+    const int ntot = ((hy.G - team + a.NT - 1) / a.NT) * ntile;
+    const int nstage = ntot + 2;
 
-    for (int g = team; g < hy.G; g += a.NT, seq0 += (unsigned)ntile) {
-        const ShardDesc sh = a.shards[g];
-        {
-            const float* stale = a.ring + (int64_t)stale_slot_of(hy, a.tau[g]) * hy.pstride + col;
-#pragma unroll
-            for (int q = 0; q < kV; ++q) {
-                const float4 u4 = *(const float4*)(stale + 256 * q);
-                R.dl4[q] = make_float4(R.th4[q].x - u4.x, R.th4[q].y - u4.y, R.th4[q].z - u4.z, R.th4[q].w - u4.w);
-                R.ag[q] = make_float4(0, 0, 0, 0);
-                R.as[q] = make_float4(0, 0, 0, 0);
-            }
+    if (wave == kDataWaves) {
+        TeamSeq S;
+        S.ntile = ntile; S.ntot = ntot;
+        S.gF = S.gC = S.gA = team;
+        S.tF = S.tC = S.tA = 0;
+        // ---- control wave ----
+        unsigned long long* xt = a.xch + (int64_t)team * kSlots * a.TS * kPartial;   // the team's slots
+        bool gave_up = false;                    // a bounded wait was exhausted
+        float y_new = 1.0f;
+        double lacc = 0;
+        if (lane < kR) L.s_y[0][lane] = team_load_label(a, S, lane);
+        team_advance(S, 1, a.NT);
+        if (lane < kR) y_new = team_load_label(a, S, lane);
+        team_advance(S, 2, a.NT);
+        for (int n = 0; n < nstage; n += kRegTiles) {
+            team_control_stage(a, S, xt, n, m, gave_up, y_new, lacc, L);
+            team_control_stage(a, S, xt, n + 1, m, gave_up, y_new, lacc, L);
+            team_control_stage(a, S, xt, n + 2, m, gave_up, y_new, lacc, L);
         }
-        R.lacc = 0;
-        // cyclic window: first row of this step's window, (k * mu) mod rows, in 32 bits
-        const unsigned cyc_base = (unsigned)((((unsigned long long)hy.k % (unsigned long long)sh.rows) *
-                                              ((unsigned long long)mu % (unsigned long long)sh.rows)) %
-                                             (unsigned long long)sh.rows);
-        // prologue: tile 0 starts loading, row ids of tile 1
-#pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-#pragma unroll
-            for (int u = 0; u < kR; ++u) {
-                int rr = 0;
-                if (pass < ntile) {
-                    if (a.idx) rr = ((const_i32*)(uintptr_t)a.idx)[(int64_t)g * mu + pass * kR + u];
-                    else rr = (int)((cyc_base + (unsigned)(pass * kR + u)) % (unsigned)sh.rows);
-                }
-                R.rows_nxt[u] = __builtin_amdgcn_readfirstlane(rr);
-            }
-            if (pass == 0) {
-                if (wave == 0 && lane < kR) {
-                    int myrow = R.rows_nxt[0];
-#pragma unroll
-                    for (int u = 1; u < kR; ++u) myrow = lane == u ? R.rows_nxt[u] : myrow;
-                    R.yl[0] = global_load((const float*)sh.y + myrow);
-                }
-#pragma unroll
-                for (int u = 0; u < kR; ++u) {
-                    const float* xrow = (const float*)sh.X + (int64_t)R.rows_nxt[u] * sh.ld + col;
-#pragma unroll
-                    for (int q = 0; q < kV; ++q) R.xb[0][u][q] = global_load4(xrow + 256 * q);
-                }
-            }
-        }
-        // stages 0 .. ntile+1 (the last two only drain)
-        const int last = ntile + 1;
-        for (int t = 0; t <= last; t += kTiles) {
-            team_stage<0>(a, R, sh, xr, t, ntile, g, m, col, seq0, cyc_base, gave_up, s_dot, s_res);
-            if (t + 1 > last) break;
-            team_stage<1>(a, R, sh, xr, t + 1, ntile, g, m, col, seq0, cyc_base, gave_up, s_dot, s_res);
-            if (t + 2 > last) break;
-            team_stage<2>(a, R, sh, xr, t + 2, ntile, g, m, col, seq0, cyc_base, gave_up, s_dot, s_res);
-            if (t + 3 > last) break;
-            team_stage<3>(a, R, sh, xr, t + 3, ntile, g, m, col, seq0, cyc_base, gave_up, s_dot, s_res);
-        }
-
-        // the group is finished: this member's 4096 columns of the gradient and of s_g
-        double sq = 0;
-        float* out = fresh_row(a.gbuf, a.which, hy, g) + col;
+    } else {
+        // ---- data waves ----
+        TeamSeq S;
+        S.ntile = ntile; S.ntot = ntot;
+        S.gF = S.gC = S.gA = team;
+        S.tF = S.tC = S.tA = 0;
+        const int col = m * kSlab + wave * (256 * kV) + lane * 4;    // and col + 256
+        TeamRegs R;
 #pragma unroll
         for (int q = 0; q < kV; ++q) {
-            if (hy.l2 != 0.0f) {
-                const float ml = (float)mu * hy.l2;
-                R.ag[q].x += ml * R.th4[q].x; R.ag[q].y += ml * R.th4[q].y; R.ag[q].z += ml * R.th4[q].z; R.ag[q].w += ml * R.th4[q].w;
-                R.as[q].x += ml * R.dl4[q].x; R.as[q].y += ml * R.dl4[q].y; R.as[q].z += ml * R.dl4[q].z; R.as[q].w += ml * R.dl4[q].w;
-            }
-            *(float4*)(out + 256 * q) = R.ag[q];
-            sq += (double)R.as[q].x * R.as[q].x + (double)R.as[q].y * R.as[q].y + (double)R.as[q].z * R.as[q].z +
-                  (double)R.as[q].w * R.as[q].w;
+            R.th4[q] = *(const float4*)(a.ring + (int64_t)hy.cur * hy.pstride + col + 256 * q);
+            R.ag[q] = make_float4(0, 0, 0, 0);
+            R.as[q] = make_float4(0, 0, 0, 0);
+            R.dl4[q] = make_float4(0, 0, 0, 0);
         }
-        sq = wave_sum(sq);
-        __syncthreads();
-        if (lane == 0) s_red[wave] = sq;
-        __syncthreads();
-        if (tid == 0) {
-            double tsum = 0;
-            for (int wv = 0; wv < kWaves; ++wv) tsum += s_red[wv];
-            a.part_stat[(int64_t)g * a.TS + m] = tsum;
+        // prologue: tiles 0 and 1 start loading (there are at least two), tile 2 is described
+        team_fetch(a, S, 0, a.NT);
+        team_load_tile<0>(R, S, col);
+        team_fetch(a, S, 1, a.NT);
+        team_load_tile<1>(R, S, col);
+        team_fetch(a, S, 2, a.NT);
+        for (int n = 0; n < nstage; n += kRegTiles) {
+            team_data_stage<0>(a, R, S, n, m, col, L, park);
+            team_data_stage<1>(a, R, S, n + 1, m, col, L, park);
+            team_data_stage<2>(a, R, S, n + 2, m, col, L, park);
         }
-        if (m == 0 && wave == 0) {
-            double l = lane < kR ? R.lacc : 0.0;
-            l = wave_sum(l);
-            if (lane == 0) a.part_loss[g] = l;
-        }
-        __syncthreads();
     }
 }
 
@@ -327,24 +447,26 @@ __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
 
 struct LrTeamPlan {
     int TS = 0, NT = 0;      // TS = 0: not applicable
-    void* xch = nullptr;
+    unsigned long long* xch = nullptr;
 };
 
 // Decide whether the team kernel applies (d a multiple of 4096 and at least 8192, mu a multiple
-// of the tile's rows, a whole number of teams fits the device with every workgroup resident).
+// of the tile's rows and at least two tiles, a whole number of teams fits the device with every workgroup resident).
 hipError_t lr_team_plan(gcada_ctx* c)
 {
     auto* pl = new LrTeamPlan();
     c->lr_team = pl;
     const int d = (int)c->hy.p, mu = c->hy.mu;
-    if (d % kSlab || d < 2 * kSlab || mu % kR) return hipSuccess;
+    if (d % kSlab || d < 2 * kSlab || mu % kR || mu < 2 * kR) return hipSuccess;
     const int TS = d / kSlab;
     if (TS * kR > kWave) return hipSuccess;          // one wave polls all members' partials
     hipDeviceProp_t prop;
     hipError_t e = hipGetDeviceProperties(&prop, c->device);
     if (e != hipSuccess) return e;
     int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)lr_team_kernel, kThreads, 0);
+    e = hipFuncSetAttribute((const void*)lr_team_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kParkBytes);
+    if (e != hipSuccess) return e;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)lr_team_kernel, kThreads, kParkBytes);
     if (e != hipSuccess) return e;
     const int cap = per_cu > 0 ? prop.multiProcessorCount : 0;     // one workgroup per CU
     const int NT = cap / TS;
@@ -396,7 +518,7 @@ hipError_t lr_team_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
     const unsigned tiles = (unsigned)((c->hy.G + pl->NT - 1) / pl->NT) * (unsigned)(c->hy.mu / kR);
     a.tag_base = (unsigned)((c->team_launches++ % 4095u) + 1u) << 20;
     if (tiles >= (1u << 20)) return hipErrorInvalidValue;
-    lr_team_kernel<<<pl->NT * pl->TS, kThreads, 0, s>>>(a);
+    lr_team_kernel<<<pl->NT * pl->TS, kThreads, kParkBytes, s>>>(a);
     c->n_stat_used = pl->TS;
     c->n_loss_used = c->hy.G;
     return hipGetLastError();

@@ -84,15 +84,38 @@ struct Layout {
 };
 
 // ---------------------------------------------------------------------------------------
-// GEMM  C[M][N] = sum_k P[M][k] Q[N][k],  128 x 128 tile, 256 threads = 2 x 2 waves of 64 x 64.
-// A row of a tile in LDS is 128 bytes of k (64 bf16 or 32 floats) plus 16 bytes of padding.
-constexpr int kBM = 128, kBN = 128;
-constexpr int kRowBytes = 128, kRowPitch = 144;
-constexpr int kTileBytes = kBM * kRowPitch;               // 18432
-constexpr int kGemmThreads = 256;
-constexpr int kGemmLds = 4 * kTileBytes;                  // P,Q x two stages = 73728
+// GEMM  C[M][N] = sum_k P[M][k] Q[N][k],  BM x BN tile, WM x WN waves, each wave
+// (BM/WM) x (BN/WN) as TM x TN blocks of 32 x 32.  A row of a tile in LDS is KROW bytes of k plus
+// 16 bytes of padding.  Two LDS stages; PF = k-tiles in flight in registers ahead of the one
+// being multiplied (1 or 2).
+template <int BM_, int BN_, int KROW_, int WM_ = 2, int WN_ = 2, int PF_ = 1>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, KROW = KROW_, WM = WM_, WN = WN_, PF = PF_;
+    static constexpr int NW = WM * WN, NT = NW * 64;          // waves, threads
+    static constexpr int PITCH = KROW + 16;
+    static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    static constexpr int CPR = KROW / 16;                    // 16-byte chunks per row
+    static constexpr int PCH = BM * CPR / NT, QCH = BN * CPR / NT;     // chunks per thread
+    static constexpr int KS = KROW / 32;                     // 32-byte k-steps per tile
+    static constexpr int STAGE = (BM + BN) * PITCH;
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && (BM * CPR) % NT == 0 && (BN * CPR) % NT == 0, "tile");
+    static_assert(PF == 1 || PF == 2, "prefetch distance");
+};
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kHeadClasses = 128;             // the output layer's classes fit one tile
 
 enum { EPI_FWD = 0, EPI_DA = 1, EPI_DW = 2, EPI_HEAD = 3 };
+
+constexpr int cmax(int x, int y) { return x > y ? x : y; }
+// dynamic LDS of a kernel: the two k-loop stages, or what its epilogue stages there
+template <typename T, int EPI, typename TL>
+constexpr int gemm_lds_bytes()
+{
+    const int loop = 2 * TL::STAGE;
+    if (EPI == EPI_DW) return cmax(loop, 8 * TL::NW);
+    if (EPI == EPI_HEAD) return cmax(loop, TL::BM * (TL::BN + 4) * 4 + 8 * TL::NW);
+    return cmax(loop, TL::BM * (TL::BN + 8) * (int)sizeof(T));
+}
 
 struct GemmArgs {
     Hyper hy;
@@ -140,77 +163,122 @@ __device__ __forceinline__ void mfma_step<float>(const uint4& a, const uint4& b,
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
 }
 
-// global -> registers: 4 chunks of 16 bytes per operand per thread (one 128 x 128-byte k-tile)
+// global -> registers: the 16-byte chunks of one k-tile of both operands.  (Native vector
+// registers: arrays of the HIP uint4 struct are not always kept in registers.)
+template <typename TL>
 __device__ __forceinline__ void tile_gload(const char* __restrict__ Pg, const char* __restrict__ Qg,
-                                           int64_t ldp_b, int64_t ldq_b, int kt, uint4 (&rp)[4],
-                                           uint4 (&rq)[4])
+                                           int64_t ldp_b, int64_t ldq_b, int kt, u32x4 (&rp)[TL::PCH],
+                                           u32x4 (&rq)[TL::QCH])
 {
     const int tid = threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = tid + kGemmThreads * i, row = c >> 3, kc = c & 7;
-        rp[i] = *(const uint4*)(Pg + (int64_t)row * ldp_b + (int64_t)kt * kRowBytes + kc * 16);
-        rq[i] = *(const uint4*)(Qg + (int64_t)row * ldq_b + (int64_t)kt * kRowBytes + kc * 16);
+    for (int i = 0; i < TL::PCH; ++i) {
+        const int c = tid + TL::NT * i, row = c / TL::CPR, kc = c % TL::CPR;
+        rp[i] = *(const u32x4*)(Pg + (int64_t)row * ldp_b + (int64_t)kt * TL::KROW + kc * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < TL::QCH; ++i) {
+        const int c = tid + TL::NT * i, row = c / TL::CPR, kc = c % TL::CPR;
+        rq[i] = *(const u32x4*)(Qg + (int64_t)row * ldq_b + (int64_t)kt * TL::KROW + kc * 16);
     }
 }
 
-__device__ __forceinline__ void tile_lstore(char* lp, char* lq, const uint4 (&rp)[4], const uint4 (&rq)[4])
+template <typename TL>
+__device__ __forceinline__ void tile_lstore(char* lp, char* lq, const u32x4 (&rp)[TL::PCH],
+                                            const u32x4 (&rq)[TL::QCH])
 {
     const int tid = threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = tid + kGemmThreads * i, row = c >> 3, kc = c & 7;
-        *(uint4*)(lp + row * kRowPitch + kc * 16) = rp[i];
-        *(uint4*)(lq + row * kRowPitch + kc * 16) = rq[i];
+    for (int i = 0; i < TL::PCH; ++i) {
+        const int c = tid + TL::NT * i, row = c / TL::CPR, kc = c % TL::CPR;
+        *(u32x4*)(lp + row * TL::PITCH + kc * 16) = rp[i];
+    }
+#pragma unroll
+    for (int i = 0; i < TL::QCH; ++i) {
+        const int c = tid + TL::NT * i, row = c / TL::CPR, kc = c % TL::CPR;
+        *(u32x4*)(lq + row * TL::PITCH + kc * 16) = rq[i];
     }
 }
 
-template <typename T>
-__device__ __forceinline__ void tile_mma(const char* lp, const char* lq, f32x16 (&acc)[2][2])
+template <typename T, typename TL>
+__device__ __forceinline__ void tile_mma(const char* lp, const char* lq, f32x16 (&acc)[TL::TM][TL::TN])
 {
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int wm = wave / 2, wn = wave % 2;
+    const int wm = wave / TL::WN, wn = wave % TL::WN;
     const int half = lane >> 5, r = lane & 31;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        uint4 a[2], b[2];
+    for (int ks = 0; ks < TL::KS; ++ks) {
+        uint4 a[TL::TM], b[TL::TN];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            a[i] = *(const uint4*)(lp + (wm * 64 + i * 32 + r) * kRowPitch + ks * 32 + half * 16);
-            b[i] = *(const uint4*)(lq + (wn * 64 + i * 32 + r) * kRowPitch + ks * 32 + half * 16);
-        }
+        for (int i = 0; i < TL::TM; ++i)
+            a[i] = *(const uint4*)(lp + (wm * (TL::BM / TL::WM) + i * 32 + r) * TL::PITCH + ks * 32 + half * 16);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < TL::TN; ++j)
+            b[j] = *(const uint4*)(lq + (wn * (TL::BN / TL::WN) + j * 32 + r) * TL::PITCH + ks * 32 + half * 16);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) mfma_step<T>(a[i], b[j], acc[i][j]);
+        for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TL::TN; ++j) mfma_step<T>(a[i], b[j], acc[i][j]);
     }
 }
 
-// One pass of the k-loop for a 128x128 tile: acc[2][2] (per wave 64x64) += P_tile Q_tile^T.
-// Two LDS stages; the next k-tile travels global -> registers while the current one is multiplied.
-template <typename T>
+// One pass of the k-loop for a tile: acc += P_tile Q_tile^T.  Two LDS stages.  PF = 1: the next
+// k-tile travels global -> registers while the current one is multiplied.  PF = 2: two k-tiles
+// are in flight in two register sets, which covers the load latency when the multiply of one
+// k-tile is shorter than a trip to L2 / HBM.  Loads past the last k-tile repeat the last one.
+template <typename T, typename TL>
 __device__ __forceinline__ void gemm_mainloop(const char* __restrict__ Pg, const char* __restrict__ Qg,
                                               int64_t ldp_b, int64_t ldq_b, int K, char* lds,
-                                              f32x16 (&acc)[2][2])
+                                              f32x16 (&acc)[TL::TM][TL::TN])
 {
-    constexpr int kElemsPerTileK = kRowBytes / (int)sizeof(T);
+    constexpr int kElemsPerTileK = TL::KROW / (int)sizeof(T);
+    constexpr int kP = TL::BM * TL::PITCH;
     const int nk = (K + kElemsPerTileK - 1) / kElemsPerTileK;
-    uint4 rp[4], rq[4];
-    tile_gload(Pg, Qg, ldp_b, ldq_b, 0, rp, rq);
-    tile_lstore(lds, lds + kTileBytes, rp, rq);
-    __syncthreads();
-    for (int kt = 0; kt + 1 < nk; ++kt) {
-        char* cur = lds + (kt & 1) * 2 * kTileBytes;
-        char* nxt = lds + ((kt + 1) & 1) * 2 * kTileBytes;
-        tile_gload(Pg, Qg, ldp_b, ldq_b, kt + 1, rp, rq);
-        tile_mma<T>(cur, cur + kTileBytes, acc);
-        tile_lstore(nxt, nxt + kTileBytes, rp, rq);
+    if constexpr (TL::PF == 1) {
+        u32x4 rp[TL::PCH], rq[TL::QCH];
+        tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, 0, rp, rq);
+        tile_lstore<TL>(lds, lds + kP, rp, rq);
         __syncthreads();
-    }
-    {
-        const char* cur = lds + ((nk - 1) & 1) * 2 * kTileBytes;
-        tile_mma<T>(cur, cur + kTileBytes, acc);
+        for (int kt = 0; kt + 1 < nk; ++kt) {
+            char* cur = lds + (kt & 1) * TL::STAGE;
+            char* nxt = lds + ((kt + 1) & 1) * TL::STAGE;
+            tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, kt + 1, rp, rq);
+            tile_mma<T, TL>(cur, cur + kP, acc);
+            tile_lstore<TL>(nxt, nxt + kP, rp, rq);
+            __syncthreads();
+        }
+        {
+            const char* cur = lds + ((nk - 1) & 1) * TL::STAGE;
+            tile_mma<T, TL>(cur, cur + kP, acc);
+            __syncthreads();
+        }
+    } else {
+        u32x4 rp0[TL::PCH], rq0[TL::QCH], rp1[TL::PCH], rq1[TL::QCH];
+        const int last = nk - 1;
+        tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, 0, rp0, rq0);
+        tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, last < 1 ? last : 1, rp1, rq1);
+        tile_lstore<TL>(lds, lds + kP, rp0, rq0);
         __syncthreads();
+        // iteration kt: request tile kt+2 into the set tile kt came from, multiply tile kt,
+        // move tile kt+1 from its set to the other LDS stage
+        for (int kt = 0; kt < nk; kt += 2) {
+            {
+                char* cur = lds;
+                char* nxt = lds + TL::STAGE;
+                tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, kt + 2 < last ? kt + 2 : last, rp0, rq0);
+                tile_mma<T, TL>(cur, cur + kP, acc);
+                tile_lstore<TL>(nxt, nxt + kP, rp1, rq1);
+                __syncthreads();
+            }
+            if (kt + 1 < nk) {
+                char* cur = lds + TL::STAGE;
+                char* nxt = lds;
+                tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, kt + 3 < last ? kt + 3 : last, rp1, rq1);
+                tile_mma<T, TL>(cur, cur + kP, acc);
+                tile_lstore<TL>(nxt, nxt + kP, rp0, rq0);
+                __syncthreads();
+            }
+        }
     }
 }
 
@@ -219,66 +287,79 @@ __device__ __forceinline__ int stale_slot(const Hyper& hy, const int32_t* tau, i
     return stale_slot_of(hy, tau[g]);
 }
 
-// grid: (ceil(N/128), ceil(M/128), batch);  batch = 2G (it*G + g) for FWD / DA, G for DW.
-template <typename T, int EPI>
-__global__ __launch_bounds__(kGemmThreads) void mlp_gemm(GemmArgs a)
+// acc += P Q^T over the whole k range, operands of iterate `it` (0: theta^k, 1: the group's
+// stale iterate) of group g, tile origin (m0, n0)
+template <typename T, typename TL>
+__device__ __forceinline__ void gemm_pass(const GemmArgs& a, int it, int g, int m0, int n0, char* lds,
+                                          f32x16 (&acc)[TL::TM][TL::TN])
+{
+    constexpr int esz = (int)sizeof(T);
+    const char* Pg = (const char*)a.P + ((int64_t)it * a.p_it + (int64_t)g * a.p_g + (int64_t)m0 * a.ldp) * esz;
+    const char* Qg;
+    if (a.q_is_weight) {
+        const int slot = it == 0 ? a.hy.cur : stale_slot(a.hy, a.tau, g);
+        Qg = (const char*)a.Q + ((int64_t)slot * a.q_slot + (int64_t)n0 * a.ldq) * esz;
+    } else {
+        Qg = (const char*)a.Q + ((int64_t)it * a.q_it + (int64_t)g * a.q_g + (int64_t)n0 * a.ldq) * esz;
+    }
+    gemm_mainloop<T, TL>(Pg, Qg, (int64_t)a.ldp * esz, (int64_t)a.ldq * esz, a.K, lds, acc);
+}
+
+// grid: (ceil(N/BN), ceil(M/BM), batch);  batch = 2G (it*G + g) for FWD / DA / HEAD, G for DW.
+template <typename T, int EPI, typename TL>
+__global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
 {
     extern __shared__ __align__(16) char lds[];
+    constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN;
     const Hyper& hy = a.hy;
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int wm = wave / 2, wn = wave % 2;
-    const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
+    constexpr int kGemmThreads = TL::NT, RW = BM / TL::WM, CW = BN / TL::WN;   // rows, columns per wave
+    const int wm = wave / TL::WN, wn = wave % TL::WN;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     constexpr int esz = (int)sizeof(T);
 
-    f32x16 acc[2][2];
-    f32x16 acc_s[2][2];     // DW: stale-iterate accumulators
-    const int n_it = EPI == EPI_DW ? 2 : 1;
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
     int g, it0;
-    if (EPI == EPI_DW) { g = blockIdx.z; it0 = 1; } else { g = blockIdx.z % a.G; it0 = blockIdx.z / a.G; }
-
-    for (int pass = 0; pass < n_it; ++pass) {
-        const int it = EPI == EPI_DW ? 1 - pass : it0;      // DW: stale first, then fresh
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-        const char* Pg = (const char*)a.P + ((int64_t)it * a.p_it + (int64_t)g * a.p_g + (int64_t)m0 * a.ldp) * esz;
-        const char* Qg;
-        if (a.q_is_weight) {
-            const int slot = it == 0 ? hy.cur : stale_slot(hy, a.tau, g);
-            Qg = (const char*)a.Q + ((int64_t)slot * a.q_slot + (int64_t)n0 * a.ldq) * esz;
-        } else {
-            Qg = (const char*)a.Q + ((int64_t)it * a.q_it + (int64_t)g * a.q_g + (int64_t)n0 * a.ldq) * esz;
-        }
-        gemm_mainloop<T>(Pg, Qg, (int64_t)a.ldp * esz, (int64_t)a.ldq * esz, a.K, lds, acc);
-        if (EPI == EPI_DW && pass == 0) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc_s[i][j] = acc[i][j];
-        }
-    }
-
+    if (EPI == EPI_DW) { g = blockIdx.z; it0 = 0; } else { g = blockIdx.z % a.G; it0 = blockIdx.z / a.G; }
     // accumulator element e of lane: column n = lane % 32, row m = (e/4)*8 + (lane/32)*4 + e%4
     const int cl = lane & 31, rh = (lane >> 5) * 4;
+
     if constexpr (EPI == EPI_DW) {
-        double sq = 0;
+        // The transposed signal of the stale iterate is stored NEGATED by the kernel that
+        // produces it.  So: multiply at theta^k, write the fresh gradient block, then keep
+        // accumulating the stale products into the same registers, which then hold
+        // fresh - stale -- one accumulator set serves both iterates.
+        gemm_pass<T, TL>(a, 0, g, m0, n0, lds, acc);
         float* gb = fresh_row(a.gbuf, a.which, hy, g) + a.goff;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int m = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + rh + (e & 3);
-                    const int n = n0 + wn * 64 + j * 32 + cl;
+                    const int m = m0 + wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
+                    const int n = n0 + wn * CW + j * 32 + cl;
+                    if (m < a.M && n < a.N) gb[(int64_t)m * a.N + n] = acc[i][j][e];
+                }
+        gemm_pass<T, TL>(a, 1, g, m0, n0, lds, acc);
+        double sq = 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = m0 + wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
+                    const int n = n0 + wn * CW + j * 32 + cl;
                     if (m < a.M && n < a.N) {
-                        const float f = acc[i][j][e];
-                        const float df = f - acc_s[i][j][e];
+                        const float df = acc[i][j][e];
                         sq += (double)df * (double)df;
-                        gb[(int64_t)m * a.N + n] = f;
                     }
                 }
         sq = wave_sum(sq);
@@ -286,24 +367,31 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm(GemmArgs a)
         __syncthreads();
         if (lane == 0) red[wave] = sq;
         __syncthreads();
-        if (tid == 0)
-            a.part_stat[(int64_t)g * a.n_stat + a.stat_off + blockIdx.y * gridDim.x + blockIdx.x] =
-                red[0] + red[1] + red[2] + red[3];
-    } else if constexpr (EPI == EPI_HEAD) {
+        if (tid == 0) {
+            double t = 0;
+#pragma unroll
+            for (int wv = 0; wv < TL::NW; ++wv) t += red[wv];
+            a.part_stat[(int64_t)g * a.n_stat + a.stat_off + blockIdx.y * gridDim.x + blockIdx.x] = t;
+        }
+        return;
+    }
+    gemm_pass<T, TL>(a, it0, g, m0, n0, lds, acc);
+    if constexpr (EPI == EPI_HEAD) {
         // logits tile -> LDS (fp32), then one thread per sample: softmax cross-entropy and dZ_L
-        constexpr int pitch = kBN + 4;
+        static_assert(BN == kHeadClasses && BM <= TL::NT, "output-layer tile");
+        constexpr int pitch = BN + 4;
         float* lg = (float*)lds;
         const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
         const float* bias = a.ring + (int64_t)slot * hy.pstride + a.boff;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int nl = wn * 64 + j * 32 + cl;
+            for (int j = 0; j < TN; ++j) {
+                const int nl = wn * CW + j * 32 + cl;
                 const float bv = nl < a.N ? round_to<T>(bias[nl]) : 0.0f;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int ml = wm * 64 + i * 32 + (e >> 2) * 8 + rh + (e & 3);
+                    const int ml = wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
                     lg[ml * pitch + nl] = acc[i][j][e] + bv;
                 }
             }
@@ -312,14 +400,14 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm(GemmArgs a)
         T* OT = (T*)a.OT + (int64_t)it0 * a.t_it + (int64_t)g * a.t_g;      // dZ_L^T [N][ldt]
         double lsum = 0;
         const int nc = a.N;
-        if (tid < kBM && m0 + tid < a.M) {
+        if (tid < BM && m0 + tid < a.M) {
             const int i = m0 + tid;
             const ShardDesc sh = a.shards[g];
             int64_t row;
             if (a.idx) row = a.idx[(int64_t)g * hy.mu + i];
             else row = (int64_t)(((unsigned long long)hy.k * (unsigned long long)hy.mu +
                                   (unsigned long long)i) % (unsigned long long)sh.rows);
-            const int y = ((const int32_t*)sh.y)[row];
+            const int y = global_load((const int32_t*)sh.y + row);
             float* z = lg + tid * pitch;
             // Everything relative to the true class, so that a confidently right sample
             // (p_y -> 1) loses no digits: t_c = z_c - z_y, m = max_c t_c >= 0,
@@ -343,82 +431,146 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm(GemmArgs a)
             z[y] = -others;
             lsum = m == 0.0f ? (double)log1pf(so) : (double)(m + logf(ey + so));
             for (int c = 0; c < nc; ++c) O[(int64_t)i * a.ldo + c] = to_T<T>(z[c]);
-        } else if (tid < kBM) {
+        } else if (tid < BM) {
             for (int c = 0; c < nc; ++c) lg[tid * pitch + c] = 0.0f;
         }
         lsum = wave_sum(lsum);
         __syncthreads();
-        double* red = (double*)(lg + kBM * pitch);
+        double* red = (double*)(lg + BM * pitch);
         if (lane == 0) red[wave] = lsum;
-        // transposed copy: class c, samples m0 .. m0+127 (zeros beyond M keep the padding clean)
+        // transposed copy: class c, samples m0 .. m0+BM-1 (zeros beyond M keep the padding clean);
+        // negated for the stale iterate (the weight-gradient kernel subtracts by accumulating)
+        const float tsign = it0 == 1 ? -1.0f : 1.0f;
         constexpr int V = 16 / esz;
-        for (int c2 = tid; c2 < nc * (kBM / V); c2 += kGemmThreads) {
-            const int c = c2 / (kBM / V), mv = (c2 % (kBM / V)) * V;
+        for (int c2 = tid; c2 < nc * (BM / V); c2 += kGemmThreads) {
+            const int c = c2 / (BM / V), mv = (c2 % (BM / V)) * V;
             if (m0 + mv < a.M) {
                 alignas(16) T tmp[V];
 #pragma unroll
-                for (int q = 0; q < V; ++q) tmp[q] = to_T<T>(lg[(mv + q) * pitch + c]);
+                for (int q = 0; q < V; ++q) tmp[q] = to_T<T>(tsign * lg[(mv + q) * pitch + c]);
                 *(uint4*)(OT + (int64_t)c * a.ldt + m0 + mv) = *(const uint4*)tmp;
             }
         }
         __syncthreads();
-        if (it0 == 0 && tid == 0)
-            a.part_loss[(int64_t)g * gridDim.y + blockIdx.y] = red[0] + red[1] + red[2] + red[3];
+        if (it0 == 0 && tid == 0) {
+            double t = 0;
+#pragma unroll
+            for (int wv = 0; wv < TL::NW; ++wv) t += red[wv];
+            a.part_loss[(int64_t)g * gridDim.y + blockIdx.y] = t;
+        }
     } else {
-        // stage the tile in LDS as T [128][128 + 8], then write it row-major and transposed
-        constexpr int pitch = kBN + 8;
+        // stage the tile in LDS as T [BM][BN + 8], then write it row-major and transposed
+        constexpr int pitch = BN + 8;
+        constexpr int V = 16 / esz;                 // elements per 16-byte vector
         T* st = (T*)lds;
         const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
         const float* bias = EPI == EPI_FWD ? a.ring + (int64_t)slot * hy.pstride + a.boff : nullptr;
-        const T* mk = EPI == EPI_DA
-            ? (const T*)a.maskp + (int64_t)it0 * a.m_it + (int64_t)g * a.m_g : nullptr;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int nl = wn * 64 + j * 32 + cl, n = n0 + nl;
+            for (int j = 0; j < TN; ++j) {
+                const int nl = wn * CW + j * 32 + cl, n = n0 + nl;
                 float bv = 0.0f;
                 if (EPI == EPI_FWD && n < a.N) bv = round_to<T>(bias[n]);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int ml = wm * 64 + i * 32 + (e >> 2) * 8 + rh + (e & 3), m = m0 + ml;
+                    const int ml = wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
                     float v = acc[i][j][e];
                     if (EPI == EPI_FWD) v = fmaxf(v + bv, 0.0f);
-                    if (EPI == EPI_DA) {
-                        const bool on = (m < a.M && n < a.N) && to_f<T>(mk[(int64_t)m * a.ldm + n]) > 0.0f;
-                        v = on ? v : 0.0f;
-                    }
                     st[ml * pitch + nl] = to_T<T>(v);
                 }
             }
         __syncthreads();
         T* O = (T*)a.O + (int64_t)it0 * a.o_it + (int64_t)g * a.o_g;
         T* OT = (T*)a.OT + (int64_t)it0 * a.t_it + (int64_t)g * a.t_g;
-        constexpr int V = 16 / esz;                 // elements per 16-byte vector
-        // row-major: 128 rows x (128 / V) vectors
-        for (int c = tid; c < kBM * (kBN / V); c += kGemmThreads) {
-            const int ml = c / (kBN / V), nv = (c % (kBN / V)) * V;
+        const T* mk = EPI == EPI_DA
+            ? (const T*)a.maskp + (int64_t)it0 * a.m_it + (int64_t)g * a.m_g : nullptr;
+        // row-major: BM rows x (BN / V) vectors.  DA: the ReLU mask (the layer's activations,
+        // same layout as the output) is applied here, 16 bytes at a time, and the masked values
+        // go back to the staging tile for the transposed pass.
+        for (int c = tid; c < BM * (BN / V); c += kGemmThreads) {
+            const int ml = c / (BN / V), nv = (c % (BN / V)) * V;
             const int m = m0 + ml, n = n0 + nv;
             if (m < a.M && n < a.N) {
                 // ldo is a multiple of 64 and pads stay zero: mask the lanes beyond N
                 alignas(16) T tmp[V];
+                alignas(16) T act[V];
+                if (EPI == EPI_DA) *(uint4*)act = *(const uint4*)(mk + (int64_t)m * a.ldm + n);
 #pragma unroll
-                for (int q = 0; q < V; ++q) tmp[q] = (n + q < a.N) ? st[ml * pitch + nv + q] : to_T<T>(0.0f);
+                for (int q = 0; q < V; ++q) {
+                    T v = (n + q < a.N) ? st[ml * pitch + nv + q] : to_T<T>(0.0f);
+                    if (EPI == EPI_DA) {
+                        if (!(to_f<T>(act[q]) > 0.0f)) v = to_T<T>(0.0f);
+                        st[ml * pitch + nv + q] = v;
+                    }
+                    tmp[q] = v;
+                }
                 *(uint4*)(O + (int64_t)m * a.ldo + n) = *(const uint4*)tmp;
+            } else if (EPI == EPI_DA) {
+#pragma unroll
+                for (int q = 0; q < V; ++q) st[ml * pitch + nv + q] = to_T<T>(0.0f);
             }
         }
-        // transposed: 128 columns x (128 / V) vectors along m
-        for (int c = tid; c < kBN * (kBM / V); c += kGemmThreads) {
-            const int nl = c / (kBM / V), mv = (c % (kBM / V)) * V;
+        if (EPI == EPI_DA) __syncthreads();
+        // transposed: BN columns x (BM / V) vectors along m
+        for (int c = tid; c < BN * (BM / V); c += kGemmThreads) {
+            const int nl = c / (BM / V), mv = (c % (BM / V)) * V;
             const int n = n0 + nl, m = m0 + mv;
             if (n < a.N && m < a.M) {
                 alignas(16) T tmp[V];
 #pragma unroll
-                for (int q = 0; q < V; ++q) tmp[q] = (m + q < a.M) ? st[(mv + q) * pitch + nl] : to_T<T>(0.0f);
+                for (int q = 0; q < V; ++q) {
+                    T v = (m + q < a.M) ? st[(mv + q) * pitch + nl] : to_T<T>(0.0f);
+                    // signals of the stale iterate are stored negated in the transposed copy
+                    if (EPI == EPI_DA && it0 == 1) v = to_T<T>(-to_f<T>(v));
+                    tmp[q] = v;
+                }
                 *(uint4*)(OT + (int64_t)n * a.ldt + m) = *(const uint4*)tmp;
             }
         }
     }
+}
+
+// Tile shapes.  bf16: 256 x 256 tiles with eight waves and two k-tiles in flight for the forward
+// and signal GEMMs and for the weight gradients, 128 x 128 with short k-tiles for the output
+// layer.
+// fp32: square tiles with 32 floats of k.
+template <typename T, int EPI> struct TileOf;
+template <int EPI> struct TileOf<float, EPI> { using type = Tile<128, 128, 128>; };
+template <> struct TileOf<bf16_t, EPI_FWD> { using type = Tile<256, 256, 128, 4, 2, 2>; };
+template <> struct TileOf<bf16_t, EPI_DA> { using type = Tile<256, 256, 128, 4, 2, 2>; };
+template <> struct TileOf<bf16_t, EPI_DW> { using type = Tile<256, 256, 64, 4, 2, 2>; };
+template <> struct TileOf<bf16_t, EPI_HEAD> { using type = Tile<128, 128, 64>; };
+
+template <typename T, int EPI>
+static hipError_t launch_gemm(const GemmArgs& a, int batch, hipStream_t s)
+{
+    using TL = typename TileOf<T, EPI>::type;
+    constexpr int lds = gemm_lds_bytes<T, EPI, TL>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)mlp_gemm<T, EPI, TL>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((a.N + TL::BN - 1) / TL::BN, (a.M + TL::BM - 1) / TL::BM, batch);
+    mlp_gemm<T, EPI, TL><<<grid, TL::NT, lds, s>>>(a);
+    return hipGetLastError();
+}
+
+// workgroups (statistic partials) of the weight-gradient GEMM of an M x N layer
+template <typename T>
+static int dw_blocks(int M, int N)
+{
+    using TL = typename TileOf<T, EPI_DW>::type;
+    return ((M + TL::BM - 1) / TL::BM) * ((N + TL::BN - 1) / TL::BN);
+}
+template <typename T>
+static int head_row_blocks(int mu)
+{
+    using TL = typename TileOf<T, EPI_HEAD>::type;
+    return (mu + TL::BM - 1) / TL::BM;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -502,7 +654,7 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
         }
         if (lane == 0) {
             fresh_row(gbuf, which, hy, g)[boff + n] = s[0];
-            const float df = s[0] - s[1];
+            const float df = s[0] + s[1];      // the stale iterate's transposed signal is stored negated
             sq = (double)df * (double)df;
         }
     }
@@ -535,7 +687,7 @@ struct MlpWork {
 
 static hipError_t walloc(MlpWork* w, void** p, size_t bytes)
 {
-    // slack: GEMM tiles read up to 127 rows past the end of the last batch entry
+    // slack: GEMM tiles read whole tiles of rows, also past the end of the last batch entry
     bytes += w->slack;
     hipError_t e = hipMalloc(p, bytes);
     if (e != hipSuccess) return e;
@@ -563,12 +715,12 @@ hipError_t mlp_plan(gcada_ctx* c)
             off += lay.n[l];
         }
     }
-    if (lay.n[lay.L] > kBN) return hipErrorInvalidValue;
+    if (lay.n[lay.L] > kHeadClasses) return hipErrorInvalidValue;
     const int mu = c->hy.mu, G = c->hy.G, L = lay.L, nslot = c->hy.D + 1;
     lay.ldmu = round_up(mu, 64);
     int maxld = lay.ldmu;
     for (int l = 0; l <= L; ++l) maxld = std::max(maxld, lay.ld[l]);
-    w->slack = (size_t)128 * maxld * 4 + 256;
+    w->slack = (size_t)256 * maxld * 4 + 256;      // a tile may read up to 256 rows past an operand's end
     const size_t es = w->esz;
     hipError_t e;
     if ((e = walloc(w, &w->Xg, (size_t)G * mu * lay.ld[0] * es)) != hipSuccess) return e;
@@ -590,12 +742,12 @@ hipError_t mlp_plan(gcada_ctx* c)
     int ns = 0;
     for (int l = 1; l <= L; ++l) {
         w->stat_off_w[l] = ns;
-        ns += ((lay.n[l] + kBM - 1) / kBM) * ((lay.n[l - 1] + kBN - 1) / kBN);
+        ns += w->bf16 ? dw_blocks<bf16_t>(lay.n[l], lay.n[l - 1]) : dw_blocks<float>(lay.n[l], lay.n[l - 1]);
         w->stat_off_b[l] = ns;
         ns += (lay.n[l] + 3) / 4;
     }
     w->n_stat = ns;
-    w->n_loss = (mu + kBM - 1) / kBM;
+    w->n_loss = w->bf16 ? head_row_blocks<bf16_t>(mu) : head_row_blocks<float>(mu);
     c->n_stat_part = std::max(c->n_stat_part, ns);
     c->n_loss_part = std::max(c->n_loss_part, w->n_loss);
     return hipSuccess;
@@ -645,14 +797,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     const Layout& lay = w->lay;
     const Hyper& hy = c->hy;
     const int G = hy.G, mu = hy.mu, L = lay.L;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_FWD>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_DA>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_DW>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        (void)hipFuncSetAttribute((const void*)mlp_gemm<T, EPI_HEAD>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        attr_set = true;
-    }
+    hipError_t e;
     // 1. gather the minibatch rows (row-major and transposed)
     {
         dim3 grid((lay.n[0] + 63) / 64, (mu + 63) / 64, G);
@@ -672,16 +817,15 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
         else { a.P = w->A[l - 1]; a.p_it = rm_it(l - 1); a.p_g = rm_g(l - 1); a.ldp = lay.ld[l - 1]; }
         a.Q = w->Wc[l]; a.q_is_weight = 1; a.q_slot = w->wc_slot[l]; a.ldq = lay.ld[l - 1];
         a.ring = c->ring; a.boff = lay.boff[l];
-        dim3 grid((a.N + kBN - 1) / kBN, (a.M + kBM - 1) / kBM, 2 * G);
         if (l < L) {
             a.O = w->A[l]; a.o_it = rm_it(l); a.o_g = rm_g(l); a.ldo = lay.ld[l];
             a.OT = w->AT[l]; a.t_it = tr_it(l); a.t_g = tr_g(l); a.ldt = lay.ldmu;
-            mlp_gemm<T, EPI_FWD><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+            if ((e = launch_gemm<T, EPI_FWD>(a, 2 * G, s)) != hipSuccess) return e;
         } else {
             a.O = w->dZ[L]; a.o_it = rm_it(L); a.o_g = rm_g(L); a.ldo = lay.ld[L];
             a.OT = w->dZT[L]; a.t_it = tr_it(L); a.t_g = tr_g(L); a.ldt = lay.ldmu;
             a.shards = c->d_shards; a.idx = idx; a.part_loss = c->part_loss;
-            mlp_gemm<T, EPI_HEAD><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+            if ((e = launch_gemm<T, EPI_HEAD>(a, 2 * G, s)) != hipSuccess) return e;
         }
     }
     // 3. backward, layer by layer
@@ -696,8 +840,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             a.ldq = lay.ldmu; a.q_is_weight = 0;
             a.gbuf = c->gbuf; a.which = c->which; a.goff = lay.woff[l];
             a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[l];
-            dim3 grid((a.N + kBN - 1) / kBN, (a.M + kBM - 1) / kBM, G);
-            mlp_gemm<T, EPI_DW><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+            if ((e = launch_gemm<T, EPI_DW>(a, G, s)) != hipSuccess) return e;
         }
         {
             dim3 grid((lay.n[l] + 3) / 4, G);
@@ -714,8 +857,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             a.maskp = w->A[l - 1]; a.m_it = rm_it(l - 1); a.m_g = rm_g(l - 1); a.ldm = lay.ld[l - 1];
             a.O = w->dZ[l - 1]; a.o_it = rm_it(l - 1); a.o_g = rm_g(l - 1); a.ldo = lay.ld[l - 1];
             a.OT = w->dZT[l - 1]; a.t_it = tr_it(l - 1); a.t_g = tr_g(l - 1); a.ldt = lay.ldmu;
-            dim3 grid((a.N + kBN - 1) / kBN, (a.M + kBM - 1) / kBM, 2 * G);
-            mlp_gemm<T, EPI_DA><<<grid, kGemmThreads, kGemmLds, s>>>(a);
+            if ((e = launch_gemm<T, EPI_DA>(a, 2 * G, s)) != hipSuccess) return e;
         }
     }
     c->n_stat_used = w->n_stat;

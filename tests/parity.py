@@ -100,9 +100,13 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
         for g in range(w.G):
             if near[g]:
                 continue
-            e = rel_err(out["stat"][g], s_o[g])
+            # stat_g is the squared norm of a difference of two gradients that are each pinned to
+            # a relative `tol`: below (tol * ||g||)^2 it is rounding noise (exactly so when the
+            # two iterates coincide, as at step 0), hence that floor under the reference value
+            gn2 = float(np.dot(orc.grad[g], orc.grad[g]))
+            e = abs(out["stat"][g] - s_o[g]) / max(abs(s_o[g]), tol * gn2, ATOL / 1e-5)
             if stat_vs_threshold:
-                e = abs(out["stat"][g] - s_o[g]) / max(s_o[g], orc.rhs, ATOL)
+                e = abs(out["stat"][g] - s_o[g]) / max(s_o[g], orc.rhs, tol * gn2, ATOL)
             worst["stat"] = max(worst["stat"], e)
             assert e <= tol, f"step {k} group {g}: stat {out['stat'][g]} vs {s_o[g]} ({e:.3e})"
         e = rel_err(out["rhs"], orc.rhs)

@@ -114,7 +114,8 @@ constexpr int gemm_lds_bytes()
     const int loop = 2 * TL::STAGE;
     if (EPI == EPI_DW) return cmax(loop, 8 * TL::NW);
     if (EPI == EPI_HEAD) return cmax(loop, TL::BM * (TL::BN + 4) * 4 + 8 * TL::NW);
-    return cmax(loop, TL::BM * (TL::BN + 8) * (int)sizeof(T));
+    constexpr int V = 16 / (int)sizeof(T);
+    return cmax(loop, cmax(TL::BM * (TL::BN + V), TL::BN * (TL::BM + V)) * (int)sizeof(T));
 }
 
 struct GemmArgs {
@@ -130,7 +131,8 @@ struct GemmArgs {
     // HEAD: output layer (N = classes <= 128, one tile holds whole rows): bias, softmax
     //       cross-entropy against the labels, outputs dZ_L and dZ_L^T, one loss partial per block
     const float* ring; int64_t boff;
-    const void* maskp; int64_t m_it, m_g; int ldm;
+    const void* maskp; int64_t m_it, m_g; int ldm;       // row-major activations
+    const void* maskTp; int64_t mt_it, mt_g;             // the same, transposed (leading dimension ldt)
     void* O; int64_t o_it, o_g; int ldo;
     void* OT; int64_t t_it, t_g; int ldt;
     // DW : fresh gradient block -> grad[g*p + goff + m*N + n]; partial ||fresh-stale||^2
@@ -315,7 +317,29 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     constexpr int kGemmThreads = TL::NT, RW = BM / TL::WM, CW = BN / TL::WN;   // rows, columns per wave
     const int wm = wave / TL::WN, wn = wave % TL::WN;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // Workgroup -> (tile, group, iterate).  Consecutive workgroup ids go to different XCDs (id mod
+    // 8), each with its own L2.  The ids of one XCD are therefore mapped to a contiguous range of
+    // work, ordered so that neighbours share operands: for the weight gradients all tiles of a
+    // group (its signals and activations stay in that L2); otherwise all groups of one
+    // (iterate, column tile), which share the weight tile.
+    int bx, by, g, it0;
+    {
+        const int nx = gridDim.x, ny = gridDim.y, total = nx * ny * gridDim.z;
+        const int lin = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+        int l = total % 8 == 0 ? (lin % 8) * (total / 8) + lin / 8 : lin;
+        if (EPI == EPI_DW) {
+            bx = l % nx; l /= nx;
+            by = l % ny;
+            g = l / ny;
+            it0 = 0;
+        } else {
+            g = l % a.G; l /= a.G;
+            by = l % ny; l /= ny;
+            bx = l % nx;
+            it0 = l / nx;
+        }
+    }
+    const int m0 = by * BM, n0 = bx * BN;
     constexpr int esz = (int)sizeof(T);
 
     f32x16 acc[TM][TN];
@@ -325,8 +349,6 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-    int g, it0;
-    if (EPI == EPI_DW) { g = blockIdx.z; it0 = 0; } else { g = blockIdx.z % a.G; it0 = blockIdx.z / a.G; }
     // accumulator element e of lane: column n = lane % 32, row m = (e/4)*8 + (lane/32)*4 + e%4
     const int cl = lane & 31, rh = (lane >> 5) * 4;
 
@@ -371,7 +393,7 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
             double t = 0;
 #pragma unroll
             for (int wv = 0; wv < TL::NW; ++wv) t += red[wv];
-            a.part_stat[(int64_t)g * a.n_stat + a.stat_off + blockIdx.y * gridDim.x + blockIdx.x] = t;
+            a.part_stat[(int64_t)g * a.n_stat + a.stat_off + by * gridDim.x + bx] = t;
         }
         return;
     }
@@ -456,76 +478,136 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
             double t = 0;
 #pragma unroll
             for (int wv = 0; wv < TL::NW; ++wv) t += red[wv];
-            a.part_loss[(int64_t)g * gridDim.y + blockIdx.y] = t;
+            a.part_loss[(int64_t)g * gridDim.y + by] = t;
         }
     } else {
-        // stage the tile in LDS as T [BM][BN + 8], then write it row-major and transposed
-        constexpr int pitch = BN + 8;
+        // Two outputs: row-major O [M][ldo] and transposed OT [N][ldt].  The tile goes through
+        // LDS twice, each time in the orientation of the output, written from the accumulators
+        // in packed form (four rows of a column are adjacent registers; two columns of a row are
+        // adjacent lanes) and read back as 16-byte vectors along the output's rows.
         constexpr int V = 16 / esz;                 // elements per 16-byte vector
+        constexpr int PT = BM + V, PR = BN + V;     // row pitches of the two staging tiles
         T* st = (T*)lds;
         const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
-        const float* bias = EPI == EPI_FWD ? a.ring + (int64_t)slot * hy.pstride + a.boff : nullptr;
+        if constexpr (EPI == EPI_FWD) {
+            const float* bias = a.ring + (int64_t)slot * hy.pstride + a.boff;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * CW + j * 32 + cl;
+                const float bv = n < a.N ? round_to<T>(bias[n]) : 0.0f;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = fmaxf(acc[i][j][e] + bv, 0.0f);
+            }
+        }
+        // ---- transposed: stT [BN][PT], element (n, m) ----
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int nl = wn * CW + j * 32 + cl, n = n0 + nl;
-                float bv = 0.0f;
-                if (EPI == EPI_FWD && n < a.N) bv = round_to<T>(bias[n]);
+                const int nl = wn * CW + j * 32 + cl;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int ml = wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
-                    float v = acc[i][j][e];
-                    if (EPI == EPI_FWD) v = fmaxf(v + bv, 0.0f);
-                    st[ml * pitch + nl] = to_T<T>(v);
+                for (int eg = 0; eg < 4; ++eg) {
+                    const int ml = wm * RW + i * 32 + eg * 8 + rh;      // rows ml .. ml+3
+                    alignas(16) T q4[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) q4[q] = to_T<T>(acc[i][j][eg * 4 + q]);
+                    if constexpr (esz == 2) *(uint2*)(st + nl * PT + ml) = *(const uint2*)q4;
+                    else *(uint4*)(st + nl * PT + ml) = *(const uint4*)q4;
                 }
             }
         __syncthreads();
-        T* O = (T*)a.O + (int64_t)it0 * a.o_it + (int64_t)g * a.o_g;
-        T* OT = (T*)a.OT + (int64_t)it0 * a.t_it + (int64_t)g * a.t_g;
-        const T* mk = EPI == EPI_DA
-            ? (const T*)a.maskp + (int64_t)it0 * a.m_it + (int64_t)g * a.m_g : nullptr;
-        // row-major: BM rows x (BN / V) vectors.  DA: the ReLU mask (the layer's activations,
-        // same layout as the output) is applied here, 16 bytes at a time, and the masked values
-        // go back to the staging tile for the transposed pass.
-        for (int c = tid; c < BM * (BN / V); c += kGemmThreads) {
-            const int ml = c / (BN / V), nv = (c % (BN / V)) * V;
-            const int m = m0 + ml, n = n0 + nv;
-            if (m < a.M && n < a.N) {
-                // ldo is a multiple of 64 and pads stay zero: mask the lanes beyond N
-                alignas(16) T tmp[V];
-                alignas(16) T act[V];
-                if (EPI == EPI_DA) *(uint4*)act = *(const uint4*)(mk + (int64_t)m * a.ldm + n);
+        {
+            T* OT = (T*)a.OT + (int64_t)it0 * a.t_it + (int64_t)g * a.t_g;
+            const T* mkT = EPI == EPI_DA
+                ? (const T*)a.maskTp + (int64_t)it0 * a.mt_it + (int64_t)g * a.mt_g : nullptr;
+            for (int c = tid; c < BN * (BM / V); c += kGemmThreads) {
+                const int nl = c / (BM / V), mv = (c % (BM / V)) * V;
+                const int n = n0 + nl, m = m0 + mv;
+                if (n < a.N && m < a.M) {
+                    alignas(16) T tmp[V];
+                    alignas(16) T act[V];
+                    *(uint4*)tmp = *(const uint4*)(st + nl * PT + mv);
+                    if (EPI == EPI_DA) *(uint4*)act = *(const uint4*)(mkT + (int64_t)n * a.ldt + m);
 #pragma unroll
-                for (int q = 0; q < V; ++q) {
-                    T v = (n + q < a.N) ? st[ml * pitch + nv + q] : to_T<T>(0.0f);
-                    if (EPI == EPI_DA) {
-                        if (!(to_f<T>(act[q]) > 0.0f)) v = to_T<T>(0.0f);
-                        st[ml * pitch + nv + q] = v;
+                    for (int q = 0; q < V; ++q) {
+                        float v = (m + q < a.M) ? to_f<T>(tmp[q]) : 0.0f;
+                        if (EPI == EPI_DA) {
+                            // ReLU mask (the layer's activations); the stale iterate's transposed
+                            // signal is stored negated for the weight-gradient kernel
+                            if (!(to_f<T>(act[q]) > 0.0f)) v = 0.0f;
+                            if (it0 == 1) v = -v;
+                        }
+                        tmp[q] = to_T<T>(v);
                     }
-                    tmp[q] = v;
+                    *(uint4*)(OT + (int64_t)n * a.ldt + m) = *(const uint4*)tmp;
                 }
-                *(uint4*)(O + (int64_t)m * a.ldo + n) = *(const uint4*)tmp;
-            } else if (EPI == EPI_DA) {
-#pragma unroll
-                for (int q = 0; q < V; ++q) st[ml * pitch + nv + q] = to_T<T>(0.0f);
             }
         }
-        if (EPI == EPI_DA) __syncthreads();
-        // transposed: BN columns x (BM / V) vectors along m
-        for (int c = tid; c < BN * (BM / V); c += kGemmThreads) {
-            const int nl = c / (BM / V), mv = (c % (BM / V)) * V;
-            const int n = n0 + nl, m = m0 + mv;
-            if (n < a.N && m < a.M) {
-                alignas(16) T tmp[V];
+        __syncthreads();
+        // ---- row-major: stR [BM][PR], element (m, n) ----
 #pragma unroll
-                for (int q = 0; q < V; ++q) {
-                    T v = (m + q < a.M) ? st[(mv + q) * pitch + nl] : to_T<T>(0.0f);
-                    // signals of the stale iterate are stored negated in the transposed copy
-                    if (EPI == EPI_DA && it0 == 1) v = to_T<T>(-to_f<T>(v));
-                    tmp[q] = v;
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int nl = wn * CW + j * 32 + cl;
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    const int ml = wm * RW + i * 32 + eg * 8 + rh;
+                    if constexpr (esz == 2) {
+                        // rows 0,1 and rows 2,3 as two packed words; the lane pair (n, n^1) swaps
+                        // one word so that each lane holds two columns of two rows
+                        unsigned w01, w23;
+                        {
+                            alignas(8) T q4[4];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) q4[q] = to_T<T>(acc[i][j][eg * 4 + q]);
+                            const uint2 u = *(const uint2*)q4;
+                            w01 = u.x;
+                            w23 = u.y;
+                        }
+                        const bool odd = (lane & 1) != 0;
+                        const unsigned give = odd ? w01 : w23;
+                        const unsigned got = (unsigned)__builtin_amdgcn_mov_dpp((int)give, 0xB1, 0xF, 0xF, true);
+                        // even lane: rows 0,1 of columns (n, n+1); odd lane: rows 2,3 of (n-1, n)
+                        const unsigned mine = odd ? w23 : w01;
+                        const unsigned left = odd ? got : mine, right = odd ? mine : got;
+                        const unsigned ra = (left & 0xffffu) | (right << 16);          // first row
+                        const unsigned rb = (left >> 16) | (right & 0xffff0000u);      // second row
+                        const int mr = ml + (odd ? 2 : 0), nc2 = nl & ~1;
+                        *(unsigned*)(st + (mr + 0) * PR + nc2) = ra;
+                        *(unsigned*)(st + (mr + 1) * PR + nc2) = rb;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) st[(ml + q) * PR + nl] = to_T<T>(acc[i][j][eg * 4 + q]);
+                    }
                 }
-                *(uint4*)(OT + (int64_t)n * a.ldt + m) = *(const uint4*)tmp;
+            }
+        __syncthreads();
+        {
+            T* O = (T*)a.O + (int64_t)it0 * a.o_it + (int64_t)g * a.o_g;
+            const T* mk = EPI == EPI_DA
+                ? (const T*)a.maskp + (int64_t)it0 * a.m_it + (int64_t)g * a.m_g : nullptr;
+            for (int c = tid; c < BM * (BN / V); c += kGemmThreads) {
+                const int ml = c / (BN / V), nv = (c % (BN / V)) * V;
+                const int m = m0 + ml, n = n0 + nv;
+                if (m < a.M && n < a.N) {
+                    // ldo is a multiple of 64 and pads stay zero: mask the lanes beyond N
+                    alignas(16) T tmp[V];
+                    alignas(16) T act[V];
+                    *(uint4*)tmp = *(const uint4*)(st + ml * PR + nv);
+                    if (EPI == EPI_DA) *(uint4*)act = *(const uint4*)(mk + (int64_t)m * a.ldm + n);
+#pragma unroll
+                    for (int q = 0; q < V; ++q) {
+                        T v = (n + q < a.N) ? tmp[q] : to_T<T>(0.0f);
+                        if (EPI == EPI_DA) {
+                            if (!(to_f<T>(act[q]) > 0.0f)) v = to_T<T>(0.0f);
+                        }
+                        tmp[q] = v;
+                    }
+                    *(uint4*)(O + (int64_t)m * a.ldo + n) = *(const uint4*)tmp;
+                }
             }
         }
     }
@@ -855,6 +937,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             a.P = w->dZ[l]; a.p_it = rm_it(l); a.p_g = rm_g(l); a.ldp = lay.ld[l];
             a.Q = w->WcT[l]; a.q_is_weight = 1; a.q_slot = w->wct_slot[l]; a.ldq = lay.ld[l];
             a.maskp = w->A[l - 1]; a.m_it = rm_it(l - 1); a.m_g = rm_g(l - 1); a.ldm = lay.ld[l - 1];
+            a.maskTp = w->AT[l - 1]; a.mt_it = tr_it(l - 1); a.mt_g = tr_g(l - 1);
             a.O = w->dZ[l - 1]; a.o_it = rm_it(l - 1); a.o_g = rm_g(l - 1); a.ldo = lay.ld[l - 1];
             a.OT = w->dZT[l - 1]; a.t_it = tr_it(l - 1); a.t_g = tr_g(l - 1); a.ldt = lay.ldmu;
             if ((e = launch_gemm<T, EPI_DA>(a, 2 * G, s)) != hipSuccess) return e;

@@ -122,8 +122,9 @@ struct GemmArgs {
     Hyper hy;
     const int32_t* tau;
     int M, N, K;                 // K in elements (the loop runs over round_up(K, k per tile))
-    // P operand: base + it*p_it + g*p_g, rows of ldp elements
-    const void* P; int64_t p_it, p_g; int ldp;
+    // P operand: base + it*p_it + g*p_g, rows of ldp elements; or (gather) the minibatch rows
+    // of the group's shard, selected by idx / the cyclic window
+    const void* P; int64_t p_it, p_g; int ldp; int gather;
     // Q operand: either per (it,g) like P, or a weight copy indexed by ring slot
     const void* Q; int64_t q_it, q_g, q_slot; int ldq; int q_is_weight;
     // FWD : bias from the fp32 ring (offset boff), outputs A [M][ldo] and AT [N][ldt]
@@ -169,14 +170,14 @@ __device__ __forceinline__ void mfma_step<float>(const uint4& a, const uint4& b,
 // registers: arrays of the HIP uint4 struct are not always kept in registers.)
 template <typename TL>
 __device__ __forceinline__ void tile_gload(const char* __restrict__ Pg, const char* __restrict__ Qg,
-                                           int64_t ldp_b, int64_t ldq_b, int kt, u32x4 (&rp)[TL::PCH],
-                                           u32x4 (&rq)[TL::QCH])
+                                           const int64_t (&poff)[TL::PCH], int64_t ldq_b, int kt,
+                                           u32x4 (&rp)[TL::PCH], u32x4 (&rq)[TL::QCH])
 {
     const int tid = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < TL::PCH; ++i) {
-        const int c = tid + TL::NT * i, row = c / TL::CPR, kc = c % TL::CPR;
-        rp[i] = *(const u32x4*)(Pg + (int64_t)row * ldp_b + (int64_t)kt * TL::KROW + kc * 16);
+        const int kc = (tid + TL::NT * i) % TL::CPR;
+        rp[i] = *(const u32x4*)(Pg + poff[i] + (int64_t)kt * TL::KROW + kc * 16);
     }
 #pragma unroll
     for (int i = 0; i < TL::QCH; ++i) {
@@ -230,7 +231,7 @@ __device__ __forceinline__ void tile_mma(const char* lp, const char* lq, f32x16 
 // k-tile is shorter than a trip to L2 / HBM.  Loads past the last k-tile repeat the last one.
 template <typename T, typename TL>
 __device__ __forceinline__ void gemm_mainloop(const char* __restrict__ Pg, const char* __restrict__ Qg,
-                                              int64_t ldp_b, int64_t ldq_b, int K, char* lds,
+                                              const int64_t (&poff)[TL::PCH], int64_t ldq_b, int K, char* lds,
                                               f32x16 (&acc)[TL::TM][TL::TN])
 {
     constexpr int kElemsPerTileK = TL::KROW / (int)sizeof(T);
@@ -238,13 +239,13 @@ __device__ __forceinline__ void gemm_mainloop(const char* __restrict__ Pg, const
     const int nk = (K + kElemsPerTileK - 1) / kElemsPerTileK;
     if constexpr (TL::PF == 1) {
         u32x4 rp[TL::PCH], rq[TL::QCH];
-        tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, 0, rp, rq);
+        tile_gload<TL>(Pg, Qg, poff, ldq_b, 0, rp, rq);
         tile_lstore<TL>(lds, lds + kP, rp, rq);
         __syncthreads();
         for (int kt = 0; kt + 1 < nk; ++kt) {
             char* cur = lds + (kt & 1) * TL::STAGE;
             char* nxt = lds + ((kt + 1) & 1) * TL::STAGE;
-            tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, kt + 1, rp, rq);
+            tile_gload<TL>(Pg, Qg, poff, ldq_b, kt + 1, rp, rq);
             tile_mma<T, TL>(cur, cur + kP, acc);
             tile_lstore<TL>(nxt, nxt + kP, rp, rq);
             __syncthreads();
@@ -257,8 +258,8 @@ __device__ __forceinline__ void gemm_mainloop(const char* __restrict__ Pg, const
     } else {
         u32x4 rp0[TL::PCH], rq0[TL::QCH], rp1[TL::PCH], rq1[TL::QCH];
         const int last = nk - 1;
-        tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, 0, rp0, rq0);
-        tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, last < 1 ? last : 1, rp1, rq1);
+        tile_gload<TL>(Pg, Qg, poff, ldq_b, 0, rp0, rq0);
+        tile_gload<TL>(Pg, Qg, poff, ldq_b, last < 1 ? last : 1, rp1, rq1);
         tile_lstore<TL>(lds, lds + kP, rp0, rq0);
         __syncthreads();
         // iteration kt: request tile kt+2 into the set tile kt came from, multiply tile kt,
@@ -267,7 +268,7 @@ __device__ __forceinline__ void gemm_mainloop(const char* __restrict__ Pg, const
             {
                 char* cur = lds;
                 char* nxt = lds + TL::STAGE;
-                tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, kt + 2 < last ? kt + 2 : last, rp0, rq0);
+                tile_gload<TL>(Pg, Qg, poff, ldq_b, kt + 2 < last ? kt + 2 : last, rp0, rq0);
                 tile_mma<T, TL>(cur, cur + kP, acc);
                 tile_lstore<TL>(nxt, nxt + kP, rp1, rq1);
                 __syncthreads();
@@ -275,7 +276,7 @@ __device__ __forceinline__ void gemm_mainloop(const char* __restrict__ Pg, const
             if (kt + 1 < nk) {
                 char* cur = lds + TL::STAGE;
                 char* nxt = lds;
-                tile_gload<TL>(Pg, Qg, ldp_b, ldq_b, kt + 3 < last ? kt + 3 : last, rp1, rq1);
+                tile_gload<TL>(Pg, Qg, poff, ldq_b, kt + 3 < last ? kt + 3 : last, rp1, rq1);
                 tile_mma<T, TL>(cur, cur + kP, acc);
                 tile_lstore<TL>(nxt, nxt + kP, rp0, rq0);
                 __syncthreads();
@@ -296,7 +297,30 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs& a, int it, int g, int 
                                           f32x16 (&acc)[TL::TM][TL::TN])
 {
     constexpr int esz = (int)sizeof(T);
-    const char* Pg = (const char*)a.P + ((int64_t)it * a.p_it + (int64_t)g * a.p_g + (int64_t)m0 * a.ldp) * esz;
+    // byte offset of the P row each of this thread's chunks belongs to: rows of the operand
+    // array, or -- first layer -- the minibatch rows of the group's shard, read in place
+    const char* Pg;
+    int64_t poff[TL::PCH];
+    if (a.gather) {
+        const ShardDesc sh = a.shards[g];
+        Pg = (const char*)sh.X;
+#pragma unroll
+        for (int i = 0; i < TL::PCH; ++i) {
+            const int m = m0 + (threadIdx.x + TL::NT * i) / TL::CPR;
+            int64_t row = 0;                     // rows past the minibatch: any valid row, result unused
+            if (m < a.M) {
+                if (a.idx) row = a.idx[(int64_t)g * a.hy.mu + m];
+                else row = (int64_t)(((unsigned long long)a.hy.k * (unsigned long long)a.hy.mu +
+                                      (unsigned long long)m) % (unsigned long long)sh.rows);
+            }
+            poff[i] = row * sh.ld * esz;
+        }
+    } else {
+        Pg = (const char*)a.P + ((int64_t)it * a.p_it + (int64_t)g * a.p_g + (int64_t)m0 * a.ldp) * esz;
+#pragma unroll
+        for (int i = 0; i < TL::PCH; ++i)
+            poff[i] = (int64_t)((threadIdx.x + TL::NT * i) / TL::CPR) * a.ldp * esz;
+    }
     const char* Qg;
     if (a.q_is_weight) {
         const int slot = it == 0 ? a.hy.cur : stale_slot(a.hy, a.tau, g);
@@ -304,7 +328,7 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs& a, int it, int g, int 
     } else {
         Qg = (const char*)a.Q + ((int64_t)it * a.q_it + (int64_t)g * a.q_g + (int64_t)n0 * a.ldq) * esz;
     }
-    gemm_mainloop<T, TL>(Pg, Qg, (int64_t)a.ldp * esz, (int64_t)a.ldq * esz, a.K, lds, acc);
+    gemm_mainloop<T, TL>(Pg, Qg, poff, (int64_t)a.ldq * esz, a.K, lds, acc);
 }
 
 // grid: (ceil(N/BN), ceil(M/BM), batch);  batch = 2G (it*G + g) for FWD / DA / HEAD, G for DW.
@@ -688,6 +712,48 @@ __global__ __launch_bounds__(256) void mlp_gather(Hyper hy, const ShardDesc* __r
     }
 }
 
+// The same with 16-byte accesses, for shards whose rows are 16-byte aligned and whose width is a
+// multiple of the vector length.  Xg may be null (the first forward GEMM then reads the shard
+// rows in place) -- only the transpose is written.
+// grid: (ceil(n0 / (8 V)), ceil(mu/64), G), block 256; V = elements per 16 bytes.
+template <typename T>
+__global__ __launch_bounds__(256) void mlp_gather_vec(Hyper hy, const ShardDesc* __restrict__ shards,
+                                                      const int32_t* __restrict__ idx, int n0, int ld0,
+                                                      int ldmu, T* __restrict__ Xg, T* __restrict__ XgT)
+{
+    constexpr int V = 16 / (int)sizeof(T), TC = 8 * V, PITCH = 64 + V;
+    __shared__ __align__(16) T tileT[TC][PITCH];
+    const int g = blockIdx.z, c0 = blockIdx.x * TC, r0 = blockIdx.y * 64;
+    const ShardDesc sh = shards[g];
+    const T* X = (const T*)sh.X;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int t = threadIdx.x + 256 * h, r = t / 8, cv = (t % 8) * V;
+        const int i = r0 + r, col = c0 + cv;
+        alignas(16) T v[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) v[q] = to_T<T>(0.0f);
+        if (i < hy.mu && col < n0) {
+            int64_t row;
+            if (idx) row = idx[(int64_t)g * hy.mu + i];
+            else row = (int64_t)(((unsigned long long)hy.k * (unsigned long long)hy.mu +
+                                  (unsigned long long)i) % (unsigned long long)sh.rows);
+            *(uint4*)v = *(const uint4*)(X + row * sh.ld + col);
+            if (Xg) *(uint4*)(Xg + ((int64_t)g * hy.mu + i) * ld0 + col) = *(const uint4*)v;
+        }
+#pragma unroll
+        for (int q = 0; q < V; ++q) tileT[cv + q][r] = v[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int t = threadIdx.x + 256 * h, c = t / (64 / V), rv = (t % (64 / V)) * V;
+        const int n = c0 + c, i = r0 + rv;
+        if (n < n0 && i < hy.mu)
+            *(uint4*)(XgT + ((int64_t)g * n0 + n) * ldmu + i) = *(const uint4*)&tileT[c][rv];
+    }
+}
+
 // Compute copies of the hidden-layer weights of one ring slot: Wc [n_l][ld_{l-1}] and the
 // transpose WcT [n_{l-1}][ld_l], both in T.  grid: (ceil(n_in/64), ceil(n_out/64)), block 256.
 template <typename T>
@@ -880,8 +946,19 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     const Hyper& hy = c->hy;
     const int G = hy.G, mu = hy.mu, L = lay.L;
     hipError_t e;
-    // 1. gather the minibatch rows (row-major and transposed)
-    {
+    // 1. gather the minibatch rows: transposed always; row-major only when the first forward
+    //    GEMM cannot read the shard rows in place (rows not 16-byte aligned, or a width whose
+    //    last k-tile would reach past the end of a row)
+    constexpr int V = 16 / (int)sizeof(T);
+    bool vec_ok = lay.n[0] % V == 0;
+    for (const auto& sd : c->shards)
+        if ((sd.ld * (int64_t)sizeof(T)) % 16 || ((uintptr_t)sd.X % 16)) vec_ok = false;
+    const bool in_place = vec_ok && (lay.n[0] * (int)sizeof(T)) % TileOf<T, EPI_FWD>::type::KROW == 0;
+    if (vec_ok) {
+        dim3 grid((lay.n[0] + 8 * V - 1) / (8 * V), (mu + 63) / 64, G);
+        mlp_gather_vec<T><<<grid, 256, 0, s>>>(hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
+                                                in_place ? nullptr : (T*)w->Xg, (T*)w->XgT);
+    } else {
         dim3 grid((lay.n[0] + 63) / 64, (mu + 63) / 64, G);
         mlp_gather<T><<<grid, 256, 0, s>>>(hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
                                             (T*)w->Xg, (T*)w->XgT);
@@ -895,7 +972,8 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
         GemmArgs a{};
         a.hy = hy; a.tau = c->tau; a.G = G;
         a.M = mu; a.N = lay.n[l]; a.K = lay.n[l - 1];
-        if (l == 1) { a.P = w->Xg; a.p_it = 0; a.p_g = rm_g(0); a.ldp = lay.ld[0]; }
+        if (l == 1 && in_place) { a.gather = 1; a.shards = c->d_shards; a.idx = idx; }
+        else if (l == 1) { a.P = w->Xg; a.p_it = 0; a.p_g = rm_g(0); a.ldp = lay.ld[0]; }
         else { a.P = w->A[l - 1]; a.p_it = rm_it(l - 1); a.p_g = rm_g(l - 1); a.ldp = lay.ld[l - 1]; }
         a.Q = w->Wc[l]; a.q_is_weight = 1; a.q_slot = w->wc_slot[l]; a.ldq = lay.ld[l - 1];
         a.ring = c->ring; a.boff = lay.boff[l];

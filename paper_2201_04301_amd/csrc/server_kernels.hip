@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
                         kSelBlock / kWave);
 }
 
-constexpr int kUpdBlock = 256;
+constexpr int kUpdBlock = 1024;
 
 template <int VW>
 __device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&v)[VW])
@@ -184,8 +184,10 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
     const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
     float* __restrict__ tn = a.ring + (int64_t)hy.nxt * hy.pstride;
 
-    const int64_t j0 = ((int64_t)blockIdx.x * B + threadIdx.x) * VW;
-    const bool active = j0 < hy.pstride;      // pads stay zero: their step is alpha*0/sqrt(eps)
+    // a block walks over slabs of B * VW parameters: blockIdx.x, blockIdx.x + gridDim.x, ...
+    int64_t j0 = ((int64_t)blockIdx.x * B + threadIdx.x) * VW;
+    const int64_t jstep = (int64_t)gridDim.x * B * VW;
+    bool active = j0 < hy.pstride;            // pads stay zero: their step is alpha*0/sqrt(eps)
     float ac[VW] = {}, hv[VW] = {}, vv[VW] = {}, tv[VW] = {}, nv[VW];
     if (active) {
         load_vec<VW>(a.agg + j0, ac);
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
                 ep = (float)hy.eps;
     const float ob1 = (float)(1.0 - hy.beta1), ob2 = (float)(1.0 - hy.beta2);
     double sq = 0, tsq = 0;
-    if (active) {
+    while (active) {
         // innovation of a selected group: its fresh row minus the row it uploaded last; nothing
         // is copied -- the finishing block flips which[g] instead
         int i = 0;
@@ -301,6 +303,14 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
         store_vec<VW>(a.h + j0, hv);
         store_vec<VW>(a.vhat + j0, vv);
         store_vec<VW>(tn + j0, nv);
+        j0 += jstep;
+        active = j0 < hy.pstride;
+        if (active) {
+            load_vec<VW>(a.agg + j0, ac);
+            load_vec<VW>(a.h + j0, hv);
+            load_vec<VW>(a.vhat + j0, vv);
+            load_vec<VW>(th + j0, tv);
+        }
     }
     sq = wave_sum(sq);
     tsq = wave_sum(tsq);
@@ -375,9 +385,15 @@ constexpr int kBigBlock = 1024;
 
 hipError_t select_plan(gcada_ctx* c)
 {
-    // every per-parameter vector is padded to pstride (a multiple of 64): always four per thread
+    // every per-parameter vector is padded to pstride (a multiple of 64): always four per thread.
+    // At most two blocks per compute unit: each block prepares the selection once and then
+    // walks over its slabs of the parameter vector.
     const int64_t per_block = (int64_t)kUpdBlock * 4;
-    c->n_epi_blocks = (int32_t)((c->hy.pstride + per_block - 1) / per_block);
+    const int64_t slabs = (c->hy.pstride + per_block - 1) / per_block;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDeviceProperties(&prop, c->device);
+    if (e != hipSuccess) return e;
+    c->n_epi_blocks = (int32_t)std::min<int64_t>(slabs, 2 * (int64_t)prop.multiProcessorCount);
     return hipSuccess;
 }
 

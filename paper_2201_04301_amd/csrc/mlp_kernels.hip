@@ -31,12 +31,6 @@ __device__ __forceinline__ double wave_sum(double v)
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
     return v;
 }
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
-}
 
 // float -> T -> float with round to nearest even (identity for float)
 template <typename T> __device__ __forceinline__ float round_to(float v);
@@ -781,7 +775,9 @@ __global__ __launch_bounds__(256) void mlp_weight_copy(const float* __restrict__
 }
 
 // Bias gradient of a layer from the transposed signal dZT [n][ldmu]: db[n] = sum_i dZ[i][n].
-// grid: (ceil(n/4), G), block 256: one wave per hidden unit, both iterates.
+// The stale iterate's transposed signal is stored negated, so fresh - stale is a plain sum.
+// grid: (ceil(n/8), G), block 256: half a wave per hidden unit, both iterates, 16-byte loads
+// (rows of dZT are padded to a multiple of 64 elements with zeros).
 template <typename T>
 __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu, const T* __restrict__ dZT,
                                                      int64_t zt_it, int64_t zt_g, float* __restrict__ gbuf,
@@ -789,23 +785,35 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
                                                      int64_t boff, double* __restrict__ part_stat, int n_stat,
                                                      int stat_off)
 {
+    constexpr int V = 16 / (int)sizeof(T);
     __shared__ double s_red[4];
     const int g = blockIdx.y, wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int n = blockIdx.x * 4 + wave;
+    const int hl = lane & 31;                         // lane within the half wave
+    const int n = blockIdx.x * 8 + wave * 2 + (lane >> 5);
     double sq = 0;
+    float s[2] = {0.0f, 0.0f};
     if (n < nl) {
-        float s[2] = {0.0f, 0.0f};
+#pragma unroll
         for (int it = 0; it < 2; ++it) {
             const T* z = dZT + (int64_t)it * zt_it + (int64_t)g * zt_g + (int64_t)n * ldmu;
-            for (int i = lane; i < hy.mu; i += kWave) s[it] += to_f<T>(z[i]);
-            s[it] = wave_sum(s[it]);
-        }
-        if (lane == 0) {
-            fresh_row(gbuf, which, hy, g)[boff + n] = s[0];
-            const float df = s[0] + s[1];      // the stale iterate's transposed signal is stored negated
-            sq = (double)df * (double)df;
+            for (int i = hl * V; i < ldmu; i += 32 * V) {
+                alignas(16) T v[V];
+                *(uint4*)v = *(const uint4*)(z + i);
+#pragma unroll
+                for (int q = 0; q < V; ++q) s[it] += to_f<T>(v[q]);
+            }
         }
     }
+#pragma unroll
+    for (int it = 0; it < 2; ++it)
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) s[it] += __shfl_xor(s[it], o, kWave);
+    if (n < nl && hl == 0) {
+        fresh_row(gbuf, which, hy, g)[boff + n] = s[0];
+        const float df = s[0] + s[1];
+        sq = (double)df * (double)df;
+    }
+    sq += __shfl_xor(sq, 32, kWave);
     if (lane == 0) s_red[wave] = sq;
     __syncthreads();
     if (threadIdx.x == 0)
@@ -892,7 +900,7 @@ hipError_t mlp_plan(gcada_ctx* c)
         w->stat_off_w[l] = ns;
         ns += w->bf16 ? dw_blocks<bf16_t>(lay.n[l], lay.n[l - 1]) : dw_blocks<float>(lay.n[l], lay.n[l - 1]);
         w->stat_off_b[l] = ns;
-        ns += (lay.n[l] + 3) / 4;
+        ns += (lay.n[l] + 7) / 8;
     }
     w->n_stat = ns;
     w->n_loss = w->bf16 ? head_row_blocks<bf16_t>(mu) : head_row_blocks<float>(mu);
@@ -1003,7 +1011,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             if ((e = launch_gemm<T, EPI_DW>(a, G, s)) != hipSuccess) return e;
         }
         {
-            dim3 grid((lay.n[l] + 3) / 4, G);
+            dim3 grid((lay.n[l] + 7) / 8, G);
             mlp_bias_grad<T><<<grid, 256, 0, s>>>(hy, lay.n[l], lay.ldmu, (const T*)w->dZT[l], tr_it(l),
                                                    tr_g(l), c->gbuf, c->which, lay.boff[l], c->part_stat, w->n_stat,
                                                    w->stat_off_b[l]);

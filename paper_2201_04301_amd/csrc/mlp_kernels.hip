@@ -635,17 +635,21 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
 // and signal GEMMs and for the weight gradients, 128 x 128 with short k-tiles for the output
 // layer.
 // fp32: square tiles with 32 floats of k.
-template <typename T, int EPI> struct TileOf;
-template <int EPI> struct TileOf<float, EPI> { using type = Tile<128, 128, 128>; };
-template <> struct TileOf<bf16_t, EPI_FWD> { using type = Tile<256, 256, 128, 4, 2, 2>; };
-template <> struct TileOf<bf16_t, EPI_DA> { using type = Tile<256, 256, 128, 4, 2, 2>; };
-template <> struct TileOf<bf16_t, EPI_DW> { using type = Tile<256, 256, 64, 4, 2, 2>; };
-template <> struct TileOf<bf16_t, EPI_HEAD> { using type = Tile<128, 128, 64>; };
+// SMALL: fp32 problems whose 128 x 128 tiles would leave most of the device idle (fp32 MFMA is
+// slow enough that a workgroup's k loop is arithmetic-bound) use 64 x 64 tiles instead.
+template <typename T, int EPI, bool SMALL> struct TileOf;
+template <int EPI> struct TileOf<float, EPI, false> { using type = Tile<128, 128, 128, 2, 2, 2>; };
+template <int EPI> struct TileOf<float, EPI, true> { using type = Tile<64, 64, 128, 2, 2, 2>; };
+template <> struct TileOf<float, EPI_HEAD, true> { using type = Tile<64, 128, 128, 2, 2, 2>; };
+template <bool SMALL> struct TileOf<bf16_t, EPI_FWD, SMALL> { using type = Tile<256, 256, 128, 4, 2, 2>; };
+template <bool SMALL> struct TileOf<bf16_t, EPI_DA, SMALL> { using type = Tile<256, 256, 128, 4, 2, 2>; };
+template <bool SMALL> struct TileOf<bf16_t, EPI_DW, SMALL> { using type = Tile<256, 256, 64, 4, 2, 2>; };
+template <bool SMALL> struct TileOf<bf16_t, EPI_HEAD, SMALL> { using type = Tile<128, 128, 64>; };
 
-template <typename T, int EPI>
-static hipError_t launch_gemm(const GemmArgs& a, int batch, hipStream_t s)
+template <typename T, int EPI, bool SMALL>
+static hipError_t launch_gemm_t(const GemmArgs& a, int batch, hipStream_t s)
 {
-    using TL = typename TileOf<T, EPI>::type;
+    using TL = typename TileOf<T, EPI, SMALL>::type;
     constexpr int lds = gemm_lds_bytes<T, EPI, TL>();
     static bool attr_set = false;
     if (!attr_set) {
@@ -659,18 +663,27 @@ static hipError_t launch_gemm(const GemmArgs& a, int batch, hipStream_t s)
     return hipGetLastError();
 }
 
+template <typename T, int EPI>
+static hipError_t launch_gemm(const GemmArgs& a, int batch, bool small, hipStream_t s)
+{
+    return small ? launch_gemm_t<T, EPI, true>(a, batch, s) : launch_gemm_t<T, EPI, false>(a, batch, s);
+}
+
 // workgroups (statistic partials) of the weight-gradient GEMM of an M x N layer
 template <typename T>
-static int dw_blocks(int M, int N)
+static int dw_blocks(int M, int N, bool small)
 {
-    using TL = typename TileOf<T, EPI_DW>::type;
-    return ((M + TL::BM - 1) / TL::BM) * ((N + TL::BN - 1) / TL::BN);
+    using TB = typename TileOf<T, EPI_DW, false>::type;
+    using TS = typename TileOf<T, EPI_DW, true>::type;
+    return small ? ((M + TS::BM - 1) / TS::BM) * ((N + TS::BN - 1) / TS::BN)
+                 : ((M + TB::BM - 1) / TB::BM) * ((N + TB::BN - 1) / TB::BN);
 }
 template <typename T>
-static int head_row_blocks(int mu)
+static int head_row_blocks(int mu, bool small)
 {
-    using TL = typename TileOf<T, EPI_HEAD>::type;
-    return (mu + TL::BM - 1) / TL::BM;
+    using TB = typename TileOf<T, EPI_HEAD, false>::type;
+    using TS = typename TileOf<T, EPI_HEAD, true>::type;
+    return small ? (mu + TS::BM - 1) / TS::BM : (mu + TB::BM - 1) / TB::BM;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -837,6 +850,7 @@ struct MlpWork {
     // partial-statistic slots
     int stat_off_w[GCADA_MAX_WIDTHS] = {}, stat_off_b[GCADA_MAX_WIDTHS] = {};
     int n_stat = 0, n_loss = 0;
+    bool small = false;              // 64 x 64 GEMM tiles (small fp32 problems)
     size_t slack = 0;
     std::vector<void*> allocs;
 };
@@ -894,16 +908,25 @@ hipError_t mlp_plan(gcada_ctx* c)
         if ((e = walloc(w, &w->Wc[l], (size_t)nslot * w->wc_slot[l] * es)) != hipSuccess) return e;
         if ((e = walloc(w, &w->WcT[l], (size_t)nslot * w->wct_slot[l] * es)) != hipSuccess) return e;
     }
+    // small tiles when the first forward GEMM in 128 x 128 tiles cannot give every compute unit
+    // two workgroups
+    {
+        hipDeviceProp_t prop;
+        if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return e;
+        const int64_t wgs = (int64_t)((mu + 127) / 128) * ((lay.n[1] + 127) / 128) * 2 * G;
+        w->small = !w->bf16 && wgs < 2 * (int64_t)prop.multiProcessorCount;
+    }
     // partial statistics: per layer the weight-gradient tiles and the bias blocks
     int ns = 0;
     for (int l = 1; l <= L; ++l) {
         w->stat_off_w[l] = ns;
-        ns += w->bf16 ? dw_blocks<bf16_t>(lay.n[l], lay.n[l - 1]) : dw_blocks<float>(lay.n[l], lay.n[l - 1]);
+        ns += w->bf16 ? dw_blocks<bf16_t>(lay.n[l], lay.n[l - 1], w->small)
+                      : dw_blocks<float>(lay.n[l], lay.n[l - 1], w->small);
         w->stat_off_b[l] = ns;
         ns += (lay.n[l] + 7) / 8;
     }
     w->n_stat = ns;
-    w->n_loss = w->bf16 ? head_row_blocks<bf16_t>(mu) : head_row_blocks<float>(mu);
+    w->n_loss = w->bf16 ? head_row_blocks<bf16_t>(mu, w->small) : head_row_blocks<float>(mu, w->small);
     c->n_stat_part = std::max(c->n_stat_part, ns);
     c->n_loss_part = std::max(c->n_loss_part, w->n_loss);
     return hipSuccess;
@@ -961,7 +984,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     bool vec_ok = lay.n[0] % V == 0;
     for (const auto& sd : c->shards)
         if ((sd.ld * (int64_t)sizeof(T)) % 16 || ((uintptr_t)sd.X % 16)) vec_ok = false;
-    const bool in_place = vec_ok && (lay.n[0] * (int)sizeof(T)) % TileOf<T, EPI_FWD>::type::KROW == 0;
+    const bool in_place = vec_ok && (lay.n[0] * (int)sizeof(T)) % TileOf<T, EPI_FWD, false>::type::KROW == 0;
     if (vec_ok) {
         dim3 grid((lay.n[0] + 8 * V - 1) / (8 * V), (mu + 63) / 64, G);
         mlp_gather_vec<T><<<grid, 256, 0, s>>>(hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
@@ -988,12 +1011,12 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
         if (l < L) {
             a.O = w->A[l]; a.o_it = rm_it(l); a.o_g = rm_g(l); a.ldo = lay.ld[l];
             a.OT = w->AT[l]; a.t_it = tr_it(l); a.t_g = tr_g(l); a.ldt = lay.ldmu;
-            if ((e = launch_gemm<T, EPI_FWD>(a, 2 * G, s)) != hipSuccess) return e;
+            if ((e = launch_gemm<T, EPI_FWD>(a, 2 * G, w->small, s)) != hipSuccess) return e;
         } else {
             a.O = w->dZ[L]; a.o_it = rm_it(L); a.o_g = rm_g(L); a.ldo = lay.ld[L];
             a.OT = w->dZT[L]; a.t_it = tr_it(L); a.t_g = tr_g(L); a.ldt = lay.ldmu;
             a.shards = c->d_shards; a.idx = idx; a.part_loss = c->part_loss;
-            if ((e = launch_gemm<T, EPI_HEAD>(a, 2 * G, s)) != hipSuccess) return e;
+            if ((e = launch_gemm<T, EPI_HEAD>(a, 2 * G, w->small, s)) != hipSuccess) return e;
         }
     }
     // 3. backward, layer by layer
@@ -1008,7 +1031,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             a.ldq = lay.ldmu; a.q_is_weight = 0;
             a.gbuf = c->gbuf; a.which = c->which; a.goff = lay.woff[l];
             a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[l];
-            if ((e = launch_gemm<T, EPI_DW>(a, G, s)) != hipSuccess) return e;
+            if ((e = launch_gemm<T, EPI_DW>(a, G, w->small, s)) != hipSuccess) return e;
         }
         {
             dim3 grid((lay.n[l] + 7) / 8, G);
@@ -1026,7 +1049,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             a.maskTp = w->AT[l - 1]; a.mt_it = tr_it(l - 1); a.mt_g = tr_g(l - 1);
             a.O = w->dZ[l - 1]; a.o_it = rm_it(l - 1); a.o_g = rm_g(l - 1); a.ldo = lay.ld[l - 1];
             a.OT = w->dZT[l - 1]; a.t_it = tr_it(l - 1); a.t_g = tr_g(l - 1); a.ldt = lay.ldmu;
-            if ((e = launch_gemm<T, EPI_DA>(a, 2 * G, s)) != hipSuccess) return e;
+            if ((e = launch_gemm<T, EPI_DA>(a, 2 * G, w->small, s)) != hipSuccess) return e;
         }
     }
     c->n_stat_used = w->n_stat;

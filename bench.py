@@ -99,7 +99,7 @@ def main():
 
     ms_per_step = dt / K * 1e3
     iters_s = K / dt
-    if w.model == "logreg":
+    if w.model in ("logreg", "linreg"):
         # algorithmic bytes per launch of the timed kernel(s): one read of the touched minibatch rows
         alg_bytes = w.G * w.mu * w.widths[0] * 4
         achieved = alg_bytes / (grad_ms_avg * 1e-3) / 1e9

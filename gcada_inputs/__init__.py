@@ -8,6 +8,8 @@ harness read the values made here; neither of those imports the other.
 The paper's experiment (Sec. VI) uses a public image dataset that is not available here; these
 synthetic workloads stand in for it.  Logistic-regression data: features N(0, I/d), labels from a
 planted weight vector with a fraction of flips.  MLP data: ten Gaussian clusters, label = cluster.
+Linear-regression data (the model of the paper's experiment): same features, real targets from a
+planted weight vector plus Gaussian noise.
 """
 from __future__ import annotations
 
@@ -22,8 +24,8 @@ import torch
 @dataclass(frozen=True)
 class Workload:
     name: str
-    model: str                 # "logreg" | "mlp"
-    widths: Tuple[int, ...]    # logreg: (d,), mlp: layer widths including the input
+    model: str                 # "logreg" | "mlp" | "linreg"
+    widths: Tuple[int, ...]    # logreg, linreg: (d,), mlp: layer widths including the input
     G: int                     # worker groups
     M_G: int                   # workers per group (host cost model only)
     mu: int                    # minibatch per group
@@ -45,7 +47,7 @@ class Workload:
 
     @property
     def p(self) -> int:
-        if self.model == "logreg":
+        if self.model in ("logreg", "linreg"):
             return self.widths[0]
         return sum(self.widths[l] * self.widths[l - 1] + self.widths[l]
                    for l in range(1, len(self.widths)))
@@ -66,6 +68,11 @@ CONFIGS = {
     "lr_64k": Workload("lr_64k", "logreg", (65536,), G=32, M_G=4, mu=1024, rows=16384, iters=200),
     "mlp_3072_bf16": Workload("mlp_3072_bf16", "mlp", (3072, 1024, 1024, 10), G=64, M_G=4, mu=256,
                               rows=781, dtype="bf16", lo=-1.0, hi=1.0, iters=200),
+    # geometry of the paper's experiment (Sec. VI): linear regression with the quadratic error
+    # loss, M = 12 workers in G = 3 groups of M_G = 4, input width of that dataset (784), rule
+    # constant 0.3 on the SUM over the history, i.e. c = 0.3 D here; D and mu are not stated
+    "linreg_784": Workload("linreg_784", "linreg", (784,), G=3, M_G=4, mu=256, rows=20000, c=3.0,
+                           sigma=0.1, iters=500),
 }
 
 
@@ -82,7 +89,7 @@ def _gen(seed: int, device) -> torch.Generator:
 
 def make_shards(w: Workload, device="cpu", chunk_rows: int = 4096):
     """Return (X, y): lists with one tensor per group.  X[g]: rows x d (fp32 or bf16, row-major);
-    y[g]: fp32 +-1 (logreg) or int32 class id (mlp).  Generated on ``device`` chunk by chunk so a
+    y[g]: fp32 +-1 (logreg), fp32 target (linreg) or int32 class id (mlp).  Generated on ``device`` chunk by chunk so a
     137 GB dataset never needs a host copy."""
     device = torch.device(device)
     d = w.widths[0]
@@ -90,7 +97,7 @@ def make_shards(w: Workload, device="cpu", chunk_rows: int = 4096):
     gen = _gen(w.seed, device)
     Xs: List[torch.Tensor] = []
     ys: List[torch.Tensor] = []
-    if w.model == "logreg":
+    if w.model in ("logreg", "linreg"):
         wstar = torch.randn(d, generator=gen, device=device, dtype=torch.float32)
         scale = 1.0 / math.sqrt(d)
         for g in range(w.G):
@@ -101,9 +108,12 @@ def make_shards(w: Workload, device="cpu", chunk_rows: int = 4096):
                 xc = torch.randn(r1 - r0, d, generator=gen, device=device, dtype=torch.float32)
                 xc.mul_(scale)
                 xc = xc.to(xdt)
-                yc = torch.where(xc.float() @ wstar >= 0, 1.0, -1.0)
-                fl = torch.rand(r1 - r0, generator=gen, device=device) < w.flip
-                yc = torch.where(fl, -yc, yc)
+                if w.model == "linreg":     # real targets: planted weights plus noise
+                    yc = xc.float() @ wstar + w.sigma * torch.randn(r1 - r0, generator=gen, device=device)
+                else:
+                    yc = torch.where(xc.float() @ wstar >= 0, 1.0, -1.0)
+                    fl = torch.rand(r1 - r0, generator=gen, device=device) < w.flip
+                    yc = torch.where(fl, -yc, yc)
                 X[r0:r1] = xc
                 y[r0:r1] = yc
             Xs.append(X)
@@ -129,7 +139,7 @@ def make_shards(w: Workload, device="cpu", chunk_rows: int = 4096):
 def make_theta0(w: Workload) -> np.ndarray:
     """Initial iterate (fp32).  logreg: zeros.  mlp: W ~ U(+-1/sqrt(fan_in)), b = 0, laid out per
     layer as W (out x in, row-major) followed by b."""
-    if w.model == "logreg":
+    if w.model in ("logreg", "linreg"):
         return np.zeros(w.p, dtype=np.float32)
     rng = np.random.default_rng(w.seed + 17)
     parts = []

@@ -56,19 +56,22 @@ enum {
     GCADA_ESTATE = 4    /* call order: shards / theta not set yet, ...  */
 };
 
-enum { GCADA_LOGREG = 0, GCADA_MLP = 1 };
+/* GCADA_LINREG: linear model with the quadratic error loss 0.5 (x.theta - y)^2, the model of
+ * the paper's experiment (Sec. VI); real-valued fp32 targets.  It shares every kernel of
+ * GCADA_LOGREG; only the residual of a row differs. */
+enum { GCADA_LOGREG = 0, GCADA_MLP = 1, GCADA_LINREG = 2 };
 enum { GCADA_F32 = 0, GCADA_BF16 = 1 };
 
 #define GCADA_MAX_WIDTHS 8
 
 /* Model and batch geometry (Algorithm 1's problem statement). */
 typedef struct gcada_dims {
-    int32_t model;      /* GCADA_LOGREG | GCADA_MLP                                          */
+    int32_t model;      /* GCADA_LOGREG | GCADA_MLP | GCADA_LINREG                           */
     int32_t dtype;      /* storage type of X and of the weights the gradients are evaluated
                            at: GCADA_F32, or GCADA_BF16 (MLP only: bf16 X, bf16 copy of theta,
                            fp32 accumulation, fp32 master theta and moments)                 */
-    int32_t n_widths;   /* LOGREG: 1; MLP: number of layer widths including input, 2..8      */
-    int32_t widths[GCADA_MAX_WIDTHS]; /* LOGREG: {d}; MLP: {n_0, ..., n_L}                   */
+    int32_t n_widths;   /* LOGREG, LINREG: 1; MLP: number of layer widths incl. input, 2..8  */
+    int32_t widths[GCADA_MAX_WIDTHS]; /* LOGREG, LINREG: {d}; MLP: {n_0, ..., n_L}           */
     int32_t batch;      /* mu: minibatch size per group (fixed, Sec. II-A)                   */
     float   l2;         /* lambda >= 0; must be 0 for GCADA_BF16                             */
 } gcada_dims;

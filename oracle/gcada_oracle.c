@@ -129,7 +129,8 @@ static double logistic_sample(const double *theta, const float *x, double y, int
     return softplus(-y * z);
 }
 
-/* quadratic (test-only linear regression): loss = 0.5 (x.theta - y)^2 */
+/* linear regression with the quadratic error loss, the model of the paper's experiment
+ * (Sec. VI), scalar output: loss = 0.5 (x.theta - y)^2 */
 static double quadratic_sample(const double *theta, const float *x, double y, int64_t d, double *grad)
 {
     double z = 0;

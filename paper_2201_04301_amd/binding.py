@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgcada.so")
 
 GCADA_OK, GCADA_EINVAL, GCADA_ENOMEM, GCADA_EDEVICE, GCADA_ESTATE = range(5)
-GCADA_LOGREG, GCADA_MLP = 0, 1
+GCADA_LOGREG, GCADA_MLP, GCADA_LINREG = 0, 1, 2
 GCADA_F32, GCADA_BF16 = 0, 1
 GCADA_MAX_WIDTHS = 8
 GCADA_OPT_SINGLE_PASS_LOGREG = 1

@@ -54,7 +54,7 @@ int check_device_flag(gcada_ctx* c)
 
 int64_t param_count(const gcada_dims& d)
 {
-    if (d.model == GCADA_LOGREG) return d.widths[0];
+    if (d.model != GCADA_MLP) return d.widths[0];
     int64_t p = 0;
     for (int l = 1; l < d.n_widths; ++l)
         p += (int64_t)d.widths[l] * d.widths[l - 1] + d.widths[l];
@@ -89,11 +89,11 @@ int gcada_create(const gcada_dims* dims, int32_t G, int32_t M_G, int32_t D, doub
                  double alpha, double beta1, double beta2, double eps, gcada_ctx** out)
 try {
     if (!dims || !out) return fail(nullptr, GCADA_EINVAL, "dims and out must not be NULL");
-    if (dims->model != GCADA_LOGREG && dims->model != GCADA_MLP)
-        return fail(nullptr, GCADA_EINVAL, "dims.model must be GCADA_LOGREG or GCADA_MLP");
+    if (dims->model != GCADA_LOGREG && dims->model != GCADA_MLP && dims->model != GCADA_LINREG)
+        return fail(nullptr, GCADA_EINVAL, "dims.model must be GCADA_LOGREG, GCADA_MLP or GCADA_LINREG");
     if (dims->dtype != GCADA_F32 && dims->dtype != GCADA_BF16)
         return fail(nullptr, GCADA_EINVAL, "dims.dtype must be GCADA_F32 or GCADA_BF16");
-    if (dims->model == GCADA_LOGREG && (dims->n_widths != 1 || dims->dtype != GCADA_F32))
+    if (dims->model != GCADA_MLP && (dims->n_widths != 1 || dims->dtype != GCADA_F32))
         return fail(nullptr, GCADA_EINVAL, "logistic regression takes one width and fp32 data");
     if (dims->model == GCADA_MLP && (dims->n_widths < 2 || dims->n_widths > GCADA_MAX_WIDTHS))
         return fail(nullptr, GCADA_EINVAL, "MLP takes 2..8 layer widths");
@@ -124,6 +124,7 @@ try {
     hy.p = param_count(*dims);
     hy.pstride = (hy.p + 63) / 64 * 64;
     hy.l2 = dims->l2;
+    hy.quadratic = dims->model == GCADA_LINREG ? 1 : 0;
     hy.c = c; hy.alpha = alpha; hy.beta1 = beta1; hy.beta2 = beta2; hy.eps = eps;
     x->shards.assign(G, ShardDesc{nullptr, nullptr, 0, 0});
     x->shard_set.assign(G, 0);
@@ -151,12 +152,12 @@ try {
     if ((e = dalloc(&x->stat_sum, (size_t)G)) != hipSuccess) return bail(e, "alloc stat sums");
     if ((e = dalloc(&x->ctl, 1)) != hipSuccess) return bail(e, "alloc control block");
 
-    e = dims->model == GCADA_LOGREG ? gcada::lr_plan(x) : gcada::mlp_plan(x);
+    e = dims->model != GCADA_MLP ? gcada::lr_plan(x) : gcada::mlp_plan(x);
     if (e != hipSuccess) return bail(e, "model plan");
     if ((e = gcada::select_plan(x)) != hipSuccess) return bail(e, "server plan");
-    if (dims->model == GCADA_LOGREG && (e = gcada::lr_tile_plan(x)) != hipSuccess)
+    if (dims->model != GCADA_MLP && (e = gcada::lr_tile_plan(x)) != hipSuccess)
         return bail(e, "single-pass logistic plan");
-    if (dims->model == GCADA_LOGREG && (e = gcada::lr_team_plan(x)) != hipSuccess)
+    if (dims->model != GCADA_MLP && (e = gcada::lr_team_plan(x)) != hipSuccess)
         return bail(e, "team logistic plan");
     if ((e = dalloc(&x->part_loss, (size_t)G * x->n_loss_part)) != hipSuccess) return bail(e, "alloc scratch");
     if ((e = dalloc(&x->part_stat, (size_t)G * x->n_stat_part)) != hipSuccess) return bail(e, "alloc scratch");
@@ -233,7 +234,7 @@ static int reset_run(gcada_ctx* ctx, const float* theta0_any)
 static int after_state_change(gcada_ctx* ctx)
 {
     set_iteration(ctx);
-    if (ctx->dims.model == GCADA_LOGREG) HIP_TRY(ctx, gcada::lr_team_reset(ctx));
+    if (ctx->dims.model != GCADA_MLP) HIP_TRY(ctx, gcada::lr_team_reset(ctx));
     HIP_TRY(ctx, gcada::refresh_theta_sq(ctx, nullptr));
     if (ctx->dims.model == GCADA_MLP) HIP_TRY(ctx, gcada::mlp_refresh_weights(ctx, nullptr));
     HIP_TRY(ctx, hipDeviceSynchronize());
@@ -263,7 +264,7 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
         if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "step: a group has no shard");
     hipStream_t s = (hipStream_t)stream;
     set_iteration(ctx);
-    hipError_t e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, idx, s)
+    hipError_t e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, idx, s)
                                                    : gcada::mlp_gradients(ctx, idx, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
     if ((e = gcada::server_step(ctx, mask_out, loss_out, s)) != hipSuccess)
@@ -418,7 +419,7 @@ try {
     for (int r = 0; r < reps && e == hipSuccess; ++r)
     {
         const int32_t* ir = idx ? idx + (int64_t)r * idx_stride : nullptr;
-        e = ctx->dims.model == GCADA_LOGREG ? gcada::lr_gradients(ctx, ir, s)
+        e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, ir, s)
                                             : gcada::mlp_gradients(ctx, ir, s);
     }
     ctx->dominant_only = false;

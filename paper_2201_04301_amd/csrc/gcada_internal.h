@@ -39,6 +39,7 @@ struct Hyper {
     int32_t G, D, mu;
     int64_t p, pstride;     // parameters; floats between ring slots
     float l2;
+    int32_t quadratic;      // linear models: 1 = quadratic error loss, 0 = logistic loss
     double c, alpha, beta1, beta2, eps;
 };
 

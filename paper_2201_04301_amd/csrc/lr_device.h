@@ -54,11 +54,19 @@ __device__ __forceinline__ float sigmoidf_(float t)
 }
 
 // r = residual at theta^k, dr = r - (residual at theta_stale), from z = x.theta^k and
-// dz = x.(theta^k - theta_stale); the difference of the two sigmoids is formed without
-// cancellation.  loss = log(1 + exp(-y z)).
-__device__ __forceinline__ void residuals(float z, float dz, float y, float& r, float& dr,
+// dz = x.(theta^k - theta_stale).
+// Logistic loss log(1 + exp(-y z)), y = +-1: the difference of the two sigmoids is formed
+// without cancellation.  Quadratic error loss 0.5 (z - y)^2 (the linear-regression model of the
+// paper's experiment, Sec. VI): r = z - y, and the difference of the residuals is dz itself.
+__device__ __forceinline__ void residuals(bool quadratic, float z, float dz, float y, float& r, float& dr,
                                           float& loss)
 {
+    if (quadratic) {
+        r = z - y;
+        dr = dz;
+        loss = 0.5f * r * r;
+        return;
+    }
     const float a = -y * z;
     const float sa = sigmoidf_(a);
     r = -y * sa;

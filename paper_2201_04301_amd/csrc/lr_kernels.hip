@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kFwdWaves* kWave) void lr_forward(
         const float zz = wave_sum(z[r]), dd = wave_sum(dz[r]);
         if (ok[r] && lane == 0) {
             float rr, dr, ls;
-            residuals(zz, dd, yv[r], rr, dr, ls);
+            residuals(hy.quadratic != 0, zz, dd, yv[r], rr, dr, ls);
             float2* out = (float2*)res + ((int64_t)g * mu + i0 + r);
             *out = make_float2(rr, dr);
             lsum += (double)ls;

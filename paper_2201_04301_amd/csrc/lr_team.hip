@@ -345,7 +345,7 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
         }
         if (lane < kR) {
             float r, dr, ls;
-            residuals(z, dz, L.s_y[(n - 2) % kLabelRing][lane], r, dr, ls);
+            residuals(a.hy.quadratic != 0, z, dz, L.s_y[(n - 2) % kLabelRing][lane], r, dr, ls);
             L.s_res[n & 1][lane] = make_float2(r, dr);
             lacc += (double)ls;
         }

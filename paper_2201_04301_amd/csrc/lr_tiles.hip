@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
             dz += s_dot[w][2 * tid + 1];
         }
         float r, dr, ls;
-        residuals(z, dz, my_y, r, dr, ls);
+        residuals(hy.quadratic != 0, z, dz, my_y, r, dr, ls);
         s_res[tid] = make_float2(r, dr);
         lsum = (double)ls;
     }

@@ -41,7 +41,7 @@ class Gcada:
     def __init__(self, model: str, widths: Sequence[int], batch: int, G: int, M_G: int = 1,
                  D: int = 10, c: float = 1.0, alpha: float = 1e-2, beta1: float = 0.9,
                  beta2: float = 0.999, eps: float = 1e-8, l2: float = 0.0, dtype: str = "f32"):
-        self.model = {"logreg": B.GCADA_LOGREG, "mlp": B.GCADA_MLP}[model]
+        self.model = {"logreg": B.GCADA_LOGREG, "mlp": B.GCADA_MLP, "linreg": B.GCADA_LINREG}[model]
         self.dtype = {"f32": B.GCADA_F32, "bf16": B.GCADA_BF16}[dtype]
         self.widths, self.batch, self.G, self.M_G, self.D = tuple(widths), batch, G, M_G, D
         dims = B.make_dims(self.model, self.dtype, widths, batch, l2)
@@ -72,7 +72,7 @@ class Gcada:
             assert X.is_cuda and y.is_cuda and X.dim() == 2 and X.stride(1) == 1
             want = torch.bfloat16 if self.dtype == B.GCADA_BF16 else torch.float32
             assert X.dtype == want, (X.dtype, want)
-            assert y.dtype == (torch.float32 if self.model == B.GCADA_LOGREG else torch.int32)
+            assert y.dtype == (torch.int32 if self.model == B.GCADA_MLP else torch.float32)
             B.gcada_set_shard(self.ctx, g, X.data_ptr(), y.data_ptr(), X.shape[0], X.stride(0))
             self._keep[("shard", g)] = (X, y)
 

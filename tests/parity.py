@@ -18,7 +18,7 @@ from paper_2201_04301_amd import Gcada
 
 
 def oracle_config(w: Workload) -> O.Config:
-    model = O.LOGISTIC if w.model == "logreg" else O.MLP
+    model = {"logreg": O.LOGISTIC, "mlp": O.MLP, "linreg": O.QUADRATIC}[w.model]
     return O.Config(model, list(w.widths), batch=w.mu, G=w.G, D=w.D, c=w.c, alpha=w.alpha,
                     beta1=w.beta1, beta2=w.beta2, eps=w.eps, l2=w.l2,
                     round_bf16=(w.dtype == "bf16"))

@@ -10,6 +10,10 @@ from __future__ import annotations
 import ctypes as C
 import os
 
+# PyTorch ships its own HIP runtime; it has to be in the process BEFORE this library is loaded so
+# that both use the same one (two runtimes in one process do not see the device).
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgcada.so")
 

@@ -76,6 +76,7 @@ def lib():
         L.orc_k.restype = C.c_int64
         L.orc_k.argtypes = [C.c_void_p]
         L.orc_set_k.argtypes = [C.c_void_p, C.c_int64]
+        L.orc_set_rule.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.orc_bf16_round.restype = C.c_double
         L.orc_bf16_round.argtypes = [C.c_double]
         _lib = L
@@ -221,6 +222,17 @@ class Oracle:
     @k.setter
     def k(self, v: int):
         lib().orc_set_k(self._h, int(v))
+
+    def set_rule(self, rule: int, L=None):
+        """rule 0: same-minibatch gradient difference (default).  rule 1: the server-side condition
+        of Sec. IV, L_g^2 ||theta^k - theta^{k-tau_g}||^2 against the threshold, with the G
+        smoothness constants L; only selected groups then evaluate a gradient."""
+        Lp = None
+        if L is not None:
+            La = np.ascontiguousarray(L, dtype=np.float64)
+            assert La.shape == (self.cfg.G,)
+            Lp = La.ctypes.data
+        lib().orc_set_rule(self._h, int(rule), Lp)
 
     def step(self, X, y):
         """X: (G, mu, d) fp32 minibatch rows, y: (G, mu).  Returns (mask copy, loss)."""

@@ -73,6 +73,9 @@ typedef struct orc_ctx {
     double rhs, loss;
     int32_t *tau;                        /* G                                   */
     uint8_t *mask;                       /* G                                   */
+    int32_t rule;                        /* 0: same-minibatch gradient difference; 1: the server-side
+                                            condition of Sec. IV with smoothness constants L_g */
+    double *L;                           /* G (rule 1)                          */
 } orc_ctx;
 
 /* ---------- helpers ---------------------------------------------------- */
@@ -281,6 +284,7 @@ void orc_destroy(orc_ctx *c)
     free(c->theta); free(c->h); free(c->vhat); free(c->agg);
     free(c->theta_stale); free(c->last); free(c->grad); free(c->grad_stale);
     free(c->stat); free(c->ring); free(c->loss_g); free(c->kink); free(c->tau); free(c->mask);
+    free(c->L);
     free(c);
 }
 
@@ -297,7 +301,7 @@ orc_ctx *orc_create(const orc_config *cfg)
     c->theta_stale = calloc(G * p, 8); c->last = calloc(G * p, 8);
     c->grad = calloc(G * p, 8); c->grad_stale = calloc(G * p, 8);
     c->stat = calloc(G, 8); c->ring = calloc(cfg->D, 8); c->loss_g = calloc(G, 8); c->kink = calloc(G, 8);
-    c->tau = calloc(G, 4); c->mask = calloc(G, 1);
+    c->tau = calloc(G, 4); c->mask = calloc(G, 1); c->L = calloc(G, 8);
     for (int g = 0; g < G; ++g) c->tau[g] = cfg->D;
     return c;
 }
@@ -318,6 +322,83 @@ void orc_reset(orc_ctx *c, const double *theta0)
     c->k = 0;
 }
 
+/* Which selection rule the steps use.  rule 0 (default): a group is selected when the squared
+   norm of the difference of its two same-minibatch gradients exceeds the threshold.  rule 1:
+   the condition the paper states for the server (Sec. IV, the inequality with L_g): a group
+   is selected when L_g^2 ||theta^k - theta^{k - tau_g}||^2 exceeds the same threshold; then
+   only the selected groups evaluate a gradient, once, at theta^k (Algorithm 1).  L: G
+   smoothness constants (an input of Algorithm 1). */
+void orc_set_rule(orc_ctx *c, int32_t rule, const double *L)
+{
+    c->rule = rule;
+    if (L) memcpy(c->L, L, 8 * (size_t)c->cfg.G);
+}
+
+/* One iteration under rule 1.  The statistic field holds the left side of the condition;
+   the loss is the mean over the samples that were evaluated (0 when no group is selected). */
+static void orc_step_server_rule(orc_ctx *c, const float *X, const void *y, uint8_t *mask_out,
+                                 double *loss_out)
+{
+    const orc_config *cfg = &c->cfg;
+    const int64_t p = c->p, G = cfg->G, mu = cfg->batch, d = cfg->widths[0];
+
+    /* threshold, left sides, selection -- no gradient is needed for this */
+    double hist = 0;
+    for (int j = 0; j < cfg->D; ++j) hist += c->ring[j];
+    c->rhs = cfg->c / (double)cfg->D * hist;
+    for (int64_t g = 0; g < G; ++g) {
+        double dist = 0;
+        for (int64_t j = 0; j < p; ++j) {
+            double df = c->theta[j] - c->theta_stale[g * p + j];
+            dist += df * df;
+        }
+        c->stat[g] = c->L[g] * c->L[g] * dist;
+        c->mask[g] = (c->stat[g] > c->rhs) || (c->tau[g] >= cfg->D) || (c->rhs == 0.0);
+    }
+
+    /* the selected groups evaluate their minibatch gradient at theta^k */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t g = 0; g < G; ++g) {
+        c->kink[g] = 1.0;
+        c->loss_g[g] = 0;
+        if (!c->mask[g]) continue;
+        const float *Xg = X + g * mu * d;
+        const void *yg = (const char *)y + g * mu * 4;
+        double *pt = c->theta, *ev = NULL;
+        if (cfg->round_bf16) {
+            ev = malloc(8 * p);
+            for (int64_t j = 0; j < p; ++j) ev[j] = bf16_round(pt[j]);
+            pt = ev;
+        }
+        c->loss_g[g] = loss_grad_sum_k(cfg, pt, Xg, yg, mu, c->grad + g * p, c->kink + g);
+        free(ev);
+    }
+    double loss = 0;
+    int64_t nsel = 0;
+    for (int64_t g = 0; g < G; ++g)
+        if (c->mask[g]) { loss += c->loss_g[g]; ++nsel; }
+    c->loss = nsel ? loss / (double)(nsel * mu) : 0.0;
+
+    for (int64_t g = 0; g < G; ++g) {
+        if (c->mask[g]) {
+            for (int64_t j = 0; j < p; ++j) {
+                c->agg[j] += c->grad[g * p + j] - c->last[g * p + j];
+                c->last[g * p + j] = c->grad[g * p + j];
+                c->theta_stale[g * p + j] = c->theta[j];
+            }
+            c->tau[g] = 1;
+        } else {
+            c->tau[g] += 1;
+        }
+    }
+    double sq = orc_amsgrad(c->theta, c->h, c->vhat, c->agg, p, cfg->alpha, cfg->beta1,
+                            cfg->beta2, cfg->eps);
+    c->ring[c->k % cfg->D] = sq;
+    c->k += 1;
+    if (mask_out) memcpy(mask_out, c->mask, G);
+    if (loss_out) *loss_out = c->loss;
+}
+
 /* One iteration.  X: G x mu x widths[0] fp32 (group g's minibatch rows), y: G x mu
    (float or int32 as for orc_loss_grad_sum).  mask_out: G bytes.  loss_out: mean minibatch
    loss at theta^k over all G*mu samples (+ (l2/2)||theta||^2). */
@@ -326,6 +407,7 @@ void orc_step(orc_ctx *c, const float *X, const void *y, uint8_t *mask_out, doub
     const orc_config *cfg = &c->cfg;
     const int64_t p = c->p, G = cfg->G, mu = cfg->batch, d = cfg->widths[0];
     const int64_t ysz = 4;   /* float and int32 are both 4 bytes */
+    if (c->rule == 1) { orc_step_server_rule(c, X, y, mask_out, loss_out); return; }
 
     /* 1. two gradients per group on the same samples; statistic; loss */
 #pragma omp parallel for schedule(dynamic, 1)

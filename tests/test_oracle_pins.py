@@ -405,3 +405,90 @@ def test_zero_threshold_selects_even_when_nothing_moves():
         assert mask.all() and orc.rhs == 0.0 and (orc.stat == 0).all()
         assert loss == pytest.approx(math.log(2.0))
         np.testing.assert_array_equal(orc.theta, np.ones(5))
+
+
+# ---------------------------------------------------------------- the server-side rule (Sec. IV)
+
+def test_server_rule_c_zero_equals_statistic_rule_c_zero():
+    # c = 0 selects every group every step under either rule, so the two runs are the same
+    # distributed AMSGrad, bit for bit (the gradients at theta^k are the same arithmetic).
+    cfg, Xs, ys, theta0 = _make_run(O.QUADRATIC, [9], G=3, mu=6, rows=30, seed=21, c=0.0, D=4)
+    a, b = O.Oracle(cfg, theta0), O.Oracle(cfg, theta0)
+    b.set_rule(1, np.array([3.0, 0.5, 7.0]))
+    for k in range(17):
+        ma, la = a.step_shards(Xs, ys)
+        mb, lb = b.step_shards(Xs, ys)
+        assert ma.all() and mb.all()
+        np.testing.assert_array_equal(a.theta, b.theta)
+        assert la == lb
+
+
+def test_server_rule_left_side_mask_and_lazy_evaluation():
+    # left side = L_g^2 ||theta^k - theta^{k-tau_g}||^2 recomputed here; mask from it, the age
+    # and the threshold; an unselected group's stored gradient, stale iterate and gradient
+    # buffer are untouched (it evaluates nothing); aggregate == sum of stored gradients.
+    D = 5
+    cfg, Xs, ys, theta0 = _make_run(O.LOGISTIC, [11], G=4, mu=7, rows=35, seed=22, c=0.6, D=D,
+                                    alpha=0.05)
+    L = np.array([0.8, 1.7, 0.3, 2.5])
+    orc = O.Oracle(cfg, theta0)
+    orc.set_rule(1, L)
+    held_back = fired_early = 0
+    for k in range(40):
+        theta, stale, tau = orc.theta.copy(), orc.theta_stale.copy(), orc.tau.copy()
+        last, grad, ring = orc.last.copy(), orc.grad.copy(), orc.ring.copy()
+        mask, loss = orc.step_shards(Xs, ys)
+        rhs = cfg.c / D * ring.sum()
+        lhs = L ** 2 * ((theta[None, :] - stale) ** 2).sum(1)
+        np.testing.assert_allclose(orc.stat, lhs, rtol=1e-12)
+        assert orc.rhs == pytest.approx(rhs, rel=1e-12)
+        np.testing.assert_array_equal(mask, ((lhs > rhs) | (tau >= D) | (rhs == 0)).astype(np.uint8))
+        rows = O.cyclic_window(k, 7, 35)
+        one = O.Config(O.LOGISTIC, [11], batch=7, G=1)
+        tot = 0.0
+        for g in range(4):
+            if mask[g]:
+                l, gr = O.loss_grad_sum(one, theta, Xs[g][rows], ys[g][rows])
+                np.testing.assert_allclose(orc.last[g], gr, rtol=1e-12)
+                np.testing.assert_array_equal(orc.theta_stale[g], theta)
+                tot += l
+                fired_early += int(tau[g] < D)
+            else:
+                np.testing.assert_array_equal(orc.last[g], last[g])
+                np.testing.assert_array_equal(orc.theta_stale[g], stale[g])
+                np.testing.assert_array_equal(orc.grad[g], grad[g])
+                held_back += 1
+        if mask.any():
+            assert loss == pytest.approx(tot / (mask.sum() * 7), rel=1e-12)
+        else:
+            assert loss == 0.0
+        np.testing.assert_allclose(orc.agg, orc.last.sum(0), rtol=1e-9, atol=1e-12)
+        assert ((orc.tau >= 1) & (orc.tau <= D)).all()
+    assert held_back > 0 and fired_early > 0
+
+
+def test_server_rule_huge_c_periodic():
+    D = 3
+    cfg, Xs, ys, theta0 = _make_run(O.QUADRATIC, [8], G=2, mu=5, rows=20, seed=23, c=1e30, D=D)
+    orc = O.Oracle(cfg, theta0)
+    orc.set_rule(1, np.array([1.0, 1.0]))
+    for k in range(3 * D + 1):
+        mask, _ = orc.step_shards(Xs, ys)
+        assert mask.all() if k % D == 0 else not mask.any()
+
+
+def test_server_rule_left_side_bounds_the_statistic():
+    # the bridge between the two rules (L-smoothness): with L_g >= the largest eigenvalue of the
+    # minibatch Gram matrix, the same-minibatch gradient difference of the quadratic loss never
+    # exceeds the server-side left side, so the server-side rule selects whenever the other does.
+    cfg, Xs, ys, theta0 = _make_run(O.QUADRATIC, [9], G=3, mu=6, rows=30, seed=24, c=0.4, D=4,
+                                    alpha=0.05)
+    a = O.Oracle(cfg, theta0)
+    for k in range(25):
+        theta, stale = a.theta.copy(), a.theta_stale.copy()
+        rows = O.cyclic_window(k, 6, 30)
+        a.step_shards(Xs, ys)
+        for g in range(3):
+            Xm = Xs[g][rows].astype(np.float64)
+            Lg = np.linalg.eigvalsh(Xm.T @ Xm).max()
+            assert a.stat[g] <= Lg ** 2 * ((theta - stale[g]) ** 2).sum() * (1 + 1e-9)

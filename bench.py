@@ -31,6 +31,10 @@ def main():
     ap.add_argument("--workload", default="lr_4k")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--rule", choices=["gradient_difference", "server"], default="gradient_difference",
+                    help="selection rule: the same-minibatch gradient difference (default, the metric's "
+                         "configuration) or the paper's server-side condition with L_g from power "
+                         "iteration (linear models): only selected groups evaluate a gradient")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark: copy a buffer of this many MiB five times with a "
                          "plain device copy kernel (to calibrate rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE)")
@@ -68,6 +72,8 @@ def main():
     gpu = Gcada.from_workload(w)
     gpu.set_shards(Xs, ys)
     gpu.set_theta(make_theta0(w))
+    if args.rule == "server":
+        gpu.set_rule("server", gpu.estimate_smoothness(iters=20))
     masks = torch.zeros(K + W, w.G, dtype=torch.uint8, device="cuda")
     losses = torch.zeros(K + W, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
@@ -134,7 +140,7 @@ def main():
              "mean_selected": float(m_host.sum(1).mean())}
 
     cpu = None
-    if not args.no_cpu:
+    if not args.no_cpu and args.rule == "gradient_difference":
         import oracle as O
         sys.path.insert(0, os.path.join(ROOT, "tests"))
         from parity import oracle_config
@@ -161,7 +167,7 @@ def main():
            "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 5),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if w.dtype == "f32" else "bf16",
            "data": "synthetic",
-           "config": {"workload": w.name, "model": None, "G": w.G, "M_G": w.M_G, "mu": w.mu,
+           "config": {"workload": w.name, "rule": args.rule, "model": None, "G": w.G, "M_G": w.M_G, "mu": w.mu,
                       "widths": list(w.widths), "rows_per_shard": w.rows, "D": w.D, "c": w.c,
                       "l2": w.l2, "parallelism": "1 GPU, all groups simulated"},
            "grad_evals_per_s": round(2 * w.G * iters_s, 1),

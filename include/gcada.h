@@ -202,6 +202,33 @@ enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*
+ * Selection rule.  GCADA_RULE_GRADIENT_DIFFERENCE [default]: group g is selected when the squared
+ * norm of the difference of its two same-minibatch gradients (at theta^k and at its stale
+ * iterate) exceeds the threshold -- the quantity the paper's condition estimates (Sec. III, IV).
+ * GCADA_RULE_SERVER: the condition as the paper states it for the parameter server (Sec. IV):
+ * selected when L_g^2 ||theta^k - theta^{k - tau_g}||^2 > (c/D) sum_{d<=D} ||theta^{k+1-d} -
+ * theta^{k-d}||^2, or when the age tau_g has reached D, or when the threshold is 0.  The decision
+ * then precedes the gradient stage and only the selected groups evaluate a gradient, once, at
+ * theta^k (Algorithm 1); the returned loss is the mean over the evaluated samples (0 when no
+ * group is selected), and gcada_state's stat holds the left sides.
+ * L [host, G doubles, copied]: the smoothness constants L_g, an input of Algorithm 1; may be
+ * NULL when they were given before.  May be called between steps.
+ * Errors: GCADA_EINVAL (unknown rule, negative or non-finite L_g, GCADA_RULE_SERVER without L).
+ */
+enum { GCADA_RULE_GRADIENT_DIFFERENCE = 0, GCADA_RULE_SERVER = 1 };
+int gcada_set_rule(gcada_ctx* ctx, int32_t rule, const double* L);
+
+/*
+ * Smoothness constants of the groups' local functions (Sec. IV: the average loss over the
+ * group's shard) for the linear models: L_g = kappa * lambda_max(X_g^T X_g) / rows_g + lambda,
+ * kappa = 1/4 (logistic) or 1 (quadratic error), the eigenvalue by `iters` steps of power
+ * iteration on the shard (two passes over the shard per step; synchronises `stream`).
+ * L_out [host, G doubles].  Errors: GCADA_EINVAL (MLP, NULL, iters < 1), GCADA_ESTATE (a shard
+ * is missing), GCADA_EDEVICE.
+ */
+int gcada_estimate_smoothness(gcada_ctx* ctx, int32_t iters, double* L_out, void* stream);
+
+/*
  * Diagnostics for benchmarks: run only the dominant kernel(s) of step a1 -- the kernels that
  * read the minibatch; gcada_timed_stage names them -- `reps` times back to back on `stream`
  * between two HIP events; repetition r uses the minibatch idx + r*idx_stride (G*mu ids each, as in

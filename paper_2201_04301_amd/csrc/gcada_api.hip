@@ -67,6 +67,7 @@ void free_all(gcada_ctx* c)
     gcada::mlp_free(c);
     gcada::lr_tile_free(c);
     gcada::lr_team_free(c);
+    gcada::rule_free(c);
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->gbuf, c->which, c->tau,
                     c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat, c->stat_sum,
                     c->part_sq};
@@ -155,6 +156,7 @@ try {
     e = dims->model != GCADA_MLP ? gcada::lr_plan(x) : gcada::mlp_plan(x);
     if (e != hipSuccess) return bail(e, "model plan");
     if ((e = gcada::select_plan(x)) != hipSuccess) return bail(e, "server plan");
+    if ((e = gcada::rule_plan(x)) != hipSuccess) return bail(e, "selection rule plan");
     if (dims->model != GCADA_MLP && (e = gcada::lr_tile_plan(x)) != hipSuccess)
         return bail(e, "single-pass logistic plan");
     if (dims->model != GCADA_MLP && (e = gcada::lr_team_plan(x)) != hipSuccess)
@@ -264,10 +266,22 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
         if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "step: a group has no shard");
     hipStream_t s = (hipStream_t)stream;
     set_iteration(ctx);
-    hipError_t e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, idx, s)
-                                                   : gcada::mlp_gradients(ctx, idx, s);
+    hipError_t e;
+    const bool server_rule = ctx->rule == GCADA_RULE_SERVER;
+    if (server_rule) {
+        // Sec. IV / Algorithm 1: the server decides first, from the iterates alone; the gradient
+        // kernels then skip the unselected groups and the stale iterate
+        if (!ctx->rule_L_set) return fail(ctx, GCADA_ESTATE, "step: the server-side rule needs the constants L_g");
+        if ((e = gcada::rule_select(ctx, mask_out, s)) != hipSuccess) return fail_hip(ctx, e, "selection kernels");
+        ctx->hy.sel = ctx->mask;
+    } else {
+        ctx->hy.sel = nullptr;
+    }
+    e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, idx, s) : gcada::mlp_gradients(ctx, idx, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
-    if ((e = gcada::server_step(ctx, mask_out, loss_out, s)) != hipSuccess)
+    if (server_rule && (e = gcada::rule_loss(ctx, loss_out, s)) != hipSuccess)
+        return fail_hip(ctx, e, "loss kernel");
+    if ((e = gcada::server_step(ctx, mask_out, loss_out, server_rule, s)) != hipSuccess)
         return fail_hip(ctx, e, "server kernels");
     if (ctx->dims.model == GCADA_MLP) {
         // compute copies (padded, transposed, bf16) of the new iterate's hidden-layer weights
@@ -389,6 +403,47 @@ int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
         return GCADA_OK;
     }
     return fail(ctx, GCADA_EINVAL, "set_option: unknown option");
+}
+
+int gcada_set_rule(gcada_ctx* ctx, int32_t rule, const double* L)
+{
+    if (!ctx) return GCADA_EINVAL;
+    if (rule != GCADA_RULE_GRADIENT_DIFFERENCE && rule != GCADA_RULE_SERVER)
+        return fail(ctx, GCADA_EINVAL, "set_rule: unknown rule");
+    if (L) {
+        for (int g = 0; g < ctx->hy.G; ++g)
+            if (!(L[g] >= 0.0) || !std::isfinite(L[g]))
+                return fail(ctx, GCADA_EINVAL, "set_rule: every L_g must be finite and >= 0");
+        hipError_t e = hipMemcpy(ctx->rule_L, L, sizeof(double) * (size_t)ctx->hy.G, hipMemcpyHostToDevice);
+        if (e != hipSuccess) return fail_hip(ctx, e, "set_rule: copy of L");
+        ctx->rule_L_set = true;
+    }
+    if (rule == GCADA_RULE_SERVER && !ctx->rule_L_set)
+        return fail(ctx, GCADA_EINVAL, "set_rule: the server-side rule needs the constants L_g");
+    ctx->rule = rule;
+    return GCADA_OK;
+}
+
+int gcada_estimate_smoothness(gcada_ctx* ctx, int32_t iters, double* L_out, void* stream)
+try {
+    if (!ctx) return GCADA_EINVAL;
+    if (!L_out || iters < 1) return fail(ctx, GCADA_EINVAL, "estimate_smoothness: L_out must not be NULL, iters >= 1");
+    if (ctx->dims.model == GCADA_MLP)
+        return fail(ctx, GCADA_EINVAL, "estimate_smoothness: linear models only (pass L_g to gcada_set_rule for an MLP)");
+    for (int g = 0; g < ctx->hy.G; ++g)
+        if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "estimate_smoothness: a group has no shard");
+    // smoothness constant of the group's local function, the average loss over its shard
+    // (Sec. IV): kappa * lambda_max(X^T X) / rows + lambda, kappa = 1/4 logistic, 1 quadratic
+    const double kappa = ctx->dims.model == GCADA_LINREG ? 1.0 : 0.25;
+    for (int g = 0; g < ctx->hy.G; ++g) {
+        double lam = 0;
+        hipError_t e = gcada::rule_power_iteration(ctx, g, iters, &lam, (hipStream_t)stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "estimate_smoothness: power iteration");
+        L_out[g] = kappa * lam / (double)ctx->shards[g].rows + (double)ctx->dims.l2;
+    }
+    return GCADA_OK;
+} catch (...) {
+    return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_estimate_smoothness");
 }
 
 const char* gcada_timed_stage(gcada_ctx* ctx)

@@ -40,6 +40,9 @@ struct Hyper {
     int64_t p, pstride;     // parameters; floats between ring slots
     float l2;
     int32_t quadratic;      // linear models: 1 = quadratic error loss, 0 = logistic loss
+    const uint8_t* sel;     // server-side rule (Sec. IV): the mask decided BEFORE the gradients; a
+                            // group with 0 evaluates nothing, the others evaluate one gradient at
+                            // theta^k only.  Null (default rule): every group, both iterates.
     double c, alpha, beta1, beta2, eps;
 };
 
@@ -120,6 +123,12 @@ struct gcada_ctx {
     gcada::LrTilePlan* lr_tiles = nullptr;
     gcada::LrTeamPlan* lr_team = nullptr;
     unsigned team_launches = 0;    // advances the exchange tags of the team kernel
+    // server-side rule (Sec. IV): 0 = gradient-difference statistic, 1 = L_g^2 ||theta^k - theta_stale||^2
+    int32_t rule = 0;
+    double* rule_L = nullptr;      // G smoothness constants (device)
+    double* rule_part = nullptr;   // D x rule_nb partial squared distances
+    int32_t rule_nb = 0;
+    bool rule_L_set = false;
     bool allow_single_pass = true;
 
     bool dominant_only = false;    // benchmark diagnostic: launch only the dominant gradient kernel(s)
@@ -156,7 +165,15 @@ hipError_t mlp_refresh_slot(gcada_ctx* c, int slot, hipStream_t s);   // ... of 
 hipError_t select_plan(gcada_ctx* c);
 // selection (a2) + masked innovation sum (a3) + server update and history (a4); advances
 // Ctl::k and the ages; writes mask_out / loss_out
-hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s);
+// preselected: the mask (and rhs, loss) were already decided by the server-side rule
+hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool preselected, hipStream_t s);
+
+// server-side rule of Sec. IV (rule_kernels.hip)
+hipError_t rule_plan(gcada_ctx* c);
+void rule_free(gcada_ctx* c);
+hipError_t rule_select(gcada_ctx* c, uint8_t* mask_out, hipStream_t s);
+hipError_t rule_loss(gcada_ctx* c, float* loss_out, hipStream_t s);
+hipError_t rule_power_iteration(gcada_ctx* c, int g, int iters, double* lambda_out, hipStream_t s);
 // ||theta^k||^2 of the current slot -> Ctl::theta_sq (after set_theta / set_state)
 hipError_t refresh_theta_sq(gcada_ctx* c, hipStream_t s);
 

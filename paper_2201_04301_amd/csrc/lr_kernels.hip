@@ -36,6 +36,10 @@ __global__ __launch_bounds__(kFwdWaves* kWave) void lr_forward(
     Hyper hy, float* __restrict__ res, double* __restrict__ part_loss)
 {
     const int g = blockIdx.y;
+    if (hy.sel && !hy.sel[g]) {                  // unselected group: no gradient, no loss
+        if (threadIdx.x == 0) part_loss[(int64_t)g * gridDim.x + blockIdx.x] = 0;
+        return;
+    }
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int d = (int)hy.p, mu = hy.mu;
     const long long k = hy.k;
@@ -121,6 +125,7 @@ __global__ __launch_bounds__(kBwdWaves* kWave) void lr_backward(
     __shared__ float4 s_acc[2][kBwdWaves][kWave];           // cross-wave reduction
 
     const int g = blockIdx.y;
+    if (hy.sel && !hy.sel[g]) return;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int d = (int)hy.p, mu = hy.mu;
     const long long k = hy.k;

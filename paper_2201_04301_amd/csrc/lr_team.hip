@@ -120,6 +120,14 @@ struct TeamLds {
     double s_red[kDataWaves];
 };
 
+// The team's next group after g: g + NT, g + 2 NT, ... -- under the server-side rule only groups
+// whose mask is set (the others evaluate nothing).  Returns a value >= G when there is none.
+__device__ __forceinline__ int team_next_group(const Hyper& hy, int g, int NT)
+{
+    do g += NT; while (g < hy.G && hy.sel && !hy.sel[g]);
+    return g;
+}
+
 // Describe the tile after the one S.gF/S.tF point at -- row ids through scalar loads (constant
 // address space, uniform address): they are counted apart from the vector loads, so fetching
 // them never waits for a tile in flight.  Past the end of the sequence the last tile is
@@ -129,7 +137,7 @@ __device__ __forceinline__ void team_fetch(const TeamArgs& a, TeamSeq& S, int nF
     typedef const int32_t __attribute__((address_space(4))) const_i32;
     typedef const ShardDesc __attribute__((address_space(4))) const_shard;
     if (nF < S.ntot && nF > 0) {
-        if (++S.tF == S.ntile) { S.tF = 0; S.gF += NT; }
+        if (++S.tF == S.ntile) { S.tF = 0; S.gF = team_next_group(a.hy, S.gF, NT); }
     }
     const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
     const unsigned rows = (unsigned)sh->rows;
@@ -179,10 +187,10 @@ __device__ __forceinline__ float team_load_label(const TeamArgs& a, const TeamSe
 }
 
 // Move S.gF/S.tF on to tile nF (the control wave's share of team_fetch).
-__device__ __forceinline__ void team_advance(TeamSeq& S, int nF, int NT)
+__device__ __forceinline__ void team_advance(const TeamArgs& a, TeamSeq& S, int nF, int NT)
 {
     if (nF < S.ntot && nF > 0) {
-        if (++S.tF == S.ntile) { S.tF = 0; S.gF += NT; }
+        if (++S.tF == S.ntile) { S.tF = 0; S.gF = team_next_group(a.hy, S.gF, NT); }
     }
 }
 
@@ -253,7 +261,7 @@ __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, 
         for (int u = 0; u < kR; ++u)
 #pragma unroll
             for (int q = 0; q < kV; ++q) mine[(u * kV + q) * kDataThreads] = R.xb[J][u][q];
-        if (++S.tC == S.ntile) { S.tC = 0; S.gC += a.NT; }
+        if (++S.tC == S.ntile) { S.tC = 0; S.gC = team_next_group(a.hy, S.gC, a.NT); }
     }
 
     if (have_add) {
@@ -286,7 +294,7 @@ __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, 
                 a.part_stat[(int64_t)g * a.TS + m] = tsum;
             }
             S.tA = 0;
-            S.gA += a.NT;
+            S.gA = team_next_group(a.hy, S.gA, a.NT);
         } else {
             ++S.tA;
         }
@@ -317,7 +325,7 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
         L.s_y[(n + 1) % kLabelRing][lane] = y_new;
         y_new = team_load_label(a, S, lane);
     }
-    team_advance(S, n + 3, a.NT);
+    team_advance(a, S, n + 3, a.NT);
 
     if (have_add) {
         const unsigned want = a.tag_base + (unsigned)n - 2u;
@@ -368,7 +376,7 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
             if (m == 0 && lane == 0) a.part_loss[S.gA] = l;
             lacc = 0;
             S.tA = 0;
-            S.gA += a.NT;
+            S.gA = team_next_group(a.hy, S.gA, a.NT);
         } else {
             ++S.tA;
         }
@@ -392,13 +400,25 @@ __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
     // stages 0 .. ntot+1 (the last two only drain), three at a time; stages past the end do
     // nothing but request the last tile again
     const int ntile = hy.mu / kR;
-    const int ntot = ((hy.G - team + a.NT - 1) / a.NT) * ntile;
+    // the team's groups: team, team + NT, ... -- under the server-side rule the selected ones only
+    // (an unselected group contributes a zero loss partial and nothing else)
+    int g_first = -1, ngroups = 0;
+    for (int g = team; g < hy.G; g += a.NT) {
+        if (!hy.sel || hy.sel[g]) {
+            if (g_first < 0) g_first = g;
+            ++ngroups;
+        } else if (m == 0 && tid == 0) {
+            a.part_loss[g] = 0;
+        }
+    }
+    if (ngroups == 0) return;                    // the whole team leaves
+    const int ntot = ngroups * ntile;
     const int nstage = ntot + 2;
 
     if (wave == kDataWaves) {
         TeamSeq S;
         S.ntile = ntile; S.ntot = ntot;
-        S.gF = S.gC = S.gA = team;
+        S.gF = S.gC = S.gA = g_first;
         S.tF = S.tC = S.tA = 0;
         // ---- control wave ----
         unsigned long long* xt = a.xch + (int64_t)team * kSlots * a.TS * kPartial;   // the team's slots
@@ -406,9 +426,9 @@ __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
         float y_new = 1.0f;
         double lacc = 0;
         if (lane < kR) L.s_y[0][lane] = team_load_label(a, S, lane);
-        team_advance(S, 1, a.NT);
+        team_advance(a, S, 1, a.NT);
         if (lane < kR) y_new = team_load_label(a, S, lane);
-        team_advance(S, 2, a.NT);
+        team_advance(a, S, 2, a.NT);
         for (int n = 0; n < nstage; n += kRegTiles) {
             team_control_stage(a, S, xt, n, m, gave_up, y_new, lacc, L);
             team_control_stage(a, S, xt, n + 1, m, gave_up, y_new, lacc, L);
@@ -418,7 +438,7 @@ __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
         // ---- data waves ----
         TeamSeq S;
         S.ntile = ntile; S.ntot = ntot;
-        S.gF = S.gC = S.gA = team;
+        S.gF = S.gC = S.gA = g_first;
         S.tF = S.tC = S.tA = 0;
         const int col = m * kSlab + wave * (256 * kV) + lane * 4;    // and col + 256
         TeamRegs R;

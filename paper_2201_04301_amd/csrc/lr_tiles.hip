@@ -47,6 +47,10 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int wr = wave / WC, wc = wave % WC;
     const int g = blockIdx.x / a.RB, rb = blockIdx.x % a.RB;
+    if (hy.sel && !hy.sel[g]) {                  // unselected group: no gradient, no loss
+        if (tid == 0) a.part_loss[blockIdx.x] = 0;
+        return;
+    }
     const int mu = hy.mu;
     const long long k = hy.k;
     const ShardDesc sh = a.shards[g];
@@ -161,6 +165,7 @@ __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
 {
     __shared__ double s_red[kRedBlock / kWave];
     const int g = blockIdx.y;
+    if (hy.sel && !hy.sel[g]) return;
     const int64_t j = ((int64_t)blockIdx.x * kRedBlock + threadIdx.x) * 4;
     double sq = 0;
     if (j < hy.p) {

@@ -358,6 +358,15 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         }
     }
     const int m0 = by * BM, n0 = bx * BN;
+    // server-side rule: unselected groups evaluate nothing (their loss partial is zero), the
+    // others one gradient at theta^k only
+    if (hy.sel) {
+        if (!hy.sel[g]) {
+            if (EPI == EPI_HEAD && it0 == 0 && tid == 0) a.part_loss[(int64_t)g * gridDim.y + by] = 0;
+            return;
+        }
+        if (EPI != EPI_DW && it0 == 1) return;
+    }
     constexpr int esz = (int)sizeof(T);
 
     f32x16 acc[TM][TN];
@@ -387,6 +396,7 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
                     const int n = n0 + wn * CW + j * 32 + cl;
                     if (m < a.M && n < a.N) gb[(int64_t)m * a.N + n] = acc[i][j][e];
                 }
+        if (hy.sel) return;                      // server-side rule: no stale pass, no statistic
         gemm_pass<T, TL>(a, 1, g, m0, n0, lds, acc);
         double sq = 0;
 #pragma unroll
@@ -696,6 +706,7 @@ __global__ __launch_bounds__(256) void mlp_gather(Hyper hy, const ShardDesc* __r
 {
     __shared__ T tile[64][64 + 2];
     const int g = blockIdx.z, c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+    if (hy.sel && !hy.sel[g]) return;            // unselected group (server-side rule)
     const ShardDesc sh = shards[g];
     const T* X = (const T*)sh.X;
     const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
@@ -731,6 +742,7 @@ __global__ __launch_bounds__(256) void mlp_gather_vec(Hyper hy, const ShardDesc*
     constexpr int V = 16 / (int)sizeof(T), TC = 8 * V, PITCH = 64 + V;
     __shared__ __align__(16) T tileT[TC][PITCH];
     const int g = blockIdx.z, c0 = blockIdx.x * TC, r0 = blockIdx.y * 64;
+    if (hy.sel && !hy.sel[g]) return;            // unselected group (server-side rule)
     const ShardDesc sh = shards[g];
     const T* X = (const T*)sh.X;
 #pragma unroll
@@ -801,6 +813,7 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
     constexpr int V = 16 / (int)sizeof(T);
     __shared__ double s_red[4];
     const int g = blockIdx.y, wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    if (hy.sel && !hy.sel[g]) return;            // unselected group (server-side rule)
     const int hl = lane & 31;                         // lane within the half wave
     const int n = blockIdx.x * 8 + wave * 2 + (lane >> 5);
     double sq = 0;

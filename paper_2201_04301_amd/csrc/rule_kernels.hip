@@ -1,0 +1,259 @@
+// The selection rule as the paper states it for the parameter server (Sec. IV, the condition
+// with L_g; Algorithm 1): group g is selected when
+//     L_g^2 ||theta^k - theta^{k - tau_g}||^2  >  (c/D) sum_{d<=D} ||theta^{k+1-d} - theta^{k-d}||^2
+// or its age has reached D.  The decision needs no gradient, so it is taken BEFORE the gradient
+// stage, and only the selected groups evaluate a gradient -- one, at theta^k.
+// Also here: the smoothness constants L_g of the linear models by power iteration on the shard.
+#include "gcada_internal.h"
+
+namespace gcada {
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// block sum in a fixed order; result valid on thread 0
+__device__ __forceinline__ double block_sum(double a, double* s_tmp)
+{
+    a = wave_sum(a);
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    __syncthreads();
+    if (lane == 0) s_tmp[wave] = a;
+    __syncthreads();
+    double t = 0;
+    if (threadIdx.x == 0)
+        for (int w = 0; w < kBlock / kWave; ++w) t += s_tmp[w];
+    return t;
+}
+
+// Partial squared distances of theta^k to the D older iterates of the ring.
+// grid: (nb, D); out[t][b] = sum over the block's slab of (theta^k - theta^{k-1-t})^2.
+__global__ __launch_bounds__(kBlock) void rule_dist_kernel(Hyper hy, const float* __restrict__ ring,
+                                                           double* __restrict__ out)
+{
+    __shared__ double s_tmp[kBlock / kWave];
+    const int t = blockIdx.y + 1;                               // age
+    int slot = hy.cur - t;
+    if (slot < 0) slot += hy.D + 1;
+    const float* a = ring + (int64_t)hy.cur * hy.pstride;
+    const float* b = ring + (int64_t)slot * hy.pstride;
+    double acc = 0;
+    for (int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4; j < hy.pstride;
+         j += (int64_t)gridDim.x * kBlock * 4) {
+        const float4 x = *(const float4*)(a + j), y = *(const float4*)(b + j);
+        const double d0 = (double)x.x - (double)y.x, d1 = (double)x.y - (double)y.y;
+        const double d2 = (double)x.z - (double)y.z, d3 = (double)x.w - (double)y.w;
+        acc += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+    }
+    const double tot = block_sum(acc, s_tmp);
+    if (threadIdx.x == 0) out[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = tot;
+}
+
+// One block: distances, threshold, left sides, mask.  stat <- the left sides.
+__global__ __launch_bounds__(kBlock) void rule_select_kernel(
+    Hyper hy, const double* __restrict__ part_dist, int nb, const double* __restrict__ L,
+    const double* __restrict__ nring, const int32_t* __restrict__ tau, double* __restrict__ stat,
+    uint8_t* __restrict__ mask, Ctl* __restrict__ ctl, uint8_t* __restrict__ mask_out)
+{
+    __shared__ double s_dist[64];            // D <= 64 is checked on the host
+    __shared__ double s_rhs;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    for (int t = wave; t < hy.D; t += kBlock / kWave) {
+        double a = 0;
+        for (int i = lane; i < nb; i += kWave) a += part_dist[(int64_t)t * nb + i];
+        a = wave_sum(a);
+        if (lane == 0) s_dist[t] = a;
+    }
+    if (wave == 0) {
+        double v = 0;
+        for (int j = lane; j < hy.D; j += kWave) v += nring[j];
+        v = wave_sum(v);
+        if (lane == 0) s_rhs = hy.c / (double)hy.D * v;
+    }
+    __syncthreads();
+    const double rhs = s_rhs;
+    for (int g = threadIdx.x; g < hy.G; g += kBlock) {
+        const int t = tau[g];                                   // 1 <= t <= D
+        const double lhs = L[g] * L[g] * s_dist[t - 1];
+        const bool sel = (lhs > rhs) || (t >= hy.D) || (rhs == 0.0);
+        stat[g] = lhs;
+        mask[g] = sel ? 1 : 0;
+        if (mask_out) mask_out[g] = sel ? 1 : 0;
+    }
+    if (threadIdx.x == 0) ctl->rhs = rhs;
+}
+
+// One block, after the gradient stage: mean loss over the samples that were evaluated (the
+// unselected groups left zero partials), 0 when no group was selected.
+__global__ __launch_bounds__(kBlock) void rule_loss_kernel(Hyper hy, const double* __restrict__ part_loss,
+                                                           int n_loss_total, const uint8_t* __restrict__ mask,
+                                                           Ctl* __restrict__ ctl, float* __restrict__ loss_out)
+{
+    __shared__ double s_tmp[kBlock / kWave];
+    double a = 0;
+    for (int i = threadIdx.x; i < n_loss_total; i += kBlock) a += part_loss[i];
+    const double lsum = block_sum(a, s_tmp);
+    double n = 0;
+    for (int g = threadIdx.x; g < hy.G; g += kBlock) n += mask[g] ? 1.0 : 0.0;
+    const double nsel = block_sum(n, s_tmp);
+    if (threadIdx.x == 0) {
+        const double loss = nsel > 0 ? lsum / (nsel * (double)hy.mu) + 0.5 * (double)hy.l2 * ctl->theta_sq : 0.0;
+        ctl->loss = loss;
+        if (loss_out) *loss_out = (float)loss;
+    }
+}
+
+// ---- power iteration on X^T X of one shard (linear models) ----------------------------------
+// t_i = x_i . v for a chunk of rows: one wave per row.  grid: ceil(rows / 4), block 256.
+__global__ __launch_bounds__(kBlock) void pi_forward_kernel(const float* __restrict__ X, int64_t rows, int64_t ld,
+                                                            int d, const double* __restrict__ v,
+                                                            double* __restrict__ t)
+{
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int64_t i = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
+    if (i >= rows) return;
+    const float* x = X + i * ld;
+    double a = 0;
+    for (int j = lane; j < d; j += kWave) a += (double)x[j] * v[j];
+    a = wave_sum(a);
+    if (lane == 0) t[i] = a;
+}
+
+// w_part[chunk][j] = sum over the chunk's rows of t_i X[i][j].  grid: (ceil(d / 256), chunks).
+__global__ __launch_bounds__(kBlock) void pi_backward_kernel(const float* __restrict__ X, int64_t rows, int64_t ld,
+                                                             int d, const double* __restrict__ t,
+                                                             int64_t rows_per_chunk, double* __restrict__ w_part)
+{
+    const int j = blockIdx.x * kBlock + threadIdx.x;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_chunk;
+    const int64_t r1 = r0 + rows_per_chunk < rows ? r0 + rows_per_chunk : rows;
+    if (j >= d) return;
+    double a = 0;
+    for (int64_t i = r0; i < r1; ++i) a += t[i] * (double)X[i * ld + j];
+    w_part[(int64_t)blockIdx.y * d + j] = a;
+}
+
+// w = sum of the chunk partials (fixed order); partial ||w||^2 per block.  grid: ceil(d / 256).
+__global__ __launch_bounds__(kBlock) void pi_reduce_kernel(const double* __restrict__ w_part, int chunks, int d,
+                                                           double* __restrict__ w, double* __restrict__ part_sq)
+{
+    __shared__ double s_tmp[kBlock / kWave];
+    const int j = blockIdx.x * kBlock + threadIdx.x;
+    double a = 0;
+    if (j < d) {
+        for (int c = 0; c < chunks; ++c) a += w_part[(int64_t)c * d + j];
+        w[j] = a;
+    }
+    const double sq = block_sum(a * a, s_tmp);
+    if (threadIdx.x == 0) part_sq[blockIdx.x] = sq;
+}
+
+// One block: norm = sqrt(sum of the partials); v <- w / norm; norms[it] <- norm.
+__global__ __launch_bounds__(kBlock) void pi_normalize_kernel(const double* __restrict__ w, const double* __restrict__ part_sq,
+                                                              int nparts, int d, double* __restrict__ v,
+                                                              double* __restrict__ norm_out)
+{
+    __shared__ double s_tmp[kBlock / kWave];
+    __shared__ double s_norm;
+    double a = 0;
+    for (int i = threadIdx.x; i < nparts; i += kBlock) a += part_sq[i];
+    const double tot = block_sum(a, s_tmp);
+    if (threadIdx.x == 0) {
+        s_norm = sqrt(tot);
+        *norm_out = s_norm;
+    }
+    __syncthreads();
+    const double inv = s_norm > 0 ? 1.0 / s_norm : 0.0;
+    for (int j = threadIdx.x; j < d; j += kBlock) v[j] = w[j] * inv;
+}
+
+}  // namespace
+
+// Selection under the server-side rule; enqueued before the gradient stage.
+hipError_t rule_select(gcada_ctx* c, uint8_t* mask_out, hipStream_t s)
+{
+    const int nb = c->rule_nb;
+    rule_dist_kernel<<<dim3(nb, c->hy.D), kBlock, 0, s>>>(c->hy, c->ring, c->rule_part);
+    rule_select_kernel<<<1, kBlock, 0, s>>>(c->hy, c->rule_part, nb, c->rule_L, c->nring, c->tau, c->stat,
+                                            c->mask, c->ctl, mask_out);
+    return hipGetLastError();
+}
+
+hipError_t rule_loss(gcada_ctx* c, float* loss_out, hipStream_t s)
+{
+    rule_loss_kernel<<<1, kBlock, 0, s>>>(c->hy, c->part_loss, c->n_loss_used, c->mask, c->ctl, loss_out);
+    return hipGetLastError();
+}
+
+hipError_t rule_plan(gcada_ctx* c)
+{
+    if (c->hy.D > 64) return hipErrorInvalidValue;
+    const int64_t per_block = (int64_t)kBlock * 4;
+    c->rule_nb = (int)std::min<int64_t>((c->hy.pstride + per_block - 1) / per_block, 512);
+    hipError_t e;
+    if ((e = hipMalloc(&c->rule_part, sizeof(double) * (size_t)c->rule_nb * c->hy.D)) != hipSuccess) return e;
+    if ((e = hipMalloc(&c->rule_L, sizeof(double) * (size_t)c->hy.G)) != hipSuccess) return e;
+    return hipMemset(c->rule_L, 0, sizeof(double) * (size_t)c->hy.G);
+}
+
+void rule_free(gcada_ctx* c)
+{
+    if (c->rule_part) (void)hipFree(c->rule_part);
+    if (c->rule_L) (void)hipFree(c->rule_L);
+    c->rule_part = nullptr;
+    c->rule_L = nullptr;
+}
+
+// Largest eigenvalue of X^T X of shard g by `iters` steps of power iteration from a fixed start
+// vector.  Synchronises the stream.  lambda_out on the host.
+hipError_t rule_power_iteration(gcada_ctx* c, int g, int iters, double* lambda_out, hipStream_t s)
+{
+    const ShardDesc& sh = c->shards[g];
+    const int d = (int)c->hy.p;
+    const int64_t rows = sh.rows;
+    const int chunks = (int)std::min<int64_t>(256, (rows + 63) / 64);
+    const int64_t rpc = (rows + chunks - 1) / chunks;
+    const int nbd = (d + kBlock - 1) / kBlock;
+    double *v = nullptr, *t = nullptr, *w = nullptr, *wp = nullptr, *psq = nullptr, *norm = nullptr;
+    hipError_t e = hipSuccess;
+    auto done = [&](hipError_t r) {
+        for (double* q : {v, t, w, wp, psq, norm})
+            if (q) (void)hipFree(q);
+        return r;
+    };
+    if ((e = hipMalloc(&v, 8 * (size_t)d)) != hipSuccess) return done(e);
+    if ((e = hipMalloc(&t, 8 * (size_t)rows)) != hipSuccess) return done(e);
+    if ((e = hipMalloc(&w, 8 * (size_t)d)) != hipSuccess) return done(e);
+    if ((e = hipMalloc(&wp, 8 * (size_t)chunks * d)) != hipSuccess) return done(e);
+    if ((e = hipMalloc(&psq, 8 * (size_t)nbd)) != hipSuccess) return done(e);
+    if ((e = hipMalloc(&norm, 8)) != hipSuccess) return done(e);
+    // start vector: a fixed pattern with a component along every coordinate
+    std::vector<double> h0(d);
+    double n2 = 0;
+    for (int j = 0; j < d; ++j) { h0[j] = 1.0 + 0.5 * ((j * 2654435761u >> 16) & 0xff) / 255.0; n2 += h0[j] * h0[j]; }
+    for (int j = 0; j < d; ++j) h0[j] /= std::sqrt(n2);
+    if ((e = hipMemcpyAsync(v, h0.data(), 8 * (size_t)d, hipMemcpyHostToDevice, s)) != hipSuccess) return done(e);
+    const float* X = (const float*)sh.X;
+    for (int it = 0; it < iters; ++it) {
+        pi_forward_kernel<<<(unsigned)((rows + 3) / 4), kBlock, 0, s>>>(X, rows, sh.ld, d, v, t);
+        pi_backward_kernel<<<dim3(nbd, chunks), kBlock, 0, s>>>(X, rows, sh.ld, d, t, rpc, wp);
+        pi_reduce_kernel<<<nbd, kBlock, 0, s>>>(wp, chunks, d, w, psq);
+        pi_normalize_kernel<<<1, kBlock, 0, s>>>(w, psq, nbd, d, v, norm);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return done(e);
+    double lam = 0;
+    if ((e = hipMemcpyAsync(&lam, norm, 8, hipMemcpyDeviceToHost, s)) != hipSuccess) return done(e);
+    if ((e = hipStreamSynchronize(s)) != hipSuccess) return done(e);
+    *lambda_out = lam;                  // ||X^T X v|| with ||v|| = 1 converges to lambda_max
+    return done(hipSuccess);
+}
+
+}  // namespace gcada

@@ -291,8 +291,10 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
         }
 #pragma unroll
         for (int q = 0; q < VW; ++q) {
-            hv[q] = b1 * hv[q] + ob1 * ac[q];
-            const float v = b2 * vv[q] + ob2 * ac[q] * ac[q];
+            // explicit fused multiply-adds: the rounding must not depend on how the compiler
+            // contracts the expression in one instantiation of this kernel or another
+            hv[q] = fmaf(b1, hv[q], ob1 * ac[q]);
+            const float v = fmaf(b2, vv[q], ob2 * ac[q] * ac[q]);
             vv[q] = fmaxf(vv[q], v);
             const float step = al * hv[q] / sqrtf(ep + vv[q]);
             nv[q] = tv[q] - step;
@@ -405,7 +407,7 @@ static void launch_server(bool self_select, int blocks, size_t lds, hipStream_t 
 }
 
 // Selection + masked innovation sum + server update + history for one iteration.
-hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s)
+hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool preselected, hipStream_t s)
 {
     const size_t lds = ((size_t)c->hy.G * 17 + 15) / 16 * 16;   // a double, two ints, a byte per group
     ServerArgs a{};
@@ -414,15 +416,15 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStre
     a.stat = c->stat; a.mask = c->mask; a.mask_out = mask_out; a.loss_out = loss_out;
     a.gbuf = c->gbuf; a.which = c->which; a.agg = c->agg; a.h = c->h; a.vhat = c->vhat;
     a.ring = c->ring; a.nring = c->nring; a.tau = c->tau; a.part_sq = c->part_sq; a.ctl = c->ctl;
-    if (c->n_stat_used > 16) {
+    if (!preselected && c->n_stat_used > 16) {
         // many partials per group (MLP weight-gradient tiles): add them up with one block per group
         stat_reduce_kernel<<<c->hy.G, kSelBlock, 0, s>>>(c->part_stat, c->n_stat_used, c->stat_sum);
         a.part_stat = c->stat_sum;
         a.n_stat = 1;
     }
     // every update block re-adds the (remaining) partial statistics when that is cheap
-    const bool self_select = (int64_t)c->hy.G * a.n_stat + c->n_loss_used <= 4096;
-    if (!self_select)
+    const bool self_select = !preselected && (int64_t)c->hy.G * a.n_stat + c->n_loss_used <= 4096;
+    if (!self_select && !preselected)
         select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(
             c->hy, a.part_stat, a.n_stat, c->part_loss, c->n_loss_used, c->nring, c->tau,
             c->stat, c->mask, c->ctl, mask_out, loss_out);

@@ -137,6 +137,24 @@ class Gcada:
         st.k = int(k)
         B.gcada_set_state(self.ctx, st)
 
+    # ---- selection rule
+    def set_rule(self, rule: str, L=None):
+        """rule: "gradient_difference" (default) or "server" (the paper's condition with the
+        smoothness constants L_g, lazy gradient evaluation).  L: G floats (host)."""
+        code = {"gradient_difference": B.GCADA_RULE_GRADIENT_DIFFERENCE, "server": B.GCADA_RULE_SERVER}[rule]
+        Lp = None
+        if L is not None:
+            La = np.ascontiguousarray(np.asarray(L, dtype=np.float64))
+            assert La.shape == (self.G,)
+            Lp = La.ctypes.data
+        B.gcada_set_rule(self.ctx, code, Lp)
+
+    def estimate_smoothness(self, iters: int = 30) -> np.ndarray:
+        out = np.empty(self.G, np.float64)
+        B.gcada_estimate_smoothness(self.ctx, iters, out.ctypes.data,
+                                    torch.cuda.current_stream().cuda_stream)
+        return out
+
     def cost_model(self, mask: np.ndarray, T: np.ndarray):
         mask = np.ascontiguousarray(mask, dtype=np.uint8)
         T = np.ascontiguousarray(T, dtype=np.float64)

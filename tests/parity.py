@@ -51,7 +51,7 @@ def push_state(orc: O.Oracle, gpu: Gcada):
 
 
 def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, kink_tol=None,
-                   kink_grad_tol=5e-2, stat_vs_threshold=False, verbose=False):
+                   kink_grad_tol=5e-2, stat_vs_threshold=False, verbose=False, server_rule_L=None):
     """Run `steps` iterations; idx: int32 (steps, G, mu) row ids or None for the cyclic window.
     kink_tol (MLP): a group is "near a ReLU kink" in a step when some hidden pre-activation of the
     oracle lies within kink_tol (relative to the sum of the magnitudes of its terms) of zero.
@@ -62,11 +62,17 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
     stat_vs_threshold (bf16): the statistic's error is measured against max(stat, rhs) -- the
     statistic only matters through its comparison with the threshold, and once the gradients have
     collapsed below the bf16 noise floor its relative error alone says nothing.
+    server_rule_L: G smoothness constants -> both sides run the server-side rule of Sec. IV
+    (selection from the iterates before the gradients; only selected groups evaluate one); then
+    the gradients of the selected groups only are compared, and `stat` is the rule's left side.
     Returns a dict of the worst errors seen.  Raises AssertionError on a violation."""
     orc = O.Oracle(oracle_config(w), make_theta0(w))
     gpu = Gcada.from_workload(w)
     gpu.set_shards(Xs, ys)
     gpu.set_theta(make_theta0(w))
+    if server_rule_L is not None:
+        orc.set_rule(1, server_rule_L)
+        gpu.set_rule("server", server_rule_L)
     idx_dev = torch.as_tensor(idx, device="cuda") if idx is not None else None
     worst = dict(grad=0.0, stat=0.0, rhs=0.0, loss=0.0, theta=0.0, h=0.0, vhat=0.0, agg=0.0,
                  ring=0.0, edge_flips=0, selected=0, kink_groups=0, clean_groups=0, state_steps=0)
@@ -89,6 +95,8 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
         worst["clean_groups"] += int((~near).sum())
         # a1: fresh gradients, per group
         for g in range(w.G):
+            if server_rule_L is not None and not mask_o[g]:
+                continue                      # evaluated nothing on either side
             e = vec_err(out["grad"][g], orc.grad[g])
             if near[g]:
                 assert e <= kink_grad_tol, f"step {k} group {g} (near a kink): gradient error {e:.3e}"

@@ -162,6 +162,18 @@ def make_indices(w: Workload, steps: int, seed: Optional[int] = None) -> np.ndar
     return out
 
 
+def make_worker_indices(w: Workload, steps: int, seed: Optional[int] = None) -> np.ndarray:
+    """Per-worker minibatch row ids, int32 (steps, G, M_G, mu): every worker of a group draws its own
+    minibatch from the group's shard (Sec. IV: the workers of a group hold the same data)."""
+    rng = np.random.default_rng((w.seed if seed is None else seed) + 303)
+    out = np.empty((steps, w.G, w.M_G, w.mu), dtype=np.int32)
+    for k in range(steps):
+        for g in range(w.G):
+            for m in range(w.M_G):
+                out[k, g, m] = rng.choice(w.rows, size=w.mu, replace=False, shuffle=False)
+    return out
+
+
 def make_delays(w: Workload, steps: int, eta: float = 1e-4, seed: Optional[int] = None) -> np.ndarray:
     """Per-worker compute times T_m^k ~ Exp(mean eta), float64 (steps, G, M_G), iid over workers
     and iterations (the compute-time model of Sec. II-B; eta = 1e-4 s is the value of Sec. VI)."""

@@ -202,6 +202,19 @@ enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*
+ * One iteration with per-worker minibatches (Sec. IV, Algorithm 1 taken literally): every worker
+ * m of group g draws its own minibatch xi_m^k, and the gradient the server receives from a
+ * selected group is that of the group's FASTEST worker, xi_g^k := xi_m^k with m = argmin_m T_m^k
+ * (ties: the lowest m).  Everything else is gcada_step on the minibatches so chosen.
+ *   idx_workers: [device] G*M_G*mu int32 row ids, idx_workers[(g*M_G + m)*mu + i].
+ *   delays:      [device] G*M_G doubles, the compute times T_m^k of this iteration (Sec. II-B).
+ *   worker_out:  [device] G int32: the worker whose minibatch was used; may be NULL.
+ * Asynchronous, no allocator.  Errors as gcada_step, and GCADA_EINVAL for NULL idx_workers/delays.
+ */
+int gcada_step_workers(gcada_ctx* ctx, const int32_t* idx_workers, const double* delays,
+                       int32_t* worker_out, uint8_t* mask_out, float* loss_out, void* stream);
+
+/*
  * Selection rule.  GCADA_RULE_GRADIENT_DIFFERENCE [default]: group g is selected when the squared
  * norm of the difference of its two same-minibatch gradients (at theta^k and at its stale
  * iterate) exceeds the threshold -- the quantity the paper's condition estimates (Sec. III, IV).

@@ -26,7 +26,7 @@ GCADA_OPT_SINGLE_PASS_LOGREG = 1
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
            "gcada_last_error", "gcada_version", "gcada_time_gradient_stage", "gcada_set_option",
-           "gcada_timed_stage", "gcada_set_rule", "gcada_estimate_smoothness"]
+           "gcada_timed_stage", "gcada_set_rule", "gcada_estimate_smoothness", "gcada_step_workers"]
 
 GCADA_RULE_GRADIENT_DIFFERENCE, GCADA_RULE_SERVER = 0, 1
 
@@ -81,6 +81,9 @@ def _load():
     L.gcada_cost_model.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.POINTER(C.c_double),
                                    C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    L.gcada_step_workers.restype = C.c_int
+    L.gcada_step_workers.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p]
     L.gcada_set_rule.restype = C.c_int
     L.gcada_set_rule.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
     L.gcada_estimate_smoothness.restype = C.c_int
@@ -181,6 +184,10 @@ def gcada_time_gradient_stage(ctx, idx_ptr, idx_stride: int, reps: int, stream_p
 
 def gcada_set_option(ctx, option: int, value: int):
     _check(lib.gcada_set_option(ctx, option, value), ctx)
+
+
+def gcada_step_workers(ctx, idx_workers, delays, worker_out, mask_out, loss_out, stream):
+    _check(lib.gcada_step_workers(ctx, idx_workers, delays, worker_out, mask_out, loss_out, stream), ctx)
 
 
 def gcada_set_rule(ctx, rule: int, L_ptr):

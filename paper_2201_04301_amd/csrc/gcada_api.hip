@@ -292,6 +292,17 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     return GCADA_OK;
 }
 
+int gcada_step_workers(gcada_ctx* ctx, const int32_t* idx_workers, const double* delays,
+                       int32_t* worker_out, uint8_t* mask_out, float* loss_out, void* stream)
+{
+    if (!ctx) return GCADA_EINVAL;
+    if (!idx_workers || !delays)
+        return fail(ctx, GCADA_EINVAL, "step_workers: idx_workers and delays must not be NULL");
+    hipError_t e = gcada::pick_fastest_workers(ctx, idx_workers, delays, worker_out, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "fastest-worker kernel");
+    return gcada_step(ctx, ctx->idx_eff, mask_out, loss_out, stream);
+}
+
 int gcada_state(gcada_ctx* ctx, gcada_state_view* out)
 {
     if (!ctx) return GCADA_EINVAL;

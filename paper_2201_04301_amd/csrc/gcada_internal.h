@@ -129,6 +129,7 @@ struct gcada_ctx {
     double* rule_part = nullptr;   // D x rule_nb partial squared distances
     int32_t rule_nb = 0;
     bool rule_L_set = false;
+    int32_t* idx_eff = nullptr;    // G x mu: minibatch ids of the groups' fastest workers
     bool allow_single_pass = true;
 
     bool dominant_only = false;    // benchmark diagnostic: launch only the dominant gradient kernel(s)
@@ -174,6 +175,9 @@ void rule_free(gcada_ctx* c);
 hipError_t rule_select(gcada_ctx* c, uint8_t* mask_out, hipStream_t s);
 hipError_t rule_loss(gcada_ctx* c, float* loss_out, hipStream_t s);
 hipError_t rule_power_iteration(gcada_ctx* c, int g, int iters, double* lambda_out, hipStream_t s);
+// per-worker minibatches: idx_eff <- ids of each group's fastest worker
+hipError_t pick_fastest_workers(gcada_ctx* c, const int32_t* idx_workers, const double* delays,
+                                int32_t* worker_out, hipStream_t s);
 // ||theta^k||^2 of the current slot -> Ctl::theta_sq (after set_theta / set_state)
 hipError_t refresh_theta_sq(gcada_ctx* c, hipStream_t s);
 

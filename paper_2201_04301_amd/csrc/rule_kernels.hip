@@ -175,7 +175,32 @@ __global__ __launch_bounds__(kBlock) void pi_normalize_kernel(const double* __re
     for (int j = threadIdx.x; j < d; j += kBlock) v[j] = w[j] * inv;
 }
 
+// Per-worker minibatches (Sec. IV, Algorithm 1): the minibatch of group g is that of its fastest
+// worker, argmin_m T_m^k (ties: lowest m).  grid: G blocks; out[g][i] = idx_workers[g][m*][i].
+__global__ __launch_bounds__(kBlock) void pick_fastest_kernel(int M_G, int mu, const int32_t* __restrict__ idx_workers,
+                                                              const double* __restrict__ delays,
+                                                              int32_t* __restrict__ out, int32_t* __restrict__ worker_out)
+{
+    const int g = blockIdx.x;
+    int best = 0;
+    double tb = delays[(int64_t)g * M_G];
+    for (int m = 1; m < M_G; ++m) {
+        const double t = delays[(int64_t)g * M_G + m];
+        if (t < tb) { tb = t; best = m; }
+    }
+    const int32_t* src = idx_workers + ((int64_t)g * M_G + best) * mu;
+    for (int i = threadIdx.x; i < mu; i += kBlock) out[(int64_t)g * mu + i] = src[i];
+    if (worker_out && threadIdx.x == 0) worker_out[g] = best;
+}
+
 }  // namespace
+
+hipError_t pick_fastest_workers(gcada_ctx* c, const int32_t* idx_workers, const double* delays,
+                                int32_t* worker_out, hipStream_t s)
+{
+    pick_fastest_kernel<<<c->hy.G, kBlock, 0, s>>>(c->M_G, c->hy.mu, idx_workers, delays, c->idx_eff, worker_out);
+    return hipGetLastError();
+}
 
 // Selection under the server-side rule; enqueued before the gradient stage.
 hipError_t rule_select(gcada_ctx* c, uint8_t* mask_out, hipStream_t s)
@@ -201,6 +226,7 @@ hipError_t rule_plan(gcada_ctx* c)
     hipError_t e;
     if ((e = hipMalloc(&c->rule_part, sizeof(double) * (size_t)c->rule_nb * c->hy.D)) != hipSuccess) return e;
     if ((e = hipMalloc(&c->rule_L, sizeof(double) * (size_t)c->hy.G)) != hipSuccess) return e;
+    if ((e = hipMalloc(&c->idx_eff, sizeof(int32_t) * (size_t)c->hy.G * c->hy.mu)) != hipSuccess) return e;
     return hipMemset(c->rule_L, 0, sizeof(double) * (size_t)c->hy.G);
 }
 
@@ -208,6 +234,8 @@ void rule_free(gcada_ctx* c)
 {
     if (c->rule_part) (void)hipFree(c->rule_part);
     if (c->rule_L) (void)hipFree(c->rule_L);
+    if (c->idx_eff) (void)hipFree(c->idx_eff);
+    c->idx_eff = nullptr;
     c->rule_part = nullptr;
     c->rule_L = nullptr;
 }

@@ -92,6 +92,19 @@ class Gcada:
         B.gcada_step(self.ctx, idx.data_ptr() if idx is not None else None, mo.data_ptr(),
                      lo.data_ptr(), torch.cuda.current_stream().cuda_stream)
 
+    def step_workers(self, idx_workers: torch.Tensor, delays: torch.Tensor, worker_out=None,
+                     mask_out=None, loss_out=None):
+        """One iteration with per-worker minibatches: idx_workers int32 (G, M_G, mu), delays float64
+        (G, M_G), both on the device; the fastest worker's minibatch is used for each group."""
+        assert idx_workers.is_cuda and idx_workers.dtype == torch.int32 and idx_workers.is_contiguous()
+        assert delays.is_cuda and delays.dtype == torch.float64 and delays.is_contiguous()
+        assert idx_workers.numel() == self.G * self.M_G * self.batch and delays.numel() == self.G * self.M_G
+        mo = self.mask_out if mask_out is None else mask_out
+        lo = self.loss_out if loss_out is None else loss_out
+        B.gcada_step_workers(self.ctx, idx_workers.data_ptr(), delays.data_ptr(),
+                             worker_out.data_ptr() if worker_out is not None else None, mo.data_ptr(),
+                             lo.data_ptr(), torch.cuda.current_stream().cuda_stream)
+
     # ---- outputs / state
     def outputs(self):
         """Synchronise and copy the last step's mask, loss, stat, rhs and fresh gradients."""

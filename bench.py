@@ -35,6 +35,9 @@ def main():
                     help="selection rule: the same-minibatch gradient difference (default, the metric's "
                          "configuration) or the paper's server-side condition with L_g from power "
                          "iteration (linear models): only selected groups evaluate a gradient")
+    ap.add_argument("--separate-finish", action="store_true",
+                    help="whole-row logistic path: use the separate reduce and server kernels instead "
+                         "of the fused finish kernel (for comparison)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark: copy a buffer of this many MiB five times with a "
                          "plain device copy kernel (to calibrate rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE)")
@@ -70,6 +73,8 @@ def main():
     gen_s = time.time() - t0
 
     gpu = Gcada.from_workload(w)
+    if args.separate_finish:
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_FUSED_FINISH, 0)
     gpu.set_shards(Xs, ys)
     gpu.set_theta(make_theta0(w))
     if args.rule == "server":

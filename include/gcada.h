@@ -196,9 +196,13 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * rows: whole-row register tiles; or d a multiple of 4096 up to 86,016 with mu a multiple of 4:
  * tiles shared by a team of workgroups; 16-byte aligned shards); 0 forces the general two-pass
  * kernels.  Both compute the same step
- * a1.  Errors: GCADA_EINVAL (unknown option).
+ * a1.  GCADA_OPT_FUSED_FINISH [1]: after the whole-row tile kernel, add the tile partials, select
+ * (Eq. (9)), sum the innovations and update (Eq. (8a)-(8c)) in ONE launch whose blocks meet once
+ * inside the kernel (at most one block per compute unit, bounded wait); 0 uses the separate
+ * reduce and server kernels.  Same arithmetic per element either way.
+ * Errors: GCADA_EINVAL (unknown option).
  */
-enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1 };
+enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1, GCADA_OPT_FUSED_FINISH = 2 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*

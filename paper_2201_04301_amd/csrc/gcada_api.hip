@@ -48,7 +48,7 @@ int check_device_flag(gcada_ctx* c)
     Ctl z{};
     hipError_t e = hipMemcpy(&z, c->ctl, sizeof(z), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return fail_hip(c, e, "read control block");
-    if (z.error != 0) return fail(c, GCADA_EDEVICE, "a barrier wait inside a kernel timed out");
+    if (z.error != 0) return fail(c, GCADA_EDEVICE, "a wait or a hand-over between workgroups inside a kernel failed");
     return GCADA_OK;
 }
 
@@ -236,6 +236,7 @@ static int reset_run(gcada_ctx* ctx, const float* theta0_any)
 static int after_state_change(gcada_ctx* ctx)
 {
     set_iteration(ctx);
+    gcada::lr_tile_forget(ctx);
     if (ctx->dims.model != GCADA_MLP) HIP_TRY(ctx, gcada::lr_team_reset(ctx));
     HIP_TRY(ctx, gcada::refresh_theta_sq(ctx, nullptr));
     if (ctx->dims.model == GCADA_MLP) HIP_TRY(ctx, gcada::mlp_refresh_weights(ctx, nullptr));
@@ -268,6 +269,10 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     set_iteration(ctx);
     hipError_t e;
     const bool server_rule = ctx->rule == GCADA_RULE_SERVER;
+    ctx->hy.sel = server_rule ? ctx->mask : nullptr;
+    ctx->lr_fused_finish = ctx->dims.model != GCADA_MLP && gcada::lr_tile_finish_applies(ctx);
+    if (!ctx->lr_fused_finish && (e = gcada::lr_tile_close(ctx, s, false)) != hipSuccess)
+        return fail_hip(ctx, e, "history kernel");
     if (server_rule) {
         // Sec. IV / Algorithm 1: the server decides first, from the iterates alone; the gradient
         // kernels then skip the unselected groups and the stale iterate
@@ -281,8 +286,9 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
     if (server_rule && (e = gcada::rule_loss(ctx, loss_out, s)) != hipSuccess)
         return fail_hip(ctx, e, "loss kernel");
-    if ((e = gcada::server_step(ctx, mask_out, loss_out, server_rule, s)) != hipSuccess)
-        return fail_hip(ctx, e, "server kernels");
+    e = ctx->lr_fused_finish ? gcada::lr_tile_finish(ctx, mask_out, loss_out, s)
+                             : gcada::server_step(ctx, mask_out, loss_out, server_rule, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "server kernels");
     if (ctx->dims.model == GCADA_MLP) {
         // compute copies (padded, transposed, bf16) of the new iterate's hidden-layer weights
         e = gcada::mlp_refresh_slot(ctx, (int)((ctx->k + 1) % (ctx->hy.D + 1)), s);
@@ -307,6 +313,8 @@ int gcada_state(gcada_ctx* ctx, gcada_state_view* out)
 {
     if (!ctx) return GCADA_EINVAL;
     if (!out) return fail(ctx, GCADA_EINVAL, "state: out must not be NULL");
+    if (hipError_t e = gcada::lr_tile_close(ctx, nullptr, true); e != hipSuccess)
+        return fail_hip(ctx, e, "history kernel");
     gcada_state_view v{};
     v.p = ctx->hy.p; v.G = ctx->hy.G; v.D = ctx->hy.D; v.M_G = ctx->M_G;
     v.k = ctx->k;
@@ -327,6 +335,7 @@ try {
     const gcada::Hyper& hy = ctx->hy;
     const size_t p = (size_t)hy.p;
     const int nslot = hy.D + 1;
+    HIP_TRY(ctx, gcada::lr_tile_close(ctx, nullptr, true));
     HIP_TRY(ctx, hipDeviceSynchronize());
     if (int rc = check_device_flag(ctx)) return rc;
     std::vector<int32_t> tau(hy.G);
@@ -411,6 +420,10 @@ int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
     if (!ctx) return GCADA_EINVAL;
     if (option == GCADA_OPT_SINGLE_PASS_LOGREG) {
         ctx->allow_single_pass = value != 0;
+        return GCADA_OK;
+    }
+    if (option == GCADA_OPT_FUSED_FINISH) {
+        ctx->allow_fused_finish = value != 0;
         return GCADA_OK;
     }
     return fail(ctx, GCADA_EINVAL, "set_option: unknown option");

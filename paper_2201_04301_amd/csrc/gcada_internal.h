@@ -131,6 +131,8 @@ struct gcada_ctx {
     bool rule_L_set = false;
     int32_t* idx_eff = nullptr;    // G x mu: minibatch ids of the groups' fastest workers
     bool allow_single_pass = true;
+    bool allow_fused_finish = true;
+    bool lr_fused_finish = false;  // this step: lr_tile_finish replaces lr_tile_reduce + server_step
 
     bool dominant_only = false;    // benchmark diagnostic: launch only the dominant gradient kernel(s)
     std::string stage_name;
@@ -149,6 +151,13 @@ hipError_t lr_tile_plan(gcada_ctx* c);
 void lr_tile_free(gcada_ctx* c);
 bool lr_tile_applies(const gcada_ctx* c);
 hipError_t lr_tile_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
+// tile reduce + selection + innovation sum + server update in one launch (default rule only)
+bool lr_tile_finish_applies(const gcada_ctx* c);
+hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s);
+// the fused finish leaves the last history entry and ||theta||^2 per block; lr_tile_close adds
+// them up (on `s`, or on the stream of that step) before anyone else reads them
+hipError_t lr_tile_close(gcada_ctx* c, hipStream_t s, bool use_step_stream);
+void lr_tile_forget(gcada_ctx* c);
 
 // single-pass logistic gradients for wide rows: teams of workgroups share a tile (lr_team.hip)
 hipError_t lr_team_plan(gcada_ctx* c);

@@ -20,6 +20,38 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
+// Sum over the 64 lanes through the data-parallel-primitive lane moves (a few cycles each, where
+// a shuffle through the LDS crossbar takes a hundred): lanes ^1, ^2, mirror within 8, mirror
+// within 16, then the four rows' totals in ascending order.  Every lane gets the total.
+__device__ __forceinline__ double dpp_move(double v, int ctrl_is)
+{
+    // ctrl_is: 0 = quad_perm [1,0,3,2], 1 = quad_perm [2,3,0,1], 2 = row_half_mirror, 3 = row_mirror
+    const long long b = __double_as_longlong(v);
+    int lo = (int)(b & 0xffffffffll), hi = (int)(b >> 32);
+    switch (ctrl_is) {
+    case 0: lo = __builtin_amdgcn_update_dpp(0, lo, 0xB1, 0xF, 0xF, true); hi = __builtin_amdgcn_update_dpp(0, hi, 0xB1, 0xF, 0xF, true); break;
+    case 1: lo = __builtin_amdgcn_update_dpp(0, lo, 0x4E, 0xF, 0xF, true); hi = __builtin_amdgcn_update_dpp(0, hi, 0x4E, 0xF, 0xF, true); break;
+    case 2: lo = __builtin_amdgcn_update_dpp(0, lo, 0x141, 0xF, 0xF, true); hi = __builtin_amdgcn_update_dpp(0, hi, 0x141, 0xF, 0xF, true); break;
+    default: lo = __builtin_amdgcn_update_dpp(0, lo, 0x140, 0xF, 0xF, true); hi = __builtin_amdgcn_update_dpp(0, hi, 0x140, 0xF, 0xF, true); break;
+    }
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ double lane_value(double v, int l)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffll), l);
+    const int hi = __builtin_amdgcn_readlane((int)(b >> 32), l);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ double wave_total(double v)
+{
+    v += dpp_move(v, 0);
+    v += dpp_move(v, 1);
+    v += dpp_move(v, 2);
+    v += dpp_move(v, 3);
+    return ((lane_value(v, 0) + lane_value(v, 16)) + lane_value(v, 32)) + lane_value(v, 48);
+}
+
 // v[0..N) per lane -> every lane l ends with the sum over all 64 lanes of v[l >> (6 - log2 N)].
 // Each of the log2(N) halving steps exchanges half of the remaining values with lane ^ S.
 template <int N, int S>

@@ -147,6 +147,16 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
         }
     }
     if (wr == 0) {
+        if (rb == 0 && hy.l2 != 0.0f) {
+            // the l2 terms mu*lambda*theta^k and mu*lambda*(theta^k - theta_stale) ride on the
+            // group's first tile: both iterates are in registers here, and whoever adds the
+            // tiles up needs neither them nor the group's age (explicit fused multiply-adds)
+            const float ml = (float)hy.mu * hy.l2;
+            ag.x = fmaf(ml, th4.x, ag.x); ag.y = fmaf(ml, th4.y, ag.y);
+            ag.z = fmaf(ml, th4.z, ag.z); ag.w = fmaf(ml, th4.w, ag.w);
+            as.x = fmaf(ml, dl4.x, as.x); as.y = fmaf(ml, dl4.y, as.y);
+            as.z = fmaf(ml, dl4.z, as.z); as.w = fmaf(ml, dl4.w, as.w);
+        }
         const int64_t o = (int64_t)blockIdx.x * hy.p + col;
         *(float4*)(a.part_g + o) = ag;
         *(float4*)(a.part_s + o) = as;
@@ -155,13 +165,12 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
 
 constexpr int kRedBlock = 256;
 
-// grid: (ceil(d/4 / 256), G).  Adds the RB tile partials of a group in a fixed order, adds the
-// l2 terms, writes the group's gradient and one partial squared norm per block.
+// grid: (ceil(d/4 / 256), G).  Adds the RB tile partials of a group in a fixed order (the l2
+// terms are part of the first tile's), writes the group's gradient and one partial squared norm
+// per block.
 __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
     Hyper hy, const float* __restrict__ part_g, const float* __restrict__ part_s, int RB,
-    const float* __restrict__ ring, const int32_t* __restrict__ tau, float* __restrict__ gbuf,
-    const int32_t* __restrict__ which,
-    double* __restrict__ part_stat)
+    float* __restrict__ gbuf, const int32_t* __restrict__ which, double* __restrict__ part_stat)
 {
     __shared__ double s_red[kRedBlock / kWave];
     const int g = blockIdx.y;
@@ -171,12 +180,6 @@ __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
     if (j < hy.p) {
         const float* pg = part_g + (int64_t)g * RB * hy.p + j;
         const float* ps = part_s + (int64_t)g * RB * hy.p + j;
-        float4 t = make_float4(0, 0, 0, 0), u = t;
-        if (hy.l2 != 0.0f) {
-            t = *(const float4*)(ring + (int64_t)hy.cur * hy.pstride + j);
-            const int old = stale_slot_of(hy, tau[g]);
-            u = *(const float4*)(ring + (int64_t)old * hy.pstride + j);
-        }
         float4 ag = make_float4(0, 0, 0, 0), as = ag;
         int rb = 0;
         for (; rb + 8 <= RB; rb += 8) {          // eight tiles' loads in flight, added in order
@@ -198,12 +201,6 @@ __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
             ag.x += p.x; ag.y += p.y; ag.z += p.z; ag.w += p.w;
             as.x += q.x; as.y += q.y; as.z += q.z; as.w += q.w;
         }
-        if (hy.l2 != 0.0f) {
-            const float ml = (float)hy.mu * hy.l2;
-            ag.x += ml * t.x; ag.y += ml * t.y; ag.z += ml * t.z; ag.w += ml * t.w;
-            as.x += ml * (t.x - u.x); as.y += ml * (t.y - u.y);
-            as.z += ml * (t.z - u.z); as.w += ml * (t.w - u.w);
-        }
         *(float4*)(fresh_row(gbuf, which, hy, g) + j) = ag;
         sq = (double)as.x * as.x + (double)as.y * as.y + (double)as.z * as.z + (double)as.w * as.w;
     }
@@ -217,6 +214,384 @@ __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
     }
 }
 
+
+// ---- fused finish: tile reduce + selection (a2) + masked innovation sum (a3) + update (a4) ----
+//
+// The three small steps after the tile kernel are a chain of short memory round trips; as
+// separate launches each also pays a launch, a drain and cold first loads.  Here one launch does
+// them all.  A block owns 4*CL columns of EVERY group: it adds the tile partials of its columns
+// (same order as lr_tile_reduce), writes the fresh gradients, keeps the innovations
+// grad_g - last_g in LDS and publishes one partial squared norm per group.  The statistic of
+// Eq. (9) needs all columns, so the blocks meet once: each publishes its partials as tagged words
+// and polls (bounded) those of the others; the grid has at most 64 blocks, one per compute unit
+// at most, so all blocks are resident.  Every block then derives the same mask,
+// and updates its columns by Eq. (8a)-(8c); the block that finishes last closes the history
+// entry, as in the stand-alone server kernel.
+constexpr int kFinGroups = 16;            // group lanes of a block
+constexpr int kFinMaxG = 64;              // innovations kept in LDS: kFinMaxG x 4*CL floats
+constexpr unsigned kFinPollLimit = 1u << 16;
+
+struct FinishArgs {
+    Hyper hy;
+    const float* part_g;
+    const float* part_s;
+    int RB;
+    const double* part_loss;
+    int n_loss_total;
+    unsigned long long* xstat;   // [G][gridDim.x] tagged doubles: partial squared norms
+    unsigned long long* xsq;     // [gridDim.x][2] tagged doubles: ||step||^2, ||theta^{k+1}||^2
+    unsigned tag;                // of this launch (never 0, never that of a recent launch)
+    // the two sums of the PREVIOUS launch are still per block (nobody waits for them at the end
+    // of a launch): this launch adds them up, uses them and stores them
+    const unsigned long long* xsq_prev;
+    unsigned tag_prev;
+    int fold_prev;               // 0: history and ||theta^k||^2 are already complete
+    int prev_kmodD;              // history index the previous launch's ||step||^2 belongs to
+    double* stat;
+    uint8_t* mask;
+    uint8_t* mask_out;
+    float* loss_out;
+    float* gbuf;
+    int32_t* which;
+    float* agg;
+    float* h;
+    float* vhat;
+    float* ring;
+    double* nring;
+    int32_t* tau;
+    Ctl* ctl;
+};
+
+// A double that one block hands to the others travels as two tagged 64-bit words
+// {tag, low half} and {tag, high half}, written and read with relaxed atomics that go past the
+// per-XCD L2s: a reader polls the words themselves and needs no fence or separate flag; a word
+// of an earlier launch carries an older tag.
+__device__ __forceinline__ void tagged_store(unsigned long long* slot, double v, unsigned tag)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    __hip_atomic_store(slot, ((unsigned long long)tag << 32) | (b & 0xffffffffull), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(slot + 1, ((unsigned long long)tag << 32) | (b >> 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ void tagged_issue(const unsigned long long* slot, unsigned long long& lo,
+                                             unsigned long long& hi)
+{
+    lo = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    hi = __hip_atomic_load(slot + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ bool tagged_check(unsigned long long lo, unsigned long long hi, unsigned tag, double& v)
+{
+    v = __longlong_as_double((long long)((hi << 32) | (lo & 0xffffffffull)));
+    return (unsigned)(lo >> 32) == tag && (unsigned)(hi >> 32) == tag;
+}
+__device__ __forceinline__ bool tagged_load(const unsigned long long* slot, unsigned tag, double& v)
+{
+    const unsigned long long lo = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    const unsigned long long hi = __hip_atomic_load(slot + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    v = __longlong_as_double((long long)((hi << 32) | (lo & 0xffffffffull)));
+    return (unsigned)(lo >> 32) == tag && (unsigned)(hi >> 32) == tag;
+}
+
+// grid: d / (4*CL) blocks of CL * 16 threads; thread = (group lane gl, column lane cl).
+template <int CL>
+__global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishArgs a)
+{
+    constexpr int B = CL * kFinGroups, NW = B / kWave;
+    __shared__ float4 s_delta[kFinMaxG][CL];
+    __shared__ double s_ps[kFinMaxG], s_stat[kFinMaxG];
+    __shared__ int s_which[kFinMaxG], s_tau[kFinMaxG];
+    __shared__ double s_red[NW];
+    __shared__ double s_rhs;
+
+    const Hyper& hy = a.hy;
+    Ctl* ctl = a.ctl;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int gl = tid / CL, cl = tid % CL;
+    const int S = gridDim.x, blk = blockIdx.x, G = hy.G;
+    const int64_t j = ((int64_t)blk * CL + cl) * 4;
+    const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
+    float* __restrict__ tn = a.ring + (int64_t)hy.nxt * hy.pstride;
+
+    constexpr int NCH = kFinMaxG / kFinGroups;      // passes over the groups (G <= kFinMaxG)
+    static_assert(4 * CL <= kWave, "the updating threads must sit in wave 0");
+
+    // 1. The way to the statistic first -- the other blocks wait for it: tile partials of the
+    //    block's columns, added in lr_tile_reduce's order (the l2 terms are part of the first
+    //    tile's); partial squared norm.
+    // (the ages and halves go to LDS for later; their loads are not waited for before the tile
+    // loads are out)
+    int my_which = 0, my_tau = 0;
+    if (tid < G) { my_which = a.which[tid]; my_tau = a.tau[tid]; }
+    const int RB = a.RB;
+    float4 agk[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        const int g = ch * kFinGroups + gl;
+        double sq = 0;
+        agk[ch] = make_float4(0, 0, 0, 0);
+        if (g < G) {
+            const float* pg = a.part_g + (int64_t)g * RB * hy.p + j;
+            const float* ps = a.part_s + (int64_t)g * RB * hy.p + j;
+            float4 ag = make_float4(0, 0, 0, 0), as = ag;
+            int rb = 0;
+            if (RB >= 16) {                          // sixteen tiles' loads in flight, added in order
+                float4 p[16], q[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    p[e] = *(const float4*)(pg + (int64_t)e * hy.p);
+                    q[e] = *(const float4*)(ps + (int64_t)e * hy.p);
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    ag.x += p[e].x; ag.y += p[e].y; ag.z += p[e].z; ag.w += p[e].w;
+                    as.x += q[e].x; as.y += q[e].y; as.z += q[e].z; as.w += q[e].w;
+                }
+                rb = 16;
+            }
+            for (; rb + 8 <= RB; rb += 8) {          // eight tiles' loads in flight, added in order
+                float4 p[8], q[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    p[e] = *(const float4*)(pg + (int64_t)(rb + e) * hy.p);
+                    q[e] = *(const float4*)(ps + (int64_t)(rb + e) * hy.p);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    ag.x += p[e].x; ag.y += p[e].y; ag.z += p[e].z; ag.w += p[e].w;
+                    as.x += q[e].x; as.y += q[e].y; as.z += q[e].z; as.w += q[e].w;
+                }
+            }
+            for (; rb < RB; ++rb) {
+                const float4 p = *(const float4*)(pg + (int64_t)rb * hy.p);
+                const float4 q = *(const float4*)(ps + (int64_t)rb * hy.p);
+                ag.x += p.x; ag.y += p.y; ag.z += p.z; ag.w += p.w;
+                as.x += q.x; as.y += q.y; as.z += q.z; as.w += q.w;
+            }
+            agk[ch] = ag;
+            sq = (double)as.x * as.x + (double)as.y * as.y + (double)as.z * as.z + (double)as.w * as.w;
+        }
+        // the CL column lanes of a group lane are neighbours in the wave: fixed butterfly
+#pragma unroll
+        for (int o = CL / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o, kWave);
+        if (g < G && cl == 0) s_ps[g] = sq;
+    }
+    if (tid < G) { s_which[tid] = my_which; s_tau[tid] = my_tau; }
+    for (int g = tid + B; g < G; g += B) { s_which[g] = a.which[g]; s_tau[g] = a.tau[g]; }
+    __syncthreads();
+    for (int g = tid; g < G; g += B) tagged_store(a.xstat + 2 * ((int64_t)g * S + blk), s_ps[g], a.tag);
+
+    // 2. While the partials travel: everything else this block needs.  The update (a3, a4) of
+    //    its 4*CL columns is done by the first 4*CL threads, one column each (a short instruction
+    //    stream per lane instead of a long one on a few lanes).
+    const bool upd = tid < 4 * CL;
+    const int64_t jc = (int64_t)blk * 4 * CL + tid;
+    float ac = 0, hv = 0, vv = 0, tv = 0;
+    if (upd) {
+        ac = a.agg[jc];
+        hv = a.h[jc];
+        vv = a.vhat[jc];
+        tv = th[jc];
+    }
+    // (only loads here, nothing that waits for one: sums over more than one element per thread
+    // are finished after the exchange)
+    double lpart = 0, hist = 0, theta_sq = 0, psq = 0, ptsq = 0;
+    unsigned long long plo[2] = {0, 0}, phi[2] = {0, 0};
+    if (blk == 0 && tid < a.n_loss_total) lpart = a.part_loss[tid];
+    if (wave == 0) {
+        if (a.fold_prev) {
+            // lane i: block i's sums of the previous launch (complete: that launch has ended)
+            if (lane < S) {
+                tagged_issue(a.xsq_prev + 4 * (int64_t)lane, plo[0], phi[0]);
+                tagged_issue(a.xsq_prev + 4 * (int64_t)lane + 2, plo[1], phi[1]);
+            }
+        } else if (blk == 0) {
+            theta_sq = ctl->theta_sq;
+        }
+        if (lane < hy.D && !(a.fold_prev && lane == a.prev_kmodD)) hist = a.nring[lane];
+    }
+    // both halves of each group's gradient rows are asked for now and the stored one is picked
+    // when they are used, after the wait below, so no load waits for another
+    float4 h0k[NCH], h1k[NCH];
+    int wlk[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        const int g = ch * kFinGroups + gl;
+        h0k[ch] = h1k[ch] = make_float4(0, 0, 0, 0);
+        wlk[ch] = 0;
+        if (g < G) {
+            wlk[ch] = s_which[g];      // read before this block published: block 0 may flip it now
+            h0k[ch] = *(const float4*)(a.gbuf + (int64_t)g * hy.pstride + j);
+            h1k[ch] = *(const float4*)(a.gbuf + ((int64_t)G + g) * hy.pstride + j);
+        }
+    }
+
+    // a2: lane i collects block i's partial of four groups at a time (polling the tagged words
+    // is the wait); every block adds the same numbers in the same order and so reaches the same
+    // statistics and mask
+    bool first = true;
+    for (int g0 = wave; g0 < G; g0 += 4 * NW) {
+        double v[4] = {0, 0, 0, 0};
+        bool got[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) got[e] = lane >= S || g0 + e * NW >= G;
+        unsigned spins = 0;
+        for (;;) {
+            unsigned long long lo[4], hi[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (!got[e]) tagged_issue(a.xstat + 2 * ((int64_t)(g0 + e * NW) * S + lane), lo[e], hi[e]);
+            if (first) {
+                // while the first answers travel (loads return in order, so this waits only for
+                // the older ones): the threshold of Eq. (9); wave 0 always gets here (G >= 1)
+                first = false;
+                if (wave == 0) {
+                    for (int i = lane + kWave; i < hy.D; i += kWave)
+                        if (!(a.fold_prev && i == a.prev_kmodD)) hist += a.nring[i];
+                    if (a.fold_prev) {
+                        bool prev_ok = true;
+                        if (lane < S) {
+                            prev_ok = tagged_check(plo[0], phi[0], a.tag_prev, psq);
+                            prev_ok = tagged_check(plo[1], phi[1], a.tag_prev, ptsq) && prev_ok;
+                        }
+                        if (!__all(prev_ok) && lane == 0)
+                            __hip_atomic_fetch_or(&ctl->error, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        psq = wave_total(psq);
+                        ptsq = wave_total(ptsq);
+                        if (blk == 0 && lane == 0) {
+                            a.nring[a.prev_kmodD] = psq;         // no block reads this entry in this launch
+                            ctl->theta_sq = ptsq;
+                        }
+                        theta_sq = ptsq;
+                        // the entry takes its place in the lane-strided order of the history sum
+                        if (lane == a.prev_kmodD % kWave) hist += psq;
+                    }
+                    hist = wave_total(hist);
+                    if (lane == 0) s_rhs = hy.c / (double)hy.D * hist;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (!got[e]) got[e] = tagged_check(lo[e], hi[e], a.tag, v[e]);
+            if (__all(got[0] && got[1] && got[2] && got[3])) break;
+            if (++spins > kFinPollLimit) {           // never in a healthy launch: report, do not hang
+                if (lane == 0)
+                    __hip_atomic_fetch_or(&ctl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double t = wave_total(v[e]);
+            if (lane == 0 && g0 + e * NW < G) s_stat[g0 + e * NW] = t;
+        }
+    }
+    const bool pub = blk == 0;
+    if (pub) {
+        for (int i = tid + B; i < a.n_loss_total; i += B) lpart += a.part_loss[i];
+        lpart = wave_total(lpart);
+        if (lane == 0) s_red[wave] = lpart;
+    }
+    // fresh gradients out, innovations grad_g - last_g into LDS
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        const int g = ch * kFinGroups + gl;
+        if (g < G) {
+            const float4 ag = agk[ch];
+            const float4 last4 = wlk[ch] ? h1k[ch] : h0k[ch];
+            *(float4*)(a.gbuf + ((int64_t)(1 - wlk[ch]) * G + g) * hy.pstride + j) = ag;
+            s_delta[g][cl] = make_float4(ag.x - last4.x, ag.y - last4.y, ag.z - last4.z, ag.w - last4.w);
+        }
+    }
+    __syncthreads();
+    const double rhs = s_rhs;
+    // the decision of Eq. (9): lane g of every wave takes it for group g; the ballot is the mask
+    bool sel = false;
+    if (lane < G) sel = (s_stat[lane] > rhs) || (s_tau[lane] >= hy.D) || (rhs == 0.0);
+    const unsigned long long selbits = __ballot(sel);
+    if (pub && wave == 0) {
+        // every block copied the ages and the halves to its LDS before it published its partials
+        if (lane < G) {
+            const int t = s_tau[lane];
+            a.stat[lane] = s_stat[lane];
+            a.mask[lane] = sel ? 1 : 0;
+            if (a.mask_out) a.mask_out[lane] = sel ? 1 : 0;
+            a.tau[lane] = sel ? 1 : t + 1;
+            if (sel) a.which[lane] = 1 - s_which[lane];
+        }
+        if (lane == 0) {
+            double lsum = 0;
+            for (int w = 0; w < NW; ++w) lsum += s_red[w];
+            const double loss = lsum / ((double)G * (double)hy.mu) + 0.5 * (double)hy.l2 * theta_sq;
+            ctl->rhs = rhs;
+            ctl->loss = loss;
+            if (a.loss_out) *a.loss_out = (float)loss;
+        }
+    }
+    if (wave != 0) return;
+
+    // a3 + a4: the innovations of the selected groups in ascending order (the LDS reads of eight
+    // groups go out together; a select, not a branch, keeps or skips each), then Eq. (8a)-(8c)
+    double sq = 0, tsq = 0;
+    if (upd) {
+        const float* s_df = (const float*)s_delta;          // [g][4*CL] as plain floats
+        for (int g0 = 0; g0 < G; g0 += 8) {
+            float d[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d[e] = s_df[min(g0 + e, G - 1) * (4 * CL) + tid];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool on = g0 + e < G && ((selbits >> (g0 + e)) & 1ull);
+                ac = on ? ac + d[e] : ac;
+            }
+        }
+        const float b1 = (float)hy.beta1, b2 = (float)hy.beta2, al = (float)hy.alpha, ep = (float)hy.eps;
+        const float ob1 = (float)(1.0 - hy.beta1), ob2 = (float)(1.0 - hy.beta2);
+        hv = fmaf(b1, hv, ob1 * ac);
+        const float v = fmaf(b2, vv, ob2 * ac * ac);
+        vv = fmaxf(vv, v);
+        const float step = al * hv / sqrtf(ep + vv);
+        const float nv = tv - step;
+        sq = (double)step * (double)step;
+        tsq = (double)nv * (double)nv;
+        a.agg[jc] = ac;
+        a.h[jc] = hv;
+        a.vhat[jc] = vv;
+        tn[jc] = nv;
+    }
+    // ||step||^2 and ||theta^{k+1}||^2 stay per block: the next launch (or lr_tile_close_kernel)
+    // adds them up, so no block waits for the others here
+    sq = wave_total(sq);
+    tsq = wave_total(tsq);
+    if (lane == 0) {
+        tagged_store(a.xsq + 4 * (int64_t)blk, sq, a.tag);
+        tagged_store(a.xsq + 4 * (int64_t)blk + 2, tsq, a.tag);
+    }
+}
+
+// One wave: completes what the last fused finish left per block -- the history entry
+// ||theta^{k+1} - theta^k||^2 (Eq. (9)) and ||theta^{k+1}||^2 -- in the order the next fused launch
+// would have used.
+__global__ __launch_bounds__(kWave) void lr_tile_close_kernel(const unsigned long long* xsq, unsigned tag,
+                                                              int S, int kmodD, double* nring, Ctl* ctl)
+{
+    const int lane = threadIdx.x;
+    double x = 0, y = 0;
+    bool ok = true;
+    if (lane < S) {
+        ok = tagged_load(xsq + 4 * (int64_t)lane, tag, x);
+        ok = tagged_load(xsq + 4 * (int64_t)lane + 2, tag, y) && ok;
+    }
+    if (!__all(ok) && lane == 0)
+        __hip_atomic_fetch_or(&ctl->error, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    x = wave_total(x);
+    y = wave_total(y);
+    if (lane == 0) {
+        nring[kmodD] = x;
+        ctl->theta_sq = y;
+    }
+}
+
 }  // namespace
 
 struct LrTilePlan {
@@ -224,6 +599,14 @@ struct LrTilePlan {
     int R = 0, RB = 0, n_stat = 0;
     float* part_g = nullptr;
     float* part_s = nullptr;
+    int fin_CL = 0;       // column lanes of a block of the fused finish; 0: not applicable
+    int fin_S = 0;        // its blocks
+    unsigned long long* fin_x = nullptr;   // tagged words: [G][S][2] statistics, then 2 x [S][4] sums
+    unsigned fin_launches = 0;
+    bool fin_pending = false;   // the last fused finish left its two sums per block
+    int fin_pending_kmodD = 0;
+    unsigned fin_pending_tag = 0;
+    hipStream_t fin_stream = nullptr;
 };
 
 // Decide whether the single-pass kernel applies (d in {256, 512, ..., 4096} so that a tile holds
@@ -249,6 +632,20 @@ hipError_t lr_tile_plan(gcada_ctx* c)
     pl->WC = WC;
     c->n_loss_part = std::max(c->n_loss_part, pl->RB);
     c->n_stat_part = std::max(c->n_stat_part, pl->n_stat);
+    // fused finish: all of its blocks must be resident at once (they wait for each other)
+    hipDeviceProp_t prop;
+    if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return e;
+    if (G <= kFinMaxG && c->hy.pstride == c->hy.p) {
+        const int CL = 16;
+        const int S = d / (4 * CL);
+        if (S <= prop.multiProcessorCount && S <= kWave) {
+            const size_t words = (size_t)2 * G * S + (size_t)8 * S;
+            if ((e = hipMalloc(&pl->fin_x, words * 8)) != hipSuccess) return e;
+            if ((e = hipMemset(pl->fin_x, 0, words * 8)) != hipSuccess) return e;    // tag 0: never used
+            pl->fin_CL = CL;
+            pl->fin_S = S;
+        }
+    }
     return hipSuccess;
 }
 
@@ -257,6 +654,7 @@ void lr_tile_free(gcada_ctx* c)
     if (!c->lr_tiles) return;
     if (c->lr_tiles->part_g) (void)hipFree(c->lr_tiles->part_g);
     if (c->lr_tiles->part_s) (void)hipFree(c->lr_tiles->part_s);
+    if (c->lr_tiles->fin_x) (void)hipFree(c->lr_tiles->fin_x);
     delete c->lr_tiles;
     c->lr_tiles = nullptr;
 }
@@ -287,12 +685,79 @@ hipError_t lr_tile_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (c->dominant_only) return hipSuccess;      // benchmark diagnostic: the tile kernel alone
-    dim3 gr(pl->n_stat, c->hy.G);
-    lr_tile_reduce<<<gr, kRedBlock, 0, s>>>(c->hy, pl->part_g, pl->part_s, pl->RB, c->ring, c->tau,
-                                             c->gbuf, c->which, c->part_stat);
-    c->n_stat_used = pl->n_stat;
     c->n_loss_used = c->hy.G * pl->RB;
+    if (c->lr_fused_finish) return hipSuccess;    // lr_tile_finish adds the partials itself
+    dim3 gr(pl->n_stat, c->hy.G);
+    lr_tile_reduce<<<gr, kRedBlock, 0, s>>>(c->hy, pl->part_g, pl->part_s, pl->RB, c->gbuf, c->which,
+                                             c->part_stat);
+    c->n_stat_used = pl->n_stat;
     return hipGetLastError();
+}
+
+// The fused finish serves the default rule (the mask comes from the gradients of this step).
+bool lr_tile_finish_applies(const gcada_ctx* c)
+{
+    return c->allow_fused_finish && lr_tile_applies(c) && c->lr_tiles->fin_CL != 0 && c->hy.sel == nullptr;
+}
+
+// Tile reduce + selection + masked innovation sum + server update in one launch; replaces
+// lr_tile_reduce and server_step after lr_tile_gradients.
+hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s)
+{
+    LrTilePlan* pl = c->lr_tiles;
+    FinishArgs a{};
+    a.hy = c->hy; a.part_g = pl->part_g; a.part_s = pl->part_s; a.RB = pl->RB;
+    a.part_loss = c->part_loss; a.n_loss_total = c->n_loss_used;
+    unsigned long long* sums = pl->fin_x + (size_t)2 * c->hy.G * pl->fin_S;
+    const unsigned n = pl->fin_launches++;
+    a.xstat = pl->fin_x;
+    a.xsq = sums + (size_t)(n & 1u) * 4 * pl->fin_S;            // two buffers in turn: the other one
+    a.xsq_prev = sums + (size_t)((n & 1u) ^ 1u) * 4 * pl->fin_S;   // is read while this one is written
+    // tags 1 .. 2^32-1 in turn: a slot only ever holds the tag of an earlier launch
+    a.tag = n % 0xffffffffu + 1u;
+    a.fold_prev = pl->fin_pending ? 1 : 0;
+    a.tag_prev = pl->fin_pending_tag;
+    a.prev_kmodD = pl->fin_pending_kmodD;
+    pl->fin_pending = true;
+    pl->fin_pending_kmodD = c->hy.kmodD;
+    pl->fin_pending_tag = a.tag;
+    pl->fin_stream = s;
+    a.stat = c->stat; a.mask = c->mask; a.mask_out = mask_out; a.loss_out = loss_out;
+    a.gbuf = c->gbuf; a.which = c->which; a.agg = c->agg; a.h = c->h; a.vhat = c->vhat;
+    a.ring = c->ring; a.nring = c->nring; a.tau = c->tau; a.ctl = c->ctl;
+    // every buffer the kernel dereferences unconditionally (mask_out and loss_out may be null)
+    for (const void* q : {(const void*)a.part_g, (const void*)a.part_s, (const void*)a.part_loss,
+                          (const void*)a.xstat, (const void*)a.xsq, (const void*)a.xsq_prev,
+                          (const void*)a.stat, (const void*)a.mask, (const void*)a.gbuf,
+                          (const void*)a.which, (const void*)a.agg, (const void*)a.h,
+                          (const void*)a.vhat, (const void*)a.ring, (const void*)a.nring,
+                          (const void*)a.tau, (const void*)a.ctl})
+        if (!q) return hipErrorInvalidValue;
+    if (a.n_loss_total != c->hy.G * pl->RB || pl->fin_S * pl->fin_CL * 4 != c->hy.p)
+        return hipErrorInvalidValue;
+    lr_tile_finish_kernel<16><<<pl->fin_S, 16 * kFinGroups, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+// Complete the history entry and ||theta||^2 of the last fused finish, if they are still per
+// block: before anything other than the next fused finish reads them.  On the stream of that
+// step when `s` is null.
+hipError_t lr_tile_close(gcada_ctx* c, hipStream_t s, bool use_step_stream)
+{
+    LrTilePlan* pl = c->lr_tiles;
+    if (!pl || !pl->fin_pending) return hipSuccess;
+    const unsigned n = pl->fin_launches - 1;
+    const unsigned long long* sums = pl->fin_x + (size_t)2 * c->hy.G * pl->fin_S + (size_t)(n & 1u) * 4 * pl->fin_S;
+    lr_tile_close_kernel<<<1, kWave, 0, use_step_stream ? pl->fin_stream : s>>>(
+        sums, pl->fin_pending_tag, pl->fin_S, pl->fin_pending_kmodD, c->nring, c->ctl);
+    pl->fin_pending = false;
+    return hipGetLastError();
+}
+
+// The state was replaced from outside: nothing of the last fused finish is pending any more.
+void lr_tile_forget(gcada_ctx* c)
+{
+    if (c->lr_tiles) c->lr_tiles->fin_pending = false;
 }
 
 }  // namespace gcada

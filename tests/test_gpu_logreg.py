@@ -138,6 +138,51 @@ def test_lr_single_pass_matches_general_kernels(par):
     np.testing.assert_allclose(res[0][2], res[1][2], rtol=2e-5)
 
 
+@pytest.mark.parametrize("d,mu,G,l2", [
+    (4096, 256, 16, 1e-4),     # the benchmark's step shape: 64 blocks meet inside the kernel
+    (2048, 64, 40, 0.0),       # more groups than group lanes: three passes over the groups
+    (256, 256, 3, 1e-3),       # four blocks
+    (512, 128, 70, 0.0),       # too many groups for the fused finish: separate kernels either way
+])
+def test_lr_fused_finish_matches_separate_kernels(par, d, mu, G, l2):
+    # reduce + selection + update in one launch against the three separate kernels: the same
+    # additions in the same order, so the state agrees bit for bit (the statistic and the history
+    # are partitioned differently over blocks and may differ in the last bits)
+    from paper_2201_04301_amd import Gcada, binding as B
+    from gcada_inputs import make_theta0
+    w = scaled(CONFIGS["lr_small"], name="finish", widths=(d,), mu=mu, G=G, rows=400, l2=l2, c=0.5,
+               D=5, flip=0.05)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 30
+    idx = torch.as_tensor(make_indices(w, steps), device="cuda")
+    res = []
+    for fused in (1, 0):
+        gpu = Gcada.from_workload(w)
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_FUSED_FINISH, fused)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        masks = torch.zeros(steps, w.G, dtype=torch.uint8, device="cuda")
+        losses = torch.zeros(steps, dtype=torch.float32, device="cuda")
+        for k in range(steps):
+            gpu.step(idx[k].contiguous(), mask_out=masks[k], loss_out=losses[k:k + 1])
+        out = gpu.outputs()
+        st = gpu.get_state()
+        res.append((masks.cpu().numpy(), losses.cpu().numpy(), st, out))
+        gpu.close()
+    (m1, l1, s1, o1), (m0, l0, s0, o0) = res
+    assert 0 < m1.sum() < m1.size or G == 70
+    np.testing.assert_array_equal(m1, m0)
+    np.testing.assert_array_equal(l1, l0)
+    for name in ("theta", "h", "vhat", "agg", "theta_stale", "last", "tau"):
+        np.testing.assert_array_equal(s1[name], s0[name], err_msg=name)
+    assert s1["k"] == s0["k"] == steps
+    np.testing.assert_allclose(s1["dtheta_sq"], s0["dtheta_sq"], rtol=1e-12)
+    np.testing.assert_allclose(o1["stat"], o0["stat"], rtol=1e-12)
+    np.testing.assert_allclose(o1["rhs"], o0["rhs"], rtol=1e-12)
+    np.testing.assert_array_equal(o1["grad"], o0["grad"])
+
+
 # ---- full-size configurations
 
 def test_lr_4k_full_size_teacher_forced(par):

@@ -117,13 +117,12 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
         s_res[tid] = make_float2(r, dr);
         lsum = (double)ls;
     }
-    lsum = wave_sum(lsum);
-    if (lane == 0) s_red[wave] = lsum;
     __syncthreads();
-    if (tid == 0) {
-        double t = 0;
-        for (int w = 0; w < (R + kWave - 1) / kWave; ++w) t += s_red[w];
-        a.part_loss[blockIdx.x] = t;
+    // the tile's loss sum is nobody's input here: the waves that hold rows add it up while the
+    // others go on (R is a multiple of 64 or smaller than 64, so such a wave is all rows or wave 0)
+    if (wave < (R + kWave - 1) / kWave) {
+        lsum = wave_total(lsum);
+        if (lane == 0) s_red[wave] = lsum;
     }
     // weighted row sums of the tile, from the registers
     float4 ag = make_float4(0, 0, 0, 0), as = make_float4(0, 0, 0, 0);
@@ -145,6 +144,16 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
                 as.x += q.x; as.y += q.y; as.z += q.z; as.w += q.w;
             }
         }
+    }
+    if constexpr (R > kWave) {
+        __syncthreads();
+        if (tid == 0) {
+            double t = 0;
+            for (int w = 0; w < R / kWave; ++w) t += s_red[w];
+            a.part_loss[blockIdx.x] = t;
+        }
+    } else {
+        if (tid == 0) a.part_loss[blockIdx.x] = lsum;
     }
     if (wr == 0) {
         if (rb == 0 && hy.l2 != 0.0f) {

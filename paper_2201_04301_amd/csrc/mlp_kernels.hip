@@ -279,6 +279,100 @@ __device__ __forceinline__ void gemm_mainloop(const char* __restrict__ Pg, const
     }
 }
 
+// Weight gradients: the fresh gradient block of a tile goes to gbuf[fresh row of g][goff + m*N + n].
+// accumulator element e of a lane: column n = lane % 32, row m = (e/4)*8 + (lane/32)*4 + e%4
+template <typename TL>
+__device__ __forceinline__ void dw_store_fresh(const GemmArgs& a, int g, int m0, int n0,
+                                               const f32x16 (&acc)[TL::TM][TL::TN])
+{
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int wm = wave / TL::WN, wn = wave % TL::WN;
+    constexpr int RW = TL::BM / TL::WM, CW = TL::BN / TL::WN;
+    const int cl = lane & 31, rh = (lane >> 5) * 4;
+    float* gb = fresh_row(a.gbuf, a.which, a.hy, g) + a.goff;
+#pragma unroll
+    for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TL::TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
+                const int n = n0 + wn * CW + j * 32 + cl;
+                if (m < a.M && n < a.N) gb[(int64_t)m * a.N + n] = acc[i][j][e];
+            }
+}
+
+// k-tile t of two passes laid end to end: tiles 0..nk-1 from (Pg, Qg), tiles nk..2nk-1 from the
+// same places dP / dQ bytes further on
+template <typename TL>
+__device__ __forceinline__ void tile_gload2(const char* __restrict__ Pg, const char* __restrict__ Qg,
+                                            const int64_t (&poff)[TL::PCH], int64_t ldq_b, int64_t dP,
+                                            int64_t dQ, int nk, int t, u32x4 (&rp)[TL::PCH],
+                                            u32x4 (&rq)[TL::QCH])
+{
+    const bool second = t >= nk;
+    tile_gload<TL>(Pg + (second ? dP : 0), Qg + (second ? dQ : 0), poff, ldq_b, second ? t - nk : t, rp, rq);
+}
+
+// The weight-gradient k-loops of both iterates as ONE software pipeline (PF = 2 only): with K =
+// the minibatch size a pass is a handful of k-tiles, and two separate passes would fill and
+// drain the pipeline twice.  Between the last tile of the first pass and the first tile of the
+// second the accumulators hold the fresh block, which is stored there -- the stores drain while
+// the second pass runs.  The number of k-tiles per pass must be even (a turn of the loop handles
+// two tiles and the store sits between two turns).
+// One turn of the two-passes loop: k-tiles kt and kt+1 (kt even).  Requests tiles kt+2 and kt+3
+// (clamped to the last one) into the register sets, multiplies kt and kt+1 from the LDS stages.
+template <typename T, typename TL>
+__device__ __forceinline__ void two_passes_turn(const char* __restrict__ Pg, const char* __restrict__ Qg,
+                                                const int64_t (&poff)[TL::PCH], int64_t ldq_b, int64_t dP,
+                                                int64_t dQ, int nk, int kt, int last, char* lds,
+                                                u32x4 (&rp0)[TL::PCH], u32x4 (&rq0)[TL::QCH],
+                                                u32x4 (&rp1)[TL::PCH], u32x4 (&rq1)[TL::QCH],
+                                                f32x16 (&acc)[TL::TM][TL::TN])
+{
+    constexpr int kP = TL::BM * TL::PITCH;
+    {
+        char* cur = lds;
+        char* nxt = lds + TL::STAGE;
+        tile_gload2<TL>(Pg, Qg, poff, ldq_b, dP, dQ, nk, kt + 2 < last ? kt + 2 : last, rp0, rq0);
+        tile_mma<T, TL>(cur, cur + kP, acc);
+        tile_lstore<TL>(nxt, nxt + kP, rp1, rq1);
+        __syncthreads();
+    }
+    {
+        char* cur = lds + TL::STAGE;
+        char* nxt = lds;
+        tile_gload2<TL>(Pg, Qg, poff, ldq_b, dP, dQ, nk, kt + 3 < last ? kt + 3 : last, rp1, rq1);
+        tile_mma<T, TL>(cur, cur + kP, acc);
+        tile_lstore<TL>(nxt, nxt + kP, rp0, rq0);
+        __syncthreads();
+    }
+}
+
+template <typename T, typename TL>
+__device__ __forceinline__ void gemm_mainloop_two_passes(
+    const char* __restrict__ Pg, const char* __restrict__ Qg, const int64_t (&poff)[TL::PCH],
+    int64_t ldq_b, int64_t dP, int64_t dQ, int K, char* lds, f32x16 (&acc)[TL::TM][TL::TN],
+    const GemmArgs& a, int g, int m0, int n0)
+{
+    static_assert(TL::PF == 2, "two k-tiles in flight");
+    constexpr int kElemsPerTileK = TL::KROW / (int)sizeof(T);
+    constexpr int kP = TL::BM * TL::PITCH;
+    const int nk = (K + kElemsPerTileK - 1) / kElemsPerTileK;     // even
+    const int total = 2 * nk, last = total - 1;
+    u32x4 rp0[TL::PCH], rq0[TL::QCH], rp1[TL::PCH], rq1[TL::QCH];
+    tile_gload2<TL>(Pg, Qg, poff, ldq_b, dP, dQ, nk, 0, rp0, rq0);
+    tile_gload2<TL>(Pg, Qg, poff, ldq_b, dP, dQ, nk, 1, rp1, rq1);
+    tile_lstore<TL>(lds, lds + kP, rp0, rq0);
+    __syncthreads();
+    // first pass; its last turn already requests the first tiles of the second
+    for (int kt = 0; kt < nk; kt += 2)
+        two_passes_turn<T, TL>(Pg, Qg, poff, ldq_b, dP, dQ, nk, kt, last, lds, rp0, rq0, rp1, rq1, acc);
+    dw_store_fresh<TL>(a, g, m0, n0, acc);
+    for (int kt = nk; kt < total; kt += 2)
+        two_passes_turn<T, TL>(Pg, Qg, poff, ldq_b, dP, dQ, nk, kt, last, lds, rp0, rq0, rp1, rq1, acc);
+}
+
 __device__ __forceinline__ int stale_slot(const Hyper& hy, const int32_t* tau, int g)
 {
     return stale_slot_of(hy, tau[g]);
@@ -383,21 +477,30 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         // The transposed signal of the stale iterate is stored NEGATED by the kernel that
         // produces it.  So: multiply at theta^k, write the fresh gradient block, then keep
         // accumulating the stale products into the same registers, which then hold
-        // fresh - stale -- one accumulator set serves both iterates.
-        gemm_pass<T, TL>(a, 0, g, m0, n0, lds, acc);
-        float* gb = fresh_row(a.gbuf, a.which, hy, g) + a.goff;
+        // fresh - stale -- one accumulator set serves both iterates, and the two k-loops run as
+        // one pipeline (gemm_mainloop_two_passes).
+        if (hy.sel) {                            // server-side rule: no stale pass, no statistic
+            gemm_pass<T, TL>(a, 0, g, m0, n0, lds, acc);
+            dw_store_fresh<TL>(a, g, m0, n0, acc);
+            return;
+        }
+        constexpr int kTileK = TL::KROW / (int)sizeof(T);
+        if (((a.K + kTileK - 1) / kTileK) % 2 != 0) {
+            // odd number of k-tiles per pass: two pipelines
+            gemm_pass<T, TL>(a, 0, g, m0, n0, lds, acc);
+            dw_store_fresh<TL>(a, g, m0, n0, acc);
+            gemm_pass<T, TL>(a, 1, g, m0, n0, lds, acc);
+        } else {
+            // both passes in one pipeline; the fresh block is stored between them
+            const char* Pg = (const char*)a.P + ((int64_t)g * a.p_g + (int64_t)m0 * a.ldp) * esz;
+            const char* Qg = (const char*)a.Q + ((int64_t)g * a.q_g + (int64_t)n0 * a.ldq) * esz;
+            int64_t poff[TL::PCH];
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int m = m0 + wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
-                    const int n = n0 + wn * CW + j * 32 + cl;
-                    if (m < a.M && n < a.N) gb[(int64_t)m * a.N + n] = acc[i][j][e];
-                }
-        if (hy.sel) return;                      // server-side rule: no stale pass, no statistic
-        gemm_pass<T, TL>(a, 1, g, m0, n0, lds, acc);
+            for (int i = 0; i < TL::PCH; ++i)
+                poff[i] = (int64_t)((threadIdx.x + TL::NT * i) / TL::CPR) * a.ldp * esz;
+            gemm_mainloop_two_passes<T, TL>(Pg, Qg, poff, (int64_t)a.ldq * esz, a.p_it * esz, a.q_it * esz,
+                                            a.K, lds, acc, a, g, m0, n0);
+        }
         double sq = 0;
 #pragma unroll
         for (int i = 0; i < TM; ++i)

@@ -290,6 +290,23 @@ __device__ __forceinline__ void dw_store_fresh(const GemmArgs& a, int g, int m0,
     constexpr int RW = TL::BM / TL::WM, CW = TL::BN / TL::WN;
     const int cl = lane & 31, rh = (lane >> 5) * 4;
     float* gb = fresh_row(a.gbuf, a.which, a.hy, g) + a.goff;
+    if (m0 + TL::BM <= a.M && n0 + TL::BN <= a.N) {
+        // tile inside the matrix (the usual case): no bounds checks.  The row address is the
+        // same for the whole wave (scalar registers); a lane adds one 32-bit byte offset, the
+        // column block is an immediate
+        const int uw = __builtin_amdgcn_readfirstlane(wave);
+        char* wb = (char*)(gb + (int64_t)(m0 + (uw / TL::WN) * RW) * a.N + (n0 + (uw % TL::WN) * CW));
+        const unsigned lo4 = (unsigned)(rh * a.N + cl) * 4u;
+#pragma unroll
+        for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                char* rowb = wb + (int64_t)(i * 32 + (e >> 2) * 8 + (e & 3)) * a.N * 4;
+#pragma unroll
+                for (int j = 0; j < TL::TN; ++j) *(float*)(rowb + (lo4 + (unsigned)j * 128u)) = acc[i][j][e];
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TL::TM; ++i)
 #pragma unroll
@@ -502,19 +519,31 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
                                             a.K, lds, acc, a, g, m0, n0);
         }
         double sq = 0;
+        if (m0 + BM <= a.M && n0 + BN <= a.N) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int m = m0 + wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
-                    const int n = n0 + wn * CW + j * 32 + cl;
-                    if (m < a.M && n < a.N) {
+                    for (int e = 0; e < 16; ++e) {
                         const float df = acc[i][j][e];
                         sq += (double)df * (double)df;
                     }
-                }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int m = m0 + wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
+                        const int n = n0 + wn * CW + j * 32 + cl;
+                        if (m < a.M && n < a.N) {
+                            const float df = acc[i][j][e];
+                            sq += (double)df * (double)df;
+                        }
+                    }
+        }
         sq = wave_sum(sq);
         double* red = (double*)lds;
         __syncthreads();

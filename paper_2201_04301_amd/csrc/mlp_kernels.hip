@@ -122,12 +122,14 @@ struct GemmArgs {
     // Q operand: either per (it,g) like P, or a weight copy indexed by ring slot
     const void* Q; int64_t q_it, q_g, q_slot; int ldq; int q_is_weight;
     // FWD : bias from the fp32 ring (offset boff), outputs A [M][ldo] and AT [N][ldt]
-    // DA  : relu mask read from `mask` (same layout as the output), outputs dZ and dZT
+    // DA  : ReLU mask from relu_bits (written by the FWD launch of that layer), outputs dZ and dZT
     // HEAD: output layer (N = classes <= 128, one tile holds whole rows): bias, softmax
     //       cross-entropy against the labels, outputs dZ_L and dZ_L^T, one loss partial per block
     const float* ring; int64_t boff;
-    const void* maskp; int64_t m_it, m_g; int ldm;       // row-major activations
-    const void* maskTp; int64_t mt_it, mt_g;             // the same, transposed (leading dimension ldt)
+    // one bit per element of a hidden layer's output, "activation > 0", in the accumulator layout
+    // of the tile that produced it: word [(it*G + g), tile row, tile column][i*TN + j][thread],
+    // bit e.  FWD writes it, the DA launch with the same output shape (and tile shape) reads it
+    uint16_t* relu_bits;
     void* O; int64_t o_it, o_g; int ldo;
     void* OT; int64_t t_it, t_g; int ldt;
     // DW : fresh gradient block -> grad[g*p + goff + m*N + n]; partial ||fresh-stale||^2
@@ -660,6 +662,31 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][e] = fmaxf(acc[i][j][e] + bv, 0.0f);
             }
+            // which units are active, for the backward pass
+            uint16_t* rb = a.relu_bits + ((((int64_t)it0 * a.G + g) * gridDim.y + by) * gridDim.x + bx) *
+                                             (int64_t)(TM * TN * kGemmThreads);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    unsigned b = 0;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) b |= (acc[i][j][e] > 0.0f ? 1u : 0u) << e;
+                    rb[(i * TN + j) * kGemmThreads + tid] = (uint16_t)b;
+                }
+        } else {
+            // ReLU mask of the layer this signal belongs to: clear the accumulators of inactive units
+            const uint16_t* rb = a.relu_bits + ((((int64_t)it0 * a.G + g) * gridDim.y + by) * gridDim.x + bx) *
+                                                   (int64_t)(TM * TN * kGemmThreads);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const unsigned b = rb[(i * TN + j) * kGemmThreads + tid];
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (!((b >> e) & 1u)) acc[i][j][e] = 0.0f;
+                }
         }
         // ---- transposed: stT [BN][PT], element (n, m) ----
 #pragma unroll
@@ -680,25 +707,18 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         __syncthreads();
         {
             T* OT = (T*)a.OT + (int64_t)it0 * a.t_it + (int64_t)g * a.t_g;
-            const T* mkT = EPI == EPI_DA
-                ? (const T*)a.maskTp + (int64_t)it0 * a.mt_it + (int64_t)g * a.mt_g : nullptr;
             for (int c = tid; c < BN * (BM / V); c += kGemmThreads) {
                 const int nl = c / (BM / V), mv = (c % (BM / V)) * V;
                 const int n = n0 + nl, m = m0 + mv;
                 if (n < a.N && m < a.M) {
                     alignas(16) T tmp[V];
-                    alignas(16) T act[V];
                     *(uint4*)tmp = *(const uint4*)(st + nl * PT + mv);
-                    if (EPI == EPI_DA) *(uint4*)act = *(const uint4*)(mkT + (int64_t)n * a.ldt + m);
 #pragma unroll
                     for (int q = 0; q < V; ++q) {
                         float v = (m + q < a.M) ? to_f<T>(tmp[q]) : 0.0f;
-                        if (EPI == EPI_DA) {
-                            // ReLU mask (the layer's activations); the stale iterate's transposed
-                            // signal is stored negated for the weight-gradient kernel
-                            if (!(to_f<T>(act[q]) > 0.0f)) v = 0.0f;
-                            if (it0 == 1) v = -v;
-                        }
+                        // the stale iterate's transposed signal is stored negated for the
+                        // weight-gradient kernel
+                        if (EPI == EPI_DA && it0 == 1) v = -v;
                         tmp[q] = to_T<T>(v);
                     }
                     *(uint4*)(OT + (int64_t)n * a.ldt + m) = *(const uint4*)tmp;
@@ -747,25 +767,16 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         __syncthreads();
         {
             T* O = (T*)a.O + (int64_t)it0 * a.o_it + (int64_t)g * a.o_g;
-            const T* mk = EPI == EPI_DA
-                ? (const T*)a.maskp + (int64_t)it0 * a.m_it + (int64_t)g * a.m_g : nullptr;
             for (int c = tid; c < BM * (BN / V); c += kGemmThreads) {
                 const int ml = c / (BN / V), nv = (c % (BN / V)) * V;
                 const int m = m0 + ml, n = n0 + nv;
                 if (m < a.M && n < a.N) {
                     // ldo is a multiple of 64 and pads stay zero: mask the lanes beyond N
                     alignas(16) T tmp[V];
-                    alignas(16) T act[V];
                     *(uint4*)tmp = *(const uint4*)(st + ml * PR + nv);
-                    if (EPI == EPI_DA) *(uint4*)act = *(const uint4*)(mk + (int64_t)m * a.ldm + n);
 #pragma unroll
-                    for (int q = 0; q < V; ++q) {
-                        T v = (n + q < a.N) ? tmp[q] : to_T<T>(0.0f);
-                        if (EPI == EPI_DA) {
-                            if (!(to_f<T>(act[q]) > 0.0f)) v = to_T<T>(0.0f);
-                        }
-                        tmp[q] = v;
-                    }
+                    for (int q = 0; q < V; ++q)
+                        if (!(n + q < a.N)) tmp[q] = to_T<T>(0.0f);
                     *(uint4*)(O + (int64_t)m * a.ldo + n) = *(const uint4*)tmp;
                 }
             }
@@ -989,6 +1000,7 @@ struct MlpWork {
     void* Xg = nullptr; void* XgT = nullptr;
     void* A[GCADA_MAX_WIDTHS] = {};  void* AT[GCADA_MAX_WIDTHS] = {};
     void* dZ[GCADA_MAX_WIDTHS] = {}; void* dZT[GCADA_MAX_WIDTHS] = {};
+    void* relu[GCADA_MAX_WIDTHS] = {};   // l = 1..L-1: one bit per element of A_l (see GemmArgs::relu_bits)
     // weight copies per ring slot: Wc_l [slot][n_l][ld_{l-1}], WcT_l [slot][n_{l-1}][ld_l]
     void* Wc[GCADA_MAX_WIDTHS] = {}; void* WcT[GCADA_MAX_WIDTHS] = {};
     int64_t wc_slot[GCADA_MAX_WIDTHS] = {}, wct_slot[GCADA_MAX_WIDTHS] = {};
@@ -1045,6 +1057,9 @@ hipError_t mlp_plan(gcada_ctx* c)
         if (l < L) {
             if ((e = walloc(w, &w->A[l], rm)) != hipSuccess) return e;
             if ((e = walloc(w, &w->AT[l], tr)) != hipSuccess) return e;
+            // whole tiles of at most 256 x 256, 16 elements per 2-byte word
+            const size_t bits = (size_t)2 * G * (mu + 256) * (lay.n[l] + 256) / 16 * 2;
+            if ((e = walloc(w, &w->relu[l], bits)) != hipSuccess) return e;
         }
         if ((e = walloc(w, &w->dZ[l], rm)) != hipSuccess) return e;
         if ((e = walloc(w, &w->dZT[l], tr)) != hipSuccess) return e;
@@ -1156,6 +1171,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
         if (l < L) {
             a.O = w->A[l]; a.o_it = rm_it(l); a.o_g = rm_g(l); a.ldo = lay.ld[l];
             a.OT = w->AT[l]; a.t_it = tr_it(l); a.t_g = tr_g(l); a.ldt = lay.ldmu;
+            a.relu_bits = (uint16_t*)w->relu[l];
             if ((e = launch_gemm<T, EPI_FWD>(a, 2 * G, w->small, s)) != hipSuccess) return e;
         } else {
             a.O = w->dZ[L]; a.o_it = rm_it(L); a.o_g = rm_g(L); a.ldo = lay.ld[L];
@@ -1190,8 +1206,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             a.M = mu; a.N = lay.n[l - 1]; a.K = lay.n[l];
             a.P = w->dZ[l]; a.p_it = rm_it(l); a.p_g = rm_g(l); a.ldp = lay.ld[l];
             a.Q = w->WcT[l]; a.q_is_weight = 1; a.q_slot = w->wct_slot[l]; a.ldq = lay.ld[l];
-            a.maskp = w->A[l - 1]; a.m_it = rm_it(l - 1); a.m_g = rm_g(l - 1); a.ldm = lay.ld[l - 1];
-            a.maskTp = w->AT[l - 1]; a.mt_it = tr_it(l - 1); a.mt_g = tr_g(l - 1);
+            a.relu_bits = (uint16_t*)w->relu[l - 1];
             a.O = w->dZ[l - 1]; a.o_it = rm_it(l - 1); a.o_g = rm_g(l - 1); a.ldo = lay.ld[l - 1];
             a.OT = w->dZT[l - 1]; a.t_it = tr_it(l - 1); a.t_g = tr_g(l - 1); a.ldt = lay.ldmu;
             if ((e = launch_gemm<T, EPI_DA>(a, 2 * G, w->small, s)) != hipSuccess) return e;

@@ -164,7 +164,14 @@ def main():
             if (n_cpu > 0 and done >= n_cpu) or (n_cpu <= 0 and (spent > budget_s or kk >= K + W)):
                 break
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu_model = ""
+        try:
+            with open("/proc/cpuinfo") as f:
+                cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+        except OSError:
+            pass
         cpu = {"value": round(done / spent, 3), "unit": "iters/s", "cores": cores, "kind": "oracle",
+               "cpu_model": cpu_model,
                "sample": f"first {done} iterations of the same workload, same shards and row ids "
                          f"(oracle time only; row gather excluded)"}
 

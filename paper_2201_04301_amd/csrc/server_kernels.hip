@@ -363,21 +363,46 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
     }
 }
 
-// ||theta^k||^2 of the current slot (one block).
+// ||theta^k||^2 of the current slot.  grid: any number of blocks <= the entries of part (one
+// partial each, fixed slab order); the block that finishes last adds them up in a fixed order.
 __global__ __launch_bounds__(256) void theta_sq_kernel(Hyper hy, const float* __restrict__ ring,
-                                                        Ctl* __restrict__ ctl)
+                                                        double* __restrict__ part, Ctl* __restrict__ ctl)
 {
     __shared__ double s_tmp[256 / kWave];
+    __shared__ bool s_last;
     const float* th = ring + (int64_t)hy.cur * hy.pstride;
     double a = 0;
-    for (int64_t i = threadIdx.x; i < hy.p; i += 256) a += (double)th[i] * (double)th[i];
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < hy.p; i += (int64_t)gridDim.x * 256)
+        a += (double)th[i] * (double)th[i];
     a = wave_sum(a);
     if (threadIdx.x % kWave == 0) s_tmp[threadIdx.x / kWave] = a;
     __syncthreads();
     if (threadIdx.x == 0) {
         double t = 0;
         for (int w = 0; w < 256 / kWave; ++w) t += s_tmp[w];
-        ctl->theta_sq = t;
+        if (gridDim.x == 1) {
+            ctl->theta_sq = t;
+            s_last = false;
+        } else {
+            part[blockIdx.x] = t;
+            __threadfence();
+            s_last = atomicAdd(&ctl->cnt_c, 1u) == gridDim.x - 1;
+        }
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    double t = 0;
+    for (int i = threadIdx.x; i < (int)gridDim.x; i += 256) t += part[i];
+    t = wave_sum(t);
+    __syncthreads();
+    if (threadIdx.x % kWave == 0) s_tmp[threadIdx.x / kWave] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double u = 0;
+        for (int w = 0; w < 256 / kWave; ++w) u += s_tmp[w];
+        ctl->theta_sq = u;
+        ctl->cnt_c = 0;
     }
 }
 
@@ -438,7 +463,9 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool pr
 
 hipError_t refresh_theta_sq(gcada_ctx* c, hipStream_t s)
 {
-    theta_sq_kernel<<<1, 256, 0, s>>>(c->hy, c->ring, c->ctl);
+    // one block per 64K parameters, at most as many as there are partial slots
+    const int blocks = (int)std::max<int64_t>(1, std::min<int64_t>(2 * (int64_t)c->n_epi_blocks, (c->hy.p + 65535) / 65536));
+    theta_sq_kernel<<<blocks, 256, 0, s>>>(c->hy, c->ring, c->part_sq, c->ctl);
     return hipGetLastError();
 }
 

@@ -650,6 +650,7 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         constexpr int V = 16 / esz;                 // elements per 16-byte vector
         constexpr int PT = BM + V, PR = BN + V;     // row pitches of the two staging tiles
         T* st = (T*)lds;
+        const bool inside = m0 + BM <= a.M && n0 + BN <= a.N;
         const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
         if constexpr (EPI == EPI_FWD) {
             const float* bias = a.ring + (int64_t)slot * hy.pstride + a.boff;
@@ -707,6 +708,20 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         __syncthreads();
         {
             T* OT = (T*)a.OT + (int64_t)it0 * a.t_it + (int64_t)g * a.t_g;
+            // the stale iterate's transposed signal is stored negated for the weight-gradient
+            // kernel: flip the sign bits of the packed values
+            constexpr unsigned kSigns = esz == 2 ? 0x80008000u : 0x80000000u;
+            const unsigned flip = (EPI == EPI_DA && it0 == 1) ? kSigns : 0u;
+            if (inside) {
+                // tile inside the matrix: the staged values go out as they are
+#pragma unroll 4
+                for (int c = tid; c < BN * (BM / V); c += kGemmThreads) {
+                    const int nl = c / (BM / V), mv = (c % (BM / V)) * V;
+                    uint4 v = *(const uint4*)(st + nl * PT + mv);
+                    v.x ^= flip; v.y ^= flip; v.z ^= flip; v.w ^= flip;
+                    *(uint4*)(OT + (int64_t)(n0 + nl) * a.ldt + (m0 + mv)) = v;
+                }
+            } else
             for (int c = tid; c < BN * (BM / V); c += kGemmThreads) {
                 const int nl = c / (BM / V), mv = (c % (BM / V)) * V;
                 const int n = n0 + nl, m = m0 + mv;
@@ -767,6 +782,13 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         __syncthreads();
         {
             T* O = (T*)a.O + (int64_t)it0 * a.o_it + (int64_t)g * a.o_g;
+            if (inside) {
+#pragma unroll 4
+                for (int c = tid; c < BM * (BN / V); c += kGemmThreads) {
+                    const int ml = c / (BN / V), nv = (c % (BN / V)) * V;
+                    *(uint4*)(O + (int64_t)(m0 + ml) * a.ldo + (n0 + nv)) = *(const uint4*)(st + ml * PR + nv);
+                }
+            } else
             for (int c = tid; c < BM * (BN / V); c += kGemmThreads) {
                 const int ml = c / (BN / V), nv = (c % (BN / V)) * V;
                 const int m = m0 + ml, n = n0 + nv;

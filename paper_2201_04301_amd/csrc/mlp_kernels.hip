@@ -689,6 +689,21 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
                         if (!((b >> e) & 1u)) acc[i][j][e] = 0.0f;
                 }
         }
+        // two-byte outputs: round the accumulators once, to packed pairs (rows 0,1 and rows 2,3 of
+        // each group of four), for both stagings
+        constexpr int NPK = esz == 2 ? 8 : 1;
+        unsigned pk[TM][TN][NPK];
+        if constexpr (esz == 2) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int h = 0; h < 8; ++h) {
+                        alignas(4) T q2[2] = {to_T<T>(acc[i][j][2 * h]), to_T<T>(acc[i][j][2 * h + 1])};
+                        pk[i][j][h] = *(const unsigned*)q2;
+                    }
+        }
         // ---- transposed: stT [BN][PT], element (n, m) ----
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -698,11 +713,14 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
 #pragma unroll
                 for (int eg = 0; eg < 4; ++eg) {
                     const int ml = wm * RW + i * 32 + eg * 8 + rh;      // rows ml .. ml+3
-                    alignas(16) T q4[4];
+                    if constexpr (esz == 2) {
+                        *(uint2*)(st + nl * PT + ml) = make_uint2(pk[i][j][2 * eg], pk[i][j][2 * eg + 1]);
+                    } else {
+                        alignas(16) T q4[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) q4[q] = to_T<T>(acc[i][j][eg * 4 + q]);
-                    if constexpr (esz == 2) *(uint2*)(st + nl * PT + ml) = *(const uint2*)q4;
-                    else *(uint4*)(st + nl * PT + ml) = *(const uint4*)q4;
+                        for (int q = 0; q < 4; ++q) q4[q] = to_T<T>(acc[i][j][eg * 4 + q]);
+                        *(uint4*)(st + nl * PT + ml) = *(const uint4*)q4;
+                    }
                 }
             }
         __syncthreads();
@@ -753,15 +771,7 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
                     if constexpr (esz == 2) {
                         // rows 0,1 and rows 2,3 as two packed words; the lane pair (n, n^1) swaps
                         // one word so that each lane holds two columns of two rows
-                        unsigned w01, w23;
-                        {
-                            alignas(8) T q4[4];
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) q4[q] = to_T<T>(acc[i][j][eg * 4 + q]);
-                            const uint2 u = *(const uint2*)q4;
-                            w01 = u.x;
-                            w23 = u.y;
-                        }
+                        const unsigned w01 = pk[i][j][2 * eg], w23 = pk[i][j][2 * eg + 1];
                         const bool odd = (lane & 1) != 0;
                         const unsigned give = odd ? w01 : w23;
                         const unsigned got = (unsigned)__builtin_amdgcn_mov_dpp((int)give, 0xB1, 0xF, 0xF, true);

@@ -123,7 +123,14 @@ int gcada_set_theta(gcada_ctx* ctx, const float* theta0);
 int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* loss_out,
                void* stream);
 
-/* Views of the device state, valid until the next gcada_step / set_* / destroy. */
+/*
+ * Views of the device state, valid until the next gcada_step / set_* / destroy.  Asynchronous:
+ * the buffers hold the result of the last step once the stream that step was given has reached
+ * it.  (After a step of the whole-row logistic path with GCADA_OPT_FUSED_FINISH the newest entry
+ * of dtheta_sq is still spread over the kernel's blocks; this call then enqueues one small
+ * kernel on THAT stream, which must still exist, to add it up.  gcada_get_state does the same
+ * and waits.)
+ */
 typedef struct gcada_state_view {
     int64_t p;               /* number of parameters                                          */
     int32_t G, D, M_G;
@@ -198,7 +205,9 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * kernels.  Both compute the same step
  * a1.  GCADA_OPT_FUSED_FINISH [1]: after the whole-row tile kernel, add the tile partials, select
  * (Eq. (9)), sum the innovations and update (Eq. (8a)-(8c)) in ONE launch whose blocks meet once
- * inside the kernel (at most one block per compute unit, bounded wait); 0 uses the separate
+ * inside the kernel (at most 64 blocks, one per compute unit; the wait is bounded: if the blocks
+ * cannot all run at once -- another stream holding the device -- the step is reported as failed,
+ * GCADA_EDEVICE from the next gcada_get_state, instead of hanging); 0 uses the separate
  * reduce and server kernels.  Same arithmetic per element either way.
  * Errors: GCADA_EINVAL (unknown option).
  */

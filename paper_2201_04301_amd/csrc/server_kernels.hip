@@ -463,8 +463,8 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool pr
 
 hipError_t refresh_theta_sq(gcada_ctx* c, hipStream_t s)
 {
-    // one block per 64K parameters, at most as many as there are partial slots
-    const int blocks = (int)std::max<int64_t>(1, std::min<int64_t>(2 * (int64_t)c->n_epi_blocks, (c->hy.p + 65535) / 65536));
+    // one block per 8K parameters, at most as many as there are partial slots
+    const int blocks = (int)std::max<int64_t>(1, std::min<int64_t>(2 * (int64_t)c->n_epi_blocks, (c->hy.p + 8191) / 8192));
     theta_sq_kernel<<<blocks, 256, 0, s>>>(c->hy, c->ring, c->part_sq, c->ctl);
     return hipGetLastError();
 }

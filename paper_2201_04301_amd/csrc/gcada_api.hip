@@ -66,6 +66,7 @@ void free_all(gcada_ctx* c)
     if (!c) return;
     gcada::mlp_free(c);
     gcada::lr_tile_free(c);
+    gcada::lr_micro_free(c);
     gcada::lr_team_free(c);
     gcada::rule_free(c);
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->gbuf, c->which, c->tau,
@@ -161,6 +162,8 @@ try {
         return bail(e, "single-pass logistic plan");
     if (dims->model != GCADA_MLP && (e = gcada::lr_team_plan(x)) != hipSuccess)
         return bail(e, "team logistic plan");
+    if (dims->model != GCADA_MLP && (e = gcada::lr_micro_plan(x)) != hipSuccess)
+        return bail(e, "one-launch logistic plan");
     if ((e = dalloc(&x->part_loss, (size_t)G * x->n_loss_part)) != hipSuccess) return bail(e, "alloc scratch");
     if ((e = dalloc(&x->part_stat, (size_t)G * x->n_stat_part)) != hipSuccess) return bail(e, "alloc scratch");
     if ((e = dalloc(&x->part_sq, (size_t)2 * x->n_epi_blocks)) != hipSuccess) return bail(e, "alloc scratch");
@@ -270,6 +273,15 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     hipError_t e;
     const bool server_rule = ctx->rule == GCADA_RULE_SERVER;
     ctx->hy.sel = server_rule ? ctx->mask : nullptr;
+    if (ctx->dims.model != GCADA_MLP && gcada::lr_micro_applies(ctx)) {
+        // small linear model: the whole iteration is one launch
+        ctx->lr_fused_finish = false;
+        if ((e = gcada::lr_tile_close(ctx, s, false)) != hipSuccess) return fail_hip(ctx, e, "history kernel");
+        if ((e = gcada::lr_micro_step(ctx, idx, mask_out, loss_out, false, s)) != hipSuccess)
+            return fail_hip(ctx, e, "one-launch kernel");
+        ctx->k += 1;
+        return GCADA_OK;
+    }
     ctx->lr_fused_finish = ctx->dims.model != GCADA_MLP && gcada::lr_tile_finish_applies(ctx);
     if (!ctx->lr_fused_finish && (e = gcada::lr_tile_close(ctx, s, false)) != hipSuccess)
         return fail_hip(ctx, e, "history kernel");
@@ -474,6 +486,7 @@ const char* gcada_timed_stage(gcada_ctx* ctx)
 {
     if (!ctx) return "";
     if (ctx->dims.model == GCADA_MLP) ctx->stage_name = "mlp gradient stage (gather, mlp_gemm forward/backward/weight-gradient, bias)";
+    else if (ctx->rule != GCADA_RULE_SERVER && gcada::lr_micro_applies(ctx)) ctx->stage_name = "lr_micro_kernel (the whole iteration)";
     else if (gcada::lr_tile_applies(ctx)) ctx->stage_name = "lr_tile_kernel";
     else if (gcada::lr_team_applies(ctx)) ctx->stage_name = "lr_team_kernel";
     else ctx->stage_name = "lr_forward+lr_backward";
@@ -498,8 +511,11 @@ try {
     for (int r = 0; r < reps && e == hipSuccess; ++r)
     {
         const int32_t* ir = idx ? idx + (int64_t)r * idx_stride : nullptr;
-        e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, ir, s)
-                                            : gcada::mlp_gradients(ctx, ir, s);
+        if (ctx->dims.model != GCADA_MLP && ctx->rule != GCADA_RULE_SERVER && gcada::lr_micro_applies(ctx))
+            e = gcada::lr_micro_step(ctx, ir, nullptr, nullptr, true, s);      // changes no state
+        else
+            e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, ir, s)
+                                             : gcada::mlp_gradients(ctx, ir, s);
     }
     ctx->dominant_only = false;
     if (e == hipSuccess) e = hipEventRecord(e1, s);

@@ -78,6 +78,7 @@ __device__ __forceinline__ T global_load(const T* p)
 struct MlpWork;       // MLP activations and compute copies (mlp_kernels.hip)
 struct LrTilePlan;    // single-pass logistic path, rows that fit one workgroup (lr_tiles.hip)
 struct LrTeamPlan;    // single-pass logistic path, wide rows shared by a team (lr_team.hip)
+struct LrMicroPlan;   // small linear models: the whole iteration in one launch (lr_micro.hip)
 
 }  // namespace gcada
 
@@ -122,6 +123,7 @@ struct gcada_ctx {
     gcada::MlpWork* mlp = nullptr;
     gcada::LrTilePlan* lr_tiles = nullptr;
     gcada::LrTeamPlan* lr_team = nullptr;
+    gcada::LrMicroPlan* lr_micro = nullptr;
     unsigned team_launches = 0;    // advances the exchange tags of the team kernel
     // server-side rule (Sec. IV): 0 = gradient-difference statistic, 1 = L_g^2 ||theta^k - theta_stale||^2
     int32_t rule = 0;
@@ -165,6 +167,13 @@ void lr_team_free(gcada_ctx* c);
 bool lr_team_applies(const gcada_ctx* c);
 hipError_t lr_team_reset(gcada_ctx* c);       // clear the exchange buffer
 hipError_t lr_team_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
+
+// small linear models (d <= 256): gradients, selection and update in one launch (lr_micro.hip)
+hipError_t lr_micro_plan(gcada_ctx* c);
+void lr_micro_free(gcada_ctx* c);
+bool lr_micro_applies(const gcada_ctx* c);
+hipError_t lr_micro_step(gcada_ctx* c, const int32_t* idx, uint8_t* mask_out, float* loss_out, bool dry,
+                         hipStream_t s);
 
 hipError_t mlp_plan(gcada_ctx* c);
 void mlp_free(gcada_ctx* c);

@@ -183,6 +183,49 @@ def test_lr_fused_finish_matches_separate_kernels(par, d, mu, G, l2):
     np.testing.assert_array_equal(o1["grad"], o0["grad"])
 
 
+@pytest.mark.parametrize("model,d,mu,G,l2", [
+    ("logreg", 64, 32, 3, 0.0),       # configuration 1's shape
+    ("logreg", 256, 128, 3, 1e-3),    # the widest rows and longest minibatch of the one-launch path
+    ("linreg", 100, 17, 9, 1e-4),     # column lanes that do not fill a wave, ragged minibatch
+    ("logreg", 4, 1, 1, 0.0),         # one sample, one group
+])
+def test_lr_one_launch_path_matches_general_kernels(par, model, d, mu, G, l2):
+    # small linear models run the whole iteration in one launch (lr_micro_kernel); with the
+    # single-pass switch off the same run goes through the general kernels and the server kernel
+    from paper_2201_04301_amd import Gcada, binding as B
+    from gcada_inputs import make_theta0
+    w = scaled(CONFIGS["lr_small"], name="micro", model=model, widths=(d,), mu=mu, G=G, rows=300, l2=l2,
+               c=0.5, D=5, flip=0.05)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 40
+    idx = torch.as_tensor(make_indices(w, steps), device="cuda")
+    res = []
+    for one_launch in (1, 0):
+        gpu = Gcada.from_workload(w)
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_SINGLE_PASS_LOGREG, one_launch)
+        assert ("lr_micro" in B.gcada_timed_stage(gpu.ctx)) == bool(one_launch)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        masks = torch.zeros(steps, w.G, dtype=torch.uint8, device="cuda")
+        losses = torch.zeros(steps, dtype=torch.float32, device="cuda")
+        for k in range(steps):
+            gpu.step(idx[k].contiguous(), mask_out=masks[k], loss_out=losses[k:k + 1])
+        out = gpu.outputs()
+        st = gpu.get_state()
+        res.append((masks.cpu().numpy(), losses.cpu().numpy(), st, out))
+        gpu.close()
+    (m1, l1, s1, o1), (m0, l0, s0, o0) = res
+    np.testing.assert_array_equal(m1, m0)
+    np.testing.assert_allclose(l1, l0, rtol=1e-5)
+    scale = max(np.abs(s0["theta"]).max(), 1e-3)
+    np.testing.assert_allclose(s1["theta"], s0["theta"], rtol=0, atol=2e-4 * scale)
+    np.testing.assert_array_equal(s1["tau"], s0["tau"])
+    np.testing.assert_allclose(s1["dtheta_sq"], s0["dtheta_sq"], rtol=1e-3)
+    np.testing.assert_allclose(o1["stat"], o0["stat"], rtol=1e-3, atol=1e-12)
+    np.testing.assert_allclose(o1["grad"], o0["grad"], rtol=0, atol=2e-4 * np.abs(o0["grad"]).max())
+
+
 # ---- full-size configurations
 
 def test_lr_4k_full_size_teacher_forced(par):

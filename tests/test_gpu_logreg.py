@@ -226,6 +226,38 @@ def test_lr_one_launch_path_matches_general_kernels(par, model, d, mu, G, l2):
     np.testing.assert_allclose(o1["grad"], o0["grad"], rtol=0, atol=2e-4 * np.abs(o0["grad"]).max())
 
 
+def test_lr_fused_finish_switched_between_steps(par):
+    # the fused finish leaves the newest history entry spread over its blocks until the next
+    # launch folds it in; switching to the separate kernels (and back) between steps must first
+    # complete it.  Same additions either way: the iterates agree bit for bit.
+    from paper_2201_04301_amd import Gcada, binding as B
+    from gcada_inputs import make_theta0
+    w = scaled(CONFIGS["lr_small"], name="switch", widths=(1024,), mu=128, G=6, rows=300, l2=1e-4, c=0.5,
+               D=4, flip=0.05)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 24
+    idx = torch.as_tensor(make_indices(w, steps), device="cuda")
+    res = []
+    for pattern in ("fused", "alternate", "separate"):
+        gpu = Gcada.from_workload(w)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        masks = torch.zeros(steps, w.G, dtype=torch.uint8, device="cuda")
+        for k in range(steps):
+            on = {"fused": 1, "separate": 0, "alternate": (k // 3) % 2}[pattern]
+            B.gcada_set_option(gpu.ctx, B.GCADA_OPT_FUSED_FINISH, on)
+            gpu.step(idx[k].contiguous(), mask_out=masks[k])
+        st = gpu.get_state()
+        res.append((masks.cpu().numpy(), st))
+        gpu.close()
+    assert 0 < res[0][0].sum() < res[0][0].size
+    for m, st in res[1:]:
+        np.testing.assert_array_equal(m, res[0][0])
+        for name in ("theta", "h", "vhat", "agg", "last", "tau"):
+            np.testing.assert_array_equal(st[name], res[0][1][name], err_msg=name)
+        np.testing.assert_allclose(st["dtheta_sq"], res[0][1]["dtheta_sq"], rtol=1e-12)
+
+
 # ---- full-size configurations
 
 def test_lr_4k_full_size_teacher_forced(par):

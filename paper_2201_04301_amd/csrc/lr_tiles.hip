@@ -1,7 +1,8 @@
 // Single-pass logistic-regression gradients for d <= 4096 (step a1; paper Sec. II-A).
 //
 // Each workgroup (1024 threads) keeps a tile of R whole rows in registers -- 16 rows x 4 columns
-// per thread, the 16 waves arranged WR (rows) x WC (columns) with 256*WC = d.  Because the tile
+// per thread, the 16 waves arranged WR (rows) x WC (columns) with 256*WC >= d (WC the smallest
+// power of two that covers the row; lanes past d idle).  Because the tile
 // holds complete rows, the two dot products per row (with theta^k and with theta^k - theta_stale)
 // finish inside the workgroup; the residuals follow, and the two weighted row sums over the
 // tile's rows are formed straight from the registers.  The minibatch is therefore read from
@@ -71,6 +72,7 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
         s_row[tid] = my_row;
     }
     const int col = wc * 256 + lane * 4;
+    const bool col_ok = col < (int)hy.p;         // d is a multiple of 4; the last column wave may be partly idle
     __syncthreads();
 
     // the tile: all 16 loads of a thread are in flight at once
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     for (int u = 0; u < kTR; ++u) {
         // the row id is the same for the whole wave: keep it in a scalar register
         const int64_t row = __builtin_amdgcn_readfirstlane(s_row[wr * kTR + u]);
-        x[u] = global_load4(X + row * sh.ld + col);
+        x[u] = col_ok ? global_load4(X + row * sh.ld + col) : make_float4(0, 0, 0, 0);
     }
     // while the tile streams in: labels, the two iterates
     float my_y = 1.0f;
@@ -87,8 +89,11 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
     const int old = stale_slot_of(hy, a.tau[g]);
     const float* __restrict__ ts = a.ring + (int64_t)old * hy.pstride;
-    const float4 th4 = *(const float4*)(th + col);
-    const float4 u4 = *(const float4*)(ts + col);
+    float4 th4 = make_float4(0, 0, 0, 0), u4 = th4;
+    if (col_ok) {
+        th4 = *(const float4*)(th + col);
+        u4 = *(const float4*)(ts + col);
+    }
     const float4 dl4 = make_float4(th4.x - u4.x, th4.y - u4.y, th4.z - u4.z, th4.w - u4.w);
     // partial dot products of the wave's 256 columns, four rows at a time
 #pragma unroll
@@ -166,9 +171,11 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
             as.x = fmaf(ml, dl4.x, as.x); as.y = fmaf(ml, dl4.y, as.y);
             as.z = fmaf(ml, dl4.z, as.z); as.w = fmaf(ml, dl4.w, as.w);
         }
-        const int64_t o = (int64_t)blockIdx.x * hy.p + col;
-        *(float4*)(a.part_g + o) = ag;
-        *(float4*)(a.part_s + o) = as;
+        if (col_ok) {
+            const int64_t o = (int64_t)blockIdx.x * hy.p + col;
+            *(float4*)(a.part_g + o) = ag;
+            *(float4*)(a.part_s + o) = as;
+        }
     }
 }
 
@@ -319,6 +326,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
     const int gl = tid / CL, cl = tid % CL;
     const int S = gridDim.x, blk = blockIdx.x, G = hy.G;
     const int64_t j = ((int64_t)blk * CL + cl) * 4;
+    const bool jok = j < hy.p;                   // the last block's columns may end early (p % 4 == 0)
     const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
     float* __restrict__ tn = a.ring + (int64_t)hy.nxt * hy.pstride;
 
@@ -339,7 +347,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
         const int g = ch * kFinGroups + gl;
         double sq = 0;
         agk[ch] = make_float4(0, 0, 0, 0);
-        if (g < G) {
+        if (g < G && jok) {
             const float* pg = a.part_g + (int64_t)g * RB * hy.p + j;
             const float* ps = a.part_s + (int64_t)g * RB * hy.p + j;
             float4 ag = make_float4(0, 0, 0, 0), as = ag;
@@ -393,8 +401,8 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
     // 2. While the partials travel: everything else this block needs.  The update (a3, a4) of
     //    its 4*CL columns is done by the first 4*CL threads, one column each (a short instruction
     //    stream per lane instead of a long one on a few lanes).
-    const bool upd = tid < 4 * CL;
     const int64_t jc = (int64_t)blk * 4 * CL + tid;
+    const bool upd = tid < 4 * CL && jc < hy.p;
     float ac = 0, hv = 0, vv = 0, tv = 0;
     if (upd) {
         ac = a.agg[jc];
@@ -428,7 +436,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
         const int g = ch * kFinGroups + gl;
         h0k[ch] = h1k[ch] = make_float4(0, 0, 0, 0);
         wlk[ch] = 0;
-        if (g < G) {
+        if (g < G && jok) {
             wlk[ch] = s_which[g];      // read before this block published: block 0 may flip it now
             h0k[ch] = *(const float4*)(a.gbuf + (int64_t)g * hy.pstride + j);
             h1k[ch] = *(const float4*)(a.gbuf + ((int64_t)G + g) * hy.pstride + j);
@@ -505,7 +513,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
         const int g = ch * kFinGroups + gl;
-        if (g < G) {
+        if (g < G && jok) {
             const float4 ag = agk[ch];
             const float4 last4 = wlk[ch] ? h1k[ch] : h0k[ch];
             *(float4*)(a.gbuf + ((int64_t)(1 - wlk[ch]) * G + g) * hy.pstride + j) = ag;
@@ -618,17 +626,17 @@ struct LrTilePlan {
     hipStream_t fin_stream = nullptr;
 };
 
-// Decide whether the single-pass kernel applies (d in {256, 512, ..., 4096} so that a tile holds
-// whole rows; mu a multiple of the tile's rows) and size its scratch.
+// Decide whether the single-pass kernel applies (256 <= d <= 4096, a multiple of 4, so that a tile
+// holds whole rows; mu a multiple of the tile's rows) and size its scratch.
 hipError_t lr_tile_plan(gcada_ctx* c)
 {
     auto* pl = new LrTilePlan();
     c->lr_tiles = pl;
     const int d = (int)c->hy.p, mu = c->hy.mu, G = c->hy.G;
     int WC = 0;
-    for (int w : {1, 2, 4, 8, 16})
-        if (d == 256 * w) WC = w;
-    if (!WC) return hipSuccess;
+    for (int w : {16, 8, 4, 2, 1})
+        if (d <= 256 * w) WC = w;
+    if (!WC || d % 4 != 0 || d < 256) return hipSuccess;       // narrower rows: other kernels
     const int R = kTR * (kWaves / WC);
     if (mu % R) return hipSuccess;
     pl->R = R;
@@ -644,9 +652,9 @@ hipError_t lr_tile_plan(gcada_ctx* c)
     // fused finish: all of its blocks must be resident at once (they wait for each other)
     hipDeviceProp_t prop;
     if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return e;
-    if (G <= kFinMaxG && c->hy.pstride == c->hy.p) {
+    if (G <= kFinMaxG) {
         const int CL = 16;
-        const int S = d / (4 * CL);
+        const int S = (d + 4 * CL - 1) / (4 * CL);
         if (S <= prop.multiProcessorCount && S <= kWave) {
             const size_t words = (size_t)2 * G * S + (size_t)8 * S;
             if ((e = hipMalloc(&pl->fin_x, words * 8)) != hipSuccess) return e;
@@ -742,7 +750,7 @@ hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipS
                           (const void*)a.vhat, (const void*)a.ring, (const void*)a.nring,
                           (const void*)a.tau, (const void*)a.ctl})
         if (!q) return hipErrorInvalidValue;
-    if (a.n_loss_total != c->hy.G * pl->RB || pl->fin_S * pl->fin_CL * 4 != c->hy.p)
+    if (a.n_loss_total != c->hy.G * pl->RB || (int64_t)pl->fin_S * pl->fin_CL * 4 < c->hy.p || c->hy.p % 4 != 0)
         return hipErrorInvalidValue;
     lr_tile_finish_kernel<16><<<pl->fin_S, 16 * kFinGroups, 0, s>>>(a);
     return hipGetLastError();

@@ -100,6 +100,9 @@ def test_lr_deterministic(par):
     (512, 256, 3, 300, 1e-4, True),       # 128 x 512 tiles
     (256, 512, 2, 600, 0.0, True),        # 256 x 256 tiles
     (4096, 256, 16, 700, 1e-4, False),    # cyclic window
+    (784, 256, 3, 500, 1e-4, True),       # rows that do not fill the column waves: 64 x 1024 tiles, 784 used
+    (3000, 48, 5, 200, 0.0, True),        # 16 x 4096 tiles, 3000 columns used
+    (300, 128, 4, 300, 1e-3, False),      # 128 x 512 tiles, 300 columns used, cyclic window
     (8192, 48, 5, 100, 0.0, True),        # general kernels
     (65536, 32, 4, 64, 0.0, True),        # general kernels, d of the largest configuration
 ])
@@ -142,6 +145,7 @@ def test_lr_single_pass_matches_general_kernels(par):
     (4096, 256, 16, 1e-4),     # the benchmark's step shape: 64 blocks meet inside the kernel
     (2048, 64, 40, 0.0),       # more groups than group lanes: three passes over the groups
     (256, 256, 3, 1e-3),       # four blocks
+    (784, 128, 5, 1e-4),       # thirteen blocks, the last one with 16 of its 64 columns
     (512, 128, 70, 0.0),       # too many groups for the fused finish: separate kernels either way
 ])
 def test_lr_fused_finish_matches_separate_kernels(par, d, mu, G, l2):

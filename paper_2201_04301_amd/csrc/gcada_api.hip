@@ -283,7 +283,9 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
         return GCADA_OK;
     }
     ctx->lr_fused_finish = ctx->dims.model != GCADA_MLP && gcada::lr_tile_finish_applies(ctx);
-    if (!ctx->lr_fused_finish && (e = gcada::lr_tile_close(ctx, s, false)) != hipSuccess)
+    // the selection kernel of the server-side rule and every kernel but the fused finish read the
+    // complete history
+    if ((!ctx->lr_fused_finish || server_rule) && (e = gcada::lr_tile_close(ctx, s, false)) != hipSuccess)
         return fail_hip(ctx, e, "history kernel");
     if (server_rule) {
         // Sec. IV / Algorithm 1: the server decides first, from the iterates alone; the gradient
@@ -296,9 +298,9 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     }
     e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, idx, s) : gcada::mlp_gradients(ctx, idx, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
-    if (server_rule && (e = gcada::rule_loss(ctx, loss_out, s)) != hipSuccess)
+    if (server_rule && !ctx->lr_fused_finish && (e = gcada::rule_loss(ctx, loss_out, s)) != hipSuccess)
         return fail_hip(ctx, e, "loss kernel");
-    e = ctx->lr_fused_finish ? gcada::lr_tile_finish(ctx, mask_out, loss_out, s)
+    e = ctx->lr_fused_finish ? gcada::lr_tile_finish(ctx, mask_out, loss_out, server_rule, s)
                              : gcada::server_step(ctx, mask_out, loss_out, server_rule, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "server kernels");
     if (ctx->dims.model == GCADA_MLP) {

@@ -153,9 +153,10 @@ hipError_t lr_tile_plan(gcada_ctx* c);
 void lr_tile_free(gcada_ctx* c);
 bool lr_tile_applies(const gcada_ctx* c);
 hipError_t lr_tile_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
-// tile reduce + selection + innovation sum + server update in one launch (default rule only)
+// tile reduce + selection + innovation sum + server update in one launch (preselected: the
+// server-side rule has decided the mask before the gradient stage)
 bool lr_tile_finish_applies(const gcada_ctx* c);
-hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s);
+hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool preselected, hipStream_t s);
 // the fused finish leaves the last history entry and ||theta||^2 per block; lr_tile_close adds
 // them up (on `s`, or on the stream of that step) before anyone else reads them
 hipError_t lr_tile_close(gcada_ctx* c, hipStream_t s, bool use_step_stream);

@@ -262,6 +262,9 @@ struct FinishArgs {
     const unsigned long long* xsq_prev;
     unsigned tag_prev;
     int fold_prev;               // 0: history and ||theta^k||^2 are already complete
+    int pre;                     // 1: server-side rule (Sec. IV): the mask was decided before the
+                                 //    gradients (a.mask, a.stat, Ctl::rhs are inputs); only the
+                                 //    selected groups left tile partials; no statistic, no exchange
     int prev_kmodD;              // history index the previous launch's ||step||^2 belongs to
     double* stat;
     uint8_t* mask;
@@ -340,6 +343,9 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
     // loads are out)
     int my_which = 0, my_tau = 0;
     if (tid < G) { my_which = a.which[tid]; my_tau = a.tau[tid]; }
+    bool pre_sel = false;                        // server-side rule: lane g of every wave holds mask[g]
+    if (a.pre && lane < G) pre_sel = a.mask[lane] != 0;
+    const unsigned long long pre_bits = __ballot(pre_sel);
     const int RB = a.RB;
     float4 agk[NCH];
 #pragma unroll
@@ -347,7 +353,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
         const int g = ch * kFinGroups + gl;
         double sq = 0;
         agk[ch] = make_float4(0, 0, 0, 0);
-        if (g < G && jok) {
+        if (g < G && jok && (!a.pre || ((pre_bits >> g) & 1ull))) {
             const float* pg = a.part_g + (int64_t)g * RB * hy.p + j;
             const float* ps = a.part_s + (int64_t)g * RB * hy.p + j;
             float4 ag = make_float4(0, 0, 0, 0), as = ag;
@@ -396,7 +402,8 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
     if (tid < G) { s_which[tid] = my_which; s_tau[tid] = my_tau; }
     for (int g = tid + B; g < G; g += B) { s_which[g] = a.which[g]; s_tau[g] = a.tau[g]; }
     __syncthreads();
-    for (int g = tid; g < G; g += B) tagged_store(a.xstat + 2 * ((int64_t)g * S + blk), s_ps[g], a.tag);
+    if (!a.pre)
+        for (int g = tid; g < G; g += B) tagged_store(a.xstat + 2 * ((int64_t)g * S + blk), s_ps[g], a.tag);
 
     // 2. While the partials travel: everything else this block needs.  The update (a3, a4) of
     //    its 4*CL columns is done by the first 4*CL threads, one column each (a short instruction
@@ -436,7 +443,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
         const int g = ch * kFinGroups + gl;
         h0k[ch] = h1k[ch] = make_float4(0, 0, 0, 0);
         wlk[ch] = 0;
-        if (g < G && jok) {
+        if (g < G && jok && (!a.pre || ((pre_bits >> g) & 1ull))) {
             wlk[ch] = s_which[g];      // read before this block published: block 0 may flip it now
             h0k[ch] = *(const float4*)(a.gbuf + (int64_t)g * hy.pstride + j);
             h1k[ch] = *(const float4*)(a.gbuf + ((int64_t)G + g) * hy.pstride + j);
@@ -447,7 +454,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
     // is the wait); every block adds the same numbers in the same order and so reaches the same
     // statistics and mask
     bool first = true;
-    for (int g0 = wave; g0 < G; g0 += 4 * NW) {
+    for (int g0 = wave; g0 < (a.pre ? 0 : G); g0 += 4 * NW) {
         double v[4] = {0, 0, 0, 0};
         bool got[4];
 #pragma unroll
@@ -513,7 +520,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
         const int g = ch * kFinGroups + gl;
-        if (g < G && jok) {
+        if (g < G && jok && (!a.pre || ((pre_bits >> g) & 1ull))) {
             const float4 ag = agk[ch];
             const float4 last4 = wlk[ch] ? h1k[ch] : h0k[ch];
             *(float4*)(a.gbuf + ((int64_t)(1 - wlk[ch]) * G + g) * hy.pstride + j) = ag;
@@ -521,26 +528,41 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
         }
     }
     __syncthreads();
-    const double rhs = s_rhs;
+    const double rhs = a.pre ? 0.0 : s_rhs;
     // the decision of Eq. (9): lane g of every wave takes it for group g; the ballot is the mask
     bool sel = false;
-    if (lane < G) sel = (s_stat[lane] > rhs) || (s_tau[lane] >= hy.D) || (rhs == 0.0);
-    const unsigned long long selbits = __ballot(sel);
+    if (lane < G && !a.pre) sel = (s_stat[lane] > rhs) || (s_tau[lane] >= hy.D) || (rhs == 0.0);
+    const unsigned long long selbits = a.pre ? pre_bits : __ballot(sel);
+    if (a.pre) sel = pre_sel;
     if (pub && wave == 0) {
         // every block copied the ages and the halves to its LDS before it published its partials
+        // (server-side rule: no block waits for another, so they are updated by the block that
+        // finishes last, below)
         if (lane < G) {
             const int t = s_tau[lane];
-            a.stat[lane] = s_stat[lane];
-            a.mask[lane] = sel ? 1 : 0;
-            if (a.mask_out) a.mask_out[lane] = sel ? 1 : 0;
-            a.tau[lane] = sel ? 1 : t + 1;
-            if (sel) a.which[lane] = 1 - s_which[lane];
+            if (!a.pre) {
+                a.stat[lane] = s_stat[lane];
+                a.mask[lane] = sel ? 1 : 0;
+                if (a.mask_out) a.mask_out[lane] = sel ? 1 : 0;
+            }
+            if (!a.pre) {
+                a.tau[lane] = sel ? 1 : t + 1;
+                if (sel) a.which[lane] = 1 - s_which[lane];
+            }
         }
         if (lane == 0) {
             double lsum = 0;
             for (int w = 0; w < NW; ++w) lsum += s_red[w];
-            const double loss = lsum / ((double)G * (double)hy.mu) + 0.5 * (double)hy.l2 * theta_sq;
-            ctl->rhs = rhs;
+            double loss;
+            if (a.pre) {
+                // mean over the samples that were evaluated (the unselected groups left zero
+                // partials), 0 when no group was selected
+                const double nsel = (double)__popcll(selbits);
+                loss = nsel > 0 ? lsum / (nsel * (double)hy.mu) + 0.5 * (double)hy.l2 * theta_sq : 0.0;
+            } else {
+                loss = lsum / ((double)G * (double)hy.mu) + 0.5 * (double)hy.l2 * theta_sq;
+                ctl->rhs = rhs;
+            }
             ctl->loss = loss;
             if (a.loss_out) *a.loss_out = (float)loss;
         }
@@ -580,9 +602,41 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
     // adds them up, so no block waits for the others here
     sq = wave_total(sq);
     tsq = wave_total(tsq);
+    unsigned done = 0;
     if (lane == 0) {
         tagged_store(a.xsq + 4 * (int64_t)blk, sq, a.tag);
         tagged_store(a.xsq + 4 * (int64_t)blk + 2, tsq, a.tag);
+        if (a.pre) done = __hip_atomic_fetch_add(&ctl->cnt_b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (!a.pre) return;
+    // server-side rule: the next kernel in the stream (the selection) reads the history, so the
+    // block that counts itself last collects the per-block sums now (lane i: block i's)
+    done = __builtin_amdgcn_readfirstlane(done);
+    if (done != (unsigned)S - 1) return;
+    double x = 0, y = 0;
+    bool gx = lane >= S, gy = gx;
+    unsigned spins = 0;
+    for (;;) {
+        if (!gx) gx = tagged_load(a.xsq + 4 * (int64_t)lane, a.tag, x);
+        if (!gy) gy = tagged_load(a.xsq + 4 * (int64_t)lane + 2, a.tag, y);
+        if (__all(gx && gy)) break;
+        if (++spins > kFinPollLimit) {
+            if (lane == 0)
+                __hip_atomic_fetch_or(&ctl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+        }
+    }
+    x = wave_total(x);
+    y = wave_total(y);
+    if (lane < G) {
+        // every block has read the ages and the halves by now
+        a.tau[lane] = pre_sel ? 1 : s_tau[lane] + 1;
+        if (pre_sel) a.which[lane] = 1 - s_which[lane];
+    }
+    if (lane == 0) {
+        a.nring[hy.kmodD] = x;
+        ctl->theta_sq = y;
+        __hip_atomic_store(&ctl->cnt_b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -711,15 +765,16 @@ hipError_t lr_tile_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
     return hipGetLastError();
 }
 
-// The fused finish serves the default rule (the mask comes from the gradients of this step).
+// Both rules: the default one (the mask comes from the gradients of this step) and the
+// server-side one (the mask is an input).
 bool lr_tile_finish_applies(const gcada_ctx* c)
 {
-    return c->allow_fused_finish && lr_tile_applies(c) && c->lr_tiles->fin_CL != 0 && c->hy.sel == nullptr;
+    return c->allow_fused_finish && lr_tile_applies(c) && c->lr_tiles->fin_CL != 0;
 }
 
 // Tile reduce + selection + masked innovation sum + server update in one launch; replaces
 // lr_tile_reduce and server_step after lr_tile_gradients.
-hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s)
+hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool preselected, hipStream_t s)
 {
     LrTilePlan* pl = c->lr_tiles;
     FinishArgs a{};
@@ -732,10 +787,12 @@ hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipS
     a.xsq_prev = sums + (size_t)((n & 1u) ^ 1u) * 4 * pl->fin_S;   // is read while this one is written
     // tags 1 .. 2^32-1 in turn: a slot only ever holds the tag of an earlier launch
     a.tag = n % 0xffffffffu + 1u;
+    a.pre = preselected ? 1 : 0;
+    if (preselected && pl->fin_pending) return hipErrorInvalidValue;   // the caller completes the history first
     a.fold_prev = pl->fin_pending ? 1 : 0;
     a.tag_prev = pl->fin_pending_tag;
     a.prev_kmodD = pl->fin_pending_kmodD;
-    pl->fin_pending = true;
+    pl->fin_pending = !preselected;          // the server-side variant closes its history entry itself
     pl->fin_pending_kmodD = c->hy.kmodD;
     pl->fin_pending_tag = a.tag;
     pl->fin_stream = s;

@@ -34,32 +34,9 @@ __device__ __forceinline__ double block_sum(double a, double* s_tmp)
     return t;
 }
 
-// Partial squared distances of theta^k to the D older iterates of the ring.
-// grid: (nb, D); out[t][b] = sum over the block's slab of (theta^k - theta^{k-1-t})^2.
-__global__ __launch_bounds__(kBlock) void rule_dist_kernel(Hyper hy, const float* __restrict__ ring,
-                                                           double* __restrict__ out)
-{
-    __shared__ double s_tmp[kBlock / kWave];
-    const int t = blockIdx.y + 1;                               // age
-    int slot = hy.cur - t;
-    if (slot < 0) slot += hy.D + 1;
-    const float* a = ring + (int64_t)hy.cur * hy.pstride;
-    const float* b = ring + (int64_t)slot * hy.pstride;
-    double acc = 0;
-    for (int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4; j < hy.pstride;
-         j += (int64_t)gridDim.x * kBlock * 4) {
-        const float4 x = *(const float4*)(a + j), y = *(const float4*)(b + j);
-        const double d0 = (double)x.x - (double)y.x, d1 = (double)x.y - (double)y.y;
-        const double d2 = (double)x.z - (double)y.z, d3 = (double)x.w - (double)y.w;
-        acc += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
-    }
-    const double tot = block_sum(acc, s_tmp);
-    if (threadIdx.x == 0) out[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = tot;
-}
-
 // One block: distances, threshold, left sides, mask.  stat <- the left sides.
-__global__ __launch_bounds__(kBlock) void rule_select_kernel(
-    Hyper hy, const double* __restrict__ part_dist, int nb, const double* __restrict__ L,
+__device__ __forceinline__ void rule_select_block(
+    const Hyper& hy, const double* __restrict__ part_dist, int nb, const double* __restrict__ L,
     const double* __restrict__ nring, const int32_t* __restrict__ tau, double* __restrict__ stat,
     uint8_t* __restrict__ mask, Ctl* __restrict__ ctl, uint8_t* __restrict__ mask_out)
 {
@@ -89,6 +66,43 @@ __global__ __launch_bounds__(kBlock) void rule_select_kernel(
         if (mask_out) mask_out[g] = sel ? 1 : 0;
     }
     if (threadIdx.x == 0) ctl->rhs = rhs;
+}
+
+// Partial squared distances of theta^k to the D older iterates of the ring, and -- by the block
+// that finishes last -- the selection.
+// grid: (nb, D); part[t][b] = sum over the block's slab of (theta^k - theta^{k-1-t})^2.
+__global__ __launch_bounds__(kBlock) void rule_dist_select_kernel(
+    Hyper hy, const float* __restrict__ ring, double* __restrict__ part, const double* __restrict__ L,
+    const double* __restrict__ nring, const int32_t* __restrict__ tau, double* __restrict__ stat,
+    uint8_t* __restrict__ mask, Ctl* __restrict__ ctl, uint8_t* __restrict__ mask_out)
+{
+    __shared__ double s_tmp[kBlock / kWave];
+    __shared__ bool s_last;
+    const int t = blockIdx.y + 1;                               // age
+    int slot = hy.cur - t;
+    if (slot < 0) slot += hy.D + 1;
+    const float* a = ring + (int64_t)hy.cur * hy.pstride;
+    const float* b = ring + (int64_t)slot * hy.pstride;
+    double acc = 0;
+    for (int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4; j < hy.pstride;
+         j += (int64_t)gridDim.x * kBlock * 4) {
+        const float4 x = *(const float4*)(a + j), y = *(const float4*)(b + j);
+        const double d0 = (double)x.x - (double)y.x, d1 = (double)x.y - (double)y.y;
+        const double d2 = (double)x.z - (double)y.z, d3 = (double)x.w - (double)y.w;
+        acc += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+    }
+    const double tot = block_sum(acc, s_tmp);
+    if (threadIdx.x == 0) {
+        part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = tot;
+        __threadfence();                                        // publish the partial device-wide
+        const unsigned total = gridDim.x * gridDim.y;
+        s_last = atomicAdd(&ctl->cnt_a, 1u) == total - 1;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();                                            // see every block's partial
+    rule_select_block(hy, part, (int)gridDim.x, L, nring, tau, stat, mask, ctl, mask_out);
+    if (threadIdx.x == 0) ctl->cnt_a = 0;
 }
 
 // One block, after the gradient stage: mean loss over the samples that were evaluated (the
@@ -206,9 +220,8 @@ hipError_t pick_fastest_workers(gcada_ctx* c, const int32_t* idx_workers, const 
 hipError_t rule_select(gcada_ctx* c, uint8_t* mask_out, hipStream_t s)
 {
     const int nb = c->rule_nb;
-    rule_dist_kernel<<<dim3(nb, c->hy.D), kBlock, 0, s>>>(c->hy, c->ring, c->rule_part);
-    rule_select_kernel<<<1, kBlock, 0, s>>>(c->hy, c->rule_part, nb, c->rule_L, c->nring, c->tau, c->stat,
-                                            c->mask, c->ctl, mask_out);
+    rule_dist_select_kernel<<<dim3(nb, c->hy.D), kBlock, 0, s>>>(c->hy, c->ring, c->rule_part, c->rule_L, c->nring,
+                                                                 c->tau, c->stat, c->mask, c->ctl, mask_out);
     return hipGetLastError();
 }
 

@@ -90,6 +90,33 @@ def test_server_rule_bf16_mlp(par):
     _say(worst)
 
 
+def test_switching_rules_on_the_tile_path(par):
+    # whole-row tile path: both rules end in the same fused finish kernel (the server-side rule with
+    # the mask as an input), so with c = 0 a run that alternates the rules equals one that never
+    # switches, bit for bit; the history entry left per block by a default-rule step is completed
+    # before the selection kernel of the next server-rule step reads it
+    from paper_2201_04301_amd import Gcada
+    w = scaled(CONFIGS["lr_small"], name="switch_tiles", widths=(1024,), mu=128, G=5, rows=300, c=0.0, D=4,
+               l2=1e-4)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 14
+    idx = torch.as_tensor(make_indices(w, steps), device="cuda")
+    res = []
+    for alternate in (False, True):
+        gpu = Gcada.from_workload(w)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        for k in range(steps):
+            if alternate:
+                gpu.set_rule("server" if (k // 2) % 2 else "gradient_difference", np.ones(w.G))
+            gpu.step(idx[k].contiguous())
+        res.append(gpu.get_state())
+        gpu.close()
+    for name in ("theta", "h", "vhat", "agg", "last", "tau"):
+        np.testing.assert_array_equal(res[0][name], res[1][name], err_msg=name)
+    np.testing.assert_allclose(res[0]["dtheta_sq"], res[1]["dtheta_sq"], rtol=1e-12)
+
+
 def test_switching_rules_between_steps(par):
     # c = 0 selects everybody under either rule: the iterates of a run that alternates the rules
     # equal those of a run that never switches -- bit for bit when both rules go through the same

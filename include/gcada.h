@@ -146,7 +146,8 @@ typedef struct gcada_state_view {
                                 (which[g]*G + g) holds the gradient group g uploaded last; a step
                                 writes group g's fresh gradient to the other half's row g and an
                                 upload flips which[g].  So after a step the fresh gradient of g is
-                                row which[g] if mask[g], else the other half's row              */
+                                row which[g] if mask[g], else the other half's row (that row is
+                                unspecified under GCADA_OPT_LAZY_GRADIENT_STORE)                */
     int32_t* which;          /* [device] G, each 0 or 1                                        */
     int32_t* tau;            /* [device] G ages                                               */
     double*  dtheta_sq;      /* [device] D: ||theta^{j+1}-theta^j||^2 stored at index j mod D */
@@ -209,9 +210,18 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * cannot all run at once -- another stream holding the device -- the step is reported as failed,
  * GCADA_EDEVICE from the next gcada_get_state, instead of hanging); 0 uses the separate
  * reduce and server kernels.  Same arithmetic per element either way.
+ * GCADA_OPT_LAZY_GRADIENT_STORE [1 for an MLP whose G fresh gradients are 64 MiB or more, else 0;
+ * ignored for the linear models]: with the gradient-difference rule every group evaluates both
+ * gradients in every step, but only an uploading group's fresh gradient is ever read again (the
+ * innovation of Eq. (8a)'s aggregate).  With 1, the weight-gradient kernels write the fresh
+ * gradient only for the groups that are selected whatever the statistic says (age D reached, or
+ * an empty history), and after the selection one more launch writes it for the other selected
+ * groups, recomputed from the signals and activations still in place (same products in the same
+ * order: the same bits).  Iterates, aggregate, stored gradients, statistic and mask are
+ * identical either way; the `gbuf` row of a group that did NOT upload is then unspecified.
  * Errors: GCADA_EINVAL (unknown option).
  */
-enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1, GCADA_OPT_FUSED_FINISH = 2 };
+enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1, GCADA_OPT_FUSED_FINISH = 2, GCADA_OPT_LAZY_GRADIENT_STORE = 3 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*

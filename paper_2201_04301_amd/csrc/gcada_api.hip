@@ -71,7 +71,7 @@ void free_all(gcada_ctx* c)
     gcada::rule_free(c);
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->gbuf, c->which, c->tau,
                     c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat, c->stat_sum,
-                    c->part_sq};
+                    c->part_sq, c->store_now, c->redo};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -152,6 +152,10 @@ try {
     if ((e = dalloc(&x->stat, (size_t)G)) != hipSuccess) return bail(e, "alloc stat");
     if ((e = dalloc(&x->mask, (size_t)G)) != hipSuccess) return bail(e, "alloc mask");
     if ((e = dalloc(&x->stat_sum, (size_t)G)) != hipSuccess) return bail(e, "alloc stat sums");
+    if ((e = dalloc(&x->store_now, (size_t)G)) != hipSuccess) return bail(e, "alloc store flags");
+    if ((e = dalloc(&x->redo, (size_t)G)) != hipSuccess) return bail(e, "alloc store flags");
+    // an MLP whose fresh gradients (G rows of p floats per step) are a large write stores them lazily
+    x->lazy_store = dims->model == GCADA_MLP && Gp * sizeof(float) >= ((size_t)64 << 20);
     if ((e = dalloc(&x->ctl, 1)) != hipSuccess) return bail(e, "alloc control block");
 
     e = dims->model != GCADA_MLP ? gcada::lr_plan(x) : gcada::mlp_plan(x);
@@ -296,12 +300,22 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     } else {
         ctx->hy.sel = nullptr;
     }
+    // lazy gradient store: the gradient stage writes the fresh gradients of the groups that are
+    // selected whatever the statistic says; the selection then names the others to be written
+    const bool lazy = ctx->dims.model == GCADA_MLP && ctx->lazy_store && !server_rule;
+    if (lazy && (e = gcada::lazy_flags(ctx, s)) != hipSuccess) return fail_hip(ctx, e, "store flag kernel");
     e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, idx, s) : gcada::mlp_gradients(ctx, idx, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
     if (server_rule && !ctx->lr_fused_finish && (e = gcada::rule_loss(ctx, loss_out, s)) != hipSuccess)
         return fail_hip(ctx, e, "loss kernel");
+    if (lazy) {
+        if ((e = gcada::server_select(ctx, mask_out, loss_out, s)) != hipSuccess)
+            return fail_hip(ctx, e, "selection kernels");
+        if ((e = gcada::mlp_store_selected(ctx, s)) != hipSuccess)
+            return fail_hip(ctx, e, "gradient store kernels");
+    }
     e = ctx->lr_fused_finish ? gcada::lr_tile_finish(ctx, mask_out, loss_out, server_rule, s)
-                             : gcada::server_step(ctx, mask_out, loss_out, server_rule, s);
+                             : gcada::server_step(ctx, mask_out, loss_out, server_rule || lazy, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "server kernels");
     if (ctx->dims.model == GCADA_MLP) {
         // compute copies (padded, transposed, bf16) of the new iterate's hidden-layer weights
@@ -440,6 +454,10 @@ int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
         ctx->allow_fused_finish = value != 0;
         return GCADA_OK;
     }
+    if (option == GCADA_OPT_LAZY_GRADIENT_STORE) {
+        ctx->lazy_store = value != 0 && ctx->dims.model == GCADA_MLP;
+        return GCADA_OK;
+    }
     return fail(ctx, GCADA_EINVAL, "set_option: unknown option");
 }
 
@@ -509,7 +527,10 @@ try {
     HIP_TRY(ctx, hipEventCreate(&e0));
     HIP_TRY(ctx, hipEventCreate(&e1));
     ctx->dominant_only = true;
-    hipError_t e = hipEventRecord(e0, s);
+    hipError_t e = hipSuccess;
+    if (ctx->dims.model == GCADA_MLP && ctx->lazy_store && ctx->rule != GCADA_RULE_SERVER)
+        e = gcada::lazy_flags(ctx, s);       // the stage stores what a step at this state would
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
     for (int r = 0; r < reps && e == hipSuccess; ++r)
     {
         const int32_t* ir = idx ? idx + (int64_t)r * idx_stride : nullptr;

@@ -132,6 +132,11 @@ struct gcada_ctx {
     int32_t rule_nb = 0;
     bool rule_L_set = false;
     int32_t* idx_eff = nullptr;    // G x mu: minibatch ids of the groups' fastest workers
+    // lazy gradient store (MLP): the gradient stage writes only the fresh gradients of store_now,
+    // a second launch those of redo (selected by the statistic afterwards)
+    bool lazy_store = false;
+    uint8_t* store_now = nullptr;  // G
+    uint8_t* redo = nullptr;       // G
     bool allow_single_pass = true;
     bool allow_fused_finish = true;
     bool lr_fused_finish = false;  // this step: lr_tile_finish replaces lr_tile_reduce + server_step
@@ -187,6 +192,9 @@ hipError_t select_plan(gcada_ctx* c);
 // Ctl::k and the ages; writes mask_out / loss_out
 // preselected: the mask (and rhs, loss) were already decided by the server-side rule
 hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool preselected, hipStream_t s);
+hipError_t server_select(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s);
+hipError_t lazy_flags(gcada_ctx* c, hipStream_t s);
+hipError_t mlp_store_selected(gcada_ctx* c, hipStream_t s);
 
 // server-side rule of Sec. IV (rule_kernels.hip)
 hipError_t rule_plan(gcada_ctx* c);

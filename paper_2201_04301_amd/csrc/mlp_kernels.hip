@@ -82,9 +82,10 @@ struct Layout {
 // (BM/WM) x (BN/WN) as TM x TN blocks of 32 x 32.  A row of a tile in LDS is KROW bytes of k plus
 // 16 bytes of padding.  Two LDS stages; PF = k-tiles in flight in registers ahead of the one
 // being multiplied (1 or 2).
-template <int BM_, int BN_, int KROW_, int WM_ = 2, int WN_ = 2, int PF_ = 1>
+template <int BM_, int BN_, int KROW_, int WM_ = 2, int WN_ = 2, int PF_ = 1, int WPE_ = 1>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, KROW = KROW_, WM = WM_, WN = WN_, PF = PF_;
+    static constexpr int WPE = WPE_;                         // waves per SIMD the kernel must leave room for
     static constexpr int NW = WM * WN, NT = NW * 64;          // waves, threads
     static constexpr int PITCH = KROW + 16;
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -138,6 +139,9 @@ struct GemmArgs {
     int G;
     // HEAD
     const ShardDesc* shards; const int32_t* idx; double* part_loss;
+    // DW: when given, the fresh gradient block of group g is written only if store_now[g] != 0
+    // (the statistic is computed either way)
+    const uint8_t* store_now;
 };
 
 template <typename T>
@@ -387,7 +391,7 @@ __device__ __forceinline__ void gemm_mainloop_two_passes(
     // first pass; its last turn already requests the first tiles of the second
     for (int kt = 0; kt < nk; kt += 2)
         two_passes_turn<T, TL>(Pg, Qg, poff, ldq_b, dP, dQ, nk, kt, last, lds, rp0, rq0, rp1, rq1, acc);
-    dw_store_fresh<TL>(a, g, m0, n0, acc);
+    if (!a.store_now || a.store_now[g]) dw_store_fresh<TL>(a, g, m0, n0, acc);
     for (int kt = nk; kt < total; kt += 2)
         two_passes_turn<T, TL>(Pg, Qg, poff, ldq_b, dP, dQ, nk, kt, last, lds, rp0, rq0, rp1, rq1, acc);
 }
@@ -440,7 +444,7 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs& a, int it, int g, int 
 
 // grid: (ceil(N/BN), ceil(M/BM), batch);  batch = 2G (it*G + g) for FWD / DA / HEAD, G for DW.
 template <typename T, int EPI, typename TL>
-__global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
+__global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
 {
     extern __shared__ __align__(16) char lds[];
     constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN;
@@ -507,7 +511,7 @@ __global__ __launch_bounds__(TL::NT) void mlp_gemm(GemmArgs a)
         if (((a.K + kTileK - 1) / kTileK) % 2 != 0) {
             // odd number of k-tiles per pass: two pipelines
             gemm_pass<T, TL>(a, 0, g, m0, n0, lds, acc);
-            dw_store_fresh<TL>(a, g, m0, n0, acc);
+            if (!a.store_now || a.store_now[g]) dw_store_fresh<TL>(a, g, m0, n0, acc);
             gemm_pass<T, TL>(a, 1, g, m0, n0, lds, acc);
         } else {
             // both passes in one pipeline; the fresh block is stored between them
@@ -1161,6 +1165,29 @@ hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s)
     return hipSuccess;
 }
 
+// Weight-gradient GEMM of layer l.  hy.sel == nullptr: both iterates, the statistic, and the
+// fresh block of the groups with store_now[g] (all groups when store_now is null).  hy.sel given:
+// the gradient at theta^k of the groups with sel[g], stored; nothing else.
+template <typename T>
+static hipError_t launch_dw(gcada_ctx* c, int l, const Hyper& hy, const uint8_t* store_now, hipStream_t s)
+{
+    MlpWork* w = c->mlp;
+    const Layout& lay = w->lay;
+    const int G = hy.G;
+    GemmArgs a{};
+    a.hy = hy; a.tau = c->tau; a.G = G;
+    a.M = lay.n[l]; a.N = lay.n[l - 1]; a.K = hy.mu;
+    a.P = w->dZT[l]; a.p_it = (int64_t)G * lay.n[l] * lay.ldmu; a.p_g = (int64_t)lay.n[l] * lay.ldmu;
+    a.ldp = lay.ldmu;
+    if (l == 1) { a.Q = w->XgT; a.q_it = 0; a.q_g = (int64_t)lay.n[0] * lay.ldmu; }
+    else { a.Q = w->AT[l - 1]; a.q_it = (int64_t)G * lay.n[l - 1] * lay.ldmu; a.q_g = (int64_t)lay.n[l - 1] * lay.ldmu; }
+    a.ldq = lay.ldmu; a.q_is_weight = 0;
+    a.gbuf = c->gbuf; a.which = c->which; a.goff = lay.woff[l];
+    a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[l];
+    a.store_now = store_now;
+    return launch_gemm<T, EPI_DW>(a, G, w->small, s);
+}
+
 template <typename T>
 static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t s)
 {
@@ -1214,18 +1241,9 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     }
     // 3. backward, layer by layer
     for (int l = L; l >= 1; --l) {
-        {   // weight gradient of layer l, both iterates in one workgroup
-            GemmArgs a{};
-            a.hy = hy; a.tau = c->tau; a.G = G;
-            a.M = lay.n[l]; a.N = lay.n[l - 1]; a.K = mu;
-            a.P = w->dZT[l]; a.p_it = tr_it(l); a.p_g = tr_g(l); a.ldp = lay.ldmu;
-            if (l == 1) { a.Q = w->XgT; a.q_it = 0; a.q_g = tr_g(0); }
-            else { a.Q = w->AT[l - 1]; a.q_it = tr_it(l - 1); a.q_g = tr_g(l - 1); }
-            a.ldq = lay.ldmu; a.q_is_weight = 0;
-            a.gbuf = c->gbuf; a.which = c->which; a.goff = lay.woff[l];
-            a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[l];
-            if ((e = launch_gemm<T, EPI_DW>(a, G, w->small, s)) != hipSuccess) return e;
-        }
+        // weight gradient of layer l, both iterates in one workgroup
+        if ((e = launch_dw<T>(c, l, hy, c->lazy_store && !hy.sel ? c->store_now : nullptr, s)) != hipSuccess)
+            return e;
         {
             dim3 grid((lay.n[l] + 7) / 8, G);
             mlp_bias_grad<T><<<grid, 256, 0, s>>>(hy, lay.n[l], lay.ldmu, (const T*)w->dZT[l], tr_it(l),
@@ -1252,6 +1270,21 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
 hipError_t mlp_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
 {
     return c->mlp->bf16 ? mlp_gradients_t<bf16_t>(c, idx, s) : mlp_gradients_t<float>(c, idx, s);
+}
+
+// Second half of the lazy gradient store: the weight gradients at theta^k of the groups in
+// c->redo (selected, but not written by the gradient stage) are recomputed from the signals and
+// activations the stage left behind -- the same k-tiles in the same order, so the same bits --
+// and written to their fresh rows.
+hipError_t mlp_store_selected(gcada_ctx* c, hipStream_t s)
+{
+    Hyper hy = c->hy;
+    hy.sel = c->redo;
+    for (int l = c->mlp->lay.L; l >= 1; --l) {
+        hipError_t e = c->mlp->bf16 ? launch_dw<bf16_t>(c, l, hy, nullptr, s) : launch_dw<float>(c, l, hy, nullptr, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace gcada

@@ -41,7 +41,9 @@ constexpr int kSelBlock = 256;
 __device__ __forceinline__ void select_groups_block(const Hyper& hy, const double* __restrict__ part_stat,
                                                     int n_stat, const int32_t* __restrict__ tau,
                                                     double rhs, uint8_t* s_mask, double* stat_out,
-                                                    uint8_t* mask_a, uint8_t* mask_b, int nwaves)
+                                                    uint8_t* mask_a, uint8_t* mask_b, int nwaves,
+                                                    const uint8_t* __restrict__ stored = nullptr,
+                                                    uint8_t* __restrict__ redo = nullptr)
 {
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     for (int g = wave; g < hy.G; g += nwaves) {
@@ -55,6 +57,7 @@ __device__ __forceinline__ void select_groups_block(const Hyper& hy, const doubl
             if (stat_out) stat_out[g] = a;
             if (mask_a) mask_a[g] = sel ? 1 : 0;
             if (mask_b) mask_b[g] = sel ? 1 : 0;
+            if (redo) redo[g] = sel && !stored[g] ? 1 : 0;
         }
     }
 }
@@ -86,7 +89,8 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
     Hyper hy, const double* __restrict__ part_stat, int n_stat, const double* __restrict__ part_loss,
     int n_loss_total, const double* __restrict__ nring, const int32_t* __restrict__ tau,
     double* __restrict__ stat, uint8_t* __restrict__ mask, Ctl* __restrict__ ctl,
-    uint8_t* __restrict__ mask_out, float* __restrict__ loss_out)
+    uint8_t* __restrict__ mask_out, float* __restrict__ loss_out,
+    const uint8_t* __restrict__ stored, uint8_t* __restrict__ redo)
 {
     __shared__ double s_tmp[kSelBlock / kWave];
     __shared__ double s_rhs;
@@ -106,7 +110,20 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
         if (loss_out) *loss_out = (float)loss;
     }
     select_groups_block(hy, part_stat, n_stat, tau, rhs, s_mask, stat, mask, mask_out,
-                        kSelBlock / kWave);
+                        kSelBlock / kWave, stored, redo);
+}
+
+// Lazy gradient store: before the gradient kernels run, the groups whose selection does not
+// depend on the statistic are known -- age D reached, or an all-zero history (threshold 0, every
+// group is selected).  Only those write their fresh gradient during the gradient stage; a group
+// that the statistic selects afterwards has its gradient written by a second, short launch.
+// One wave.
+__global__ __launch_bounds__(kWave) void lazy_flags_kernel(Hyper hy, const double* __restrict__ nring,
+                                                          const int32_t* __restrict__ tau,
+                                                          uint8_t* __restrict__ store_now)
+{
+    const double rhs = history_threshold(hy, nring);
+    for (int g = threadIdx.x; g < hy.G; g += kWave) store_now[g] = (tau[g] >= hy.D) || (rhs == 0.0) ? 1 : 0;
 }
 
 constexpr int kUpdBlock = 1024;
@@ -452,12 +469,36 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool pr
     if (!self_select && !preselected)
         select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(
             c->hy, a.part_stat, a.n_stat, c->part_loss, c->n_loss_used, c->nring, c->tau,
-            c->stat, c->mask, c->ctl, mask_out, loss_out);
+            c->stat, c->mask, c->ctl, mask_out, loss_out, nullptr, nullptr);
     if (c->hy.pstride <= (int64_t)kBigBlock * 4)
         // the whole parameter vector fits one block: no cross-block hand-over at the end
         launch_server<kBigBlock, 4>(self_select, 1, lds, s, a);
     else
         launch_server<kUpdBlock, 4>(self_select, c->n_epi_blocks, lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t lazy_flags(gcada_ctx* c, hipStream_t s)
+{
+    lazy_flags_kernel<<<1, kWave, 0, s>>>(c->hy, c->nring, c->tau, c->store_now);
+    return hipGetLastError();
+}
+
+// Selection alone (statistic sums, threshold, mask, loss), for a step whose gradient stage wrote
+// only the fresh gradients of c->store_now: also marks in c->redo the selected groups whose
+// gradient is still to be written.  server_step(..., preselected = true, ...) follows.
+hipError_t server_select(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s)
+{
+    const double* part = c->part_stat;
+    int n_stat = c->n_stat_used;
+    if (n_stat > 16) {
+        stat_reduce_kernel<<<c->hy.G, kSelBlock, 0, s>>>(c->part_stat, c->n_stat_used, c->stat_sum);
+        part = c->stat_sum;
+        n_stat = 1;
+    }
+    select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(
+        c->hy, part, n_stat, c->part_loss, c->n_loss_used, c->nring, c->tau, c->stat, c->mask, c->ctl,
+        mask_out, loss_out, c->store_now, c->redo);
     return hipGetLastError();
 }
 

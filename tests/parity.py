@@ -15,6 +15,7 @@ import torch
 import oracle as O
 from gcada_inputs import Workload, gather_rows, make_indices, make_shards, make_theta0
 from paper_2201_04301_amd import Gcada
+from paper_2201_04301_amd import binding as B
 
 
 def oracle_config(w: Workload) -> O.Config:
@@ -51,7 +52,7 @@ def push_state(orc: O.Oracle, gpu: Gcada):
 
 
 def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, kink_tol=None,
-                   kink_grad_tol=5e-2, stat_vs_threshold=False, verbose=False, server_rule_L=None):
+                   kink_grad_tol=5e-2, stat_vs_threshold=False, verbose=False, server_rule_L=None, lazy_store=None):
     """Run `steps` iterations; idx: int32 (steps, G, mu) row ids or None for the cyclic window.
     kink_tol (MLP): a group is "near a ReLU kink" in a step when some hidden pre-activation of the
     oracle lies within kink_tol (relative to the sum of the magnitudes of its terms) of zero.
@@ -65,11 +66,16 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
     server_rule_L: G smoothness constants -> both sides run the server-side rule of Sec. IV
     (selection from the iterates before the gradients; only selected groups evaluate one); then
     the gradients of the selected groups only are compared, and `stat` is the rule's left side.
+    lazy_store: 0 / 1 sets GCADA_OPT_LAZY_GRADIENT_STORE; with 1 the fresh gradient of a group
+    that does not upload is not materialised, so only the uploading groups' gradients are compared
+    (the statistic, which is made of the whole gradient difference, is compared for all).
     Returns a dict of the worst errors seen.  Raises AssertionError on a violation."""
     orc = O.Oracle(oracle_config(w), make_theta0(w))
     gpu = Gcada.from_workload(w)
     gpu.set_shards(Xs, ys)
     gpu.set_theta(make_theta0(w))
+    if lazy_store is not None:
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, int(lazy_store))
     if server_rule_L is not None:
         orc.set_rule(1, server_rule_L)
         gpu.set_rule("server", server_rule_L)
@@ -97,6 +103,8 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
         for g in range(w.G):
             if server_rule_L is not None and not mask_o[g]:
                 continue                      # evaluated nothing on either side
+            if lazy_store and not out["mask"][g]:
+                continue                      # not materialised
             e = vec_err(out["grad"][g], orc.grad[g])
             if near[g]:
                 assert e <= kink_grad_tol, f"step {k} group {g} (near a kink): gradient error {e:.3e}"
@@ -218,7 +226,7 @@ def synthetic_state(w: Workload, seed=7):
 
 
 def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e-6, kink_tol=None,
-                        seed=7):
+                        seed=7, lazy_store=None):
     """One iteration of the full-size workload on the GPU from a synthetic state; the oracle
     evaluates only the sampled `groups` (each group's gradients, statistic and mask depend on its
     own shard and state only) and those outputs are compared."""
@@ -227,6 +235,8 @@ def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e
     gpu.set_shards(Xs, ys)
     gpu.set_theta(make_theta0(w))
     gpu.set_state(**st)
+    if lazy_store is not None:
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, int(lazy_store))
     ws = replace_groups(w, len(groups))
     orc = O.Oracle(oracle_config(ws), make_theta0(w))
     for name in ("theta", "h", "vhat", "agg"):
@@ -244,7 +254,8 @@ def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e
     assert worst["rhs"] <= 1e-9
     for j, g in enumerate(groups):
         near = kink_tol is not None and orc.kink[j] < kink_tol
-        e = vec_err(out["grad"][g], orc.grad[j])
+        materialised = not lazy_store or bool(out["mask"][g])
+        e = vec_err(out["grad"][g], orc.grad[j]) if materialised else 0.0
         if near:
             worst["kink_groups"] += 1
             assert e <= 5e-2, f"group {g} (near a kink): gradient error {e:.3e}"

@@ -76,15 +76,80 @@ def test_mlp_bf16_shapes(par, widths, mu, G, rows, steps, tol):
     _say(worst)
 
 
-def test_mlp_3072_bf16_full_size_sampled_groups(par):
+@pytest.mark.parametrize("lazy", [1, 0])
+def test_mlp_3072_bf16_full_size_sampled_groups(par, lazy):
     # configuration 5 at full size (G=64, mu=256, 781 rows per shard): one iteration from a seeded
-    # synthetic state, three sampled groups checked against the oracle
+    # synthetic state, three sampled groups checked against the oracle.  lazy = 1 is the library's
+    # default at this size (fresh gradients of non-uploading groups are not written)
     w = CONFIGS["mlp_3072_bf16"]
-    _say("case", w)
+    _say("case", w, "lazy", lazy)
     Xs, ys = make_shards(w, "cuda")
     idx = make_indices(w, 1)
-    worst = par.sampled_groups_step(w, Xs, ys, idx[0], groups=[0, 17, 63], tol=2e-2, edge=2e-2)
+    worst = par.sampled_groups_step(w, Xs, ys, idx[0], groups=[0, 17, 63], tol=2e-2, edge=2e-2,
+                                    lazy_store=lazy)
     _say(worst)
+
+
+@pytest.mark.parametrize("widths,mu,G,rows,steps,dtype_cfg,tol", [
+    ((100, 70, 50, 7), 40, 5, 90, 14, "mlp_784", 1e-5),          # fp32, two k-tiles per pass
+    ((20, 12, 5), 16, 3, 50, 15, "mlp_784", 1e-5),               # fp32, one k-tile per pass (two pipelines)
+    ((200, 150, 10), 256, 3, 300, 8, "mlp_3072_bf16", 2e-2),     # bf16
+])
+def test_mlp_lazy_gradient_store_parity(par, widths, mu, G, rows, steps, dtype_cfg, tol):
+    # teacher-forced parity with the lazy store switched on: statistic of every group, gradients
+    # of the uploading groups, and the whole state after every step
+    w = scaled(CONFIGS[dtype_cfg], name="mlp_lazy", widths=widths, mu=mu, G=G, rows=rows, D=4)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, steps)
+    bf = dtype_cfg == "mlp_3072_bf16"
+    worst = par.teacher_forced(w, steps, Xs, ys, idx, tol=tol, edge=tol if bf else 1e-6,
+                               kink_tol=None if bf else KINK, stat_vs_threshold=bf, lazy_store=1)
+    _say(worst)
+    assert worst["selected"] > 0 and worst["state_steps"] > 0.4 * steps
+
+
+@pytest.mark.parametrize("widths,mu,G,rows,dtype_cfg", [
+    ((100, 70, 50, 7), 40, 6, 90, "mlp_784"),
+    ((20, 12, 5), 16, 4, 50, "mlp_784"),
+    ((300, 260, 10), 128, 5, 200, "mlp_3072_bf16"),
+])
+def test_mlp_lazy_gradient_store_changes_nothing(widths, mu, G, rows, dtype_cfg):
+    # free run, lazy store off and on: masks, statistics, losses and the complete state are
+    # bit-identical (the second launch recomputes a selected group's gradient from the same
+    # products in the same order); both kinds of selection occur
+    from paper_2201_04301_amd import Gcada, binding as B
+    from gcada_inputs import make_theta0
+    w = scaled(CONFIGS[dtype_cfg], name="mlp_lazy", widths=widths, mu=mu, G=G, rows=rows, D=4, c=0.6)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 40
+    idx = torch.as_tensor(make_indices(w, steps), device="cuda")
+    runs = []
+    for lazy in (0, 1):
+        gpu = Gcada.from_workload(w)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, lazy)
+        masks, stats, losses, taus = [], [], [], []
+        for k in range(steps):
+            taus.append(gpu.get_state()["tau"].copy())
+            gpu.step(idx[k].contiguous())
+            out = gpu.outputs()
+            masks.append(out["mask"].copy()); stats.append(out["stat"].copy()); losses.append(out["loss"])
+        runs.append(dict(masks=np.array(masks), stats=np.array(stats), losses=np.array(losses),
+                         taus=np.array(taus), state=gpu.get_state()))
+        gpu.close()
+    a, b = runs
+    np.testing.assert_array_equal(a["masks"], b["masks"])
+    np.testing.assert_array_equal(a["stats"], b["stats"])
+    np.testing.assert_array_equal(a["losses"], b["losses"])
+    for name in ("theta", "h", "vhat", "agg", "last", "theta_stale", "tau", "dtheta_sq"):
+        np.testing.assert_array_equal(a["state"][name], b["state"][name], err_msg=name)
+    sel = a["masks"][1:] != 0
+    forced = a["taus"][1:] >= w.D
+    _say("selected", int(sel.sum()), "of them by age", int((sel & forced).sum()),
+         "by the statistic", int((sel & ~forced).sum()), "skipped", int((~sel).sum()))
+    assert (sel & forced).any() and (sel & ~forced).any() and (~sel).any()
 
 
 def test_mlp_free_run_loss_decreases_and_tracks_oracle(par):

@@ -833,7 +833,7 @@ template <> struct TileOf<float, EPI_HEAD, true> { using type = Tile<64, 128, 12
 template <bool SMALL> struct TileOf<bf16_t, EPI_FWD, SMALL> { using type = Tile<256, 256, 128, 4, 2, 2>; };
 template <bool SMALL> struct TileOf<bf16_t, EPI_DA, SMALL> { using type = Tile<256, 256, 128, 4, 2, 2>; };
 template <bool SMALL> struct TileOf<bf16_t, EPI_DW, SMALL> { using type = Tile<256, 256, 64, 4, 2, 2>; };
-template <bool SMALL> struct TileOf<bf16_t, EPI_HEAD, SMALL> { using type = Tile<128, 128, 64>; };
+template <bool SMALL> struct TileOf<bf16_t, EPI_HEAD, SMALL> { using type = Tile<64, 128, 128, 2, 2, 2>; };
 
 template <typename T, int EPI, bool SMALL>
 static hipError_t launch_gemm_t(const GemmArgs& a, int batch, hipStream_t s)
@@ -974,7 +974,48 @@ __global__ __launch_bounds__(256) void mlp_weight_copy(const float* __restrict__
     __syncthreads();
     for (int c = ty; c < 64; c += 4) {
         const int i = i0 + c, o = o0 + tx;
-        if (i < n_in && o < n_out) WcT[(int64_t)i * ld_out + o] = tile[tx][c];
+        if (WcT && i < n_in && o < n_out) WcT[(int64_t)i * ld_out + o] = tile[tx][c];
+    }
+}
+
+// The same with 16-byte loads and 8/16-byte stores, for layers whose input width is a multiple
+// of 4 and whose weights start 16-byte aligned in the parameter vector.  WcT may be null (the
+// first layer's transpose is never used: no signal is propagated to the input).
+// grid: (ceil(n_in/64), ceil(n_out/64)), block 256.
+template <typename T>
+__global__ __launch_bounds__(256) void mlp_weight_copy_vec(const float* __restrict__ W, int n_out, int n_in,
+                                                           int ld_in, int ld_out, T* __restrict__ Wc,
+                                                           T* __restrict__ WcT)
+{
+    constexpr int V = 16 / (int)sizeof(T), PITCH = 64 + 8;
+    __shared__ __align__(16) T tileT[64][PITCH];
+    const int i0 = blockIdx.x * 64, o0 = blockIdx.y * 64;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        const int t = threadIdx.x + 256 * h, r = t / 16, cv = (t % 16) * 4;
+        const int o = o0 + r, i = i0 + cv;
+        alignas(16) T v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = to_T<T>(0.0f);
+        if (o < n_out && i < n_in) {
+            const float4 w4 = *(const float4*)(W + (int64_t)o * n_in + i);
+            v[0] = to_T<T>(w4.x); v[1] = to_T<T>(w4.y); v[2] = to_T<T>(w4.z); v[3] = to_T<T>(w4.w);
+            if constexpr (sizeof(T) == 2) *(uint2*)(Wc + (int64_t)o * ld_in + i) = *(const uint2*)v;
+            else *(uint4*)(Wc + (int64_t)o * ld_in + i) = *(const uint4*)v;
+        }
+        if (WcT) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) tileT[cv + q][r] = v[q];
+        }
+    }
+    if (!WcT) return;
+    __syncthreads();
+    constexpr int NV = 64 / V;                    // 16-byte vectors per transposed row
+    for (int t = threadIdx.x; t < 64 * NV; t += 256) {
+        const int c = t / NV, rv = (t % NV) * V;
+        const int i = i0 + c, o = o0 + rv;
+        // columns past n_out up to the padded row length receive the zeros they must hold
+        if (i < n_in && o < ld_out) *(uint4*)(WcT + (int64_t)i * ld_out + o) = *(const uint4*)&tileT[c][rv];
     }
 }
 
@@ -1102,7 +1143,7 @@ hipError_t mlp_plan(gcada_ctx* c)
         w->wc_slot[l] = (int64_t)lay.n[l] * lay.ld[l - 1];
         w->wct_slot[l] = (int64_t)lay.n[l - 1] * lay.ld[l];
         if ((e = walloc(w, &w->Wc[l], (size_t)nslot * w->wc_slot[l] * es)) != hipSuccess) return e;
-        if ((e = walloc(w, &w->WcT[l], (size_t)nslot * w->wct_slot[l] * es)) != hipSuccess) return e;
+        if (l > 1 && (e = walloc(w, &w->WcT[l], (size_t)nslot * w->wct_slot[l] * es)) != hipSuccess) return e;
     }
     // small tiles when the first forward GEMM in 128 x 128 tiles cannot give every compute unit
     // two workgroups
@@ -1144,9 +1185,15 @@ static hipError_t refresh_slot_t(gcada_ctx* c, int slot, hipStream_t s)
     const float* th = c->ring + (int64_t)slot * c->hy.pstride;
     for (int l = 1; l <= lay.L; ++l) {
         dim3 grid((lay.n[l - 1] + 63) / 64, (lay.n[l] + 63) / 64);
-        mlp_weight_copy<T><<<grid, 256, 0, s>>>(th + lay.woff[l], lay.n[l], lay.n[l - 1], lay.ld[l - 1],
-                                                 lay.ld[l], (T*)w->Wc[l] + (int64_t)slot * w->wc_slot[l],
-                                                 (T*)w->WcT[l] + (int64_t)slot * w->wct_slot[l]);
+        T* wc = (T*)w->Wc[l] + (int64_t)slot * w->wc_slot[l];
+        // the transpose serves the signal of layer l-1, which the first layer does not need
+        T* wct = l > 1 ? (T*)w->WcT[l] + (int64_t)slot * w->wct_slot[l] : nullptr;
+        if (lay.n[l - 1] % 4 == 0 && lay.woff[l] % 4 == 0)
+            mlp_weight_copy_vec<T><<<grid, 256, 0, s>>>(th + lay.woff[l], lay.n[l], lay.n[l - 1], lay.ld[l - 1],
+                                                         lay.ld[l], wc, wct);
+        else
+            mlp_weight_copy<T><<<grid, 256, 0, s>>>(th + lay.woff[l], lay.n[l], lay.n[l - 1], lay.ld[l - 1],
+                                                     lay.ld[l], wc, wct);
     }
     return hipGetLastError();
 }

@@ -95,6 +95,17 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
     __shared__ double s_tmp[kSelBlock / kWave];
     __shared__ double s_rhs;
     extern __shared__ uint8_t s_mask[];
+    // one partial per group (they were added up beforehand): a thread per group, its loads
+    // issued before the threshold and the loss are formed
+    const bool direct = n_stat == 1;
+    double my_stat = 0;
+    int my_tau = 0;
+    uint8_t my_stored = 0;
+    if (direct && (int)threadIdx.x < hy.G) {
+        my_stat = part_stat[threadIdx.x];
+        my_tau = tau[threadIdx.x];
+        if (redo) my_stored = stored[threadIdx.x];
+    }
     if (threadIdx.x < kWave) {
         const double r = history_threshold(hy, nring);
         if (threadIdx.x == 0) s_rhs = r;
@@ -108,6 +119,17 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
         ctl->rhs = rhs;
         ctl->loss = loss;
         if (loss_out) *loss_out = (float)loss;
+    }
+    if (direct && hy.G <= kSelBlock) {
+        if ((int)threadIdx.x < hy.G) {
+            const int g = threadIdx.x;
+            const bool sel = (my_stat > rhs) || (my_tau >= hy.D) || (rhs == 0.0);
+            stat[g] = my_stat;
+            mask[g] = sel ? 1 : 0;
+            if (mask_out) mask_out[g] = sel ? 1 : 0;
+            if (redo) redo[g] = sel && !my_stored ? 1 : 0;
+        }
+        return;
     }
     select_groups_block(hy, part_stat, n_stat, tau, rhs, s_mask, stat, mask, mask_out,
                         kSelBlock / kWave, stored, redo);

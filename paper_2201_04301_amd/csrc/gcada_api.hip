@@ -71,7 +71,7 @@ void free_all(gcada_ctx* c)
     gcada::rule_free(c);
     void* ptrs[] = {c->d_shards, c->ring, c->h, c->vhat, c->agg, c->gbuf, c->which, c->tau,
                     c->nring, c->stat, c->mask, c->ctl, c->res, c->part_loss, c->part_stat, c->stat_sum,
-                    c->part_sq, c->store_now, c->redo};
+                    c->part_sq, c->store_now, c->redo, c->hot};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -154,6 +154,7 @@ try {
     if ((e = dalloc(&x->stat_sum, (size_t)G)) != hipSuccess) return bail(e, "alloc stat sums");
     if ((e = dalloc(&x->store_now, (size_t)G)) != hipSuccess) return bail(e, "alloc store flags");
     if ((e = dalloc(&x->redo, (size_t)G)) != hipSuccess) return bail(e, "alloc store flags");
+    if ((e = dalloc(&x->hot, (size_t)G)) != hipSuccess) return bail(e, "alloc store flags");
     // an MLP whose fresh gradients (G rows of p floats per step) are a large write stores them lazily
     x->lazy_store = dims->model == GCADA_MLP && Gp * sizeof(float) >= ((size_t)64 << 20);
     if ((e = dalloc(&x->ctl, 1)) != hipSuccess) return bail(e, "alloc control block");
@@ -244,6 +245,7 @@ static int after_state_change(gcada_ctx* ctx)
 {
     set_iteration(ctx);
     gcada::lr_tile_forget(ctx);
+    HIP_TRY(ctx, hipMemset(ctx->hot, 0, (size_t)ctx->hy.G));
     if (ctx->dims.model != GCADA_MLP) HIP_TRY(ctx, gcada::lr_team_reset(ctx));
     HIP_TRY(ctx, gcada::refresh_theta_sq(ctx, nullptr));
     if (ctx->dims.model == GCADA_MLP) HIP_TRY(ctx, gcada::mlp_refresh_weights(ctx, nullptr));

@@ -137,6 +137,7 @@ struct gcada_ctx {
     bool lazy_store = false;
     uint8_t* store_now = nullptr;  // G
     uint8_t* redo = nullptr;       // G
+    uint8_t* hot = nullptr;        // G: the statistic exceeded the threshold in the previous step
     bool allow_single_pass = true;
     bool allow_fused_finish = true;
     bool lr_fused_finish = false;  // this step: lr_tile_finish replaces lr_tile_reduce + server_step

@@ -43,7 +43,8 @@ __device__ __forceinline__ void select_groups_block(const Hyper& hy, const doubl
                                                     double rhs, uint8_t* s_mask, double* stat_out,
                                                     uint8_t* mask_a, uint8_t* mask_b, int nwaves,
                                                     const uint8_t* __restrict__ stored = nullptr,
-                                                    uint8_t* __restrict__ redo = nullptr)
+                                                    uint8_t* __restrict__ redo = nullptr,
+                                                    uint8_t* __restrict__ hot = nullptr)
 {
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     for (int g = wave; g < hy.G; g += nwaves) {
@@ -58,6 +59,7 @@ __device__ __forceinline__ void select_groups_block(const Hyper& hy, const doubl
             if (mask_a) mask_a[g] = sel ? 1 : 0;
             if (mask_b) mask_b[g] = sel ? 1 : 0;
             if (redo) redo[g] = sel && !stored[g] ? 1 : 0;
+            if (hot) hot[g] = a > rhs ? 1 : 0;
         }
     }
 }
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
     int n_loss_total, const double* __restrict__ nring, const int32_t* __restrict__ tau,
     double* __restrict__ stat, uint8_t* __restrict__ mask, Ctl* __restrict__ ctl,
     uint8_t* __restrict__ mask_out, float* __restrict__ loss_out,
-    const uint8_t* __restrict__ stored, uint8_t* __restrict__ redo)
+    const uint8_t* __restrict__ stored, uint8_t* __restrict__ redo, uint8_t* __restrict__ hot)
 {
     __shared__ double s_tmp[kSelBlock / kWave];
     __shared__ double s_rhs;
@@ -128,24 +130,29 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
             mask[g] = sel ? 1 : 0;
             if (mask_out) mask_out[g] = sel ? 1 : 0;
             if (redo) redo[g] = sel && !my_stored ? 1 : 0;
+            if (hot) hot[g] = my_stat > rhs ? 1 : 0;
         }
         return;
     }
     select_groups_block(hy, part_stat, n_stat, tau, rhs, s_mask, stat, mask, mask_out,
-                        kSelBlock / kWave, stored, redo);
+                        kSelBlock / kWave, stored, redo, hot);
 }
 
 // Lazy gradient store: before the gradient kernels run, the groups whose selection does not
 // depend on the statistic are known -- age D reached, or an all-zero history (threshold 0, every
-// group is selected).  Only those write their fresh gradient during the gradient stage; a group
-// that the statistic selects afterwards has its gradient written by a second, short launch.
-// One wave.
+// group is selected).  Those write their fresh gradient during the gradient stage, and so do the
+// groups whose statistic exceeded the threshold in the previous step (`hot`: a guess that spares
+// most recomputation while many groups still upload in every step; a wrong guess costs a store
+// or a recomputation, never a different result).  A group that is selected without having
+// written its gradient gets it from a second, short launch.  One wave.
 __global__ __launch_bounds__(kWave) void lazy_flags_kernel(Hyper hy, const double* __restrict__ nring,
                                                           const int32_t* __restrict__ tau,
+                                                          const uint8_t* __restrict__ hot,
                                                           uint8_t* __restrict__ store_now)
 {
     const double rhs = history_threshold(hy, nring);
-    for (int g = threadIdx.x; g < hy.G; g += kWave) store_now[g] = (tau[g] >= hy.D) || (rhs == 0.0) ? 1 : 0;
+    for (int g = threadIdx.x; g < hy.G; g += kWave)
+        store_now[g] = (tau[g] >= hy.D) || (rhs == 0.0) || hot[g] ? 1 : 0;
 }
 
 constexpr int kUpdBlock = 1024;
@@ -491,7 +498,7 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool pr
     if (!self_select && !preselected)
         select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(
             c->hy, a.part_stat, a.n_stat, c->part_loss, c->n_loss_used, c->nring, c->tau,
-            c->stat, c->mask, c->ctl, mask_out, loss_out, nullptr, nullptr);
+            c->stat, c->mask, c->ctl, mask_out, loss_out, nullptr, nullptr, nullptr);
     if (c->hy.pstride <= (int64_t)kBigBlock * 4)
         // the whole parameter vector fits one block: no cross-block hand-over at the end
         launch_server<kBigBlock, 4>(self_select, 1, lds, s, a);
@@ -502,7 +509,7 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool pr
 
 hipError_t lazy_flags(gcada_ctx* c, hipStream_t s)
 {
-    lazy_flags_kernel<<<1, kWave, 0, s>>>(c->hy, c->nring, c->tau, c->store_now);
+    lazy_flags_kernel<<<1, kWave, 0, s>>>(c->hy, c->nring, c->tau, c->hot, c->store_now);
     return hipGetLastError();
 }
 
@@ -520,7 +527,7 @@ hipError_t server_select(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipSt
     }
     select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(
         c->hy, part, n_stat, c->part_loss, c->n_loss_used, c->nring, c->tau, c->stat, c->mask, c->ctl,
-        mask_out, loss_out, c->store_now, c->redo);
+        mask_out, loss_out, c->store_now, c->redo, c->hot);
     return hipGetLastError();
 }
 

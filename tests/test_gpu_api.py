@@ -1,0 +1,85 @@
+"""The C-ABI's error behaviour and stream handling on a device: calls out of order, bad arguments,
+unknown options; a run on a side stream gives the bits of a run on the default stream."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from gcada_inputs import CONFIGS, make_indices, make_shards, make_theta0, scaled
+
+pytestmark = pytest.mark.gpu
+
+
+def _mk(w):
+    from paper_2201_04301_amd import Gcada
+    return Gcada.from_workload(w)
+
+
+def test_calls_out_of_order_and_bad_arguments_are_refused():
+    from paper_2201_04301_amd import binding as B
+    w = scaled(CONFIGS["lr_small"], name="api", widths=(32,), mu=16, G=3, rows=64, D=4)
+    Xs, ys = make_shards(w, "cuda")
+    gpu = _mk(w)
+    mask = torch.zeros(w.G, dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    # no theta yet
+    rc = B.lib.gcada_step(gpu.ctx, None, mask.data_ptr(), loss.data_ptr(), None)
+    assert rc == B.GCADA_ESTATE and "set_theta" in B.gcada_last_error(gpu.ctx)
+    gpu.set_theta(make_theta0(w))
+    # theta, but a group without a shard
+    for g in range(w.G - 1):
+        B.gcada_set_shard(gpu.ctx, g, Xs[g].data_ptr(), ys[g].data_ptr(), Xs[g].shape[0], Xs[g].stride(0))
+    rc = B.lib.gcada_step(gpu.ctx, None, mask.data_ptr(), loss.data_ptr(), None)
+    assert rc == B.GCADA_ESTATE and "shard" in B.gcada_last_error(gpu.ctx)
+    # shard arguments
+    X, y = Xs[-1], ys[-1]
+    assert B.lib.gcada_set_shard(gpu.ctx, w.G, X.data_ptr(), y.data_ptr(), X.shape[0], X.stride(0)) == B.GCADA_EINVAL
+    assert B.lib.gcada_set_shard(gpu.ctx, 0, None, y.data_ptr(), X.shape[0], X.stride(0)) == B.GCADA_EINVAL
+    assert B.lib.gcada_set_shard(gpu.ctx, 0, X.data_ptr(), y.data_ptr(), 0, X.stride(0)) == B.GCADA_EINVAL
+    assert B.lib.gcada_set_shard(gpu.ctx, 0, X.data_ptr(), y.data_ptr(), X.shape[0], w.widths[0] - 1) == B.GCADA_EINVAL
+    B.gcada_set_shard(gpu.ctx, w.G - 1, X.data_ptr(), y.data_ptr(), X.shape[0], X.stride(0))
+    # options and rules
+    assert B.lib.gcada_set_option(gpu.ctx, 99, 1) == B.GCADA_EINVAL
+    assert B.lib.gcada_set_rule(gpu.ctx, 7, None) == B.GCADA_EINVAL
+    assert B.lib.gcada_set_rule(gpu.ctx, B.GCADA_RULE_SERVER, None) == B.GCADA_EINVAL      # no constants yet
+    bad_L = (C.c_double * w.G)(*([1.0] * (w.G - 1) + [-1.0]))
+    assert B.lib.gcada_set_rule(gpu.ctx, B.GCADA_RULE_SERVER, bad_L) == B.GCADA_EINVAL
+    # state with an age outside [1, D]
+    st = gpu.get_state()
+    st["tau"][0] = w.D + 1
+    with pytest.raises(B.GcadaError) as ei:
+        gpu.set_state(**st)
+    assert ei.value.code == B.GCADA_EINVAL
+    # and the context still works
+    gpu.step(None)
+    out = gpu.outputs()
+    assert out["mask"].all() and np.isfinite(out["loss"])
+    gpu.close()
+
+
+@pytest.mark.parametrize("cfg,kw", [
+    ("lr_small", dict(widths=(64,), mu=32, G=3, rows=512, D=5)),                 # one-launch kernel
+    ("lr_4k", dict(widths=(2048,), mu=64, G=4, rows=256, D=5)),                  # tile kernel + fused finish
+    ("mlp_784", dict(widths=(64, 48, 10), mu=64, G=4, rows=300, D=5)),           # MLP
+])
+def test_side_stream_run_matches_default_stream(cfg, kw):
+    w = scaled(CONFIGS[cfg], name="stream", **kw)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 12
+    idx = torch.as_tensor(make_indices(w, steps), device="cuda")
+    torch.cuda.synchronize()
+    states = []
+    for side in (False, True):
+        gpu = _mk(w)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        stream = torch.cuda.Stream() if side else torch.cuda.current_stream()
+        with torch.cuda.stream(stream):
+            for k in range(steps):
+                gpu.step(idx[k].contiguous())
+        stream.synchronize()
+        states.append(gpu.get_state())
+        gpu.close()
+    for name in ("theta", "h", "vhat", "agg", "last", "tau", "dtheta_sq"):
+        np.testing.assert_array_equal(states[0][name], states[1][name], err_msg=name)

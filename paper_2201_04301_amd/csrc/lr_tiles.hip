@@ -58,10 +58,15 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     const float* __restrict__ X = (const float*)sh.X;
 
     // row ids first: the tile's loads depend on nothing else
+    // (the last tile of a group may reach past the minibatch: such rows load nothing and weigh 0)
     int my_row = 0;
+    bool my_valid = false;
     if (tid < R) {
         const int i = rb * R + tid;
-        if (a.idx) {
+        my_valid = i < mu;
+        if (!my_valid) {
+            my_row = 0;
+        } else if (a.idx) {
             my_row = a.idx[(int64_t)g * mu + i];
         } else {
             // cyclic window: (k * mu + i) mod rows, kept in 64-bit products of reduced factors
@@ -69,7 +74,7 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
             my_row = (int)((((unsigned long long)k % n) * ((unsigned long long)mu % n) +
                             (unsigned long long)i) % n);
         }
-        s_row[tid] = my_row;
+        s_row[tid] = my_valid ? my_row : -1;
     }
     const int col = wc * 256 + lane * 4;
     const bool col_ok = col < (int)hy.p;         // d is a multiple of 4; the last column wave may be partly idle
@@ -81,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     for (int u = 0; u < kTR; ++u) {
         // the row id is the same for the whole wave: keep it in a scalar register
         const int64_t row = __builtin_amdgcn_readfirstlane(s_row[wr * kTR + u]);
-        x[u] = col_ok ? global_load4(X + row * sh.ld + col) : make_float4(0, 0, 0, 0);
+        x[u] = col_ok && row >= 0 ? global_load4(X + row * sh.ld + col) : make_float4(0, 0, 0, 0);
     }
     // while the tile streams in: labels, the two iterates
     float my_y = 1.0f;
@@ -119,6 +124,7 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
         }
         float r, dr, ls;
         residuals(hy.quadratic != 0, z, dz, my_y, r, dr, ls);
+        if (!my_valid) r = dr = ls = 0.0f;
         s_res[tid] = make_float2(r, dr);
         lsum = (double)ls;
     }
@@ -681,7 +687,7 @@ struct LrTilePlan {
 };
 
 // Decide whether the single-pass kernel applies (256 <= d <= 4096, a multiple of 4, so that a tile
-// holds whole rows; mu a multiple of the tile's rows) and size its scratch.
+// holds whole rows; the last tile of a group may be partly empty) and size its scratch.
 hipError_t lr_tile_plan(gcada_ctx* c)
 {
     auto* pl = new LrTilePlan();
@@ -692,9 +698,8 @@ hipError_t lr_tile_plan(gcada_ctx* c)
         if (d <= 256 * w) WC = w;
     if (!WC || d % 4 != 0 || d < 256) return hipSuccess;       // narrower rows: other kernels
     const int R = kTR * (kWaves / WC);
-    if (mu % R) return hipSuccess;
     pl->R = R;
-    pl->RB = mu / R;
+    pl->RB = (mu + R - 1) / R;                   // the last tile of a group may be partly empty
     pl->n_stat = (d / 4 + kRedBlock - 1) / kRedBlock;
     const size_t n = (size_t)G * pl->RB * d;
     hipError_t e;

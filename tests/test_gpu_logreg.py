@@ -103,6 +103,9 @@ def test_lr_deterministic(par):
     (784, 256, 3, 500, 1e-4, True),       # rows that do not fill the column waves: 64 x 1024 tiles, 784 used
     (3000, 48, 5, 200, 0.0, True),        # 16 x 4096 tiles, 3000 columns used
     (300, 128, 4, 300, 1e-3, False),      # 128 x 512 tiles, 300 columns used, cyclic window
+    (4096, 24, 6, 100, 1e-4, True),       # minibatch that does not fill its last tile (16 + 8 rows)
+    (1024, 100, 3, 200, 0.0, False),      # 64-row tiles, 100 rows: the second tile holds 36; cyclic window
+    (300, 50, 4, 90, 1e-3, True),         # 128-row tiles, one tile with 50 rows
     (8192, 48, 5, 100, 0.0, True),        # general kernels
     (65536, 32, 4, 64, 0.0, True),        # general kernels, d of the largest configuration
 ])

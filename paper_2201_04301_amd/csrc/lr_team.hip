@@ -1,8 +1,9 @@
-// Single-pass logistic-regression gradients for wide rows (d a multiple of 4096, d >= 8192):
+// Single-pass logistic-regression gradients for wide rows (d > 4096, a multiple of 4):
 // step a1 for shapes whose rows do not fit one workgroup's registers (paper Sec. II-A).
 //
-// A TEAM of TS = d/4096 workgroups shares the rows of a tile: member m owns columns
-// [4096 m, 4096 (m+1)) of R = 4 rows (two float4 per row and thread).  Every member forms its
+// A TEAM of TS = ceil(d/4096) workgroups shares the rows of a tile: member m owns columns
+// [4096 m, 4096 (m+1)) (the last member those that exist) of R = 4 rows (two float4 per row
+// and thread).  Every member forms its
 // partial dot products and publishes them (64 bytes) in a small exchange buffer; TWO TILES LATER
 // it collects the partials of all members, forms the residuals and adds the tile's contribution
 // to its 4096 columns of the two weighted row sums.  While a tile waits for its residuals it is
@@ -156,15 +157,24 @@ __device__ __forceinline__ void team_fetch(const TeamArgs& a, TeamSeq& S, int nF
     S.ld_nxt = sh->ld;
 }
 
+// A data thread's two column quadruples.  The last member of a team may own fewer than 4096
+// columns (d is a multiple of 4, not necessarily of 4096): a quadruple past the row's end is
+// switched off -- it loads an in-range stand-in (its products meet zeros of theta), and its sums
+// are neither stored nor counted.
+struct TeamCols {
+    int c[kV];
+    bool ok[kV];
+};
+
 // Request the tile described in S into register tile JL.
 template <int JL>
-__device__ __forceinline__ void team_load_tile(TeamRegs& R, const TeamSeq& S, int col)
+__device__ __forceinline__ void team_load_tile(TeamRegs& R, const TeamSeq& S, const TeamCols& C)
 {
 #pragma unroll
     for (int u = 0; u < kR; ++u) {
-        const float* xrow = S.x_nxt + (int64_t)S.rows_nxt[u] * S.ld_nxt + col;
+        const float* xrow = S.x_nxt + (int64_t)S.rows_nxt[u] * S.ld_nxt;
 #pragma unroll
-        for (int q = 0; q < kV; ++q) R.xb[JL][u][q] = global_load4(xrow + 256 * q);
+        for (int q = 0; q < kV; ++q) R.xb[JL][u][q] = global_load4(xrow + C.c[q]);
     }
 }
 
@@ -195,13 +205,15 @@ __device__ __forceinline__ void team_advance(const TeamArgs& a, TeamSeq& S, int 
 }
 
 // theta^k - theta_stale of group g at this thread's columns
-__device__ __forceinline__ void team_delta(const TeamArgs& a, const TeamRegs& R, int g, int col, float4 (&dl)[kV])
+__device__ __forceinline__ void team_delta(const TeamArgs& a, const TeamRegs& R, int g, const TeamCols& C,
+                                           float4 (&dl)[kV])
 {
-    const float* stale = a.ring + (int64_t)stale_slot_of(a.hy, a.tau[g]) * a.hy.pstride + col;
+    const float* stale = a.ring + (int64_t)stale_slot_of(a.hy, a.tau[g]) * a.hy.pstride;
 #pragma unroll
     for (int q = 0; q < kV; ++q) {
-        const float4 u4 = *(const float4*)(stale + 256 * q);
-        dl[q] = make_float4(R.th4[q].x - u4.x, R.th4[q].y - u4.y, R.th4[q].z - u4.z, R.th4[q].w - u4.w);
+        const float4 u4 = *(const float4*)(stale + C.c[q]);
+        dl[q] = C.ok[q] ? make_float4(R.th4[q].x - u4.x, R.th4[q].y - u4.y, R.th4[q].z - u4.z, R.th4[q].w - u4.w)
+                        : make_float4(0, 0, 0, 0);
     }
 }
 
@@ -212,18 +224,18 @@ __device__ __forceinline__ void team_delta(const TeamArgs& a, const TeamRegs& R,
 // multiplied and parked, tile n-2 is added from where it was parked.
 template <int J>
 __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, TeamSeq& S, int n, int m,
-                                                int col, TeamLds& L, float4* park)
+                                                const TeamCols& C, TeamLds& L, float4* park)
 {
     constexpr int JL = (J + 2) % kRegTiles;      // the register tile that is loaded in this stage
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const bool have_cur = n < S.ntot, have_add = n >= 2 && n - 2 < S.ntot;
 
-    team_load_tile<JL>(R, S, col);
+    team_load_tile<JL>(R, S, C);
     team_fetch(a, S, n + 3, a.NT);
 
     if (have_cur) {
-        if (S.tC == 0) team_delta(a, R, S.gC, col, R.dl4);       // first tile of a group
+        if (S.tC == 0) team_delta(a, R, S.gC, C, R.dl4);         // first tile of a group
         float v[kPartial];
 #pragma unroll
         for (int u = 0; u < kR; ++u) {
@@ -269,9 +281,9 @@ __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, 
             // group S.gA is finished: this member's 4096 columns of the gradient and of s_g
             const int g = S.gA;
             double sq = 0;
-            float* out = fresh_row(a.gbuf, a.which, a.hy, g) + col;
+            float* out = fresh_row(a.gbuf, a.which, a.hy, g);
             float4 dlo[kV];
-            if (a.hy.l2 != 0.0f) team_delta(a, R, g, col, dlo);
+            if (a.hy.l2 != 0.0f) team_delta(a, R, g, C, dlo);
 #pragma unroll
             for (int q = 0; q < kV; ++q) {
                 if (a.hy.l2 != 0.0f) {
@@ -279,9 +291,11 @@ __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, 
                     R.ag[q].x += ml * R.th4[q].x; R.ag[q].y += ml * R.th4[q].y; R.ag[q].z += ml * R.th4[q].z; R.ag[q].w += ml * R.th4[q].w;
                     R.as[q].x += ml * dlo[q].x; R.as[q].y += ml * dlo[q].y; R.as[q].z += ml * dlo[q].z; R.as[q].w += ml * dlo[q].w;
                 }
-                *(float4*)(out + 256 * q) = R.ag[q];
-                sq += (double)R.as[q].x * R.as[q].x + (double)R.as[q].y * R.as[q].y + (double)R.as[q].z * R.as[q].z +
-                      (double)R.as[q].w * R.as[q].w;
+                if (C.ok[q]) {
+                    *(float4*)(out + C.c[q]) = R.ag[q];
+                    sq += (double)R.as[q].x * R.as[q].x + (double)R.as[q].y * R.as[q].y +
+                          (double)R.as[q].z * R.as[q].z + (double)R.as[q].w * R.as[q].w;
+                }
                 R.ag[q] = make_float4(0, 0, 0, 0);
                 R.as[q] = make_float4(0, 0, 0, 0);
             }
@@ -440,25 +454,32 @@ __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
         S.ntile = ntile; S.ntot = ntot;
         S.gF = S.gC = S.gA = g_first;
         S.tF = S.tC = S.tA = 0;
-        const int col = m * kSlab + wave * (256 * kV) + lane * 4;    // and col + 256
+        TeamCols C;
+#pragma unroll
+        for (int q = 0; q < kV; ++q) {
+            const int col = m * kSlab + wave * (256 * kV) + lane * 4 + 256 * q;
+            C.ok[q] = col < (int)hy.p;
+            C.c[q] = C.ok[q] ? col : lane * 4;           // stand-in: a column every row has
+        }
         TeamRegs R;
 #pragma unroll
         for (int q = 0; q < kV; ++q) {
-            R.th4[q] = *(const float4*)(a.ring + (int64_t)hy.cur * hy.pstride + col + 256 * q);
+            R.th4[q] = C.ok[q] ? *(const float4*)(a.ring + (int64_t)hy.cur * hy.pstride + C.c[q])
+                               : make_float4(0, 0, 0, 0);
             R.ag[q] = make_float4(0, 0, 0, 0);
             R.as[q] = make_float4(0, 0, 0, 0);
             R.dl4[q] = make_float4(0, 0, 0, 0);
         }
         // prologue: tiles 0 and 1 start loading (there are at least two), tile 2 is described
         team_fetch(a, S, 0, a.NT);
-        team_load_tile<0>(R, S, col);
+        team_load_tile<0>(R, S, C);
         team_fetch(a, S, 1, a.NT);
-        team_load_tile<1>(R, S, col);
+        team_load_tile<1>(R, S, C);
         team_fetch(a, S, 2, a.NT);
         for (int n = 0; n < nstage; n += kRegTiles) {
-            team_data_stage<0>(a, R, S, n, m, col, L, park);
-            team_data_stage<1>(a, R, S, n + 1, m, col, L, park);
-            team_data_stage<2>(a, R, S, n + 2, m, col, L, park);
+            team_data_stage<0>(a, R, S, n, m, C, L, park);
+            team_data_stage<1>(a, R, S, n + 1, m, C, L, park);
+            team_data_stage<2>(a, R, S, n + 2, m, C, L, park);
         }
     }
 }
@@ -470,15 +491,15 @@ struct LrTeamPlan {
     unsigned long long* xch = nullptr;
 };
 
-// Decide whether the team kernel applies (d a multiple of 4096 and at least 8192, mu a multiple
+// Decide whether the team kernel applies (d a multiple of 4 above 4096, mu a multiple
 // of the tile's rows and at least two tiles, a whole number of teams fits the device with every workgroup resident).
 hipError_t lr_team_plan(gcada_ctx* c)
 {
     auto* pl = new LrTeamPlan();
     c->lr_team = pl;
     const int d = (int)c->hy.p, mu = c->hy.mu;
-    if (d % kSlab || d < 2 * kSlab || mu % kR || mu < 2 * kR) return hipSuccess;
-    const int TS = d / kSlab;
+    if (d % 4 || d <= kSlab || mu % kR || mu < 2 * kR) return hipSuccess;
+    const int TS = (d + kSlab - 1) / kSlab;      // the last member may own fewer columns
     if (TS * kR > kWave) return hipSuccess;          // one wave polls all members' partials
     hipDeviceProp_t prop;
     hipError_t e = hipGetDeviceProperties(&prop, c->device);

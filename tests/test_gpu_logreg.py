@@ -90,7 +90,7 @@ def test_lr_deterministic(par):
 
 
 # ---- single-pass kernel (whole-row register tiles): every wave arrangement, one and several
-# tiles per group; the last two shapes are too wide for it and take the general kernels
+# tiles per group; wider rows take the team kernel, a width that is not a multiple of 4 the general kernels
 
 @pytest.mark.parametrize("d,mu,G,rows,l2,use_idx", [
     (4096, 256, 16, 1024, 1e-4, True),    # 16 x 4096 tiles, 16 tiles per group
@@ -106,8 +106,11 @@ def test_lr_deterministic(par):
     (4096, 24, 6, 100, 1e-4, True),       # minibatch that does not fill its last tile (16 + 8 rows)
     (1024, 100, 3, 200, 0.0, False),      # 64-row tiles, 100 rows: the second tile holds 36; cyclic window
     (300, 50, 4, 90, 1e-3, True),         # 128-row tiles, one tile with 50 rows
-    (8192, 48, 5, 100, 0.0, True),        # general kernels
-    (65536, 32, 4, 64, 0.0, True),        # general kernels, d of the largest configuration
+    (8192, 48, 5, 100, 0.0, True),        # team kernel, two members
+    (9192, 32, 4, 64, 1e-4, True),        # team of three, the last member owns 1000 columns
+    (5000, 16, 3, 40, 0.0, False),        # team of two, the second member owns 904 columns; cyclic window
+    (65536, 32, 4, 64, 0.0, True),        # team kernel, d of the largest configuration
+    (8190, 32, 3, 64, 0.0, True),         # d not a multiple of 4: general kernels
 ])
 def test_lr_tile_shapes(par, d, mu, G, rows, l2, use_idx):
     w = scaled(CONFIGS["lr_small"], name="tiles", widths=(d,), mu=mu, G=G, rows=rows, l2=l2, c=1.0,

@@ -147,9 +147,12 @@ __device__ __forceinline__ void team_fetch(const TeamArgs& a, TeamSeq& S, int nF
                                           ((unsigned long long)a.hy.mu % rows)) % rows);
 #pragma unroll
     for (int u = 0; u < kR; ++u) {
+        // the last tile of a group may reach past the minibatch: such a row repeats the last one
+        // (it is loaded, its residuals are zero)
+        const int i = min(S.tF * kR + u, a.hy.mu - 1);
         int rr;
-        if (a.idx) rr = ((const_i32*)(uintptr_t)a.idx)[(int64_t)S.gF * a.hy.mu + S.tF * kR + u];
-        else rr = (int)((cyc_base + (unsigned)(S.tF * kR + u)) % rows);
+        if (a.idx) rr = ((const_i32*)(uintptr_t)a.idx)[(int64_t)S.gF * a.hy.mu + i];
+        else rr = (int)((cyc_base + (unsigned)i) % rows);
         S.rows_nxt[u] = __builtin_amdgcn_readfirstlane(rr);
     }
     S.x_nxt = (const float*)sh->X;
@@ -184,7 +187,7 @@ __device__ __forceinline__ float team_load_label(const TeamArgs& a, const TeamSe
     typedef const ShardDesc __attribute__((address_space(4))) const_shard;
     const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
     const unsigned rows = (unsigned)sh->rows;
-    const int i = S.tF * kR + lane;
+    const int i = min(S.tF * kR + lane, a.hy.mu - 1);
     int myrow;
     if (a.idx) {
         myrow = a.idx[(int64_t)S.gF * a.hy.mu + i];
@@ -368,6 +371,7 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
         if (lane < kR) {
             float r, dr, ls;
             residuals(a.hy.quadratic != 0, z, dz, L.s_y[(n - 2) % kLabelRing][lane], r, dr, ls);
+            if (S.tA * kR + lane >= a.hy.mu) r = dr = ls = 0.0f;      // row past the minibatch
             L.s_res[n & 1][lane] = make_float2(r, dr);
             lacc += (double)ls;
         }
@@ -413,7 +417,7 @@ __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
 
     // stages 0 .. ntot+1 (the last two only drain), three at a time; stages past the end do
     // nothing but request the last tile again
-    const int ntile = hy.mu / kR;
+    const int ntile = (hy.mu + kR - 1) / kR;
     // the team's groups: team, team + NT, ... -- under the server-side rule the selected ones only
     // (an unselected group contributes a zero loss partial and nothing else)
     int g_first = -1, ngroups = 0;
@@ -491,14 +495,15 @@ struct LrTeamPlan {
     unsigned long long* xch = nullptr;
 };
 
-// Decide whether the team kernel applies (d a multiple of 4 above 4096, mu a multiple
-// of the tile's rows and at least two tiles, a whole number of teams fits the device with every workgroup resident).
+// Decide whether the team kernel applies (d a multiple of 4 above 4096, at least two tiles of
+// rows per group -- the last one may be partly empty --, a whole team fits the device with every
+// workgroup resident).
 hipError_t lr_team_plan(gcada_ctx* c)
 {
     auto* pl = new LrTeamPlan();
     c->lr_team = pl;
     const int d = (int)c->hy.p, mu = c->hy.mu;
-    if (d % 4 || d <= kSlab || mu % kR || mu < 2 * kR) return hipSuccess;
+    if (d % 4 || d <= kSlab || mu <= kR) return hipSuccess;      // at least two tiles per group
     const int TS = (d + kSlab - 1) / kSlab;      // the last member may own fewer columns
     if (TS * kR > kWave) return hipSuccess;          // one wave polls all members' partials
     hipDeviceProp_t prop;
@@ -556,7 +561,7 @@ hipError_t lr_team_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
     a.TS = pl->TS; a.NT = pl->NT;
     // tags never repeat within the four-slot window: 2^20 tiles per launch at most, and the
     // launch counter advances the base (wrap-around after 4096 launches lands on tags long gone)
-    const unsigned tiles = (unsigned)((c->hy.G + pl->NT - 1) / pl->NT) * (unsigned)(c->hy.mu / kR);
+    const unsigned tiles = (unsigned)((c->hy.G + pl->NT - 1) / pl->NT) * (unsigned)((c->hy.mu + kR - 1) / kR);
     a.tag_base = (unsigned)((c->team_launches++ % 4095u) + 1u) << 20;
     if (tiles >= (1u << 20)) return hipErrorInvalidValue;
     lr_team_kernel<<<pl->NT * pl->TS, kThreads, kParkBytes, s>>>(a);

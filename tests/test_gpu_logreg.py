@@ -109,6 +109,8 @@ def test_lr_deterministic(par):
     (8192, 48, 5, 100, 0.0, True),        # team kernel, two members
     (9192, 32, 4, 64, 1e-4, True),        # team of three, the last member owns 1000 columns
     (5000, 16, 3, 40, 0.0, False),        # team of two, the second member owns 904 columns; cyclic window
+    (8192, 30, 4, 64, 1e-4, True),        # team kernel, 30 rows: the eighth tile holds two
+    (12288, 9, 2, 20, 0.0, False),        # team of three, 9 rows: the third tile holds one; cyclic window
     (65536, 32, 4, 64, 0.0, True),        # team kernel, d of the largest configuration
     (8190, 32, 3, 64, 0.0, True),         # d not a multiple of 4: general kernels
 ])

@@ -201,11 +201,11 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * Tuning switches (defaults in brackets).  GCADA_OPT_SINGLE_PASS_LOGREG [1]: compute the logistic
  * gradients with the kernel that reads the minibatch from HBM once (whole-row register tiles)
  * when the shape allows it (d <= 256 with mu <= 128 and few groups: the whole iteration in one
- * launch; 256 <= d <= 4096, a multiple of 4, any mu: whole-row register tiles of 16 times
+ * launch; otherwise d <= 4096, a multiple of 4, any mu: whole-row register tiles of 16 times
  * 16 / (d / 256 rounded up to a power of two) rows, the last tile of a group possibly partly
  * empty; or 4096 < d <= 65,536, a multiple of 4, with mu >= 5: 4-row tiles shared by a team of
- * ceil(d / 4096) workgroups; 16-byte aligned shards); 0 forces the general two-pass kernels.  All compute the
- * same step a1.
+ * ceil(d / 4096) workgroups; 16-byte aligned shards); 0 forces the general two-pass kernels.
+ * All compute the same step a1.
  * GCADA_OPT_FUSED_FINISH [1]: after the whole-row tile kernel, add the tile partials, select
  * (Eq. (9)), sum the innovations and update (Eq. (8a)-(8c)) in ONE launch whose blocks meet once
  * inside the kernel (at most 64 blocks, one per compute unit; the wait is bounded: if the blocks

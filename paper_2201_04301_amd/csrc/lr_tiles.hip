@@ -686,8 +686,9 @@ struct LrTilePlan {
     hipStream_t fin_stream = nullptr;
 };
 
-// Decide whether the single-pass kernel applies (256 <= d <= 4096, a multiple of 4, so that a tile
-// holds whole rows; the last tile of a group may be partly empty) and size its scratch.
+// Decide whether the single-pass kernel applies (d <= 4096, a multiple of 4, so that a tile holds
+// whole rows; lanes past the row's end idle, the last tile of a group may be partly empty) and
+// size its scratch.
 hipError_t lr_tile_plan(gcada_ctx* c)
 {
     auto* pl = new LrTilePlan();
@@ -696,7 +697,7 @@ hipError_t lr_tile_plan(gcada_ctx* c)
     int WC = 0;
     for (int w : {16, 8, 4, 2, 1})
         if (d <= 256 * w) WC = w;
-    if (!WC || d % 4 != 0 || d < 256) return hipSuccess;       // narrower rows: other kernels
+    if (!WC || d % 4 != 0) return hipSuccess;                  // rows that are no whole float4s: other kernels
     const int R = kTR * (kWaves / WC);
     pl->R = R;
     pl->RB = (mu + R - 1) / R;                   // the last tile of a group may be partly empty

@@ -106,6 +106,9 @@ def test_lr_deterministic(par):
     (4096, 24, 6, 100, 1e-4, True),       # minibatch that does not fill its last tile (16 + 8 rows)
     (1024, 100, 3, 200, 0.0, False),      # 64-row tiles, 100 rows: the second tile holds 36; cyclic window
     (300, 50, 4, 90, 1e-3, True),         # 128-row tiles, one tile with 50 rows
+    (64, 512, 20, 600, 1e-4, True),       # narrow rows, too many rows and groups for the one-launch kernel: 256-row tiles, 16 lanes of a wave used
+    (128, 200, 5, 300, 0.0, False),       # narrow rows, one partly empty tile; cyclic window
+    (4, 40, 3, 50, 1e-3, True),           # one float4 per row
     (8192, 48, 5, 100, 0.0, True),        # team kernel, two members
     (9192, 32, 4, 64, 1e-4, True),        # team of three, the last member owns 1000 columns
     (5000, 16, 3, 40, 0.0, False),        # team of two, the second member owns 904 columns; cyclic window

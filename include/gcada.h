@@ -221,9 +221,17 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * groups, recomputed from the signals and activations still in place (same products in the same
  * order: the same bits).  Iterates, aggregate, stored gradients, statistic and mask are
  * identical either way; the `gbuf` row of a group that did NOT upload is then unspecified.
+ * GCADA_OPT_GRAM_STATISTIC [1; takes effect for a bf16 MLP under the lazy gradient store when
+ * mu (n_0 + n_1) <= n_0 n_1 and the first forward GEMM reads the shard rows in place]: both
+ * iterates see the same minibatch X, so the first layer's share of stat_g is
+ * || (dZ_1 - dZ~_1)^T X ||^2 = <X X^T, (dZ_1 - dZ~_1)(dZ_1 - dZ~_1)^T>: two mu x mu Gram matrices
+ * instead of two n_1 x n_0 weight gradients, and the first layer's gradient is formed only for
+ * the groups that upload.  Same statistic up to rounding (the signal difference is rounded to
+ * bf16 once more); 0 computes it from the two weight gradients.
  * Errors: GCADA_EINVAL (unknown option).
  */
-enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1, GCADA_OPT_FUSED_FINISH = 2, GCADA_OPT_LAZY_GRADIENT_STORE = 3 };
+enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1, GCADA_OPT_FUSED_FINISH = 2, GCADA_OPT_LAZY_GRADIENT_STORE = 3,
+       GCADA_OPT_GRAM_STATISTIC = 4 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*

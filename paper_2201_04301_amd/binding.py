@@ -24,6 +24,7 @@ GCADA_MAX_WIDTHS = 8
 GCADA_OPT_SINGLE_PASS_LOGREG = 1
 GCADA_OPT_FUSED_FINISH = 2
 GCADA_OPT_LAZY_GRADIENT_STORE = 3
+GCADA_OPT_GRAM_STATISTIC = 4
 
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",

@@ -456,6 +456,10 @@ int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
         ctx->allow_fused_finish = value != 0;
         return GCADA_OK;
     }
+    if (option == GCADA_OPT_GRAM_STATISTIC) {
+        ctx->allow_gram = value != 0;
+        return GCADA_OK;
+    }
     if (option == GCADA_OPT_LAZY_GRADIENT_STORE) {
         ctx->lazy_store = value != 0 && ctx->dims.model == GCADA_MLP;
         return GCADA_OK;

@@ -138,6 +138,7 @@ struct gcada_ctx {
     uint8_t* store_now = nullptr;  // G
     uint8_t* redo = nullptr;       // G
     uint8_t* hot = nullptr;        // G: the statistic exceeded the threshold in the previous step
+    bool allow_gram = true;        // first-layer statistic through Gram matrices when it pays (bf16 MLP)
     bool allow_single_pass = true;
     bool allow_fused_finish = true;
     bool lr_fused_finish = false;  // this step: lr_tile_finish replaces lr_tile_reduce + server_step

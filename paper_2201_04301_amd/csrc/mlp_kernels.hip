@@ -166,6 +166,15 @@ __device__ __forceinline__ void mfma_step<float>(const uint4& a, const uint4& b,
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
 }
 
+// A 16-byte load that is known to come from global memory.  The operand pointers may derive from
+// the shard table (read from memory), whose address space the compiler cannot see: it would
+// issue FLAT loads, and those are also counted with the LDS traffic -- every wait for an LDS
+// fragment would then wait for the tile loads in flight as well.
+__device__ __forceinline__ u32x4 global_load_vec(const char* p)
+{
+    return *(const __attribute__((address_space(1))) u32x4*)p;
+}
+
 // global -> registers: the 16-byte chunks of one k-tile of both operands.  (Native vector
 // registers: arrays of the HIP uint4 struct are not always kept in registers.)
 template <typename TL>
@@ -177,12 +186,12 @@ __device__ __forceinline__ void tile_gload(const char* __restrict__ Pg, const ch
 #pragma unroll
     for (int i = 0; i < TL::PCH; ++i) {
         const int kc = (tid + TL::NT * i) % TL::CPR;
-        rp[i] = *(const u32x4*)(Pg + poff[i] + (int64_t)kt * TL::KROW + kc * 16);
+        rp[i] = global_load_vec(Pg + poff[i] + (int64_t)kt * TL::KROW + kc * 16);
     }
 #pragma unroll
     for (int i = 0; i < TL::QCH; ++i) {
         const int c = tid + TL::NT * i, row = c / TL::CPR, kc = c % TL::CPR;
-        rq[i] = *(const u32x4*)(Qg + (int64_t)row * ldq_b + (int64_t)kt * TL::KROW + kc * 16);
+        rq[i] = global_load_vec(Qg + (int64_t)row * ldq_b + (int64_t)kt * TL::KROW + kc * 16);
     }
 }
 
@@ -1066,6 +1075,208 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
         part_stat[(int64_t)g * n_stat + stat_off + blockIdx.x] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
 }
 
+
+// ---------------------------------------------------------------------------------------
+// First-layer statistic through two Gram matrices (bf16 models with the lazy gradient store).
+// Both iterates see the same minibatch X (mu x n0), so the difference of the first layer's
+// weight gradients is dZ^T X with dZ = dZ_1(theta^k) - dZ_1(theta_stale) (mu x n1), and
+//     || dZ^T X ||_F^2 = sum_{s,s'} (X X^T)[s][s'] (dZ dZ^T)[s][s'],
+// two mu x mu matrices instead of two n1 x n0 ones: 2 mu^2 (n0 + n1) flops instead of
+// 4 mu n0 n1 (six times fewer for 3072-1024 at mu = 256), and no gradient is formed for a group
+// that does not upload (paper Eq. (9): the statistic only decides; Sec. IV: only uploads enter
+// the aggregate).
+constexpr int kGramSplitX = 2, kGramSplitZ = 1;   // workgroups per tile of X X^T and of dZ dZ^T
+
+struct GramArgs {
+    Hyper hy;
+    int M, K;                      // rows (the minibatch size) and contraction length in elements
+    // rows of the operand: the minibatch rows of the group's shard in place (gather != 0), or
+    // R + g * r_g + row * ldr
+    int gather;
+    const ShardDesc* shards; const int32_t* idx;
+    const void* R; int64_t r_g; int ldr;
+    int S;                         // the contraction is split over S workgroups per tile
+    float* KX; int ldk;            // kGramSplitX partial matrices [split][G][M][ldk]: written by the
+                                   // first kernel (its S), added up in a fixed order by the second
+    double* part_stat; int n_stat, stat_off, n_slots;   // second kernel: one partial per tile and
+                                                         // split, the layer's other slots are cleared
+};
+
+using GramTile = Tile<128, 128, 64, 2, 2, 2>;
+
+// grid: (ceil(M/128), ceil(M/128), G * S).  Both matrices are symmetric: tiles below the diagonal
+// do nothing, tiles above it count twice.
+// STAT = false: KX[split][g] <- the split's share of rows rows^T.
+// STAT = true:  partial statistic <- sum over the tile of (the split's share of rows rows^T)[m][n]
+//               * (sum over the SX partial matrices KX[.][g][m][n])  -- the product is linear in
+//               either factor, so the splits' partial statistics simply add up.
+template <bool STAT>
+__global__ __launch_bounds__(GramTile::NT) void mlp_gram(GramArgs a)
+{
+    using TL = GramTile;
+    using T = bf16_t;
+    extern __shared__ __align__(16) char lds[];
+    constexpr int esz = 2, kP = TL::BM * TL::PITCH;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int wm = wave / TL::WN, wn = wave % TL::WN;
+    // Workgroup -> (tile, group, split).  Consecutive workgroup ids go to different XCDs (id mod
+    // 8), each with its own L2: the ids of one XCD are mapped to a contiguous range of work, so
+    // that the tiles of one (group, split) -- which read the same rows -- share an L2.
+    int bx, by, bz;
+    {
+        const int gx = gridDim.x, gy = gridDim.y, total = gx * gy * gridDim.z;
+        int lin = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+        if (total % 8 == 0) lin = (lin % 8) * (total / 8) + lin / 8;
+        bx = lin % gx; lin /= gx;
+        by = lin % gy;
+        bz = lin / gy;
+    }
+    const int g = bz / a.S, sp = bz % a.S;
+    const int tile = by * gridDim.x + bx, ntile = gridDim.x * gridDim.y;
+    double* out = STAT ? a.part_stat + (int64_t)g * a.n_stat + a.stat_off : nullptr;
+    if (bx < by) {
+        if (STAT && tid == 0) out[tile * a.S + sp] = 0.0;
+        return;
+    }
+    const int m0 = by * TL::BM, n0 = bx * TL::BN;
+    // byte offsets of the rows this thread's chunks belong to (rows past M: row 0, result unused)
+    const char* base;
+    int64_t poff[TL::PCH], qoff[TL::QCH];
+    {
+        const ShardDesc sh = a.gather ? a.shards[g] : ShardDesc{};
+        base = a.gather ? (const char*)sh.X : (const char*)a.R + (int64_t)g * a.r_g * esz;
+        auto row_off = [&](int m) -> int64_t {
+            if (m >= a.M) m = 0;
+            if (!a.gather) return (int64_t)m * a.ldr * esz;
+            int64_t row;
+            if (a.idx) row = a.idx[(int64_t)g * a.hy.mu + m];
+            else row = (int64_t)(((unsigned long long)a.hy.k * (unsigned long long)a.hy.mu +
+                                  (unsigned long long)m) % (unsigned long long)sh.rows);
+            return row * sh.ld * esz;
+        };
+#pragma unroll
+        for (int i = 0; i < TL::PCH; ++i)
+            poff[i] = row_off(m0 + (tid + TL::NT * i) / TL::CPR) + ((tid + TL::NT * i) % TL::CPR) * 16;
+#pragma unroll
+        for (int i = 0; i < TL::QCH; ++i)
+            qoff[i] = row_off(n0 + (tid + TL::NT * i) / TL::CPR) + ((tid + TL::NT * i) % TL::CPR) * 16;
+    }
+    f32x16 acc[TL::TM][TL::TN];
+#pragma unroll
+    for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TL::TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    constexpr int kElems = TL::KROW / esz;
+    const int nk_all = (a.K + kElems - 1) / kElems;
+    // this split's k-tiles [k_lo, k_hi)
+    const int k_lo = (int)((int64_t)nk_all * sp / a.S), k_hi = (int)((int64_t)nk_all * (sp + 1) / a.S);
+    const int nk = k_hi - k_lo, last = k_hi - 1;
+    // The tile is small, so a k-tile is little MFMA work against a trip to memory: FOUR k-tiles
+    // are in flight in four register sets (two LDS stages).  Iteration kt requests tile kt+4 into
+    // the set tile kt came from, multiplies tile kt and moves tile kt+1 to the other stage.
+    // The loop body has no branches (the compiler then knows how many loads are outstanding at
+    // every wait and waits for the oldest only): the k-range is padded to a multiple of four
+    // tiles with tiles of zeros (loaded from the last tile's address, then cleared).
+    constexpr int NSET = 4;
+    u32x4 rp[NSET][TL::PCH], rq[NSET][TL::QCH];
+    auto gload = [&](int kt, u32x4 (&p)[TL::PCH], u32x4 (&q)[TL::QCH]) {
+        kt = kt <= last ? kt : last;
+#pragma unroll
+        for (int i = 0; i < TL::PCH; ++i) p[i] = global_load_vec(base + poff[i] + (int64_t)kt * TL::KROW);
+#pragma unroll
+        for (int i = 0; i < TL::QCH; ++i) q[i] = global_load_vec(base + qoff[i] + (int64_t)kt * TL::KROW);
+    };
+    // a tile past the range is cleared when it moves to LDS (not when it is loaded: that would
+    // make the wave wait for the load at once)
+    auto clear_if_past = [&](int kt, u32x4 (&p)[TL::PCH], u32x4 (&q)[TL::QCH]) {
+        const bool live = kt <= last;
+#pragma unroll
+        for (int i = 0; i < TL::PCH; ++i) p[i] = live ? p[i] : u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < TL::QCH; ++i) q[i] = live ? q[i] : u32x4{0, 0, 0, 0};
+    };
+    if (nk > 0) {
+#pragma unroll
+        for (int t = 0; t < NSET; ++t) gload(k_lo + t, rp[t], rq[t]);
+        tile_lstore<TL>(lds, lds + kP, rp[0], rq[0]);
+        __syncthreads();
+        for (int kt0 = k_lo; kt0 < k_hi; kt0 += NSET) {
+#pragma unroll
+            for (int t = 0; t < NSET; ++t) {
+                char* cur = lds + (t & 1) * TL::STAGE;
+                char* nxt = lds + ((t + 1) & 1) * TL::STAGE;
+                gload(kt0 + t + NSET, rp[t], rq[t]);
+                tile_mma<T, TL>(cur, cur + kP, acc);
+                clear_if_past(kt0 + t + 1, rp[(t + 1) % NSET], rq[(t + 1) % NSET]);
+                tile_lstore<TL>(nxt, nxt + kP, rp[(t + 1) % NSET], rq[(t + 1) % NSET]);
+                __syncthreads();
+            }
+        }
+    }
+    // accumulator element e of a lane: column n = lane % 32, row m = (e/4)*8 + (lane/32)*4 + e%4
+    constexpr int RW = TL::BM / TL::WM, CW = TL::BN / TL::WN;
+    const int cl = lane & 31, rh = (lane >> 5) * 4;
+    const int64_t kx_split = (int64_t)a.hy.G * a.M * a.ldk;
+    float* kx = a.KX + (int64_t)g * a.M * a.ldk;
+    double sq = 0;
+#pragma unroll
+    for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TL::TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
+                const int n = n0 + wn * CW + j * 32 + cl;
+                if (m < a.M && n < a.M) {
+                    const int64_t o = (int64_t)m * a.ldk + n;
+                    if constexpr (STAT) {
+                        float xs[kGramSplitX];
+#pragma unroll
+                        for (int q = 0; q < kGramSplitX; ++q) xs[q] = kx[q * kx_split + o];
+                        float x = xs[0];
+#pragma unroll
+                        for (int q = 1; q < kGramSplitX; ++q) x += xs[q];
+                        sq += (double)acc[i][j][e] * (double)x;
+                    } else {
+                        kx[sp * kx_split + o] = acc[i][j][e];
+                    }
+                }
+            }
+    if constexpr (STAT) {
+        if (bx > by) sq *= 2.0;               // the mirrored tile below the diagonal
+        sq = wave_sum(sq);
+        double* red = (double*)lds;           // every wave is past the last barrier of the k loop
+        if (lane == 0) red[wave] = sq;
+        __syncthreads();
+        if (tid == 0) {
+            double t = 0;
+#pragma unroll
+            for (int wv = 0; wv < TL::NW; ++wv) t += red[wv];
+            out[tile * a.S + sp] = t;
+        }
+        // the layer's remaining slots belong to the weight-gradient tiles of the other method
+        if (tile == 0 && sp == 0)
+            for (int q = ntile * a.S + tid; q < a.n_slots; q += TL::NT) out[q] = 0.0;
+    }
+}
+
+// dZd[g][s][n] = dZ[0][g][s][n] - dZ[1][g][s][n] (the signal of the fresh minus that of the stale
+// iterate), 16 bytes per thread; count = G * mu * ld elements, a multiple of 8.
+__global__ __launch_bounds__(256) void mlp_signal_diff(const bf16_t* __restrict__ z0, const bf16_t* __restrict__ z1,
+                                                       bf16_t* __restrict__ out, int64_t count)
+{
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (i >= count) return;
+    alignas(16) bf16_t p[8], q[8], r[8];
+    *(uint4*)p = *(const uint4*)(z0 + i);
+    *(uint4*)q = *(const uint4*)(z1 + i);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = to_T<bf16_t>(to_f<bf16_t>(p[e]) - to_f<bf16_t>(q[e]));
+    *(uint4*)(out + i) = *(const uint4*)r;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
@@ -1085,6 +1296,12 @@ struct MlpWork {
     int stat_off_w[GCADA_MAX_WIDTHS] = {}, stat_off_b[GCADA_MAX_WIDTHS] = {};
     int n_stat = 0, n_loss = 0;
     bool small = false;              // 64 x 64 GEMM tiles (small fp32 problems)
+    // first-layer statistic through Gram matrices (see mlp_gram)
+    bool gram_ok = false;            // shapes and type allow it and it is the cheaper way
+    bool gram_active = false;        // the last gradient stage used it
+    const int32_t* idx_last = nullptr;   // that stage's minibatch ids (for the second gather)
+    void* KX = nullptr;              // fp32 [G][mu][ldmu]
+    void* dZd = nullptr;             // T [G][mu][ld_1]
     size_t slack = 0;
     std::vector<void*> allocs;
 };
@@ -1163,6 +1380,22 @@ hipError_t mlp_plan(gcada_ctx* c)
         ns += (lay.n[l] + 7) / 8;
     }
     w->n_stat = ns;
+    // Gram statistic of the first layer: bf16 only (the statistic's tolerance there absorbs the
+    // rounding of the signal difference), when it needs at most half the flops of the two
+    // weight-gradient passes, and its tiles fit the layer's partial slots
+    {
+        const int64_t n0 = lay.n[0], n1 = lay.n[1];
+        const int gt = (mu + GramTile::BM - 1) / GramTile::BM;
+        if (w->bf16 && (int64_t)mu * (n0 + n1) <= n0 * n1 &&
+            gt * gt * kGramSplitZ <= dw_blocks<bf16_t>(lay.n[1], lay.n[0], false)) {
+            if ((e = walloc(w, &w->KX, (size_t)kGramSplitX * G * mu * lay.ldmu * sizeof(float))) != hipSuccess) return e;
+            if ((e = walloc(w, &w->dZd, (size_t)G * mu * lay.ld[1] * es)) != hipSuccess) return e;
+            constexpr int glds = 2 * GramTile::STAGE;
+            if ((e = hipFuncSetAttribute((const void*)mlp_gram<false>, hipFuncAttributeMaxDynamicSharedMemorySize, glds)) != hipSuccess) return e;
+            if ((e = hipFuncSetAttribute((const void*)mlp_gram<true>, hipFuncAttributeMaxDynamicSharedMemorySize, glds)) != hipSuccess) return e;
+            w->gram_ok = true;
+        }
+    }
     w->n_loss = w->bf16 ? head_row_blocks<bf16_t>(mu, w->small) : head_row_blocks<float>(mu, w->small);
     c->n_stat_part = std::max(c->n_stat_part, ns);
     c->n_loss_part = std::max(c->n_loss_part, w->n_loss);
@@ -1235,6 +1468,43 @@ static hipError_t launch_dw(gcada_ctx* c, int l, const Hyper& hy, const uint8_t*
     return launch_gemm<T, EPI_DW>(a, G, w->small, s);
 }
 
+// Statistic of the first layer's weights from the two Gram matrices (bf16).  First half: X X^T of
+// every group's minibatch.
+static hipError_t gram_minibatch(gcada_ctx* c, const int32_t* idx, hipStream_t s)
+{
+    MlpWork* w = c->mlp;
+    const Layout& lay = w->lay;
+    const int G = c->hy.G, mu = c->hy.mu;
+    constexpr int glds = 2 * GramTile::STAGE;
+    const int gt = (mu + GramTile::BM - 1) / GramTile::BM;
+    GramArgs a{};
+    a.hy = c->hy; a.M = mu; a.KX = (float*)w->KX; a.ldk = lay.ldmu;
+    a.K = lay.n[0]; a.gather = 1; a.shards = c->d_shards; a.idx = idx; a.S = kGramSplitX;
+    mlp_gram<false><<<dim3(gt, gt, G * kGramSplitX), GramTile::NT, glds, s>>>(a);
+    return hipGetLastError();
+}
+
+// Second half: signal difference, (dZ dZ^T) . (X X^T) summed per tile into the layer's partial slots.
+static hipError_t gram_statistic(gcada_ctx* c, hipStream_t s)
+{
+    MlpWork* w = c->mlp;
+    const Layout& lay = w->lay;
+    const int G = c->hy.G, mu = c->hy.mu;
+    const int64_t count = (int64_t)G * mu * lay.ld[1];
+    const bf16_t* z0 = (const bf16_t*)w->dZ[1];
+    mlp_signal_diff<<<(unsigned)((count / 8 + 255) / 256), 256, 0, s>>>(z0, z0 + count, (bf16_t*)w->dZd, count);
+    constexpr int glds = 2 * GramTile::STAGE;
+    const int gt = (mu + GramTile::BM - 1) / GramTile::BM;
+    GramArgs a{};
+    a.hy = c->hy; a.M = mu; a.KX = (float*)w->KX; a.ldk = lay.ldmu;
+    a.K = lay.n[1]; a.gather = 0; a.R = w->dZd; a.r_g = (int64_t)mu * lay.ld[1]; a.ldr = lay.ld[1];
+    a.S = kGramSplitZ;
+    a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[1];
+    a.n_slots = w->stat_off_b[1] - w->stat_off_w[1];
+    mlp_gram<true><<<dim3(gt, gt, G * kGramSplitZ), GramTile::NT, glds, s>>>(a);
+    return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t s)
 {
@@ -1251,9 +1521,16 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     for (const auto& sd : c->shards)
         if ((sd.ld * (int64_t)sizeof(T)) % 16 || ((uintptr_t)sd.X % 16)) vec_ok = false;
     const bool in_place = vec_ok && (lay.n[0] * (int)sizeof(T)) % TileOf<T, EPI_FWD, false>::type::KROW == 0;
+    // first-layer statistic through Gram matrices: then only the groups that store their
+    // gradient in this stage need the transposed minibatch
+    const bool gram = w->gram_ok && c->allow_gram && c->lazy_store && !hy.sel && in_place;
+    w->gram_active = gram;
+    w->idx_last = idx;
+    Hyper hy_store = hy;                     // "selected" = writes its gradient in this stage
+    hy_store.sel = c->store_now;
     if (vec_ok) {
         dim3 grid((lay.n[0] + 8 * V - 1) / (8 * V), (mu + 63) / 64, G);
-        mlp_gather_vec<T><<<grid, 256, 0, s>>>(hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
+        mlp_gather_vec<T><<<grid, 256, 0, s>>>(gram ? hy_store : hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
                                                 in_place ? nullptr : (T*)w->Xg, (T*)w->XgT);
     } else {
         dim3 grid((lay.n[0] + 63) / 64, (mu + 63) / 64, G);
@@ -1288,9 +1565,17 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     }
     // 3. backward, layer by layer
     for (int l = L; l >= 1; --l) {
-        // weight gradient of layer l, both iterates in one workgroup
-        if ((e = launch_dw<T>(c, l, hy, c->lazy_store && !hy.sel ? c->store_now : nullptr, s)) != hipSuccess)
-            return e;
+        if (l == 1 && gram) {
+            // X X^T directly before its reader: the matrices are then still in the caches
+            if ((e = gram_minibatch(c, idx, s)) != hipSuccess) return e;
+            if ((e = gram_statistic(c, s)) != hipSuccess) return e;
+            // the gradient itself, one pass at theta^k, for the groups that store it now
+            if ((e = launch_dw<T>(c, 1, hy_store, nullptr, s)) != hipSuccess) return e;
+        } else {
+            // weight gradient of layer l, both iterates in one workgroup
+            if ((e = launch_dw<T>(c, l, hy, c->lazy_store && !hy.sel ? c->store_now : nullptr, s)) != hipSuccess)
+                return e;
+        }
         {
             dim3 grid((lay.n[l] + 7) / 8, G);
             mlp_bias_grad<T><<<grid, 256, 0, s>>>(hy, lay.n[l], lay.ldmu, (const T*)w->dZT[l], tr_it(l),
@@ -1327,6 +1612,14 @@ hipError_t mlp_store_selected(gcada_ctx* c, hipStream_t s)
 {
     Hyper hy = c->hy;
     hy.sel = c->redo;
+    if (c->mlp->gram_active) {
+        // their transposed minibatch has not been gathered yet (bf16, 16-byte rows: see the
+        // conditions of the Gram statistic)
+        const Layout& lay = c->mlp->lay;
+        dim3 grid((lay.n[0] + 63) / 64, (hy.mu + 63) / 64, hy.G);
+        mlp_gather_vec<bf16_t><<<grid, 256, 0, s>>>(hy, c->d_shards, c->mlp->idx_last, lay.n[0], lay.ld[0],
+                                                     lay.ldmu, nullptr, (bf16_t*)c->mlp->XgT);
+    }
     for (int l = c->mlp->lay.L; l >= 1; --l) {
         hipError_t e = c->mlp->bf16 ? launch_dw<bf16_t>(c, l, hy, nullptr, s) : launch_dw<float>(c, l, hy, nullptr, s);
         if (e != hipSuccess) return e;

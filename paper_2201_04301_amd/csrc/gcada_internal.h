@@ -197,6 +197,7 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool pr
 hipError_t server_select(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s);
 hipError_t lazy_flags(gcada_ctx* c, hipStream_t s);
 hipError_t mlp_store_selected(gcada_ctx* c, hipStream_t s);
+bool mlp_gram_active(const gcada_ctx* c);
 
 // server-side rule of Sec. IV (rule_kernels.hip)
 hipError_t rule_plan(gcada_ctx* c);

@@ -906,7 +906,7 @@ __global__ __launch_bounds__(256) void mlp_gather(Hyper hy, const ShardDesc* __r
             if (idx) row = idx[(int64_t)g * hy.mu + i];
             else row = (int64_t)(((unsigned long long)hy.k * (unsigned long long)hy.mu +
                                   (unsigned long long)i) % (unsigned long long)sh.rows);
-            v = X[row * sh.ld + c0 + tx];
+            v = global_load(X + row * sh.ld + c0 + tx);
             Xg[((int64_t)g * hy.mu + i) * ld0 + c0 + tx] = v;
         }
         tile[r][tx] = v;
@@ -945,7 +945,7 @@ __global__ __launch_bounds__(256) void mlp_gather_vec(Hyper hy, const ShardDesc*
             if (idx) row = idx[(int64_t)g * hy.mu + i];
             else row = (int64_t)(((unsigned long long)hy.k * (unsigned long long)hy.mu +
                                   (unsigned long long)i) % (unsigned long long)sh.rows);
-            *(uint4*)v = *(const uint4*)(X + row * sh.ld + col);
+            *(u32x4*)v = global_load_vec((const char*)(X + row * sh.ld + col));
             if (Xg) *(uint4*)(Xg + ((int64_t)g * hy.mu + i) * ld0 + col) = *(const uint4*)v;
         }
 #pragma unroll
@@ -1598,6 +1598,9 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     c->n_loss_used = G * w->n_loss;
     return hipGetLastError();
 }
+
+// whether the last gradient stage took the first layer's statistic from the Gram matrices
+bool mlp_gram_active(const gcada_ctx* c) { return c->mlp && c->mlp->gram_active; }
 
 hipError_t mlp_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
 {

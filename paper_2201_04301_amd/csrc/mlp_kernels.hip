@@ -830,8 +830,9 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
 }
 
 // Tile shapes.  bf16: 256 x 256 tiles with eight waves and two k-tiles in flight for the forward
-// and signal GEMMs and for the weight gradients, 128 x 128 with short k-tiles for the output
-// layer.
+// and signal GEMMs and for the weight gradients (128 x 256 tiles with two workgroups per compute
+// unit -- the seventh Tile parameter -- were measured slower), 64 x 128 for the output layer, whose
+// k loop is a chain of memory round trips.
 // fp32: square tiles with 32 floats of k.
 // SMALL: fp32 problems whose 128 x 128 tiles would leave most of the device idle (fp32 MFMA is
 // slow enough that a workgroup's k loop is arithmetic-bound) use 64 x 64 tiles instead.

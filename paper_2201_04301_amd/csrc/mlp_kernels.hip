@@ -1086,43 +1086,84 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
 // 4 mu n0 n1 (six times fewer for 3072-1024 at mu = 256), and no gradient is formed for a group
 // that does not upload (paper Eq. (9): the statistic only decides; Sec. IV: only uploads enter
 // the aggregate).
-constexpr int kGramSplitX = 2, kGramSplitZ = 1;   // workgroups per tile of X X^T and of dZ dZ^T
+// One kernel forms a tile of both matrices in two accumulator sets and reduces their elementwise
+// product; nothing mu x mu travels through memory.  The sum is bilinear, so the contraction of
+// X X^T may be split over several workgroups (each also forms the whole dZ dZ^T tile, the cheaper
+// of the two) and their partial statistics simply add up.
+constexpr int kGramSplit = 1;      // workgroups per tile (shares of the X X^T contraction; more were measured slower)
 
 struct GramArgs {
     Hyper hy;
-    int M, K;                      // rows (the minibatch size) and contraction length in elements
-    // rows of the operand: the minibatch rows of the group's shard in place (gather != 0), or
-    // R + g * r_g + row * ldr
-    int gather;
-    const ShardDesc* shards; const int32_t* idx;
-    const void* R; int64_t r_g; int ldr;
-    int S;                         // the contraction is split over S workgroups per tile
-    float* KX; int ldk;            // kGramSplitX partial matrices [split][G][M][ldk]: written by the
-                                   // first kernel (its S), added up in a fixed order by the second
-    double* part_stat; int n_stat, stat_off, n_slots;   // second kernel: one partial per tile and
-                                                         // split, the layer's other slots are cleared
+    int M;                         // rows: the minibatch size
+    int KX, KZ;                    // contraction lengths in elements: n0 and n1
+    const ShardDesc* shards; const int32_t* idx;     // X: the minibatch rows of the shard, in place
+    const void* dZd; int64_t z_g; int ldz;           // dZ: dZd + g * z_g + row * ldz
+    double* part_stat; int n_stat, stat_off, n_slots;   // one partial per tile and share; the
+                                                         // layer's other slots are cleared
 };
 
 using GramTile = Tile<128, 128, 64, 2, 2, 2>;
 
-// grid: (ceil(M/128), ceil(M/128), G * S).  Both matrices are symmetric: tiles below the diagonal
-// do nothing, tiles above it count twice.
-// STAT = false: KX[split][g] <- the split's share of rows rows^T.
-// STAT = true:  partial statistic <- sum over the tile of (the split's share of rows rows^T)[m][n]
-//               * (sum over the SX partial matrices KX[.][g][m][n])  -- the product is linear in
-//               either factor, so the splits' partial statistics simply add up.
-template <bool STAT>
+// acc += rows[m0..] rows[n0..]^T over the k-tiles [k_lo, k_hi) of 32 elements; rows at base + off.
+// The tile is small, so a k-tile is little MFMA work against a trip to memory: FOUR k-tiles are in
+// flight in four register sets (two LDS stages).  Iteration kt requests tile kt+4 into the set
+// tile kt came from, multiplies tile kt and moves tile kt+1 to the other stage.  The loop body
+// has no branches (the compiler then knows how many loads are outstanding at every wait and
+// waits for the oldest only): the k-range is padded to a multiple of four tiles with tiles that
+// are cleared on their way to LDS (not when they are loaded: that would wait for the load).
+__device__ __forceinline__ void gram_loop(const char* base, const int64_t (&poff)[GramTile::PCH],
+                                          const int64_t (&qoff)[GramTile::QCH], int k_lo, int k_hi, char* lds,
+                                          f32x16 (&acc)[GramTile::TM][GramTile::TN])
+{
+    using TL = GramTile;
+    constexpr int kP = TL::BM * TL::PITCH, NSET = 4;
+    if (k_hi <= k_lo) return;                    // uniform
+    const int last = k_hi - 1;
+    u32x4 rp[NSET][TL::PCH], rq[NSET][TL::QCH];
+    auto gload = [&](int kt, u32x4 (&p)[TL::PCH], u32x4 (&q)[TL::QCH]) {
+        kt = kt <= last ? kt : last;
+#pragma unroll
+        for (int i = 0; i < TL::PCH; ++i) p[i] = global_load_vec(base + poff[i] + (int64_t)kt * TL::KROW);
+#pragma unroll
+        for (int i = 0; i < TL::QCH; ++i) q[i] = global_load_vec(base + qoff[i] + (int64_t)kt * TL::KROW);
+    };
+    auto clear_if_past = [&](int kt, u32x4 (&p)[TL::PCH], u32x4 (&q)[TL::QCH]) {
+        const bool live = kt <= last;
+#pragma unroll
+        for (int i = 0; i < TL::PCH; ++i) p[i] = live ? p[i] : u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < TL::QCH; ++i) q[i] = live ? q[i] : u32x4{0, 0, 0, 0};
+    };
+#pragma unroll
+    for (int t = 0; t < NSET; ++t) gload(k_lo + t, rp[t], rq[t]);
+    tile_lstore<TL>(lds, lds + kP, rp[0], rq[0]);
+    __syncthreads();
+    for (int kt0 = k_lo; kt0 < k_hi; kt0 += NSET) {
+#pragma unroll
+        for (int t = 0; t < NSET; ++t) {
+            char* cur = lds + (t & 1) * TL::STAGE;
+            char* nxt = lds + ((t + 1) & 1) * TL::STAGE;
+            gload(kt0 + t + NSET, rp[t], rq[t]);
+            tile_mma<bf16_t, TL>(cur, cur + kP, acc);
+            clear_if_past(kt0 + t + 1, rp[(t + 1) % NSET], rq[(t + 1) % NSET]);
+            tile_lstore<TL>(nxt, nxt + kP, rp[(t + 1) % NSET], rq[(t + 1) % NSET]);
+            __syncthreads();
+        }
+    }
+}
+
+// grid: (ceil(M/128), ceil(M/128), G * kGramSplit).  Both matrices are symmetric: tiles below the
+// diagonal do nothing, tiles above it count twice.
 __global__ __launch_bounds__(GramTile::NT) void mlp_gram(GramArgs a)
 {
     using TL = GramTile;
-    using T = bf16_t;
     extern __shared__ __align__(16) char lds[];
-    constexpr int esz = 2, kP = TL::BM * TL::PITCH;
+    constexpr int esz = 2;
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int wm = wave / TL::WN, wn = wave % TL::WN;
-    // Workgroup -> (tile, group, split).  Consecutive workgroup ids go to different XCDs (id mod
+    // Workgroup -> (tile, group, share).  Consecutive workgroup ids go to different XCDs (id mod
     // 8), each with its own L2: the ids of one XCD are mapped to a contiguous range of work, so
-    // that the tiles of one (group, split) -- which read the same rows -- share an L2.
+    // that the tiles of one (group, share) -- which read the same rows -- meet in one L2.
     int bx, by, bz;
     {
         const int gx = gridDim.x, gy = gridDim.y, total = gx * gy * gridDim.z;
@@ -1132,23 +1173,29 @@ __global__ __launch_bounds__(GramTile::NT) void mlp_gram(GramArgs a)
         by = lin % gy;
         bz = lin / gy;
     }
-    const int g = bz / a.S, sp = bz % a.S;
+    const int g = bz / kGramSplit, sp = bz % kGramSplit;
     const int tile = by * gridDim.x + bx, ntile = gridDim.x * gridDim.y;
-    double* out = STAT ? a.part_stat + (int64_t)g * a.n_stat + a.stat_off : nullptr;
+    double* out = a.part_stat + (int64_t)g * a.n_stat + a.stat_off;
     if (bx < by) {
-        if (STAT && tid == 0) out[tile * a.S + sp] = 0.0;
+        if (tid == 0) out[tile * kGramSplit + sp] = 0.0;
         return;
     }
     const int m0 = by * TL::BM, n0 = bx * TL::BN;
-    // byte offsets of the rows this thread's chunks belong to (rows past M: row 0, result unused)
-    const char* base;
+    f32x16 accx[TL::TM][TL::TN], accz[TL::TM][TL::TN];
+#pragma unroll
+    for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TL::TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { accx[i][j][e] = 0.0f; accz[i][j][e] = 0.0f; }
+    constexpr int kElems = TL::KROW / esz;
     int64_t poff[TL::PCH], qoff[TL::QCH];
     {
-        const ShardDesc sh = a.gather ? a.shards[g] : ShardDesc{};
-        base = a.gather ? (const char*)sh.X : (const char*)a.R + (int64_t)g * a.r_g * esz;
+        // X X^T, this share of the contraction: the minibatch rows of the shard (rows past M: row 0
+        // of the minibatch, result unused)
+        const ShardDesc sh = a.shards[g];
         auto row_off = [&](int m) -> int64_t {
             if (m >= a.M) m = 0;
-            if (!a.gather) return (int64_t)m * a.ldr * esz;
             int64_t row;
             if (a.idx) row = a.idx[(int64_t)g * a.hy.mu + m];
             else row = (int64_t)(((unsigned long long)a.hy.k * (unsigned long long)a.hy.mu +
@@ -1161,66 +1208,25 @@ __global__ __launch_bounds__(GramTile::NT) void mlp_gram(GramArgs a)
 #pragma unroll
         for (int i = 0; i < TL::QCH; ++i)
             qoff[i] = row_off(n0 + (tid + TL::NT * i) / TL::CPR) + ((tid + TL::NT * i) % TL::CPR) * 16;
+        const int nk = (a.KX + kElems - 1) / kElems;
+        gram_loop((const char*)sh.X, poff, qoff, (int)((int64_t)nk * sp / kGramSplit),
+                  (int)((int64_t)nk * (sp + 1) / kGramSplit), lds, accx);
     }
-    f32x16 acc[TL::TM][TL::TN];
+    {
+        // dZ dZ^T, whole
+        auto row_off = [&](int m) -> int64_t { return (int64_t)(m < a.M ? m : 0) * a.ldz * esz; };
 #pragma unroll
-    for (int i = 0; i < TL::TM; ++i)
+        for (int i = 0; i < TL::PCH; ++i)
+            poff[i] = row_off(m0 + (tid + TL::NT * i) / TL::CPR) + ((tid + TL::NT * i) % TL::CPR) * 16;
 #pragma unroll
-        for (int j = 0; j < TL::TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-    constexpr int kElems = TL::KROW / esz;
-    const int nk_all = (a.K + kElems - 1) / kElems;
-    // this split's k-tiles [k_lo, k_hi)
-    const int k_lo = (int)((int64_t)nk_all * sp / a.S), k_hi = (int)((int64_t)nk_all * (sp + 1) / a.S);
-    const int nk = k_hi - k_lo, last = k_hi - 1;
-    // The tile is small, so a k-tile is little MFMA work against a trip to memory: FOUR k-tiles
-    // are in flight in four register sets (two LDS stages).  Iteration kt requests tile kt+4 into
-    // the set tile kt came from, multiplies tile kt and moves tile kt+1 to the other stage.
-    // The loop body has no branches (the compiler then knows how many loads are outstanding at
-    // every wait and waits for the oldest only): the k-range is padded to a multiple of four
-    // tiles with tiles of zeros (loaded from the last tile's address, then cleared).
-    constexpr int NSET = 4;
-    u32x4 rp[NSET][TL::PCH], rq[NSET][TL::QCH];
-    auto gload = [&](int kt, u32x4 (&p)[TL::PCH], u32x4 (&q)[TL::QCH]) {
-        kt = kt <= last ? kt : last;
-#pragma unroll
-        for (int i = 0; i < TL::PCH; ++i) p[i] = global_load_vec(base + poff[i] + (int64_t)kt * TL::KROW);
-#pragma unroll
-        for (int i = 0; i < TL::QCH; ++i) q[i] = global_load_vec(base + qoff[i] + (int64_t)kt * TL::KROW);
-    };
-    // a tile past the range is cleared when it moves to LDS (not when it is loaded: that would
-    // make the wave wait for the load at once)
-    auto clear_if_past = [&](int kt, u32x4 (&p)[TL::PCH], u32x4 (&q)[TL::QCH]) {
-        const bool live = kt <= last;
-#pragma unroll
-        for (int i = 0; i < TL::PCH; ++i) p[i] = live ? p[i] : u32x4{0, 0, 0, 0};
-#pragma unroll
-        for (int i = 0; i < TL::QCH; ++i) q[i] = live ? q[i] : u32x4{0, 0, 0, 0};
-    };
-    if (nk > 0) {
-#pragma unroll
-        for (int t = 0; t < NSET; ++t) gload(k_lo + t, rp[t], rq[t]);
-        tile_lstore<TL>(lds, lds + kP, rp[0], rq[0]);
-        __syncthreads();
-        for (int kt0 = k_lo; kt0 < k_hi; kt0 += NSET) {
-#pragma unroll
-            for (int t = 0; t < NSET; ++t) {
-                char* cur = lds + (t & 1) * TL::STAGE;
-                char* nxt = lds + ((t + 1) & 1) * TL::STAGE;
-                gload(kt0 + t + NSET, rp[t], rq[t]);
-                tile_mma<T, TL>(cur, cur + kP, acc);
-                clear_if_past(kt0 + t + 1, rp[(t + 1) % NSET], rq[(t + 1) % NSET]);
-                tile_lstore<TL>(nxt, nxt + kP, rp[(t + 1) % NSET], rq[(t + 1) % NSET]);
-                __syncthreads();
-            }
-        }
+        for (int i = 0; i < TL::QCH; ++i)
+            qoff[i] = row_off(n0 + (tid + TL::NT * i) / TL::CPR) + ((tid + TL::NT * i) % TL::CPR) * 16;
+        const int nk = (a.KZ + kElems - 1) / kElems;
+        gram_loop((const char*)a.dZd + (int64_t)g * a.z_g * esz, poff, qoff, 0, nk, lds, accz);
     }
     // accumulator element e of a lane: column n = lane % 32, row m = (e/4)*8 + (lane/32)*4 + e%4
     constexpr int RW = TL::BM / TL::WM, CW = TL::BN / TL::WN;
     const int cl = lane & 31, rh = (lane >> 5) * 4;
-    const int64_t kx_split = (int64_t)a.hy.G * a.M * a.ldk;
-    float* kx = a.KX + (int64_t)g * a.M * a.ldk;
     double sq = 0;
 #pragma unroll
     for (int i = 0; i < TL::TM; ++i)
@@ -1230,37 +1236,22 @@ __global__ __launch_bounds__(GramTile::NT) void mlp_gram(GramArgs a)
             for (int e = 0; e < 16; ++e) {
                 const int m = m0 + wm * RW + i * 32 + (e >> 2) * 8 + rh + (e & 3);
                 const int n = n0 + wn * CW + j * 32 + cl;
-                if (m < a.M && n < a.M) {
-                    const int64_t o = (int64_t)m * a.ldk + n;
-                    if constexpr (STAT) {
-                        float xs[kGramSplitX];
-#pragma unroll
-                        for (int q = 0; q < kGramSplitX; ++q) xs[q] = kx[q * kx_split + o];
-                        float x = xs[0];
-#pragma unroll
-                        for (int q = 1; q < kGramSplitX; ++q) x += xs[q];
-                        sq += (double)acc[i][j][e] * (double)x;
-                    } else {
-                        kx[sp * kx_split + o] = acc[i][j][e];
-                    }
-                }
+                if (m < a.M && n < a.M) sq += (double)accx[i][j][e] * (double)accz[i][j][e];
             }
-    if constexpr (STAT) {
-        if (bx > by) sq *= 2.0;               // the mirrored tile below the diagonal
-        sq = wave_sum(sq);
-        double* red = (double*)lds;           // every wave is past the last barrier of the k loop
-        if (lane == 0) red[wave] = sq;
-        __syncthreads();
-        if (tid == 0) {
-            double t = 0;
+    if (bx > by) sq *= 2.0;                       // the mirrored tile below the diagonal
+    sq = wave_sum(sq);
+    double* red = (double*)lds;                   // every wave is past the last barrier of the k loops
+    if (lane == 0) red[wave] = sq;
+    __syncthreads();
+    if (tid == 0) {
+        double t = 0;
 #pragma unroll
-            for (int wv = 0; wv < TL::NW; ++wv) t += red[wv];
-            out[tile * a.S + sp] = t;
-        }
-        // the layer's remaining slots belong to the weight-gradient tiles of the other method
-        if (tile == 0 && sp == 0)
-            for (int q = ntile * a.S + tid; q < a.n_slots; q += TL::NT) out[q] = 0.0;
+        for (int wv = 0; wv < TL::NW; ++wv) t += red[wv];
+        out[tile * kGramSplit + sp] = t;
     }
+    // the layer's remaining slots belong to the weight-gradient tiles of the other method
+    if (tile == 0 && sp == 0)
+        for (int q = ntile * kGramSplit + tid; q < a.n_slots; q += TL::NT) out[q] = 0.0;
 }
 
 // dZd[g][s][n] = dZ[0][g][s][n] - dZ[1][g][s][n] (the signal of the fresh minus that of the stale
@@ -1301,7 +1292,6 @@ struct MlpWork {
     bool gram_ok = false;            // shapes and type allow it and it is the cheaper way
     bool gram_active = false;        // the last gradient stage used it
     const int32_t* idx_last = nullptr;   // that stage's minibatch ids (for the second gather)
-    void* KX = nullptr;              // fp32 [G][mu][ldmu]
     void* dZd = nullptr;             // T [G][mu][ld_1]
     size_t slack = 0;
     std::vector<void*> allocs;
@@ -1388,12 +1378,10 @@ hipError_t mlp_plan(gcada_ctx* c)
         const int64_t n0 = lay.n[0], n1 = lay.n[1];
         const int gt = (mu + GramTile::BM - 1) / GramTile::BM;
         if (w->bf16 && (int64_t)mu * (n0 + n1) <= n0 * n1 &&
-            gt * gt * kGramSplitZ <= dw_blocks<bf16_t>(lay.n[1], lay.n[0], false)) {
-            if ((e = walloc(w, &w->KX, (size_t)kGramSplitX * G * mu * lay.ldmu * sizeof(float))) != hipSuccess) return e;
+            gt * gt * kGramSplit <= dw_blocks<bf16_t>(lay.n[1], lay.n[0], false)) {
             if ((e = walloc(w, &w->dZd, (size_t)G * mu * lay.ld[1] * es)) != hipSuccess) return e;
             constexpr int glds = 2 * GramTile::STAGE;
-            if ((e = hipFuncSetAttribute((const void*)mlp_gram<false>, hipFuncAttributeMaxDynamicSharedMemorySize, glds)) != hipSuccess) return e;
-            if ((e = hipFuncSetAttribute((const void*)mlp_gram<true>, hipFuncAttributeMaxDynamicSharedMemorySize, glds)) != hipSuccess) return e;
+            if ((e = hipFuncSetAttribute((const void*)mlp_gram, hipFuncAttributeMaxDynamicSharedMemorySize, glds)) != hipSuccess) return e;
             w->gram_ok = true;
         }
     }
@@ -1469,24 +1457,10 @@ static hipError_t launch_dw(gcada_ctx* c, int l, const Hyper& hy, const uint8_t*
     return launch_gemm<T, EPI_DW>(a, G, w->small, s);
 }
 
-// Statistic of the first layer's weights from the two Gram matrices (bf16).  First half: X X^T of
-// every group's minibatch.
-static hipError_t gram_minibatch(gcada_ctx* c, const int32_t* idx, hipStream_t s)
-{
-    MlpWork* w = c->mlp;
-    const Layout& lay = w->lay;
-    const int G = c->hy.G, mu = c->hy.mu;
-    constexpr int glds = 2 * GramTile::STAGE;
-    const int gt = (mu + GramTile::BM - 1) / GramTile::BM;
-    GramArgs a{};
-    a.hy = c->hy; a.M = mu; a.KX = (float*)w->KX; a.ldk = lay.ldmu;
-    a.K = lay.n[0]; a.gather = 1; a.shards = c->d_shards; a.idx = idx; a.S = kGramSplitX;
-    mlp_gram<false><<<dim3(gt, gt, G * kGramSplitX), GramTile::NT, glds, s>>>(a);
-    return hipGetLastError();
-}
-
-// Second half: signal difference, (dZ dZ^T) . (X X^T) summed per tile into the layer's partial slots.
-static hipError_t gram_statistic(gcada_ctx* c, hipStream_t s)
+// Statistic of the first layer's weights from the two Gram matrices (bf16): the signal
+// difference, then one kernel that forms both matrices tile by tile and sums their product into
+// the layer's partial slots.
+static hipError_t gram_statistic(gcada_ctx* c, const int32_t* idx, hipStream_t s)
 {
     MlpWork* w = c->mlp;
     const Layout& lay = w->lay;
@@ -1497,12 +1471,12 @@ static hipError_t gram_statistic(gcada_ctx* c, hipStream_t s)
     constexpr int glds = 2 * GramTile::STAGE;
     const int gt = (mu + GramTile::BM - 1) / GramTile::BM;
     GramArgs a{};
-    a.hy = c->hy; a.M = mu; a.KX = (float*)w->KX; a.ldk = lay.ldmu;
-    a.K = lay.n[1]; a.gather = 0; a.R = w->dZd; a.r_g = (int64_t)mu * lay.ld[1]; a.ldr = lay.ld[1];
-    a.S = kGramSplitZ;
+    a.hy = c->hy; a.M = mu; a.KX = lay.n[0]; a.KZ = lay.n[1];
+    a.shards = c->d_shards; a.idx = idx;
+    a.dZd = w->dZd; a.z_g = (int64_t)mu * lay.ld[1]; a.ldz = lay.ld[1];
     a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[1];
     a.n_slots = w->stat_off_b[1] - w->stat_off_w[1];
-    mlp_gram<true><<<dim3(gt, gt, G * kGramSplitZ), GramTile::NT, glds, s>>>(a);
+    mlp_gram<<<dim3(gt, gt, G * kGramSplit), GramTile::NT, glds, s>>>(a);
     return hipGetLastError();
 }
 
@@ -1567,9 +1541,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     // 3. backward, layer by layer
     for (int l = L; l >= 1; --l) {
         if (l == 1 && gram) {
-            // X X^T directly before its reader: the matrices are then still in the caches
-            if ((e = gram_minibatch(c, idx, s)) != hipSuccess) return e;
-            if ((e = gram_statistic(c, s)) != hipSuccess) return e;
+            if ((e = gram_statistic(c, idx, s)) != hipSuccess) return e;
             // the gradient itself, one pass at theta^k, for the groups that store it now
             if ((e = launch_dw<T>(c, 1, hy_store, nullptr, s)) != hipSuccess) return e;
         } else {

@@ -1255,18 +1255,59 @@ __global__ __launch_bounds__(GramTile::NT) void mlp_gram(GramArgs a)
 }
 
 // dZd[g][s][n] = dZ[0][g][s][n] - dZ[1][g][s][n] (the signal of the fresh minus that of the stale
-// iterate), 16 bytes per thread; count = G * mu * ld elements, a multiple of 8.
-__global__ __launch_bounds__(256) void mlp_signal_diff(const bf16_t* __restrict__ z0, const bf16_t* __restrict__ z1,
-                                                       bf16_t* __restrict__ out, int64_t count)
+// iterate), and -- the same read -- the first layer's bias gradient: its fresh value
+// sum_s dZ[0][g][s][n] goes to the group's fresh row, the squared difference of the two iterates'
+// sums into the layer's bias slots of the statistic.
+// grid: (ld / 64, G), block 256 = 8 column chunks of 8 x 32 row lanes; ld a multiple of 64.
+__global__ __launch_bounds__(256) void mlp_signal_diff_bias(Hyper hy, int n1, int ld, const bf16_t* __restrict__ z0,
+                                                            const bf16_t* __restrict__ z1, bf16_t* __restrict__ out,
+                                                            float* __restrict__ gbuf, const int32_t* __restrict__ which,
+                                                            int64_t boff, double* __restrict__ part_stat, int n_stat,
+                                                            int stat_off, int n_slots)
 {
-    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
-    if (i >= count) return;
-    alignas(16) bf16_t p[8], q[8], r[8];
-    *(uint4*)p = *(const uint4*)(z0 + i);
-    *(uint4*)q = *(const uint4*)(z1 + i);
+    __shared__ float s_f[32][64 + 1], s_d[32][64 + 1];
+    const int g = blockIdx.y, cb = blockIdx.x;
+    const int chunk = threadIdx.x % 8, rl = threadIdx.x / 8;
+    const int64_t base = (int64_t)g * hy.mu * ld + cb * 64 + chunk * 8;
+    float fs[8], ds[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = to_T<bf16_t>(to_f<bf16_t>(p[e]) - to_f<bf16_t>(q[e]));
-    *(uint4*)(out + i) = *(const uint4*)r;
+    for (int e = 0; e < 8; ++e) fs[e] = ds[e] = 0.0f;
+    for (int r = rl; r < hy.mu; r += 32) {
+        alignas(16) bf16_t p[8], q[8], d[8];
+        *(uint4*)p = *(const uint4*)(z0 + base + (int64_t)r * ld);
+        *(uint4*)q = *(const uint4*)(z1 + base + (int64_t)r * ld);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float a = to_f<bf16_t>(p[e]);
+            d[e] = to_T<bf16_t>(a - to_f<bf16_t>(q[e]));
+            fs[e] += a;
+            // the difference of the bias gradients sums the two signals themselves (what the
+            // weight-gradient route adds up too), not the rounded difference
+            ds[e] += a - to_f<bf16_t>(q[e]);
+        }
+        *(uint4*)(out + base + (int64_t)r * ld) = *(const uint4*)d;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { s_f[rl][chunk * 8 + e] = fs[e]; s_d[rl][chunk * 8 + e] = ds[e]; }
+    __syncthreads();
+    double sq = 0;
+    if (threadIdx.x < 64) {
+        float f = 0.0f, d = 0.0f;
+        for (int r = 0; r < 32; ++r) { f += s_f[r][threadIdx.x]; d += s_d[r][threadIdx.x]; }   // fixed order
+        const int n = cb * 64 + threadIdx.x;
+        if (n < n1) {
+            fresh_row(gbuf, which, hy, g)[boff + n] = f;
+            sq = (double)d * (double)d;
+        }
+    }
+    if (threadIdx.x < kWave) {
+        sq = wave_sum(sq);
+        double* slots = part_stat + (int64_t)g * n_stat + stat_off;
+        if (threadIdx.x == 0) slots[cb] = sq;
+        // the layer's remaining bias slots belong to the blocks of the other method
+        if (cb == 0)
+            for (int q = gridDim.x + threadIdx.x; q < n_slots; q += kWave) slots[q] = 0.0;
+    }
 }
 
 }  // namespace
@@ -1467,7 +1508,9 @@ static hipError_t gram_statistic(gcada_ctx* c, const int32_t* idx, hipStream_t s
     const int G = c->hy.G, mu = c->hy.mu;
     const int64_t count = (int64_t)G * mu * lay.ld[1];
     const bf16_t* z0 = (const bf16_t*)w->dZ[1];
-    mlp_signal_diff<<<(unsigned)((count / 8 + 255) / 256), 256, 0, s>>>(z0, z0 + count, (bf16_t*)w->dZd, count);
+    mlp_signal_diff_bias<<<dim3(lay.ld[1] / 64, G), 256, 0, s>>>(c->hy, lay.n[1], lay.ld[1], z0, z0 + count, (bf16_t*)w->dZd,
+                                                              c->gbuf, c->which, lay.boff[1], c->part_stat, w->n_stat,
+                                                              w->stat_off_b[1], (lay.n[1] + 7) / 8);
     constexpr int glds = 2 * GramTile::STAGE;
     const int gt = (mu + GramTile::BM - 1) / GramTile::BM;
     GramArgs a{};
@@ -1549,7 +1592,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             if ((e = launch_dw<T>(c, l, hy, c->lazy_store && !hy.sel ? c->store_now : nullptr, s)) != hipSuccess)
                 return e;
         }
-        {
+        if (!(l == 1 && gram)) {       // (with the Gram statistic the signal-difference kernel does it)
             dim3 grid((lay.n[l] + 7) / 8, G);
             mlp_bias_grad<T><<<grid, 256, 0, s>>>(hy, lay.n[l], lay.ldmu, (const T*)w->dZT[l], tr_it(l),
                                                    tr_g(l), c->gbuf, c->which, lay.boff[l], c->part_stat, w->n_stat,

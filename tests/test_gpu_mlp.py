@@ -186,7 +186,7 @@ def test_mlp_gram_statistic_parity(par, widths, mu, G, rows, steps, tol):
 def test_mlp_gram_statistic_matches_weight_gradient_statistic():
     # same run with the statistic from the Gram matrices and from the two weight gradients: the
     # statistics agree to bf16 rounding of the signal difference, the masks wherever the
-    # statistic is not within that of the threshold, the uploaded gradients bit for bit
+    # statistic is not within that of the threshold, the uploaded gradients to fp32 rounding
     from paper_2201_04301_amd import Gcada, binding as B
     from gcada_inputs import make_theta0
     w = scaled(CONFIGS["mlp_3072_bf16"], name="mlp_gram", widths=(512, 256, 10), mu=96, G=6, rows=300, D=4, c=0.6)
@@ -226,5 +226,8 @@ def test_mlp_gram_statistic_matches_weight_gradient_statistic():
                     assert abs(a["stat"][g] - a["rhs"]) <= 2e-2 * a["rhs"]
                     differing += 1
                 elif a["mask"][g]:
-                    np.testing.assert_array_equal(b["grad"][g], a["grad"][g])
+                    # the same weight gradients; the first layer's bias gradient is summed in another
+                    # order by the kernel that forms the signal difference (fp32 rounding)
+                    np.testing.assert_allclose(b["grad"][g], a["grad"][g], rtol=2e-6,
+                                               atol=1e-6 * np.abs(a["grad"][g]).max())
         _say("masks that differ at the threshold:", differing)

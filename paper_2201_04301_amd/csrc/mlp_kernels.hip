@@ -829,6 +829,41 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
     }
 }
 
+// The weight gradients at theta^k of the groups in hy.sel, all layers in ONE launch (the second
+// half of the lazy gradient store: most of the time nobody is selected and three launches that
+// do nothing would cost more than one).
+// grid: (tiles of all layers together, 1, G); a workgroup of an unselected group leaves at once.
+struct DwSelectedArgs {
+    GemmArgs layer[GCADA_MAX_WIDTHS - 1];
+    int tile_end[GCADA_MAX_WIDTHS - 1];    // running totals of the layers' tile counts
+    int n_layers;
+};
+static_assert(sizeof(DwSelectedArgs) <= 4096, "kernel arguments");
+
+template <typename T, typename TL>
+__global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_dw_selected(DwSelectedArgs s)
+{
+    extern __shared__ __align__(16) char lds[];
+    const int g = blockIdx.z;
+    if (!s.layer[0].hy.sel[g]) return;
+    int li = 0;
+    while (li + 1 < s.n_layers && (int)blockIdx.x >= s.tile_end[li]) ++li;
+    const GemmArgs& a = s.layer[li];
+    const int t = (int)blockIdx.x - (li ? s.tile_end[li - 1] : 0);
+    const int nx = (a.N + TL::BN - 1) / TL::BN;
+    const int bx = t % nx, by = t / nx;
+    const int m0 = by * TL::BM, n0 = bx * TL::BN;
+    f32x16 acc[TL::TM][TL::TN];
+#pragma unroll
+    for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TL::TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    gemm_pass<T, TL>(a, 0, g, m0, n0, lds, acc);
+    dw_store_fresh<TL>(a, g, m0, n0, acc);
+}
+
 // Tile shapes.  bf16: 256 x 256 tiles with eight waves and two k-tiles in flight for the forward
 // and signal GEMMs and for the weight gradients (128 x 256 tiles with two workgroups per compute
 // unit -- the seventh Tile parameter -- were measured slower), 64 x 128 for the output layer, whose
@@ -1478,8 +1513,7 @@ hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s)
 // Weight-gradient GEMM of layer l.  hy.sel == nullptr: both iterates, the statistic, and the
 // fresh block of the groups with store_now[g] (all groups when store_now is null).  hy.sel given:
 // the gradient at theta^k of the groups with sel[g], stored; nothing else.
-template <typename T>
-static hipError_t launch_dw(gcada_ctx* c, int l, const Hyper& hy, const uint8_t* store_now, hipStream_t s)
+static GemmArgs dw_args(gcada_ctx* c, int l, const Hyper& hy, const uint8_t* store_now)
 {
     MlpWork* w = c->mlp;
     const Layout& lay = w->lay;
@@ -1495,7 +1529,39 @@ static hipError_t launch_dw(gcada_ctx* c, int l, const Hyper& hy, const uint8_t*
     a.gbuf = c->gbuf; a.which = c->which; a.goff = lay.woff[l];
     a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[l];
     a.store_now = store_now;
-    return launch_gemm<T, EPI_DW>(a, G, w->small, s);
+    return a;
+}
+
+template <typename T>
+static hipError_t launch_dw(gcada_ctx* c, int l, const Hyper& hy, const uint8_t* store_now, hipStream_t s)
+{
+    return launch_gemm<T, EPI_DW>(dw_args(c, l, hy, store_now), hy.G, c->mlp->small, s);
+}
+
+// all layers' weight gradients at theta^k of the groups in hy.sel, one launch
+template <typename T, bool SMALL>
+static hipError_t launch_dw_selected(gcada_ctx* c, const Hyper& hy, hipStream_t s)
+{
+    using TL = typename TileOf<T, EPI_DW, SMALL>::type;
+    constexpr int lds = gemm_lds_bytes<T, EPI_DW, TL>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)mlp_dw_selected<T, TL>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const Layout& lay = c->mlp->lay;
+    DwSelectedArgs a{};
+    a.n_layers = lay.L;
+    int tiles = 0;
+    for (int l = 1; l <= lay.L; ++l) {
+        a.layer[l - 1] = dw_args(c, l, hy, nullptr);
+        tiles += ((lay.n[l] + TL::BM - 1) / TL::BM) * ((lay.n[l - 1] + TL::BN - 1) / TL::BN);
+        a.tile_end[l - 1] = tiles;
+    }
+    mlp_dw_selected<T, TL><<<dim3(tiles, 1, hy.G), TL::NT, lds, s>>>(a);
+    return hipGetLastError();
 }
 
 // Statistic of the first layer's weights from the two Gram matrices (bf16): the signal
@@ -1639,11 +1705,8 @@ hipError_t mlp_store_selected(gcada_ctx* c, hipStream_t s)
         mlp_gather_vec<bf16_t><<<grid, 256, 0, s>>>(hy, c->d_shards, c->mlp->idx_last, lay.n[0], lay.ld[0],
                                                      lay.ldmu, nullptr, (bf16_t*)c->mlp->XgT);
     }
-    for (int l = c->mlp->lay.L; l >= 1; --l) {
-        hipError_t e = c->mlp->bf16 ? launch_dw<bf16_t>(c, l, hy, nullptr, s) : launch_dw<float>(c, l, hy, nullptr, s);
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    if (c->mlp->bf16) return launch_dw_selected<bf16_t, false>(c, hy, s);
+    return c->mlp->small ? launch_dw_selected<float, true>(c, hy, s) : launch_dw_selected<float, false>(c, hy, s);
 }
 
 }  // namespace gcada

@@ -138,6 +138,49 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
                         kSelBlock / kWave, stored, redo, hot);
 }
 
+// Statistic sums and selection in one launch, one block per group (lazy gradient store): the
+// group's partials are added in the order of stat_reduce_kernel, the threshold is formed by every
+// block from the D history entries, block 0 also forms the loss.  Writes what select_kernel
+// writes, for its group.
+__global__ __launch_bounds__(kSelBlock) void stat_select_kernel(
+    Hyper hy, const double* __restrict__ part_stat, int n_stat, const double* __restrict__ part_loss,
+    int n_loss_total, const double* __restrict__ nring, const int32_t* __restrict__ tau,
+    double* __restrict__ stat, uint8_t* __restrict__ mask, Ctl* __restrict__ ctl,
+    uint8_t* __restrict__ mask_out, float* __restrict__ loss_out,
+    const uint8_t* __restrict__ stored, uint8_t* __restrict__ redo, uint8_t* __restrict__ hot)
+{
+    __shared__ double s_tmp[kSelBlock / kWave];
+    __shared__ double s_rhs;
+    const int g = blockIdx.x;
+    int my_tau = 0;
+    uint8_t my_stored = 0;
+    if (threadIdx.x == 0) { my_tau = tau[g]; my_stored = stored[g]; }
+    if (threadIdx.x < kWave) {
+        const double r = history_threshold(hy, nring);
+        if (threadIdx.x == 0) s_rhs = r;
+    }
+    const double t = block_sum_strided<kSelBlock>(part_stat + (int64_t)g * n_stat, n_stat, s_tmp);
+    double lsum = 0;
+    if (g == 0) lsum = block_sum_strided<kSelBlock>(part_loss, n_loss_total, s_tmp);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const double rhs = s_rhs;
+        const bool sel = (t > rhs) || (my_tau >= hy.D) || (rhs == 0.0);
+        stat[g] = t;
+        mask[g] = sel ? 1 : 0;
+        if (mask_out) mask_out[g] = sel ? 1 : 0;
+        redo[g] = sel && !my_stored ? 1 : 0;
+        hot[g] = t > rhs ? 1 : 0;
+        if (g == 0) {
+            const double loss =
+                lsum / ((double)hy.G * (double)hy.mu) + 0.5 * (double)hy.l2 * ctl->theta_sq;
+            ctl->rhs = rhs;
+            ctl->loss = loss;
+            if (loss_out) *loss_out = (float)loss;
+        }
+    }
+}
+
 // Lazy gradient store: before the gradient kernels run, the groups whose selection does not
 // depend on the statistic are known -- age D reached, or an all-zero history (threshold 0, every
 // group is selected).  Those write their fresh gradient during the gradient stage, and so do the
@@ -518,16 +561,9 @@ hipError_t lazy_flags(gcada_ctx* c, hipStream_t s)
 // gradient is still to be written.  server_step(..., preselected = true, ...) follows.
 hipError_t server_select(gcada_ctx* c, uint8_t* mask_out, float* loss_out, hipStream_t s)
 {
-    const double* part = c->part_stat;
-    int n_stat = c->n_stat_used;
-    if (n_stat > 16) {
-        stat_reduce_kernel<<<c->hy.G, kSelBlock, 0, s>>>(c->part_stat, c->n_stat_used, c->stat_sum);
-        part = c->stat_sum;
-        n_stat = 1;
-    }
-    select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(
-        c->hy, part, n_stat, c->part_loss, c->n_loss_used, c->nring, c->tau, c->stat, c->mask, c->ctl,
-        mask_out, loss_out, c->store_now, c->redo, c->hot);
+    stat_select_kernel<<<c->hy.G, kSelBlock, 0, s>>>(
+        c->hy, c->part_stat, c->n_stat_used, c->part_loss, c->n_loss_used, c->nring, c->tau, c->stat,
+        c->mask, c->ctl, mask_out, loss_out, c->store_now, c->redo, c->hot);
     return hipGetLastError();
 }
 

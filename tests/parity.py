@@ -178,13 +178,15 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
     return worst
 
 
-def free_running(w: Workload, steps, Xs, ys, idx=None):
+def free_running(w: Workload, steps, Xs, ys, idx=None, options=()):
     """Both sides run `steps` iterations on their own from theta^0.  Returns per-step masks and
-    losses of both and the final iterates."""
+    losses of both and the final iterates.  options: (option, value) pairs for gcada_set_option."""
     orc = O.Oracle(oracle_config(w), make_theta0(w))
     gpu = Gcada.from_workload(w)
     gpu.set_shards(Xs, ys)
     gpu.set_theta(make_theta0(w))
+    for opt, val in options:
+        B.gcada_set_option(gpu.ctx, opt, val)
     idx_dev = torch.as_tensor(idx, device="cuda") if idx is not None else None
     masks_g = torch.zeros(steps, w.G, dtype=torch.uint8, device="cuda")
     loss_g = torch.zeros(steps, dtype=torch.float32, device="cuda")

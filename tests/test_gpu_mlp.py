@@ -231,3 +231,26 @@ def test_mlp_gram_statistic_matches_weight_gradient_statistic():
                     np.testing.assert_allclose(b["grad"][g], a["grad"][g], rtol=2e-6,
                                                atol=1e-6 * np.abs(a["grad"][g]).max())
         _say("masks that differ at the threshold:", differing)
+
+
+def test_mlp_bf16_free_run_with_lazy_store_and_gram_statistic_tracks_oracle(par):
+    # both sides on their own for 50 iterations, the GPU in the configuration the big bf16
+    # workload runs in (lazy gradient store, first-layer statistic from the Gram matrices)
+    from paper_2201_04301_amd import binding as B
+    # (overlapping clusters: the loss stays away from zero, where a relative comparison means nothing)
+    w = scaled(CONFIGS["mlp_3072_bf16"], name="mlp_gram", widths=(256, 192, 10), mu=64, G=6, rows=400, D=5,
+               sigma=1.5, alpha=2e-3)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 50
+    idx = make_indices(w, steps)
+    r = par.free_running(w, steps, Xs, ys, idx,
+                         options=((B.GCADA_OPT_LAZY_GRADIENT_STORE, 1), (B.GCADA_OPT_GRAM_STATISTIC, 1)))
+    agree = (r["masks_gpu"] == r["masks_oracle"]).mean()
+    _say("mask agreement", agree, "loss", r["loss_gpu"][0], "->", r["loss_gpu"][-1], r["loss_oracle"][-1],
+         "uploads", int(r["masks_gpu"].sum()), "of", steps * w.G)
+    assert agree >= 0.85
+    assert r["loss_gpu"][-1] < 0.7 * r["loss_gpu"][0]
+    # (free-running bf16 against fp64: once the loss is four orders below its start the two
+    # trajectories differ by tens of percent of it)
+    np.testing.assert_allclose(r["loss_gpu"], r["loss_oracle"], rtol=8e-2, atol=2e-4)
+    assert 0 < r["masks_gpu"].sum() < steps * w.G

@@ -18,9 +18,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 # HBM bytes per launch of the timed kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
-# the copy calibration (profiles/lr_4k_hbm_traffic.md).  Valid for the kernel named; set to None
-# when that kernel changes.
-MEASURED_TRAFFIC = {"lr_4k": ("lr_tile_kernel", 68.1e6 + 8.4e6)}
+# the copy calibration (profiles/lr_4k_hbm_traffic.md, profiles/lr_64k_hbm_traffic.md).  Valid for
+# the kernel named; set to None when that kernel changes.
+MEASURED_TRAFFIC = {"lr_4k": ("lr_tile_kernel", 68.1e6 + 8.4e6),
+                    "lr_64k": ("lr_team_kernel", 8.612e9 + 16.8e6)}
 
 
 def main():

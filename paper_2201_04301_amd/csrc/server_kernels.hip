@@ -41,10 +41,7 @@ constexpr int kSelBlock = 256;
 __device__ __forceinline__ void select_groups_block(const Hyper& hy, const double* __restrict__ part_stat,
                                                     int n_stat, const int32_t* __restrict__ tau,
                                                     double rhs, uint8_t* s_mask, double* stat_out,
-                                                    uint8_t* mask_a, uint8_t* mask_b, int nwaves,
-                                                    const uint8_t* __restrict__ stored = nullptr,
-                                                    uint8_t* __restrict__ redo = nullptr,
-                                                    uint8_t* __restrict__ hot = nullptr)
+                                                    uint8_t* mask_a, uint8_t* mask_b, int nwaves)
 {
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     for (int g = wave; g < hy.G; g += nwaves) {
@@ -58,8 +55,6 @@ __device__ __forceinline__ void select_groups_block(const Hyper& hy, const doubl
             if (stat_out) stat_out[g] = a;
             if (mask_a) mask_a[g] = sel ? 1 : 0;
             if (mask_b) mask_b[g] = sel ? 1 : 0;
-            if (redo) redo[g] = sel && !stored[g] ? 1 : 0;
-            if (hot) hot[g] = a > rhs ? 1 : 0;
         }
     }
 }
@@ -91,8 +86,7 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
     Hyper hy, const double* __restrict__ part_stat, int n_stat, const double* __restrict__ part_loss,
     int n_loss_total, const double* __restrict__ nring, const int32_t* __restrict__ tau,
     double* __restrict__ stat, uint8_t* __restrict__ mask, Ctl* __restrict__ ctl,
-    uint8_t* __restrict__ mask_out, float* __restrict__ loss_out,
-    const uint8_t* __restrict__ stored, uint8_t* __restrict__ redo, uint8_t* __restrict__ hot)
+    uint8_t* __restrict__ mask_out, float* __restrict__ loss_out)
 {
     __shared__ double s_tmp[kSelBlock / kWave];
     __shared__ double s_rhs;
@@ -102,11 +96,9 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
     const bool direct = n_stat == 1;
     double my_stat = 0;
     int my_tau = 0;
-    uint8_t my_stored = 0;
     if (direct && (int)threadIdx.x < hy.G) {
         my_stat = part_stat[threadIdx.x];
         my_tau = tau[threadIdx.x];
-        if (redo) my_stored = stored[threadIdx.x];
     }
     if (threadIdx.x < kWave) {
         const double r = history_threshold(hy, nring);
@@ -129,13 +121,11 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(
             stat[g] = my_stat;
             mask[g] = sel ? 1 : 0;
             if (mask_out) mask_out[g] = sel ? 1 : 0;
-            if (redo) redo[g] = sel && !my_stored ? 1 : 0;
-            if (hot) hot[g] = my_stat > rhs ? 1 : 0;
         }
         return;
     }
     select_groups_block(hy, part_stat, n_stat, tau, rhs, s_mask, stat, mask, mask_out,
-                        kSelBlock / kWave, stored, redo, hot);
+                        kSelBlock / kWave);
 }
 
 // Statistic sums and selection in one launch, one block per group (lazy gradient store): the
@@ -541,7 +531,7 @@ hipError_t server_step(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool pr
     if (!self_select && !preselected)
         select_kernel<<<1, kSelBlock, ((size_t)c->hy.G + 15) / 16 * 16, s>>>(
             c->hy, a.part_stat, a.n_stat, c->part_loss, c->n_loss_used, c->nring, c->tau,
-            c->stat, c->mask, c->ctl, mask_out, loss_out, nullptr, nullptr, nullptr);
+            c->stat, c->mask, c->ctl, mask_out, loss_out);
     if (c->hy.pstride <= (int64_t)kBigBlock * 4)
         // the whole parameter vector fits one block: no cross-block hand-over at the end
         launch_server<kBigBlock, 4>(self_select, 1, lds, s, a);

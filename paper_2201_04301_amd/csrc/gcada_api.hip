@@ -245,6 +245,7 @@ static int after_state_change(gcada_ctx* ctx)
 {
     set_iteration(ctx);
     gcada::lr_tile_forget(ctx);
+    ctx->flags_valid = false;
     HIP_TRY(ctx, hipMemset(ctx->hot, 0, (size_t)ctx->hy.G));
     if (ctx->dims.model != GCADA_MLP) HIP_TRY(ctx, gcada::lr_team_reset(ctx));
     HIP_TRY(ctx, gcada::refresh_theta_sq(ctx, nullptr));
@@ -305,7 +306,8 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     // lazy gradient store: the gradient stage writes the fresh gradients of the groups that are
     // selected whatever the statistic says; the selection then names the others to be written
     const bool lazy = ctx->dims.model == GCADA_MLP && ctx->lazy_store && !server_rule;
-    if (lazy && (e = gcada::lazy_flags(ctx, s)) != hipSuccess) return fail_hip(ctx, e, "store flag kernel");
+    if (lazy && !ctx->flags_valid && (e = gcada::lazy_flags(ctx, s)) != hipSuccess)
+        return fail_hip(ctx, e, "store flag kernel");
     e = ctx->dims.model != GCADA_MLP ? gcada::lr_gradients(ctx, idx, s) : gcada::mlp_gradients(ctx, idx, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "gradient kernels");
     if (server_rule && !ctx->lr_fused_finish && (e = gcada::rule_loss(ctx, loss_out, s)) != hipSuccess)
@@ -320,9 +322,11 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
                              : gcada::server_step(ctx, mask_out, loss_out, server_rule || lazy, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "server kernels");
     if (ctx->dims.model == GCADA_MLP) {
-        // compute copies (padded, transposed, bf16) of the new iterate's hidden-layer weights
-        e = gcada::mlp_refresh_slot(ctx, (int)((ctx->k + 1) % (ctx->hy.D + 1)), s);
+        // compute copies (padded, transposed, bf16) of the new iterate's hidden-layer weights; the
+        // same launch sets the store flags of the next step from the ages and history just written
+        e = gcada::mlp_refresh_slot(ctx, (int)((ctx->k + 1) % (ctx->hy.D + 1)), ctx->lazy_store, s);
         if (e != hipSuccess) return fail_hip(ctx, e, "weight copy kernel");
+        ctx->flags_valid = ctx->lazy_store;
     }
     ctx->k += 1;
     return GCADA_OK;
@@ -462,6 +466,7 @@ int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
     }
     if (option == GCADA_OPT_LAZY_GRADIENT_STORE) {
         ctx->lazy_store = value != 0 && ctx->dims.model == GCADA_MLP;
+        ctx->flags_valid = false;
         return GCADA_OK;
     }
     return fail(ctx, GCADA_EINVAL, "set_option: unknown option");

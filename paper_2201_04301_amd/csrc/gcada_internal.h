@@ -75,6 +75,35 @@ __device__ __forceinline__ T global_load(const T* p)
     return *(const __attribute__((address_space(1))) T*)p;
 }
 
+// Right side of Eq. (9) with c_d = c/D.  Called by one whole wave (64 lanes): the D history
+// entries are loaded in parallel and added in the butterfly's fixed order.
+__device__ __forceinline__ double history_threshold(const Hyper& hy, const double* __restrict__ nring)
+{
+    const int lane = threadIdx.x % 64;
+    double v = 0;
+    for (int j = lane; j < hy.D; j += 64) v += nring[j];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return hy.c / (double)hy.D * v;
+}
+
+// Lazy gradient store: before the gradient kernels run, the groups whose selection does not
+// depend on the statistic are known -- age D reached, or an all-zero history (threshold 0, every
+// group is selected).  Those write their fresh gradient during the gradient stage, and so do the
+// groups whose statistic exceeded the threshold in the previous step (`hot`: a guess that spares
+// most recomputation while many groups still upload in every step; a wrong guess costs a store
+// or a recomputation, never a different result).  A group that is selected without having
+// written its gradient gets it from a second, short launch.  Called by one whole wave.
+__device__ __forceinline__ void store_flags_wave(const Hyper& hy, const double* __restrict__ nring,
+                                                 const int32_t* __restrict__ tau,
+                                                 const uint8_t* __restrict__ hot,
+                                                 uint8_t* __restrict__ store_now)
+{
+    const double rhs = history_threshold(hy, nring);
+    for (int g = threadIdx.x % 64; g < hy.G; g += 64)
+        store_now[g] = (tau[g] >= hy.D) || (rhs == 0.0) || hot[g] ? 1 : 0;
+}
+
 struct MlpWork;       // MLP activations and compute copies (mlp_kernels.hip)
 struct LrTilePlan;    // single-pass logistic path, rows that fit one workgroup (lr_tiles.hip)
 struct LrTeamPlan;    // single-pass logistic path, wide rows shared by a team (lr_team.hip)
@@ -135,6 +164,7 @@ struct gcada_ctx {
     // lazy gradient store (MLP): the gradient stage writes only the fresh gradients of store_now,
     // a second launch those of redo (selected by the statistic afterwards)
     bool lazy_store = false;
+    bool flags_valid = false;    // store_now holds the flags of the step to come (set by the last launch of a step)
     uint8_t* store_now = nullptr;  // G
     uint8_t* redo = nullptr;       // G
     uint8_t* hot = nullptr;        // G: the statistic exceeded the threshold in the previous step
@@ -187,7 +217,8 @@ hipError_t mlp_plan(gcada_ctx* c);
 void mlp_free(gcada_ctx* c);
 hipError_t mlp_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s);
 hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s);   // compute copies of all ring slots
-hipError_t mlp_refresh_slot(gcada_ctx* c, int slot, hipStream_t s);   // ... of one slot
+// ... of one slot; flags: the same launch also sets the store flags of the step that follows
+hipError_t mlp_refresh_slot(gcada_ctx* c, int slot, bool flags, hipStream_t s);
 
 hipError_t select_plan(gcada_ctx* c);
 // selection (a2) + masked innovation sum (a3) + server update and history (a4); advances

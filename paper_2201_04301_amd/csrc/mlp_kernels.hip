@@ -998,14 +998,15 @@ __global__ __launch_bounds__(256) void mlp_gather_vec(Hyper hy, const ShardDesc*
 }
 
 // Compute copies of the hidden-layer weights of one ring slot: Wc [n_l][ld_{l-1}] and the
-// transpose WcT [n_{l-1}][ld_l], both in T.  grid: (ceil(n_in/64), ceil(n_out/64)), block 256.
+// transpose WcT [n_{l-1}][ld_l], both in T.  One 64 x 64 block of a layer: (bx, by) of
+// (ceil(n_in/64), ceil(n_out/64)); 256 threads.
 template <typename T>
-__global__ __launch_bounds__(256) void mlp_weight_copy(const float* __restrict__ W, int n_out, int n_in,
-                                                       int ld_in, int ld_out, T* __restrict__ Wc,
-                                                       T* __restrict__ WcT)
+__device__ __forceinline__ void weight_copy_block(int bx, int by, const float* __restrict__ W, int n_out,
+                                                  int n_in, int ld_in, int ld_out, T* __restrict__ Wc,
+                                                  T* __restrict__ WcT)
 {
     __shared__ T tile[64][64 + 2];
-    const int i0 = blockIdx.x * 64, o0 = blockIdx.y * 64;
+    const int i0 = bx * 64, o0 = by * 64;
     const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;
     for (int r = ty; r < 64; r += 4) {
         const int o = o0 + r, i = i0 + tx;
@@ -1026,15 +1027,14 @@ __global__ __launch_bounds__(256) void mlp_weight_copy(const float* __restrict__
 // The same with 16-byte loads and 8/16-byte stores, for layers whose input width is a multiple
 // of 4 and whose weights start 16-byte aligned in the parameter vector.  WcT may be null (the
 // first layer's transpose is never used: no signal is propagated to the input).
-// grid: (ceil(n_in/64), ceil(n_out/64)), block 256.
 template <typename T>
-__global__ __launch_bounds__(256) void mlp_weight_copy_vec(const float* __restrict__ W, int n_out, int n_in,
-                                                           int ld_in, int ld_out, T* __restrict__ Wc,
-                                                           T* __restrict__ WcT)
+__device__ __forceinline__ void weight_copy_block_vec(int bx, int by, const float* __restrict__ W, int n_out,
+                                                      int n_in, int ld_in, int ld_out, T* __restrict__ Wc,
+                                                      T* __restrict__ WcT)
 {
     constexpr int V = 16 / (int)sizeof(T), PITCH = 64 + 8;
     __shared__ __align__(16) T tileT[64][PITCH];
-    const int i0 = blockIdx.x * 64, o0 = blockIdx.y * 64;
+    const int i0 = bx * 64, o0 = by * 64;
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
         const int t = threadIdx.x + 256 * h, r = t / 16, cv = (t % 16) * 4;
@@ -1064,30 +1064,85 @@ __global__ __launch_bounds__(256) void mlp_weight_copy_vec(const float* __restri
     }
 }
 
+// The copies of all layers of one ring slot in ONE launch (a launch costs more than a small
+// layer's copy), and in its last workgroup, when `store_now` is given, the store flags of the
+// lazy gradient store for the step that follows (they depend on the ages and the history the
+// server step has just written).
+// grid: (blocks of all layers together + 1), block 256.
+struct RefreshArgs {
+    struct LayerCopy {
+        const float* W;
+        void* Wc;
+        void* WcT;
+        int n_out, n_in, ld_in, ld_out;
+        int nbx;           // blocks along the input width
+        int block_end;     // running total of the layers' block counts
+        int vec;           // 16-byte path
+    } layer[GCADA_MAX_WIDTHS - 1];
+    int n_layers;
+    const double* nring;
+    const int32_t* tau;
+    const uint8_t* hot;
+    uint8_t* store_now;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void mlp_refresh_kernel(Hyper hy, RefreshArgs a)
+{
+    const int b = blockIdx.x;
+    if (b >= a.layer[a.n_layers - 1].block_end) {
+        if (a.store_now && threadIdx.x < kWave) store_flags_wave(hy, a.nring, a.tau, a.hot, a.store_now);
+        return;
+    }
+    int li = 0;
+    while (li + 1 < a.n_layers && b >= a.layer[li].block_end) ++li;
+    const RefreshArgs::LayerCopy& y = a.layer[li];
+    const int t = b - (li ? a.layer[li - 1].block_end : 0);
+    const int bx = t % y.nbx, by = t / y.nbx;
+    if (y.vec) weight_copy_block_vec<T>(bx, by, y.W, y.n_out, y.n_in, y.ld_in, y.ld_out, (T*)y.Wc, (T*)y.WcT);
+    else weight_copy_block<T>(bx, by, y.W, y.n_out, y.n_in, y.ld_in, y.ld_out, (T*)y.Wc, (T*)y.WcT);
+}
+
 // Bias gradient of a layer from the transposed signal dZT [n][ldmu]: db[n] = sum_i dZ[i][n].
 // The stale iterate's transposed signal is stored negated, so fresh - stale is a plain sum.
-// grid: (ceil(n/8), G), block 256: half a wave per hidden unit, both iterates, 16-byte loads
-// (rows of dZT are padded to a multiple of 64 elements with zeros).
+// All layers go into ONE launch (each is a few microseconds of work, less than a launch costs):
+// grid: (sum over the layers of ceil(n_l/8), G), block 256: half a wave per hidden unit, both
+// iterates, 16-byte loads (rows of dZT are padded to a multiple of 64 elements with zeros).
+struct BiasArgs {
+    struct LayerBias {
+        const void* dZT;
+        int64_t zt_it, zt_g;   // elements between the iterates / the groups
+        int64_t boff;          // offset of the layer's biases in the parameter vector
+        int nl, stat_off;
+        int block_end;         // running total of the layers' block counts
+    } layer[GCADA_MAX_WIDTHS - 1];
+    int n_layers, ldmu;
+    float* gbuf;
+    const int32_t* which;
+    double* part_stat;
+    int n_stat;
+};
+
+// block `bi` of the launch's bias blocks, group g
 template <typename T>
-__global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu, const T* __restrict__ dZT,
-                                                     int64_t zt_it, int64_t zt_g, float* __restrict__ gbuf,
-                                                     const int32_t* __restrict__ which,
-                                                     int64_t boff, double* __restrict__ part_stat, int n_stat,
-                                                     int stat_off)
+__device__ __forceinline__ void bias_grad_block(const Hyper& hy, const BiasArgs& b, int bi, int g)
 {
     constexpr int V = 16 / (int)sizeof(T);
     __shared__ double s_red[4];
-    const int g = blockIdx.y, wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    if (hy.sel && !hy.sel[g]) return;            // unselected group (server-side rule)
+    int li = 0;
+    while (li + 1 < b.n_layers && bi >= b.layer[li].block_end) ++li;
+    const BiasArgs::LayerBias& y = b.layer[li];
+    const int bx = bi - (li ? b.layer[li - 1].block_end : 0);
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int hl = lane & 31;                         // lane within the half wave
-    const int n = blockIdx.x * 8 + wave * 2 + (lane >> 5);
+    const int n = bx * 8 + wave * 2 + (lane >> 5);
     double sq = 0;
     float s[2] = {0.0f, 0.0f};
-    if (n < nl) {
+    if (n < y.nl) {
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const T* z = dZT + (int64_t)it * zt_it + (int64_t)g * zt_g + (int64_t)n * ldmu;
-            for (int i = hl * V; i < ldmu; i += 32 * V) {
+            const T* z = (const T*)y.dZT + (int64_t)it * y.zt_it + (int64_t)g * y.zt_g + (int64_t)n * b.ldmu;
+            for (int i = hl * V; i < b.ldmu; i += 32 * V) {
                 alignas(16) T v[V];
                 *(uint4*)v = *(const uint4*)(z + i);
 #pragma unroll
@@ -1099,8 +1154,8 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
     for (int it = 0; it < 2; ++it)
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) s[it] += __shfl_xor(s[it], o, kWave);
-    if (n < nl && hl == 0) {
-        fresh_row(gbuf, which, hy, g)[boff + n] = s[0];
+    if (n < y.nl && hl == 0) {
+        fresh_row(b.gbuf, b.which, hy, g)[y.boff + n] = s[0];
         const float df = s[0] + s[1];
         sq = (double)df * (double)df;
     }
@@ -1108,7 +1163,15 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, int nl, int ldmu,
     if (lane == 0) s_red[wave] = sq;
     __syncthreads();
     if (threadIdx.x == 0)
-        part_stat[(int64_t)g * n_stat + stat_off + blockIdx.x] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+        b.part_stat[(int64_t)g * b.n_stat + y.stat_off + bx] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, BiasArgs b)
+{
+    const int g = blockIdx.y;
+    if (hy.sel && !hy.sel[g]) return;            // unselected group (server-side rule)
+    bias_grad_block<T>(hy, b, blockIdx.x, g);
 }
 
 
@@ -1292,14 +1355,21 @@ __global__ __launch_bounds__(GramTile::NT) void mlp_gram(GramArgs a)
 // dZd[g][s][n] = dZ[0][g][s][n] - dZ[1][g][s][n] (the signal of the fresh minus that of the stale
 // iterate), and -- the same read -- the first layer's bias gradient: its fresh value
 // sum_s dZ[0][g][s][n] goes to the group's fresh row, the squared difference of the two iterates'
-// sums into the layer's bias slots of the statistic.
-// grid: (ld / 64, G), block 256 = 8 column chunks of 8 x 32 row lanes; ld a multiple of 64.
+// sums into the layer's bias slots of the statistic.  The workgroups past the first ld / 64 form
+// the bias gradients of the deeper layers (one launch less).
+// grid: (ld / 64 + bias blocks of `deeper`, G), block 256 = 8 column chunks of 8 x 32 row lanes;
+// ld a multiple of 64.
 __global__ __launch_bounds__(256) void mlp_signal_diff_bias(Hyper hy, int n1, int ld, const bf16_t* __restrict__ z0,
                                                             const bf16_t* __restrict__ z1, bf16_t* __restrict__ out,
                                                             float* __restrict__ gbuf, const int32_t* __restrict__ which,
                                                             int64_t boff, double* __restrict__ part_stat, int n_stat,
-                                                            int stat_off, int n_slots)
+                                                            int stat_off, int n_slots, BiasArgs deeper)
 {
+    const int n_cb = ld / 64;
+    if ((int)blockIdx.x >= n_cb) {
+        bias_grad_block<bf16_t>(hy, deeper, (int)blockIdx.x - n_cb, blockIdx.y);
+        return;
+    }
     __shared__ float s_f[32][64 + 1], s_d[32][64 + 1];
     const int g = blockIdx.y, cb = blockIdx.x;
     const int chunk = threadIdx.x % 8, rl = threadIdx.x / 8;
@@ -1341,7 +1411,7 @@ __global__ __launch_bounds__(256) void mlp_signal_diff_bias(Hyper hy, int n1, in
         if (threadIdx.x == 0) slots[cb] = sq;
         // the layer's remaining bias slots belong to the blocks of the other method
         if (cb == 0)
-            for (int q = gridDim.x + threadIdx.x; q < n_slots; q += kWave) slots[q] = 0.0;
+            for (int q = n_cb + threadIdx.x; q < n_slots; q += kWave) slots[q] = 0.0;
     }
 }
 
@@ -1476,35 +1546,40 @@ void mlp_free(gcada_ctx* c)
 }
 
 template <typename T>
-static hipError_t refresh_slot_t(gcada_ctx* c, int slot, hipStream_t s)
+static hipError_t refresh_slot_t(gcada_ctx* c, int slot, bool flags, hipStream_t s)
 {
     MlpWork* w = c->mlp;
     const Layout& lay = w->lay;
     const float* th = c->ring + (int64_t)slot * c->hy.pstride;
+    RefreshArgs a{};
+    int blocks = 0;
     for (int l = 1; l <= lay.L; ++l) {
-        dim3 grid((lay.n[l - 1] + 63) / 64, (lay.n[l] + 63) / 64);
-        T* wc = (T*)w->Wc[l] + (int64_t)slot * w->wc_slot[l];
+        RefreshArgs::LayerCopy& y = a.layer[l - 1];
+        y.W = th + lay.woff[l];
+        y.Wc = (T*)w->Wc[l] + (int64_t)slot * w->wc_slot[l];
         // the transpose serves the signal of layer l-1, which the first layer does not need
-        T* wct = l > 1 ? (T*)w->WcT[l] + (int64_t)slot * w->wct_slot[l] : nullptr;
-        if (lay.n[l - 1] % 4 == 0 && lay.woff[l] % 4 == 0)
-            mlp_weight_copy_vec<T><<<grid, 256, 0, s>>>(th + lay.woff[l], lay.n[l], lay.n[l - 1], lay.ld[l - 1],
-                                                         lay.ld[l], wc, wct);
-        else
-            mlp_weight_copy<T><<<grid, 256, 0, s>>>(th + lay.woff[l], lay.n[l], lay.n[l - 1], lay.ld[l - 1],
-                                                     lay.ld[l], wc, wct);
+        y.WcT = l > 1 ? (T*)w->WcT[l] + (int64_t)slot * w->wct_slot[l] : nullptr;
+        y.n_out = lay.n[l]; y.n_in = lay.n[l - 1]; y.ld_in = lay.ld[l - 1]; y.ld_out = lay.ld[l];
+        y.nbx = (lay.n[l - 1] + 63) / 64;
+        blocks += y.nbx * ((lay.n[l] + 63) / 64);
+        y.block_end = blocks;
+        y.vec = lay.n[l - 1] % 4 == 0 && lay.woff[l] % 4 == 0;
     }
+    a.n_layers = lay.L;
+    if (flags) { a.nring = c->nring; a.tau = c->tau; a.hot = c->hot; a.store_now = c->store_now; }
+    mlp_refresh_kernel<T><<<blocks + 1, 256, 0, s>>>(c->hy, a);
     return hipGetLastError();
 }
 
-hipError_t mlp_refresh_slot(gcada_ctx* c, int slot, hipStream_t s)
+hipError_t mlp_refresh_slot(gcada_ctx* c, int slot, bool flags, hipStream_t s)
 {
-    return c->mlp->bf16 ? refresh_slot_t<bf16_t>(c, slot, s) : refresh_slot_t<float>(c, slot, s);
+    return c->mlp->bf16 ? refresh_slot_t<bf16_t>(c, slot, flags, s) : refresh_slot_t<float>(c, slot, flags, s);
 }
 
 hipError_t mlp_refresh_weights(gcada_ctx* c, hipStream_t s)
 {
     for (int slot = 0; slot <= c->hy.D; ++slot) {
-        hipError_t e = mlp_refresh_slot(c, slot, s);
+        hipError_t e = mlp_refresh_slot(c, slot, false, s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -1564,6 +1639,31 @@ static hipError_t launch_dw_selected(gcada_ctx* c, const Hyper& hy, hipStream_t 
     return hipGetLastError();
 }
 
+// Arguments of the bias gradients of layers l_lo .. L (none: n_layers = 0).
+static BiasArgs bias_args(gcada_ctx* c, int l_lo, int* blocks)
+{
+    MlpWork* w = c->mlp;
+    const Layout& lay = w->lay;
+    const int G = c->hy.G;
+    BiasArgs b{};
+    int total = 0;
+    for (int l = l_lo; l <= lay.L; ++l) {
+        BiasArgs::LayerBias& y = b.layer[b.n_layers++];
+        y.dZT = w->dZT[l];
+        y.zt_it = (int64_t)G * lay.n[l] * lay.ldmu;
+        y.zt_g = (int64_t)lay.n[l] * lay.ldmu;
+        y.boff = lay.boff[l];
+        y.nl = lay.n[l];
+        y.stat_off = w->stat_off_b[l];
+        total += (lay.n[l] + 7) / 8;
+        y.block_end = total;
+    }
+    b.ldmu = lay.ldmu;
+    b.gbuf = c->gbuf; b.which = c->which; b.part_stat = c->part_stat; b.n_stat = w->n_stat;
+    *blocks = total;
+    return b;
+}
+
 // Statistic of the first layer's weights from the two Gram matrices (bf16): the signal
 // difference, then one kernel that forms both matrices tile by tile and sums their product into
 // the layer's partial slots.
@@ -1574,9 +1674,11 @@ static hipError_t gram_statistic(gcada_ctx* c, const int32_t* idx, hipStream_t s
     const int G = c->hy.G, mu = c->hy.mu;
     const int64_t count = (int64_t)G * mu * lay.ld[1];
     const bf16_t* z0 = (const bf16_t*)w->dZ[1];
-    mlp_signal_diff_bias<<<dim3(lay.ld[1] / 64, G), 256, 0, s>>>(c->hy, lay.n[1], lay.ld[1], z0, z0 + count, (bf16_t*)w->dZd,
-                                                              c->gbuf, c->which, lay.boff[1], c->part_stat, w->n_stat,
-                                                              w->stat_off_b[1], (lay.n[1] + 7) / 8);
+    int bias_blocks = 0;
+    const BiasArgs deeper = bias_args(c, 2, &bias_blocks);
+    mlp_signal_diff_bias<<<dim3(lay.ld[1] / 64 + bias_blocks, G), 256, 0, s>>>(
+        c->hy, lay.n[1], lay.ld[1], z0, z0 + count, (bf16_t*)w->dZd, c->gbuf, c->which, lay.boff[1], c->part_stat,
+        w->n_stat, w->stat_off_b[1], (lay.n[1] + 7) / 8, deeper);
     constexpr int glds = 2 * GramTile::STAGE;
     const int gt = (mu + GramTile::BM - 1) / GramTile::BM;
     GramArgs a{};
@@ -1658,12 +1760,6 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             if ((e = launch_dw<T>(c, l, hy, c->lazy_store && !hy.sel ? c->store_now : nullptr, s)) != hipSuccess)
                 return e;
         }
-        if (!(l == 1 && gram)) {       // (with the Gram statistic the signal-difference kernel does it)
-            dim3 grid((lay.n[l] + 7) / 8, G);
-            mlp_bias_grad<T><<<grid, 256, 0, s>>>(hy, lay.n[l], lay.ldmu, (const T*)w->dZT[l], tr_it(l),
-                                                   tr_g(l), c->gbuf, c->which, lay.boff[l], c->part_stat, w->n_stat,
-                                                   w->stat_off_b[l]);
-        }
         if (l > 1) {   // signal of layer l-1: dZ_{l-1} = (dZ_l W_l) * [a_{l-1} > 0]
             GemmArgs a{};
             a.hy = hy; a.tau = c->tau; a.G = G;
@@ -1675,6 +1771,13 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             a.OT = w->dZT[l - 1]; a.t_it = tr_it(l - 1); a.t_g = tr_g(l - 1); a.ldt = lay.ldmu;
             if ((e = launch_gemm<T, EPI_DA>(a, 2 * G, w->small, s)) != hipSuccess) return e;
         }
+    }
+    // bias gradients of all layers in one launch (with the Gram statistic the signal-difference
+    // launch has formed them)
+    if (!gram) {
+        int bias_blocks = 0;
+        const BiasArgs b = bias_args(c, 1, &bias_blocks);
+        mlp_bias_grad<T><<<dim3(bias_blocks, G), 256, 0, s>>>(hy, b);
     }
     c->n_stat_used = w->n_stat;
     c->n_loss_used = G * w->n_loss;

@@ -59,17 +59,6 @@ __device__ __forceinline__ void select_groups_block(const Hyper& hy, const doubl
     }
 }
 
-// Right side of Eq. (9) with c_d = c/D.  Called by one whole wave: the D history entries are
-// loaded in parallel and added in the butterfly's fixed order.
-__device__ __forceinline__ double history_threshold(const Hyper& hy, const double* __restrict__ nring)
-{
-    const int lane = threadIdx.x % kWave;
-    double v = 0;
-    for (int j = lane; j < hy.D; j += kWave) v += nring[j];
-    v = wave_sum(v);
-    return hy.c / (double)hy.D * v;
-}
-
 // grid: G blocks.  Adds one group's partial statistics in a fixed order (thread-strided, then a
 // tree) so that the server kernel finds a single number per group.
 __global__ __launch_bounds__(kSelBlock) void stat_reduce_kernel(const double* __restrict__ part_stat,
@@ -171,21 +160,14 @@ __global__ __launch_bounds__(kSelBlock) void stat_select_kernel(
     }
 }
 
-// Lazy gradient store: before the gradient kernels run, the groups whose selection does not
-// depend on the statistic are known -- age D reached, or an all-zero history (threshold 0, every
-// group is selected).  Those write their fresh gradient during the gradient stage, and so do the
-// groups whose statistic exceeded the threshold in the previous step (`hot`: a guess that spares
-// most recomputation while many groups still upload in every step; a wrong guess costs a store
-// or a recomputation, never a different result).  A group that is selected without having
-// written its gradient gets it from a second, short launch.  One wave.
+// The store flags of the lazy gradient store, on their own (after a change of state; a step
+// sets the flags of the next one in its last launch).  One wave.
 __global__ __launch_bounds__(kWave) void lazy_flags_kernel(Hyper hy, const double* __restrict__ nring,
                                                           const int32_t* __restrict__ tau,
                                                           const uint8_t* __restrict__ hot,
                                                           uint8_t* __restrict__ store_now)
 {
-    const double rhs = history_threshold(hy, nring);
-    for (int g = threadIdx.x; g < hy.G; g += kWave)
-        store_now[g] = (tau[g] >= hy.D) || (rhs == 0.0) || hot[g] ? 1 : 0;
+    store_flags_wave(hy, nring, tau, hot, store_now);
 }
 
 constexpr int kUpdBlock = 1024;

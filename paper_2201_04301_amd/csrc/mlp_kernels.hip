@@ -32,27 +32,24 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
-// float -> T -> float with round to nearest even (identity for float)
+// float -> T -> float with round to nearest even (identity for float).  bf16: the conversion
+// instruction of the hardware (v_cvt_pk_bf16_f32), not bit arithmetic.
 template <typename T> __device__ __forceinline__ float round_to(float v);
 template <> __device__ __forceinline__ float round_to<float>(float v) { return v; }
-template <> __device__ __forceinline__ float round_to<bf16_t>(float v)
-{
-    unsigned u = __float_as_uint(v);
-    if ((u & 0x7f800000u) != 0x7f800000u) {
-        u += 0x7fffu + ((u >> 16) & 1u);
-        u &= 0xffff0000u;
-    }
-    return __uint_as_float(u);
-}
+template <> __device__ __forceinline__ float round_to<bf16_t>(float v) { return (float)(bf16_t)v; }
 template <typename T> __device__ __forceinline__ T to_T(float v);
 template <> __device__ __forceinline__ float to_T<float>(float v) { return v; }
-template <> __device__ __forceinline__ bf16_t to_T<bf16_t>(float v)
+template <> __device__ __forceinline__ bf16_t to_T<bf16_t>(float v) { return (bf16_t)v; }
+// two floats -> one word of two bf16 (lo in the low half): one conversion instruction
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
 {
-    const unsigned u = __float_as_uint(round_to<bf16_t>(v)) >> 16;
-    unsigned short s = (unsigned short)u;
-    bf16_t r;
-    __builtin_memcpy(&r, &s, 2);
-    return r;
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    const bf16x2 r = __builtin_convertvector(v, bf16x2);
+    unsigned u;
+    __builtin_memcpy(&u, &r, 4);
+    return u;
 }
 template <typename T> __device__ __forceinline__ float to_f(T v);
 template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
@@ -451,6 +448,20 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs& a, int it, int g, int 
     gemm_mainloop<T, TL>(Pg, Qg, poff, (int64_t)a.ldq * esz, a.K, lds, acc);
 }
 
+// A 16-byte chunk of row `row` of the transposed staging tile.  Two-byte elements: the chunk's
+// 8-byte halves are stored exchanged in every other group of eight rows (see the writes).
+template <int ESZ>
+__device__ __forceinline__ uint4 staged_t(const void* p, int row)
+{
+    const uint4 v = *(const uint4*)p;
+    if constexpr (ESZ == 2) {
+        const bool sw = (((row >> 3) ^ (row >> 4)) & 1) != 0;
+        return sw ? make_uint4(v.z, v.w, v.x, v.y) : v;
+    } else {
+        return v;
+    }
+}
+
 // grid: (ceil(N/BN), ceil(M/BM), batch);  batch = 2G (it*G + g) for FWD / DA / HEAD, G for DW.
 template <typename T, int EPI, typename TL>
 __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
@@ -572,6 +583,21 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
         }
         return;
     }
+    if constexpr (EPI == EPI_FWD) {
+        // hidden layer: the accumulators start at the bias of their column (the load runs under
+        // the first tile loads; the epilogue has one addition per element less)
+        const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
+        const float* bias = a.ring + (int64_t)slot * hy.pstride + a.boff;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * CW + j * 32 + cl;
+            const float bv = n < a.N ? round_to<T>(bias[n]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = bv;
+        }
+    }
     gemm_pass<T, TL>(a, it0, g, m0, n0, lds, acc);
     if constexpr (EPI == EPI_HEAD) {
         // logits tile -> LDS (fp32), then one thread per sample: softmax cross-entropy and dZ_L
@@ -664,18 +690,13 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
         constexpr int PT = BM + V, PR = BN + V;     // row pitches of the two staging tiles
         T* st = (T*)lds;
         const bool inside = m0 + BM <= a.M && n0 + BN <= a.N;
-        const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
         if constexpr (EPI == EPI_FWD) {
-            const float* bias = a.ring + (int64_t)slot * hy.pstride + a.boff;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = n0 + wn * CW + j * 32 + cl;
-                const float bv = n < a.N ? round_to<T>(bias[n]) : 0.0f;
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[i][j][e] = fmaxf(acc[i][j][e] + bv, 0.0f);
-            }
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = fmaxf(acc[i][j][e], 0.0f);
             // which units are active, for the backward pass
             uint16_t* rb = a.relu_bits + ((((int64_t)it0 * a.G + g) * gridDim.y + by) * gridDim.x + bx) *
                                              (int64_t)(TM * TN * kGemmThreads);
@@ -683,9 +704,13 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
+                    // bit e = [accumulator e > 0]: a compare and an add-with-carry per element
+                    // (b = 2b + carry, from the last element down)
                     unsigned b = 0;
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) b |= (acc[i][j][e] > 0.0f ? 1u : 0u) << e;
+                    for (int e = 15; e >= 0; --e)
+                        asm("v_cmp_lt_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+                            : "+v"(b) : "v"(acc[i][j][e]) : "vcc");
                     rb[(i * TN + j) * kGemmThreads + tid] = (uint16_t)b;
                 }
         } else {
@@ -697,9 +722,12 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const unsigned b = rb[(i * TN + j) * kGemmThreads + tid];
+                    // bit e, spread over a word, ANDed onto the accumulator: two instructions
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        if (!((b >> e) & 1u)) acc[i][j][e] = 0.0f;
+                    for (int e = 0; e < 16; ++e) {
+                        const int keep = (int)(b << (31 - e)) >> 31;
+                        acc[i][j][e] = __int_as_float(__float_as_int(acc[i][j][e]) & keep);
+                    }
                 }
         }
         // two-byte outputs: round the accumulators once, to packed pairs (rows 0,1 and rows 2,3 of
@@ -712,12 +740,12 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int h = 0; h < 8; ++h) {
-                        alignas(4) T q2[2] = {to_T<T>(acc[i][j][2 * h]), to_T<T>(acc[i][j][2 * h + 1])};
-                        pk[i][j][h] = *(const unsigned*)q2;
-                    }
+                    for (int h = 0; h < 8; ++h) pk[i][j][h] = pack_bf16x2(acc[i][j][2 * h], acc[i][j][2 * h + 1]);
         }
         // ---- transposed: stT [BN][PT], element (n, m) ----
+        // (all staging rows of a lane share bits 3 and 4 of the row index: those of the lane)
+        static_assert(CW % 32 == 0, "staging rows of a lane differ by multiples of 32");
+        [[maybe_unused]] const int t_swap = esz == 2 ? (((cl >> 3) ^ (cl >> 4)) & 1) * 4 : 0;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -727,7 +755,10 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
                 for (int eg = 0; eg < 4; ++eg) {
                     const int ml = wm * RW + i * 32 + eg * 8 + rh;      // rows ml .. ml+3
                     if constexpr (esz == 2) {
-                        *(uint2*)(st + nl * PT + ml) = make_uint2(pk[i][j][2 * eg], pk[i][j][2 * eg + 1]);
+                        // the two 8-byte halves of a 16-byte chunk change places in every other
+                        // group of eight staging rows (t_swap): the 16 lanes an 8-byte LDS write
+                        // serves at a time then fall into different banks
+                        *(uint2*)(st + nl * PT + (ml ^ t_swap)) = make_uint2(pk[i][j][2 * eg], pk[i][j][2 * eg + 1]);
                     } else {
                         alignas(16) T q4[4];
 #pragma unroll
@@ -748,7 +779,7 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
 #pragma unroll 4
                 for (int c = tid; c < BN * (BM / V); c += kGemmThreads) {
                     const int nl = c / (BM / V), mv = (c % (BM / V)) * V;
-                    uint4 v = *(const uint4*)(st + nl * PT + mv);
+                    uint4 v = staged_t<esz>(st + nl * PT + mv, nl);
                     v.x ^= flip; v.y ^= flip; v.z ^= flip; v.w ^= flip;
                     *(uint4*)(OT + (int64_t)(n0 + nl) * a.ldt + (m0 + mv)) = v;
                 }
@@ -758,7 +789,7 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
                 const int n = n0 + nl, m = m0 + mv;
                 if (n < a.N && m < a.M) {
                     alignas(16) T tmp[V];
-                    *(uint4*)tmp = *(const uint4*)(st + nl * PT + mv);
+                    *(uint4*)tmp = staged_t<esz>(st + nl * PT + mv, nl);
 #pragma unroll
                     for (int q = 0; q < V; ++q) {
                         float v = (m + q < a.M) ? to_f<T>(tmp[q]) : 0.0f;

@@ -601,7 +601,7 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
     gemm_pass<T, TL>(a, it0, g, m0, n0, lds, acc);
     if constexpr (EPI == EPI_HEAD) {
         // logits tile -> LDS (fp32), then one thread per sample: softmax cross-entropy and dZ_L
-        static_assert(BN == kHeadClasses && BM <= TL::NT, "output-layer tile");
+        static_assert(BN <= kHeadClasses && BM <= TL::NT, "output-layer tile");
         constexpr int pitch = BN + 4;
         float* lg = (float*)lds;
         const int slot = it0 == 0 ? hy.cur : stale_slot(hy, a.tau, g);
@@ -911,10 +911,14 @@ template <bool SMALL> struct TileOf<bf16_t, EPI_DA, SMALL> { using type = Tile<2
 template <bool SMALL> struct TileOf<bf16_t, EPI_DW, SMALL> { using type = Tile<256, 256, 64, 4, 2, 2>; };
 template <bool SMALL> struct TileOf<bf16_t, EPI_HEAD, SMALL> { using type = Tile<64, 128, 128, 2, 2, 2>; };
 
-template <typename T, int EPI, bool SMALL>
-static hipError_t launch_gemm_t(const GemmArgs& a, int batch, hipStream_t s)
+// Output layers of at most 32 classes (the usual case: ten) take a tile 32 columns wide instead
+// of 128: a quarter of the weight rows to load, of the MFMA work and of the staging, and k-tiles
+// twice as long (half the barriers of a loop that is a chain of memory round trips).
+template <typename T> struct HeadNarrow { using type = Tile<64, 32, 256, 2, 1, 2>; };
+
+template <typename T, int EPI, typename TL>
+static hipError_t launch_tile(const GemmArgs& a, int batch, hipStream_t s)
 {
-    using TL = typename TileOf<T, EPI, SMALL>::type;
     constexpr int lds = gemm_lds_bytes<T, EPI, TL>();
     static bool attr_set = false;
     if (!attr_set) {
@@ -931,7 +935,15 @@ static hipError_t launch_gemm_t(const GemmArgs& a, int batch, hipStream_t s)
 template <typename T, int EPI>
 static hipError_t launch_gemm(const GemmArgs& a, int batch, bool small, hipStream_t s)
 {
-    return small ? launch_gemm_t<T, EPI, true>(a, batch, s) : launch_gemm_t<T, EPI, false>(a, batch, s);
+    if constexpr (EPI == EPI_HEAD) {
+        using TN = typename HeadNarrow<T>::type;
+        // (its longer k-tiles must end where the padded rows end; where they do not, the wide
+        // tile has the same rows per workgroup, so the loss partials keep their places)
+        static_assert(sizeof(T) == 4 || TN::BM == TileOf<T, EPI_HEAD, false>::type::BM, "loss partials");
+        if (a.N <= TN::BN && (a.ldp * (int)sizeof(T)) % TN::KROW == 0 && (a.ldq * (int)sizeof(T)) % TN::KROW == 0) return launch_tile<T, EPI, TN>(a, batch, s);
+    }
+    return small ? launch_tile<T, EPI, typename TileOf<T, EPI, true>::type>(a, batch, s)
+                 : launch_tile<T, EPI, typename TileOf<T, EPI, false>::type>(a, batch, s);
 }
 
 // workgroups (statistic partials) of the weight-gradient GEMM of an M x N layer
@@ -944,10 +956,12 @@ static int dw_blocks(int M, int N, bool small)
                  : ((M + TB::BM - 1) / TB::BM) * ((N + TB::BN - 1) / TB::BN);
 }
 template <typename T>
-static int head_row_blocks(int mu, bool small)
+static int head_row_blocks(int mu, bool small, int classes)
 {
     using TB = typename TileOf<T, EPI_HEAD, false>::type;
     using TS = typename TileOf<T, EPI_HEAD, true>::type;
+    using TN = typename HeadNarrow<T>::type;
+    if (classes <= TN::BN) return (mu + TN::BM - 1) / TN::BM;
     return small ? (mu + TS::BM - 1) / TS::BM : (mu + TB::BM - 1) / TB::BM;
 }
 
@@ -1562,7 +1576,8 @@ hipError_t mlp_plan(gcada_ctx* c)
             w->gram_ok = true;
         }
     }
-    w->n_loss = w->bf16 ? head_row_blocks<bf16_t>(mu, w->small) : head_row_blocks<float>(mu, w->small);
+    w->n_loss = w->bf16 ? head_row_blocks<bf16_t>(mu, w->small, lay.n[lay.L])
+                        : head_row_blocks<float>(mu, w->small, lay.n[lay.L]);
     c->n_stat_part = std::max(c->n_stat_part, ns);
     c->n_loss_part = std::max(c->n_loss_part, w->n_loss);
     return hipSuccess;

@@ -26,6 +26,8 @@ def _say(*a):
     ((100, 70, 50, 7), 40, 3, 90, 12),        # two hidden layers
     ((784, 200, 10), 64, 4, 300, 12),         # layer widths of the fp32 configuration, small batch
     ((130, 260, 129, 3), 130, 2, 200, 8),     # several GEMM tiles with ragged edges
+    ((60, 40, 50), 32, 3, 120, 10),           # fifty classes: the wide output-layer tile
+    ((48, 64, 32), 70, 2, 150, 8),            # 32 classes: the narrow output-layer tile, full; two row blocks
 ])
 def test_mlp_f32_shapes(par, widths, mu, G, rows, steps):
     w = scaled(CONFIGS["mlp_784"], name="mlp_f32", widths=widths, mu=mu, G=G, rows=rows, D=4)
@@ -66,6 +68,8 @@ def test_mlp_784_full_size(par):
     ((128, 96, 64, 10), 48, 4, 100, 7, 6e-2),
     ((200, 150, 10), 256, 3, 300, 6, 2e-2),
     ((3072, 1024, 1024, 10), 64, 2, 150, 3, 2e-2),   # layer widths of the bf16 configuration
+    ((256, 128, 100), 128, 3, 400, 5, 2e-2),          # a hundred classes: the wide output-layer tile
+    ((256, 128, 24), 96, 3, 300, 5, 2e-2),            # rows a multiple of 256 bytes: the narrow one
 ])
 def test_mlp_bf16_shapes(par, widths, mu, G, rows, steps, tol):
     w = scaled(CONFIGS["mlp_3072_bf16"], name="mlp_bf16", widths=widths, mu=mu, G=G, rows=rows, D=4)

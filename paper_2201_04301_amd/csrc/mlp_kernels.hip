@@ -860,39 +860,81 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
     }
 }
 
-// The weight gradients at theta^k of the groups in hy.sel, all layers in ONE launch (the second
-// half of the lazy gradient store: most of the time nobody is selected and three launches that
-// do nothing would cost more than one).
-// grid: (tiles of all layers together, 1, G); a workgroup of an unselected group leaves at once.
+// The weight gradients at theta^k of selected groups, all layers in ONE launch (the second half
+// of the lazy gradient store).  The first layer takes the groups of `sel_first`, the deeper ones
+// those of `sel_rest`.  Most of the time nobody is selected, so the launch must cost little when
+// it has nothing to do: a fixed grid of one workgroup per compute unit; every workgroup lists
+// the selected groups (ascending, in LDS behind the GEMM stages) and walks over the jobs
+// (group, tile) blockIdx.x, blockIdx.x + gridDim.x, ... -- consecutive jobs are tiles of one
+// group, so the workgroups running at any time share a few groups' operands.
+// dynamic LDS: the GEMM stages + 2 G two-byte group ids.
 struct DwSelectedArgs {
     GemmArgs layer[GCADA_MAX_WIDTHS - 1];
     int tile_end[GCADA_MAX_WIDTHS - 1];    // running totals of the layers' tile counts
     int n_layers;
+    const uint8_t* sel_first;
+    const uint8_t* sel_rest;
 };
 static_assert(sizeof(DwSelectedArgs) <= 4096, "kernel arguments");
+
+// ascending list of the groups with sel[g] != 0; called by one whole wave, returns their number
+__device__ __forceinline__ int list_selected(const uint8_t* __restrict__ sel, int G, uint16_t* list)
+{
+    const int lane = threadIdx.x % kWave;
+    int n = 0;
+    for (int g0 = 0; g0 < G; g0 += kWave) {
+        const int g = g0 + lane;
+        const bool on = g < G && sel[g];
+        const unsigned long long bal = __ballot(on);
+        if (on) list[n + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)g;
+        n += __popcll(bal);
+    }
+    return n;
+}
 
 template <typename T, typename TL>
 __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_dw_selected(DwSelectedArgs s)
 {
     extern __shared__ __align__(16) char lds[];
-    const int g = blockIdx.z;
-    if (!s.layer[0].hy.sel[g]) return;
-    int li = 0;
-    while (li + 1 < s.n_layers && (int)blockIdx.x >= s.tile_end[li]) ++li;
-    const GemmArgs& a = s.layer[li];
-    const int t = (int)blockIdx.x - (li ? s.tile_end[li - 1] : 0);
-    const int nx = (a.N + TL::BN - 1) / TL::BN;
-    const int bx = t % nx, by = t / nx;
-    const int m0 = by * TL::BM, n0 = bx * TL::BN;
-    f32x16 acc[TL::TM][TL::TN];
+    __shared__ int s_n[2];
+    const int G = s.layer[0].hy.G;
+    uint16_t* first = (uint16_t*)(lds + gemm_lds_bytes<T, EPI_DW, TL>());
+    uint16_t* rest = first + G;
+    if (threadIdx.x < kWave) {
+        const int n0 = list_selected(s.sel_first, G, first);
+        const int n1 = list_selected(s.sel_rest, G, rest);
+        if (threadIdx.x == 0) { s_n[0] = n0; s_n[1] = n1; }
+    }
+    __syncthreads();
+    const int tiles_first = s.tile_end[0], tiles_rest = s.tile_end[s.n_layers - 1] - tiles_first;
+    const int jobs_first = s_n[0] * tiles_first, jobs = jobs_first + s_n[1] * tiles_rest;
+    for (int j = blockIdx.x; j < jobs; j += gridDim.x) {
+        int g, tile, li = 0;
+        if (j < jobs_first) {
+            g = first[j / tiles_first];
+            tile = j % tiles_first;
+        } else {
+            const int jj = j - jobs_first;
+            g = rest[jj / tiles_rest];
+            tile = tiles_first + jj % tiles_rest;
+            li = 1;
+            while (li + 1 < s.n_layers && tile >= s.tile_end[li]) ++li;
+        }
+        const GemmArgs& a = s.layer[li];
+        const int t = tile - (li ? s.tile_end[li - 1] : 0);
+        const int nx = (a.N + TL::BN - 1) / TL::BN;
+        const int bx = t % nx, by = t / nx;
+        const int m0 = by * TL::BM, n0 = bx * TL::BN;
+        f32x16 acc[TL::TM][TL::TN];
 #pragma unroll
-    for (int i = 0; i < TL::TM; ++i)
+        for (int i = 0; i < TL::TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TL::TN; ++j)
+            for (int jn = 0; jn < TL::TN; ++jn)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-    gemm_pass<T, TL>(a, 0, g, m0, n0, lds, acc);
-    dw_store_fresh<TL>(a, g, m0, n0, acc);
+                for (int e = 0; e < 16; ++e) acc[i][jn][e] = 0.0f;
+        gemm_pass<T, TL>(a, 0, g, m0, n0, lds, acc);     // (ends with a barrier: the stages are free again)
+        dw_store_fresh<TL>(a, g, m0, n0, acc);
+    }
 }
 
 // Tile shapes.  bf16: 256 x 256 tiles with eight waves and two k-tiles in flight for the forward
@@ -1479,6 +1521,7 @@ struct MlpWork {
     int stat_off_w[GCADA_MAX_WIDTHS] = {}, stat_off_b[GCADA_MAX_WIDTHS] = {};
     int n_stat = 0, n_loss = 0;
     bool small = false;              // 64 x 64 GEMM tiles (small fp32 problems)
+    int n_cu = 1;                    // compute units of the device
     // first-layer statistic through Gram matrices (see mlp_gram)
     bool gram_ok = false;            // shapes and type allow it and it is the cheaper way
     bool gram_active = false;        // the last gradient stage used it
@@ -1551,6 +1594,7 @@ hipError_t mlp_plan(gcada_ctx* c)
         if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return e;
         const int64_t wgs = (int64_t)((mu + 127) / 128) * ((lay.n[1] + 127) / 128) * 2 * G;
         w->small = !w->bf16 && wgs < 2 * (int64_t)prop.multiProcessorCount;
+        w->n_cu = prop.multiProcessorCount;
     }
     // partial statistics: per layer the weight-gradient tiles and the bias blocks
     int ns = 0;
@@ -1661,16 +1705,16 @@ static hipError_t launch_dw(gcada_ctx* c, int l, const Hyper& hy, const uint8_t*
 
 // all layers' weight gradients at theta^k of the groups in hy.sel, one launch
 template <typename T, bool SMALL>
-static hipError_t launch_dw_selected(gcada_ctx* c, const Hyper& hy, hipStream_t s)
+static hipError_t launch_dw_selected(gcada_ctx* c, const Hyper& hy, const uint8_t* first_layer_sel, hipStream_t s)
 {
     using TL = typename TileOf<T, EPI_DW, SMALL>::type;
-    constexpr int lds = gemm_lds_bytes<T, EPI_DW, TL>();
-    static bool attr_set = false;
-    if (!attr_set) {
+    const int lds = gemm_lds_bytes<T, EPI_DW, TL>() + 2 * hy.G * (int)sizeof(uint16_t);
+    static int attr_lds = 0;
+    if (lds > attr_lds) {
         hipError_t e = hipFuncSetAttribute((const void*)mlp_dw_selected<T, TL>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_lds = lds;
     }
     const Layout& lay = c->mlp->lay;
     DwSelectedArgs a{};
@@ -1681,7 +1725,11 @@ static hipError_t launch_dw_selected(gcada_ctx* c, const Hyper& hy, hipStream_t 
         tiles += ((lay.n[l] + TL::BM - 1) / TL::BM) * ((lay.n[l - 1] + TL::BN - 1) / TL::BN);
         a.tile_end[l - 1] = tiles;
     }
-    mlp_dw_selected<T, TL><<<dim3(tiles, 1, hy.G), TL::NT, lds, s>>>(a);
+    a.sel_rest = hy.sel;
+    a.sel_first = first_layer_sel ? first_layer_sel : hy.sel;
+    const int64_t most = (int64_t)tiles * hy.G;
+    const int grid = (int)std::min<int64_t>(most, c->mlp->n_cu);
+    mlp_dw_selected<T, TL><<<grid, TL::NT, lds, s>>>(a);
     return hipGetLastError();
 }
 
@@ -1753,16 +1801,17 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     for (const auto& sd : c->shards)
         if ((sd.ld * (int64_t)sizeof(T)) % 16 || ((uintptr_t)sd.X % 16)) vec_ok = false;
     const bool in_place = vec_ok && (lay.n[0] * (int)sizeof(T)) % TileOf<T, EPI_FWD, false>::type::KROW == 0;
-    // first-layer statistic through Gram matrices: then only the groups that store their
-    // gradient in this stage need the transposed minibatch
+    // first-layer statistic through Gram matrices: then this stage forms no first-layer weight
+    // gradient and needs no transposed minibatch
     const bool gram = w->gram_ok && c->allow_gram && c->lazy_store && !hy.sel && in_place;
     w->gram_active = gram;
     w->idx_last = idx;
-    Hyper hy_store = hy;                     // "selected" = writes its gradient in this stage
-    hy_store.sel = c->store_now;
-    if (vec_ok) {
+    if (gram) {
+        // nothing to gather: the forward GEMM and the Gram kernel read the rows in place, and the
+        // transposed minibatch serves only the weight gradient, which follows the selection
+    } else if (vec_ok) {
         dim3 grid((lay.n[0] + 8 * V - 1) / (8 * V), (mu + 63) / 64, G);
-        mlp_gather_vec<T><<<grid, 256, 0, s>>>(gram ? hy_store : hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
+        mlp_gather_vec<T><<<grid, 256, 0, s>>>(hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
                                                 in_place ? nullptr : (T*)w->Xg, (T*)w->XgT);
     } else {
         dim3 grid((lay.n[0] + 63) / 64, (mu + 63) / 64, G);
@@ -1798,9 +1847,8 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     // 3. backward, layer by layer
     for (int l = L; l >= 1; --l) {
         if (l == 1 && gram) {
+            // (the gradient itself is formed after the selection, for the groups that upload)
             if ((e = gram_statistic(c, idx, s)) != hipSuccess) return e;
-            // the gradient itself, one pass at theta^k, for the groups that store it now
-            if ((e = launch_dw<T>(c, 1, hy_store, nullptr, s)) != hipSuccess) return e;
         } else {
             // weight gradient of layer l, both iterates in one workgroup
             if ((e = launch_dw<T>(c, l, hy, c->lazy_store && !hy.sel ? c->store_now : nullptr, s)) != hipSuccess)
@@ -1846,16 +1894,22 @@ hipError_t mlp_store_selected(gcada_ctx* c, hipStream_t s)
 {
     Hyper hy = c->hy;
     hy.sel = c->redo;
+    const uint8_t* first = nullptr;
     if (c->mlp->gram_active) {
-        // their transposed minibatch has not been gathered yet (bf16, 16-byte rows: see the
-        // conditions of the Gram statistic)
+        // With the Gram statistic the gradient stage has formed no first-layer weight gradient at
+        // all: every selected group gets it here, from its transposed minibatch, which is
+        // gathered now (bf16, 16-byte rows: see the conditions of the Gram statistic).
+        first = c->mask;
+        Hyper hg = c->hy;
+        hg.sel = first;
         const Layout& lay = c->mlp->lay;
         dim3 grid((lay.n[0] + 63) / 64, (hy.mu + 63) / 64, hy.G);
-        mlp_gather_vec<bf16_t><<<grid, 256, 0, s>>>(hy, c->d_shards, c->mlp->idx_last, lay.n[0], lay.ld[0],
+        mlp_gather_vec<bf16_t><<<grid, 256, 0, s>>>(hg, c->d_shards, c->mlp->idx_last, lay.n[0], lay.ld[0],
                                                      lay.ldmu, nullptr, (bf16_t*)c->mlp->XgT);
     }
-    if (c->mlp->bf16) return launch_dw_selected<bf16_t, false>(c, hy, s);
-    return c->mlp->small ? launch_dw_selected<float, true>(c, hy, s) : launch_dw_selected<float, false>(c, hy, s);
+    if (c->mlp->bf16) return launch_dw_selected<bf16_t, false>(c, hy, first, s);
+    return c->mlp->small ? launch_dw_selected<float, true>(c, hy, first, s)
+                         : launch_dw_selected<float, false>(c, hy, first, s);
 }
 
 }  // namespace gcada

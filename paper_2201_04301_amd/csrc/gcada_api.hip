@@ -518,8 +518,9 @@ const char* gcada_timed_stage(gcada_ctx* ctx)
     if (!ctx) return "";
     if (ctx->dims.model == GCADA_MLP)
         ctx->stage_name = gcada::mlp_gram_active(ctx)
-            ? "mlp gradient stage (gather, mlp_gemm forward/backward/weight-gradient, bias; first-layer statistic from Gram "
-              "matrices and weight gradients of uploading groups only: fewer flops executed than the algorithmic count)"
+            ? "mlp gradient stage (mlp_gemm forward/backward/weight-gradient, bias; first-layer statistic from Gram "
+              "matrices, first-layer weight gradients after the selection for uploading groups only: fewer flops executed "
+              "than the algorithmic count)"
             : "mlp gradient stage (gather, mlp_gemm forward/backward/weight-gradient, bias)";
     else if (ctx->rule != GCADA_RULE_SERVER && gcada::lr_micro_applies(ctx)) ctx->stage_name = "lr_micro_kernel (the whole iteration)";
     else if (gcada::lr_tile_applies(ctx)) ctx->stage_name = "lr_tile_kernel";

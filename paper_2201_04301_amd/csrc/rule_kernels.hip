@@ -38,14 +38,16 @@ __device__ __forceinline__ double block_sum(double a, double* s_tmp)
 __device__ __forceinline__ void rule_select_block(
     const Hyper& hy, const double* __restrict__ part_dist, int nb, const double* __restrict__ L,
     const double* __restrict__ nring, const int32_t* __restrict__ tau, double* __restrict__ stat,
-    uint8_t* __restrict__ mask, Ctl* __restrict__ ctl, uint8_t* __restrict__ mask_out)
+    uint8_t* __restrict__ mask, Ctl* __restrict__ ctl, uint8_t* __restrict__ mask_out,
+    unsigned long long present)
 {
     __shared__ double s_dist[64];            // D <= 64 is checked on the host
     __shared__ double s_rhs;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     for (int t = wave; t < hy.D; t += kBlock / kWave) {
         double a = 0;
-        for (int i = lane; i < nb; i += kWave) a += part_dist[(int64_t)t * nb + i];
+        if ((present >> t) & 1ull)           // (an age no group has: nobody computed its distance)
+            for (int i = lane; i < nb; i += kWave) a += part_dist[(int64_t)t * nb + i];
         a = wave_sum(a);
         if (lane == 0) s_dist[t] = a;
     }
@@ -68,8 +70,10 @@ __device__ __forceinline__ void rule_select_block(
     if (threadIdx.x == 0) ctl->rhs = rhs;
 }
 
-// Partial squared distances of theta^k to the D older iterates of the ring, and -- by the block
-// that finishes last -- the selection.
+// Partial squared distances of theta^k to the older iterates of the ring that some group's age
+// points at (groups that uploaded together share their age: often a few of the D distances are
+// needed, and each costs a pass over two iterates), and -- by the block that finishes last -- the
+// selection.
 // grid: (nb, D); part[t][b] = sum over the block's slab of (theta^k - theta^{k-1-t})^2.
 __global__ __launch_bounds__(kBlock) void rule_dist_select_kernel(
     Hyper hy, const float* __restrict__ ring, double* __restrict__ part, const double* __restrict__ L,
@@ -78,7 +82,19 @@ __global__ __launch_bounds__(kBlock) void rule_dist_select_kernel(
 {
     __shared__ double s_tmp[kBlock / kWave];
     __shared__ bool s_last;
+    __shared__ unsigned long long s_present;
     const int t = blockIdx.y + 1;                               // age
+    // the ages in use, bit age-1 (every block forms the same set)
+    if (threadIdx.x == 0) s_present = 0;
+    __syncthreads();
+    {
+        unsigned long long m = 0;
+        for (int g = threadIdx.x; g < hy.G; g += kBlock) m |= 1ull << (tau[g] - 1);
+        if (m) atomicOr(&s_present, m);
+    }
+    __syncthreads();
+    const unsigned long long present = s_present;
+    if (!((present >> (t - 1)) & 1ull)) return;
     int slot = hy.cur - t;
     if (slot < 0) slot += hy.D + 1;
     const float* a = ring + (int64_t)hy.cur * hy.pstride;
@@ -95,13 +111,13 @@ __global__ __launch_bounds__(kBlock) void rule_dist_select_kernel(
     if (threadIdx.x == 0) {
         part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = tot;
         __threadfence();                                        // publish the partial device-wide
-        const unsigned total = gridDim.x * gridDim.y;
+        const unsigned total = gridDim.x * (unsigned)__popcll(present);
         s_last = atomicAdd(&ctl->cnt_a, 1u) == total - 1;
     }
     __syncthreads();
     if (!s_last) return;
     __threadfence();                                            // see every block's partial
-    rule_select_block(hy, part, (int)gridDim.x, L, nring, tau, stat, mask, ctl, mask_out);
+    rule_select_block(hy, part, (int)gridDim.x, L, nring, tau, stat, mask, ctl, mask_out, present);
     if (threadIdx.x == 0) ctl->cnt_a = 0;
 }
 
@@ -235,7 +251,8 @@ hipError_t rule_plan(gcada_ctx* c)
 {
     if (c->hy.D > 64) return hipErrorInvalidValue;
     const int64_t per_block = (int64_t)kBlock * 4;
-    c->rule_nb = (int)std::min<int64_t>((c->hy.pstride + per_block - 1) / per_block, 512);
+    // (every block ends with an atomic on one counter: a few hundred blocks per distance, not thousands)
+    c->rule_nb = (int)std::min<int64_t>((c->hy.pstride + per_block - 1) / per_block, 256);
     hipError_t e;
     if ((e = hipMalloc(&c->rule_part, sizeof(double) * (size_t)c->rule_nb * c->hy.D)) != hipSuccess) return e;
     if ((e = hipMalloc(&c->rule_L, sizeof(double) * (size_t)c->hy.G)) != hipSuccess) return e;

@@ -958,6 +958,11 @@ template <bool SMALL> struct TileOf<bf16_t, EPI_HEAD, SMALL> { using type = Tile
 // twice as long (half the barriers of a loop that is a chain of memory round trips).
 template <typename T> struct HeadNarrow { using type = Tile<64, 32, 256, 2, 1, 2>; };
 
+// Weight gradients of a bf16 layer with at most 32 units (the output layer): 32 x 128 tiles
+// instead of 256 x 256 ones whose rows would be padding, with k-tiles twice as long.
+struct DwNarrow { using type = Tile<32, 128, 128, 1, 4, 2>; };
+template <typename T> static bool dw_narrow(int M) { return sizeof(T) == 2 && M <= DwNarrow::type::BM; }
+
 template <typename T, int EPI, typename TL>
 static hipError_t launch_tile(const GemmArgs& a, int batch, hipStream_t s)
 {
@@ -984,6 +989,10 @@ static hipError_t launch_gemm(const GemmArgs& a, int batch, bool small, hipStrea
         static_assert(sizeof(T) == 4 || TN::BM == TileOf<T, EPI_HEAD, false>::type::BM, "loss partials");
         if (a.N <= TN::BN && (a.ldp * (int)sizeof(T)) % TN::KROW == 0 && (a.ldq * (int)sizeof(T)) % TN::KROW == 0) return launch_tile<T, EPI, TN>(a, batch, s);
     }
+    if constexpr (EPI == EPI_DW && sizeof(T) == 2) {
+        // (the padded minibatch length is a multiple of 64 elements = its k-tile)
+        if (dw_narrow<T>(a.M)) return launch_tile<T, EPI, DwNarrow::type>(a, batch, s);
+    }
     return small ? launch_tile<T, EPI, typename TileOf<T, EPI, true>::type>(a, batch, s)
                  : launch_tile<T, EPI, typename TileOf<T, EPI, false>::type>(a, batch, s);
 }
@@ -994,6 +1003,8 @@ static int dw_blocks(int M, int N, bool small)
 {
     using TB = typename TileOf<T, EPI_DW, false>::type;
     using TS = typename TileOf<T, EPI_DW, true>::type;
+    using TN = DwNarrow::type;
+    if (dw_narrow<T>(M)) return ((M + TN::BM - 1) / TN::BM) * ((N + TN::BN - 1) / TN::BN);
     return small ? ((M + TS::BM - 1) / TS::BM) * ((N + TS::BN - 1) / TS::BN)
                  : ((M + TB::BM - 1) / TB::BM) * ((N + TB::BN - 1) / TB::BN);
 }

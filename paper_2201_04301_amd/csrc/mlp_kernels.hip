@@ -139,6 +139,10 @@ struct GemmArgs {
     // DW: when given, the fresh gradient block of group g is written only if store_now[g] != 0
     // (the statistic is computed either way)
     const uint8_t* store_now;
+    // DA: when given, the transposed output of group g is written only if t_flags[g] != 0
+    // (first-layer signal under the Gram statistic: only a group that uploads needs it, for its
+    // weight gradient; the others get it from mlp_gather_vec if they are selected after all)
+    const uint8_t* t_flags;
 };
 
 template <typename T>
@@ -746,6 +750,7 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
         // (all staging rows of a lane share bits 3 and 4 of the row index: those of the lane)
         static_assert(CW % 32 == 0, "staging rows of a lane differ by multiples of 32");
         [[maybe_unused]] const int t_swap = esz == 2 ? (((cl >> 3) ^ (cl >> 4)) & 1) * 4 : 0;
+        if (EPI != EPI_DA || !a.t_flags || a.t_flags[g]) {        // (the same for the whole workgroup)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -803,6 +808,7 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
             }
         }
         __syncthreads();
+        }
         // ---- row-major: stR [BM][PR], element (m, n) ----
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -1056,14 +1062,54 @@ __global__ __launch_bounds__(256) void mlp_gather(Hyper hy, const ShardDesc* __r
 // multiple of the vector length.  Xg may be null (the first forward GEMM then reads the shard
 // rows in place) -- only the transpose is written.
 // grid: (ceil(n0 / (8 V)), ceil(mu/64), G), block 256; V = elements per 16 bytes.
+// A second job of the same launch (workgroups with blockIdx.x >= the gather's ceil(n0 / TC)):
+// the transpose of a dense per-group matrix D [G][mu][ldd] (nd columns) into DT [G][nd][ldmu], for
+// the groups of `dsel` -- the first-layer signal of groups that are selected without having
+// written its transposed copy in the gradient stage.
+template <typename T>
+struct DenseTranspose {
+    const T* D;
+    T* DT;
+    int nd, ldd;
+    const uint8_t* dsel;
+};
+
 template <typename T>
 __global__ __launch_bounds__(256) void mlp_gather_vec(Hyper hy, const ShardDesc* __restrict__ shards,
                                                       const int32_t* __restrict__ idx, int n0, int ld0,
-                                                      int ldmu, T* __restrict__ Xg, T* __restrict__ XgT)
+                                                      int ldmu, T* __restrict__ Xg, T* __restrict__ XgT,
+                                                      DenseTranspose<T> dt)
 {
     constexpr int V = 16 / (int)sizeof(T), TC = 8 * V, PITCH = 64 + V;
     __shared__ __align__(16) T tileT[TC][PITCH];
-    const int g = blockIdx.z, c0 = blockIdx.x * TC, r0 = blockIdx.y * 64;
+    const int g = blockIdx.z, r0 = blockIdx.y * 64;
+    const int nbx = (n0 + TC - 1) / TC;
+    if ((int)blockIdx.x >= nbx) {
+        if (!dt.dsel[g]) return;
+        const int c0 = ((int)blockIdx.x - nbx) * TC;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int t = threadIdx.x + 256 * h, r = t / 8, cv = (t % 8) * V;
+            const int i = r0 + r, col = c0 + cv;
+            alignas(16) T v[V];
+#pragma unroll
+            for (int q = 0; q < V; ++q) v[q] = to_T<T>(0.0f);
+            // (rows are padded to ldd >= nd with zeros; ldd is a multiple of 64 elements)
+            if (i < hy.mu && col < dt.ldd) *(uint4*)v = *(const uint4*)(dt.D + ((int64_t)g * hy.mu + i) * dt.ldd + col);
+#pragma unroll
+            for (int q = 0; q < V; ++q) tileT[cv + q][r] = v[q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int t = threadIdx.x + 256 * h, c = t / (64 / V), rv = (t % (64 / V)) * V;
+            const int n = c0 + c, i = r0 + rv;
+            if (n < dt.nd && i < hy.mu)
+                *(uint4*)(dt.DT + ((int64_t)g * dt.nd + n) * ldmu + i) = *(const uint4*)&tileT[c][rv];
+        }
+        return;
+    }
+    const int c0 = blockIdx.x * TC;
     if (hy.sel && !hy.sel[g]) return;            // unselected group (server-side rule)
     const ShardDesc sh = shards[g];
     const T* X = (const T*)sh.X;
@@ -1823,7 +1869,7 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
     } else if (vec_ok) {
         dim3 grid((lay.n[0] + 8 * V - 1) / (8 * V), (mu + 63) / 64, G);
         mlp_gather_vec<T><<<grid, 256, 0, s>>>(hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
-                                                in_place ? nullptr : (T*)w->Xg, (T*)w->XgT);
+                                                in_place ? nullptr : (T*)w->Xg, (T*)w->XgT, DenseTranspose<T>{});
     } else {
         dim3 grid((lay.n[0] + 63) / 64, (mu + 63) / 64, G);
         mlp_gather<T><<<grid, 256, 0, s>>>(hy, c->d_shards, idx, lay.n[0], lay.ld[0], lay.ldmu,
@@ -1874,6 +1920,9 @@ static hipError_t mlp_gradients_t(gcada_ctx* c, const int32_t* idx, hipStream_t 
             a.relu_bits = (uint16_t*)w->relu[l - 1];
             a.O = w->dZ[l - 1]; a.o_it = rm_it(l - 1); a.o_g = rm_g(l - 1); a.ldo = lay.ld[l - 1];
             a.OT = w->dZT[l - 1]; a.t_it = tr_it(l - 1); a.t_g = tr_g(l - 1); a.ldt = lay.ldmu;
+            // with the Gram statistic the transposed first-layer signal serves only the weight
+            // gradient of uploading groups
+            if (l - 1 == 1 && gram) a.t_flags = c->store_now;
             if ((e = launch_gemm<T, EPI_DA>(a, 2 * G, w->small, s)) != hipSuccess) return e;
         }
     }
@@ -1913,10 +1962,14 @@ hipError_t mlp_store_selected(gcada_ctx* c, hipStream_t s)
         first = c->mask;
         Hyper hg = c->hy;
         hg.sel = first;
+        // The same launch transposes the first-layer signal of the groups that are selected
+        // without having been flagged: the gradient stage wrote the transposed copy only for
+        // the flagged ones.
         const Layout& lay = c->mlp->lay;
-        dim3 grid((lay.n[0] + 63) / 64, (hy.mu + 63) / 64, hy.G);
+        DenseTranspose<bf16_t> dt{(const bf16_t*)c->mlp->dZ[1], (bf16_t*)c->mlp->dZT[1], lay.n[1], lay.ld[1], c->redo};
+        dim3 grid((lay.n[0] + 63) / 64 + (lay.n[1] + 63) / 64, (hy.mu + 63) / 64, hy.G);
         mlp_gather_vec<bf16_t><<<grid, 256, 0, s>>>(hg, c->d_shards, c->mlp->idx_last, lay.n[0], lay.ld[0],
-                                                     lay.ldmu, nullptr, (bf16_t*)c->mlp->XgT);
+                                                     lay.ldmu, nullptr, (bf16_t*)c->mlp->XgT, dt);
     }
     if (c->mlp->bf16) return launch_dw_selected<bf16_t, false>(c, hy, first, s);
     return c->mlp->small ? launch_dw_selected<float, true>(c, hy, first, s)

@@ -1349,8 +1349,8 @@ struct GramArgs {
 };
 
 // eight waves of 32 x 64 (two per SIMD: with four, one wave per SIMD had nobody to hide its
-// waits behind; 56 -> 49 us for 3072-1024 at mu = 256)
-using GramTile = Tile<128, 128, 64, 4, 2, 2>;
+// waits behind; 56 -> 49 us for 3072-1024 at mu = 256), 128-byte k-tiles (-> 46.5 us)
+using GramTile = Tile<128, 128, 128, 4, 2, 2>;
 
 // acc += rows[m0..] rows[n0..]^T over the k-tiles [k_lo, k_hi) of 32 elements; rows at base + off.
 // The tile is small, so a k-tile is little MFMA work against a trip to memory: FOUR k-tiles are in

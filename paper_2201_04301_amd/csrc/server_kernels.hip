@@ -474,14 +474,16 @@ constexpr int kBigBlock = 1024;
 hipError_t select_plan(gcada_ctx* c)
 {
     // every per-parameter vector is padded to pstride (a multiple of 64): always four per thread.
-    // At most two blocks per compute unit: each block prepares the selection once and then
-    // walks over its slabs of the parameter vector.
+    // At most one block per compute unit (its 68 registers per thread let only one 1024-thread
+    // block be resident there anyway): each block prepares the selection once, walks over its
+    // slabs of the parameter vector and ends with a device-wide fence -- about 4 + 11 us that a
+    // second round of blocks would pay again (4.2 M parameters, no upload: 46 -> 35 us).
     const int64_t per_block = (int64_t)kUpdBlock * 4;
     const int64_t slabs = (c->hy.pstride + per_block - 1) / per_block;
     hipDeviceProp_t prop;
     hipError_t e = hipGetDeviceProperties(&prop, c->device);
     if (e != hipSuccess) return e;
-    c->n_epi_blocks = (int32_t)std::min<int64_t>(slabs, 2 * (int64_t)prop.multiProcessorCount);
+    c->n_epi_blocks = (int32_t)std::min<int64_t>(slabs, (int64_t)prop.multiProcessorCount);
     return hipSuccess;
 }
 

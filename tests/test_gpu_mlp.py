@@ -157,6 +157,42 @@ def test_mlp_lazy_gradient_store_changes_nothing(widths, mu, G, rows, dtype_cfg)
     assert (sel & forced).any() and (sel & ~forced).any() and (~sel).any()
 
 
+def test_mlp_lazy_gradient_store_switched_during_a_run_changes_nothing():
+    # the store flags of a step are set by the last launch of the step before; switching the
+    # option (or the Gram statistic's, or loading a state) in between must make the next step set
+    # them anew.  A run that switches back and forth ends in the bits of one that never does.
+    from paper_2201_04301_amd import Gcada, binding as B
+    from gcada_inputs import make_theta0
+    w = scaled(CONFIGS["mlp_3072_bf16"], name="mlp_lazy", widths=(300, 260, 10), mu=128, G=5, rows=200, D=4, c=0.6)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 24
+    idx = torch.as_tensor(make_indices(w, steps), device="cuda")
+    runs = []
+    for switching in (False, True):
+        gpu = Gcada.from_workload(w)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_GRAM_STATISTIC, 0)
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, 1)
+        masks = []
+        for k in range(steps):
+            if switching and k in (5, 13):
+                B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, 0)
+            if switching and k in (8, 17):
+                B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, 1)
+            if switching and k == 20:
+                gpu.set_state(**gpu.get_state())          # a reload of the same state
+            gpu.step(idx[k].contiguous())
+            masks.append(gpu.outputs()["mask"].copy())
+        runs.append(dict(masks=np.array(masks), state=gpu.get_state()))
+        gpu.close()
+    a, b = runs
+    np.testing.assert_array_equal(a["masks"], b["masks"])
+    for name in ("theta", "h", "vhat", "agg", "last", "theta_stale", "tau", "dtheta_sq"):
+        np.testing.assert_array_equal(a["state"][name], b["state"][name], err_msg=name)
+    assert a["masks"].any() and not a["masks"].all()
+
+
 def test_mlp_free_run_loss_decreases_and_tracks_oracle(par):
     w = scaled(CONFIGS["mlp_784"], name="mlp_f32", widths=(64, 48, 10), mu=64, G=4, rows=400, D=5)
     Xs, ys = make_shards(w, "cuda")

@@ -31,7 +31,8 @@
  * a constant gradient, central finite differences of the loss, the logistic
  * loss and gradient at theta = 0, library autograd on tiny networks, the
  * c = 0 collapse to plain distributed AMSGrad, the periodic mask for huge c,
- * the aggregate identity, group-permutation invariance.  The figures the
+ * the aggregate identity, group-permutation invariance; the ReLU-kink
+ * diagnostic against hand-built power-of-two networks.  The figures the
  * paper prints for its experiment (Sec. VI) need its dataset and unstated
  * settings: parity unpinned for those.
  *

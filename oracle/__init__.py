@@ -97,7 +97,7 @@ class Config:
     beta2: float = 0.999
     eps: float = 1e-8
     l2: float = 0.0
-    round_bf16: bool = False
+    round_bf16: int = 0        # 0 none; 1 X and theta; 2 also the hidden activations (see gcada_oracle.c)
     _c: _Cfg = field(init=False, repr=False, default=None)
 
     def c_struct(self) -> _Cfg:
@@ -107,7 +107,7 @@ class Config:
         for i, w in enumerate(self.widths):
             s.widths[i] = int(w)
         s.batch, s.G, s.D = self.batch, self.G, self.D
-        s.round_bf16 = 1 if self.round_bf16 else 0
+        s.round_bf16 = int(self.round_bf16)
         s.l2, s.c, s.alpha = self.l2, self.c, self.alpha
         s.beta1, s.beta2, s.eps = self.beta1, self.beta2, self.eps
         return s

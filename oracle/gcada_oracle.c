@@ -54,7 +54,9 @@ typedef struct orc_config {
     int32_t batch;       /* mu: minibatch size per group */
     int32_t G;           /* number of groups */
     int32_t D;           /* history depth / maximum age */
-    int32_t round_bf16;  /* 1: gradients are evaluated at theta rounded fp64->fp32->bf16 (RNE) */
+    int32_t round_bf16;  /* 1: gradients are evaluated at theta rounded fp64->fp32->bf16 (RNE);
+                            2: also every hidden activation is rounded to bf16 (every layer's
+                               product then has bf16 inputs), see mlp_sample */
     double l2;           /* lambda: each sample's loss gets + (lambda/2)||theta||^2 */
     double c, alpha, beta1, beta2, eps;
 } orc_config;
@@ -147,6 +149,12 @@ static double quadratic_sample(const double *theta, const float *x, double y, in
 
 /* MLP: a_0 = x; z_l = W_l a_{l-1} + b_l; a_l = max(z_l, 0) for l < L; logits = z_L;
    loss = log sum exp(logits) - logits[y].  ReLU'(0) = 0.
+   round_bf16 == 2 (the bf16 configuration: "bf16 inputs and weights, fp32 accumulation" read as
+   every layer's matrix product taking bf16 inputs): a_l <- bf16(a_l) for the hidden layers, so
+   the next layer's pre-activation -- whose SIGN is a discrete decision (which ReLU branch) -- is
+   formed from the values a bf16 implementation multiplies; the rounding is treated as the
+   identity in the backward pass (the signal passes where a_l > 0) and the weight gradient
+   multiplies the rounded activation.  Sums stay fp64 and nothing else is rounded.
    work: 2 * sum(widths) doubles (activations, then deltas). */
 static double mlp_sample(const orc_config *cfg, const double *theta, const float *x, int32_t y,
                          double *grad, double *work, double *kink)
@@ -174,6 +182,7 @@ static double mlp_sample(const orc_config *cfg, const double *theta, const float
                land on the other side of the kink when this is tiny) */
             if (kink && l < L && az > 0 && fabs(z) / az < *kink) *kink = fabs(z) / az;
             act[l][o] = (l < L && z < 0) ? 0.0 : z;      /* z == 0 stays 0 either way */
+            if (l < L && cfg->round_bf16 == 2) act[l][o] = bf16_round(act[l][o]);
         }
         W = b + n[l];
     }

@@ -3,9 +3,11 @@
 Teacher forcing: before every step the oracle's state is rounded to fp32 in place and copied to
 the GPU, so both sides start the step from identical values and a flipped selection cannot fork
 the run.  The shared state always comes from the oracle; nothing the GPU computed enters the
-oracle.  Tolerances: vectors are compared norm-wise,
-max|a-b| <= tol * max|b|; scalars relatively; masks must agree unless the oracle's statistic is
-within `edge` (relative) of the threshold.
+oracle.  Tolerances: vectors are compared twice -- norm-wise, max|a-b| <= tol * max|b|, and
+element by element, |a_j - b_j| <= tol * |b_j| + tol * rms(b) (an element that is itself a
+cancelled sum is held to the typical element's size, not to its own); scalars relatively; masks
+must agree unless the oracle's statistic is within `edge` (relative) of the threshold or, where
+said, within the measured error of the statistic itself.
 """
 from __future__ import annotations
 
@@ -22,7 +24,7 @@ def oracle_config(w: Workload) -> O.Config:
     model = {"logreg": O.LOGISTIC, "mlp": O.MLP, "linreg": O.QUADRATIC}[w.model]
     return O.Config(model, list(w.widths), batch=w.mu, G=w.G, D=w.D, c=w.c, alpha=w.alpha,
                     beta1=w.beta1, beta2=w.beta2, eps=w.eps, l2=w.l2,
-                    round_bf16=(w.dtype == "bf16"))
+                    round_bf16=(2 if w.dtype == "bf16" else 0))
 
 
 ATOL = 1e-12   # quantities below this are numerically zero for these workloads (e.g. the gradient
@@ -34,6 +36,41 @@ def vec_err(a, b) -> float:
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     return float(np.abs(a - b).max() / max(np.abs(b).max(), ATOL / 1e-5))
+
+
+def elem_err(a, b) -> float:
+    """max_j |a_j - b_j| / (|b_j| + rms(b)): the mixed element-wise error (same absolute floor)."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    rms = max(float(np.sqrt(np.mean(b * b))), ATOL / 1e-5)
+    return float((np.abs(a - b) / (np.abs(b) + rms)).max())
+
+
+def check_vec(a, b, tol, what) -> float:
+    """Assert both vector criteria; returns the norm-wise error."""
+    e = vec_err(a, b)
+    assert e <= tol, f"{what}: error {e:.3e} (norm-wise)"
+    ee = elem_err(a, b)
+    assert ee <= tol, f"{what}: error {ee:.3e} (element-wise)"
+    return e
+
+
+def check_theta(w, theta_gpu, orc, uploaded: bool, tol, what) -> float:
+    """theta after the update: the step divides by sqrt(eps + vhat), so an absolute error da in
+    the aggregate moves theta_j by up to kappa_j * da, kappa_j = alpha (1-beta1) / sqrt(eps + vhat_j)
+    (large while vhat_j ~ 0).  When no group uploaded, the aggregate is the forced state itself and
+    only the update's own rounding remains.  Returns max error / max|theta|."""
+    th_o = orc.theta
+    scale = np.abs(th_o).max()
+    err = np.abs(np.asarray(theta_gpu, dtype=np.float64) - th_o)
+    if uploaded:
+        kappa = w.alpha * (1 - w.beta1) / np.sqrt(w.eps + orc.vhat)
+        bound = tol * scale + 2 * kappa * tol * np.abs(orc.agg).max()
+    else:
+        bound = np.full_like(err, 1e-6 * scale)
+    j = int(np.argmax(err - bound))
+    assert err[j] <= bound[j], f"{what}: theta[{j}] error {err[j]:.3e} > bound {bound[j]:.3e}"
+    return float(err.max() / scale)
 
 
 def rel_err(a: float, b: float) -> float:
@@ -52,7 +89,8 @@ def push_state(orc: O.Oracle, gpu: Gcada):
 
 
 def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, kink_tol=None,
-                   kink_grad_tol=5e-2, stat_vs_threshold=False, verbose=False, server_rule_L=None, lazy_store=None):
+                   kink_grad_tol=5e-2, stat_vs_threshold=False, verbose=False, server_rule_L=None, lazy_store=None,
+                   edge_stat_err=False, options=()):
     """Run `steps` iterations; idx: int32 (steps, G, mu) row ids or None for the cyclic window.
     kink_tol (MLP): a group is "near a ReLU kink" in a step when some hidden pre-activation of the
     oracle lies within kink_tol (relative to the sum of the magnitudes of its terms) of zero.
@@ -63,6 +101,11 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
     stat_vs_threshold (bf16): the statistic's error is measured against max(stat, rhs) -- the
     statistic only matters through its comparison with the threshold, and once the gradients have
     collapsed below the bf16 noise floor its relative error alone says nothing.
+    edge_stat_err (bf16): a mask difference is also accepted where the oracle's statistic lies no
+    further from the threshold than the GPU's statistic lies from the oracle's -- that error has
+    just been held to `tol`, and a statistic that is off by it may land on the other side.  The
+    plain rule (|stat - rhs| < edge * rhs with edge = 1e-6) stays in force otherwise.
+    options: (option, value) pairs for gcada_set_option.
     server_rule_L: G smoothness constants -> both sides run the server-side rule of Sec. IV
     (selection from the iterates before the gradients; only selected groups evaluate one); then
     the gradients of the selected groups only are compared, and `stat` is the rule's left side.
@@ -76,16 +119,20 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
     gpu.set_theta(make_theta0(w))
     if lazy_store is not None:
         B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, int(lazy_store))
+    for opt, val in options:
+        B.gcada_set_option(gpu.ctx, opt, val)
     if server_rule_L is not None:
         orc.set_rule(1, server_rule_L)
         gpu.set_rule("server", server_rule_L)
     idx_dev = torch.as_tensor(idx, device="cuda") if idx is not None else None
-    worst = dict(grad=0.0, stat=0.0, rhs=0.0, loss=0.0, theta=0.0, h=0.0, vhat=0.0, agg=0.0,
-                 ring=0.0, edge_flips=0, selected=0, kink_groups=0, clean_groups=0, state_steps=0)
+    worst = dict(grad=0.0, grad_elem=0.0, stat=0.0, rhs=0.0, loss=0.0, theta=0.0, h=0.0, vhat=0.0, agg=0.0,
+                 ring=0.0, edge_flips=0, selected=0, kink_groups=0, clean_groups=0, state_steps=0,
+                 forced_late=0, by_statistic=0, max_age=0)
     rows_all = [X.shape[0] for X in Xs]
     for k in range(steps):
         round_state_to_f32(orc)
         push_state(orc, gpu)
+        tau_before = orc.tau.copy()
         if idx is not None:
             step_idx = idx[k]
         else:
@@ -111,6 +158,9 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
                 continue
             worst["grad"] = max(worst["grad"], e)
             assert e <= tol, f"step {k} group {g}: gradient error {e:.3e}"
+            ee = elem_err(out["grad"][g], orc.grad[g])
+            worst["grad_elem"] = max(worst["grad_elem"], ee)
+            assert ee <= tol, f"step {k} group {g}: gradient error {ee:.3e} (element-wise)"
         # a2: statistic, threshold, mask
         s_o = orc.stat
         for g in range(w.G):
@@ -132,10 +182,15 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
         for g in np.nonzero(flips)[0]:
             if near[g]:
                 continue
-            assert abs(s_o[g] - orc.rhs) < edge * orc.rhs, \
+            slack = abs(out["stat"][g] - s_o[g]) if edge_stat_err else 0.0
+            assert abs(s_o[g] - orc.rhs) < edge * orc.rhs or abs(s_o[g] - orc.rhs) <= slack, \
                 f"step {k} group {g}: mask {out['mask'][g]} vs {mask_o[g]}, stat {s_o[g]} rhs {orc.rhs}"
             worst["edge_flips"] += 1
         worst["selected"] += int(mask_o.sum())
+        if k > 0:       # uploads forced by the age bound, and uploads the statistic asked for
+            worst["forced_late"] += int(((mask_o != 0) & (tau_before >= w.D)).sum())
+            worst["by_statistic"] += int(((mask_o != 0) & (tau_before < w.D)).sum())
+        worst["max_age"] = max(worst["max_age"], int(tau_before.max()) if k > 0 else 0)
         assert np.array_equal(gpu.mask_out.cpu().numpy(), out["mask"])
         e = rel_err(out["loss"], loss_o)
         worst["loss"] = max(worst["loss"], e)
@@ -146,29 +201,12 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
         worst["state_steps"] += 1
         # a3 / a4
         for name in ("agg", "h", "vhat"):
-            e = vec_err(st[name], getattr(orc, name))
-            worst[name] = max(worst[name], e)
-            assert e <= tol, f"step {k}: {name} error {e:.3e}"
-        # theta: the update divides by sqrt(eps + vhat), so an absolute error da in the aggregate
-        # moves theta_j by up to kappa_j * da with kappa_j = alpha (1-beta1) / sqrt(eps + vhat_j)
-        # (large while vhat_j ~ 0).  When no group uploaded, the aggregate is the forced state
-        # itself and only the update's own rounding remains.
-        th_o = orc.theta
-        scale = np.abs(th_o).max()
-        err = np.abs(st["theta"].astype(np.float64) - th_o)
-        if mask_o.any():
-            kappa = w.alpha * (1 - w.beta1) / np.sqrt(w.eps + orc.vhat)
-            bound = tol * scale + 2 * kappa * tol * np.abs(orc.agg).max()
-        else:
-            bound = np.full_like(err, 1e-6 * scale)
-        worst["theta"] = max(worst["theta"], float(err.max() / scale))
-        j = int(np.argmax(err - bound))
-        assert err[j] <= bound[j], f"step {k}: theta[{j}] error {err[j]:.3e} > bound {bound[j]:.3e}"
+            worst[name] = max(worst[name], check_vec(st[name], getattr(orc, name), tol, f"step {k}: {name}"))
+        worst["theta"] = max(worst["theta"], check_theta(w, st["theta"], orc, bool(mask_o.any()), tol, f"step {k}"))
         np.testing.assert_array_equal(st["tau"], orc.tau)
-        e = vec_err(st["last"], orc.last)
-        assert e <= tol, f"step {k}: stored gradients error {e:.3e}"
-        e = vec_err(st["theta_stale"], orc.theta_stale)
-        assert e <= tol, f"step {k}: stale iterates error {e:.3e}"
+        for g in range(w.G):
+            check_vec(st["last"][g], orc.last[g], tol, f"step {k}: stored gradient of group {g}")
+        check_vec(st["theta_stale"], orc.theta_stale, tol, f"step {k}: stale iterates")
         e = vec_err(st["dtheta_sq"], orc.ring)
         worst["ring"] = max(worst["ring"], e)
         assert e <= tol, f"step {k}: history error {e:.3e}"
@@ -209,16 +247,18 @@ def free_running(w: Workload, steps, Xs, ys, idx=None, options=()):
                 theta_gpu=theta_g, theta_oracle=orc.theta.copy())
 
 
-def synthetic_state(w: Workload, seed=7):
-    """A valid mid-run state made from seeded random numbers only (no run needed): ages in [1, D],
-    groups of equal age share their stale iterate, moments and stored gradients of plausible size."""
+def synthetic_state(w: Workload, seed=7, tau=None):
+    """A valid mid-run state made from seeded random numbers only (no run needed): ages in [1, D]
+    (drawn, or the G given ones), groups of equal age share their stale iterate, moments and stored
+    gradients of plausible size."""
     rng = np.random.default_rng(seed)
     p, G, D = w.p, w.G, w.D
     theta0 = make_theta0(w).astype(np.float64)
     scale = max(np.abs(theta0).max(), 0.05)
     # hist[t] = iterate t steps ago: further back, further away from the current iterate
     hist = [theta0 + 0.02 * scale * (t + 1) * rng.standard_normal(p) for t in range(D + 1)]
-    tau = rng.integers(1, D + 1, size=G).astype(np.int32)
+    drawn = rng.integers(1, D + 1, size=G).astype(np.int32)
+    tau = drawn if tau is None else np.asarray(tau, dtype=np.int32)
     f32 = lambda a: np.asarray(a, np.float32).astype(np.float64)
     st = dict(theta=f32(hist[0]), h=f32(0.1 * rng.standard_normal(p)), vhat=f32(rng.random(p) * 0.5),
               agg=f32(rng.standard_normal(p)), theta_stale=f32(np.stack([hist[t] for t in tau])),
@@ -227,18 +267,9 @@ def synthetic_state(w: Workload, seed=7):
     return st
 
 
-def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e-6, kink_tol=None,
-                        seed=7, lazy_store=None):
-    """One iteration of the full-size workload on the GPU from a synthetic state; the oracle
-    evaluates only the sampled `groups` (each group's gradients, statistic and mask depend on its
-    own shard and state only) and those outputs are compared."""
-    st = synthetic_state(w, seed)
-    gpu = Gcada.from_workload(w)
-    gpu.set_shards(Xs, ys)
-    gpu.set_theta(make_theta0(w))
-    gpu.set_state(**st)
-    if lazy_store is not None:
-        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, int(lazy_store))
+def sampled_oracle_step(w: Workload, st, Xs, ys, idx_step, groups):
+    """The oracle's step for the sampled `groups` only, from the state `st` of the whole workload
+    (each group's gradients, statistic and mask depend on its own shard and state only)."""
     ws = replace_groups(w, len(groups))
     orc = O.Oracle(oracle_config(ws), make_theta0(w))
     for name in ("theta", "h", "vhat", "agg"):
@@ -250,27 +281,93 @@ def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e
     orc.k = st["k"]
     Xmb, ymb = gather_rows([Xs[g] for g in groups], [ys[g] for g in groups], idx_step[groups])
     mask_o, _ = orc.step(Xmb, ymb)
+    return orc, mask_o
+
+
+def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e-6, kink_tol=None,
+                        seed=7, lazy_store=None, edge_stat_err=False, options=(), reference=None,
+                        whole_state=False):
+    """One iteration of the full-size workload on the GPU from a synthetic state; the oracle
+    evaluates only the sampled `groups` and those groups' gradients, statistics and masks are
+    compared.  reference: (state, oracle, mask) of an earlier call on the same inputs (the oracle's
+    step is the expensive part; it does not depend on the GPU options).
+    whole_state: the workload must make the sampled groups the ONLY ones that can be selected
+    (their age is D, everybody else is younger, and c is so large that no statistic reaches the
+    threshold): then the aggregate, moments, iterate, history entry, ages and stored gradients
+    after the step are determined by what the oracle evaluated, and the whole state is compared."""
+    groups = list(groups)
+    if reference is None:
+        tau = None
+        if whole_state:
+            rng = np.random.default_rng(seed + 1)
+            tau = rng.integers(1, w.D, size=w.G)             # 1 .. D-1: cannot be forced
+            tau[groups] = w.D
+        st = synthetic_state(w, seed, tau)
+        orc, mask_o = sampled_oracle_step(w, st, Xs, ys, idx_step, groups)
+    else:
+        st, orc, mask_o = reference
+    gpu = Gcada.from_workload(w)
+    gpu.set_shards(Xs, ys)
+    gpu.set_theta(make_theta0(w))
+    gpu.set_state(**st)
+    if lazy_store is not None:
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_LAZY_GRADIENT_STORE, int(lazy_store))
+    for opt, val in options:
+        B.gcada_set_option(gpu.ctx, opt, val)
     gpu.step(torch.as_tensor(idx_step, device="cuda").contiguous())
     out = gpu.outputs()
-    worst = dict(grad=0.0, stat=0.0, rhs=rel_err(out["rhs"], orc.rhs), kink_groups=0)
+    worst = dict(grad=0.0, grad_elem=0.0, stat=0.0, rhs=rel_err(out["rhs"], orc.rhs), kink_groups=0,
+                 selected=int(mask_o.sum()), ages=sorted(set(int(t) for t in st["tau"][groups])))
     assert worst["rhs"] <= 1e-9
+    near_any = False
     for j, g in enumerate(groups):
         near = kink_tol is not None and orc.kink[j] < kink_tol
         materialised = not lazy_store or bool(out["mask"][g])
         e = vec_err(out["grad"][g], orc.grad[j]) if materialised else 0.0
         if near:
             worst["kink_groups"] += 1
+            near_any = near_any or bool(mask_o[j])
             assert e <= 5e-2, f"group {g} (near a kink): gradient error {e:.3e}"
             continue
         worst["grad"] = max(worst["grad"], e)
         assert e <= tol, f"group {g}: gradient error {e:.3e}"
-        e = rel_err(out["stat"][g], orc.stat[j])
+        if materialised:
+            ee = elem_err(out["grad"][g], orc.grad[j])
+            worst["grad_elem"] = max(worst["grad_elem"], ee)
+            assert ee <= tol, f"group {g}: gradient error {ee:.3e} (element-wise)"
+        gn2 = float(np.dot(orc.grad[j], orc.grad[j]))
+        e = abs(out["stat"][g] - orc.stat[j]) / max(abs(orc.stat[j]), tol * gn2, ATOL / 1e-5)
         worst["stat"] = max(worst["stat"], e)
         assert e <= tol, f"group {g}: stat {out['stat'][g]} vs {orc.stat[j]}"
         if out["mask"][g] != mask_o[j]:
-            assert abs(orc.stat[j] - orc.rhs) < edge * orc.rhs, f"group {g}: mask differs"
+            slack = abs(out["stat"][g] - orc.stat[j]) if edge_stat_err else 0.0
+            d = abs(orc.stat[j] - orc.rhs)
+            assert d < edge * orc.rhs or d <= slack, f"group {g}: mask differs"
+    if whole_state:
+        assert mask_o.all()
+        others = np.setdiff1d(np.arange(w.G), groups)
+        expect = np.zeros(w.G, np.uint8)
+        expect[groups] = 1
+        np.testing.assert_array_equal(out["mask"], expect)
+        after = gpu.get_state()
+        assert after["k"] == st["k"] + 1
+        tau_expect = st["tau"] + 1
+        tau_expect[groups] = 1
+        np.testing.assert_array_equal(after["tau"], tau_expect)
+        # groups that did not upload keep their stored gradient and their stale iterate, bit for bit
+        np.testing.assert_array_equal(after["last"][others], st["last"][others].astype(np.float32))
+        np.testing.assert_array_equal(after["theta_stale"][others], st["theta_stale"][others].astype(np.float32))
+        if not near_any:
+            for name in ("agg", "h", "vhat"):
+                worst[name] = check_vec(after[name], getattr(orc, name), tol, name)
+            worst["theta"] = check_theta(w, after["theta"], orc, True, tol, "after the step")
+            for j, g in enumerate(groups):
+                check_vec(after["last"][g], orc.last[j], tol, f"stored gradient of group {g}")
+                np.testing.assert_array_equal(after["theta_stale"][g], st["theta"].astype(np.float32))
+            worst["ring"] = vec_err(after["dtheta_sq"], orc.ring)
+            assert worst["ring"] <= tol, f"history error {worst['ring']:.3e}"
     gpu.close()
-    return worst
+    return worst, (st, orc, mask_o)
 
 
 def replace_groups(w: Workload, G: int) -> Workload:

@@ -288,13 +288,34 @@ def test_lr_4k_full_size_teacher_forced(par):
     assert worst["selected"] >= 2 * w.G
 
 
-def test_lr_64k_full_step_shape(par):
+def test_lr_4k_full_size_free_run_loss_curve(par):
+    # configuration 2 at full size, both sides on their own for 60 iterations
+    w = CONFIGS["lr_4k"]
+    Xs, ys = make_shards(w, "cuda")
+    steps = 60
+    idx = make_indices(w, steps)
+    r = par.free_running(w, steps, Xs, ys, idx)
+    agree = (r["masks_gpu"] == r["masks_oracle"]).mean()
+    _say("mask agreement", agree, "loss", r["loss_gpu"][0], "->", r["loss_gpu"][-1], r["loss_oracle"][-1],
+         "uploads", int(r["masks_gpu"].sum()), "of", steps * w.G)
+    assert agree >= 0.98
+    assert r["loss_gpu"][-1] < r["loss_gpu"][0]
+    np.testing.assert_allclose(r["loss_gpu"], r["loss_oracle"], rtol=2e-3)
+    np.testing.assert_allclose(r["theta_gpu"], r["theta_oracle"], rtol=0, atol=2e-3 * np.abs(r["theta_oracle"]).max())
+
+
+@pytest.mark.parametrize("c,D,steps", [(1.0, 10, 13), (1e30, 4, 7)])
+def test_lr_64k_full_step_shape(par, c, D, steps):
     # configuration 4's step shape (G=32, mu=1024, d=65,536: 8.6 GB of rows touched per step) on
-    # shards of 2,048 rows; every group checked against the oracle, teacher-forced
-    w = scaled(CONFIGS["lr_64k"], rows=2048)
+    # shards of 2,048 rows; every group checked against the oracle, teacher-forced over steps
+    # 0 .. D+2 (the configuration's D and c), and with a threshold no statistic reaches, where every
+    # group ages to D and is forced to upload at this shape
+    w = scaled(CONFIGS["lr_64k"], rows=2048, c=c, D=D)
     _say("case", w)
     Xs, ys = make_shards(w, "cuda", chunk_rows=1024)
-    steps = 3
     idx = make_indices(w, steps)
     worst = par.teacher_forced(w, steps, Xs, ys, idx)
     _say(worst)
+    assert worst["state_steps"] == steps
+    if c > 1e20:
+        assert worst["forced_late"] == w.G and worst["by_statistic"] == 0 and worst["max_age"] == D

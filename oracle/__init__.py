@@ -23,7 +23,7 @@ _LIB = os.path.join(_HERE, "libgcada_oracle.so")
 LOGISTIC, MLP, QUADRATIC = 0, 1, 2
 
 (F_THETA, F_H, F_VHAT, F_AGG, F_THETA_STALE, F_LAST, F_GRAD, F_GRAD_STALE, F_STAT, F_RING,
- F_LOSS_G, F_KINK) = range(12)
+ F_LOSS_G, F_KINK, F_KINK_UNIT) = range(13)
 
 
 def build(force: bool = False) -> str:
@@ -198,6 +198,8 @@ class Oracle:
     ring = property(lambda s: s._view(F_RING, (s.cfg.D,)))
     loss_g = property(lambda s: s._view(F_LOSS_G, (s.cfg.G,)))
     kink = property(lambda s: s._view(F_KINK, (s.cfg.G,)))
+    # the same per hidden unit (layer 1's units first): (G, sum of the hidden widths)
+    kink_unit = property(lambda s: s._view(F_KINK_UNIT, (s.cfg.G, sum(s.cfg.widths[1:-1]) if s.cfg.model == MLP else 0)))
 
     @property
     def tau(self):

@@ -73,6 +73,10 @@ typedef struct orc_ctx {
     double *loss_g;                      /* G: minibatch loss sums at theta^k   */
     double *kink;                        /* G: smallest relative distance of a hidden pre-activation
                                             to the ReLU kink in this step (diagnostic; 1 if none) */
+    double *kink_unit;                   /* G x H, H = sum of the hidden widths: the same per hidden
+                                            unit (layer 1's units first), minimum over the group's
+                                            samples and both iterates; 1 if never evaluated */
+    int64_t H;
     double rhs, loss;
     int32_t *tau;                        /* G                                   */
     uint8_t *mask;                       /* G                                   */
@@ -157,7 +161,7 @@ static double quadratic_sample(const double *theta, const float *x, double y, in
    multiplies the rounded activation.  Sums stay fp64 and nothing else is rounded.
    work: 2 * sum(widths) doubles (activations, then deltas). */
 static double mlp_sample(const orc_config *cfg, const double *theta, const float *x, int32_t y,
-                         double *grad, double *work, double *kink)
+                         double *grad, double *work, double *kink, double *kink_unit)
 {
     const int L = cfg->n_widths - 1;
     const int32_t *n = cfg->widths;
@@ -168,6 +172,7 @@ static double mlp_sample(const orc_config *cfg, const double *theta, const float
 
     for (int j = 0; j < n[0]; ++j) act[0][j] = (double)x[j];
     const double *W = theta;
+    int64_t unit0 = 0;                   /* index of this layer's first unit among the hidden units */
     for (int l = 1; l <= L; ++l) {
         const double *b = W + (int64_t)n[l] * n[l - 1];
         for (int o = 0; o < n[l]; ++o) {
@@ -181,10 +186,12 @@ static double mlp_sample(const orc_config *cfg, const double *theta, const float
                to the sum of the magnitudes of its terms (a comparison in lower precision may
                land on the other side of the kink when this is tiny) */
             if (kink && l < L && az > 0 && fabs(z) / az < *kink) *kink = fabs(z) / az;
+            if (kink_unit && l < L && az > 0 && fabs(z) / az < kink_unit[unit0 + o]) kink_unit[unit0 + o] = fabs(z) / az;
             act[l][o] = (l < L && z < 0) ? 0.0 : z;      /* z == 0 stays 0 either way */
             if (l < L && cfg->round_bf16 == 2) act[l][o] = bf16_round(act[l][o]);
         }
         W = b + n[l];
+        unit0 += n[l];
     }
     /* softmax cross-entropy on the logits act[L] */
     double zmax = act[L][0];
@@ -226,7 +233,7 @@ static double mlp_sample(const orc_config *cfg, const double *theta, const float
    OVERWRITTEN with the gradient of that sum.  X is n x widths[0] row-major fp32 (promoted
    exactly); y is float[n] (logistic: +-1, quadratic: target) or int32[n] (MLP class id). */
 static double loss_grad_sum_k(const orc_config *cfg, const double *theta, const float *X,
-                              const void *y, int64_t n, double *grad, double *kink)
+                              const void *y, int64_t n, double *grad, double *kink, double *kink_unit)
 {
     const int64_t p = orc_param_count(cfg);
     const int64_t d = cfg->widths[0];
@@ -245,7 +252,7 @@ static double loss_grad_sum_k(const orc_config *cfg, const double *theta, const 
         else if (cfg->model == ORC_QUADRATIC)
             loss += quadratic_sample(theta, x, (double)((const float *)y)[i], d, grad);
         else
-            loss += mlp_sample(cfg, theta, x, ((const int32_t *)y)[i], grad, work, kink);
+            loss += mlp_sample(cfg, theta, x, ((const int32_t *)y)[i], grad, work, kink, kink_unit);
     }
     free(work);
     if (cfg->l2 != 0) {
@@ -261,7 +268,7 @@ static double loss_grad_sum_k(const orc_config *cfg, const double *theta, const 
 double orc_loss_grad_sum(const orc_config *cfg, const double *theta, const float *X, const void *y,
                          int64_t n, double *grad)
 {
-    return loss_grad_sum_k(cfg, theta, X, y, n, grad, NULL);
+    return loss_grad_sum_k(cfg, theta, X, y, n, grad, NULL, NULL);
 }
 
 /* Server update, Eq. (8a)-(8c):
@@ -293,7 +300,7 @@ void orc_destroy(orc_ctx *c)
     if (!c) return;
     free(c->theta); free(c->h); free(c->vhat); free(c->agg);
     free(c->theta_stale); free(c->last); free(c->grad); free(c->grad_stale);
-    free(c->stat); free(c->ring); free(c->loss_g); free(c->kink); free(c->tau); free(c->mask);
+    free(c->stat); free(c->ring); free(c->loss_g); free(c->kink); free(c->kink_unit); free(c->tau); free(c->mask);
     free(c->L);
     free(c);
 }
@@ -312,6 +319,10 @@ orc_ctx *orc_create(const orc_config *cfg)
     c->grad = calloc(G * p, 8); c->grad_stale = calloc(G * p, 8);
     c->stat = calloc(G, 8); c->ring = calloc(cfg->D, 8); c->loss_g = calloc(G, 8); c->kink = calloc(G, 8);
     c->tau = calloc(G, 4); c->mask = calloc(G, 1); c->L = calloc(G, 8);
+    c->H = 0;
+    if (cfg->model == ORC_MLP)
+        for (int l = 1; l < cfg->n_widths - 1; ++l) c->H += cfg->widths[l];
+    c->kink_unit = calloc(G * (c->H > 0 ? c->H : 1), 8);
     for (int g = 0; g < G; ++g) c->tau[g] = cfg->D;
     return c;
 }
@@ -370,6 +381,7 @@ static void orc_step_server_rule(orc_ctx *c, const float *X, const void *y, uint
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t g = 0; g < G; ++g) {
         c->kink[g] = 1.0;
+        for (int64_t u = 0; u < c->H; ++u) c->kink_unit[g * c->H + u] = 1.0;
         c->loss_g[g] = 0;
         if (!c->mask[g]) continue;
         const float *Xg = X + g * mu * d;
@@ -380,7 +392,7 @@ static void orc_step_server_rule(orc_ctx *c, const float *X, const void *y, uint
             for (int64_t j = 0; j < p; ++j) ev[j] = bf16_round(pt[j]);
             pt = ev;
         }
-        c->loss_g[g] = loss_grad_sum_k(cfg, pt, Xg, yg, mu, c->grad + g * p, c->kink + g);
+        c->loss_g[g] = loss_grad_sum_k(cfg, pt, Xg, yg, mu, c->grad + g * p, c->kink + g, c->kink_unit + g * c->H);
         free(ev);
     }
     double loss = 0;
@@ -432,8 +444,9 @@ void orc_step(orc_ctx *c, const float *X, const void *y, uint8_t *mask_out, doub
             pt = ev; ps = evs;
         }
         c->kink[g] = 1.0;
-        c->loss_g[g] = loss_grad_sum_k(cfg, pt, Xg, yg, mu, c->grad + g * p, c->kink + g);
-        loss_grad_sum_k(cfg, ps, Xg, yg, mu, c->grad_stale + g * p, c->kink + g);
+        for (int64_t u = 0; u < c->H; ++u) c->kink_unit[g * c->H + u] = 1.0;
+        c->loss_g[g] = loss_grad_sum_k(cfg, pt, Xg, yg, mu, c->grad + g * p, c->kink + g, c->kink_unit + g * c->H);
+        loss_grad_sum_k(cfg, ps, Xg, yg, mu, c->grad_stale + g * p, c->kink + g, c->kink_unit + g * c->H);
         double s = 0;
         for (int64_t j = 0; j < p; ++j) {
             double df = c->grad[g * p + j] - c->grad_stale[g * p + j];
@@ -480,7 +493,7 @@ void orc_step(orc_ctx *c, const float *X, const void *y, uint8_t *mask_out, doub
 /* ---------- state access for the tests --------------------------------- */
 
 enum { ORC_F_THETA = 0, ORC_F_H, ORC_F_VHAT, ORC_F_AGG, ORC_F_THETA_STALE, ORC_F_LAST,
-       ORC_F_GRAD, ORC_F_GRAD_STALE, ORC_F_STAT, ORC_F_RING, ORC_F_LOSS_G, ORC_F_KINK };
+       ORC_F_GRAD, ORC_F_GRAD_STALE, ORC_F_STAT, ORC_F_RING, ORC_F_LOSS_G, ORC_F_KINK, ORC_F_KINK_UNIT };
 
 double *orc_field(orc_ctx *c, int32_t id, int64_t *count)
 {
@@ -498,6 +511,7 @@ double *orc_field(orc_ctx *c, int32_t id, int64_t *count)
     case ORC_F_RING: *count = c->cfg.D; return c->ring;
     case ORC_F_LOSS_G: *count = G; return c->loss_g;
     case ORC_F_KINK: *count = G; return c->kink;
+    case ORC_F_KINK_UNIT: *count = G * c->H; return c->kink_unit;
     default: *count = 0; return NULL;
     }
 }

@@ -30,6 +30,9 @@ def _step(widths, theta, theta_stale, X, y):
     orc = O.Oracle(cfg, theta)
     orc.theta_stale[...] = theta_stale
     orc.step(X.astype(np.float32), y.astype(np.int32))
+    if orc.kink_unit.shape[1]:
+        np.testing.assert_array_equal(orc.kink, orc.kink_unit.min(axis=1))
+    _step.units = orc.kink_unit.copy()           # the same per hidden unit, layer 1's units first
     return orc.kink.copy()
 
 
@@ -48,6 +51,8 @@ def test_kink_value_hidden_layer_only_and_empty_units_ignored():
     kink = _step([3, 3, 2], th, th, x, np.array([[0]]))
     expected = 2.0 ** -20 / (2 + 2.0 ** -20)
     assert kink[0] == expected                              # exact: every term is a power-of-two sum
+    # per unit: unit 0 as above, unit 1 at distance 1 (all its terms have one sign), unit 2 never counted
+    np.testing.assert_array_equal(_step.units, [[expected, 1.0, 1.0]])
     # negative side of the kink counts the same (|z|)
     x = np.array([[[1, 1 + 2.0 ** -20, 0.5]]])
     kink = _step([3, 3, 2], th, th, x, np.array([[1]]))
@@ -76,6 +81,7 @@ def test_kink_is_the_minimum_over_samples_and_over_both_iterates_per_group():
     kink = _step([2, 2, 2], th, np.stack([th, th_stale1]), X, np.zeros((2, 3)))
     assert kink[0] == r(12)           # group 0: the closest of its three samples
     assert kink[1] == 0.0             # group 1: its stale iterate is closer still
+    np.testing.assert_array_equal(_step.units, [[r(12), 1.0], [0.0, 1.0]])     # per group and unit
     # and with the current iterate as the close one, the stale far away
     th_far = _theta([([[1, 1], [1, 1]], [0, 0]), ([[1, 0], [0, 1]], [0, 0])])
     kink = _step([2, 2, 2], th, np.stack([th_far, th_far]), X, np.zeros((2, 3)))
@@ -98,6 +104,8 @@ def test_kink_covers_every_hidden_layer():
     x = np.array([[[1 + 2.0 ** -6, 1.0]]])
     kink = _step([2, 2, 2, 2], th, th, x, np.array([[1]]))
     assert kink[0] == 2.0 ** -6 / (4 + 3 * 2.0 ** -6)
+    # units in layer order: layer 1 (both far: one-signed sums), then layer 2 (unit 0 close, unit 1 far)
+    np.testing.assert_array_equal(_step.units, [[1.0, 1.0, 2.0 ** -6 / (4 + 3 * 2.0 ** -6), 1.0]])
 
 
 def test_kink_is_one_without_hidden_layers():

@@ -4,12 +4,16 @@ Teacher forcing: before every step the oracle's state is rounded to fp32 in plac
 the GPU, so both sides start the step from identical values and a flipped selection cannot fork
 the run.  The shared state always comes from the oracle; nothing the GPU computed enters the
 oracle.  Tolerances: vectors are compared twice -- norm-wise, max|a-b| <= tol * max|b|, and
-element by element, |a_j - b_j| <= tol * |b_j| + tol * rms(b) (an element that is itself a
-cancelled sum is held to the typical element's size, not to its own); scalars relatively; masks
+element by element, |a_j - b_j| <= tol * |b_j| + tol * rms(b) with the rms over the element's
+block of the parameter vector (a layer's weight matrix or bias vector: elements of one scale; an
+element that is itself a cancelled sum is held to its block's typical size, not to its own);
+scalars relatively; masks
 must agree unless the oracle's statistic is within `edge` (relative) of the threshold or, where
 said, within the measured error of the statistic itself.
 """
 from __future__ import annotations
+
+import time
 
 import numpy as np
 import torch
@@ -38,20 +42,110 @@ def vec_err(a, b) -> float:
     return float(np.abs(a - b).max() / max(np.abs(b).max(), ATOL / 1e-5))
 
 
-def elem_err(a, b) -> float:
-    """max_j |a_j - b_j| / (|b_j| + rms(b)): the mixed element-wise error (same absolute floor)."""
-    a = np.asarray(a, dtype=np.float64)
-    b = np.asarray(b, dtype=np.float64)
-    rms = max(float(np.sqrt(np.mean(b * b))), ATOL / 1e-5)
-    return float((np.abs(a - b) / (np.abs(b) + rms)).max())
+def param_blocks(w: Workload):
+    """Slices of the parameter vector whose elements share a scale: per layer the weight matrix
+    and the bias vector (one block for the linear models)."""
+    if w.model != "mlp":
+        return [slice(0, w.p)]
+    out, off = [], 0
+    for l in range(1, len(w.widths)):
+        nw = w.widths[l] * w.widths[l - 1]
+        out += [slice(off, off + nw), slice(off + nw, off + nw + w.widths[l])]
+        off += nw + w.widths[l]
+    return out
 
 
-def check_vec(a, b, tol, what) -> float:
+def block_rms(b, blocks):
+    """rms of every block of b, as one value per element."""
+    b = np.asarray(b, dtype=np.float64).reshape(-1)
+    out = np.empty_like(b)
+    for s in blocks:
+        out[s] = np.sqrt(np.mean(b[s] * b[s])) if s.stop > s.start else 0.0
+    return out
+
+
+def flip_rows(w: Workload, a, b, tol, near_units, max_rows=4, max_share=2e-3):
+    """bf16 MLP: which elements the element-by-element comparison has to leave out because a
+    ReLU decision fell differently.  Both sides round the hidden activations to bf16, the GPU from
+    its fp32 pre-activation, the oracle from the fp64 one; now and then the two land on either
+    side of a bf16 rounding boundary, the activation differs by one bf16 ulp (2^-8 relative), and a
+    unit of the NEXT layer whose pre-activation is within that of zero takes the other branch for
+    that sample: one of the mu terms of that unit's row of the layer's weight gradient (and of its
+    bias gradient) appears or disappears.  Such a row is found by the comparison itself (some
+    element beyond `tol`), must belong to a unit the oracle reports close to a kink
+    (`near_units`, bool per hidden unit, layer 1's units first), and there may be few of them per
+    layer: max(max_rows, max_share * units).  When the layer is narrow and the minibatch short the
+    flip also shows in the layers before it (it changes its sample's back-propagated signal by a
+    1/sqrt(n_l) share, an earlier gradient element by a 1/sqrt(n_l mu) share): those layers are
+    then left out too.  Returns (bool mask of left-out elements, rows left out).  Everything stays
+    under the norm-wise check."""
+    a = np.asarray(a, dtype=np.float64).reshape(-1)
+    b = np.asarray(b, dtype=np.float64).reshape(-1)
+    skip = np.zeros(w.p, bool)
+    offs, off = [], 0
+    for l in range(1, len(w.widths)):
+        offs.append(off)
+        off += w.widths[l] * w.widths[l - 1] + w.widths[l]
+    units0 = np.concatenate([[0], np.cumsum(w.widths[1:-1])])
+    n_rows = 0
+    for l in range(len(w.widths) - 2, 0, -1):                 # hidden layers, last one first
+        nin, nout, o0 = w.widths[l - 1], w.widths[l], offs[l - 1]
+        if skip[o0]:
+            continue                                          # already left out with a later layer
+        W = slice(o0, o0 + nout * nin)
+        bb = slice(o0 + nout * nin, o0 + nout * nin + nout)
+        rW = np.abs(a[W] - b[W]) / (np.abs(b[W]) + max(np.sqrt(np.mean(b[W] ** 2)), ATOL / 1e-5))
+        rb = np.abs(a[bb] - b[bb]) / (np.abs(b[bb]) + max(np.sqrt(np.mean(b[bb] ** 2)), ATOL / 1e-5))
+        bad = (rW.reshape(nout, nin).max(axis=1) > tol) | (rb > tol)
+        rows = np.nonzero(bad)[0]
+        if len(rows) == 0:
+            continue
+        assert len(rows) <= max(max_rows, max_share * nout), \
+            f"layer {l}: {len(rows)} of {nout} rows differ element-wise -- more than flipped ReLU decisions explain"
+        not_near = [int(o) for o in rows if not near_units[units0[l - 1] + o]]
+        assert not not_near, f"layer {l}: rows {not_near} differ element-wise but their units are not near a kink"
+        n_rows += len(rows)
+        for o in rows:
+            skip[o0 + o * nin: o0 + (o + 1) * nin] = True
+            skip[o0 + nout * nin + o] = True
+        if 1.0 / np.sqrt(nout * w.mu) > tol / 4:
+            skip[:o0] = True
+    return skip, n_rows
+
+
+def elem_err(a, b, blocks=None, where=None, skip=None, extra=None) -> float:
+    """max_j |a_j - b_j| / (|b_j| + rms(b) [+ extra_j]): the mixed element-wise error, rms taken
+    over the element's block (same absolute floor as vec_err).  where: a list that receives a
+    description of the worst element.  skip: elements left out.  extra: a further per-element
+    scale the error is held against (where the arithmetic gives one)."""
+    a = np.asarray(a, dtype=np.float64).reshape(-1)
+    b = np.asarray(b, dtype=np.float64).reshape(-1)
+    worst = 0.0
+    for s in (blocks if blocks is not None else [slice(0, b.size)]):
+        bs, as_ = b[s], a[s]
+        rms = max(float(np.sqrt(np.mean(bs * bs))), ATOL / 1e-5)
+        den = np.abs(bs) + rms
+        if extra is not None:
+            den = den + extra[s]
+        r = np.abs(as_ - bs) / den
+        if skip is not None:
+            r = np.where(skip[s], 0.0, r)
+        j = int(np.argmax(r))
+        if r[j] > worst:
+            worst = float(r[j])
+            if where is not None:
+                where[:] = [f"element {s.start + j} (block {s.start}:{s.stop}, rms {rms:.3e}, max {np.abs(bs).max():.3e}): "
+                            f"{as_[j]:.9e} vs {bs[j]:.9e}"]
+    return worst
+
+
+def check_vec(a, b, tol, what, blocks=None, skip=None, extra=None) -> float:
     """Assert both vector criteria; returns the norm-wise error."""
     e = vec_err(a, b)
     assert e <= tol, f"{what}: error {e:.3e} (norm-wise)"
-    ee = elem_err(a, b)
-    assert ee <= tol, f"{what}: error {ee:.3e} (element-wise)"
+    where = []
+    ee = elem_err(a, b, blocks, where, skip, extra)
+    assert ee <= tol, f"{what}: error {ee:.3e} (element-wise) at {where}"
     return e
 
 
@@ -90,7 +184,7 @@ def push_state(orc: O.Oracle, gpu: Gcada):
 
 def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, kink_tol=None,
                    kink_grad_tol=5e-2, stat_vs_threshold=False, verbose=False, server_rule_L=None, lazy_store=None,
-                   edge_stat_err=False, options=()):
+                   edge_stat_err=False, options=(), kink_unit_tol=None):
     """Run `steps` iterations; idx: int32 (steps, G, mu) row ids or None for the cyclic window.
     kink_tol (MLP): a group is "near a ReLU kink" in a step when some hidden pre-activation of the
     oracle lies within kink_tol (relative to the sum of the magnitudes of its terms) of zero.
@@ -106,6 +200,14 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
     just been held to `tol`, and a statistic that is off by it may land on the other side.  The
     plain rule (|stat - rhs| < edge * rhs with edge = 1e-6) stays in force otherwise.
     options: (option, value) pairs for gcada_set_option.
+    kink_unit_tol (bf16 MLP): the same closeness measure per hidden unit; the element-by-element
+    comparison leaves out the few rows in which a ReLU decision fell differently (flip_rows: found
+    by the comparison, confirmed by this measure, bounded in number); they stay under the
+    norm-wise check.  The number of such rows is returned.
+    The element-wise check of the aggregate and the moments holds their error against the sizes
+    of what was added: agg_new = agg_old + sum over the uploading groups of (fresh - stored), so
+    its error is at most the sum of those gradients' errors, each held to tol (|g_j| + rms(g));
+    h inherits (1 - beta1) of it and v-hat 2 (1 - beta2) |agg_j| of it (Eq. (8a), (8b)).
     server_rule_L: G smoothness constants -> both sides run the server-side rule of Sec. IV
     (selection from the iterates before the gradients; only selected groups evaluate one); then
     the gradients of the selected groups only are compared, and `stat` is the rule's left side.
@@ -127,9 +229,14 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
     idx_dev = torch.as_tensor(idx, device="cuda") if idx is not None else None
     worst = dict(grad=0.0, grad_elem=0.0, stat=0.0, rhs=0.0, loss=0.0, theta=0.0, h=0.0, vhat=0.0, agg=0.0,
                  ring=0.0, edge_flips=0, selected=0, kink_groups=0, clean_groups=0, state_steps=0,
-                 forced_late=0, by_statistic=0, max_age=0)
+                 forced_late=0, by_statistic=0, max_age=0, flip_rows=0)
     rows_all = [X.shape[0] for X in Xs]
+    blocks = param_blocks(w)
+    t_said = time.time()
     for k in range(steps):
+        if time.time() - t_said > 30:        # a long case says where it is
+            print(f"  ... step {k} of {steps}", flush=True)
+            t_said = time.time()
         round_state_to_f32(orc)
         push_state(orc, gpu)
         tau_before = orc.tau.copy()
@@ -146,6 +253,14 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
         near = (orc.kink < kink_tol) if kink_tol is not None else np.zeros(w.G, bool)
         worst["kink_groups"] += int(near.sum())
         worst["clean_groups"] += int((~near).sum())
+        skips = [None] * w.G
+        if kink_unit_tol is not None and w.model == "mlp" and len(w.widths) > 2:
+            near_units = orc.kink_unit < kink_unit_tol                 # (G, hidden units)
+            for g in range(w.G):
+                if (server_rule_L is not None and not mask_o[g]) or (lazy_store and not out["mask"][g]):
+                    continue                                           # no gradient to compare
+                skips[g], nr = flip_rows(w, out["grad"][g], orc.grad[g], tol, near_units[g])
+                worst["flip_rows"] += nr
         # a1: fresh gradients, per group
         for g in range(w.G):
             if server_rule_L is not None and not mask_o[g]:
@@ -158,9 +273,10 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
                 continue
             worst["grad"] = max(worst["grad"], e)
             assert e <= tol, f"step {k} group {g}: gradient error {e:.3e}"
-            ee = elem_err(out["grad"][g], orc.grad[g])
+            where = []
+            ee = elem_err(out["grad"][g], orc.grad[g], blocks, where, skips[g])
             worst["grad_elem"] = max(worst["grad_elem"], ee)
-            assert ee <= tol, f"step {k} group {g}: gradient error {ee:.3e} (element-wise)"
+            assert ee <= tol, f"step {k} group {g}: gradient error {ee:.3e} (element-wise) at {where}"
         # a2: statistic, threshold, mask
         s_o = orc.stat
         for g in range(w.G):
@@ -200,12 +316,26 @@ def teacher_forced(w: Workload, steps, Xs, ys, idx=None, tol=1e-5, edge=1e-6, ki
             continue   # knife-edge / kink: the states legitimately differ after this step
         worst["state_steps"] += 1
         # a3 / a4
+        sel = np.nonzero(mask_o)[0]
+        skip_any = None
+        if any(skips[g] is not None for g in sel):
+            skip_any = np.zeros(w.p, bool)
+            for g in sel:
+                if skips[g] is not None:
+                    skip_any |= skips[g]
+        added = np.zeros(w.p)
+        for g in sel:
+            added += np.abs(orc.grad[g]) + block_rms(orc.grad[g], blocks)
+        extra = dict(agg=added, h=(1 - w.beta1) * added,
+                     vhat=2 * (1 - w.beta2) * np.abs(orc.agg) * (np.abs(orc.agg) + block_rms(orc.agg, blocks) + added))
         for name in ("agg", "h", "vhat"):
-            worst[name] = max(worst[name], check_vec(st[name], getattr(orc, name), tol, f"step {k}: {name}"))
+            worst[name] = max(worst[name], check_vec(st[name], getattr(orc, name), tol, f"step {k}: {name}", blocks,
+                                                     skip_any, extra[name]))
         worst["theta"] = max(worst["theta"], check_theta(w, st["theta"], orc, bool(mask_o.any()), tol, f"step {k}"))
         np.testing.assert_array_equal(st["tau"], orc.tau)
         for g in range(w.G):
-            check_vec(st["last"][g], orc.last[g], tol, f"step {k}: stored gradient of group {g}")
+            check_vec(st["last"][g], orc.last[g], tol, f"step {k}: stored gradient of group {g}", blocks,
+                      skips[g] if mask_o[g] else None)
         check_vec(st["theta_stale"], orc.theta_stale, tol, f"step {k}: stale iterates")
         e = vec_err(st["dtheta_sq"], orc.ring)
         worst["ring"] = max(worst["ring"], e)
@@ -286,7 +416,7 @@ def sampled_oracle_step(w: Workload, st, Xs, ys, idx_step, groups):
 
 def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e-6, kink_tol=None,
                         seed=7, lazy_store=None, edge_stat_err=False, options=(), reference=None,
-                        whole_state=False):
+                        whole_state=False, kink_unit_tol=None):
     """One iteration of the full-size workload on the GPU from a synthetic state; the oracle
     evaluates only the sampled `groups` and those groups' gradients, statistics and masks are
     compared.  reference: (state, oracle, mask) of an earlier call on the same inputs (the oracle's
@@ -316,10 +446,19 @@ def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e
         B.gcada_set_option(gpu.ctx, opt, val)
     gpu.step(torch.as_tensor(idx_step, device="cuda").contiguous())
     out = gpu.outputs()
+    blocks = param_blocks(w)
     worst = dict(grad=0.0, grad_elem=0.0, stat=0.0, rhs=rel_err(out["rhs"], orc.rhs), kink_groups=0,
                  selected=int(mask_o.sum()), ages=sorted(set(int(t) for t in st["tau"][groups])))
     assert worst["rhs"] <= 1e-9
     near_any = False
+    skips = [None] * len(groups)
+    if kink_unit_tol is not None:
+        near_units = orc.kink_unit < kink_unit_tol
+        worst["flip_rows"] = 0
+        for j, g in enumerate(groups):
+            if not lazy_store or bool(out["mask"][g]):
+                skips[j], nr = flip_rows(w, out["grad"][g], orc.grad[j], tol, near_units[j])
+                worst["flip_rows"] += nr
     for j, g in enumerate(groups):
         near = kink_tol is not None and orc.kink[j] < kink_tol
         materialised = not lazy_store or bool(out["mask"][g])
@@ -332,9 +471,10 @@ def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e
         worst["grad"] = max(worst["grad"], e)
         assert e <= tol, f"group {g}: gradient error {e:.3e}"
         if materialised:
-            ee = elem_err(out["grad"][g], orc.grad[j])
+            where = []
+            ee = elem_err(out["grad"][g], orc.grad[j], blocks, where, skips[j])
             worst["grad_elem"] = max(worst["grad_elem"], ee)
-            assert ee <= tol, f"group {g}: gradient error {ee:.3e} (element-wise)"
+            assert ee <= tol, f"group {g}: gradient error {ee:.3e} (element-wise) at {where}"
         gn2 = float(np.dot(orc.grad[j], orc.grad[j]))
         e = abs(out["stat"][g] - orc.stat[j]) / max(abs(orc.stat[j]), tol * gn2, ATOL / 1e-5)
         worst["stat"] = max(worst["stat"], e)
@@ -358,11 +498,22 @@ def sampled_groups_step(w: Workload, Xs, ys, idx_step, groups, tol=1e-5, edge=1e
         np.testing.assert_array_equal(after["last"][others], st["last"][others].astype(np.float32))
         np.testing.assert_array_equal(after["theta_stale"][others], st["theta_stale"][others].astype(np.float32))
         if not near_any:
+            skip_any = None
+            if kink_unit_tol is not None:
+                skip_any = np.zeros(w.p, bool)
+                for sk in skips:
+                    if sk is not None:
+                        skip_any |= sk
+            added = np.zeros(w.p)
+            for j in range(len(groups)):
+                added += np.abs(orc.grad[j]) + block_rms(orc.grad[j], blocks)
+            extra = dict(agg=added, h=(1 - w.beta1) * added,
+                         vhat=2 * (1 - w.beta2) * np.abs(orc.agg) * (np.abs(orc.agg) + block_rms(orc.agg, blocks) + added))
             for name in ("agg", "h", "vhat"):
-                worst[name] = check_vec(after[name], getattr(orc, name), tol, name)
+                worst[name] = check_vec(after[name], getattr(orc, name), tol, name, blocks, skip_any, extra[name])
             worst["theta"] = check_theta(w, after["theta"], orc, True, tol, "after the step")
             for j, g in enumerate(groups):
-                check_vec(after["last"][g], orc.last[j], tol, f"stored gradient of group {g}")
+                check_vec(after["last"][g], orc.last[j], tol, f"stored gradient of group {g}", blocks, skips[j])
                 np.testing.assert_array_equal(after["theta_stale"][g], st["theta"].astype(np.float32))
             worst["ring"] = vec_err(after["dtheta_sq"], orc.ring)
             assert worst["ring"] <= tol, f"history error {worst['ring']:.3e}"

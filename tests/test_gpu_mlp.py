@@ -80,10 +80,16 @@ def test_mlp_784_full_size_free_run_loss_curve(par):
 # signals are bf16 on the GPU with fp32 accumulation.  The oracle evaluates at the bf16-rounded X
 # and iterates and rounds the hidden activations to bf16 (every layer's product has bf16 inputs),
 # so both sides form each ReLU decision from the same values, up to the rounding of the fp32
-# accumulation -- the same kink excuse as in fp32 applies.  The back-propagated signals' rounding is
-# what the 2e-2 tolerance is for.  Masks: the plain 1e-6 edge, or a statistic that is closer to the
-# threshold than the GPU's statistic is to the oracle's (that error is held to the tolerance).
-BF16 = dict(tol=2e-2, edge=1e-6, edge_stat_err=True, kink_tol=KINK)
+# accumulation.  No kink excuse is made here: a unit that such rounding does flip is one term of a
+# sum over the minibatch, far inside this tolerance (and at the full widths nearly every group
+# has SOME unit within 5e-8 of its kink among its million pre-activations: the per-group excuse
+# of the fp32 tests would skip everything).  The back-propagated signals' rounding is what the 2e-2
+# tolerance is for.  Masks: the plain 1e-6 edge, or a statistic that is closer to the threshold
+# than the GPU's statistic is to the oracle's (that error is held to the tolerance).
+# Element by element, the few rows in which a ReLU decision fell differently are left out
+# (parity.flip_rows: a one-ulp difference of a bf16 activation moves the next layer's
+# pre-activation by up to ~1e-4 of the sum of its terms' magnitudes).
+BF16 = dict(tol=2e-2, edge=1e-6, edge_stat_err=True, kink_tol=None, kink_unit_tol=1e-4)
 
 
 @pytest.mark.parametrize("widths,mu,G,rows,steps", [
@@ -100,7 +106,7 @@ def test_mlp_bf16_shapes(par, widths, mu, G, rows, steps):
     idx = make_indices(w, steps)
     worst = par.teacher_forced(w, steps, Xs, ys, idx, **BF16)
     _say(worst)
-    assert worst["clean_groups"] >= 0.6 * G * steps and worst["state_steps"] >= 0.4 * steps
+    assert worst["clean_groups"] == G * steps and worst["state_steps"] >= steps - 1
 
 
 # ---- configuration 5 at full size (G=64, mu=256, 781 rows per shard, p = 4.2 M): iterations from
@@ -179,7 +185,7 @@ def test_mlp_lazy_gradient_store_parity(par, widths, mu, G, rows, steps, dtype_c
     idx = make_indices(w, steps)
     bf = dtype_cfg == "mlp_3072_bf16"
     worst = par.teacher_forced(w, steps, Xs, ys, idx, tol=tol, edge=1e-6, edge_stat_err=bf,
-                               kink_tol=KINK, lazy_store=1)
+                               kink_tol=None if bf else KINK, kink_unit_tol=1e-4 if bf else None, lazy_store=1)
     _say(worst)
     assert worst["selected"] > 0 and worst["state_steps"] > 0.4 * steps
 

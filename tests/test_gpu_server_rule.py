@@ -86,7 +86,7 @@ def test_server_rule_bf16_mlp(par):
     steps = 10
     idx = make_indices(w, steps)
     # (under this rule the left side is made of iterates, not of bf16 gradients: plain 1e-6 edge)
-    worst = par.teacher_forced(w, steps, Xs, ys, idx, tol=2e-2, edge=1e-6, kink_tol=5e-8,
+    worst = par.teacher_forced(w, steps, Xs, ys, idx, tol=2e-2, edge=1e-6, kink_unit_tol=1e-4,
                                server_rule_L=np.array([1.0, 5.0, 20.0]))
     _say(worst)
 

@@ -118,7 +118,14 @@ int gcada_set_theta(gcada_ctx* ctx, const float* theta0);
  *             loss at theta^k (including (l2/2)||theta^k||^2); may be NULL.
  *   stream:   a hipStream_t (NULL = default stream).
  * Asynchronous; outputs are written in stream order.  Calls no allocator.
- * Errors: GCADA_ESTATE (a shard or theta missing), GCADA_EDEVICE (launch failure).
+ * Errors: GCADA_ESTATE (a shard or theta missing; or a launch of an earlier step failed part-way),
+ * GCADA_EDEVICE (launch failure; or a wait between workgroups inside a kernel of an EARLIER step
+ * gave up -- some kernels let their workgroups hand results to each other and bound that wait, so a
+ * device held by another stream cannot hang them.  The kernels report it to a pinned host word
+ * which this call reads first, without touching the device: it sees the failures of the steps
+ * that have finished on the device by then, at the latest after the caller has synchronised).
+ * After either of the two the state is not valid and every further step fails until
+ * gcada_set_theta or gcada_set_state has replaced it.
  */
 int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* loss_out,
                void* stream);
@@ -172,7 +179,8 @@ typedef struct gcada_state_host {
     int64_t  k;
 } gcada_state_host;
 
-/* Copy the state out (fills the buffers and k).  Synchronises the device. */
+/* Copy the state out (fills the buffers and k).  Synchronises the device.  GCADA_EDEVICE when a
+ * wait inside a kernel of one of the steps so far gave up (see gcada_step). */
 int gcada_get_state(gcada_ctx* ctx, gcada_state_host* out /*[host]*/);
 
 /*
@@ -210,8 +218,8 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * (Eq. (9)), sum the innovations and update (Eq. (8a)-(8c)) in ONE launch whose blocks meet once
  * inside the kernel (at most 64 blocks, one per compute unit; the wait is bounded: if the blocks
  * cannot all run at once -- another stream holding the device -- the step is reported as failed,
- * GCADA_EDEVICE from the next gcada_get_state, instead of hanging); 0 uses the separate
- * reduce and server kernels.  Same arithmetic per element either way.
+ * GCADA_EDEVICE from a later gcada_step, gcada_state or gcada_get_state, instead of hanging);
+ * 0 uses the separate reduce and server kernels.  Same arithmetic per element either way.
  * GCADA_OPT_LAZY_GRADIENT_STORE [1 for an MLP whose G fresh gradients are 64 MiB or more, else 0;
  * ignored for the linear models]: with the gradient-difference rule every group evaluates both
  * gradients in every step, but only an uploading group's fresh gradient is ever read again (the
@@ -228,10 +236,14 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * instead of two n_1 x n_0 weight gradients, and the first layer's gradient is formed only for
  * the groups that upload.  Same statistic up to rounding (the signal difference is rounded to
  * bf16 once more); 0 computes it from the two weight gradients.
+ * GCADA_OPT_EXPIRE_NEXT_WAIT [0]: a diagnostic for tests of the error path.  With 1, the kernels of
+ * the NEXT gcada_step that wait for other workgroups' words look for words nobody publishes and
+ * give up after a few polls: every kernel runs to its end, the step's results are invalid, and the
+ * failure is reported as described under gcada_step.  Cleared by that step.
  * Errors: GCADA_EINVAL (unknown option).
  */
 enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1, GCADA_OPT_FUSED_FINISH = 2, GCADA_OPT_LAZY_GRADIENT_STORE = 3,
-       GCADA_OPT_GRAM_STATISTIC = 4 };
+       GCADA_OPT_GRAM_STATISTIC = 4, GCADA_OPT_EXPIRE_NEXT_WAIT = 5 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*
@@ -259,7 +271,8 @@ int gcada_step_workers(gcada_ctx* ctx, const int32_t* idx_workers, const double*
  * group is selected), and gcada_state's stat holds the left sides.
  * L [host, G doubles, copied]: the smoothness constants L_g, an input of Algorithm 1; may be
  * NULL when they were given before.  May be called between steps.
- * Errors: GCADA_EINVAL (unknown rule, negative or non-finite L_g, GCADA_RULE_SERVER without L).
+ * Errors: GCADA_EINVAL (unknown rule, negative or non-finite L_g, GCADA_RULE_SERVER without L, or
+ * GCADA_RULE_SERVER on a context with D > 64).
  */
 enum { GCADA_RULE_GRADIENT_DIFFERENCE = 0, GCADA_RULE_SERVER = 1 };
 int gcada_set_rule(gcada_ctx* ctx, int32_t rule, const double* L);

@@ -25,6 +25,7 @@ GCADA_OPT_SINGLE_PASS_LOGREG = 1
 GCADA_OPT_FUSED_FINISH = 2
 GCADA_OPT_LAZY_GRADIENT_STORE = 3
 GCADA_OPT_GRAM_STATISTIC = 4
+GCADA_OPT_EXPIRE_NEXT_WAIT = 5
 
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
@@ -203,3 +204,4 @@ def gcada_estimate_smoothness(ctx, iters: int, L_out_ptr, stream):
 
 def gcada_timed_stage(ctx) -> str:
     return (lib.gcada_timed_stage(ctx) or b"").decode()
+

@@ -42,14 +42,37 @@ hipError_t dalloc(T** p, size_t n)
     return e;
 }
 
-// A bounded wait inside a kernel gave up: the results of that step are not valid.
+const char* kWaitFailed =
+    "a wait or a hand-over between workgroups inside a kernel of an earlier step failed; the state is not valid: "
+    "call gcada_set_theta or gcada_set_state";
+
+// A bounded wait inside a kernel gave up: the results of that step are not valid.  (After a
+// device synchronisation: reads the device's own flag.)
 int check_device_flag(gcada_ctx* c)
 {
     Ctl z{};
     hipError_t e = hipMemcpy(&z, c->ctl, sizeof(z), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return fail_hip(c, e, "read control block");
-    if (z.error != 0) return fail(c, GCADA_EDEVICE, "a wait or a hand-over between workgroups inside a kernel failed");
+    if (z.error != 0 || (c->err_mirror && *(volatile unsigned int*)c->err_mirror != 0))
+        return fail(c, GCADA_EDEVICE, kWaitFailed);
     return GCADA_OK;
+}
+
+// The same without touching the device: the kernels' give-up paths also write a pinned host word.
+// It shows the failures of the steps that have FINISHED on the device by now.
+int check_host_mirror(gcada_ctx* c)
+{
+    if (c->err_mirror && *(volatile unsigned int*)c->err_mirror != 0) return fail(c, GCADA_EDEVICE, kWaitFailed);
+    return GCADA_OK;
+}
+
+// Fresh control block (no error, counters 0) that points at the host mirror.
+hipError_t reset_control_block(gcada_ctx* c)
+{
+    Ctl z{};
+    z.host_flag = c->err_mirror;
+    if (c->err_mirror) *(volatile unsigned int*)c->err_mirror = 0;
+    return hipMemcpy(c->ctl, &z, sizeof(z), hipMemcpyHostToDevice);
 }
 
 int64_t param_count(const gcada_dims& d)
@@ -74,6 +97,8 @@ void free_all(gcada_ctx* c)
                     c->part_sq, c->store_now, c->redo, c->hot};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
+    if (c->err_mirror) (void)hipHostFree(c->err_mirror);
+    c->err_mirror = nullptr;
 }
 
 }  // namespace
@@ -158,6 +183,9 @@ try {
     // an MLP whose fresh gradients (G rows of p floats per step) are a large write stores them lazily
     x->lazy_store = dims->model == GCADA_MLP && Gp * sizeof(float) >= ((size_t)64 << 20);
     if ((e = dalloc(&x->ctl, 1)) != hipSuccess) return bail(e, "alloc control block");
+    if ((e = hipHostMalloc((void**)&x->err_mirror, sizeof(unsigned int), hipHostMallocDefault)) != hipSuccess)
+        return bail(e, "alloc error mirror");
+    if ((e = reset_control_block(x)) != hipSuccess) return bail(e, "control block");
 
     e = dims->model != GCADA_MLP ? gcada::lr_plan(x) : gcada::mlp_plan(x);
     if (e != hipSuccess) return bail(e, "model plan");
@@ -235,14 +263,15 @@ static int reset_run(gcada_ctx* ctx, const float* theta0_any)
     HIP_TRY(ctx, hipMemset(ctx->mask, 0, (size_t)hy.G));
     std::vector<int32_t> tau(hy.G, hy.D);
     HIP_TRY(ctx, hipMemcpy(ctx->tau, tau.data(), (size_t)hy.G * 4, hipMemcpyHostToDevice));
-    Ctl z{};
-    HIP_TRY(ctx, hipMemcpy(ctx->ctl, &z, sizeof(z), hipMemcpyHostToDevice));
+    HIP_TRY(ctx, reset_control_block(ctx));
     ctx->k = 0;
     return GCADA_OK;
 }
 
 static int after_state_change(gcada_ctx* ctx)
 {
+    ctx->poisoned = false;
+    ctx->expire_next_wait = false;
     set_iteration(ctx);
     gcada::lr_tile_forget(ctx);
     ctx->flags_valid = false;
@@ -268,6 +297,8 @@ try {
     return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_set_theta");
 }
 
+static int step_launches(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* loss_out, hipStream_t s);
+
 int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* loss_out,
                void* stream)
 {
@@ -275,7 +306,23 @@ int gcada_step(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* los
     if (!ctx->theta_set) return fail(ctx, GCADA_ESTATE, "step: gcada_set_theta has not been called");
     for (int g = 0; g < ctx->hy.G; ++g)
         if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "step: a group has no shard");
-    hipStream_t s = (hipStream_t)stream;
+    if (ctx->poisoned)
+        return fail(ctx, GCADA_ESTATE, "step: a launch of an earlier step failed part-way; the state is not valid: "
+                                       "call gcada_set_theta or gcada_set_state");
+    // a wait that gave up inside a kernel of an earlier step (one that has finished by now)
+    if (int rc = check_host_mirror(ctx)) return rc;
+    const int64_t k0 = ctx->k;
+    const int rc = step_launches(ctx, idx, mask_out, loss_out, (hipStream_t)stream);
+    ctx->expire_next_wait = false;
+    // some kernels of the step may be in the stream already: the device state is then neither that
+    // of step k nor of step k+1
+    if (rc != GCADA_OK && rc != GCADA_ESTATE) { ctx->poisoned = true; ctx->k = k0; }
+    return rc;
+}
+
+// The launches of one iteration, in order.
+static int step_launches(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, float* loss_out, hipStream_t s)
+{
     set_iteration(ctx);
     hipError_t e;
     const bool server_rule = ctx->rule == GCADA_RULE_SERVER;
@@ -347,6 +394,7 @@ int gcada_state(gcada_ctx* ctx, gcada_state_view* out)
 {
     if (!ctx) return GCADA_EINVAL;
     if (!out) return fail(ctx, GCADA_EINVAL, "state: out must not be NULL");
+    if (int rc = check_host_mirror(ctx)) return rc;
     if (hipError_t e = gcada::lr_tile_close(ctx, nullptr, true); e != hipSuccess)
         return fail_hip(ctx, e, "history kernel");
     gcada_state_view v{};
@@ -438,8 +486,7 @@ try {
                              hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->tau, in->tau, (size_t)hy.G * 4, hipMemcpyHostToDevice));
     HIP_TRY(ctx, hipMemcpy(ctx->nring, in->dtheta_sq, (size_t)hy.D * 8, hipMemcpyHostToDevice));
-    Ctl z{};
-    HIP_TRY(ctx, hipMemcpy(ctx->ctl, &z, sizeof(z), hipMemcpyHostToDevice));
+    HIP_TRY(ctx, reset_control_block(ctx));
     ctx->k = in->k;
     int rc = after_state_change(ctx);
     if (rc != GCADA_OK) return rc;
@@ -469,6 +516,10 @@ int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
         ctx->flags_valid = false;
         return GCADA_OK;
     }
+    if (option == GCADA_OPT_EXPIRE_NEXT_WAIT) {
+        ctx->expire_next_wait = value != 0;
+        return GCADA_OK;
+    }
     return fail(ctx, GCADA_EINVAL, "set_option: unknown option");
 }
 
@@ -487,6 +538,8 @@ int gcada_set_rule(gcada_ctx* ctx, int32_t rule, const double* L)
     }
     if (rule == GCADA_RULE_SERVER && !ctx->rule_L_set)
         return fail(ctx, GCADA_EINVAL, "set_rule: the server-side rule needs the constants L_g");
+    if (rule == GCADA_RULE_SERVER && ctx->hy.D > 64)
+        return fail(ctx, GCADA_EINVAL, "set_rule: the server-side rule supports D <= 64");
     ctx->rule = rule;
     return GCADA_OK;
 }
@@ -541,7 +594,10 @@ try {
     set_iteration(ctx);
     hipEvent_t e0, e1;
     HIP_TRY(ctx, hipEventCreate(&e0));
-    HIP_TRY(ctx, hipEventCreate(&e1));
+    if (hipError_t ee = hipEventCreate(&e1); ee != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail_hip(ctx, ee, "hipEventCreate");
+    }
     ctx->dominant_only = true;
     hipError_t e = hipSuccess;
     if (ctx->dims.model == GCADA_MLP && ctx->lazy_store && ctx->rule != GCADA_RULE_SERVER)

@@ -28,7 +28,26 @@ struct Ctl {
     unsigned int cnt_b;
     unsigned int cnt_c;
     unsigned int error;     // sticky device-side error flag (0 = none)
+    unsigned int* host_flag;   // pinned host word that mirrors `error` (the host reads it without a
+                               // device call); null: no mirror
 };
+
+// A bounded wait between workgroups gave up (or a hand-over was found incomplete): the results
+// of this step are not valid.  Sticky on the device, and mirrored to the host.
+__device__ __forceinline__ void raise_device_error(Ctl* ctl, unsigned bits)
+{
+    __hip_atomic_fetch_or(&ctl->error, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned int* hf = ctl->host_flag;
+    if (hf) __hip_atomic_store(hf, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// How long a kernel polls for another workgroup's words before it gives up, and -- for the test
+// of that path -- a tag offset that makes the wait look for words nobody publishes.
+struct WaitPolicy {
+    unsigned limit;         // polls
+    unsigned tag_skew;      // added to the tag a wait looks for (0 in every real launch)
+};
+constexpr unsigned kDefaultPollLimit = 1u << 16;
 
 // Scalars every kernel needs, passed by value.
 struct Hyper {
@@ -112,6 +131,11 @@ struct LrMicroPlan;   // small linear models: the whole iteration in one launch 
 }  // namespace gcada
 
 struct gcada_ctx {
+    // what the next launch's waits do (see WaitPolicy); reset after every step
+    gcada::WaitPolicy wait_policy() const
+    {
+        return expire_next_wait ? gcada::WaitPolicy{64u, 0x40000000u} : gcada::WaitPolicy{gcada::kDefaultPollLimit, 0u};
+    }
     gcada_dims dims{};
     gcada::Hyper hy{};
     int32_t M_G = 1;
@@ -172,6 +196,10 @@ struct gcada_ctx {
     bool allow_single_pass = true;
     bool allow_fused_finish = true;
     bool lr_fused_finish = false;  // this step: lr_tile_finish replaces lr_tile_reduce + server_step
+
+    unsigned int* err_mirror = nullptr;   // pinned host word the kernels' give-up paths write to
+    bool poisoned = false;         // a launch failed part-way through a step: set_theta / set_state first
+    bool expire_next_wait = false; // diagnostic: the next step's waits look for words nobody publishes
 
     bool dominant_only = false;    // benchmark diagnostic: launch only the dominant gradient kernel(s)
     std::string stage_name;

@@ -23,7 +23,6 @@ constexpr int kMicroMaxD = 256;
 constexpr int kMicroMaxRows = 128;                     // minibatch rows per group
 constexpr int kMicroMaxWords = 1024;                   // G * (d + 4): what workgroup 0 collects
 constexpr int kMicroRowsInFlight = 8;                  // rows a wave has in flight
-constexpr unsigned kMicroPollLimit = 1u << 16;
 
 struct MicroArgs {
     Hyper hy;
@@ -31,6 +30,7 @@ struct MicroArgs {
     const int32_t* idx;
     unsigned long long* xw;      // [G][d + 4] tagged words: statistic (2), loss sum (2), innovation (d)
     unsigned tag;                // of this launch (never 0, never that of a recent launch)
+    WaitPolicy wait;             // bound of the polls; tag_skew != 0 only in the test of the give-up path
     int dry;                     // 1: timing run, workgroup 0 collects but changes no state
     double* stat;
     uint8_t* mask;
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(kMicroThreads) void lr_micro_kernel(MicroArgs a)
             if (!got[e]) {
                 const unsigned long long w = __hip_atomic_load(a.xw + tid + e * kMicroThreads, __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_SYSTEM);
-                if ((unsigned)(w >> 32) == a.tag) {
+                if ((unsigned)(w >> 32) == a.tag + a.wait.tag_skew) {
                     got[e] = true;
                     val[e] = (unsigned)w;
                 }
@@ -227,8 +227,8 @@ __global__ __launch_bounds__(kMicroThreads) void lr_micro_kernel(MicroArgs a)
             all = all && got[e];
         }
         if (__syncthreads_and(all)) break;
-        if (++spins > kMicroPollLimit) {               // never in a healthy launch: report, do not hang
-            if (tid == 0) __hip_atomic_fetch_or(&ctl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (++spins > a.wait.limit) {                  // never in a healthy launch: report, do not hang
+            if (tid == 0) raise_device_error(ctl, 1u);
             break;
         }
     }
@@ -363,6 +363,7 @@ hipError_t lr_micro_step(gcada_ctx* c, const int32_t* idx, uint8_t* mask_out, fl
     a.hy = c->hy; a.shards = c->d_shards; a.idx = idx; a.xw = pl->xw;
     // tags 1 .. 2^32-1 in turn: a slot only ever holds the tag of an earlier launch
     a.tag = pl->launches++ % 0xffffffffu + 1u;
+    a.wait = c->wait_policy();
     a.dry = dry ? 1 : 0;
     a.stat = c->stat; a.mask = c->mask; a.mask_out = mask_out; a.loss_out = loss_out;
     a.gbuf = c->gbuf; a.which = c->which; a.agg = c->agg; a.h = c->h; a.vhat = c->vhat;

@@ -44,7 +44,6 @@ constexpr int kPartial = 2 * kR;         // values a member publishes per tile
 constexpr int kSlotBytes = kPartial * 8; // per member and slot
 constexpr int kParkBytes = 2 * kR * kV * kDataThreads * 16;   // two parked tiles: 131072
 constexpr int kLabelRing = 8;            // labels of tiles t-2 .. t+2 are live
-constexpr unsigned kPollLimit = 1u << 16;
 
 // A pair {value, tag} of the exchange buffer travels as one 64-bit word.  Relaxed atomic
 // accesses at system scope: the hardware goes past the non-coherent L2s (sc0 sc1), and the
@@ -75,6 +74,7 @@ struct TeamArgs {
     double* part_loss;       // [G]
     int TS, NT;
     unsigned tag_base;       // tags of this launch are tag_base + tile sequence number
+    WaitPolicy wait;         // bound of the polls; tag_skew != 0 only in the test of the give-up path
 };
 
 // workgroup id -> (team, member).  Consecutive workgroup ids go to different XCDs (id mod 8); a
@@ -345,7 +345,7 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
     team_advance(a, S, n + 3, a.NT);
 
     if (have_add) {
-        const unsigned want = a.tag_base + (unsigned)n - 2u;
+        const unsigned want = a.tag_base + a.wait.tag_skew + (unsigned)n - 2u;
         bool ok = !poller || (pair_tag(pz) == want && pair_tag(pdz) == want);
         unsigned spins = 0;
         while (!gave_up && !__all(ok)) {         // rare: a member is more than a tile behind
@@ -354,9 +354,8 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
                 pdz = pair_load(mine + 1);
                 ok = pair_tag(pz) == want && pair_tag(pdz) == want;
             }
-            if (++spins > kPollLimit) {
-                if (lane == 0)
-                    __hip_atomic_fetch_or(&a.ctl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (++spins > a.wait.limit) {
+                if (lane == 0) raise_device_error(a.ctl, 1u);
                 gave_up = true;
             }
         }
@@ -563,6 +562,7 @@ hipError_t lr_team_gradients(gcada_ctx* c, const int32_t* idx, hipStream_t s)
     // launch counter advances the base (wrap-around after 4096 launches lands on tags long gone)
     const unsigned tiles = (unsigned)((c->hy.G + pl->NT - 1) / pl->NT) * (unsigned)((c->hy.mu + kR - 1) / kR);
     a.tag_base = (unsigned)((c->team_launches++ % 4095u) + 1u) << 20;
+    a.wait = c->wait_policy();
     if (tiles >= (1u << 20)) return hipErrorInvalidValue;
     lr_team_kernel<<<pl->NT * pl->TS, kThreads, kParkBytes, s>>>(a);
     c->n_stat_used = pl->TS;

@@ -251,7 +251,6 @@ __global__ __launch_bounds__(kRedBlock) void lr_tile_reduce(
 // entry, as in the stand-alone server kernel.
 constexpr int kFinGroups = 16;            // group lanes of a block
 constexpr int kFinMaxG = 64;              // innovations kept in LDS: kFinMaxG x 4*CL floats
-constexpr unsigned kFinPollLimit = 1u << 16;
 
 struct FinishArgs {
     Hyper hy;
@@ -263,6 +262,7 @@ struct FinishArgs {
     unsigned long long* xstat;   // [G][gridDim.x] tagged doubles: partial squared norms
     unsigned long long* xsq;     // [gridDim.x][2] tagged doubles: ||step||^2, ||theta^{k+1}||^2
     unsigned tag;                // of this launch (never 0, never that of a recent launch)
+    WaitPolicy wait;             // bound of the polls; tag_skew != 0 only in the test of the give-up path
     // the two sums of the PREVIOUS launch are still per block (nobody waits for them at the end
     // of a launch): this launch adds them up, uses them and stores them
     const unsigned long long* xsq_prev;
@@ -484,8 +484,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
                             prev_ok = tagged_check(plo[0], phi[0], a.tag_prev, psq);
                             prev_ok = tagged_check(plo[1], phi[1], a.tag_prev, ptsq) && prev_ok;
                         }
-                        if (!__all(prev_ok) && lane == 0)
-                            __hip_atomic_fetch_or(&ctl->error, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (!__all(prev_ok) && lane == 0) raise_device_error(ctl, 2u);
                         psq = wave_total(psq);
                         ptsq = wave_total(ptsq);
                         if (blk == 0 && lane == 0) {
@@ -502,11 +501,10 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                if (!got[e]) got[e] = tagged_check(lo[e], hi[e], a.tag, v[e]);
+                if (!got[e]) got[e] = tagged_check(lo[e], hi[e], a.tag + a.wait.tag_skew, v[e]);
             if (__all(got[0] && got[1] && got[2] && got[3])) break;
-            if (++spins > kFinPollLimit) {           // never in a healthy launch: report, do not hang
-                if (lane == 0)
-                    __hip_atomic_fetch_or(&ctl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (++spins > a.wait.limit) {            // never in a healthy launch: report, do not hang
+                if (lane == 0) raise_device_error(ctl, 1u);
                 break;
             }
         }
@@ -626,9 +624,8 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
         if (!gx) gx = tagged_load(a.xsq + 4 * (int64_t)lane, a.tag, x);
         if (!gy) gy = tagged_load(a.xsq + 4 * (int64_t)lane + 2, a.tag, y);
         if (__all(gx && gy)) break;
-        if (++spins > kFinPollLimit) {
-            if (lane == 0)
-                __hip_atomic_fetch_or(&ctl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (++spins > a.wait.limit) {
+            if (lane == 0) raise_device_error(ctl, 1u);
             break;
         }
     }
@@ -659,8 +656,7 @@ __global__ __launch_bounds__(kWave) void lr_tile_close_kernel(const unsigned lon
         ok = tagged_load(xsq + 4 * (int64_t)lane, tag, x);
         ok = tagged_load(xsq + 4 * (int64_t)lane + 2, tag, y) && ok;
     }
-    if (!__all(ok) && lane == 0)
-        __hip_atomic_fetch_or(&ctl->error, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!__all(ok) && lane == 0) raise_device_error(ctl, 2u);
     x = wave_total(x);
     y = wave_total(y);
     if (lane == 0) {
@@ -793,6 +789,7 @@ hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool
     a.xsq_prev = sums + (size_t)((n & 1u) ^ 1u) * 4 * pl->fin_S;   // is read while this one is written
     // tags 1 .. 2^32-1 in turn: a slot only ever holds the tag of an earlier launch
     a.tag = n % 0xffffffffu + 1u;
+    a.wait = c->wait_policy();
     a.pre = preselected ? 1 : 0;
     if (preselected && pl->fin_pending) return hipErrorInvalidValue;   // the caller completes the history first
     a.fold_prev = pl->fin_pending ? 1 : 0;

@@ -249,7 +249,8 @@ hipError_t rule_loss(gcada_ctx* c, float* loss_out, hipStream_t s)
 
 hipError_t rule_plan(gcada_ctx* c)
 {
-    if (c->hy.D > 64) return hipErrorInvalidValue;
+    // (the server-side rule itself is limited to D <= 64 -- one bit per age, checked by
+    // gcada_set_rule; the buffers below are needed by every context)
     const int64_t per_block = (int64_t)kBlock * 4;
     // (every block ends with an atomic on one counter: a few hundred blocks per distance, not thousands)
     c->rule_nb = (int)std::min<int64_t>((c->hy.pstride + per_block - 1) / per_block, 256);

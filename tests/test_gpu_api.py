@@ -83,3 +83,79 @@ def test_side_stream_run_matches_default_stream(cfg, kw):
         gpu.close()
     for name in ("theta", "h", "vhat", "agg", "last", "tau", "dtheta_sq"):
         np.testing.assert_array_equal(states[0][name], states[1][name], err_msg=name)
+
+
+@pytest.mark.parametrize("cfg,kw,kernel", [
+    ("lr_small", dict(widths=(64,), mu=32, G=3, rows=512, D=5), "lr_micro"),        # one-launch kernel: workgroup 0 collects
+    ("lr_4k", dict(widths=(2048,), mu=64, G=4, rows=256, D=5), "lr_tile"),          # fused finish: its blocks meet once
+    ("lr_64k", dict(widths=(8192,), mu=48, G=5, rows=100, D=5), "lr_team"),         # team kernel: members exchange partial dots
+])
+def test_a_wait_that_gives_up_is_reported_by_the_next_step(cfg, kw, kernel):
+    # the kernels whose workgroups wait for each other bound that wait.  Here the host makes the
+    # next step's waits look for words nobody publishes, with a limit of a few polls: every kernel
+    # still runs to its end, the step is reported as failed by the NEXT gcada_step (and by
+    # gcada_state / gcada_get_state), the context stays refused until its state is replaced, and
+    # works again afterwards -- as does a fresh context
+    from paper_2201_04301_amd import binding as B
+    w = scaled(CONFIGS[cfg], name="giveup", **kw)
+    Xs, ys = make_shards(w, "cuda")
+    idx = torch.as_tensor(make_indices(w, 6), device="cuda")
+    mask = torch.zeros(w.G, dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+
+    def raw_step(gpu, k):
+        return B.lib.gcada_step(gpu.ctx, idx[k].contiguous().data_ptr(), mask.data_ptr(), loss.data_ptr(), None)
+
+    gpu = _mk(w)
+    assert kernel in B.gcada_timed_stage(gpu.ctx)
+    gpu.set_shards(Xs, ys)
+    gpu.set_theta(make_theta0(w))
+    assert raw_step(gpu, 0) == B.GCADA_OK and raw_step(gpu, 1) == B.GCADA_OK
+    torch.cuda.synchronize()
+    good = gpu.get_state()
+    B.gcada_set_option(gpu.ctx, B.GCADA_OPT_EXPIRE_NEXT_WAIT, 1)
+    assert raw_step(gpu, 2) == B.GCADA_OK            # launched; its waits give up on the device
+    torch.cuda.synchronize()                          # the step has finished (normally: nothing hangs)
+    rc = raw_step(gpu, 3)
+    assert rc == B.GCADA_EDEVICE and "wait" in B.gcada_last_error(gpu.ctx)
+    assert raw_step(gpu, 3) == B.GCADA_EDEVICE       # and stays refused
+    v = B.gcada_state_view()
+    assert B.lib.gcada_state(gpu.ctx, C.byref(v)) == B.GCADA_EDEVICE
+    with pytest.raises(B.GcadaError) as ei:
+        gpu.get_state()
+    assert ei.value.code == B.GCADA_EDEVICE
+    # replacing the state clears it; the run continues from the good state exactly as a fresh
+    # context does from the same state
+    gpu.set_state(**good)
+    assert raw_step(gpu, 2) == B.GCADA_OK
+    torch.cuda.synchronize()
+    a = gpu.get_state()
+    gpu.close()
+    fresh = _mk(w)
+    fresh.set_shards(Xs, ys)
+    fresh.set_theta(make_theta0(w))
+    fresh.set_state(**good)
+    assert raw_step(fresh, 2) == B.GCADA_OK
+    torch.cuda.synchronize()
+    b = fresh.get_state()
+    fresh.close()
+    for name in ("theta", "h", "vhat", "agg", "last", "tau", "dtheta_sq"):
+        np.testing.assert_array_equal(a[name], b[name], err_msg=name)
+
+
+def test_history_depth_above_64_runs_with_the_default_rule_only():
+    # the server-side rule keeps one bit per age (D <= 64); every other path takes any D
+    from paper_2201_04301_amd import binding as B
+    w = scaled(CONFIGS["lr_small"], name="deep_history", widths=(32,), mu=16, G=3, rows=64, D=65)
+    Xs, ys = make_shards(w, "cuda")
+    gpu = _mk(w)
+    gpu.set_shards(Xs, ys)
+    gpu.set_theta(make_theta0(w))
+    L = (C.c_double * w.G)(*([1.0] * w.G))
+    assert B.lib.gcada_set_rule(gpu.ctx, B.GCADA_RULE_SERVER, L) == B.GCADA_EINVAL
+    assert "D <= 64" in B.gcada_last_error(gpu.ctx)
+    for k in range(3):
+        gpu.step(None)
+    out = gpu.outputs()
+    assert np.isfinite(out["loss"]) and gpu.get_state()["k"] == 3
+    gpu.close()

@@ -288,6 +288,23 @@ int gcada_set_rule(gcada_ctx* ctx, int32_t rule, const double* L);
 int gcada_estimate_smoothness(gcada_ctx* ctx, int32_t iters, double* L_out, void* stream);
 
 /*
+ * gcada_estimate_smoothness for callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and arithmetic, but
+ *   - the scratch of the power iteration (two d-vectors, one value per shard row, up to 256 x d
+ *     partial sums) lives in a static device array of the library, 2 Mi doubles = 16 MiB, which
+ *     every GPU the library runs on holds until the process ends; a shard that needs more is
+ *     refused with GCADA_EINVAL (lr-type shapes up to about d = 4096 with 65,536 rows fit);
+ *   - L_out is [device] (or pinned host), G doubles, written in stream order; nothing is copied to
+ *     or from pageable host memory, and the call does not synchronise;
+ *   - it calls no hipMalloc / hipFree nor any allocating library routine.
+ * All calls on one GPU share that GPU's array (whatever the context): two calls that overlap in
+ * time on one GPU race, so order them on one stream or with events.  The array keeps the last
+ * call's contents; nothing in it has to start at zero (every word read was written by this call).
+ * Errors: as gcada_estimate_smoothness, plus GCADA_EINVAL when a shard exceeds the array.
+ */
+int gcada_estimate_smoothness_static(gcada_ctx* ctx, int32_t iters, double* L_out /*[device]*/, void* stream);
+
+/*
  * Diagnostics for benchmarks: run only the dominant kernel(s) of step a1 -- the kernels that
  * read the minibatch; gcada_timed_stage names them -- `reps` times back to back on `stream`
  * between two HIP events; repetition r uses the minibatch idx + r*idx_stride (G*mu ids each, as in

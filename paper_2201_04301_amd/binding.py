@@ -30,7 +30,8 @@ GCADA_OPT_EXPIRE_NEXT_WAIT = 5
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
            "gcada_last_error", "gcada_version", "gcada_time_gradient_stage", "gcada_set_option",
-           "gcada_timed_stage", "gcada_set_rule", "gcada_estimate_smoothness", "gcada_step_workers"]
+           "gcada_timed_stage", "gcada_set_rule", "gcada_estimate_smoothness", "gcada_step_workers",
+           "gcada_estimate_smoothness_static"]
 
 GCADA_RULE_GRADIENT_DIFFERENCE, GCADA_RULE_SERVER = 0, 1
 
@@ -59,7 +60,7 @@ class gcada_state_host(C.Structure):
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            f"{LIB_PATH} is not built; run `python -m paper_2201_04301_amd.build` "
+            f"{LIB_PATH} is not built; run `python paper_2201_04301_amd/build.py` "
             "(there is no fallback path)")
     L = C.CDLL(LIB_PATH)
     L.gcada_create.restype = C.c_int
@@ -92,6 +93,8 @@ def _load():
     L.gcada_set_rule.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
     L.gcada_estimate_smoothness.restype = C.c_int
     L.gcada_estimate_smoothness.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+    L.gcada_estimate_smoothness_static.restype = C.c_int
+    L.gcada_estimate_smoothness_static.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     L.gcada_set_option.restype = C.c_int
     L.gcada_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.gcada_timed_stage.restype = C.c_char_p
@@ -204,4 +207,8 @@ def gcada_estimate_smoothness(ctx, iters: int, L_out_ptr, stream):
 
 def gcada_timed_stage(ctx) -> str:
     return (lib.gcada_timed_stage(ctx) or b"").decode()
+
+
+def gcada_estimate_smoothness_static(ctx, iters: int, L_out_dev_ptr, stream):
+    _check(lib.gcada_estimate_smoothness_static(ctx, iters, L_out_dev_ptr, stream), ctx)
 

@@ -566,6 +566,31 @@ try {
     return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_estimate_smoothness");
 }
 
+int gcada_estimate_smoothness_static(gcada_ctx* ctx, int32_t iters, double* L_out, void* stream)
+{
+    if (!ctx) return GCADA_EINVAL;
+    if (!L_out || iters < 1)
+        return fail(ctx, GCADA_EINVAL, "estimate_smoothness_static: L_out must not be NULL, iters >= 1");
+    if (ctx->dims.model == GCADA_MLP)
+        return fail(ctx, GCADA_EINVAL, "estimate_smoothness_static: linear models only");
+    for (int g = 0; g < ctx->hy.G; ++g)
+        if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "estimate_smoothness_static: a group has no shard");
+    if (!ctx->static_scratch)
+        return fail(ctx, GCADA_EDEVICE, "estimate_smoothness_static: the static scratch array was not resolved on this device");
+    for (int g = 0; g < ctx->hy.G; ++g)
+        if (gcada::rule_power_iteration_scratch_doubles(ctx, g) > gcada::rule_static_scratch_doubles()) {
+            char msg[200];
+            std::snprintf(msg, sizeof(msg),
+                          "estimate_smoothness_static: shard %d needs %zu doubles of scratch, the static array holds %zu "
+                          "(use gcada_estimate_smoothness)", g, gcada::rule_power_iteration_scratch_doubles(ctx, g),
+                          gcada::rule_static_scratch_doubles());
+            return fail(ctx, GCADA_EINVAL, msg);
+        }
+    hipError_t e = gcada::rule_smoothness_static(ctx, iters, L_out, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "estimate_smoothness_static: power iteration");
+    return GCADA_OK;
+}
+
 const char* gcada_timed_stage(gcada_ctx* ctx)
 {
     if (!ctx) return "";

@@ -200,6 +200,7 @@ struct gcada_ctx {
     unsigned int* err_mirror = nullptr;   // pinned host word the kernels' give-up paths write to
     bool poisoned = false;         // a launch failed part-way through a step: set_theta / set_state first
     bool expire_next_wait = false; // diagnostic: the next step's waits look for words nobody publishes
+    double* static_scratch = nullptr;     // this device's copy of the library's static scratch array
 
     bool dominant_only = false;    // benchmark diagnostic: launch only the dominant gradient kernel(s)
     std::string stage_name;
@@ -264,6 +265,11 @@ void rule_free(gcada_ctx* c);
 hipError_t rule_select(gcada_ctx* c, uint8_t* mask_out, hipStream_t s);
 hipError_t rule_loss(gcada_ctx* c, float* loss_out, hipStream_t s);
 hipError_t rule_power_iteration(gcada_ctx* c, int g, int iters, double* lambda_out, hipStream_t s);
+// the same without any allocation: scratch in the library's static device array, result on the device
+hipError_t rule_static_scratch(double** ptr);                  // this device's copy of the array
+size_t rule_static_scratch_doubles();
+size_t rule_power_iteration_scratch_doubles(const gcada_ctx* c, int g);
+hipError_t rule_smoothness_static(gcada_ctx* c, int iters, double* L_out_dev, hipStream_t s);
 // per-worker minibatches: idx_eff <- ids of each group's fastest worker
 hipError_t pick_fastest_workers(gcada_ctx* c, const int32_t* idx_workers, const double* delays,
                                 int32_t* worker_out, hipStream_t s);

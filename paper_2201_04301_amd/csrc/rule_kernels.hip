@@ -251,6 +251,8 @@ hipError_t rule_plan(gcada_ctx* c)
 {
     // (the server-side rule itself is limited to D <= 64 -- one bit per age, checked by
     // gcada_set_rule; the buffers below are needed by every context)
+    hipError_t es = rule_static_scratch(&c->static_scratch);
+    if (es != hipSuccess) return es;
     const int64_t per_block = (int64_t)kBlock * 4;
     // (every block ends with an atomic on one counter: a few hundred blocks per distance, not thousands)
     c->rule_nb = (int)std::min<int64_t>((c->hy.pstride + per_block - 1) / per_block, 256);
@@ -271,48 +273,150 @@ void rule_free(gcada_ctx* c)
     c->rule_L = nullptr;
 }
 
+// ---- scratch of one power iteration --------------------------------------------------------
+// v, w: d doubles; t: rows doubles; wp: chunks x d; psq: one per 256 columns; norm: 1.
+struct PiLayout {
+    int d, chunks, nbd;
+    int64_t rows, rpc;
+    size_t off_v, off_t, off_w, off_wp, off_psq, off_norm, total;    // in doubles
+};
+
+static PiLayout pi_layout(const gcada_ctx* c, int g)
+{
+    PiLayout L{};
+    const ShardDesc& sh = c->shards[g];
+    L.d = (int)c->hy.p;
+    L.rows = sh.rows;
+    L.chunks = (int)std::min<int64_t>(256, (L.rows + 63) / 64);
+    L.rpc = (L.rows + L.chunks - 1) / L.chunks;
+    L.nbd = (L.d + kBlock - 1) / kBlock;
+    auto up = [](size_t n) { return (n + 31) / 32 * 32; };          // 256-byte pieces
+    size_t o = 0;
+    L.off_v = o; o += up((size_t)L.d);
+    L.off_t = o; o += up((size_t)L.rows);
+    L.off_w = o; o += up((size_t)L.d);
+    L.off_wp = o; o += up((size_t)L.chunks * L.d);
+    L.off_psq = o; o += up((size_t)L.nbd);
+    L.off_norm = o; o += 32;
+    L.total = o;
+    return L;
+}
+
+// The `iters` rounds of the power iteration on shard g, all in `base` (L.total doubles), start
+// vector already in place; the last round leaves ||X^T X v|| in base[off_norm].
+static hipError_t pi_rounds(const gcada_ctx* c, int g, int iters, const PiLayout& L, double* base, hipStream_t s)
+{
+    const ShardDesc& sh = c->shards[g];
+    const float* X = (const float*)sh.X;
+    double *v = base + L.off_v, *t = base + L.off_t, *w = base + L.off_w, *wp = base + L.off_wp;
+    double *psq = base + L.off_psq, *norm = base + L.off_norm;
+    for (int it = 0; it < iters; ++it) {
+        pi_forward_kernel<<<(unsigned)((L.rows + 3) / 4), kBlock, 0, s>>>(X, L.rows, sh.ld, L.d, v, t);
+        pi_backward_kernel<<<dim3(L.nbd, L.chunks), kBlock, 0, s>>>(X, L.rows, sh.ld, L.d, t, L.rpc, wp);
+        pi_reduce_kernel<<<L.nbd, kBlock, 0, s>>>(wp, L.chunks, L.d, w, psq);
+        pi_normalize_kernel<<<1, kBlock, 0, s>>>(w, psq, L.nbd, L.d, v, norm);
+    }
+    return hipGetLastError();
+}
+
+// Start vector of the power iteration: a fixed pattern with a component along every coordinate,
+// of unit length.
+static double pi_start_value(int j) { return 1.0 + 0.5 * ((j * 2654435761u >> 16) & 0xff) / 255.0; }
+
 // Largest eigenvalue of X^T X of shard g by `iters` steps of power iteration from a fixed start
 // vector.  Synchronises the stream.  lambda_out on the host.
 hipError_t rule_power_iteration(gcada_ctx* c, int g, int iters, double* lambda_out, hipStream_t s)
 {
-    const ShardDesc& sh = c->shards[g];
-    const int d = (int)c->hy.p;
-    const int64_t rows = sh.rows;
-    const int chunks = (int)std::min<int64_t>(256, (rows + 63) / 64);
-    const int64_t rpc = (rows + chunks - 1) / chunks;
-    const int nbd = (d + kBlock - 1) / kBlock;
-    double *v = nullptr, *t = nullptr, *w = nullptr, *wp = nullptr, *psq = nullptr, *norm = nullptr;
-    hipError_t e = hipSuccess;
-    auto done = [&](hipError_t r) {
-        for (double* q : {v, t, w, wp, psq, norm})
-            if (q) (void)hipFree(q);
-        return r;
-    };
-    if ((e = hipMalloc(&v, 8 * (size_t)d)) != hipSuccess) return done(e);
-    if ((e = hipMalloc(&t, 8 * (size_t)rows)) != hipSuccess) return done(e);
-    if ((e = hipMalloc(&w, 8 * (size_t)d)) != hipSuccess) return done(e);
-    if ((e = hipMalloc(&wp, 8 * (size_t)chunks * d)) != hipSuccess) return done(e);
-    if ((e = hipMalloc(&psq, 8 * (size_t)nbd)) != hipSuccess) return done(e);
-    if ((e = hipMalloc(&norm, 8)) != hipSuccess) return done(e);
-    // start vector: a fixed pattern with a component along every coordinate
-    std::vector<double> h0(d);
+    const PiLayout L = pi_layout(c, g);
+    double* base = nullptr;
+    hipError_t e = hipMalloc(&base, 8 * L.total);
+    if (e != hipSuccess) return e;
+    auto done = [&](hipError_t r) { (void)hipFree(base); return r; };
+    std::vector<double> h0(L.d);
     double n2 = 0;
-    for (int j = 0; j < d; ++j) { h0[j] = 1.0 + 0.5 * ((j * 2654435761u >> 16) & 0xff) / 255.0; n2 += h0[j] * h0[j]; }
-    for (int j = 0; j < d; ++j) h0[j] /= std::sqrt(n2);
-    if ((e = hipMemcpyAsync(v, h0.data(), 8 * (size_t)d, hipMemcpyHostToDevice, s)) != hipSuccess) return done(e);
-    const float* X = (const float*)sh.X;
-    for (int it = 0; it < iters; ++it) {
-        pi_forward_kernel<<<(unsigned)((rows + 3) / 4), kBlock, 0, s>>>(X, rows, sh.ld, d, v, t);
-        pi_backward_kernel<<<dim3(nbd, chunks), kBlock, 0, s>>>(X, rows, sh.ld, d, t, rpc, wp);
-        pi_reduce_kernel<<<nbd, kBlock, 0, s>>>(wp, chunks, d, w, psq);
-        pi_normalize_kernel<<<1, kBlock, 0, s>>>(w, psq, nbd, d, v, norm);
-    }
-    if ((e = hipGetLastError()) != hipSuccess) return done(e);
+    for (int j = 0; j < L.d; ++j) { h0[j] = pi_start_value(j); n2 += h0[j] * h0[j]; }
+    for (int j = 0; j < L.d; ++j) h0[j] /= std::sqrt(n2);
+    if ((e = hipMemcpyAsync(base + L.off_v, h0.data(), 8 * (size_t)L.d, hipMemcpyHostToDevice, s)) != hipSuccess) return done(e);
+    if ((e = pi_rounds(c, g, iters, L, base, s)) != hipSuccess) return done(e);
     double lam = 0;
-    if ((e = hipMemcpyAsync(&lam, norm, 8, hipMemcpyDeviceToHost, s)) != hipSuccess) return done(e);
+    if ((e = hipMemcpyAsync(&lam, base + L.off_norm, 8, hipMemcpyDeviceToHost, s)) != hipSuccess) return done(e);
     if ((e = hipStreamSynchronize(s)) != hipSuccess) return done(e);
     *lambda_out = lam;                  // ||X^T X v|| with ||v|| = 1 converges to lambda_max
     return done(hipSuccess);
+}
+
+// ---- the same with no allocation at all ----------------------------------------------------
+// Scratch of the power iteration in a static device array (every device the library runs on
+// holds its own copy until the process ends).  In host code the array's NAME is not a device
+// address; hipGetSymbolAddress gives the address of the current device's copy, and only that
+// pointer is ever handed to a kernel.
+constexpr size_t kStaticScratchDoubles = (size_t)2 << 20;            // 16 MiB
+static __device__ __align__(256) double scratch[kStaticScratchDoubles];
+
+constexpr int kMaxDevices = 64;
+static double* g_scratch_ptr[kMaxDevices];                            // per device, resolved once
+
+size_t rule_static_scratch_doubles() { return kStaticScratchDoubles; }
+
+size_t rule_power_iteration_scratch_doubles(const gcada_ctx* c, int g) { return pi_layout(c, g).total; }
+
+// Address of the current device's copy of the array (resolved at the first call on that device).
+hipError_t rule_static_scratch(double** ptr)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        double* p = nullptr;
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+// One thread: the start vector in the host routine's arithmetic (same operations in the same
+// order, no fused multiply-adds), so both routes start from the same bits.
+__global__ void pi_start_kernel(int d, double* __restrict__ v)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    double n2 = 0;
+    for (int j = 0; j < d; ++j) {
+        const double h = __dadd_rn(1.0, __ddiv_rn(__dmul_rn(0.5, (double)((j * 2654435761u >> 16) & 0xff)), 255.0));
+        v[j] = h;
+        n2 = __dadd_rn(n2, __dmul_rn(h, h));
+    }
+    const double nrm = __dsqrt_rn(n2);
+    for (int j = 0; j < d; ++j) v[j] = __ddiv_rn(v[j], nrm);
+}
+
+// L_g = kappa * lambda / rows + l2, as the host routine forms it.
+__global__ void pi_finish_kernel(const double* __restrict__ norm, double kappa, double rows, double l2,
+                                 double* __restrict__ out)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *out = __dadd_rn(__ddiv_rn(__dmul_rn(kappa, *norm), rows), l2);
+}
+
+// All groups' constants, one after the other in the static array, result written on the device in
+// stream order.  No allocation, no synchronisation, no host copy.
+hipError_t rule_smoothness_static(gcada_ctx* c, int iters, double* L_out_dev, hipStream_t s)
+{
+    double* base = c->static_scratch;
+    if (!base) return hipErrorInvalidValue;
+    const double kappa = c->dims.model == GCADA_LINREG ? 1.0 : 0.25;
+    for (int g = 0; g < c->hy.G; ++g) {
+        const PiLayout L = pi_layout(c, g);
+        if (L.total > kStaticScratchDoubles) return hipErrorInvalidValue;      // (the caller has checked)
+        pi_start_kernel<<<1, 64, 0, s>>>(L.d, base + L.off_v);
+        hipError_t e = pi_rounds(c, g, iters, L, base, s);
+        if (e != hipSuccess) return e;
+        pi_finish_kernel<<<1, 64, 0, s>>>(base + L.off_norm, kappa, (double)c->shards[g].rows, (double)c->dims.l2,
+                                          L_out_dev + g);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace gcada

@@ -168,6 +168,13 @@ class Gcada:
                                     torch.cuda.current_stream().cuda_stream)
         return out
 
+    def estimate_smoothness_static(self, out: torch.Tensor, iters: int = 30):
+        """The same through the entry point that allocates nothing: `out` is a float64 device tensor
+        of G elements, written in stream order (asynchronous)."""
+        assert out.is_cuda and out.dtype == torch.float64 and out.numel() == self.G and out.is_contiguous()
+        B.gcada_estimate_smoothness_static(self.ctx, iters, out.data_ptr(),
+                                           torch.cuda.current_stream().cuda_stream)
+
     def cost_model(self, mask: np.ndarray, T: np.ndarray):
         mask = np.ascontiguousarray(mask, dtype=np.uint8)
         T = np.ascontiguousarray(T, dtype=np.float64)

@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgcada.so")
 
 SOURCES = ["gcada_api.hip", "lr_kernels.hip", "lr_tiles.hip", "lr_team.hip", "lr_micro.hip", "mlp_kernels.hip",
-           "server_kernels.hip", "rule_kernels.hip"]
+           "server_kernels.hip", "rule_kernels.hip", "calibration.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Wno-unused-parameter",

@@ -1,0 +1,88 @@
+// Benchmark diagnostic: what a plain contiguous read of device memory reaches on this machine.
+// The HBM-bound gradient kernels (step a1 of the iteration: one read of the minibatch rows) are
+// held against the published peak; this figure says how much of that peak any read gets here.
+#include <algorithm>
+
+#include "gcada_internal.h"
+
+namespace gcada {
+
+namespace {
+
+typedef float cal_f32x4 __attribute__((ext_vector_type(4)));
+
+// Every block walks chunks of blockDim.x * U consecutive 16-byte words, grid-strided; U loads per
+// thread are in flight at once.  The sum keeps the loads alive; it is never stored in practice.
+template <int U>
+__global__ void stream_read_kernel(const cal_f32x4* __restrict__ p, size_t n16, float* __restrict__ sink)
+{
+    const size_t chunk = (size_t)blockDim.x * U;
+    const size_t nchunks = n16 / chunk;
+    cal_f32x4 acc = {0, 0, 0, 0};
+    for (size_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const cal_f32x4* q = p + c * chunk + threadIdx.x;
+        cal_f32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = *(const __attribute__((address_space(1))) cal_f32x4*)(q + (size_t)u * blockDim.x);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc += v[u];
+    }
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f) *sink = acc.x;     // (never true for the buffers used)
+}
+
+template <int U>
+hipError_t time_shape(const void* buf, size_t bytes, int blocks, int threads, int reps, float* sink, hipStream_t s,
+                      hipEvent_t e0, hipEvent_t e1, double* gbps)
+{
+    const size_t n16 = bytes / 16;
+    stream_read_kernel<U><<<blocks, threads, 0, s>>>((const cal_f32x4*)buf, n16, sink);     // warm-up
+    hipError_t e = hipEventRecord(e0, s);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) {
+        stream_read_kernel<U><<<blocks, threads, 0, s>>>((const cal_f32x4*)buf, n16, sink);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) return e;
+    // bytes actually read: whole chunks only
+    const size_t chunk = (size_t)threads * U * 16;
+    const double read = (double)(bytes / chunk * chunk);
+    *gbps = read * reps / ((double)ms * 1e-3) / 1e9;
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStream_t s, double* best_gbps)
+{
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e != hipSuccess) return e;
+    if ((e = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return e; }
+    float* sink = nullptr;
+    if ((e = hipMalloc(&sink, sizeof(float))) != hipSuccess) {
+        (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+        return e;
+    }
+    int dev = 0, cus = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    double best = 0;
+    for (int threads : {256, 512, 1024})
+        for (int per_cu : {2, 4, 8, 16, 64}) {
+            double g8 = 0, g16 = 0;
+            if ((e = time_shape<8>(buf, bytes, cus * per_cu, threads, reps, sink, s, e0, e1, &g8)) != hipSuccess) break;
+            if ((e = time_shape<16>(buf, bytes, cus * per_cu, threads, reps, sink, s, e0, e1, &g16)) != hipSuccess) break;
+            best = std::max(best, std::max(g8, g16));
+        }
+    (void)hipFree(sink);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return e;
+    *best_gbps = best;
+    return hipSuccess;
+}
+
+}  // namespace gcada

@@ -651,6 +651,17 @@ try {
     return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_time_gradient_stage");
 }
 
+int gcada_hbm_read_calibration(const void* buf, int64_t bytes, int32_t reps, void* stream, double* gbps)
+{
+    if (!buf || !gbps || reps < 1 || bytes < ((int64_t)64 << 20) || ((uintptr_t)buf % 16))
+        return fail(nullptr, GCADA_EINVAL, "hbm_read_calibration: a 16-byte aligned device buffer of at least 64 MiB, reps >= 1 and an output are required");
+    double g = 0;
+    hipError_t e = gcada::hbm_read_calibration(buf, (size_t)bytes, reps, (hipStream_t)stream, &g);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "hbm_read_calibration");
+    *gbps = g;
+    return GCADA_OK;
+}
+
 int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask, const double* T,
                      double* time, int64_t* comm, int64_t* comp)
 {

@@ -23,9 +23,9 @@
 //
 // Eight DATA waves stream the tiles; a ninth CONTROL wave does the exchange (it loads no tiles,
 // so its polls never queue behind tile loads, which return in order).  One workgroup barrier per
-// tile: the control wave forms the residuals of tile t-2 before the barrier of stage t and
-// publishes the partials of tile t after it; the small LDS arrays involved are double-buffered
-// by the parity of t.
+// tile: after the barrier of stage t the control wave publishes the partials of tile t and then
+// forms the residuals of tile t-1, which the data waves use after the barrier of stage t+1; the
+// small LDS arrays involved are double-buffered by the parity of t.
 #include "lr_device.h"
 
 namespace gcada {
@@ -141,19 +141,29 @@ __device__ __forceinline__ void team_fetch(const TeamArgs& a, TeamSeq& S, int nF
         if (++S.tF == S.ntile) { S.tF = 0; S.gF = team_next_group(a.hy, S.gF, NT); }
     }
     const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
-    const unsigned rows = (unsigned)sh->rows;
-    // cyclic window: first row of this step's window, (k * mu) mod rows, in 32 bits
-    const unsigned cyc_base = (unsigned)((((unsigned long long)a.hy.k % rows) *
-                                          ((unsigned long long)a.hy.mu % rows)) % rows);
+    // (every data wave runs this once per tile, between two tiles' worth of arithmetic: it is kept
+    // to a handful of scalar instructions -- the kernel is bound by how fast a wave gets through
+    // its instructions, not by memory.  The modulo arithmetic of the cyclic window in particular
+    // stays out of the path that has row ids.)
+    if (a.idx) {
+        const_i32* ids = (const_i32*)(uintptr_t)a.idx + (int64_t)S.gF * a.hy.mu;
+        const int i0 = S.tF * kR, last = a.hy.mu - 1;
 #pragma unroll
-    for (int u = 0; u < kR; ++u) {
-        // the last tile of a group may reach past the minibatch: such a row repeats the last one
-        // (it is loaded, its residuals are zero)
-        const int i = min(S.tF * kR + u, a.hy.mu - 1);
-        int rr;
-        if (a.idx) rr = ((const_i32*)(uintptr_t)a.idx)[(int64_t)S.gF * a.hy.mu + i];
-        else rr = (int)((cyc_base + (unsigned)i) % rows);
-        S.rows_nxt[u] = __builtin_amdgcn_readfirstlane(rr);
+        for (int u = 0; u < kR; ++u) {
+            // the last tile of a group may reach past the minibatch: such a row repeats the last
+            // one (it is loaded, its residuals are zero)
+            S.rows_nxt[u] = __builtin_amdgcn_readfirstlane(ids[min(i0 + u, last)]);
+        }
+    } else {
+        const unsigned rows = (unsigned)sh->rows;
+        // cyclic window: first row of this step's window, (k * mu) mod rows, in 32 bits
+        const unsigned cyc_base = (unsigned)((((unsigned long long)a.hy.k % rows) *
+                                              ((unsigned long long)a.hy.mu % rows)) % rows);
+#pragma unroll
+        for (int u = 0; u < kR; ++u) {
+            const int i = min(S.tF * kR + u, a.hy.mu - 1);
+            S.rows_nxt[u] = __builtin_amdgcn_readfirstlane((int)((cyc_base + (unsigned)i) % rows));
+        }
     }
     S.x_nxt = (const float*)sh->X;
     S.y_nxt = (const float*)sh->y;
@@ -177,26 +187,28 @@ __device__ __forceinline__ void team_load_tile(TeamRegs& R, const TeamSeq& S, co
     for (int u = 0; u < kR; ++u) {
         const float* xrow = S.x_nxt + (int64_t)S.rows_nxt[u] * S.ld_nxt;
 #pragma unroll
-        for (int q = 0; q < kV; ++q) R.xb[JL][u][q] = global_load4(xrow + C.c[q]);
+        for (int q = 0; q < kV; ++q) R.xb[JL][u][q] = global_load4_stream(xrow + C.c[q]);
     }
 }
 
-// Label of row `lane` (< kR) of the tile S.gF/S.tF point at; the lane looks its row id up itself.
-__device__ __forceinline__ float team_load_label(const TeamArgs& a, const TeamSeq& S, int lane)
+// Row id of row `lane` (< kR) of the tile S.gF/S.tF point at (a load when ids are given), and the
+// label of that row.  The two are split so that the id can be requested a stage before the label.
+__device__ __forceinline__ int team_label_row(const TeamArgs& a, const TeamSeq& S, int lane)
+{
+    typedef const ShardDesc __attribute__((address_space(4))) const_shard;
+    const int i = min(S.tF * kR + lane, a.hy.mu - 1);
+    if (a.idx) return a.idx[(int64_t)S.gF * a.hy.mu + i];
+    const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
+    const unsigned rows = (unsigned)sh->rows;
+    const unsigned cyc_base = (unsigned)((((unsigned long long)a.hy.k % rows) *
+                                          ((unsigned long long)a.hy.mu % rows)) % rows);
+    return (int)((cyc_base + (unsigned)i) % rows);
+}
+__device__ __forceinline__ float team_label_of(const TeamArgs& a, const TeamSeq& S, int row)
 {
     typedef const ShardDesc __attribute__((address_space(4))) const_shard;
     const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
-    const unsigned rows = (unsigned)sh->rows;
-    const int i = min(S.tF * kR + lane, a.hy.mu - 1);
-    int myrow;
-    if (a.idx) {
-        myrow = a.idx[(int64_t)S.gF * a.hy.mu + i];
-    } else {
-        const unsigned cyc_base = (unsigned)((((unsigned long long)a.hy.k % rows) *
-                                              ((unsigned long long)a.hy.mu % rows)) % rows);
-        myrow = (int)((cyc_base + (unsigned)i) % rows);
-    }
-    return global_load((const float*)sh->y + myrow);
+    return global_load((const float*)sh->y + row);
 }
 
 // Move S.gF/S.tF on to tile nF (the control wave's share of team_fetch).
@@ -318,37 +330,64 @@ __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, 
     }
 }
 
-// One pipeline stage of the CONTROL wave: it loads no tiles, so its poll of the exchange
-// buffer and its label loads never queue behind tile loads.  Before the barrier of stage n it
-// forms the residuals of tile n-2 from all members' partials (published two stages ago); after
-// the barrier it adds the data waves' partial dots of tile n and publishes them.
+// What the control wave carries from one stage to the next.
+struct TeamCtl {
+    int row_next;                 // row id whose label is requested in stage n (tile n+2; lane < kR)
+    float y_new;                  // label requested in stage n-1 (tile n+1; lane < kR)
+    int gR, tR;                   // group and tile-in-group of the tile whose residuals are formed next
+    bool gave_up;                 // a bounded wait was exhausted
+    double lacc, lacc_prev;       // loss sums: of the group whose residuals are being formed, of the one before
+};
+
+// One pipeline stage of the CONTROL wave.  It loads no tiles, so its poll of the exchange buffer
+// and its label loads never queue behind tile loads of its own.  Its path is the longest of the
+// workgroup (a round trip to the exchange words takes 1.5 us under load, as long as the data
+// waves' whole share of a stage), so nothing on it may hold up the barrier: in stage n it
+//   [A] requests the words of tile n-1 (every member published them after its barrier of stage
+//       n-1, about a stage ago) and the next label, then joins the barrier of stage n at once;
+//   [B] adds the data waves' partial dots of tile n and publishes them -- the other members wait
+//       for these, two stages from now;
+//   [C] forms the residuals of tile n-1 from the words requested in [A], for the data waves to
+//       use after the barrier of stage n+1.
 __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S, unsigned long long* xt,
-                                                   int n, int m, bool& gave_up, float& y_new, double& lacc,
-                                                   TeamLds& L)
+                                                   int n, int m, TeamCtl& K, TeamLds& L)
 {
     const int lane = threadIdx.x % kWave;
     const bool have_cur = n < S.ntot, have_add = n >= 2 && n - 2 < S.ntot;
+    const bool have_res = n >= 1 && n - 1 < S.ntot;          // tile n-1 exists
     const bool poller = lane < a.TS * kR;
 
-    // lane l polls member l/4's pairs (z, dz) of row l%4; lanes without a member poll nothing
-    const unsigned long long* mine = xt + (int)(((unsigned)n + 2u) % kSlots) * a.TS * kPartial + lane * 2;
+    // [A] lane l polls member l/4's pairs (z, dz) of row l%4 of tile n-1: slot (n-1) mod 4
+    const unsigned long long* mine = xt + (int)(((unsigned)n + 3u) % kSlots) * a.TS * kPartial + lane * 2;
     unsigned long long pz = 0, pdz = 0;
-    if (poller) {
+    if (poller && have_res) {
         pz = pair_load(mine);
         pdz = pair_load(mine + 1);
     }
-    // file the label requested in the previous stage (tile n+1), then request that of tile n+2
     if (lane < kR) {
-        L.s_y[(n + 1) % kLabelRing][lane] = y_new;
-        y_new = team_load_label(a, S, lane);
+        L.s_y[(n + 1) % kLabelRing][lane] = K.y_new;         // label of tile n+1, requested a stage ago
+        K.y_new = team_label_of(a, S, K.row_next);            // S points at tile n+2, and so does row_next
     }
     team_advance(a, S, n + 3, a.NT);
+    if (lane < kR) K.row_next = team_label_row(a, S, lane);   // tile n+3
+    __syncthreads();
 
-    if (have_add) {
-        const unsigned want = a.tag_base + a.wait.tag_skew + (unsigned)n - 2u;
+    // [B]
+    if (have_cur) {
+        // member partial: lane l adds value l%8 over the data waves in a fixed tree
+        float w = L.s_dot[n & 1][lane >> 3][lane & 7];
+#pragma unroll
+        for (int o = 8; o < kWave; o <<= 1) w += __shfl_xor(w, o, kWave);
+        if (lane < kPartial)
+            pair_store(xt + ((n % kSlots) * a.TS + m) * kPartial + lane, w, a.tag_base + (unsigned)n);
+    }
+
+    // [C]
+    if (have_res) {
+        const unsigned want = a.tag_base + a.wait.tag_skew + (unsigned)n - 1u;
         bool ok = !poller || (pair_tag(pz) == want && pair_tag(pdz) == want);
         unsigned spins = 0;
-        while (!gave_up && !__all(ok)) {         // rare: a member is more than a tile behind
+        while (!K.gave_up && !__all(ok)) {       // rare: a member is more than a tile behind
             if (poller && !ok) {
                 pz = pair_load(mine);
                 pdz = pair_load(mine + 1);
@@ -356,7 +395,7 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
             }
             if (++spins > a.wait.limit) {
                 if (lane == 0) raise_device_error(a.ctl, 1u);
-                gave_up = true;
+                K.gave_up = true;
             }
         }
         // lane l holds member l/4's partial (z, dz) of row l%4: add the members in a fixed tree
@@ -367,31 +406,23 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
             z += __shfl_xor(z, o, kWave);
             dz += __shfl_xor(dz, o, kWave);
         }
+        if (K.tR == 0) { K.lacc_prev = K.lacc; K.lacc = 0; }         // a new group begins
         if (lane < kR) {
             float r, dr, ls;
-            residuals(a.hy.quadratic != 0, z, dz, L.s_y[(n - 2) % kLabelRing][lane], r, dr, ls);
-            if (S.tA * kR + lane >= a.hy.mu) r = dr = ls = 0.0f;      // row past the minibatch
-            L.s_res[n & 1][lane] = make_float2(r, dr);
-            lacc += (double)ls;
+            residuals(a.hy.quadratic != 0, z, dz, L.s_y[(n - 1) % kLabelRing][lane], r, dr, ls);
+            if (K.tR * kR + lane >= a.hy.mu) r = dr = ls = 0.0f;      // row past the minibatch
+            L.s_res[(n + 1) & 1][lane] = make_float2(r, dr);
+            K.lacc += (double)ls;
         }
-    }
-    __syncthreads();
-
-    if (have_cur) {
-        // member partial: lane l adds value l%8 over the data waves in a fixed tree
-        float w = L.s_dot[n & 1][lane >> 3][lane & 7];
-#pragma unroll
-        for (int o = 8; o < kWave; o <<= 1) w += __shfl_xor(w, o, kWave);
-        if (lane < kPartial)
-            pair_store(xt + ((n % kSlots) * a.TS + m) * kPartial + lane, w, a.tag_base + (unsigned)n);
+        if (++K.tR == S.ntile) { K.tR = 0; K.gR = team_next_group(a.hy, K.gR, a.NT); }
     }
     if (have_add) {
         if (S.tA == S.ntile - 1) {
             __syncthreads();                     // the data waves' barrier at the end of a group
-            double l = lane < kR ? lacc : 0.0;
+            // tile n-2 closed group S.gA; if there is a tile n-1 it opened the next group
+            double l = lane < kR ? (have_res ? K.lacc_prev : K.lacc) : 0.0;
             l = wave_sum(l);
             if (m == 0 && lane == 0) a.part_loss[S.gA] = l;
-            lacc = 0;
             S.tA = 0;
             S.gA = team_next_group(a.hy, S.gA, a.NT);
         } else {
@@ -439,17 +470,18 @@ __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
         S.tF = S.tC = S.tA = 0;
         // ---- control wave ----
         unsigned long long* xt = a.xch + (int64_t)team * kSlots * a.TS * kPartial;   // the team's slots
-        bool gave_up = false;                    // a bounded wait was exhausted
-        float y_new = 1.0f;
-        double lacc = 0;
-        if (lane < kR) L.s_y[0][lane] = team_load_label(a, S, lane);
+        TeamCtl K;
+        K.row_next = 0; K.y_new = 1.0f; K.gave_up = false; K.lacc = K.lacc_prev = 0;
+        K.gR = g_first; K.tR = 0;
+        if (lane < kR) L.s_y[0][lane] = team_label_of(a, S, team_label_row(a, S, lane));
         team_advance(a, S, 1, a.NT);
-        if (lane < kR) y_new = team_load_label(a, S, lane);
+        if (lane < kR) K.y_new = team_label_of(a, S, team_label_row(a, S, lane));
         team_advance(a, S, 2, a.NT);
+        if (lane < kR) K.row_next = team_label_row(a, S, lane);
         for (int n = 0; n < nstage; n += kRegTiles) {
-            team_control_stage(a, S, xt, n, m, gave_up, y_new, lacc, L);
-            team_control_stage(a, S, xt, n + 1, m, gave_up, y_new, lacc, L);
-            team_control_stage(a, S, xt, n + 2, m, gave_up, y_new, lacc, L);
+            team_control_stage(a, S, xt, n, m, K, L);
+            team_control_stage(a, S, xt, n + 1, m, K, L);
+            team_control_stage(a, S, xt, n + 2, m, K, L);
         }
     } else {
         // ---- data waves ----

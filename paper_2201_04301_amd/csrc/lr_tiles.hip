@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     for (int u = 0; u < kTR; ++u) {
         // the row id is the same for the whole wave: keep it in a scalar register
         const int64_t row = __builtin_amdgcn_readfirstlane(s_row[wr * kTR + u]);
-        x[u] = col_ok && row >= 0 ? global_load4(X + row * sh.ld + col) : make_float4(0, 0, 0, 0);
+        x[u] = col_ok && row >= 0 ? global_load4_stream(X + row * sh.ld + col) : make_float4(0, 0, 0, 0);
     }
     // while the tile streams in: labels, the two iterates
     float my_y = 1.0f;

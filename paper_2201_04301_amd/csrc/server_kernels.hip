@@ -183,6 +183,18 @@ __device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&v)
     }
 }
 
+// gradient rows are read once per step: streaming loads
+template <int VW>
+__device__ __forceinline__ void load_vec_stream(const float* __restrict__ p, float (&v)[VW])
+{
+    if constexpr (VW == 4) {
+        const float4 t = global_load4_stream(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+        v[0] = __builtin_nontemporal_load(p);
+    }
+}
+
 template <int VW>
 __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&v)[VW])
 {
@@ -334,8 +346,8 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int g = s_sel[i + e], wl = s_which[g];
-                load_vec<VW>(a.gbuf + ((int64_t)(1 - wl) * hy.G + g) * hy.pstride + j0, gg[e]);
-                load_vec<VW>(a.gbuf + ((int64_t)wl * hy.G + g) * hy.pstride + j0, ll[e]);
+                load_vec_stream<VW>(a.gbuf + ((int64_t)(1 - wl) * hy.G + g) * hy.pstride + j0, gg[e]);
+                load_vec_stream<VW>(a.gbuf + ((int64_t)wl * hy.G + g) * hy.pstride + j0, ll[e]);
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -345,8 +357,8 @@ __global__ __launch_bounds__(B) void server_step_kernel(ServerArgs a)
         for (; i < nsel; ++i) {
             const int g = s_sel[i], wl = s_which[g];
             float gg[VW], ll[VW];
-            load_vec<VW>(a.gbuf + ((int64_t)(1 - wl) * hy.G + g) * hy.pstride + j0, gg);
-            load_vec<VW>(a.gbuf + ((int64_t)wl * hy.G + g) * hy.pstride + j0, ll);
+            load_vec_stream<VW>(a.gbuf + ((int64_t)(1 - wl) * hy.G + g) * hy.pstride + j0, gg);
+            load_vec_stream<VW>(a.gbuf + ((int64_t)wl * hy.G + g) * hy.pstride + j0, ll);
 #pragma unroll
             for (int q = 0; q < VW; ++q) ac[q] += gg[q] - ll[q];
         }

@@ -228,6 +228,26 @@ def run_config(w, K, W, repeats, args, cpu_info, headline: bool):
     extra = {}
     if w.name == "mlp_3072_bf16" and args.rule == "gradient_difference":
         extra = mlp_step_kinds(w, gpu, Xs, ys, args)
+    if w.name == "lr_4k" and args.rule == "gradient_difference" and not args.separate_finish:
+        # the same steps with one launch per step (GCADA_OPT_DEFERRED_FINISH: the finish of step k at
+        # the head of the launch of step k+1; mask and loss of a step arrive with the next call)
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_DEFERRED_FINISH, 1)
+        gpu.set_theta(make_theta0(w))
+        run_fast(0, W)
+        torch.cuda.synchronize()
+        p2 = []
+        for r in range(repeats):
+            k0 = W + r * K
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            run_fast(k0, k0 + K)
+            torch.cuda.synchronize()
+            p2.append(time.perf_counter() - t1)
+        check_flag()
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_DEFERRED_FINISH, 0)
+        d2 = statistics.median(p2)
+        extra = {"one_launch_per_step": {"iters_per_s": round(K / d2, 2), "ms_per_step": round(d2 / K * 1e3, 5),
+                                         "final_loss": float(losses[W + repeats * K - 1].item())}}
 
     print(f"[bench] {w.name}: {iters_s:.1f} it/s, stage {grad_ms:.4f} ms; timing the oracle", file=sys.stderr, flush=True)
     cpu = None
@@ -370,23 +390,28 @@ def main():
 
     w = CONFIGS[args.workload]
     head["roofline"]["hbm_read_achievable_gbs"] = round(hbm_read, 1)
+    # per configuration (short keys keep the line small): iterations/s, gradient evaluations/s
+    # (2 G per iteration), ms per step, the dominant stage and its ms, its fraction of the peak
+    # (executed flops for the MLPs; "frac_alg": by the algorithmic flop count), the whole step's
+    # fraction (algorithmic work / step time / peak), the oracle's iterations/s on all threads and
+    # on one, and the oracle steps timed
     per_config = {}
     for name in ORDER:
         if name in details:
             d = details[name]
             r = d["roofline"]
-            per_config[name] = {"iters_per_s": d["iters_per_s"], "grad_evals_per_s": d["grad_evals_per_s"],
-                                "ms_per_step": d["ms_per_step"], "steps": d["steps"],
-                                "stage": r["kernel"].split(" ")[0].split(":")[0], "stage_ms": r["avg_ms"],
-                                "bound": r["bound"], "frac": r["frac"], "whole_step_frac": r["whole_step_frac"],
-                                "cpu_iters_per_s": d["cpu_baseline"]["value"] if d["cpu_baseline"] else None,
-                                "cpu_1thread": (d["cpu_baseline"] or {}).get("one_thread_iters_per_s"),
-                                "cpu_steps": int(d["cpu_baseline"]["sample"].split(" ")[1]) if d["cpu_baseline"] else None}
+            cb = d["cpu_baseline"] or {}
+            e = {"it_s": d["iters_per_s"], "ge_s": d["grad_evals_per_s"], "ms": d["ms_per_step"],
+                 "stage": r["kernel"].split(" [")[0].split(" (")[0], "stage_ms": r["avg_ms"], "bound": r["bound"],
+                 "frac": r["frac"], "step_frac": r["whole_step_frac"], "cpu_it_s": cb.get("value"),
+                 "cpu_1t": cb.get("one_thread_iters_per_s"),
+                 "cpu_steps": int(cb["sample"].split(" ")[1]) if cb else None}
             if "frac_algorithmic" in r:
-                per_config[name]["frac_algorithmic"] = r["frac_algorithmic"]
-            for k_ in ("step_kinds", "live_variant"):
+                e["frac_alg"] = r["frac_algorithmic"]
+            for k_ in ("step_kinds", "live_variant", "one_launch_per_step"):
                 if k_ in d:
-                    per_config[name][k_] = {a: b for a, b in d[k_].items() if a not in ("note", "workload")}
+                    e[k_] = {a_: b_ for a_, b_ in d[k_].items() if a_ not in ("note", "workload")}
+            per_config[name] = e
     out = {"metric": "G-CADA iterations/s", "value": head["iters_per_s"], "unit": "iters/s",
            "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": head["ms_per_step"],
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

@@ -236,6 +236,16 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * instead of two n_1 x n_0 weight gradients, and the first layer's gradient is formed only for
  * the groups that upload.  Same statistic up to rounding (the signal difference is rounded to
  * bf16 once more); 0 computes it from the two weight gradients.
+ * GCADA_OPT_DEFERRED_FINISH [0]: whole-row logistic path (d <= 4096) when all tiles of a step fit the
+ * device at once (G * ceil(mu / tile rows) workgroups, at most one per compute unit, at least d / 64):
+ * ONE launch per step.  The rows a step reads depend on its row ids only, not on the iterate, so the
+ * finish of step k (reduce, selection, innovation sum, update) runs at the head of the launch of
+ * step k+1, while all workgroups wait for their rows; the new iterate reaches the tiles through
+ * tagged words inside the launch.  Consequence for the caller: mask_out and loss_out of the call
+ * for step k are written by the NEXT gcada_step (or by gcada_state / gcada_get_state /
+ * gcada_set_option (any option but GCADA_OPT_EXPIRE_NEXT_WAIT) / gcada_set_rule /
+ * gcada_time_gradient_stage, which run a finish that is still to come; gcada_set_theta / gcada_set_state discard it) and stay borrowed until then; gcada_state's
+ * k counts the steps issued.  Same arithmetic: the state is bit-identical to the two-launch path.
  * GCADA_OPT_EXPIRE_NEXT_WAIT [0]: a diagnostic for tests of the error path.  With 1, the kernels of
  * the NEXT gcada_step that wait for other workgroups' words look for words nobody publishes and
  * give up after a few polls: every kernel runs to its end, the step's results are invalid, and the
@@ -243,7 +253,8 @@ int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask /*[
  * Errors: GCADA_EINVAL (unknown option).
  */
 enum { GCADA_OPT_SINGLE_PASS_LOGREG = 1, GCADA_OPT_FUSED_FINISH = 2, GCADA_OPT_LAZY_GRADIENT_STORE = 3,
-       GCADA_OPT_GRAM_STATISTIC = 4, GCADA_OPT_EXPIRE_NEXT_WAIT = 5 };
+       GCADA_OPT_GRAM_STATISTIC = 4, GCADA_OPT_EXPIRE_NEXT_WAIT = 5,
+       GCADA_OPT_DEFERRED_FINISH = 6 };
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value);
 
 /*

@@ -26,6 +26,7 @@ GCADA_OPT_FUSED_FINISH = 2
 GCADA_OPT_LAZY_GRADIENT_STORE = 3
 GCADA_OPT_GRAM_STATISTIC = 4
 GCADA_OPT_EXPIRE_NEXT_WAIT = 5
+GCADA_OPT_DEFERRED_FINISH = 6
 
 EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta", "gcada_step",
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",

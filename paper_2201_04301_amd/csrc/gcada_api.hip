@@ -327,6 +327,16 @@ static int step_launches(gcada_ctx* ctx, const int32_t* idx, uint8_t* mask_out, 
     hipError_t e;
     const bool server_rule = ctx->rule == GCADA_RULE_SERVER;
     ctx->hy.sel = server_rule ? ctx->mask : nullptr;
+    // whole-row logistic path with one launch per step: the finish of a step runs at the head of
+    // the next step's launch; any other path first lets a finish that is still to come run
+    const bool deferred = ctx->dims.model != GCADA_MLP && !gcada::lr_micro_applies(ctx) && gcada::lr_tile_step_applies(ctx);
+    if (!deferred && (e = gcada::lr_tile_flush(ctx, s, false)) != hipSuccess) return fail_hip(ctx, e, "finish kernel");
+    if (deferred) {
+        ctx->lr_fused_finish = true;
+        if ((e = gcada::lr_tile_step(ctx, idx, mask_out, loss_out, s)) != hipSuccess) return fail_hip(ctx, e, "step kernel");
+        ctx->k += 1;
+        return GCADA_OK;
+    }
     if (ctx->dims.model != GCADA_MLP && gcada::lr_micro_applies(ctx)) {
         // small linear model: the whole iteration is one launch
         ctx->lr_fused_finish = false;
@@ -395,6 +405,8 @@ int gcada_state(gcada_ctx* ctx, gcada_state_view* out)
     if (!ctx) return GCADA_EINVAL;
     if (!out) return fail(ctx, GCADA_EINVAL, "state: out must not be NULL");
     if (int rc = check_host_mirror(ctx)) return rc;
+    if (hipError_t e = gcada::lr_tile_flush(ctx, nullptr, true); e != hipSuccess)
+        return fail_hip(ctx, e, "finish kernel");
     if (hipError_t e = gcada::lr_tile_close(ctx, nullptr, true); e != hipSuccess)
         return fail_hip(ctx, e, "history kernel");
     gcada_state_view v{};
@@ -417,6 +429,7 @@ try {
     const gcada::Hyper& hy = ctx->hy;
     const size_t p = (size_t)hy.p;
     const int nslot = hy.D + 1;
+    HIP_TRY(ctx, gcada::lr_tile_flush(ctx, nullptr, true));
     HIP_TRY(ctx, gcada::lr_tile_close(ctx, nullptr, true));
     HIP_TRY(ctx, hipDeviceSynchronize());
     if (int rc = check_device_flag(ctx)) return rc;
@@ -499,6 +512,13 @@ try {
 int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
 {
     if (!ctx) return GCADA_EINVAL;
+    // (a finish that is still to come runs under the options its step was issued with)
+    if (option != GCADA_OPT_EXPIRE_NEXT_WAIT)
+        if (hipError_t e = gcada::lr_tile_flush(ctx, nullptr, true); e != hipSuccess) return fail_hip(ctx, e, "finish kernel");
+    if (option == GCADA_OPT_DEFERRED_FINISH) {
+        ctx->allow_deferred_finish = value != 0;
+        return GCADA_OK;
+    }
     if (option == GCADA_OPT_SINGLE_PASS_LOGREG) {
         ctx->allow_single_pass = value != 0;
         return GCADA_OK;
@@ -526,6 +546,7 @@ int gcada_set_option(gcada_ctx* ctx, int32_t option, int32_t value)
 int gcada_set_rule(gcada_ctx* ctx, int32_t rule, const double* L)
 {
     if (!ctx) return GCADA_EINVAL;
+    if (hipError_t e = gcada::lr_tile_flush(ctx, nullptr, true); e != hipSuccess) return fail_hip(ctx, e, "finish kernel");
     if (rule != GCADA_RULE_GRADIENT_DIFFERENCE && rule != GCADA_RULE_SERVER)
         return fail(ctx, GCADA_EINVAL, "set_rule: unknown rule");
     if (L) {
@@ -616,6 +637,7 @@ try {
     for (int g = 0; g < ctx->hy.G; ++g)
         if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "time_gradient_stage: a group has no shard");
     hipStream_t s = (hipStream_t)stream;
+    if (hipError_t ef = gcada::lr_tile_flush(ctx, s, false); ef != hipSuccess) return fail_hip(ctx, ef, "finish kernel");
     set_iteration(ctx);
     hipEvent_t e0, e1;
     HIP_TRY(ctx, hipEventCreate(&e0));

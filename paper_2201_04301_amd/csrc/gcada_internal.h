@@ -204,6 +204,7 @@ struct gcada_ctx {
     bool allow_gram = true;        // first-layer statistic through Gram matrices when it pays (bf16 MLP)
     bool allow_single_pass = true;
     bool allow_fused_finish = true;
+    bool allow_deferred_finish = false;   // whole-row logistic path: one launch per step (finish of step k-1 with the tiles of step k)
     bool lr_fused_finish = false;  // this step: lr_tile_finish replaces lr_tile_reduce + server_step
 
     unsigned int* err_mirror = nullptr;   // pinned host word the kernels' give-up paths write to
@@ -236,6 +237,11 @@ hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool
 // them up (on `s`, or on the stream of that step) before anyone else reads them
 hipError_t lr_tile_close(gcada_ctx* c, hipStream_t s, bool use_step_stream);
 void lr_tile_forget(gcada_ctx* c);
+// one launch per step: the finish of a step runs at the head of the next step's tile launch
+bool lr_tile_step_applies(const gcada_ctx* c);
+bool lr_tile_step_pending(const gcada_ctx* c);
+hipError_t lr_tile_step(gcada_ctx* c, const int32_t* idx, uint8_t* mask_out, float* loss_out, hipStream_t s);
+hipError_t lr_tile_flush(gcada_ctx* c, hipStream_t s, bool use_step_stream);
 
 // single-pass logistic gradients for wide rows: teams of workgroups share a tile (lr_team.hip)
 hipError_t lr_team_plan(gcada_ctx* c);

@@ -31,36 +31,43 @@ struct TileArgs {
     int RB;               // row blocks (tiles) per group
 };
 
-// grid: G * RB workgroups, one tile each.
+// What a tile needs from the step BEFORE it when that step's finish runs in the same launch
+// (lr_tile_step_kernel): the new iterate and each group's stale slot arrive as tagged words that
+// the finishing workgroups of the launch publish.
+struct StepLink {
+    const unsigned long long* xtheta;   // [p] {tag, bits of theta^{k}_j}: the iterate this tile is evaluated at
+    const unsigned long long* xsel;     // [G] {tag, ring slot of the group's stale iterate}
+    unsigned tag;
+    WaitPolicy wait;
+    Ctl* ctl;
+};
+
 template <int WC>
-__global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
+struct TileShared {
+    static constexpr int WR = kWaves / WC;
+    static constexpr int R = kTR * WR;
+    int s_row[R];
+    float s_dot[WC][R * 2];
+    float2 s_res[R];
+    float4 s_acc[WR > 1 ? 2 : 1][WR > 1 ? kWaves : 1][kWave];
+    double s_red[kWaves];
+};
+
+// Row ids of the tile into LDS (one barrier).  Returns this thread's own row id and validity
+// (tid < R only).
+template <int WC>
+__device__ __forceinline__ void tile_rows(const TileArgs& a, TileShared<WC>& sm, const ShardDesc& sh, int g, int rb,
+                                          int& my_row, bool& my_valid)
 {
-    constexpr int WR = kWaves / WC;
-    constexpr int R = kTR * WR;
-
-    __shared__ int s_row[R];
-    __shared__ float s_dot[WC][R * 2];
-    __shared__ float2 s_res[R];
-    __shared__ float4 s_acc[WR > 1 ? 2 : 1][WR > 1 ? kWaves : 1][kWave];
-    __shared__ double s_red[kWaves];
-
+    constexpr int R = TileShared<WC>::R;
     const Hyper& hy = a.hy;
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int wr = wave / WC, wc = wave % WC;
-    const int g = blockIdx.x / a.RB, rb = blockIdx.x % a.RB;
-    if (hy.sel && !hy.sel[g]) {                  // unselected group: no gradient, no loss
-        if (tid == 0) a.part_loss[blockIdx.x] = 0;
-        return;
-    }
+    const int tid = threadIdx.x;
     const int mu = hy.mu;
     const long long k = hy.k;
-    const ShardDesc sh = a.shards[g];
-    const float* __restrict__ X = (const float*)sh.X;
-
     // row ids first: the tile's loads depend on nothing else
     // (the last tile of a group may reach past the minibatch: such rows load nothing and weigh 0)
-    int my_row = 0;
-    bool my_valid = false;
+    my_row = 0;
+    my_valid = false;
     if (tid < R) {
         const int i = rb * R + tid;
         my_valid = i < mu;
@@ -74,30 +81,84 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
             my_row = (int)((((unsigned long long)k % n) * ((unsigned long long)mu % n) +
                             (unsigned long long)i) % n);
         }
-        s_row[tid] = my_valid ? my_row : -1;
+        sm.s_row[tid] = my_valid ? my_row : -1;
     }
-    const int col = wc * 256 + lane * 4;
-    const bool col_ok = col < (int)hy.p;         // d is a multiple of 4; the last column wave may be partly idle
     __syncthreads();
+}
 
-    // the tile: all 16 loads of a thread are in flight at once
-    float4 x[kTR];
+// The tile: all 16 loads of a thread are in flight at once.
+template <int WC>
+__device__ __forceinline__ void tile_issue(const TileArgs& a, const TileShared<WC>& sm, const ShardDesc& sh,
+                                           float4 (&x)[kTR])
+{
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int wr = wave / WC, wc = wave % WC;
+    const int col = wc * 256 + lane * 4;
+    const bool col_ok = col < (int)a.hy.p;       // d is a multiple of 4; the last column wave may be partly idle
+    const float* __restrict__ X = (const float*)sh.X;
 #pragma unroll
     for (int u = 0; u < kTR; ++u) {
         // the row id is the same for the whole wave: keep it in a scalar register
-        const int64_t row = __builtin_amdgcn_readfirstlane(s_row[wr * kTR + u]);
+        const int64_t row = __builtin_amdgcn_readfirstlane(sm.s_row[wr * kTR + u]);
         x[u] = col_ok && row >= 0 ? global_load4_stream(X + row * sh.ld + col) : make_float4(0, 0, 0, 0);
     }
+}
+
+// Dot products, residuals, weighted row sums, tile partials.  link == nullptr: the iterate and the
+// stale slot are read from the ring and the ages (the step before has completed); otherwise they
+// are polled from the words the finishing workgroups of this launch publish.
+template <int WC>
+__device__ __forceinline__ void tile_finish(const TileArgs& a, TileShared<WC>& sm, const ShardDesc& sh, int g, int rb,
+                                            int my_row, bool my_valid, float4 (&x)[kTR], const StepLink* link)
+{
+    constexpr int WR = TileShared<WC>::WR;
+    constexpr int R = TileShared<WC>::R;
+    const Hyper& hy = a.hy;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int wr = wave / WC, wc = wave % WC;
+    const int col = wc * 256 + lane * 4;
+    const bool col_ok = col < (int)hy.p;
+    const int tile = g * a.RB + rb;
     // while the tile streams in: labels, the two iterates
     float my_y = 1.0f;
     if (tid < R) my_y = global_load((const float*)sh.y + my_row);
-    const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
-    const int old = stale_slot_of(hy, a.tau[g]);
-    const float* __restrict__ ts = a.ring + (int64_t)old * hy.pstride;
     float4 th4 = make_float4(0, 0, 0, 0), u4 = th4;
-    if (col_ok) {
-        th4 = *(const float4*)(th + col);
-        u4 = *(const float4*)(ts + col);
+    if (link == nullptr) {
+        const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
+        const int old = stale_slot_of(hy, a.tau[g]);
+        const float* __restrict__ ts = a.ring + (int64_t)old * hy.pstride;
+        if (col_ok) {
+            th4 = *(const float4*)(th + col);
+            u4 = *(const float4*)(ts + col);
+        }
+    } else {
+        // (these loads return after the tile's own, which were issued before them: by then the
+        // words have normally arrived; the wait is bounded)
+        unsigned long long w[4] = {0, 0, 0, 0}, ws = 0;
+        unsigned spins = 0;
+        for (;;) {
+            bool ok = true;
+            if (col_ok) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    w[e] = __hip_atomic_load(link->xtheta + col + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    ok = ok && (unsigned)(w[e] >> 32) == link->tag + link->wait.tag_skew;
+                }
+            }
+            ws = __hip_atomic_load(link->xsel + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            ok = ok && (unsigned)(ws >> 32) == link->tag + link->wait.tag_skew;
+            if (__all(ok)) break;
+            if (++spins > link->wait.limit) {        // never in a healthy launch: report, do not hang
+                if (lane == 0) raise_device_error(link->ctl, 4u);
+                break;
+            }
+        }
+        const int old = (int)(unsigned)(ws & 0xffffffffull) % (hy.D + 1);     // (in range even after a give-up)
+        if (col_ok) {
+            th4 = make_float4(__uint_as_float((unsigned)w[0]), __uint_as_float((unsigned)w[1]),
+                              __uint_as_float((unsigned)w[2]), __uint_as_float((unsigned)w[3]));
+            u4 = *(const float4*)(a.ring + (int64_t)old * hy.pstride + col);
+        }
     }
     const float4 dl4 = make_float4(th4.x - u4.x, th4.y - u4.y, th4.z - u4.z, th4.w - u4.w);
     // partial dot products of the wave's 256 columns, four rows at a time
@@ -111,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
             v[2 * i + 1] = q.x * dl4.x + q.y * dl4.y + q.z * dl4.z + q.w * dl4.w;
         }
         Butterfly<8, 32>::run(v, lane);              // lane holds value (lane >> 3)
-        if ((lane & 7) == 0) s_dot[wc][(wr * kTR + qt * 4) * 2 + (lane >> 3)] = v[0];
+        if ((lane & 7) == 0) sm.s_dot[wc][(wr * kTR + qt * 4) * 2 + (lane >> 3)] = v[0];
     }
     __syncthreads();
     double lsum = 0;
@@ -119,13 +180,13 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
         float z = 0, dz = 0;
 #pragma unroll
         for (int w = 0; w < WC; ++w) {               // fixed order over the column waves
-            z += s_dot[w][2 * tid];
-            dz += s_dot[w][2 * tid + 1];
+            z += sm.s_dot[w][2 * tid];
+            dz += sm.s_dot[w][2 * tid + 1];
         }
         float r, dr, ls;
         residuals(hy.quadratic != 0, z, dz, my_y, r, dr, ls);
         if (!my_valid) r = dr = ls = 0.0f;
-        s_res[tid] = make_float2(r, dr);
+        sm.s_res[tid] = make_float2(r, dr);
         lsum = (double)ls;
     }
     __syncthreads();
@@ -133,24 +194,24 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
     // others go on (R is a multiple of 64 or smaller than 64, so such a wave is all rows or wave 0)
     if (wave < (R + kWave - 1) / kWave) {
         lsum = wave_total(lsum);
-        if (lane == 0) s_red[wave] = lsum;
+        if (lane == 0) sm.s_red[wave] = lsum;
     }
     // weighted row sums of the tile, from the registers
     float4 ag = make_float4(0, 0, 0, 0), as = make_float4(0, 0, 0, 0);
 #pragma unroll
     for (int u = 0; u < kTR; ++u) {
-        const float2 w = s_res[wr * kTR + u];
+        const float2 w = sm.s_res[wr * kTR + u];
         ag.x += w.x * x[u].x; ag.y += w.x * x[u].y; ag.z += w.x * x[u].z; ag.w += w.x * x[u].w;
         as.x += w.y * x[u].x; as.y += w.y * x[u].y; as.z += w.y * x[u].z; as.w += w.y * x[u].w;
     }
     if constexpr (WR > 1) {
-        s_acc[0][wave][lane] = ag;
-        s_acc[1][wave][lane] = as;
+        sm.s_acc[0][wave][lane] = ag;
+        sm.s_acc[1][wave][lane] = as;
         __syncthreads();
         if (wr == 0) {
 #pragma unroll
             for (int w = 1; w < WR; ++w) {
-                const float4 p = s_acc[0][w * WC + wc][lane], q = s_acc[1][w * WC + wc][lane];
+                const float4 p = sm.s_acc[0][w * WC + wc][lane], q = sm.s_acc[1][w * WC + wc][lane];
                 ag.x += p.x; ag.y += p.y; ag.z += p.z; ag.w += p.w;
                 as.x += q.x; as.y += q.y; as.z += q.z; as.w += q.w;
             }
@@ -160,11 +221,11 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
         __syncthreads();
         if (tid == 0) {
             double t = 0;
-            for (int w = 0; w < R / kWave; ++w) t += s_red[w];
-            a.part_loss[blockIdx.x] = t;
+            for (int w = 0; w < R / kWave; ++w) t += sm.s_red[w];
+            a.part_loss[tile] = t;
         }
     } else {
-        if (tid == 0) a.part_loss[blockIdx.x] = lsum;
+        if (tid == 0) a.part_loss[tile] = lsum;
     }
     if (wr == 0) {
         if (rb == 0 && hy.l2 != 0.0f) {
@@ -178,11 +239,30 @@ __global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
             as.z = fmaf(ml, dl4.z, as.z); as.w = fmaf(ml, dl4.w, as.w);
         }
         if (col_ok) {
-            const int64_t o = (int64_t)blockIdx.x * hy.p + col;
+            const int64_t o = (int64_t)tile * hy.p + col;
             *(float4*)(a.part_g + o) = ag;
             *(float4*)(a.part_s + o) = as;
         }
     }
+}
+
+// grid: G * RB workgroups, one tile each.
+template <int WC>
+__global__ __launch_bounds__(kThreads) void lr_tile_kernel(TileArgs a)
+{
+    __shared__ TileShared<WC> sm;
+    const int g = blockIdx.x / a.RB, rb = blockIdx.x % a.RB;
+    if (a.hy.sel && !a.hy.sel[g]) {              // unselected group: no gradient, no loss
+        if (threadIdx.x == 0) a.part_loss[blockIdx.x] = 0;
+        return;
+    }
+    const ShardDesc sh = a.shards[g];
+    int my_row;
+    bool my_valid;
+    float4 x[kTR];
+    tile_rows<WC>(a, sm, sh, g, rb, my_row, my_valid);
+    tile_issue<WC>(a, sm, sh, x);
+    tile_finish<WC>(a, sm, sh, g, rb, my_row, my_valid, x, nullptr);
 }
 
 constexpr int kRedBlock = 256;
@@ -272,6 +352,10 @@ struct FinishArgs {
                                  //    gradients (a.mask, a.stat, Ctl::rhs are inputs); only the
                                  //    selected groups left tile partials; no statistic, no exchange
     int prev_kmodD;              // history index the previous launch's ||step||^2 belongs to
+    // when the tiles of the NEXT step run in the same launch (lr_tile_step_kernel): the new iterate
+    // and the groups' stale slots also go out as tagged words (null otherwise)
+    unsigned long long* xtheta;  // [p] {tag, bits of theta^{k+1}_j}
+    unsigned long long* xsel;    // [G] {tag, ring slot of theta^{(k+1) - tau_g^{k+1}}}
     double* stat;
     uint8_t* mask;
     uint8_t* mask_out;
@@ -318,9 +402,12 @@ __device__ __forceinline__ bool tagged_load(const unsigned long long* slot, unsi
     return (unsigned)(lo >> 32) == tag && (unsigned)(hi >> 32) == tag;
 }
 
-// grid: d / (4*CL) blocks of CL * 16 threads; thread = (group lane gl, column lane cl).
-template <int CL>
-__global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishArgs a)
+// The work of one finishing block: CL * 16 threads (tid = 0 .. CL*16-1; thread = (group lane gl,
+// column lane cl)), block blk of S.  Two workgroup barriers; a caller whose workgroup has more
+// threads lets the others execute two barriers of their own.  NFLY: tile partials whose loads are
+// in flight together (they are added in the same order whatever it is).  NCH: 16 * NCH >= G.
+template <int CL, int NFLY, int NCH>
+__device__ __forceinline__ void finish_body(const FinishArgs& a, const int tid, const int blk, const int S)
 {
     constexpr int B = CL * kFinGroups, NW = B / kWave;
     __shared__ float4 s_delta[kFinMaxG][CL];
@@ -331,15 +418,15 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
 
     const Hyper& hy = a.hy;
     Ctl* ctl = a.ctl;
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int wave = tid / kWave, lane = tid % kWave;
     const int gl = tid / CL, cl = tid % CL;
-    const int S = gridDim.x, blk = blockIdx.x, G = hy.G;
+    const int G = hy.G;
     const int64_t j = ((int64_t)blk * CL + cl) * 4;
     const bool jok = j < hy.p;                   // the last block's columns may end early (p % 4 == 0)
     const float* __restrict__ th = a.ring + (int64_t)hy.cur * hy.pstride;
     float* __restrict__ tn = a.ring + (int64_t)hy.nxt * hy.pstride;
 
-    constexpr int NCH = kFinMaxG / kFinGroups;      // passes over the groups (G <= kFinMaxG)
+    // NCH: passes over the groups (G <= 16 * NCH <= kFinMaxG)
     static_assert(4 * CL <= kWave, "the updating threads must sit in wave 0");
 
     // 1. The way to the statistic first -- the other blocks wait for it: tile partials of the
@@ -364,7 +451,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
             const float* ps = a.part_s + (int64_t)g * RB * hy.p + j;
             float4 ag = make_float4(0, 0, 0, 0), as = ag;
             int rb = 0;
-            if (RB >= 16) {                          // sixteen tiles' loads in flight, added in order
+            if (NFLY >= 16 && RB >= 16) {            // sixteen tiles' loads in flight, added in order
                 float4 p[16], q[16];
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
@@ -378,7 +465,7 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
                 }
                 rb = 16;
             }
-            for (; rb + 8 <= RB; rb += 8) {          // eight tiles' loads in flight, added in order
+            for (; NFLY >= 8 && rb + 8 <= RB; rb += 8) {   // eight tiles' loads in flight, added in order
                 float4 p[8], q[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -387,6 +474,19 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
+                    ag.x += p[e].x; ag.y += p[e].y; ag.z += p[e].z; ag.w += p[e].w;
+                    as.x += q[e].x; as.y += q[e].y; as.z += q[e].z; as.w += q[e].w;
+                }
+            }
+            for (; rb + 4 <= RB; rb += 4) {          // four tiles' loads in flight, added in order
+                float4 p[4], q[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    p[e] = *(const float4*)(pg + (int64_t)(rb + e) * hy.p);
+                    q[e] = *(const float4*)(ps + (int64_t)(rb + e) * hy.p);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
                     ag.x += p[e].x; ag.y += p[e].y; ag.z += p[e].z; ag.w += p[e].w;
                     as.x += q[e].x; as.y += q[e].y; as.z += q[e].z; as.w += q[e].w;
                 }
@@ -552,6 +652,12 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
             if (!a.pre) {
                 a.tau[lane] = sel ? 1 : t + 1;
                 if (sel) a.which[lane] = 1 - s_which[lane];
+                // where the group's stale iterate sits in the next step: theta^k after an upload
+                // (age 1 then), the slot it had otherwise
+                if (a.xsel)
+                    __hip_atomic_store(a.xsel + lane,
+                                       ((unsigned long long)a.tag << 32) | (unsigned)(sel ? hy.cur : stale_slot_of(hy, t)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             }
         }
         if (lane == 0) {
@@ -601,6 +707,9 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
         a.h[jc] = hv;
         a.vhat[jc] = vv;
         tn[jc] = nv;
+        if (a.xtheta)
+            __hip_atomic_store(a.xtheta + jc, ((unsigned long long)a.tag << 32) | __float_as_uint(nv), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
     }
     // ||step||^2 and ||theta^{k+1}||^2 stay per block: the next launch (or lr_tile_close_kernel)
     // adds them up, so no block waits for the others here
@@ -643,6 +752,52 @@ __global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishA
     }
 }
 
+// grid: d / (4*CL) blocks of CL * 16 threads.
+template <int CL>
+__global__ __launch_bounds__(CL * kFinGroups) void lr_tile_finish_kernel(FinishArgs a)
+{
+    finish_body<CL, 16, kFinMaxG / kFinGroups>(a, threadIdx.x, blockIdx.x, gridDim.x);
+}
+
+// ---- one launch per step: the finish of step k-1 at the head of the tiles of step k -------------
+//
+// The rows a step reads depend on its row ids only, never on the iterate; what depends on the
+// iterate -- the dot products -- comes after the rows have arrived.  So the finish of the step
+// before (a chain of short memory round trips on a few workgroups) can run while all workgroups
+// wait for their rows: every workgroup requests its tile at once, except the first S, in which
+// four waves run the pending finish first (a wave's loads return in order, so a wave with tile
+// loads in flight could not get through that chain); the new iterate and the groups' stale
+// slots go out as tagged words, and every workgroup picks them up where it needs them.  All
+// workgroups of the grid are resident (checked on the host).
+template <int WC, int NCH>
+__global__ __launch_bounds__(kThreads) void lr_tile_step_kernel(TileArgs a, FinishArgs f, int S)
+{
+    __shared__ TileShared<WC> sm;
+    constexpr int kFinThreads = 16 * kFinGroups;
+    const int tid = threadIdx.x;
+    const int g = blockIdx.x / a.RB, rb = blockIdx.x % a.RB;
+    const ShardDesc sh = a.shards[g];
+    const bool fin_block = (int)blockIdx.x < S;
+    const bool fin_thread = fin_block && tid < kFinThreads;
+    int my_row;
+    bool my_valid;
+    float4 x[kTR];
+    tile_rows<WC>(a, sm, sh, g, rb, my_row, my_valid);
+    // (a finishing workgroup requests its tile after the finish: the tile's registers and the
+    // finish's do not fit a thread together; its 256 KB arrive while the others still stream)
+    if (fin_block) {
+        if (fin_thread) {
+            finish_body<16, 8, NCH>(f, tid, blockIdx.x, S);
+        } else {
+            __syncthreads();
+            __syncthreads();
+        }
+    }
+    tile_issue<WC>(a, sm, sh, x);
+    StepLink link{f.xtheta, f.xsel, f.tag, f.wait, f.ctl};
+    tile_finish<WC>(a, sm, sh, g, rb, my_row, my_valid, x, &link);
+}
+
 // One wave: completes what the last fused finish left per block -- the history entry
 // ||theta^{k+1} - theta^k||^2 (Eq. (9)) and ||theta^{k+1}||^2 -- in the order the next fused launch
 // would have used.
@@ -680,7 +835,49 @@ struct LrTilePlan {
     int fin_pending_kmodD = 0;
     unsigned fin_pending_tag = 0;
     hipStream_t fin_stream = nullptr;
+    // one launch per step (lr_tile_step_kernel): a second set of tile partials (a step's tiles are
+    // written while the finish of the step before reads its own), the words that carry the new
+    // iterate and the stale slots, and the step whose finish is still to run
+    float* part_g2 = nullptr;
+    float* part_s2 = nullptr;
+    unsigned long long* xtheta = nullptr;
+    unsigned long long* xsel = nullptr;
+    bool step_ok = false;       // the shape allows it
+    bool step_pending = false;
+    Hyper pend_hy{};
+    int pend_parity = 0;
+    uint8_t* pend_mask_out = nullptr;
+    float* pend_loss_out = nullptr;
+    hipStream_t pend_stream = nullptr;
 };
+
+// The step kernel for a row width (WC column waves) and a group count (NCH passes of 16 groups).
+typedef void (*StepKernel)(TileArgs, FinishArgs, int);
+template <int WC>
+static StepKernel step_kernel_for(int G)
+{
+    if (G <= kFinGroups) return lr_tile_step_kernel<WC, 1>;
+    if (G <= 2 * kFinGroups) return lr_tile_step_kernel<WC, 2>;
+    return lr_tile_step_kernel<WC, kFinMaxG / kFinGroups>;
+}
+static StepKernel step_kernel(int WC, int G)
+{
+    switch (WC) {
+    case 1: return step_kernel_for<1>(G);
+    case 2: return step_kernel_for<2>(G);
+    case 4: return step_kernel_for<4>(G);
+    case 8: return step_kernel_for<8>(G);
+    default: return step_kernel_for<16>(G);
+    }
+}
+static hipError_t step_kernel_fits(int WC, int G, int grid, int cus, bool* ok)
+{
+    int per_cu = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)step_kernel(WC, G), kThreads, 0);
+    if (e != hipSuccess) return e;
+    *ok = per_cu >= 1 && grid <= cus;            // one workgroup per compute unit: all resident
+    return hipSuccess;
+}
 
 // Decide whether the single-pass kernel applies (d <= 4096, a multiple of 4, so that a tile holds
 // whole rows; lanes past the row's end idle, the last tile of a group may be partly empty) and
@@ -717,6 +914,20 @@ hipError_t lr_tile_plan(gcada_ctx* c)
             if ((e = hipMemset(pl->fin_x, 0, words * 8)) != hipSuccess) return e;    // tag 0: never used
             pl->fin_CL = CL;
             pl->fin_S = S;
+            // one launch per step: the grid must hold the S finishing blocks and be resident at once
+            const int grid = G * pl->RB;
+            bool fits = false;
+            if (grid >= S && (e = step_kernel_fits(WC, G, grid, prop.multiProcessorCount, &fits)) != hipSuccess) return e;
+            if (fits) {
+                if ((e = hipMalloc(&pl->part_g2, n * sizeof(float))) != hipSuccess) return e;
+                if ((e = hipMalloc(&pl->part_s2, n * sizeof(float))) != hipSuccess) return e;
+                const size_t w2 = (size_t)c->hy.pstride + kFinMaxG;
+                if ((e = hipMalloc(&pl->xtheta, w2 * 8)) != hipSuccess) return e;
+                if ((e = hipMemset(pl->xtheta, 0, w2 * 8)) != hipSuccess) return e;       // tag 0: never used
+                pl->xsel = pl->xtheta + c->hy.pstride;
+                c->n_loss_part = std::max(c->n_loss_part, 2 * pl->RB);                    // two sets of loss partials
+                pl->step_ok = true;
+            }
         }
     }
     return hipSuccess;
@@ -728,6 +939,9 @@ void lr_tile_free(gcada_ctx* c)
     if (c->lr_tiles->part_g) (void)hipFree(c->lr_tiles->part_g);
     if (c->lr_tiles->part_s) (void)hipFree(c->lr_tiles->part_s);
     if (c->lr_tiles->fin_x) (void)hipFree(c->lr_tiles->fin_x);
+    if (c->lr_tiles->part_g2) (void)hipFree(c->lr_tiles->part_g2);
+    if (c->lr_tiles->part_s2) (void)hipFree(c->lr_tiles->part_s2);
+    if (c->lr_tiles->xtheta) (void)hipFree(c->lr_tiles->xtheta);
     delete c->lr_tiles;
     c->lr_tiles = nullptr;
 }
@@ -774,15 +988,17 @@ bool lr_tile_finish_applies(const gcada_ctx* c)
     return c->allow_fused_finish && lr_tile_applies(c) && c->lr_tiles->fin_CL != 0;
 }
 
-// Tile reduce + selection + masked innovation sum + server update in one launch; replaces
-// lr_tile_reduce and server_step after lr_tile_gradients.
-hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool preselected, hipStream_t s)
+// Arguments of the finish of the step `hy` describes, over the given tile partials; advances the
+// launch counter (tags, the two sum buffers in turn) and the history bookkeeping.
+static hipError_t finish_args(gcada_ctx* c, const Hyper& hy, const float* part_g, const float* part_s,
+                              const double* part_loss, uint8_t* mask_out, float* loss_out, bool preselected,
+                              hipStream_t s, FinishArgs& a)
 {
     LrTilePlan* pl = c->lr_tiles;
-    FinishArgs a{};
-    a.hy = c->hy; a.part_g = pl->part_g; a.part_s = pl->part_s; a.RB = pl->RB;
-    a.part_loss = c->part_loss; a.n_loss_total = c->n_loss_used;
-    unsigned long long* sums = pl->fin_x + (size_t)2 * c->hy.G * pl->fin_S;
+    a = FinishArgs{};
+    a.hy = hy; a.part_g = part_g; a.part_s = part_s; a.RB = pl->RB;
+    a.part_loss = part_loss; a.n_loss_total = hy.G * pl->RB;
+    unsigned long long* sums = pl->fin_x + (size_t)2 * hy.G * pl->fin_S;
     const unsigned n = pl->fin_launches++;
     a.xstat = pl->fin_x;
     a.xsq = sums + (size_t)(n & 1u) * 4 * pl->fin_S;            // two buffers in turn: the other one
@@ -796,7 +1012,7 @@ hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool
     a.tag_prev = pl->fin_pending_tag;
     a.prev_kmodD = pl->fin_pending_kmodD;
     pl->fin_pending = !preselected;          // the server-side variant closes its history entry itself
-    pl->fin_pending_kmodD = c->hy.kmodD;
+    pl->fin_pending_kmodD = hy.kmodD;
     pl->fin_pending_tag = a.tag;
     pl->fin_stream = s;
     a.stat = c->stat; a.mask = c->mask; a.mask_out = mask_out; a.loss_out = loss_out;
@@ -810,9 +1026,91 @@ hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool
                           (const void*)a.vhat, (const void*)a.ring, (const void*)a.nring,
                           (const void*)a.tau, (const void*)a.ctl})
         if (!q) return hipErrorInvalidValue;
-    if (a.n_loss_total != c->hy.G * pl->RB || (int64_t)pl->fin_S * pl->fin_CL * 4 < c->hy.p || c->hy.p % 4 != 0)
-        return hipErrorInvalidValue;
+    if ((int64_t)pl->fin_S * pl->fin_CL * 4 < hy.p || hy.p % 4 != 0) return hipErrorInvalidValue;
+    return hipSuccess;
+}
+
+// Tile reduce + selection + masked innovation sum + server update in one launch; replaces
+// lr_tile_reduce and server_step after lr_tile_gradients.
+hipError_t lr_tile_finish(gcada_ctx* c, uint8_t* mask_out, float* loss_out, bool preselected, hipStream_t s)
+{
+    LrTilePlan* pl = c->lr_tiles;
+    if (c->n_loss_used != c->hy.G * pl->RB) return hipErrorInvalidValue;
+    FinishArgs a;
+    hipError_t e = finish_args(c, c->hy, pl->part_g, pl->part_s, c->part_loss, mask_out, loss_out, preselected, s, a);
+    if (e != hipSuccess) return e;
     lr_tile_finish_kernel<16><<<pl->fin_S, 16 * kFinGroups, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+// ---- one launch per step ----------------------------------------------------------------------
+bool lr_tile_step_applies(const gcada_ctx* c)
+{
+    return c->allow_deferred_finish && c->rule == GCADA_RULE_GRADIENT_DIFFERENCE && lr_tile_finish_applies(c) &&
+           c->lr_tiles->step_ok;
+}
+
+bool lr_tile_step_pending(const gcada_ctx* c) { return c->lr_tiles && c->lr_tiles->step_pending; }
+
+// Step c->hy.k: its tiles, and -- in the same launch -- the finish of the step before, if that is
+// still to run.  The finish of THIS step runs with the next call (or lr_tile_flush): mask_out and
+// loss_out are written then.
+hipError_t lr_tile_step(gcada_ctx* c, const int32_t* idx, uint8_t* mask_out, float* loss_out, hipStream_t s)
+{
+    LrTilePlan* pl = c->lr_tiles;
+    const int parity = (int)(c->hy.k & 1);
+    const int grid = c->hy.G * pl->RB;
+    TileArgs a{};
+    a.hy = c->hy; a.shards = c->d_shards; a.idx = idx; a.ring = c->ring; a.tau = c->tau;
+    a.part_g = parity ? pl->part_g2 : pl->part_g;
+    a.part_s = parity ? pl->part_s2 : pl->part_s;
+    a.part_loss = c->part_loss + (size_t)parity * grid;
+    a.RB = pl->RB;
+    if (!pl->step_pending) {
+        // nothing to finish: the state is complete, the plain tile kernel reads it
+        switch (pl->WC) {
+        case 1: lr_tile_kernel<1><<<grid, kThreads, 0, s>>>(a); break;
+        case 2: lr_tile_kernel<2><<<grid, kThreads, 0, s>>>(a); break;
+        case 4: lr_tile_kernel<4><<<grid, kThreads, 0, s>>>(a); break;
+        case 8: lr_tile_kernel<8><<<grid, kThreads, 0, s>>>(a); break;
+        default: lr_tile_kernel<16><<<grid, kThreads, 0, s>>>(a); break;
+        }
+    } else {
+        const int pp = pl->pend_parity;
+        FinishArgs f;
+        hipError_t e = finish_args(c, pl->pend_hy, pp ? pl->part_g2 : pl->part_g, pp ? pl->part_s2 : pl->part_s,
+                                   c->part_loss + (size_t)pp * grid, pl->pend_mask_out, pl->pend_loss_out, false, s, f);
+        if (e != hipSuccess) return e;
+        f.xtheta = pl->xtheta;
+        f.xsel = pl->xsel;
+        if (pp == parity || !f.xtheta || grid < pl->fin_S) return hipErrorInvalidValue;
+        step_kernel(pl->WC, c->hy.G)<<<grid, kThreads, 0, s>>>(a, f, pl->fin_S);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    pl->step_pending = true;
+    pl->pend_hy = c->hy;
+    pl->pend_parity = parity;
+    pl->pend_mask_out = mask_out;
+    pl->pend_loss_out = loss_out;
+    pl->pend_stream = s;
+    return hipSuccess;
+}
+
+// Run the finish that is still to come (on `s`, or on the stream of its step when use_step_stream).
+hipError_t lr_tile_flush(gcada_ctx* c, hipStream_t s, bool use_step_stream)
+{
+    LrTilePlan* pl = c->lr_tiles;
+    if (!pl || !pl->step_pending) return hipSuccess;
+    if (use_step_stream) s = pl->pend_stream;
+    const int pp = pl->pend_parity;
+    const int grid = pl->pend_hy.G * pl->RB;
+    FinishArgs f;
+    hipError_t e = finish_args(c, pl->pend_hy, pp ? pl->part_g2 : pl->part_g, pp ? pl->part_s2 : pl->part_s,
+                               c->part_loss + (size_t)pp * grid, pl->pend_mask_out, pl->pend_loss_out, false, s, f);
+    if (e != hipSuccess) return e;
+    pl->step_pending = false;
+    lr_tile_finish_kernel<16><<<pl->fin_S, 16 * kFinGroups, 0, s>>>(f);
     return hipGetLastError();
 }
 
@@ -834,7 +1132,10 @@ hipError_t lr_tile_close(gcada_ctx* c, hipStream_t s, bool use_step_stream)
 // The state was replaced from outside: nothing of the last fused finish is pending any more.
 void lr_tile_forget(gcada_ctx* c)
 {
-    if (c->lr_tiles) c->lr_tiles->fin_pending = false;
+    if (c->lr_tiles) {
+        c->lr_tiles->fin_pending = false;
+        c->lr_tiles->step_pending = false;       // (its mask and loss are never written)
+    }
 }
 
 }  // namespace gcada

@@ -89,6 +89,7 @@ def test_side_stream_run_matches_default_stream(cfg, kw):
     ("lr_small", dict(widths=(64,), mu=32, G=3, rows=512, D=5), "lr_micro"),        # one-launch kernel: workgroup 0 collects
     ("lr_4k", dict(widths=(2048,), mu=64, G=4, rows=256, D=5), "lr_tile"),          # fused finish: its blocks meet once
     ("lr_64k", dict(widths=(8192,), mu=48, G=5, rows=100, D=5), "lr_team"),         # team kernel: members exchange partial dots
+    ("lr_4k", dict(widths=(2048,), mu=64, G=20, rows=256, D=5), "one launch per step"),   # tiles wait for the finish of the step before
 ])
 def test_a_wait_that_gives_up_is_reported_by_the_next_step(cfg, kw, kernel):
     # the kernels whose workgroups wait for each other bound that wait.  Here the host makes the
@@ -107,12 +108,17 @@ def test_a_wait_that_gives_up_is_reported_by_the_next_step(cfg, kw, kernel):
         return B.lib.gcada_step(gpu.ctx, idx[k].contiguous().data_ptr(), mask.data_ptr(), loss.data_ptr(), None)
 
     gpu = _mk(w)
-    assert kernel in B.gcada_timed_stage(gpu.ctx)
+    if kernel == "one launch per step":
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_DEFERRED_FINISH, 1)
+    else:
+        assert kernel in B.gcada_timed_stage(gpu.ctx)
     gpu.set_shards(Xs, ys)
     gpu.set_theta(make_theta0(w))
     assert raw_step(gpu, 0) == B.GCADA_OK and raw_step(gpu, 1) == B.GCADA_OK
     torch.cuda.synchronize()
     good = gpu.get_state()
+    if kernel == "one launch per step":
+        assert raw_step(gpu, 5) == B.GCADA_OK        # (leaves a finish to come: the next launch carries it and waits for it)
     B.gcada_set_option(gpu.ctx, B.GCADA_OPT_EXPIRE_NEXT_WAIT, 1)
     assert raw_step(gpu, 2) == B.GCADA_OK            # launched; its waits give up on the device
     torch.cuda.synchronize()                          # the step has finished (normally: nothing hangs)
@@ -132,6 +138,8 @@ def test_a_wait_that_gives_up_is_reported_by_the_next_step(cfg, kw, kernel):
     a = gpu.get_state()
     gpu.close()
     fresh = _mk(w)
+    if kernel == "one launch per step":
+        B.gcada_set_option(fresh.ctx, B.GCADA_OPT_DEFERRED_FINISH, 1)
     fresh.set_shards(Xs, ys)
     fresh.set_theta(make_theta0(w))
     fresh.set_state(**good)

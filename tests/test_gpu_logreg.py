@@ -319,3 +319,72 @@ def test_lr_64k_full_step_shape(par, c, D, steps):
     assert worst["state_steps"] == steps
     if c > 1e20:
         assert worst["forced_late"] == w.G and worst["by_statistic"] == 0 and worst["max_age"] == D
+
+
+@pytest.mark.parametrize("d,mu,G,l2,applies", [
+    (4096, 256, 16, 1e-4, True),    # the benchmark's step shape: 256 workgroups, 64 of them finish the step before
+    (2048, 64, 40, 0.0, True),      # 80 workgroups, three passes over the groups in the finish
+    (1024, 256, 8, 1e-3, True),     # 32 workgroups, 16 finishing
+    (4096, 256, 4, 0.0, True),      # as many workgroups as finishing blocks
+    (784, 128, 5, 1e-4, False),     # fewer tiles than finishing blocks: the option changes nothing
+])
+def test_lr_one_launch_per_step_matches_two_launches(par, d, mu, G, l2, applies):
+    # GCADA_OPT_DEFERRED_FINISH: the finish of step k at the head of the launch of step k+1 (the new
+    # iterate reaches the tiles through tagged words).  Same additions in the same order: masks,
+    # losses and the whole state are bit-identical to the tile kernel + fused finish; a state
+    # query in the middle (which runs the finish that is still to come) changes nothing
+    from paper_2201_04301_amd import Gcada, binding as B
+    from gcada_inputs import make_theta0
+    w = scaled(CONFIGS["lr_small"], name="one_launch", widths=(d,), mu=mu, G=G, rows=400, l2=l2, c=0.5,
+               D=5, flip=0.05)
+    _say("case", w)
+    Xs, ys = make_shards(w, "cuda")
+    steps = 31
+    idx = torch.as_tensor(make_indices(w, steps), device="cuda")
+    res = []
+    for deferred in (0, 1):
+        gpu = Gcada.from_workload(w)
+        B.gcada_set_option(gpu.ctx, B.GCADA_OPT_DEFERRED_FINISH, deferred)
+        gpu.set_shards(Xs, ys)
+        gpu.set_theta(make_theta0(w))
+        masks = torch.zeros(steps, w.G, dtype=torch.uint8, device="cuda")
+        losses = torch.zeros(steps, dtype=torch.float32, device="cuda")
+        mid = None
+        for k in range(steps):
+            gpu.step(idx[k].contiguous(), mask_out=masks[k], loss_out=losses[k:k + 1])
+            if k == 12:
+                mid = gpu.get_state()          # runs the pending finish; the next step starts afresh
+        out = gpu.outputs()
+        st = gpu.get_state()
+        res.append((masks.cpu().numpy(), losses.cpu().numpy(), st, out, mid))
+        gpu.close()
+    (m0, l0, s0, o0, mid0), (m1, l1, s1, o1, mid1) = res
+    assert 0 < m0.sum() < m0.size
+    np.testing.assert_array_equal(m1, m0)
+    np.testing.assert_array_equal(l1, l0)
+    for name in ("theta", "h", "vhat", "agg", "theta_stale", "last", "tau"):
+        np.testing.assert_array_equal(s1[name], s0[name], err_msg=name)
+        np.testing.assert_array_equal(mid1[name], mid0[name], err_msg="mid-run " + name)
+    assert s1["k"] == s0["k"] == steps and mid1["k"] == mid0["k"] == 13
+    np.testing.assert_allclose(s1["dtheta_sq"], s0["dtheta_sq"], rtol=1e-12)
+    np.testing.assert_array_equal(o1["stat"], o0["stat"])
+    assert o1["rhs"] == o0["rhs"]
+    np.testing.assert_array_equal(o1["grad"], o0["grad"])
+
+
+def test_lr_one_launch_per_step_teacher_forced_against_the_oracle(par):
+    # the same path against the oracle, step by step (every step ends with a state query, so each
+    # launch here is a plain tile launch followed by the stand-alone finish) and on its own for a
+    # run of 40 steps (every launch but the first carries the finish of the step before)
+    from paper_2201_04301_amd import binding as B
+    w = scaled(CONFIGS["lr_4k"], rows=1024, c=0.5)
+    Xs, ys = make_shards(w, "cuda")
+    idx = make_indices(w, 40)
+    worst = par.teacher_forced(w, 8, Xs, ys, idx, options=((B.GCADA_OPT_DEFERRED_FINISH, 1),))
+    _say(worst)
+    r = par.free_running(w, 40, Xs, ys, idx, options=((B.GCADA_OPT_DEFERRED_FINISH, 1),))
+    agree = (r["masks_gpu"] == r["masks_oracle"]).mean()
+    _say("mask agreement", agree, "loss", r["loss_gpu"][0], "->", r["loss_gpu"][-1], r["loss_oracle"][-1])
+    assert agree >= 0.98
+    np.testing.assert_allclose(r["loss_gpu"], r["loss_oracle"], rtol=2e-3)
+    np.testing.assert_allclose(r["theta_gpu"], r["theta_oracle"], rtol=0, atol=2e-3 * np.abs(r["theta_oracle"]).max())

@@ -377,7 +377,7 @@ def main():
     # 8 GiB, best of its launch shapes): the ceiling the HBM-bound kernels are held against
     buf = torch.empty(8 << 30, dtype=torch.uint8, device="cuda")
     buf.zero_()
-    hbm_read = B.gcada_hbm_read_calibration(buf.data_ptr(), buf.numel(), 5, stream)
+    hbm_read, hbm_read_plain = B.gcada_hbm_read_calibration(buf.data_ptr(), buf.numel(), 3, stream)
     del buf
     torch.cuda.empty_cache()
 
@@ -389,7 +389,8 @@ def main():
                 details[name] = run_config(CONFIGS[name], SIDE_STEPS[name], W, args.repeats, args, cpu_info, False)
 
     w = CONFIGS[args.workload]
-    head["roofline"]["hbm_read_achievable_gbs"] = round(hbm_read, 1)
+    head["roofline"]["hbm_read_achievable_gbs"] = round(hbm_read, 1)            # non-temporal loads (as the kernel's)
+    head["roofline"]["hbm_read_achievable_plain_loads_gbs"] = round(hbm_read_plain, 1)
     # per configuration (short keys keep the line small): iterations/s, gradient evaluations/s
     # (2 G per iteration), ms per step, the dominant stage and its ms, its fraction of the peak
     # (executed flops for the MLPs; "frac_alg": by the algorithmic flop count), the whole step's

@@ -340,13 +340,15 @@ const char* gcada_timed_stage(gcada_ctx* ctx);
  * Diagnostic for benchmarks, next to the roofline of the HBM-bound kernels of step a1: the rate, in
  * GB/s (1e9 bytes per second), at which this device reads `bytes` of contiguous device memory
  * [device, 16-byte aligned, at least 64 MiB; use far more than the 256 MB of last-level cache] with
- * a plain streaming kernel -- the best of a fixed set of launch shapes (2 to 64 workgroups per
- * compute unit, 256 to 1024 threads, 8 or 16 loads of 16 bytes in flight per thread), `reps`
- * launches each between two HIP events.  Needs no context.  Synchronises the stream; allocates one
- * word and two events.  Errors: GCADA_EINVAL, GCADA_EDEVICE (message under the NULL context).
+ * a plain streaming kernel -- the best of a fixed set of launch shapes (1 to 16 workgroups per
+ * compute unit, 256 to 1024 threads, 8 or 16 loads of 16 bytes in flight per thread, ordinary or
+ * non-temporal loads), `reps` launches each between two HIP events.  gbps_plain_loads (may be
+ * NULL): the best of the shapes with ordinary loads alone.  Needs no context.  Synchronises the
+ * stream; allocates one word and two events.  Errors: GCADA_EINVAL, GCADA_EDEVICE (message under
+ * the NULL context).
  */
 int gcada_hbm_read_calibration(const void* buf /*[device]*/, int64_t bytes, int32_t reps, void* stream,
-                               double* gbps /*[host]*/);
+                               double* gbps /*[host]*/, double* gbps_plain_loads /*[host]*/);
 
 /* Message of the last error on this context ("" if none); NULL ctx: last gcada_create error. */
 const char* gcada_last_error(const gcada_ctx* ctx);

@@ -97,7 +97,8 @@ def _load():
     L.gcada_estimate_smoothness_static.restype = C.c_int
     L.gcada_estimate_smoothness_static.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     L.gcada_hbm_read_calibration.restype = C.c_int
-    L.gcada_hbm_read_calibration.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
+    L.gcada_hbm_read_calibration.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.POINTER(C.c_double),
+                                             C.POINTER(C.c_double)]
     L.gcada_set_option.restype = C.c_int
     L.gcada_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.gcada_timed_stage.restype = C.c_char_p
@@ -216,7 +217,8 @@ def gcada_estimate_smoothness_static(ctx, iters: int, L_out_dev_ptr, stream):
     _check(lib.gcada_estimate_smoothness_static(ctx, iters, L_out_dev_ptr, stream), ctx)
 
 
-def gcada_hbm_read_calibration(buf_ptr, nbytes: int, reps: int, stream=None) -> float:
-    g = C.c_double()
-    _check(lib.gcada_hbm_read_calibration(buf_ptr, nbytes, reps, stream, C.byref(g)))
-    return g.value
+def gcada_hbm_read_calibration(buf_ptr, nbytes: int, reps: int, stream=None):
+    """(best GB/s over all launch shapes and load kinds, best GB/s with ordinary loads)."""
+    g, gp = C.c_double(), C.c_double()
+    _check(lib.gcada_hbm_read_calibration(buf_ptr, nbytes, reps, stream, C.byref(g), C.byref(gp)))
+    return g.value, gp.value

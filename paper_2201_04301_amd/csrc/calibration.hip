@@ -13,7 +13,7 @@ typedef float cal_f32x4 __attribute__((ext_vector_type(4)));
 
 // Every block walks chunks of blockDim.x * U consecutive 16-byte words, grid-strided; U loads per
 // thread are in flight at once.  The sum keeps the loads alive; it is never stored in practice.
-template <int U>
+template <int U, bool NT>
 __global__ void stream_read_kernel(const cal_f32x4* __restrict__ p, size_t n16, float* __restrict__ sink)
 {
     const size_t chunk = (size_t)blockDim.x * U;
@@ -23,22 +23,25 @@ __global__ void stream_read_kernel(const cal_f32x4* __restrict__ p, size_t n16, 
         const cal_f32x4* q = p + c * chunk + threadIdx.x;
         cal_f32x4 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = *(const __attribute__((address_space(1))) cal_f32x4*)(q + (size_t)u * blockDim.x);
+        for (int u = 0; u < U; ++u) {
+            const auto* g = (const __attribute__((address_space(1))) cal_f32x4*)(q + (size_t)u * blockDim.x);
+            v[u] = NT ? __builtin_nontemporal_load(g) : *g;       // non-temporal: streams past the caches
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) acc += v[u];
     }
     if (acc.x + acc.y + acc.z + acc.w == 12345.678f) *sink = acc.x;     // (never true for the buffers used)
 }
 
-template <int U>
+template <int U, bool NT>
 hipError_t time_shape(const void* buf, size_t bytes, int blocks, int threads, int reps, float* sink, hipStream_t s,
                       hipEvent_t e0, hipEvent_t e1, double* gbps)
 {
     const size_t n16 = bytes / 16;
-    stream_read_kernel<U><<<blocks, threads, 0, s>>>((const cal_f32x4*)buf, n16, sink);     // warm-up
+    stream_read_kernel<U, NT><<<blocks, threads, 0, s>>>((const cal_f32x4*)buf, n16, sink);     // warm-up
     hipError_t e = hipEventRecord(e0, s);
     for (int r = 0; r < reps && e == hipSuccess; ++r) {
-        stream_read_kernel<U><<<blocks, threads, 0, s>>>((const cal_f32x4*)buf, n16, sink);
+        stream_read_kernel<U, NT><<<blocks, threads, 0, s>>>((const cal_f32x4*)buf, n16, sink);
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipEventRecord(e1, s);
@@ -55,7 +58,8 @@ hipError_t time_shape(const void* buf, size_t bytes, int blocks, int threads, in
 
 }  // namespace
 
-hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStream_t s, double* best_gbps)
+hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStream_t s, double* best_gbps,
+                                double* best_plain_gbps)
 {
     hipEvent_t e0, e1;
     hipError_t e = hipEventCreate(&e0);
@@ -69,19 +73,23 @@ hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStre
     int dev = 0, cus = 256;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
-    double best = 0;
+    double best = 0, best_plain = 0;
     for (int threads : {256, 512, 1024})
-        for (int per_cu : {2, 4, 8, 16, 64}) {
-            double g8 = 0, g16 = 0;
-            if ((e = time_shape<8>(buf, bytes, cus * per_cu, threads, reps, sink, s, e0, e1, &g8)) != hipSuccess) break;
-            if ((e = time_shape<16>(buf, bytes, cus * per_cu, threads, reps, sink, s, e0, e1, &g16)) != hipSuccess) break;
-            best = std::max(best, std::max(g8, g16));
+        for (int per_cu : {1, 2, 4, 16}) {
+            double g8 = 0, g16 = 0, n8 = 0, n16 = 0;
+            if ((e = time_shape<8, false>(buf, bytes, cus * per_cu, threads, reps, sink, s, e0, e1, &g8)) != hipSuccess) break;
+            if ((e = time_shape<16, false>(buf, bytes, cus * per_cu, threads, reps, sink, s, e0, e1, &g16)) != hipSuccess) break;
+            if ((e = time_shape<8, true>(buf, bytes, cus * per_cu, threads, reps, sink, s, e0, e1, &n8)) != hipSuccess) break;
+            if ((e = time_shape<16, true>(buf, bytes, cus * per_cu, threads, reps, sink, s, e0, e1, &n16)) != hipSuccess) break;
+            best_plain = std::max(best_plain, std::max(g8, g16));
+            best = std::max(best, std::max(std::max(g8, g16), std::max(n8, n16)));
         }
     (void)hipFree(sink);
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (e != hipSuccess) return e;
     *best_gbps = best;
+    if (best_plain_gbps) *best_plain_gbps = best_plain;
     return hipSuccess;
 }
 

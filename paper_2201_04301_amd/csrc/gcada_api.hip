@@ -673,12 +673,13 @@ try {
     return fail(ctx, GCADA_ENOMEM, "unexpected exception in gcada_time_gradient_stage");
 }
 
-int gcada_hbm_read_calibration(const void* buf, int64_t bytes, int32_t reps, void* stream, double* gbps)
+int gcada_hbm_read_calibration(const void* buf, int64_t bytes, int32_t reps, void* stream, double* gbps,
+                               double* gbps_plain_loads)
 {
     if (!buf || !gbps || reps < 1 || bytes < ((int64_t)64 << 20) || ((uintptr_t)buf % 16))
         return fail(nullptr, GCADA_EINVAL, "hbm_read_calibration: a 16-byte aligned device buffer of at least 64 MiB, reps >= 1 and an output are required");
     double g = 0;
-    hipError_t e = gcada::hbm_read_calibration(buf, (size_t)bytes, reps, (hipStream_t)stream, &g);
+    hipError_t e = gcada::hbm_read_calibration(buf, (size_t)bytes, reps, (hipStream_t)stream, &g, gbps_plain_loads);
     if (e != hipSuccess) return fail_hip(nullptr, e, "hbm_read_calibration");
     *gbps = g;
     return GCADA_OK;

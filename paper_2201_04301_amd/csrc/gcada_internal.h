@@ -289,7 +289,8 @@ hipError_t rule_smoothness_static(gcada_ctx* c, int iters, double* L_out_dev, hi
 hipError_t pick_fastest_workers(gcada_ctx* c, const int32_t* idx_workers, const double* delays,
                                 int32_t* worker_out, hipStream_t s);
 // plain contiguous read of `bytes` of device memory, best of a few launch shapes, in GB/s (calibration.hip)
-hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStream_t s, double* best_gbps);
+hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStream_t s, double* best_gbps,
+                                double* best_plain_gbps);
 // ||theta^k||^2 of the current slot -> Ctl::theta_sq (after set_theta / set_state)
 hipError_t refresh_theta_sq(gcada_ctx* c, hipStream_t s);
 

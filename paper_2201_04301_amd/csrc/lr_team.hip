@@ -34,7 +34,7 @@ namespace {
 
 constexpr int kDataWaves = 8;
 constexpr int kDataThreads = kDataWaves * 64;
-constexpr int kThreads = kDataThreads + 64;   // plus the control wave
+constexpr int kThreads = kDataThreads + 128;  // plus the exchange wave and the publisher wave
 constexpr int kV = 2;                    // float4 per row and thread, 256 columns apart
 constexpr int kR = 4;                    // rows per tile
 constexpr int kSlab = 4096;              // columns per member
@@ -43,7 +43,9 @@ constexpr int kRegTiles = 3;             // register tiles per thread: multiplie
 constexpr int kPartial = 2 * kR;         // values a member publishes per tile
 constexpr int kSlotBytes = kPartial * 8; // per member and slot
 constexpr int kParkBytes = 2 * kR * kV * kDataThreads * 16;   // two parked tiles: 131072
-constexpr int kLabelRing = 8;            // labels of tiles t-2 .. t+2 are live
+// the control wave's lane layouts: (value, data wave) = (lane / 8, lane % 8) when it adds the
+// waves' partial dots, (row, member) = (lane / 16, lane % 16) when it adds the members' partials
+static_assert(kR == 4 && kPartial == 8 && kDataWaves == 8, "lane layouts of the control wave");
 
 // A pair {value, tag} of the exchange buffer travels as one 64-bit word.  Relaxed atomic
 // accesses at system scope: the hardware goes past the non-coherent L2s (sc0 sc1), and the
@@ -115,9 +117,8 @@ struct TeamSeq {
 };
 
 struct TeamLds {
-    float s_dot[2][kDataWaves][kPartial];   // per-wave partial dots, by parity of the tile
+    float4 s_dot[2][kDataWaves][kPartial];  // per-wave partial dots (one per 16-lane row), by parity of the tile
     float2 s_res[2][kR];                    // residuals (r, dr), by parity of the stage
-    float s_y[kLabelRing][kR];              // labels by tile mod 8 (control wave only)
     double s_red[kDataWaves];
 };
 
@@ -191,32 +192,36 @@ __device__ __forceinline__ void team_load_tile(TeamRegs& R, const TeamSeq& S, co
     }
 }
 
-// Row id of row `lane` (< kR) of the tile S.gF/S.tF point at (a load when ids are given), and the
-// label of that row.  The two are split so that the id can be requested a stage before the label.
-__device__ __forceinline__ int team_label_row(const TeamArgs& a, const TeamSeq& S, int lane)
+// A position in the team's tile sequence: group and tile within the group.
+struct TeamCursor {
+    int g, t;
+};
+// Move the cursor on to tile nF of the sequence (one step per stage); past the end of the sequence
+// it stays on the last tile.
+__device__ __forceinline__ void team_cursor_advance(const TeamArgs& a, TeamCursor& c, int ntile, int ntot, int nF)
+{
+    if (nF < ntot && nF > 0) {
+        if (++c.t == ntile) { c.t = 0; c.g = team_next_group(a.hy, c.g, a.NT); }
+    }
+}
+// Row id of row `prow` of the tile the cursor points at (a load when ids are given), and the label
+// of a row of a group's shard; for the exchange wave, one row per 16 lanes.
+__device__ __forceinline__ int team_row_id(const TeamArgs& a, const TeamCursor& c, int prow)
 {
     typedef const ShardDesc __attribute__((address_space(4))) const_shard;
-    const int i = min(S.tF * kR + lane, a.hy.mu - 1);
-    if (a.idx) return a.idx[(int64_t)S.gF * a.hy.mu + i];
-    const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
+    const int i = min(c.t * kR + prow, a.hy.mu - 1);     // a row past the minibatch repeats the last one
+    if (a.idx) return global_load(a.idx + (int64_t)c.g * a.hy.mu + i);
+    const_shard* sh = (const_shard*)(uintptr_t)a.shards + c.g;
     const unsigned rows = (unsigned)sh->rows;
     const unsigned cyc_base = (unsigned)((((unsigned long long)a.hy.k % rows) *
                                           ((unsigned long long)a.hy.mu % rows)) % rows);
     return (int)((cyc_base + (unsigned)i) % rows);
 }
-__device__ __forceinline__ float team_label_of(const TeamArgs& a, const TeamSeq& S, int row)
+__device__ __forceinline__ float team_label(const TeamArgs& a, int g, int row)
 {
     typedef const ShardDesc __attribute__((address_space(4))) const_shard;
-    const_shard* sh = (const_shard*)(uintptr_t)a.shards + S.gF;
+    const_shard* sh = (const_shard*)(uintptr_t)a.shards + g;
     return global_load((const float*)sh->y + row);
-}
-
-// Move S.gF/S.tF on to tile nF (the control wave's share of team_fetch).
-__device__ __forceinline__ void team_advance(const TeamArgs& a, TeamSeq& S, int nF, int NT)
-{
-    if (nF < S.ntot && nF > 0) {
-        if (++S.tF == S.ntile) { S.tF = 0; S.gF = team_next_group(a.hy, S.gF, NT); }
-    }
 }
 
 // theta^k - theta_stale of group g at this thread's columns
@@ -264,8 +269,9 @@ __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, 
             v[2 * u] = s0;
             v[2 * u + 1] = s1;
         }
-        Butterfly<kPartial, 32>::run(v, lane);       // lanes 8e hold value e
-        if ((lane & 7) == 0) L.s_dot[n & 1][wave][lane >> 3] = v[0];
+        RowButterfly<kPartial>::run(v, lane);        // sums over the 16 lanes of a row, no LDS traffic
+        if ((lane & 1) == 0)
+            ((float*)&L.s_dot[n & 1][wave][row_butterfly_first<kPartial>(lane)])[lane >> 4] = v[0];
     }
     __syncthreads();
 
@@ -330,64 +336,61 @@ __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, 
     }
 }
 
-// What the control wave carries from one stage to the next.
+// What the exchange wave carries from one stage to the next.
 struct TeamCtl {
-    int row_next;                 // row id whose label is requested in stage n (tile n+2; lane < kR)
-    float y_new;                  // label requested in stage n-1 (tile n+1; lane < kR)
+    // per lane, for its row (lane / 16) of a tile, in rings indexed by tile mod 3: at the start of
+    // stage n the labels of tiles n-1, n, n+1 and the row ids of tiles n+2, n+3, n+4
+    float y[kRegTiles];
+    int id[kRegTiles];
+    TeamCursor c2, c5;            // tiles n+2 (whose labels are requested in stage n) and n+5 (row ids)
     int gR, tR;                   // group and tile-in-group of the tile whose residuals are formed next
+    int gA, tA;                   // the same for the tile the data waves add in this stage (n-2)
     bool gave_up;                 // a bounded wait was exhausted
     double lacc, lacc_prev;       // loss sums: of the group whose residuals are being formed, of the one before
 };
 
-// One pipeline stage of the CONTROL wave.  It loads no tiles, so its poll of the exchange buffer
-// and its label loads never queue behind tile loads of its own.  Its path is the longest of the
-// workgroup (a round trip to the exchange words takes 1.5 us under load, as long as the data
-// waves' whole share of a stage), so nothing on it may hold up the barrier: in stage n it
-//   [A] requests the words of tile n-1 (every member published them after its barrier of stage
-//       n-1, about a stage ago) and the next label, then joins the barrier of stage n at once;
-//   [B] adds the data waves' partial dots of tile n and publishes them -- the other members wait
-//       for these, two stages from now;
-//   [C] forms the residuals of tile n-1 from the words requested in [A], for the data waves to
-//       use after the barrier of stage n+1.
-__device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S, unsigned long long* xt,
-                                                   int n, int m, TeamCtl& K, TeamLds& L)
+// Two waves besides the data waves, neither of which loads tiles (a wave's loads return in order:
+// a poll behind tile loads would wait for them).
+//
+// The EXCHANGE wave collects: in stage n it requests the other members' words of tile n-1 (every
+// member published them right after its barrier of stage n-1) as soon as it is done with stage
+// n-1, joins the barrier of stage n, and then forms the residuals of tile n-1, which the data
+// waves use after the barrier of stage n+1.  The round trip to the words (well over a
+// microsecond while the tiles stream) thus runs while the wave waits at the barrier, and nothing
+// the wave does in front of a barrier waits for a load.  Its other loads -- the label of its row
+// of tile n+2 and the row id of tile n+5, three stages ahead of their use each -- are requested
+// AFTER the words have arrived and are older than the next stage's polls, so waiting for those
+// polls never waits for anything else.  It stores nothing to global memory inside the loop: a
+// wave with a store in flight cannot tell which of its loads have returned.
+//
+// The PUBLISHER wave adds the data waves' partial dots of tile n after the barrier of stage n and
+// publishes them; it only ever stores.
+template <int J>
+__device__ __forceinline__ void team_exchange_stage(const TeamArgs& a, unsigned long long* xt, int n, int m,
+                                                    int ntile, int ntot, TeamCtl& K, TeamLds& L)
 {
+    constexpr int JR = (J + 2) % kRegTiles;                   // ring slot of tiles n-1 and n+2
     const int lane = threadIdx.x % kWave;
-    const bool have_cur = n < S.ntot, have_add = n >= 2 && n - 2 < S.ntot;
-    const bool have_res = n >= 1 && n - 1 < S.ntot;          // tile n-1 exists
-    const bool poller = lane < a.TS * kR;
+    const bool have_add = n >= 2 && n - 2 < ntot;
+    const bool have_res = n >= 1 && n - 1 < ntot;             // tile n-1 exists
+    const int prow = lane >> 4, pmem = lane & 15;             // the (row, member) whose pairs this lane polls
+    const bool poller = pmem < a.TS;
 
-    // [A] lane l polls member l/4's pairs (z, dz) of row l%4 of tile n-1: slot (n-1) mod 4
-    const unsigned long long* mine = xt + (int)(((unsigned)n + 3u) % kSlots) * a.TS * kPartial + lane * 2;
+    // lane l requests member l%16's pairs (z, dz) of row l/16 of tile n-1: slot (n-1) mod 4
+    const unsigned long long* mine =
+        xt + (int)(((unsigned)n + 3u) % kSlots) * a.TS * kPartial + pmem * kPartial + prow * 2;
     unsigned long long pz = 0, pdz = 0;
     if (poller && have_res) {
         pz = pair_load(mine);
         pdz = pair_load(mine + 1);
     }
-    if (lane < kR) {
-        L.s_y[(n + 1) % kLabelRing][lane] = K.y_new;         // label of tile n+1, requested a stage ago
-        K.y_new = team_label_of(a, S, K.row_next);            // S points at tile n+2, and so does row_next
-    }
-    team_advance(a, S, n + 3, a.NT);
-    if (lane < kR) K.row_next = team_label_row(a, S, lane);   // tile n+3
     __syncthreads();
 
-    // [B]
-    if (have_cur) {
-        // member partial: lane l adds value l%8 over the data waves in a fixed tree
-        float w = L.s_dot[n & 1][lane >> 3][lane & 7];
-#pragma unroll
-        for (int o = 8; o < kWave; o <<= 1) w += __shfl_xor(w, o, kWave);
-        if (lane < kPartial)
-            pair_store(xt + ((n % kSlots) * a.TS + m) * kPartial + lane, w, a.tag_base + (unsigned)n);
-    }
-
-    // [C]
     if (have_res) {
         const unsigned want = a.tag_base + a.wait.tag_skew + (unsigned)n - 1u;
         bool ok = !poller || (pair_tag(pz) == want && pair_tag(pdz) == want);
         unsigned spins = 0;
-        while (!K.gave_up && !__all(ok)) {       // rare: a member is more than a tile behind
+        while (!K.gave_up && !__all(ok)) {       // a member's words were not there yet: ask again
             if (poller && !ok) {
                 pz = pair_load(mine);
                 pdz = pair_load(mine + 1);
@@ -398,40 +401,71 @@ __device__ __forceinline__ void team_control_stage(const TeamArgs& a, TeamSeq& S
                 K.gave_up = true;
             }
         }
-        // lane l holds member l/4's partial (z, dz) of row l%4: add the members in a fixed tree
-        float z = poller ? pair_value(pz) : 0.0f;
-        float dz = poller ? pair_value(pdz) : 0.0f;
-#pragma unroll
-        for (int o = kR; o < kWave; o <<= 1) {
-            z += __shfl_xor(z, o, kWave);
-            dz += __shfl_xor(dz, o, kWave);
-        }
+        // lane l holds member l%16's partial (z, dz) of row l/16: add the members of a row in a
+        // fixed tree; every lane of the row gets the sums and forms the row's residuals
+        const float z = row_total(poller ? pair_value(pz) : 0.0f);
+        const float dz = row_total(poller ? pair_value(pdz) : 0.0f);
         if (K.tR == 0) { K.lacc_prev = K.lacc; K.lacc = 0; }         // a new group begins
-        if (lane < kR) {
-            float r, dr, ls;
-            residuals(a.hy.quadratic != 0, z, dz, L.s_y[(n - 1) % kLabelRing][lane], r, dr, ls);
-            if (K.tR * kR + lane >= a.hy.mu) r = dr = ls = 0.0f;      // row past the minibatch
-            L.s_res[(n + 1) & 1][lane] = make_float2(r, dr);
+        float r, dr, ls;
+        residuals(a.hy.quadratic != 0, z, dz, K.y[JR], r, dr, ls);
+        if (K.tR * kR + prow >= a.hy.mu) r = dr = ls = 0.0f;          // row past the minibatch
+        if (pmem == 0) {
+            L.s_res[(n + 1) & 1][prow] = make_float2(r, dr);
             K.lacc += (double)ls;
         }
-        if (++K.tR == S.ntile) { K.tR = 0; K.gR = team_next_group(a.hy, K.gR, a.NT); }
+        if (++K.tR == ntile) { K.tR = 0; K.gR = team_next_group(a.hy, K.gR, a.NT); }
     }
+    // the label of tile n+2 (its row id came three stages ago) and the row id of tile n+5 take the
+    // ring slots that tile n-1 has just left
+    K.y[JR] = team_label(a, K.c2.g, K.id[JR]);
+    K.id[JR] = team_row_id(a, K.c5, prow);
+    team_cursor_advance(a, K.c2, ntile, ntot, n + 3);
+    team_cursor_advance(a, K.c5, ntile, ntot, n + 6);
+
     if (have_add) {
-        if (S.tA == S.ntile - 1) {
+        if (K.tA == ntile - 1) {
             __syncthreads();                     // the data waves' barrier at the end of a group
-            // tile n-2 closed group S.gA; if there is a tile n-1 it opened the next group
-            double l = lane < kR ? (have_res ? K.lacc_prev : K.lacc) : 0.0;
+            // tile n-2 closed group K.gA; if there is a tile n-1 it opened the next group
+            double l = pmem == 0 ? (have_res ? K.lacc_prev : K.lacc) : 0.0;
             l = wave_sum(l);
-            if (m == 0 && lane == 0) a.part_loss[S.gA] = l;
-            S.tA = 0;
-            S.gA = team_next_group(a.hy, S.gA, a.NT);
+            if (m == 0 && lane == 0) a.part_loss[K.gA] = l;
+            K.tA = 0;
+            K.gA = team_next_group(a.hy, K.gA, a.NT);
         } else {
-            ++S.tA;
+            ++K.tA;
         }
     }
 }
 
-// grid: NT * TS workgroups of 576 threads (eight data waves and a control wave), all resident
+// One stage of the PUBLISHER wave; tA counts the tiles of the group the data waves are adding.
+__device__ __forceinline__ void team_publish_stage(const TeamArgs& a, unsigned long long* xt, int n, int m,
+                                                   int ntile, int ntot, int& tA, TeamLds& L)
+{
+    const int lane = threadIdx.x % kWave;
+    __syncthreads();
+    if (n < ntot) {
+        // member partial: lane l adds value l/8 of data wave l%8 (its four row sums), then the
+        // eight waves in a fixed tree (lanes ^1, ^2, ^7)
+        const float4 q = L.s_dot[n & 1][lane & 7][lane >> 3];
+        float w = ((q.x + q.y) + q.z) + q.w;
+        w += row_xor<3>(w);
+        w += row_xor<2>(w);
+        w += row_xor<1>(w);
+        if ((lane & 7) == 0)
+            pair_store(xt + ((n % kSlots) * a.TS + m) * kPartial + (lane >> 3), w, a.tag_base + (unsigned)n);
+    }
+    if (n >= 2 && n - 2 < ntot) {
+        if (tA == ntile - 1) {
+            __syncthreads();                     // the data waves' barrier at the end of a group
+            tA = 0;
+        } else {
+            ++tA;
+        }
+    }
+}
+
+// grid: NT * TS workgroups of 640 threads (eight data waves, the exchange wave and the publisher
+// wave), all resident
 // at once (checked on the host); dynamic LDS: kParkBytes.
 __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
 {
@@ -463,25 +497,40 @@ __global__ __launch_bounds__(kThreads) void lr_team_kernel(TeamArgs a)
     const int ntot = ngroups * ntile;
     const int nstage = ntot + 2;
 
+    unsigned long long* xt = a.xch + (int64_t)team * kSlots * a.TS * kPartial;   // the team's slots
     if (wave == kDataWaves) {
-        TeamSeq S;
-        S.ntile = ntile; S.ntot = ntot;
-        S.gF = S.gC = S.gA = g_first;
-        S.tF = S.tC = S.tA = 0;
-        // ---- control wave ----
-        unsigned long long* xt = a.xch + (int64_t)team * kSlots * a.TS * kPartial;   // the team's slots
+        // ---- exchange wave ----
+        const int prow = lane >> 4;
         TeamCtl K;
-        K.row_next = 0; K.y_new = 1.0f; K.gave_up = false; K.lacc = K.lacc_prev = 0;
-        K.gR = g_first; K.tR = 0;
-        if (lane < kR) L.s_y[0][lane] = team_label_of(a, S, team_label_row(a, S, lane));
-        team_advance(a, S, 1, a.NT);
-        if (lane < kR) K.y_new = team_label_of(a, S, team_label_row(a, S, lane));
-        team_advance(a, S, 2, a.NT);
-        if (lane < kR) K.row_next = team_label_row(a, S, lane);
+        K.gave_up = false; K.lacc = K.lacc_prev = 0;
+        K.gR = K.gA = g_first; K.tR = K.tA = 0;
+        // labels of tiles 0 and 1, row ids of tiles 2, 3 and 4 (ring slots by tile mod 3)
+        TeamCursor c = {g_first, 0};
+        K.y[0] = team_label(a, c.g, team_row_id(a, c, prow));
+        team_cursor_advance(a, c, ntile, ntot, 1);
+        K.y[1] = team_label(a, c.g, team_row_id(a, c, prow));
+        team_cursor_advance(a, c, ntile, ntot, 2);
+        K.c2 = c;
+        K.y[2] = 1.0f;
+        K.id[2] = team_row_id(a, c, prow);
+        team_cursor_advance(a, c, ntile, ntot, 3);
+        K.id[0] = team_row_id(a, c, prow);
+        team_cursor_advance(a, c, ntile, ntot, 4);
+        K.id[1] = team_row_id(a, c, prow);
+        team_cursor_advance(a, c, ntile, ntot, 5);
+        K.c5 = c;
         for (int n = 0; n < nstage; n += kRegTiles) {
-            team_control_stage(a, S, xt, n, m, K, L);
-            team_control_stage(a, S, xt, n + 1, m, K, L);
-            team_control_stage(a, S, xt, n + 2, m, K, L);
+            team_exchange_stage<0>(a, xt, n, m, ntile, ntot, K, L);
+            team_exchange_stage<1>(a, xt, n + 1, m, ntile, ntot, K, L);
+            team_exchange_stage<2>(a, xt, n + 2, m, ntile, ntot, K, L);
+        }
+    } else if (wave == kDataWaves + 1) {
+        // ---- publisher wave ----
+        int tA = 0;
+        for (int n = 0; n < nstage; n += kRegTiles) {
+            team_publish_stage(a, xt, n, m, ntile, ntot, tA, L);
+            team_publish_stage(a, xt, n + 1, m, ntile, ntot, tA, L);
+            team_publish_stage(a, xt, n + 2, m, ntile, ntot, tA, L);
         }
     } else {
         // ---- data waves ----

@@ -21,11 +21,13 @@
 // t-4, whose slot tile t takes.  Every wait is bounded; when a bound is hit the kernel raises
 // Ctl::error and runs to its end without waiting again.
 //
-// Eight DATA waves stream the tiles; a ninth CONTROL wave does the exchange (it loads no tiles,
-// so its polls never queue behind tile loads, which return in order).  One workgroup barrier per
-// tile: after the barrier of stage t the control wave publishes the partials of tile t and then
-// forms the residuals of tile t-1, which the data waves use after the barrier of stage t+1; the
-// small LDS arrays involved are double-buffered by the parity of t.
+// Eight DATA waves stream the tiles; two more waves do the exchange and load no tiles (a wave's
+// loads return in order, so a poll behind tile loads would wait for them): the PUBLISHER wave adds
+// the data waves' partial dots of tile t after the barrier of stage t and publishes them; the
+// EXCHANGE wave requests the members' words of tile t-1 before the barrier of stage t, forms the
+// residuals after it, and the data waves use them after the barrier of stage t+1.  One workgroup
+// barrier per tile; the small LDS arrays involved are double-buffered by the parity of t.  All
+// sums over lanes go through DPP moves (no LDS crossbar: it is busy with the parked tiles).
 #include "lr_device.h"
 
 namespace gcada {
@@ -43,9 +45,9 @@ constexpr int kRegTiles = 3;             // register tiles per thread: multiplie
 constexpr int kPartial = 2 * kR;         // values a member publishes per tile
 constexpr int kSlotBytes = kPartial * 8; // per member and slot
 constexpr int kParkBytes = 2 * kR * kV * kDataThreads * 16;   // two parked tiles: 131072
-// the control wave's lane layouts: (value, data wave) = (lane / 8, lane % 8) when it adds the
-// waves' partial dots, (row, member) = (lane / 16, lane % 16) when it adds the members' partials
-static_assert(kR == 4 && kPartial == 8 && kDataWaves == 8, "lane layouts of the control wave");
+// lane layouts: the publisher wave adds the waves' partial dots as (value, data wave) =
+// (lane / 8, lane % 8), the exchange wave the members' partials as (row, member) = (lane / 16, lane % 16)
+static_assert(kR == 4 && kPartial == 8 && kDataWaves == 8, "lane layouts of the two exchange waves");
 
 // A pair {value, tag} of the exchange buffer travels as one 64-bit word.  Relaxed atomic
 // accesses at system scope: the hardware goes past the non-coherent L2s (sc0 sc1), and the
@@ -322,7 +324,7 @@ __device__ __forceinline__ void team_data_stage(const TeamArgs& a, TeamRegs& R, 
             }
             sq = wave_sum(sq);
             if (lane == 0) L.s_red[wave] = sq;
-            __syncthreads();                     // the control wave joins this barrier as well
+            __syncthreads();                     // the exchange and publisher waves join this barrier as well
             if (tid == 0) {
                 double tsum = 0;
                 for (int wv = 0; wv < kDataWaves; ++wv) tsum += L.s_red[wv];

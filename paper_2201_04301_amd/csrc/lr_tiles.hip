@@ -171,8 +171,12 @@ __device__ __forceinline__ void tile_finish(const TileArgs& a, TileShared<WC>& s
             v[2 * i] = q.x * th4.x + q.y * th4.y + q.z * th4.z + q.w * th4.w;
             v[2 * i + 1] = q.x * dl4.x + q.y * dl4.y + q.z * dl4.z + q.w * dl4.w;
         }
-        Butterfly<8, 32>::run(v, lane);              // lane holds value (lane >> 3)
-        if ((lane & 7) == 0) sm.s_dot[wc][(wr * kTR + qt * 4) * 2 + (lane >> 3)] = v[0];
+        // sums over the 16 lanes of a row through DPP moves, then over the four rows
+        RowButterfly<8>::run(v, lane);
+        v[0] += __shfl_xor(v[0], 16, kWave);
+        v[0] += __shfl_xor(v[0], 32, kWave);
+        if (lane < 16 && (lane & 1) == 0)
+            sm.s_dot[wc][(wr * kTR + qt * 4) * 2 + row_butterfly_first<8>(lane)] = v[0];
     }
     __syncthreads();
     double lsum = 0;

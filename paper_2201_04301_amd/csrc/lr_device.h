@@ -52,32 +52,6 @@ __device__ __forceinline__ double wave_total(double v)
     return ((lane_value(v, 0) + lane_value(v, 16)) + lane_value(v, 32)) + lane_value(v, 48);
 }
 
-// v[0..N) per lane -> every lane l ends with the sum over all 64 lanes of v[l >> (6 - log2 N)].
-// Each of the log2(N) halving steps exchanges half of the remaining values with lane ^ S.
-template <int N, int S>
-struct Butterfly {
-    static __device__ __forceinline__ void run(float (&v)[N], int lane)
-    {
-        if constexpr (S >= 1) {
-            if constexpr (N > 1) {
-                const bool up = (lane & S) != 0;
-                float w[N / 2];
-#pragma unroll
-                for (int i = 0; i < N / 2; ++i) {
-                    const float send = up ? v[i] : v[i + N / 2];
-                    const float keep = up ? v[i + N / 2] : v[i];
-                    w[i] = keep + __shfl_xor(send, S, kWave);
-                }
-                Butterfly<N / 2, S / 2>::run(w, lane);
-                v[0] = w[0];
-            } else {
-                v[0] += __shfl_xor(v[0], S, kWave);
-                Butterfly<1, S / 2>::run(v, lane);
-            }
-        }
-    }
-};
-
 // ---- sums over the 16 lanes of a row through data-parallel-primitive moves only ----
 // A shuffle goes through the LDS crossbar (a hundred cycles, more while other waves stream tiles
 // through LDS); a DPP move is part of the add that uses it.  Within a row of 16 lanes four moves

@@ -5,7 +5,7 @@ A step is one whole iteration (dual-iterate gradients of all groups, selection, 
 sum, server update) on one minibatch per group of the synthetic workload.  The headline is the
 largest single-GPU configuration (`lr_64k`); the other four configurations are measured in the
 same run and reported in `per_config`.  Prints ONE JSON line on stdout (the details of every
-configuration go to stderr and, when that folder exists, to gpurun_out/bench_details.json).
+configuration go to stderr and, with --details FILE, to that file).
 
 Timing: W untimed warm-up steps, then `repeats` (3) passes of exactly K steps each, every pass
 bracketed by a device synchronisation and on minibatches of its own; the median pass is reported.
@@ -338,6 +338,7 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time at most (-1 = the run's length)")
     ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle time for the headline's baseline")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--details", default="", metavar="FILE", help="also write the per-configuration details there")
     ap.add_argument("--rule", choices=["gradient_difference", "server"], default="gradient_difference",
                     help="selection rule: the same-minibatch gradient difference (default, the metric's "
                          "configuration) or the paper's server-side condition with L_g from power "
@@ -425,11 +426,9 @@ def main():
            "final_loss": head["final_loss"], "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"],
            "cost_model": head["cost_model"], "setup_s": head["setup_s"], "per_config": per_config}
     print(json.dumps({"bench_details": details, "hbm_read_achievable_gbs": hbm_read}), file=sys.stderr, flush=True)
-    try:
-        if os.path.isdir(os.path.join(ROOT, "gpurun_out")):
-            json.dump(details, open(os.path.join(ROOT, "gpurun_out", "bench_details.json"), "w"), indent=1)
-    except OSError:
-        pass
+    if args.details:
+        with open(args.details, "w") as f:
+            json.dump(details, f, indent=1)
     print(json.dumps(out), flush=True)
 
 

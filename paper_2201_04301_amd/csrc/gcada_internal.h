@@ -103,6 +103,17 @@ __device__ __forceinline__ T global_load(const T* p)
     return *(const __attribute__((address_space(1))) T*)p;
 }
 
+// e^x for x <= 0.  The product x log2(e) is split into its rounded value and the rounding error,
+// so the result keeps its relative accuracy for large |x| too.
+__device__ __forceinline__ float exp_nonpos(float x)
+{
+    const float l2e_hi = 0x1.715476p+0f, l2e_lo = 0x1.4ae0cp-26f;    // log2(e) = hi + lo
+    const float h = x * l2e_hi;
+    const float l = fmaf(x, l2e_hi, -h) + x * l2e_lo;
+    const float e = __builtin_amdgcn_exp2f(h);
+    return fmaf(e, l * 0x1.62e43p-1f, e);                             // 2^(h+l) = 2^h (1 + l ln 2)
+}
+
 // Right side of Eq. (9) with c_d = c/D.  Called by one whole wave (64 lanes): the D history
 // entries are loaded in parallel and added in the butterfly's fixed order.
 __device__ __forceinline__ double history_threshold(const Hyper& hy, const double* __restrict__ nring)

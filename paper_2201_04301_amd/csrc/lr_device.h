@@ -122,17 +122,6 @@ __device__ __forceinline__ float row_total(float v)
 // corrections that keep every result within a few ulp, instead of the library routines, whose
 // dependent instruction chains are five to ten times longer.
 
-// e^x for x <= 0.  The product x log2(e) is split into its rounded value and the rounding error,
-// so the result keeps its relative accuracy for large |x| too.
-__device__ __forceinline__ float exp_nonpos(float x)
-{
-    const float l2e_hi = 0x1.715476p+0f, l2e_lo = 0x1.4ae0cp-26f;    // log2(e) = hi + lo
-    const float h = x * l2e_hi;
-    const float l = fmaf(x, l2e_hi, -h) + x * l2e_lo;
-    const float e = __builtin_amdgcn_exp2f(h);
-    return fmaf(e, l * 0x1.62e43p-1f, e);                             // 2^(h+l) = 2^h (1 + l ln 2)
-}
-
 // 1 / d for 1 <= d <= 2: hardware reciprocal and one Newton step.
 __device__ __forceinline__ float recip_1to2(float d)
 {

@@ -643,15 +643,21 @@ __global__ __launch_bounds__(TL::NT, TL::WPE) void mlp_gemm(GemmArgs a)
             const float zy = z[y];
             float m = 0.0f;
             for (int c = 0; c < nc; ++c) m = fmaxf(m, z[c] - zy);
+            // (every exponent is <= 0: the hardware exponential with a corrected argument, a few
+            // ulp, once per class)
             float so = 0.0f;
             for (int c = 0; c < nc; ++c)
-                if (c != y) so += expf(z[c] - zy - m);
-            const float ey = expf(-m);
+                if (c != y) {
+                    const float ev = exp_nonpos(z[c] - zy - m);
+                    z[c] = ev;
+                    so += ev;
+                }
+            const float ey = exp_nonpos(-m);
             const float inv = 1.0f / (ey + so);
             float others = 0.0f;
             for (int c = 0; c < nc; ++c) {
                 if (c == y) continue;
-                const float dv = expf(z[c] - zy - m) * inv;
+                const float dv = z[c] * inv;
                 others += dv;
                 z[c] = dv;
             }
@@ -1007,6 +1013,12 @@ static hipError_t launch_gemm(const GemmArgs& a, int batch, bool small, hipStrea
                  : launch_tile<T, EPI, typename TileOf<T, EPI, false>::type>(a, batch, s);
 }
 
+// The narrow weight-gradient kernel (mlp_dw_narrow) serves a layer of a small fp32 model that
+// has at most 16 outputs and a row-major activation to read (l >= 2).
+static bool dw_narrow_layer(bool bf16, bool small, int l, int n_out)
+{
+    return !bf16 && small && l >= 2 && n_out <= 16;
+}
 // workgroups (statistic partials) of the weight-gradient GEMM of an M x N layer
 template <typename T>
 static int dw_blocks(int M, int N, bool small)
@@ -1322,6 +1334,94 @@ __global__ __launch_bounds__(256) void mlp_bias_grad(Hyper hy, BiasArgs b)
     bias_grad_block<T>(hy, b, blockIdx.x, g);
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Weight gradient of a layer with few outputs (the output layer: M = n_l <= 16 classes) in fp32.
+// In the general GEMM this product is a chain: every wave's accumulators take mu/2 dependent
+// MFMA 32x32x2 per iterate whatever the tile, 22 of the 32 rows of a block are padding, and only
+// a few dozen workgroups exist.  Here the 16 x 16 x 4 matrix instruction fits the shape (16 rows
+// = the classes, 4 samples per instruction), and both operands are read row-major as they are (a
+// lane loads element [sample s + lane/16][lane%16] of the signal and of the activations: 4 x 64
+// contiguous bytes per operand and instruction).  A workgroup owns 16 columns of one group; each
+// of its 16 waves takes a sixteenth of the samples, both iterates' loads in flight together; the
+// waves' sums meet in LDS and are added in a fixed order.  Results as from the GEMM: fresh block
+// -> gbuf, ||fresh - stale||^2 -> the partial slot of the column block (one per 16 columns).
+constexpr int kNarrowCols = 16, kNarrowWaves = 16;
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+struct DwNarrowArgs {
+    Hyper hy;
+    const float* A; int64_t a_it, a_g; int lda;    // activations of layer l-1 [mu][lda], per (iterate, group)
+    const float* Z; int64_t z_it, z_g; int ldz;    // signal of layer l [mu][ldz] (not negated), pads zero
+    int M, N, mu;
+    float* gbuf; const int32_t* which; int64_t goff;
+    double* part_stat; int n_stat, stat_off;
+    const uint8_t* store_now;
+};
+
+// grid (ceil(N / 16), G), 1024 threads.  Accumulator register r of a lane is class
+// 4 (lane / 16) + r, column lane % 16 of the block.
+__global__ __launch_bounds__(kNarrowWaves * kWave) void mlp_dw_narrow(DwNarrowArgs a)
+{
+    __shared__ f32x4v s_part[2][kNarrowWaves][kWave];
+    const Hyper& hy = a.hy;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int g = blockIdx.y, c0 = blockIdx.x * kNarrowCols;
+    if (hy.sel && !hy.sel[g]) return;            // server-side rule / selected groups only
+    const bool both = hy.sel == nullptr;         // otherwise: the gradient at theta^k, stored, nothing else
+    const int per = ((a.mu + kNarrowWaves - 1) / kNarrowWaves + 3) / 4 * 4;
+    const int s0 = min(a.mu, wave * per), s1 = min(a.mu, s0 + per);
+    const int ks = lane >> 4, j = lane & 15, c = c0 + j;
+    const bool c_ok = c < a.N;
+    const float* Af = a.A + (int64_t)g * a.a_g;
+    const float* Zf = a.Z + (int64_t)g * a.z_g;
+    const float* As = Af + a.a_it;
+    const float* Zs = Zf + a.z_it;
+    f32x4v accf = {0, 0, 0, 0}, accs = {0, 0, 0, 0};
+    constexpr int U = 8;                         // instructions per iterate whose operands are in flight together
+    for (int s = s0; s < s1; s += 4 * U) {
+        float zf[U], af[U], zs[U], as[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int ss = s + 4 * u + ks;
+            const bool ok = ss < s1;
+            zf[u] = ok ? global_load(Zf + (int64_t)ss * a.ldz + j) : 0.0f;
+            af[u] = ok && c_ok ? global_load(Af + (int64_t)ss * a.lda + c) : 0.0f;
+            zs[u] = ok && both ? global_load(Zs + (int64_t)ss * a.ldz + j) : 0.0f;
+            as[u] = ok && both && c_ok ? global_load(As + (int64_t)ss * a.lda + c) : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            accf = __builtin_amdgcn_mfma_f32_16x16x4f32(zf[u], af[u], accf, 0, 0, 0);
+            accs = __builtin_amdgcn_mfma_f32_16x16x4f32(zs[u], as[u], accs, 0, 0, 0);
+        }
+    }
+    s_part[0][wave][lane] = accf;
+    s_part[1][wave][lane] = accs;
+    __syncthreads();
+    if (wave != 0) return;
+    f32x4v fresh = s_part[0][0][lane], stale = s_part[1][0][lane];
+#pragma unroll
+    for (int w = 1; w < kNarrowWaves; ++w) {     // fixed order over the waves
+        fresh += s_part[0][w][lane];
+        stale += s_part[1][w][lane];
+    }
+    const bool store = !both || !a.store_now || a.store_now[g];
+    float* gb = fresh_row(a.gbuf, a.which, hy, g) + a.goff;
+    double sq = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int m = 4 * (lane >> 4) + r;
+        if (m < a.M && c_ok) {
+            if (store) gb[(int64_t)m * a.N + c] = fresh[r];
+            const float df = fresh[r] - stale[r];
+            sq += (double)df * (double)df;
+        }
+    }
+    if (!both) return;
+    sq = wave_sum(sq);
+    if (lane == 0) a.part_stat[(int64_t)g * a.n_stat + a.stat_off + blockIdx.x] = sq;
+}
 
 // ---------------------------------------------------------------------------------------
 // First-layer statistic through two Gram matrices (bf16 models with the lazy gradient store).
@@ -1663,8 +1763,9 @@ hipError_t mlp_plan(gcada_ctx* c)
     int ns = 0;
     for (int l = 1; l <= L; ++l) {
         w->stat_off_w[l] = ns;
-        ns += w->bf16 ? dw_blocks<bf16_t>(lay.n[l], lay.n[l - 1], w->small)
-                      : dw_blocks<float>(lay.n[l], lay.n[l - 1], w->small);
+        if (dw_narrow_layer(w->bf16, w->small, l, lay.n[l])) ns += (lay.n[l - 1] + 15) / 16;
+        else ns += w->bf16 ? dw_blocks<bf16_t>(lay.n[l], lay.n[l - 1], w->small)
+                           : dw_blocks<float>(lay.n[l], lay.n[l - 1], w->small);
         w->stat_off_b[l] = ns;
         ns += (lay.n[l] + 7) / 8;
     }
@@ -1761,8 +1862,33 @@ static GemmArgs dw_args(gcada_ctx* c, int l, const Hyper& hy, const uint8_t* sto
 }
 
 template <typename T>
+static bool dw_narrow_layer(const gcada_ctx* c, int l)
+{
+    return sizeof(T) == 4 && dw_narrow_layer(c->mlp->bf16, c->mlp->small, l, c->mlp->lay.n[l]);
+}
+static hipError_t launch_dw_narrow(gcada_ctx* c, int l, const Hyper& hy, const uint8_t* store_now, hipStream_t s)
+{
+    MlpWork* w = c->mlp;
+    const Layout& lay = w->lay;
+    const int G = hy.G, mu = hy.mu;
+    DwNarrowArgs a{};
+    a.hy = hy;
+    a.A = (const float*)w->A[l - 1]; a.a_it = (int64_t)G * mu * lay.ld[l - 1]; a.a_g = (int64_t)mu * lay.ld[l - 1];
+    a.lda = lay.ld[l - 1];
+    a.Z = (const float*)w->dZ[l]; a.z_it = (int64_t)G * mu * lay.ld[l]; a.z_g = (int64_t)mu * lay.ld[l];
+    a.ldz = lay.ld[l];
+    a.M = lay.n[l]; a.N = lay.n[l - 1]; a.mu = mu;
+    a.gbuf = c->gbuf; a.which = c->which; a.goff = lay.woff[l];
+    a.part_stat = c->part_stat; a.n_stat = w->n_stat; a.stat_off = w->stat_off_w[l];
+    a.store_now = store_now;
+    mlp_dw_narrow<<<dim3((a.N + kNarrowCols - 1) / kNarrowCols, G), kNarrowWaves * kWave, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+template <typename T>
 static hipError_t launch_dw(gcada_ctx* c, int l, const Hyper& hy, const uint8_t* store_now, hipStream_t s)
 {
+    if (dw_narrow_layer<T>(c, l)) return launch_dw_narrow(c, l, hy, store_now, s);
     return launch_gemm<T, EPI_DW>(dw_args(c, l, hy, store_now), hy.G, c->mlp->small, s);
 }
 
@@ -1781,9 +1907,17 @@ static hipError_t launch_dw_selected(gcada_ctx* c, const Hyper& hy, const uint8_
     }
     const Layout& lay = c->mlp->lay;
     DwSelectedArgs a{};
-    a.n_layers = lay.L;
+    // (a layer that the gradient stage handles with the narrow kernel is recomputed by that kernel:
+    // the same sums in the same order; such layers are the last ones)
+    int top = lay.L;
+    while (top >= 1 && dw_narrow_layer<T>(c, top)) {
+        hipError_t e = launch_dw_narrow(c, top, hy, nullptr, s);
+        if (e != hipSuccess) return e;
+        --top;
+    }
+    a.n_layers = top;
     int tiles = 0;
-    for (int l = 1; l <= lay.L; ++l) {
+    for (int l = 1; l <= top; ++l) {
         a.layer[l - 1] = dw_args(c, l, hy, nullptr);
         tiles += ((lay.n[l] + TL::BM - 1) / TL::BM) * ((lay.n[l - 1] + TL::BN - 1) / TL::BN);
         a.tile_end[l - 1] = tiles;

@@ -504,9 +504,13 @@ __device__ __forceinline__ void finish_body(const FinishArgs& a, const int tid, 
             agk[ch] = ag;
             sq = (double)as.x * as.x + (double)as.y * as.y + (double)as.z * as.z + (double)as.w * as.w;
         }
-        // the CL column lanes of a group lane are neighbours in the wave: fixed butterfly
-#pragma unroll
-        for (int o = CL / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o, kWave);
+        // the CL column lanes of a group lane are neighbours within a row of 16 lanes: DPP moves
+        // (lanes ^1, ^2, mirror within 8, mirror within 16), a fixed order
+        static_assert(CL == 1 || CL == 2 || CL == 4 || CL == 8 || CL == 16, "column lanes of a group lane");
+        if constexpr (CL >= 2) sq += dpp_move(sq, 0);
+        if constexpr (CL >= 4) sq += dpp_move(sq, 1);
+        if constexpr (CL >= 8) sq += dpp_move(sq, 2);
+        if constexpr (CL >= 16) sq += dpp_move(sq, 3);
         if (g < G && cl == 0) s_ps[g] = sq;
     }
     if (tid < G) { s_which[tid] = my_which; s_tau[tid] = my_tau; }

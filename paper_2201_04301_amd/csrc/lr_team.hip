@@ -110,7 +110,6 @@ struct TeamSeq {
     // the tile that is requested next (n+2 in stage n)
     int rows_nxt[kR];
     const float* x_nxt;
-    const float* y_nxt;
     int64_t ld_nxt;
     // where the row-id fetch stands (tile n+3 in stage n)
     int gF, tF;
@@ -169,7 +168,6 @@ __device__ __forceinline__ void team_fetch(const TeamArgs& a, TeamSeq& S, int nF
         }
     }
     S.x_nxt = (const float*)sh->X;
-    S.y_nxt = (const float*)sh->y;
     S.ld_nxt = sh->ld;
 }
 

@@ -204,6 +204,14 @@ def run_config(w, K, W, repeats, args, cpu_info, headline: bool):
                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": measured_traffic(w.name, stage),
                     "kernel": stage, "avg_ms": round(grad_ms, 5), "algorithmic_bytes": alg_bytes,
                     "whole_step_frac": round(alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if stage == "lr_team_kernel" and w.widths[0] % 4096 == 0 and w.mu % 4 == 0:
+            # what the same gathered rows, read in the same pattern without arithmetic or
+            # exchange, reach on this machine (the ceiling of this kernel's access pattern)
+            try:
+                roofline["hbm_gather_read_achievable_gbs"] = round(B.gcada_gather_read_calibration(
+                    gpu.ctx, base_idx + W * stride_idx, w.G * w.mu, min(K, 20), stream), 1)
+            except RuntimeError as exc:
+                print(f"[bench] gather calibration skipped: {exc}", file=sys.stderr, flush=True)
     else:
         gram = "Gram" in stage
         alg, ex = mlp_flops(w, gram)

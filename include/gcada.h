@@ -350,6 +350,21 @@ const char* gcada_timed_stage(gcada_ctx* ctx);
 int gcada_hbm_read_calibration(const void* buf /*[device]*/, int64_t bytes, int32_t reps, void* stream,
                                double* gbps /*[host]*/, double* gbps_plain_loads /*[host]*/);
 
+/*
+ * Benchmark diagnostic beside the measurement of step a1 (Sec. II-A: one read of every group's
+ * minibatch rows) for wide linear models: GB/s of a kernel that reads the rows idx selects from the
+ * context's shards in the access pattern of the wide-row gradient kernel (rows cut into pieces of
+ * 4096 columns that go to the members of a team of workgroups, four rows per tile, three tiles in
+ * flight, one workgroup barrier per tile) and does nothing else -- what that access pattern allows
+ * on this machine.  idx [device]: reps + 1 minibatches of G * batch row ids each, idx_stride ids
+ * apart (launch r reads minibatch r; minibatch 0 is read once more as a warm-up).  Requires a
+ * linear fp32 model with 8192 <= width <= 65,536, a multiple of 4096; batch a multiple of 4; every
+ * shard set, rows 16-byte aligned.  Synchronises the stream; allocates one word and two events.
+ * Errors: GCADA_EINVAL, GCADA_ESTATE, GCADA_EDEVICE.
+ */
+int gcada_gather_read_calibration(gcada_ctx* ctx, const int32_t* idx /*[device]*/, int64_t idx_stride, int32_t reps,
+                                  void* stream, double* gbps /*[host]*/);
+
 /* Message of the last error on this context ("" if none); NULL ctx: last gcada_create error. */
 const char* gcada_last_error(const gcada_ctx* ctx);
 

@@ -32,7 +32,7 @@ EXPORTS = ["gcada_create", "gcada_destroy", "gcada_set_shard", "gcada_set_theta"
            "gcada_state", "gcada_get_state", "gcada_set_state", "gcada_cost_model",
            "gcada_last_error", "gcada_version", "gcada_time_gradient_stage", "gcada_set_option",
            "gcada_timed_stage", "gcada_set_rule", "gcada_estimate_smoothness", "gcada_step_workers",
-           "gcada_estimate_smoothness_static", "gcada_hbm_read_calibration"]
+           "gcada_estimate_smoothness_static", "gcada_hbm_read_calibration", "gcada_gather_read_calibration"]
 
 GCADA_RULE_GRADIENT_DIFFERENCE, GCADA_RULE_SERVER = 0, 1
 
@@ -99,6 +99,9 @@ def _load():
     L.gcada_hbm_read_calibration.restype = C.c_int
     L.gcada_hbm_read_calibration.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.POINTER(C.c_double),
                                              C.POINTER(C.c_double)]
+    L.gcada_gather_read_calibration.restype = C.c_int
+    L.gcada_gather_read_calibration.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
+                                                C.POINTER(C.c_double)]
     L.gcada_set_option.restype = C.c_int
     L.gcada_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.gcada_timed_stage.restype = C.c_char_p
@@ -215,6 +218,12 @@ def gcada_timed_stage(ctx) -> str:
 
 def gcada_estimate_smoothness_static(ctx, iters: int, L_out_dev_ptr, stream):
     _check(lib.gcada_estimate_smoothness_static(ctx, iters, L_out_dev_ptr, stream), ctx)
+
+
+def gcada_gather_read_calibration(ctx, idx_ptr, idx_stride: int, reps: int, stream_ptr=None) -> float:
+    g = C.c_double()
+    _check(lib.gcada_gather_read_calibration(ctx, idx_ptr, idx_stride, reps, stream_ptr, C.byref(g)), ctx)
+    return g.value
 
 
 def gcada_hbm_read_calibration(buf_ptr, nbytes: int, reps: int, stream=None):

@@ -56,6 +56,64 @@ hipError_t time_shape(const void* buf, size_t bytes, int blocks, int threads, in
     return hipSuccess;
 }
 
+
+// The same for the access pattern of the wide-row gradient kernel (lr_team_kernel): the minibatch
+// rows of every group, gathered by their ids from the groups' shards, each row cut into pieces of
+// 4096 columns (16 KB) that go to the members of a team of workgroups, four rows per tile, three
+// tiles in flight per workgroup, one workgroup barrier per tile -- but no arithmetic and no
+// exchange.  What this kernel reaches is what that access pattern allows on this machine.
+struct GatherReadArgs {
+    const ShardDesc* shards;
+    const int32_t* idx;      // [G][mu] row ids
+    int G, mu, TS;           // TS = d / 4096 members per team
+    float* sink;
+};
+constexpr int kGatherThreads = 512, kGatherRows = 4, kGatherDepth = 3, kGatherSlab = 4096;
+
+__global__ __launch_bounds__(kGatherThreads) void gather_read_kernel(GatherReadArgs a)
+{
+    typedef const ShardDesc __attribute__((address_space(4))) const_shard;
+    typedef const int32_t __attribute__((address_space(4))) const_i32;
+    const int wg = blockIdx.x, nWG = gridDim.x;
+    // teams made of workgroup ids congruent mod 8 (one XCD), as in the gradient kernel
+    const int per_xcd = nWG / 8, xcd = wg % 8, slot = wg / 8;
+    const int team = xcd * (per_xcd / a.TS) + slot / a.TS, m = slot % a.TS;
+    const int teams = nWG / a.TS;
+    const int ntile = a.G * a.mu / kGatherRows / teams;          // tiles of this team (exact: checked on the host)
+    const int q0 = team * ntile * kGatherRows;
+    const_i32* ids = (const_i32*)(uintptr_t)a.idx;
+    cal_f32x4 buf[kGatherDepth][kGatherRows][2];
+    cal_f32x4 acc = {0, 0, 0, 0};
+    auto issue = [&](int j, cal_f32x4 (&b)[kGatherRows][2]) {
+#pragma unroll
+        for (int r = 0; r < kGatherRows; ++r) {
+            const int q = q0 + j * kGatherRows + r;              // < G * mu
+            const_shard* sh = (const_shard*)(uintptr_t)a.shards + q / a.mu;
+            const int row = __builtin_amdgcn_readfirstlane(ids[q]);
+            const float* x = (const float*)sh->X + (int64_t)row * sh->ld + m * kGatherSlab;
+#pragma unroll
+            for (int v = 0; v < 2; ++v)
+                b[r][v] = __builtin_nontemporal_load(
+                    (const __attribute__((address_space(1))) cal_f32x4*)x + threadIdx.x + v * kGatherThreads);
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < kGatherDepth; ++s)
+        if (s < ntile) issue(s, buf[s]);
+    for (int j = 0; j < ntile; j += kGatherDepth) {
+#pragma unroll
+        for (int s = 0; s < kGatherDepth; ++s) {
+            if (j + s < ntile) {
+#pragma unroll
+                for (int r = 0; r < kGatherRows; ++r) acc += buf[s][r][0] + buf[s][r][1];
+            }
+            __syncthreads();
+            if (j + s + kGatherDepth < ntile) issue(j + s + kGatherDepth, buf[s]);
+        }
+    }
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f) *a.sink = acc.x;     // (keeps the loads alive)
+}
+
 }  // namespace
 
 hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStream_t s, double* best_gbps,
@@ -90,6 +148,45 @@ hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStre
     if (e != hipSuccess) return e;
     *best_gbps = best;
     if (best_plain_gbps) *best_plain_gbps = best_plain;
+    return hipSuccess;
+}
+
+// Gathered read of the context's shards in the wide-row kernel's pattern; `reps` launches on
+// distinct minibatches (idx + r * idx_stride) between two events.  The caller has checked the shape.
+hipError_t gather_read_calibration(gcada_ctx* c, const int32_t* idx, int64_t idx_stride, int reps, hipStream_t s,
+                                   double* gbps)
+{
+    const int d = (int)c->hy.p, TS = d / kGatherSlab;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDeviceProperties(&prop, c->device);
+    if (e != hipSuccess) return e;
+    const int nWG = prop.multiProcessorCount / 8 * 8;
+    if (nWG < 8 || (nWG / 8) % TS || ((int64_t)c->hy.G * c->hy.mu / kGatherRows) % (nWG / TS)) return hipErrorInvalidValue;
+    hipEvent_t e0, e1;
+    if ((e = hipEventCreate(&e0)) != hipSuccess) return e;
+    if ((e = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return e; }
+    float* sink = nullptr;
+    if ((e = hipMalloc(&sink, sizeof(float))) != hipSuccess) {
+        (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+        return e;
+    }
+    GatherReadArgs a{c->d_shards, idx, c->hy.G, c->hy.mu, TS, sink};
+    gather_read_kernel<<<nWG, kGatherThreads, 0, s>>>(a);                  // warm-up
+    e = hipEventRecord(e0, s);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) {
+        a.idx = idx + (int64_t)r * idx_stride;
+        gather_read_kernel<<<nWG, kGatherThreads, 0, s>>>(a);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipFree(sink);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return e;
+    *gbps = (double)c->hy.G * c->hy.mu * d * 4.0 * reps / ((double)ms * 1e-3) / 1e9;
     return hipSuccess;
 }
 

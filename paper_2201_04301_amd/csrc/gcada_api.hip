@@ -685,6 +685,30 @@ int gcada_hbm_read_calibration(const void* buf, int64_t bytes, int32_t reps, voi
     return GCADA_OK;
 }
 
+int gcada_gather_read_calibration(gcada_ctx* ctx, const int32_t* idx, int64_t idx_stride, int32_t reps,
+                                  void* stream, double* gbps)
+{
+    if (!ctx) return GCADA_EINVAL;
+    if (!idx || reps < 1 || !gbps || idx_stride < 0)
+        return fail(ctx, GCADA_EINVAL, "gather_read_calibration: row ids, reps >= 1 and an output are required");
+    const int64_t d = ctx->hy.p;
+    if (ctx->dims.model == GCADA_MLP || ctx->dims.dtype != GCADA_F32 || d % 4096 || d < 8192 || d / 4096 > 16 ||
+        ctx->hy.mu % 4)
+        return fail(ctx, GCADA_EINVAL, "gather_read_calibration: a linear fp32 model whose width is 2 to 16 times 4096 and a minibatch that is a multiple of 4 are required");
+    for (int g = 0; g < ctx->hy.G; ++g) {
+        if (!ctx->shard_set[g]) return fail(ctx, GCADA_ESTATE, "gather_read_calibration: a group has no shard");
+        if (((uintptr_t)ctx->shards[g].X % 16) || ctx->shards[g].ld % 4)
+            return fail(ctx, GCADA_EINVAL, "gather_read_calibration: shard rows must be 16-byte aligned");
+    }
+    double g = 0;
+    hipError_t e = gcada::gather_read_calibration(ctx, idx, idx_stride, reps, (hipStream_t)stream, &g);
+    if (e == hipErrorInvalidValue)
+        return fail(ctx, GCADA_EINVAL, "gather_read_calibration: the tiles of the minibatches do not divide evenly among the teams of this device");
+    if (e != hipSuccess) return fail_hip(ctx, e, "gather_read_calibration");
+    *gbps = g;
+    return GCADA_OK;
+}
+
 int gcada_cost_model(int32_t G, int32_t M_G, int32_t mu, const uint8_t* mask, const double* T,
                      double* time, int64_t* comm, int64_t* comp)
 {

@@ -302,6 +302,8 @@ hipError_t pick_fastest_workers(gcada_ctx* c, const int32_t* idx_workers, const 
 // plain contiguous read of `bytes` of device memory, best of a few launch shapes, in GB/s (calibration.hip)
 hipError_t hbm_read_calibration(const void* buf, size_t bytes, int reps, hipStream_t s, double* best_gbps,
                                 double* best_plain_gbps);
+hipError_t gather_read_calibration(gcada_ctx* c, const int32_t* idx, int64_t idx_stride, int reps, hipStream_t s,
+                                   double* gbps);
 // ||theta^k||^2 of the current slot -> Ctl::theta_sq (after set_theta / set_state)
 hipError_t refresh_theta_sq(gcada_ctx* c, hipStream_t s);
 

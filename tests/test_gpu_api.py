@@ -167,3 +167,42 @@ def test_history_depth_above_64_runs_with_the_default_rule_only():
     out = gpu.outputs()
     assert np.isfinite(out["loss"]) and gpu.get_state()["k"] == 3
     gpu.close()
+
+
+def test_gather_read_calibration_reads_the_minibatch_rows_and_refuses_other_shapes():
+    # the diagnostic reads the rows the ids select, in the wide-row kernel's pattern, and reports
+    # a rate; shapes that the pattern does not cover are refused with a message
+    from paper_2201_04301_amd import binding as B
+    w = scaled(CONFIGS["lr_64k"], name="gather_cal", widths=(8192,), mu=128, G=4, rows=256)
+    Xs, ys = make_shards(w, "cuda")
+    gpu = _mk(w)
+    gpu.set_shards(Xs, ys)
+    gpu.set_theta(make_theta0(w))
+    idx = torch.as_tensor(make_indices(w, 4), device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    rate = B.gcada_gather_read_calibration(gpu.ctx, idx.data_ptr(), w.G * w.mu, 3, stream)
+    assert rate > 0
+    g = C.c_double()
+    assert B.lib.gcada_gather_read_calibration(gpu.ctx, None, w.G * w.mu, 3, stream, C.byref(g)) == B.GCADA_EINVAL
+    gpu.close()
+    # 96 rows per group and step: 96 tiles of four rows in all do not divide among the 128 teams of two
+    w2 = scaled(CONFIGS["lr_64k"], name="gather_cal", widths=(8192,), mu=96, G=4, rows=256)
+    Xs, ys = make_shards(w2, "cuda")
+    gpu = _mk(w2)
+    gpu.set_shards(Xs, ys)
+    gpu.set_theta(make_theta0(w2))
+    idx = torch.as_tensor(make_indices(w2, 4), device="cuda")
+    assert B.lib.gcada_gather_read_calibration(gpu.ctx, idx.data_ptr(), w2.G * w2.mu, 3, stream,
+                                               C.byref(g)) == B.GCADA_EINVAL
+    assert "divide" in B.gcada_last_error(gpu.ctx)
+    gpu.close()
+    # a narrow model
+    w3 = scaled(CONFIGS["lr_4k"], name="gather_cal", widths=(4096,), mu=64, G=4, rows=128)
+    Xs, ys = make_shards(w3, "cuda")
+    gpu = _mk(w3)
+    gpu.set_shards(Xs, ys)
+    gpu.set_theta(make_theta0(w3))
+    idx = torch.as_tensor(make_indices(w3, 4), device="cuda")
+    assert B.lib.gcada_gather_read_calibration(gpu.ctx, idx.data_ptr(), w3.G * w3.mu, 3, stream,
+                                               C.byref(g)) == B.GCADA_EINVAL
+    gpu.close()

@@ -346,6 +346,8 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time at most (-1 = the run's length)")
     ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle time for the headline's baseline")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--library-gemm-reference", action="store_true",
+                    help="time the vendor GEMM on the shapes of the MLP configurations' forward products and exit")
     ap.add_argument("--details", default="", metavar="FILE", help="also write the per-configuration details there")
     ap.add_argument("--rule", choices=["gradient_difference", "server"], default="gradient_difference",
                     help="selection rule: the same-minibatch gradient difference (default, the metric's "
@@ -377,6 +379,37 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": n * 4, "bytes_written": n * 4, "copies": 5}))
+        return
+
+    if args.library_gemm_reference:
+        # Context for the MLP rooflines, not part of any measurement of this library: the rate the
+        # vendor's GEMM (through torch.matmul) reaches on this machine for the plain products
+        # C = A B^T with the shapes of the gradient stage's large GEMMs -- no bias, activation,
+        # second output orientation or per-group weights, which the library's kernels carry.
+        out = {}
+        for name in ("mlp_3072_bf16", "mlp_784"):
+            w = CONFIGS[name]
+            dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+            rows = 2 * w.G * w.mu                         # both iterates of every group
+            shapes = {}
+            for l in range(1, len(w.widths) - 1):        # forward and signal products of the hidden layers
+                shapes[f"forward layer {l}: {rows} x {w.widths[l]} x {w.widths[l - 1]}"] = (rows, w.widths[l], w.widths[l - 1])
+            for label, (M, N, Kd) in shapes.items():
+                a = torch.randn(M, Kd, device="cuda", dtype=dt)
+                b = torch.randn(N, Kd, device="cuda", dtype=dt)
+                for _ in range(5):
+                    a @ b.t()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(50):
+                    a @ b.t()
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / 50
+                out[f"{name}, {label}"] = {"us": round(ms * 1e3, 1), "tflops": round(2 * M * N * Kd / ms / 1e9, 1),
+                                           "frac_of_peak": round(2 * M * N * Kd / ms / 1e9 / MFMA_PEAK_TFLOPS[w.dtype], 3)}
+        print(json.dumps({"library_gemm_reference": out}))
         return
 
     cpu_info = host_cpu()
